@@ -1,0 +1,285 @@
+"""Pins for oracle/model.py.
+
+Each primitive is held to a library routine (torch, float64) or a closed form;
+the layer wiring is held to a decoder assembled from torch modules; the cached
+and T-row forms are held to the no-cache definition (Section 3.2: one pass over
+n rows gives the distributions of n sequential steps)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import bild_inputs as bi
+from oracle import model as om
+
+torch.set_default_dtype(torch.float64)
+RNG = np.random.default_rng(42)
+
+
+# ---------------------------------------------------------------- primitives
+def test_round_bf16_matches_library_and_ties_to_even():
+    a = (RNG.standard_normal(50000) * np.exp(RNG.uniform(-30, 30, 50000))).astype(np.float32)
+    ref = torch.from_numpy(a).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(om.round_bf16(a.astype(np.float64)), ref)
+    assert om.round_bf16(np.array([1 + 2.0 ** -8]))[0] == 1.0                   # tie -> even (down)
+    assert om.round_bf16(np.array([1 + 3 * 2.0 ** -8]))[0] == 1 + 2.0 ** -6     # tie -> even (up)
+    assert om.round_bf16(np.array([1 + 2.0 ** -8 + 2.0 ** -40]))[0] == 1 + 2.0 ** -7
+    assert om.round_bf16(np.array([0.0, -2.5]))[0] == 0.0
+
+
+def test_rmsnorm_matches_library():
+    x = RNG.standard_normal((5, 48))
+    g = RNG.standard_normal(48)
+    ref = F.rms_norm(torch.from_numpy(x), (48,), torch.from_numpy(g), eps=1e-6).numpy()
+    assert np.allclose(om.rmsnorm(x, g, 1e-6), ref, rtol=1e-13, atol=1e-14)
+    # closed form: a constant row has rms |c|
+    assert np.allclose(om.rmsnorm(np.full((1, 8), -3.0), np.ones(8), 0.0), -1.0)
+
+
+def test_activations_match_library():
+    u = RNG.standard_normal(1000) * 3
+    t = torch.from_numpy(u)
+    assert np.allclose(om.gelu_tanh(u), F.gelu(t, approximate="tanh").numpy(), rtol=1e-13, atol=1e-15)
+    assert np.allclose(om.silu(u), F.silu(t).numpy(), rtol=1e-13, atol=1e-15)
+
+
+def test_sinusoid_closed_form():
+    d = 12
+    pe = om.sinusoid(np.array([0, 1, 5]), d)
+    assert np.allclose(pe[0, 0::2], 0) and np.allclose(pe[0, 1::2], 1)
+    assert abs(pe[1, 0] - math.sin(1.0)) < 1e-15 and abs(pe[1, 1] - math.cos(1.0)) < 1e-15
+    i = d // 2 - 1
+    assert abs(pe[2, 2 * i] - math.sin(5.0 / 10000 ** (2 * i / d))) < 1e-15
+    assert abs(pe[2, 2 * i + 1] - math.cos(5.0 / 10000 ** (2 * i / d))) < 1e-15
+
+
+def test_rope_properties():
+    h, dh = 3, 8
+    x = RNG.standard_normal((4, h * dh))
+    y = RNG.standard_normal((4, h * dh))
+    pos = np.array([0, 1, 7, 30])
+    rx = om.rope(x, pos, h, dh, 10000.0)
+    assert np.allclose(rx[0], x[0])                                         # position 0: identity
+    assert np.allclose(np.linalg.norm(rx.reshape(4, h, dh), axis=2), np.linalg.norm(x.reshape(4, h, dh), axis=2))
+    # first pair rotates by exactly `position` radians, the last by position * base^(-(dh-2)/dh)
+    c, s = math.cos(7.0), math.sin(7.0)
+    assert np.allclose(rx[2, :2], [x[2, 0] * c - x[2, 1] * s, x[2, 0] * s + x[2, 1] * c])
+    a = 30.0 * 10000.0 ** (-(dh - 2) / dh)
+    c, s = math.cos(a), math.sin(a)
+    assert np.allclose(rx[3, dh - 2:dh], [x[3, dh - 2] * c - x[3, dh - 1] * s, x[3, dh - 2] * s + x[3, dh - 1] * c])
+    # scores depend on the position difference only
+    q1 = om.rope(x[:1], np.array([9]), h, dh, 10000.0)
+    k1 = om.rope(y[:1], np.array([4]), h, dh, 10000.0)
+    q2 = om.rope(x[:1], np.array([25]), h, dh, 10000.0)
+    k2 = om.rope(y[:1], np.array([20]), h, dh, 10000.0)
+    assert np.allclose((q1.reshape(h, dh) * k1.reshape(h, dh)).sum(1), (q2.reshape(h, dh) * k2.reshape(h, dh)).sum(1))
+
+
+def _sdpa(q, k, v, heads, dh, mask):
+    tq = torch.from_numpy(q).reshape(q.shape[0], heads, dh).transpose(0, 1)
+    tk = torch.from_numpy(k).reshape(k.shape[0], heads, dh).transpose(0, 1)
+    tv = torch.from_numpy(v).reshape(v.shape[0], heads, dh).transpose(0, 1)
+    o = F.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask)
+    return o.transpose(0, 1).reshape(q.shape[0], heads * dh).numpy()
+
+
+def test_attention_matches_library_sdpa():
+    heads, dh, t, p = 3, 8, 4, 11
+    q = RNG.standard_normal((t, heads * dh))
+    k = RNG.standard_normal((p, heads * dh))
+    v = RNG.standard_normal((p, heads * dh))
+    assert np.allclose(om.attention(q, k, v, heads, dh, None), _sdpa(q, k, v, heads, dh, None), rtol=1e-12, atol=1e-13)
+    qpos = np.arange(p - t, p)                      # the T new rows sit at the end of the cache
+    mask = torch.from_numpy(np.arange(p)[None, :] <= qpos[:, None])
+    assert np.allclose(om.attention(q, k, v, heads, dh, qpos), _sdpa(q, k, v, heads, dh, mask), rtol=1e-12, atol=1e-13)
+
+
+def test_attention_zero_query_is_prefix_mean():
+    heads, dh, p = 2, 4, 6
+    k = RNG.standard_normal((p, heads * dh))
+    v = RNG.standard_normal((p, heads * dh))
+    out = om.attention(np.zeros((p, heads * dh)), k, v, heads, dh, np.arange(p))
+    for r in range(p):
+        assert np.allclose(out[r], v[:r + 1].mean(axis=0))
+
+
+# ------------------------------------------------------- wiring vs torch modules
+def _torch_decoder(shape, w, y, cross_src):
+    """A pre-norm decoder assembled from library modules (nn.MultiheadAttention,
+    F.rms_norm, F.linear).  Only valid for heads*d_head == d, ReLU, sinusoidal."""
+    d, h = shape.d, shape.heads
+    tw = {k: torch.from_numpy(np.asarray(a, dtype=np.float64)) for k, a in w.items()}
+
+    def mha(pre, names, xq, xkv, mask):
+        m = torch.nn.MultiheadAttention(d, h, bias=False, batch_first=False, dtype=torch.float64)
+        with torch.no_grad():
+            m.in_proj_weight.copy_(torch.cat([tw[pre + n].T for n in names[:3]], 0))
+            m.out_proj.weight.copy_(tw[pre + names[3]].T)
+        return m(xq[:, None], xkv[:, None], xkv[:, None], attn_mask=mask, need_weights=False)[0][:, 0]
+
+    n = len(y)
+    pos = torch.arange(n, dtype=torch.float64)
+    i = torch.arange(d // 2, dtype=torch.float64)
+    ang = pos[:, None] / (10000.0 ** (2 * i / d))[None]
+    pe = torch.stack([ang.sin(), ang.cos()], -1).reshape(n, d)
+    rows = (torch.tensor(y) + shape.tie_shift) % shape.vocab
+    x = shape.embed_scale * F.embedding(rows, tw["emb"]) + pe
+    causal = torch.triu(torch.ones(n, n, dtype=torch.bool), 1)        # True = masked
+    with torch.no_grad():
+        for l in range(shape.n_dec):
+            p = f"dec.{l}."
+            xn = F.rms_norm(x, (d,), tw[p + "ln1"], eps=shape.eps)
+            x = x + mha(p, ("wq", "wk", "wv", "wo"), xn, xn, causal)
+            xn = F.rms_norm(x, (d,), tw[p + "lnc"], eps=shape.eps)
+            x = x + mha(p, ("cwq", "cwk", "cwv", "cwo"), xn, cross_src, None)
+            xn = F.rms_norm(x, (d,), tw[p + "ln2"], eps=shape.eps)
+            x = x + F.linear(F.relu(F.linear(xn, tw[p + "w_in"].T)), tw[p + "w_out"].T)
+        xn = F.rms_norm(x, (d,), tw["dec_final_norm"], eps=shape.eps)
+        return (shape.logit_scale * F.linear(xn, tw["emb"])).numpy()
+
+
+def test_decoder_wiring_matches_torch_modules():
+    cfg = bi.toy_pair(d=32, heads=2, d_head=16, d_ff=40, vocab=50)
+    _, wl = bi.make_pair_weights(cfg)
+    m = om.Model(cfg.large, wl)
+    enc = RNG.standard_normal((7, 32))                 # any memory: the encoder is pinned separately
+    y = [0, 13, 49, 2, 2, 31]
+    ours = m.logits_full(y, m.cross_kv(enc))
+    ref = _torch_decoder(cfg.large, wl, y, torch.from_numpy(enc))
+    assert np.allclose(ours, ref, rtol=1e-11, atol=1e-11)
+
+
+def test_encoder_layer_matches_torch_modules():
+    cfg = bi.toy_pair(d=32, heads=2, d_head=16, d_ff=40, vocab=50)
+    _, wl = bi.make_pair_weights(cfg)
+    shape = cfg.large
+    m = om.Model(shape, wl)
+    src = [5, 9, 0, 44, 17]
+    ours = m.encode(src)
+    tw = {k: torch.from_numpy(np.asarray(a, dtype=np.float64)) for k, a in wl.items()}
+    d = shape.d
+    x = torch.from_numpy(m.embed(src, np.arange(len(src))))       # embed is pinned by its own test
+    with torch.no_grad():
+        for l in range(shape.n_enc):
+            p = f"enc.{l}."
+            mha = torch.nn.MultiheadAttention(d, shape.heads, bias=False, dtype=torch.float64)
+            mha.in_proj_weight.copy_(torch.cat([tw[p + n].T for n in ("wq", "wk", "wv")], 0))
+            mha.out_proj.weight.copy_(tw[p + "wo"].T)
+            xn = F.rms_norm(x, (d,), tw[p + "ln1"], eps=shape.eps)
+            x = x + mha(xn[:, None], xn[:, None], xn[:, None], need_weights=False)[0][:, 0]
+            xn = F.rms_norm(x, (d,), tw[p + "ln2"], eps=shape.eps)
+            x = x + F.linear(F.relu(F.linear(xn, tw[p + "w_in"].T)), tw[p + "w_out"].T)
+        ref = F.rms_norm(x, (d,), tw["enc_final_norm"], eps=shape.eps).numpy()
+    assert np.allclose(ours, ref, rtol=1e-11, atol=1e-11)
+
+
+def test_embed_closed_form_and_tie_shift():
+    cfg = bi.toy_pair()
+    _, wl = bi.make_pair_weights(cfg)
+    s = cfg.large
+    m = om.Model(s, wl)
+    x = m.embed([3, s.vocab - 1], np.array([0, 4]))
+    e0 = s.embed_scale * wl["emb"][(3 + s.tie_shift) % s.vocab].astype(np.float64)
+    e0[1::2] += 1.0                                         # PE(0) = (0, 1, 0, 1, ...)
+    assert np.allclose(x[0], e0, rtol=0, atol=1e-15)
+    assert abs(x[1, 0] - (s.embed_scale * float(wl["emb"][(s.vocab - 1 + s.tie_shift) % s.vocab, 0]) + math.sin(4.0))) < 1e-14
+
+
+def test_gated_ffn_matches_library_composition():
+    for act, fn in ((bi.ACT_GATED_GELU, lambda t: F.gelu(t, approximate="tanh")), (bi.ACT_SWIGLU, F.silu)):
+        cfg = bi.toy_pair(act=act)
+        _, wl = bi.make_pair_weights(cfg)
+        m = om.Model(cfg.large, wl)
+        xn = RNG.standard_normal((3, cfg.large.d))
+        t = torch.from_numpy(xn)
+        w = {k: torch.from_numpy(wl["dec.1." + k].astype(np.float64)) for k in ("w_in", "w_up", "w_out")}
+        ref = F.linear(fn(F.linear(t, w["w_in"].T)) * F.linear(t, w["w_up"].T), w["w_out"].T).numpy()
+        assert np.allclose(m.ffn("dec.1.", xn), ref, rtol=1e-12, atol=1e-14)
+
+
+def test_zeroed_sublayers_reduce_to_embedding_times_head():
+    cfg = bi.toy_pair(tied=False)
+    _, wl = bi.make_pair_weights(cfg)
+    for k in wl:
+        if k.endswith((".wo", ".cwo", ".w_out")):
+            wl[k] = np.zeros_like(wl[k])
+    s = cfg.large
+    m = om.Model(s, wl)
+    y = [0, 7, 150]
+    z = m.logits_full(y, m.cross_kv(RNG.standard_normal((4, s.d))))
+    x = s.embed_scale * wl["emb"][y].astype(np.float64) + om.sinusoid(np.arange(3), s.d)
+    xn = x / np.sqrt((x * x).mean(1, keepdims=True) + s.eps) * wl["dec_final_norm"]
+    assert np.allclose(z, s.logit_scale * xn @ wl["head"].astype(np.float64).T, rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------ cached / T-row == definition
+VARIANTS = [
+    dict(),
+    dict(dtype=bi.DT_BF16),
+    dict(act=bi.ACT_GATED_GELU, tied=False),
+    dict(act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=False),
+    dict(act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=False, dtype=bi.DT_BF16),
+    dict(truncate=True, dtype=bi.DT_BF16),
+]
+
+
+@pytest.mark.parametrize("kw", VARIANTS)
+def test_cached_and_block_passes_equal_the_definition(kw):
+    cfg = bi.toy_pair(**kw)
+    ws, wl = bi.make_pair_weights(cfg)
+    for shape, w in ((cfg.large, wl), (cfg.small, ws)):
+        m = om.Model(shape, w)
+        if shape.cross:
+            enc = m.encode(bi.make_source(cfg)) if shape.n_enc else RNG.standard_normal((cfg.n_src, shape.d))
+            cross = m.cross_kv(enc)
+        else:
+            cross = []
+        y = [int(t) for t in bi.make_tokens(shape.vocab, 13, seed=5)]
+        full = m.logits_full(y, cross)
+        # one row at a time
+        c = om.DecoderCache(m, cross, 32)
+        seq = np.stack([c.step([t])[0] for t in y])
+        assert np.allclose(seq, full, rtol=1e-12, atol=1e-12)
+        # ragged blocks: 1, 5, 1, 6 rows (a T-row pass equals T sequential steps)
+        c = om.DecoderCache(m, cross, 32)
+        blocks, at = [], 0
+        for n in (1, 5, 1, 6):
+            blocks.append(c.step(y[at:at + n]))
+            at += n
+        assert np.allclose(np.concatenate(blocks), full, rtol=1e-12, atol=1e-12)
+        # truncate, then continue with different tokens == fresh run on the new prefix
+        c.truncate(4)
+        y2 = y[:4] + [int(t) for t in bi.make_tokens(shape.vocab, 5, seed=6)]
+        again = c.step(y2[4:])
+        assert np.allclose(again, m.logits_full(y2, cross)[4:], rtol=1e-12, atol=1e-12)
+
+
+def test_causality_and_encoder_bidirectionality():
+    cfg = bi.toy_pair()
+    _, wl = bi.make_pair_weights(cfg)
+    m = om.Model(cfg.large, wl)
+    src = [int(t) for t in bi.make_source(cfg)]
+    e1 = m.encode(src)
+    src2 = list(src)
+    src2[-1] = (src2[-1] + 1) % cfg.large.vocab
+    e2 = m.encode(src2)
+    assert np.abs(e1[0] - e2[0]).max() > 1e-6           # the first source position sees the last one
+    cross = m.cross_kv(e1)
+    y = [0, 5, 9, 11, 3]
+    z1 = m.logits_full(y, cross)
+    y2 = list(y)
+    y2[3] = 12
+    z2 = m.logits_full(y2, cross)
+    assert np.array_equal(z1[:3], z2[:3])               # rows before the change are untouched
+    assert np.abs(z1[3:] - z2[3:]).max() > 1e-6
+
+
+def test_compact_storage_gives_identical_values():
+    cfg = bi.toy_pair(act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=False, dtype=bi.DT_BF16)
+    _, wl = bi.make_pair_weights(cfg)
+    y = [1, 2, 3, 100]
+    a = om.Model(cfg.large, wl).logits_full(y, [])
+    b = om.Model(cfg.large, wl, compact=True).logits_full(y, [])
+    assert np.allclose(a, b, rtol=1e-13, atol=1e-13)      # same values; only the BLAS call pattern differs
