@@ -167,14 +167,14 @@ def toy_pair(dtype=DT_F32, act=ACT_RELU, pos=POS_SINUSOIDAL, cross=True, tied=Tr
     force.  Norm gains are jittered so that a dropped gain shows up, widths are
     deliberately not powers of two and `heads*d_head != d`."""
     n_enc = 2 if cross else 0
-    large = ModelShape("toy-large", n_enc=n_enc, n_dec=n_large, d=d, heads=heads, d_head=d_head,
-                       d_ff=d_ff, act=act, pos=pos, vocab=vocab, tied=tied, dtype=dtype, cross=cross,
+    mul = 2 if truncate else 1          # a truncated pair: the large model is twice as wide as the small one
+    large = ModelShape("toy-large", n_enc=n_enc, n_dec=n_large, d=d * mul, heads=heads * mul, d_head=d_head,
+                       d_ff=d_ff * mul, act=act, pos=pos, vocab=vocab, tied=tied, dtype=dtype, cross=cross,
                        logit_scale=logit_scale, embed_scale=embed_scale, tie_shift=tie_shift if tied else 0)
     if truncate:
-        small = replace(large, name="toy-small", n_enc=min(1, n_enc), n_dec=n_small, d=d // 2,
-                        heads=max(1, heads // 2), d_ff=d_ff // 2)
+        small = replace(large, name="toy-small", n_enc=min(1, n_enc), n_dec=n_small, d=d, heads=heads, d_ff=d_ff)
     else:
-        small = replace(large, name="toy-small", n_enc=0 if cross else 0, n_dec=n_small)
+        small = replace(large, name="toy-small", n_enc=0, n_dec=n_small)
     return PairConfig("toy", small, large, n_src=n_src, max_new=max_new, alpha_fb=0.5, alpha_rb=2.0,
                       src_dist="uniform", gain_jitter=gain_jitter, decoder_only=not cross)
 

@@ -1,0 +1,213 @@
+/*
+ * bild.h - C ABI of the MI355X (gfx950) Big Little Decoder library.
+ *
+ * The calls follow the paper's problem statement (Section 3.2) and Algorithm 1:
+ * a small model drafts tokens autoregressively, a large model reviews a block
+ * of drafts in one non-autoregressive pass.  Every numerical step runs in HIP
+ * kernels on the device; the host side of this library only owns memory and
+ * launches.  There is no CPU fallback.
+ *
+ * Conventions
+ *   - every function returns BILD_OK (0) or a negative BILD_E* code; nothing
+ *     throws or aborts across this boundary; on error the object passed in is
+ *     left as it was;
+ *   - pointers named host_* / src / out / draft are HOST memory owned by the
+ *     caller and only read or written during the call;
+ *   - all device memory is owned by the library behind the opaque handles;
+ *   - a handle is not thread-safe; distinct states are independent but calls
+ *     on states sharing one stream serialise on it;
+ *   - token ids are int32 in [0, vocab).
+ *
+ * Sequence model held by a bild_state
+ *   y[0..y_len)       the sequence so far: <s> (encoder-decoder pairs) or the
+ *                     prompt (decoder-only pairs) followed by generated tokens
+ *   draft_start       y[draft_start..y_len) are small-model drafts the large
+ *                     model has not reviewed yet
+ *   len_small/large   number of leading tokens of y each model has consumed
+ *                     into its KV cache (cache row p holds K/V of y[p])
+ * A pass of a model consumes rows y[len..y_len) at positions len.. and yields,
+ * for each row, the distribution of the token that follows it.
+ */
+#ifndef BILD_H
+#define BILD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BILD_OK      0
+#define BILD_EINVAL (-1) /* bad argument (null pointer, size out of range, token id >= vocab, unsupported shape) */
+#define BILD_ESTATE (-2) /* call not valid in the current state (e.g. step before encode, nothing to consume) */
+#define BILD_ECAP   (-3) /* capacity exceeded (source longer than max_src, sequence longer than max_len, n > max rows) */
+#define BILD_EHIP   (-4) /* a HIP runtime call failed */
+#define BILD_ENOMEM (-5) /* host or device allocation failed */
+
+#define BILD_ACT_RELU        0 /* relu(x W_in) W_out                       */
+#define BILD_ACT_GATED_GELU  1 /* (gelu_tanh(x W_in) * (x W_up)) W_out     */
+#define BILD_ACT_SWIGLU      2 /* (silu(x W_in) * (x W_up)) W_out          */
+#define BILD_POS_SINUSOIDAL  0 /* PE added to the embedding                */
+#define BILD_POS_ROPE        1 /* rotary on q and k, pairs (2i, 2i+1)      */
+#define BILD_DT_F32          0
+#define BILD_DT_BF16         1 /* weights and cached K/V stored as bf16    */
+
+#define BILD_MAX_ROWS 32       /* most rows one decoder pass processes     */
+
+/* Architecture of one network.  The paper fixes only layer counts and widths
+ * (Table 2); the rest is this benchmark's model contract:
+ *   x = embed_scale*E[(tok+tie_shift) mod vocab] (+ sinusoidal PE); pre-RMSNorm
+ *   sublayers x += f(norm(x)) in the order self-attn, cross-attn, FFN; scores
+ *   scaled by 1/sqrt(d_head); logits = logit_scale * norm(x) E_out^T.
+ * d_model, n_heads*d_head and d_ff must be multiples of 32. */
+typedef struct bild_model_config {
+    int32_t n_enc_layers;   /* 0: no encoder of its own                                     */
+    int32_t n_dec_layers;
+    int32_t d_model;
+    int32_t n_heads;
+    int32_t d_head;         /* 64 or 128 or any multiple of 8 up to 128                     */
+    int32_t d_ff;
+    int32_t act;            /* BILD_ACT_*                                                   */
+    int32_t pos;            /* BILD_POS_*                                                   */
+    int32_t vocab;
+    int32_t tied_head;      /* 1: the LM head is the embedding matrix                       */
+    int32_t dtype;          /* BILD_DT_*                                                    */
+    int32_t cross_attn;     /* 1: decoder layers have a cross-attention sublayer            */
+    int32_t bos;            /* first token of y for encoder-decoder pairs                   */
+    int32_t tie_shift;      /* row offset of the embedding lookup, 0 = ordinary             */
+    float   logit_scale;
+    float   embed_scale;
+    float   norm_eps;
+    float   rope_base;
+} bild_model_config;
+
+/* Counters of one bild_generate call (Table 4 reports fallback and rollback
+ * rates; the paper does not define their denominators, so raw counts are given). */
+typedef struct bild_stats {
+    int32_t small_steps;        /* small-model passes                                  */
+    int32_t large_calls;        /* large-model passes (= fallbacks of both kinds)      */
+    int32_t rows_verified;      /* rows processed by large-model passes                */
+    int32_t fallbacks_conf;     /* fallbacks because max p_S < alpha_FB                */
+    int32_t fallbacks_forced;   /* fallbacks because n_max drafts were pending         */
+    int32_t rollbacks;          /* reviews that rejected a draft                       */
+    int32_t tokens_discarded;   /* drafts removed by rollbacks                         */
+    int32_t n_generated;
+} bild_stats;
+
+typedef struct bild_model bild_model; /* one network's weights on the device, immutable            */
+typedef struct bild_pair  bild_pair;  /* {small, large}; borrows both models                       */
+typedef struct bild_state bild_state; /* one request: y, both KV caches, cross K/V, control block  */
+
+/* Number of entries bild_model_create expects in host_tensors for this config. */
+int bild_model_num_tensors(const bild_model_config* cfg);
+
+/* Uploads one network.  host_tensors[i] are fp32 host arrays in this order
+ * (entries that do not exist for the config are simply absent from the list):
+ *   emb [vocab][d]; head [vocab][d] (only if !tied_head);
+ *   enc_final_norm [d] (only if n_enc_layers > 0); dec_final_norm [d];
+ *   per encoder layer: ln1 [d], wq [d][I], wk [d][I], wv [d][I], wo [I][d], ln2 [d],
+ *                      w_in [d][F], w_up [d][F] (gated only), w_out [F][d];
+ *   per decoder layer: ln1, wq, wk, wv, wo, then (cross_attn only) lnc [d], cwq [d][I],
+ *                      cwk [d][I], cwv [d][I], cwo [I][d], then ln2, w_in, w_up (gated only), w_out.
+ * Matrices are row-major [inputs][outputs] (a layer computes x W); I = n_heads*d_head, F = d_ff.
+ * For BILD_DT_BF16 values are rounded to bf16 (nearest even) on upload.  The
+ * arrays are copied; the caller may free them on return. */
+int bild_model_create(const bild_model_config* cfg, const float* const* host_tensors, int n_tensors,
+                      bild_model** out);
+int bild_model_destroy(bild_model* m);
+
+/* Pairs two models (Section 3.5.1: the only requirement is a shared
+ * vocabulary).  Fails with BILD_EINVAL if vocab sizes or cross_attn differ, or if the
+ * small model has cross-attention but no encoder and its d_model differs from the
+ * large one's (it then attends to the large model's encoder output, the early-exit
+ * arrangement of Section 4.4).  The pair borrows the models: destroy it first. */
+int bild_pair_create(bild_model* small_model, bild_model* large_model, bild_pair** out);
+int bild_pair_destroy(bild_pair* p);
+
+/* Allocates the per-request device state: room for max_src source/prompt tokens
+ * and a sequence y of at most max_len tokens (including <s> or the prompt).
+ * n_max: cap on consecutive small-model tokens (appendix: 10); 0 disables it.
+ * hip_stream: a hipStream_t to launch on, or NULL for a stream the state creates. */
+int bild_state_create(const bild_pair* p, int max_src, int max_len, int n_max, void* hip_stream,
+                      bild_state** out);
+int bild_state_destroy(bild_state* s);
+
+/* Starts a request.  Encoder-decoder pairs: runs the encoder(s) over src[0..n_src)
+ * and fills every decoder layer's cross-attention K/V; y = [bos].  Decoder-only
+ * pairs: y = src (the prompt) and both caches are prefilled with its first
+ * n_src-1 tokens.  Requires 1 <= n_src <= max_src. */
+int bild_encode(bild_state* s, const int32_t* src, int n_src);
+
+/* One autoregressive pass of the small model (Algorithm 1, lines 3-6): consumes the
+ * unconsumed tail of y, takes token = argmax p_S and
+ *   fallback_flag = (max p_S < alpha_fb) or (n_max drafts already pending).
+ * If the flag is 0 the token is appended to y as a draft; if 1 it is returned
+ * for diagnostics only and y is unchanged.  BILD_ESTATE if nothing is unconsumed
+ * (two steps in a row after a fallback), BILD_ECAP if y is full.
+ * max_prob (nullable) receives max p_S. */
+int bild_small_step(bild_state* s, float alpha_fb, int32_t* token, int32_t* fallback_flag, float* max_prob);
+
+/* One non-autoregressive pass of the large model over the pending drafts
+ * (Algorithm 1, lines 9-16; rollback policy of Section 3.4 with d = -ln p_L(draft)).
+ * draft == NULL reviews the n = y_len - draft_start drafts pending in the state
+ * (n is then ignored).  draft != NULL first replaces the pending block by
+ * draft[0..n) (tests and stress runs drive arbitrary blocks this way; the small
+ * cache is cut back to the reviewed prefix).  n + 1 <= BILD_MAX_ROWS.
+ * On return rollback_pos = r in [0, n]: the first draft with -ln p_L > alpha_rb,
+ * or n if none; out_tokens (capacity n+1) receives the r accepted drafts followed
+ * by the large model's token for position r; *n_out = r + 1.  y and both caches
+ * are committed accordingly.  nll (nullable, capacity n) receives -ln p_L of each draft. */
+int bild_large_verify(bild_state* s, const int32_t* draft, int n, float alpha_rb, int32_t* out_tokens,
+                      int32_t* n_out, int32_t* rollback_pos, float* nll);
+
+/* Lowers a cache length: which = 1 small, 2 large, 3 both; the cache(s) keep
+ * their first pos rows (O(1): only a length changes).  BILD_EINVAL if pos exceeds
+ * the current length of a selected cache.  y is not changed; a later pass simply
+ * re-consumes the rows that were cut. */
+int bild_kv_truncate(bild_state* s, int which, int pos);
+
+/* Cuts the sequence to its first n_keep tokens (n_keep >= the initial length),
+ * with draft_start and both caches cut to match, so that decoding continues
+ * as if only that prefix had been generated. */
+int bild_seq_truncate(bild_state* s, int n_keep);
+
+/* Driver hook for tests and stress runs: overwrites y[first .. first+n) with
+ * tokens (n may be 0), sets y_len = first + n and draft_start, and cuts both caches
+ * back to the rows that are still valid (len_small <= first, len_large <=
+ * min(first, draft_start - 1)); later passes re-consume what was cut.  Requires
+ * initial length <= first <= y_len, initial length <= draft_start <= first + n,
+ * first + n < max_len.  No model runs. */
+int bild_force_tokens(bild_state* s, int first, const int32_t* tokens, int n, int draft_start);
+
+/* Algorithm 1 end to end: encode(src), then small steps / large reviews until
+ * max_new tokens exist or the last token equals eos (eos < 0: none).  out
+ * (capacity max_new) receives the generated tokens without <s> / the prompt.
+ * Equals the composition of the calls above. */
+int bild_generate(bild_state* s, const int32_t* src, int n_src, float alpha_fb, float alpha_rb, int max_new,
+                  int32_t eos, int32_t* out, int32_t* n_out, bild_stats* stats /* nullable */);
+
+/* Vanilla inference with one model alone (which = 1 small, 2 large): greedy
+ * autoregressive decoding, the baseline the paper normalises speedups to. */
+int bild_greedy(bild_state* s, int which, const int32_t* src, int n_src, int max_new, int32_t eos,
+                int32_t* out, int32_t* n_out);
+
+/* Introspection (host copies of the control block). */
+int bild_get_lengths(bild_state* s, int32_t* y_len, int32_t* draft_start, int32_t* len_small, int32_t* len_large);
+int bild_get_sequence(bild_state* s, int32_t* out, int cap, int32_t* n);
+
+/* Test/debug: when enabled, each pass also writes its rows' full logits to a device
+ * buffer that bild_debug_logits copies out ([rows][vocab] fp32, rows of the last pass
+ * of model `which`).  Off by default: the product path never materialises logits. */
+int bild_debug_enable_logits(bild_state* s, int enable);
+int bild_debug_logits(bild_state* s, int which, int row, float* out_vocab);
+
+/* Algorithmic bytes one pass of model `which` must read at cache length t_cache
+ * with `rows` new rows (weights + LM head + self K/V + cross K/V). */
+int64_t bild_pass_bytes(const bild_state* s, int which, int t_cache, int rows);
+
+const char* bild_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BILD_H */

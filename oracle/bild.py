@@ -116,7 +116,8 @@ class _Cached:
         self.c.truncate(min(self.c.length, length))
 
 
-def greedy(req: Request, which: str, max_new: int, eos: int = -1, cached: bool = True) -> Result:
+def greedy(req: Request, which: str, max_new: int, eos: int = -1, cached: bool = True,
+           keep_logits: bool = False) -> Result:
     """Vanilla inference: one model alone, autoregressive argmax (the baseline
     every speedup in the paper is normalised to when which == 'large')."""
     y = req.initial()
@@ -127,13 +128,16 @@ def greedy(req: Request, which: str, max_new: int, eos: int = -1, cached: bool =
         z = ev.next_logits(y)
         tok = policy.argmax_lowest(z)
         trace.append(dict(kind=which, pos=len(y), tok=tok, pmax=policy.max_prob(z), gap=policy.top2_gap(z)))
+        if keep_logits:
+            trace[-1]["z"] = z
         y.append(tok)
     return Result(y[n0:], [which == "small"] * (len(y) - n0), trace, Stats(), len(y) - n0)
 
 
 def bild_generate(req: Request, alpha_fb: float, alpha_rb: float, n_max: int, max_new: int,
-                  eos: int = -1, cached: bool = True) -> Result:
-    """Algorithm 1."""
+                  eos: int = -1, cached: bool = True, keep_logits: bool = False) -> Result:
+    """Algorithm 1.  keep_logits stores every evaluated logit row in the trace
+    (for element-wise comparison against another implementation)."""
     y = req.initial()
     n0 = len(y)
     src_small = [False] * n0
@@ -152,6 +156,8 @@ def bild_generate(req: Request, alpha_fb: float, alpha_rb: float, n_max: int, ma
         tok_s = policy.argmax_lowest(z_s)
         trace.append(dict(kind="small", pos=len(y), tok=tok_s, pmax=pmax, gap=policy.top2_gap(z_s),
                           fallback=bool(low_conf or forced), forced=bool(forced and not low_conf)))
+        if keep_logits:
+            trace[-1]["z"] = z_s
         if not (low_conf or forced):
             y.append(tok_s)
             src_small.append(True)
@@ -173,6 +179,8 @@ def bild_generate(req: Request, alpha_fb: float, alpha_rb: float, n_max: int, ma
         trace.append(dict(kind="large", draft_start=draft_start, n=n, r=r, tok=tok_l, nll=nlls,
                           gaps=[policy.top2_gap(z_l[i]) for i in range(r + 1)],
                           pmax=policy.max_prob(z_l[r])))
+        if keep_logits:
+            trace[-1]["z"] = z_l
         if r < n:
             st.rollbacks += 1
             st.tokens_discarded += n - r

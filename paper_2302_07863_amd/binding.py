@@ -1,0 +1,233 @@
+"""Thin ctypes binding of libbild.so: argument marshalling only.  Every step of
+the decoding path runs in the library's HIP kernels; there is no Python or CPU
+fallback, and a missing library is an error."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libbild.so")
+
+OK, EINVAL, ESTATE, ECAP, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5
+MAX_ROWS = 32
+SMALL, LARGE, BOTH = 1, 2, 3
+
+
+class ModelConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "n_enc_layers", "n_dec_layers", "d_model", "n_heads", "d_head", "d_ff", "act", "pos", "vocab",
+        "tied_head", "dtype", "cross_attn", "bos", "tie_shift")] + [
+        (n, C.c_float) for n in ("logit_scale", "embed_scale", "norm_eps", "rope_base")]
+
+
+class Stats(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "small_steps", "large_calls", "rows_verified", "fallbacks_conf", "fallbacks_forced", "rollbacks",
+        "tokens_discarded", "n_generated")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class BildError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {code} ({strerror(code)})")
+        self.code = code
+
+
+_lib = None
+
+_SIGS = {
+    "bild_model_num_tensors": (C.c_int, [C.POINTER(ModelConfig)]),
+    "bild_model_create": (C.c_int, [C.POINTER(ModelConfig), C.POINTER(C.c_void_p), C.c_int, C.POINTER(C.c_void_p)]),
+    "bild_model_destroy": (C.c_int, [C.c_void_p]),
+    "bild_pair_create": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]),
+    "bild_pair_destroy": (C.c_int, [C.c_void_p]),
+    "bild_state_create": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_void_p)]),
+    "bild_state_destroy": (C.c_int, [C.c_void_p]),
+    "bild_encode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int]),
+    "bild_small_step": (C.c_int, [C.c_void_p, C.c_float, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                  C.POINTER(C.c_float)]),
+    "bild_large_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.POINTER(C.c_int32),
+                                    C.POINTER(C.c_int32), C.c_void_p]),
+    "bild_kv_truncate": (C.c_int, [C.c_void_p, C.c_int, C.c_int]),
+    "bild_seq_truncate": (C.c_int, [C.c_void_p, C.c_int]),
+    "bild_force_tokens": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int]),
+    "bild_generate": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_int, C.c_int32,
+                                C.c_void_p, C.POINTER(C.c_int32), C.POINTER(Stats)]),
+    "bild_greedy": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int32, C.c_void_p,
+                              C.POINTER(C.c_int32)]),
+    "bild_get_lengths": (C.c_int, [C.c_void_p] + [C.POINTER(C.c_int32)] * 4),
+    "bild_get_sequence": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int32)]),
+    "bild_debug_enable_logits": (C.c_int, [C.c_void_p, C.c_int]),
+    "bild_debug_logits": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
+    "bild_pass_bytes": (C.c_int64, [C.c_void_p, C.c_int, C.c_int, C.c_int]),
+    "bild_strerror": (C.c_char_p, [C.c_int]),
+}
+
+
+def exported_symbols() -> list:
+    return sorted(_SIGS)
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().bild_strerror(code).decode()
+
+
+def _check(code: int, what: str):
+    if code != OK:
+        raise BildError(code, what)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def config_from_shape(shape) -> ModelConfig:
+    """ModelConfig from a bild_inputs.ModelShape-like record (plain field copy)."""
+    return ModelConfig(n_enc_layers=shape.n_enc, n_dec_layers=shape.n_dec, d_model=shape.d, n_heads=shape.heads,
+                       d_head=shape.d_head, d_ff=shape.d_ff, act=shape.act, pos=shape.pos, vocab=shape.vocab,
+                       tied_head=int(shape.tied), dtype=shape.dtype, cross_attn=int(shape.cross), bos=shape.bos,
+                       tie_shift=shape.tie_shift, logit_scale=shape.logit_scale, embed_scale=shape.embed_scale,
+                       norm_eps=shape.eps, rope_base=shape.rope_base)
+
+
+class Model:
+    h = None
+
+    def __init__(self, cfg: ModelConfig, tensors: Sequence[np.ndarray]):
+        arrs = [np.ascontiguousarray(t, dtype=np.float32) for t in tensors]
+        ptrs = (C.c_void_p * len(arrs))(*[a.ctypes.data for a in arrs])
+        h = C.c_void_p()
+        _check(lib().bild_model_create(C.byref(cfg), ptrs, len(arrs), C.byref(h)), "bild_model_create")
+        self.h, self.cfg = h, cfg
+
+    def close(self):
+        if self.h:
+            lib().bild_model_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+
+class Pair:
+    h = None
+
+    def __init__(self, small: Model, large: Model):
+        h = C.c_void_p()
+        _check(lib().bild_pair_create(small.h, large.h, C.byref(h)), "bild_pair_create")
+        self.h, self.small, self.large = h, small, large
+
+    def close(self):
+        if self.h:
+            lib().bild_pair_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+
+class State:
+    h = None
+
+    def __init__(self, pair: Pair, max_src: int, max_len: int, n_max: int = 10, stream: Optional[int] = None):
+        h = C.c_void_p()
+        _check(lib().bild_state_create(pair.h, max_src, max_len, n_max, C.c_void_p(stream or 0), C.byref(h)),
+               "bild_state_create")
+        self.h, self.pair, self.max_len = h, pair, max_len
+
+    def close(self):
+        if self.h:
+            lib().bild_state_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    def encode(self, src):
+        a = _i32(src)
+        _check(lib().bild_encode(self.h, a.ctypes.data, len(a)), "bild_encode")
+
+    def small_step(self, alpha_fb: float):
+        tok, flag, pm = C.c_int32(), C.c_int32(), C.c_float()
+        _check(lib().bild_small_step(self.h, alpha_fb, C.byref(tok), C.byref(flag), C.byref(pm)), "bild_small_step")
+        return tok.value, flag.value, pm.value
+
+    def large_verify(self, alpha_rb: float, draft=None):
+        if draft is None:
+            n, dptr, cap = 0, None, MAX_ROWS
+        else:
+            d = _i32(draft)
+            n, dptr, cap = len(d), d.ctypes.data, len(d) + 1
+        out = np.zeros(max(cap, 1), dtype=np.int32)
+        nll = np.zeros(MAX_ROWS, dtype=np.float32)
+        n_out, r = C.c_int32(), C.c_int32()
+        _check(lib().bild_large_verify(self.h, dptr, n, alpha_rb, out.ctypes.data, C.byref(n_out), C.byref(r),
+                                       nll.ctypes.data), "bild_large_verify")
+        return out[:n_out.value].tolist(), r.value, nll
+
+    def kv_truncate(self, which: int, pos: int):
+        _check(lib().bild_kv_truncate(self.h, which, pos), "bild_kv_truncate")
+
+    def seq_truncate(self, n_keep: int):
+        _check(lib().bild_seq_truncate(self.h, n_keep), "bild_seq_truncate")
+
+    def force_tokens(self, first: int, tokens, draft_start: int):
+        a = _i32(tokens)
+        _check(lib().bild_force_tokens(self.h, first, a.ctypes.data if len(a) else None, len(a), draft_start),
+               "bild_force_tokens")
+
+    def generate(self, src, alpha_fb: float, alpha_rb: float, max_new: int, eos: int = -1):
+        a = _i32(src)
+        out = np.zeros(max(max_new, 1), dtype=np.int32)
+        n, st = C.c_int32(), Stats()
+        _check(lib().bild_generate(self.h, a.ctypes.data, len(a), alpha_fb, alpha_rb, max_new, eos, out.ctypes.data,
+                                   C.byref(n), C.byref(st)), "bild_generate")
+        return out[:n.value].tolist(), st.as_dict()
+
+    def greedy(self, which: int, src, max_new: int, eos: int = -1):
+        a = _i32(src)
+        out = np.zeros(max(max_new, 1), dtype=np.int32)
+        n = C.c_int32()
+        _check(lib().bild_greedy(self.h, which, a.ctypes.data, len(a), max_new, eos, out.ctypes.data, C.byref(n)),
+               "bild_greedy")
+        return out[:n.value].tolist()
+
+    def lengths(self):
+        v = [C.c_int32() for _ in range(4)]
+        _check(lib().bild_get_lengths(self.h, *[C.byref(x) for x in v]), "bild_get_lengths")
+        return dict(y_len=v[0].value, draft_start=v[1].value, len_small=v[2].value, len_large=v[3].value)
+
+    def sequence(self):
+        out = np.zeros(self.max_len + 1, dtype=np.int32)
+        n = C.c_int32()
+        _check(lib().bild_get_sequence(self.h, out.ctypes.data, len(out), C.byref(n)), "bild_get_sequence")
+        return out[:n.value].tolist()
+
+    def debug_enable_logits(self, enable: bool = True):
+        _check(lib().bild_debug_enable_logits(self.h, int(enable)), "bild_debug_enable_logits")
+
+    def debug_logits(self, which: int, row: int) -> np.ndarray:
+        v = self.pair.large.cfg.vocab
+        out = np.zeros(v, dtype=np.float32)
+        _check(lib().bild_debug_logits(self.h, which, row, out.ctypes.data), "bild_debug_logits")
+        return out
+
+    def pass_bytes(self, which: int, t_cache: int, rows: int = 1) -> int:
+        return int(lib().bild_pass_bytes(self.h, which, t_cache, rows))

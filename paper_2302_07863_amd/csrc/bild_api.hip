@@ -1,0 +1,963 @@
+// C ABI of the BiLD library: model upload, per-request state, and the launch
+// sequences of the decoder passes.  All numerical work is in kernels.hip; this
+// file owns memory and ordering only.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "bild_internal.h"
+
+using namespace bild;
+
+#define HIPC(expr)                                   \
+    do {                                             \
+        hipError_t e_ = (expr);                      \
+        if (e_ != hipSuccess) return BILD_EHIP;      \
+    } while (0)
+
+namespace {
+
+struct LayerW {
+    const float* ln1 = nullptr;
+    TMat wqkv, wo;
+    const float* lnc = nullptr;
+    TMat cwq, cwkv, cwo;
+    const float* ln2 = nullptr;
+    TMat win, wout;
+};
+
+}  // namespace
+
+struct bild_model {
+    bild_model_config cfg;
+    TMat emb, head;
+    const float* enc_final = nullptr;
+    const float* dec_final = nullptr;
+    std::vector<LayerW> enc, dec;
+    std::vector<void*> allocs;
+    size_t device_bytes = 0;
+    int inner() const { return cfg.n_heads * cfg.d_head; }
+    int esz() const { return cfg.dtype == BILD_DT_BF16 ? 2 : 4; }
+    bool gated() const { return cfg.act != BILD_ACT_RELU; }
+};
+
+struct bild_pair {
+    bild_model* m[2];  // [0] small, [1] large
+    bool decoder_only;
+    bool small_borrows_encoder;
+};
+
+namespace {
+
+struct ModelState {
+    const bild_model* m = nullptr;
+    char* kcache = nullptr;  // [L][cap][I]
+    char* vcache = nullptr;
+    char* ck = nullptr;      // cross [L][max_src][I]
+    char* cv = nullptr;
+    float *x = nullptr, *q = nullptr, *a = nullptr, *h = nullptr;  // [32][d], [32][I], [32][I], [32][F]
+    StatPart* part = nullptr;
+    int nparts_cap = 0;
+    float* zt = nullptr;
+    float* dbg = nullptr;     // [32][vocab], only when debugging
+    float* att_o = nullptr;   // split-key partials
+    float* att_ml = nullptr;
+    int max_splits = 1;
+    // encoder scratch (models with an encoder)
+    float* enc_x = nullptr;   // [max_src][d]
+    float* enc_q = nullptr;   // [max_src][I]
+    char* enc_k = nullptr;    // [max_src][I]
+    char* enc_v = nullptr;
+    int last_rows = 0;        // rows of the last LM-head pass (for debug logits)
+};
+
+}  // namespace
+
+struct bild_state {
+    const bild_pair* pair = nullptr;
+    ModelState ms[2];
+    Ctl* ctl = nullptr;   // device
+    Ctl* hctl = nullptr;  // pinned host mirror of the last readback
+    int* y = nullptr;     // device [max_len + 1]
+    int* src = nullptr;   // device [max_src]
+    hipStream_t stream = nullptr;
+    bool own_stream = false;
+    int max_src = 0, max_len = 0, n_max = 0;
+    // host mirror of the control block (kept exact by reading back after every pass)
+    int y_len = 0, draft_start = 0, len[2] = {0, 0}, n_src = 0, n0 = 0;
+    bool encoded = false;
+    bool debug_logits = false;
+    std::vector<void*> allocs;
+    std::vector<void*> host_allocs;
+};
+
+namespace {
+
+// ---------------------------------------------------------------- helpers
+int dev_alloc(std::vector<void*>& keep, void** p, size_t bytes) {
+    void* d = nullptr;
+    if (bytes == 0) bytes = 16;
+    if (hipMalloc(&d, bytes) != hipSuccess) return BILD_ENOMEM;
+    keep.push_back(d);
+    *p = d;
+    return BILD_OK;
+}
+
+bool config_ok(const bild_model_config& c) {
+    if (c.n_dec_layers < 1 || c.n_enc_layers < 0) return false;
+    if (c.d_model < 32 || c.d_model % 32 || c.d_ff < 32 || c.d_ff % 32) return false;
+    if (c.n_heads < 1 || c.d_head < 8 || c.d_head > 128 || c.d_head % 8) return false;
+    if ((c.n_heads * c.d_head) % 32) return false;
+    if (c.act < 0 || c.act > 2 || c.pos < 0 || c.pos > 1 || c.dtype < 0 || c.dtype > 1) return false;
+    if (c.vocab < 1 || c.bos < 0 || c.bos >= c.vocab) return false;
+    if (c.n_enc_layers > 0 && !c.cross_attn) return false;
+    if (!(c.norm_eps >= 0.f) || !(c.rope_base > 0.f)) return false;
+    if (c.tie_shift < 0) return false;
+    return true;
+}
+
+int upload_vec(bild_model* m, const float* src, int n, const float** out) {
+    void* d;
+    int rc = dev_alloc(m->allocs, &d, (size_t)n * 4);
+    if (rc) return rc;
+    if (hipMemcpy(d, src, (size_t)n * 4, hipMemcpyHostToDevice) != hipSuccess) return BILD_EHIP;
+    m->device_bytes += (size_t)n * 4;
+    *out = (const float*)d;
+    return BILD_OK;
+}
+
+int upload_tiled(bild_model* m, std::vector<char>& staging, int n, int k, TMat* out) {
+    const int kt = m->cfg.dtype == BILD_DT_BF16 ? 32 : 16;
+    const size_t bytes = tiled_bytes(n, k, m->cfg.dtype);
+    void* d;
+    int rc = dev_alloc(m->allocs, &d, bytes);
+    if (rc) return rc;
+    if (hipMemcpy(d, staging.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return BILD_EHIP;
+    m->device_bytes += bytes;
+    out->w = d;
+    out->n = n;
+    out->k = k;
+    out->tn = (n + 15) / 16;
+    out->tk = k / kt;
+    return BILD_OK;
+}
+
+int upload_matrix(bild_model* m, const float* src, bool k_by_n, int n, int k, TMat* out) {
+    std::vector<char> st(tiled_bytes(n, k, m->cfg.dtype));
+    tile_matrix(src, k_by_n, n, k, m->cfg.dtype, st.data());
+    return upload_tiled(m, st, n, k, out);
+}
+
+int upload_concat(bild_model* m, std::initializer_list<const float*> srcs, int n_each, int k, TMat* out) {
+    std::vector<const float*> ps(srcs);
+    std::vector<int> ns(ps.size(), n_each);
+    const int n = n_each * (int)ps.size();
+    std::vector<char> st(tiled_bytes(n, k, m->cfg.dtype));
+    tile_concat(ps.data(), ns.data(), (int)ps.size(), k, m->cfg.dtype, st.data());
+    return upload_tiled(m, st, n, k, out);
+}
+
+int upload_ffn_in(bild_model* m, const float* w_in, const float* w_up, TMat* out) {
+    const int d = m->cfg.d_model, f = m->cfg.d_ff;
+    if (!m->gated()) return upload_matrix(m, w_in, true, f, d, out);
+    std::vector<char> st(tiled_bytes(2 * f, d, m->cfg.dtype));
+    tile_gated_pair(w_in, w_up, f, d, m->cfg.dtype, st.data());
+    return upload_tiled(m, st, 2 * f, d, out);
+}
+
+}  // namespace
+
+// ======================================================================= models
+extern "C" int bild_model_num_tensors(const bild_model_config* c) {
+    if (!c || !config_ok(*c)) return BILD_EINVAL;
+    const int gated = c->act != BILD_ACT_RELU;
+    int n = 1 + (c->tied_head ? 0 : 1) + (c->n_enc_layers > 0 ? 1 : 0) + 1;
+    n += c->n_enc_layers * (8 + gated);
+    n += c->n_dec_layers * (8 + gated + (c->cross_attn ? 5 : 0));
+    return n;
+}
+
+extern "C" int bild_model_destroy(bild_model* m) {
+    if (!m) return BILD_EINVAL;
+    for (void* p : m->allocs) (void)hipFree(p);
+    delete m;
+    return BILD_OK;
+}
+
+extern "C" int bild_model_create(const bild_model_config* cfg, const float* const* t, int n_tensors,
+                                 bild_model** out) {
+    if (!cfg || !t || !out) return BILD_EINVAL;
+    if (!config_ok(*cfg)) return BILD_EINVAL;
+    if (n_tensors != bild_model_num_tensors(cfg)) return BILD_EINVAL;
+    for (int i = 0; i < n_tensors; ++i)
+        if (!t[i]) return BILD_EINVAL;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return BILD_EHIP;
+    bild_model* m = new (std::nothrow) bild_model();
+    if (!m) return BILD_ENOMEM;
+    m->cfg = *cfg;
+    const int d = cfg->d_model, I = m->inner(), F = cfg->d_ff, V = cfg->vocab;
+    int i = 0, rc = BILD_OK;
+#define UP(call)                         \
+    do {                                 \
+        rc = (call);                     \
+        if (rc) {                        \
+            bild_model_destroy(m);       \
+            return rc;                   \
+        }                                \
+    } while (0)
+    UP(upload_matrix(m, t[i++], false, V, d, &m->emb));
+    if (cfg->tied_head)
+        m->head = m->emb;
+    else
+        UP(upload_matrix(m, t[i++], false, V, d, &m->head));
+    if (cfg->n_enc_layers > 0) UP(upload_vec(m, t[i++], d, &m->enc_final));
+    UP(upload_vec(m, t[i++], d, &m->dec_final));
+    m->enc.resize(cfg->n_enc_layers);
+    for (auto& L : m->enc) {
+        UP(upload_vec(m, t[i], d, &L.ln1));
+        UP(upload_concat(m, {t[i + 1], t[i + 2], t[i + 3]}, I, d, &L.wqkv));
+        UP(upload_matrix(m, t[i + 4], true, d, I, &L.wo));
+        UP(upload_vec(m, t[i + 5], d, &L.ln2));
+        i += 6;
+        UP(upload_ffn_in(m, t[i], m->gated() ? t[i + 1] : nullptr, &L.win));
+        i += m->gated() ? 2 : 1;
+        UP(upload_matrix(m, t[i++], true, d, F, &L.wout));
+    }
+    m->dec.resize(cfg->n_dec_layers);
+    for (auto& L : m->dec) {
+        UP(upload_vec(m, t[i], d, &L.ln1));
+        UP(upload_concat(m, {t[i + 1], t[i + 2], t[i + 3]}, I, d, &L.wqkv));
+        UP(upload_matrix(m, t[i + 4], true, d, I, &L.wo));
+        i += 5;
+        if (cfg->cross_attn) {
+            UP(upload_vec(m, t[i], d, &L.lnc));
+            UP(upload_matrix(m, t[i + 1], true, I, d, &L.cwq));
+            UP(upload_concat(m, {t[i + 2], t[i + 3]}, I, d, &L.cwkv));
+            UP(upload_matrix(m, t[i + 4], true, d, I, &L.cwo));
+            i += 5;
+        }
+        UP(upload_vec(m, t[i++], d, &L.ln2));
+        UP(upload_ffn_in(m, t[i], m->gated() ? t[i + 1] : nullptr, &L.win));
+        i += m->gated() ? 2 : 1;
+        UP(upload_matrix(m, t[i++], true, d, F, &L.wout));
+    }
+#undef UP
+    *out = m;
+    return BILD_OK;
+}
+
+extern "C" int bild_pair_create(bild_model* s, bild_model* l, bild_pair** out) {
+    if (!s || !l || !out) return BILD_EINVAL;
+    if (s->cfg.vocab != l->cfg.vocab) return BILD_EINVAL;
+    if (s->cfg.cross_attn != l->cfg.cross_attn) return BILD_EINVAL;
+    if (s->cfg.bos != l->cfg.bos) return BILD_EINVAL;
+    const bool dec_only = !l->cfg.cross_attn;
+    bool borrows = false;
+    if (!dec_only) {
+        if (l->cfg.n_enc_layers < 1) return BILD_EINVAL;
+        if (s->cfg.n_enc_layers == 0) {
+            if (s->cfg.d_model != l->cfg.d_model) return BILD_EINVAL;
+            borrows = true;
+        }
+    }
+    bild_pair* p = new (std::nothrow) bild_pair();
+    if (!p) return BILD_ENOMEM;
+    p->m[0] = s;
+    p->m[1] = l;
+    p->decoder_only = dec_only;
+    p->small_borrows_encoder = borrows;
+    *out = p;
+    return BILD_OK;
+}
+
+extern "C" int bild_pair_destroy(bild_pair* p) {
+    if (!p) return BILD_EINVAL;
+    delete p;
+    return BILD_OK;
+}
+
+// ======================================================================= state
+extern "C" int bild_state_destroy(bild_state* s) {
+    if (!s) return BILD_EINVAL;
+    if (s->stream) (void)hipStreamSynchronize(s->stream);
+    for (void* p : s->allocs) (void)hipFree(p);
+    for (void* p : s->host_allocs) (void)hipHostFree(p);
+    if (s->own_stream && s->stream) (void)hipStreamDestroy(s->stream);
+    delete s;
+    return BILD_OK;
+}
+
+extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, int n_max, void* hip_stream,
+                                 bild_state** out) {
+    if (!p || !out) return BILD_EINVAL;
+    if (max_src < 1 || max_len < 2 || n_max < 0 || n_max > kMaxRows - 1) return BILD_EINVAL;
+    if (p->decoder_only && max_len < max_src + 1) return BILD_EINVAL;
+    bild_state* s = new (std::nothrow) bild_state();
+    if (!s) return BILD_ENOMEM;
+    s->pair = p;
+    s->max_src = max_src;
+    s->max_len = max_len;
+    s->n_max = n_max;
+    int rc = BILD_OK;
+#define AL(ptr, bytes)                                            \
+    do {                                                          \
+        rc = dev_alloc(s->allocs, (void**)&(ptr), (bytes));       \
+        if (rc) {                                                 \
+            bild_state_destroy(s);                                \
+            return rc;                                            \
+        }                                                         \
+    } while (0)
+    if (hip_stream) {
+        s->stream = (hipStream_t)hip_stream;
+    } else {
+        if (hipStreamCreate(&s->stream) != hipSuccess) {
+            delete s;
+            return BILD_EHIP;
+        }
+        s->own_stream = true;
+    }
+    AL(s->ctl, sizeof(Ctl));
+    AL(s->y, sizeof(int) * (size_t)(max_len + 1));
+    AL(s->src, sizeof(int) * (size_t)max_src);
+    void* h = nullptr;
+    if (hipHostMalloc(&h, sizeof(Ctl), hipHostMallocDefault) != hipSuccess) {
+        bild_state_destroy(s);
+        return BILD_ENOMEM;
+    }
+    s->host_allocs.push_back(h);
+    s->hctl = (Ctl*)h;
+    for (int w = 0; w < 2; ++w) {
+        ModelState& M = s->ms[w];
+        const bild_model* m = p->m[w];
+        M.m = m;
+        const size_t I = m->inner(), d = m->cfg.d_model, F = m->cfg.d_ff, L = m->cfg.n_dec_layers;
+        const size_t esz = m->esz();
+        AL(M.kcache, L * (size_t)max_len * I * esz);
+        AL(M.vcache, L * (size_t)max_len * I * esz);
+        if (m->cfg.cross_attn) {
+            AL(M.ck, L * (size_t)max_src * I * esz);
+            AL(M.cv, L * (size_t)max_src * I * esz);
+        }
+        AL(M.x, sizeof(float) * kMaxRows * d);
+        AL(M.q, sizeof(float) * kMaxRows * I);
+        AL(M.a, sizeof(float) * kMaxRows * I);
+        AL(M.h, sizeof(float) * kMaxRows * F);
+        M.nparts_cap = (m->head.tn + 0) / 1 + 1;  // at most one partial per feature tile
+        AL(M.part, sizeof(StatPart) * (size_t)M.nparts_cap * kMaxRows);
+        AL(M.zt, sizeof(float) * kMaxRows);
+        M.max_splits = std::max(1, std::min(64, (std::max(max_len, max_src) + 511) / 512));
+        AL(M.att_o, sizeof(float) * (size_t)M.max_splits * kMaxRows * I);
+        AL(M.att_ml, sizeof(float) * (size_t)M.max_splits * kMaxRows * m->cfg.n_heads * 2);
+        if (m->cfg.n_enc_layers > 0) {
+            AL(M.enc_x, sizeof(float) * (size_t)max_src * d);
+            AL(M.enc_q, sizeof(float) * (size_t)max_src * I);
+            AL(M.enc_k, (size_t)max_src * I * esz);
+            AL(M.enc_v, (size_t)max_src * I * esz);
+        }
+    }
+#undef AL
+    if (hipMemsetAsync(s->ctl, 0, sizeof(Ctl), s->stream) != hipSuccess ||
+        hipStreamSynchronize(s->stream) != hipSuccess) {
+        bild_state_destroy(s);
+        return BILD_EHIP;
+    }
+    *out = s;
+    return BILD_OK;
+}
+
+namespace {
+
+int push_ctl(bild_state* s) {
+    Ctl* h = s->hctl;
+    std::memset(h, 0, sizeof(Ctl));
+    h->y_len = s->y_len;
+    h->draft_start = s->draft_start;
+    h->len[0] = s->len[0];
+    h->len[1] = s->len[1];
+    h->n_src = s->n_src;
+    h->n_max = s->n_max;
+    HIPC(hipMemcpyAsync(s->ctl, h, sizeof(Ctl), hipMemcpyHostToDevice, s->stream));
+    HIPC(hipStreamSynchronize(s->stream));
+    return BILD_OK;
+}
+
+int pull_ctl(bild_state* s) {
+    HIPC(hipMemcpyAsync(s->hctl, s->ctl, sizeof(Ctl), hipMemcpyDeviceToHost, s->stream));
+    HIPC(hipStreamSynchronize(s->stream));
+    s->y_len = s->hctl->y_len;
+    s->draft_start = s->hctl->draft_start;
+    s->len[0] = s->hctl->len[0];
+    s->len[1] = s->hctl->len[1];
+    return BILD_OK;
+}
+
+int pick_splits(const ModelState& M, int nkeys, int heads) {
+    // enough workgroups to cover the chip once the key range is long
+    int sp = 1;
+    while (sp < M.max_splits && heads * sp < 256 && nkeys / (sp * 2) >= 256) sp *= 2;
+    return sp;
+}
+
+GemmArgs gemm_base(const bild_model* m, const TMat& W, const float* x, int ldx, int T, const float* gain) {
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.W = W;
+    g.x = x;
+    g.ldx = ldx;
+    g.T = T;
+    g.gain = gain;
+    g.eps = m->cfg.norm_eps;
+    g.d_head = m->cfg.d_head;
+    g.i_dim = m->inner();
+    g.rope_base = m->cfg.rope_base;
+    g.act = m->cfg.act;
+    g.vocab = m->cfg.vocab;
+    return g;
+}
+
+int run_gemm(bild_state* s, const bild_model* m, GemmArgs& g) {
+    gemm_pick_shape(g, m->cfg.dtype);
+    HIPC(launch_gemm(g, m->cfg.dtype, s->stream));
+    return BILD_OK;
+}
+
+// One decoder pass of model w over rows y[len .. len+T): embed, layers, and (lm_rows > 0)
+// the LM head over the last lm_rows rows followed by the policy `mode`; lm_rows == 0
+// only advances the cache (catch-up / prefill).
+int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, float alpha) {
+    ModelState& M = s->ms[w];
+    const bild_model* m = M.m;
+    const bild_model_config& c = m->cfg;
+    const int d = c.d_model, I = m->inner(), F = c.d_ff, dt = c.dtype;
+    const size_t esz = m->esz();
+    const int* len_ptr = &s->ctl->len[w];
+    EmbedArgs e;
+    std::memset(&e, 0, sizeof(e));
+    e.E = m->emb;
+    e.tokens = s->y;
+    e.base_ptr = len_ptr;
+    e.T = T;
+    e.d = d;
+    e.vocab = c.vocab;
+    e.tie_shift = c.tie_shift;
+    e.sinusoidal = c.pos == BILD_POS_SINUSOIDAL;
+    e.embed_scale = c.embed_scale;
+    e.x = M.x;
+    HIPC(launch_embed(e, dt, s->stream));
+    const float att_scale = 1.f / std::sqrt((float)c.d_head);
+    for (int l = 0; l < c.n_dec_layers; ++l) {
+        const LayerW& L = m->dec[l];
+        char* kc = M.kcache + (size_t)l * s->max_len * I * esz;
+        char* vc = M.vcache + (size_t)l * s->max_len * I * esz;
+        {
+            GemmArgs g = gemm_base(m, L.wqkv, M.x, d, T, L.ln1);
+            g.epi = EPI_QKV;
+            g.q_dim = I;
+            g.q_out = M.q;
+            g.k_cache = kc;
+            g.v_cache = vc;
+            g.pos_ptr = len_ptr;
+            g.rope = c.pos == BILD_POS_ROPE;
+            int rc = run_gemm(s, m, g);
+            if (rc) return rc;
+        }
+        {
+            AttnArgs a;
+            std::memset(&a, 0, sizeof(a));
+            a.q = M.q; a.k = kc; a.v = vc; a.out = M.a;
+            a.T = T; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
+            a.causal = 1;
+            a.base_ptr = len_ptr;
+            a.splits = pick_splits(M, s->len[w] + T, c.n_heads);
+            a.part_o = M.att_o; a.part_ml = M.att_ml;
+            a.scale = att_scale;
+            HIPC(launch_attention(a, dt, s->stream));
+        }
+        {
+            GemmArgs g = gemm_base(m, L.wo, M.a, I, T, nullptr);
+            g.epi = EPI_RESID;
+            g.out = M.x;
+            g.ldo = d;
+            int rc = run_gemm(s, m, g);
+            if (rc) return rc;
+        }
+        if (c.cross_attn) {
+            {
+                GemmArgs g = gemm_base(m, L.cwq, M.x, d, T, L.lnc);
+                g.epi = EPI_STORE;
+                g.out = M.q;
+                g.ldo = I;
+                int rc = run_gemm(s, m, g);
+                if (rc) return rc;
+            }
+            {
+                AttnArgs a;
+                std::memset(&a, 0, sizeof(a));
+                a.q = M.q;
+                a.k = M.ck + (size_t)l * s->max_src * I * esz;
+                a.v = M.cv + (size_t)l * s->max_src * I * esz;
+                a.out = M.a;
+                a.T = T; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
+                a.causal = 0;
+                a.nkeys_ptr = &s->ctl->n_src;
+                a.splits = pick_splits(M, s->n_src, c.n_heads);
+                a.part_o = M.att_o; a.part_ml = M.att_ml;
+                a.scale = att_scale;
+                HIPC(launch_attention(a, dt, s->stream));
+            }
+            {
+                GemmArgs g = gemm_base(m, L.cwo, M.a, I, T, nullptr);
+                g.epi = EPI_RESID;
+                g.out = M.x;
+                g.ldo = d;
+                int rc = run_gemm(s, m, g);
+                if (rc) return rc;
+            }
+        }
+        {
+            GemmArgs g = gemm_base(m, L.win, M.x, d, T, L.ln2);
+            g.epi = EPI_ACT;
+            g.out = M.h;
+            g.ldo = F;
+            int rc = run_gemm(s, m, g);
+            if (rc) return rc;
+        }
+        {
+            GemmArgs g = gemm_base(m, L.wout, M.h, F, T, nullptr);
+            g.epi = EPI_RESID;
+            g.out = M.x;
+            g.ldo = d;
+            int rc = run_gemm(s, m, g);
+            if (rc) return rc;
+        }
+    }
+    FinishArgs f;
+    std::memset(&f, 0, sizeof(f));
+    f.ctl = s->ctl;
+    f.y = s->y;
+    f.which = w;
+    f.rows_consumed = T;
+    f.alpha = alpha;
+    f.y_cap = s->max_len;
+    if (lm_rows > 0) {
+        GemmArgs g = gemm_base(m, m->head, M.x + (size_t)(T - lm_rows) * d, d, lm_rows, m->dec_final);
+        g.epi = EPI_LMHEAD;
+        g.scale = c.logit_scale;
+        g.pos_ptr = len_ptr;
+        g.pos_add = T - lm_rows;
+        g.y = s->y;
+        g.ylen_ptr = &s->ctl->y_len;
+        g.part = M.part;
+        g.zt = M.zt;
+        g.dbg = s->debug_logits ? M.dbg : nullptr;
+        g.row_off = 0;
+        gemm_pick_shape(g, dt);
+        if ((int)gemm_num_blocks(g) > M.nparts_cap) return BILD_ECAP;
+        HIPC(launch_gemm(g, dt, s->stream));
+        f.part = M.part;
+        f.nparts = (int)gemm_num_blocks(g);
+        f.zt = M.zt;
+        f.T = lm_rows;
+        f.mode = mode;
+        M.last_rows = lm_rows;
+    } else {
+        f.mode = 3;
+    }
+    HIPC(launch_finish(f, s->stream));
+    return BILD_OK;
+}
+
+// Brings model w's cache up to `target` consumed rows with LM-head-less passes.
+int catch_up(bild_state* s, int w, int target) {
+    while (s->len[w] < target) {
+        const int T = std::min(kMaxRows, target - s->len[w]);
+        int rc = decoder_pass(s, w, T, 0, 3, 0.f);
+        if (rc) return rc;
+        s->len[w] += T;  // the device advances the same amount
+    }
+    return BILD_OK;
+}
+
+// Encoder of model w over the source in s->src, then the cross K/V of every decoder
+// layer of each model that uses this encoder's output.
+int run_encoder(bild_state* s, int w) {
+    ModelState& M = s->ms[w];
+    const bild_model* m = M.m;
+    const bild_model_config& c = m->cfg;
+    const int d = c.d_model, I = m->inner(), F = c.d_ff, dt = c.dtype, S = s->n_src;
+    const float att_scale = 1.f / std::sqrt((float)c.d_head);
+    for (int r0 = 0; r0 < S; r0 += kMaxRows) {
+        const int T = std::min(kMaxRows, S - r0);
+        EmbedArgs e;
+        std::memset(&e, 0, sizeof(e));
+        e.E = m->emb; e.tokens = s->src; e.base_add = r0; e.T = T; e.d = d; e.vocab = c.vocab;
+        e.tie_shift = c.tie_shift; e.sinusoidal = c.pos == BILD_POS_SINUSOIDAL; e.embed_scale = c.embed_scale;
+        e.x = M.enc_x + (size_t)r0 * d;
+        HIPC(launch_embed(e, dt, s->stream));
+    }
+    for (int l = 0; l < c.n_enc_layers; ++l) {
+        const LayerW& L = m->enc[l];
+        for (int r0 = 0; r0 < S; r0 += kMaxRows) {
+            const int T = std::min(kMaxRows, S - r0);
+            GemmArgs g = gemm_base(m, L.wqkv, M.enc_x + (size_t)r0 * d, d, T, L.ln1);
+            g.epi = EPI_QKV;
+            g.q_dim = I;
+            g.q_out = M.enc_q + (size_t)r0 * I;
+            g.k_cache = M.enc_k;
+            g.v_cache = M.enc_v;
+            g.pos_add = r0;
+            g.rope = c.pos == BILD_POS_ROPE;
+            int rc = run_gemm(s, m, g);
+            if (rc) return rc;
+        }
+        for (int r0 = 0; r0 < S; r0 += kMaxRows) {
+            const int T = std::min(kMaxRows, S - r0);
+            AttnArgs a;
+            std::memset(&a, 0, sizeof(a));
+            a.q = M.enc_q + (size_t)r0 * I; a.k = M.enc_k; a.v = M.enc_v; a.out = M.a;
+            a.T = T; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
+            a.causal = 0;
+            a.nkeys_fixed = S;
+            a.splits = 1;
+            a.scale = att_scale;
+            HIPC(launch_attention(a, dt, s->stream));
+            GemmArgs g = gemm_base(m, L.wo, M.a, I, T, nullptr);
+            g.epi = EPI_RESID;
+            g.out = M.enc_x + (size_t)r0 * d;
+            g.ldo = d;
+            int rc = run_gemm(s, m, g);
+            if (rc) return rc;
+            GemmArgs g1 = gemm_base(m, L.win, M.enc_x + (size_t)r0 * d, d, T, L.ln2);
+            g1.epi = EPI_ACT;
+            g1.out = M.h;
+            g1.ldo = F;
+            rc = run_gemm(s, m, g1);
+            if (rc) return rc;
+            GemmArgs g2 = gemm_base(m, L.wout, M.h, F, T, nullptr);
+            g2.epi = EPI_RESID;
+            g2.out = M.enc_x + (size_t)r0 * d;
+            g2.ldo = d;
+            rc = run_gemm(s, m, g2);
+            if (rc) return rc;
+        }
+    }
+    // cross K/V: K = norm_final(enc_x) Wk, V = ... for this model and, if it borrows, the small one
+    for (int u = 0; u < 2; ++u) {
+        const bool uses = (u == w) || (u == 0 && w == 1 && s->pair->small_borrows_encoder);
+        if (!uses) continue;
+        ModelState& U = s->ms[u];
+        const bild_model* mu = U.m;
+        const int Iu = mu->inner();
+        const size_t esz = mu->esz();
+        for (int l = 0; l < mu->cfg.n_dec_layers; ++l) {
+            for (int r0 = 0; r0 < S; r0 += kMaxRows) {
+                const int T = std::min(kMaxRows, S - r0);
+                GemmArgs g = gemm_base(mu, mu->dec[l].cwkv, M.enc_x + (size_t)r0 * d, d, T, m->enc_final);
+                g.eps = m->cfg.norm_eps;
+                g.epi = EPI_QKV;
+                g.q_dim = 0;
+                g.i_dim = Iu;
+                g.k_cache = U.ck + (size_t)l * s->max_src * Iu * esz;
+                g.v_cache = U.cv + (size_t)l * s->max_src * Iu * esz;
+                g.pos_add = r0;
+                g.rope = 0;
+                gemm_pick_shape(g, mu->cfg.dtype);
+                HIPC(launch_gemm(g, mu->cfg.dtype, s->stream));
+            }
+        }
+    }
+    return BILD_OK;
+}
+
+}  // namespace
+
+// ======================================================================= request API
+extern "C" int bild_encode(bild_state* s, const int32_t* src, int n_src) {
+    if (!s || !src) return BILD_EINVAL;
+    if (n_src < 1) return BILD_EINVAL;
+    if (n_src > s->max_src) return BILD_ECAP;
+    const int V = s->pair->m[1]->cfg.vocab;
+    for (int i = 0; i < n_src; ++i)
+        if (src[i] < 0 || src[i] >= V) return BILD_EINVAL;
+    const bool dec_only = s->pair->decoder_only;
+    if (dec_only && n_src + 1 > s->max_len) return BILD_ECAP;
+    s->encoded = false;
+    s->n_src = n_src;
+    s->len[0] = s->len[1] = 0;
+    if (dec_only) {
+        HIPC(hipMemcpyAsync(s->y, src, sizeof(int) * (size_t)n_src, hipMemcpyHostToDevice, s->stream));
+        s->y_len = n_src;
+    } else {
+        const int32_t bos = s->pair->m[1]->cfg.bos;
+        HIPC(hipMemcpyAsync(s->src, src, sizeof(int) * (size_t)n_src, hipMemcpyHostToDevice, s->stream));
+        HIPC(hipMemcpyAsync(s->y, &bos, sizeof(int), hipMemcpyHostToDevice, s->stream));
+        s->y_len = 1;
+    }
+    s->n0 = s->y_len;
+    s->draft_start = s->y_len;
+    int rc = push_ctl(s);
+    if (rc) return rc;
+    if (dec_only) {
+        for (int w = 0; w < 2; ++w) {
+            rc = catch_up(s, w, n_src - 1);
+            if (rc) return rc;
+        }
+    } else {
+        rc = run_encoder(s, 1);
+        if (rc) return rc;
+        if (!s->pair->small_borrows_encoder) {
+            rc = run_encoder(s, 0);
+            if (rc) return rc;
+        }
+    }
+    rc = pull_ctl(s);
+    if (rc) return rc;
+    s->encoded = true;
+    return BILD_OK;
+}
+
+extern "C" int bild_small_step(bild_state* s, float alpha_fb, int32_t* token, int32_t* fallback_flag,
+                               float* max_prob) {
+    if (!s || !token || !fallback_flag) return BILD_EINVAL;
+    if (!s->encoded) return BILD_ESTATE;
+    if (s->len[0] >= s->y_len) return BILD_ESTATE;  // nothing unconsumed
+    if (s->y_len >= s->max_len) return BILD_ECAP;
+    int rc = catch_up(s, 0, s->y_len - 1);
+    if (rc) return rc;
+    rc = decoder_pass(s, 0, 1, 1, 0, alpha_fb);
+    if (rc) return rc;
+    rc = pull_ctl(s);
+    if (rc) return rc;
+    *token = s->hctl->res_tok;
+    *fallback_flag = s->hctl->res_flag & 1;
+    if (max_prob) *max_prob = s->hctl->res_pmax;
+    return BILD_OK;
+}
+
+extern "C" int bild_large_verify(bild_state* s, const int32_t* draft, int n, float alpha_rb, int32_t* out_tokens,
+                                 int32_t* n_out, int32_t* rollback_pos, float* nll) {
+    if (!s || !out_tokens || !n_out || !rollback_pos) return BILD_EINVAL;
+    if (!s->encoded) return BILD_ESTATE;
+    if (draft) {
+        if (n < 0) return BILD_EINVAL;
+        if (n + 1 > kMaxRows) return BILD_ECAP;
+        if (s->draft_start + n + 1 > s->max_len) return BILD_ECAP;
+        const int V = s->pair->m[1]->cfg.vocab;
+        for (int i = 0; i < n; ++i)
+            if (draft[i] < 0 || draft[i] >= V) return BILD_EINVAL;
+        if (n > 0)
+            HIPC(hipMemcpyAsync(s->y + s->draft_start, draft, sizeof(int) * (size_t)n, hipMemcpyHostToDevice,
+                                s->stream));
+        s->y_len = s->draft_start + n;
+        s->len[0] = std::min(s->len[0], s->draft_start);
+        s->len[1] = std::min(s->len[1], s->draft_start - 1);
+        int rc = push_ctl(s);
+        if (rc) return rc;
+    } else {
+        n = s->y_len - s->draft_start;
+        if (n + 1 > kMaxRows) return BILD_ECAP;
+        if (s->y_len + 1 > s->max_len) return BILD_ECAP;
+    }
+    if (s->len[1] > s->draft_start - 1) return BILD_ESTATE;
+    int rc = catch_up(s, 1, s->draft_start - 1);
+    if (rc) return rc;
+    const int ds = s->draft_start;
+    rc = decoder_pass(s, 1, n + 1, n + 1, 1, alpha_rb);
+    if (rc) return rc;
+    rc = pull_ctl(s);
+    if (rc) return rc;
+    const int r = s->hctl->res_r;
+    *rollback_pos = r;
+    *n_out = r + 1;
+    HIPC(hipMemcpyAsync(out_tokens, s->y + ds, sizeof(int) * (size_t)(r + 1), hipMemcpyDeviceToHost, s->stream));
+    HIPC(hipStreamSynchronize(s->stream));
+    if (nll)
+        for (int i = 0; i < n; ++i) nll[i] = (i <= r) ? s->hctl->res_nll[i] : NAN;
+    return BILD_OK;
+}
+
+extern "C" int bild_kv_truncate(bild_state* s, int which, int pos) {
+    if (!s || which < 1 || which > 3 || pos < 0) return BILD_EINVAL;
+    if (!s->encoded) return BILD_ESTATE;
+    if ((which & 1) && pos > s->len[0]) return BILD_EINVAL;
+    if ((which & 2) && pos > s->len[1]) return BILD_EINVAL;
+    // the large model must never be ahead of draft_start - 1; cutting only lowers lengths
+    if (which & 1) s->len[0] = pos;
+    if (which & 2) s->len[1] = pos;
+    return push_ctl(s);
+}
+
+extern "C" int bild_seq_truncate(bild_state* s, int n_keep) {
+    if (!s) return BILD_EINVAL;
+    if (!s->encoded) return BILD_ESTATE;
+    if (n_keep < s->n0 || n_keep > s->y_len) return BILD_EINVAL;
+    s->y_len = n_keep;
+    s->draft_start = std::min(s->draft_start, n_keep);
+    s->len[0] = std::min(s->len[0], n_keep - 1);
+    s->len[1] = std::min(s->len[1], s->draft_start - 1);
+    return push_ctl(s);
+}
+
+extern "C" int bild_force_tokens(bild_state* s, int first, const int32_t* tokens, int n, int draft_start) {
+    if (!s || n < 0 || (n > 0 && !tokens)) return BILD_EINVAL;
+    if (!s->encoded) return BILD_ESTATE;
+    if (first < s->n0 || first > s->y_len) return BILD_EINVAL;
+    if (first + n >= s->max_len) return BILD_ECAP;
+    if (draft_start < s->n0 || draft_start > first + n) return BILD_EINVAL;
+    const int V = s->pair->m[1]->cfg.vocab;
+    for (int i = 0; i < n; ++i)
+        if (tokens[i] < 0 || tokens[i] >= V) return BILD_EINVAL;
+    if (n > 0)
+        HIPC(hipMemcpyAsync(s->y + first, tokens, sizeof(int) * (size_t)n, hipMemcpyHostToDevice, s->stream));
+    s->y_len = first + n;
+    s->draft_start = draft_start;
+    s->len[0] = std::min(s->len[0], first);
+    s->len[1] = std::min(s->len[1], std::min(first, draft_start - 1));
+    return push_ctl(s);
+}
+
+extern "C" int bild_get_lengths(bild_state* s, int32_t* y_len, int32_t* draft_start, int32_t* len_small,
+                                int32_t* len_large) {
+    if (!s) return BILD_EINVAL;
+    if (y_len) *y_len = s->y_len;
+    if (draft_start) *draft_start = s->draft_start;
+    if (len_small) *len_small = s->len[0];
+    if (len_large) *len_large = s->len[1];
+    return BILD_OK;
+}
+
+extern "C" int bild_get_sequence(bild_state* s, int32_t* out, int cap, int32_t* n) {
+    if (!s || !out || !n) return BILD_EINVAL;
+    if (cap < s->y_len) return BILD_ECAP;
+    if (s->y_len > 0) {
+        HIPC(hipMemcpyAsync(out, s->y, sizeof(int) * (size_t)s->y_len, hipMemcpyDeviceToHost, s->stream));
+        HIPC(hipStreamSynchronize(s->stream));
+    }
+    *n = s->y_len;
+    return BILD_OK;
+}
+
+extern "C" int bild_generate(bild_state* s, const int32_t* src, int n_src, float alpha_fb, float alpha_rb,
+                             int max_new, int32_t eos, int32_t* out, int32_t* n_out, bild_stats* stats) {
+    if (!s || !src || !out || !n_out || max_new < 0) return BILD_EINVAL;
+    int rc = bild_encode(s, src, n_src);
+    if (rc) return rc;
+    if (s->n0 + max_new > s->max_len) return BILD_ECAP;
+    bild_stats st;
+    std::memset(&st, 0, sizeof(st));
+    int last = -1;
+    while (s->y_len - s->n0 < max_new && !(s->y_len > s->n0 && last == eos && eos >= 0)) {
+        int32_t tok, flag;
+        rc = bild_small_step(s, alpha_fb, &tok, &flag, nullptr);
+        if (rc) return rc;
+        st.small_steps++;
+        if (!flag) {
+            last = tok;
+            continue;
+        }
+        if (s->hctl->res_flag & 2)
+            st.fallbacks_forced++;
+        else
+            st.fallbacks_conf++;
+        int32_t toks[kMaxRows], cnt, r;
+        const int n = s->y_len - s->draft_start;
+        rc = bild_large_verify(s, nullptr, 0, alpha_rb, toks, &cnt, &r, nullptr);
+        if (rc) return rc;
+        st.large_calls++;
+        st.rows_verified += n + 1;
+        if (r < n) {
+            st.rollbacks++;
+            st.tokens_discarded += n - r;
+        }
+        last = toks[r];
+    }
+    st.n_generated = s->y_len - s->n0;
+    *n_out = st.n_generated;
+    if (st.n_generated > 0) {
+        HIPC(hipMemcpyAsync(out, s->y + s->n0, sizeof(int) * (size_t)st.n_generated, hipMemcpyDeviceToHost,
+                            s->stream));
+        HIPC(hipStreamSynchronize(s->stream));
+    }
+    if (stats) *stats = st;
+    return BILD_OK;
+}
+
+extern "C" int bild_greedy(bild_state* s, int which, const int32_t* src, int n_src, int max_new, int32_t eos,
+                           int32_t* out, int32_t* n_out) {
+    if (!s || !src || !out || !n_out || max_new < 0 || which < 1 || which > 2) return BILD_EINVAL;
+    int rc = bild_encode(s, src, n_src);
+    if (rc) return rc;
+    if (s->n0 + max_new > s->max_len) return BILD_ECAP;
+    const int w = which - 1;
+    int last = -1;
+    while (s->y_len - s->n0 < max_new && !(s->y_len > s->n0 && last == eos && eos >= 0)) {
+        rc = catch_up(s, w, s->y_len - 1);
+        if (rc) return rc;
+        rc = decoder_pass(s, w, 1, 1, 2, 0.f);
+        if (rc) return rc;
+        rc = pull_ctl(s);
+        if (rc) return rc;
+        last = s->hctl->res_tok;
+    }
+    // leave the state consistent for a following BiLD call: the other model lags, which is allowed
+    *n_out = s->y_len - s->n0;
+    if (*n_out > 0) {
+        HIPC(hipMemcpyAsync(out, s->y + s->n0, sizeof(int) * (size_t)*n_out, hipMemcpyDeviceToHost, s->stream));
+        HIPC(hipStreamSynchronize(s->stream));
+    }
+    return BILD_OK;
+}
+
+extern "C" int bild_debug_enable_logits(bild_state* s, int enable) {
+    if (!s) return BILD_EINVAL;
+    if (enable) {
+        for (int w = 0; w < 2; ++w) {
+            if (s->ms[w].dbg) continue;
+            int rc = dev_alloc(s->allocs, (void**)&s->ms[w].dbg, sizeof(float) * kMaxRows * (size_t)s->ms[w].m->cfg.vocab);
+            if (rc) return rc;
+        }
+    }
+    s->debug_logits = enable != 0;
+    return BILD_OK;
+}
+
+extern "C" int bild_debug_logits(bild_state* s, int which, int row, float* out) {
+    if (!s || !out || which < 1 || which > 2) return BILD_EINVAL;
+    ModelState& M = s->ms[which - 1];
+    if (!s->debug_logits || !M.dbg) return BILD_ESTATE;
+    if (row < 0 || row >= M.last_rows) return BILD_EINVAL;
+    const size_t V = M.m->cfg.vocab;
+    HIPC(hipMemcpyAsync(out, M.dbg + (size_t)row * V, sizeof(float) * V, hipMemcpyDeviceToHost, s->stream));
+    HIPC(hipStreamSynchronize(s->stream));
+    return BILD_OK;
+}
+
+extern "C" int64_t bild_pass_bytes(const bild_state* s, int which, int t_cache, int rows) {
+    if (!s || which < 1 || which > 2) return BILD_EINVAL;
+    const bild_model* m = s->ms[which - 1].m;
+    const bild_model_config& c = m->cfg;
+    const int64_t d = c.d_model, I = m->inner(), F = c.d_ff, L = c.n_dec_layers, B = m->esz();
+    const int64_t attn = 4 * d * I * (c.cross_attn ? 2 : 1);
+    const int64_t ffn = (m->gated() ? 3 : 2) * d * F;
+    int64_t elems = L * (attn + ffn) + (int64_t)c.vocab * d + L * 2 * I * (int64_t)(t_cache + rows);
+    if (c.cross_attn) elems += L * 2 * I * (int64_t)s->n_src;
+    return elems * B;
+}
+
+extern "C" const char* bild_strerror(int code) {
+    switch (code) {
+        case BILD_OK: return "ok";
+        case BILD_EINVAL: return "invalid argument";
+        case BILD_ESTATE: return "call not valid in the current state";
+        case BILD_ECAP: return "capacity exceeded";
+        case BILD_EHIP: return "HIP runtime error";
+        case BILD_ENOMEM: return "out of memory";
+        default: return "unknown error";
+    }
+}

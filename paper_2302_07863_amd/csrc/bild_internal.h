@@ -1,0 +1,161 @@
+// Internal structures shared by the host runtime and the HIP kernels of the
+// BiLD library (gfx950).  Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bild.h"
+
+namespace bild {
+
+constexpr int kMaxRows = BILD_MAX_ROWS;  // rows per decoder pass
+constexpr int kTileBytes = 1024;         // one streamed weight tile: 16 output features x KT inputs
+
+// A weight matrix in streaming layout.  Logical shape [n features][k inputs]
+// (y = W x).  It is cut into tiles of 16 features x KT inputs (KT = 32 for bf16,
+// 16 for fp32), each 1 KiB and stored in the register order of the matrix-core
+// A operand: lane l of a wavefront owns the 16 bytes at l*16, which hold feature
+// (l % 16) and inputs (l / 16) * KT/4 .. +KT/4-1 of the tile.  Tiles of one
+// feature block are contiguous along k, so a wavefront streaming along k issues
+// back-to-back 1 KiB coalesced loads.  Features beyond n are zero padding.
+struct TMat {
+    const void* w = nullptr;
+    int n = 0;   // features (rows of the logical matrix)
+    int k = 0;   // inputs
+    int tn = 0;  // feature tiles = ceil(n / 16)
+    int tk = 0;  // input tiles   = k / KT
+};
+
+// Device-resident control block of one request.  Kernels read lengths from here
+// so that a captured launch sequence stays valid as the sequence grows.
+struct Ctl {
+    int y_len;
+    int draft_start;
+    int len[2];       // consumed rows per model: [0] small, [1] large
+    int n_src;        // source length (cross-attention keys) or prompt length
+    int n_max;
+    // results of the last pass, copied to the host after it
+    int res_tok;
+    int res_flag;
+    int res_r;
+    int res_n;
+    float res_pmax;
+    int pad;
+    float res_nll[kMaxRows];
+    int res_rowtok[kMaxRows];  // argmax of every row of the last pass
+};
+
+// Partial softmax statistics of one row over a slice of the vocabulary.
+struct StatPart {
+    float m;    // max logit
+    float s;    // sum exp(z - m)
+    int idx;    // argmax (lowest id among equal maxima)
+    int pad;
+};
+
+enum Epilogue : int {
+    EPI_STORE = 0,  // out[t][n] = v
+    EPI_RESID = 1,  // out[t][n] += v
+    EPI_QKV = 2,    // n < q_dim -> q_out; then K rows, then V rows of the cache (RoPE on q, k)
+    EPI_ACT = 3,    // out[t][n] = act(v) or act(gate) * up for gated FFNs
+    EPI_LMHEAD = 4  // z = scale * v; softmax partials, logit of the target token
+};
+
+struct GemmArgs {
+    TMat W;
+    const float* x;  // [T][ldx] fp32 activations
+    int ldx;
+    int T;
+    const float* gain;  // non-null: RMSNorm prologue, x_hat = x * rsqrt(mean x^2 + eps) * gain
+    float eps;
+    int epi;
+    float* out;
+    int ldo;
+    // EPI_QKV
+    int q_dim;      // features [0, q_dim) are queries (0 for a K/V-only projection)
+    int i_dim;      // inner dim I; K features follow q, V features follow K
+    float* q_out;   // [T][I] fp32
+    void* k_cache;  // [capacity][I] in the model dtype
+    void* v_cache;
+    const int* pos_ptr;  // position of row 0 = (pos_ptr ? *pos_ptr : 0) + pos_add
+    int pos_add;
+    int rope;
+    float rope_base;
+    int d_head;
+    // EPI_ACT
+    int act;
+    // EPI_LMHEAD
+    float scale;
+    int vocab;
+    const int* y;        // sequence; target of row t is y[*pos_ptr + pos_add + t + 1] if below *ylen_ptr
+    const int* ylen_ptr;
+    StatPart* part;      // [gridDim.x][kMaxRows]
+    float* zt;           // [kMaxRows] logit of each row's target
+    float* dbg;          // nullable [T][vocab] full logits (tests only)
+    int row_off;         // row index of x row 0 within the pass (for part / zt / dbg / targets)
+    // launch shape
+    int wk;  // the 4 waves of a workgroup split k wk ways (1, 2 or 4)
+    int rw;  // feature tiles per wave (1 or 2)
+    int kc;  // inputs staged in LDS per chunk
+};
+
+struct AttnArgs {
+    const float* q;  // [T][I]
+    const void* k;   // [capacity][I]
+    const void* v;
+    float* out;      // [T][I]
+    int T, heads, d_head, i_dim;
+    int causal;                // 1: row t sees keys <= base + t
+    const int* base_ptr;       // causal: base = *base_ptr + base_add = position of row 0
+    int base_add;
+    const int* nkeys_ptr;      // non-causal: number of keys = *nkeys_ptr (or nkeys_fixed if null)
+    int nkeys_fixed;
+    int splits;                // key ranges handled by separate workgroups
+    float* part_o;             // [splits][T][I]   unnormalised partial outputs
+    float* part_ml;            // [splits][T][heads][2] (max, sum)
+    float scale;
+};
+
+struct EmbedArgs {
+    TMat E;
+    const int* tokens;      // token of row t is tokens[base + t]
+    const int* base_ptr;    // base = (base_ptr ? *base_ptr : 0) + base_add; also the position of row 0
+    int base_add;
+    int T, d, vocab, tie_shift, sinusoidal;
+    float embed_scale;
+    float* x;  // [T][d]
+};
+
+struct FinishArgs {
+    Ctl* ctl;
+    int* y;
+    const StatPart* part;
+    int nparts;
+    const float* zt;
+    int T;       // rows that went through the LM head
+    int row_off; // first such row within the pass
+    int which;   // 0 small, 1 large
+    int mode;    // 0 small step, 1 verify, 2 plain greedy (always append)
+    int rows_consumed;  // rows the pass consumed (cache advance)
+    float alpha;
+    int y_cap;
+};
+
+// launch wrappers (kernels.hip); each returns the hipError_t of the launch
+hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st);
+hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st);
+hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st);
+hipError_t launch_finish(const FinishArgs& a, hipStream_t st);
+size_t gemm_num_blocks(const GemmArgs& a);
+void gemm_pick_shape(GemmArgs& a, int dtype);
+
+// host-side re-layout (layout.cpp)
+// src is [k][n] row-major (math layout, y = x W) when transposed_src, else [n][k].
+void tile_matrix(const float* src, bool src_is_k_by_n, int n, int k, int dtype, void* dst);
+size_t tiled_bytes(int n, int k, int dtype);
+// interleave gate/up feature tiles of a gated FFN: dst tiles 2j = gate tile j, 2j+1 = up tile j
+void tile_gated_pair(const float* gate_k_by_n, const float* up_k_by_n, int n, int k, int dtype, void* dst);
+// concatenate several [k][n_i] matrices along the feature axis
+void tile_concat(const float* const* srcs, const int* ns, int count, int k, int dtype, void* dst);
+
+}  // namespace bild

@@ -1,0 +1,228 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI.
+
+Toy pairs cover every architecture variant and ragged shapes (vocabulary not a
+multiple of the feature tile, several k tiles, inner dim != model dim); the
+`tiny` pair is the fp32 correctness configuration of the benchmark."""
+import math
+
+import numpy as np
+import pytest
+
+import bild_inputs as bi
+import oracle
+import paper_2302_07863_amd as pkg
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+INF = float("inf")
+
+
+class Rig:
+    """Weights, oracle request and GPU pair of one configuration."""
+
+    def __init__(self, cfg, n_src=None, compact=False):
+        self.cfg = cfg
+        self.ws, self.wl = bi.make_pair_weights(cfg)
+        self.src = bi.make_source(cfg, n_src)
+        self.req = oracle.Request(oracle.Model(cfg.small, self.ws, compact), oracle.Model(cfg.large, self.wl, compact),
+                                  self.src, cfg.decoder_only)
+        self.pair = parity.make_gpu_pair(cfg, self.ws, self.wl)
+        self.n0 = len(self.src) if cfg.decoder_only else 1
+
+    def state(self, max_new, n_max):
+        return pkg.State(self.pair, len(self.src), self.n0 + max_new + 1, n_max)
+
+
+TOY_VARIANTS = {
+    "f32-relu-tied": dict(),
+    "bf16-relu-tied": dict(dtype=bi.DT_BF16),
+    "f32-geglu-untied": dict(act=bi.ACT_GATED_GELU, tied=False),
+    "bf16-trunc-geglu": dict(act=bi.ACT_GATED_GELU, tied=False, truncate=True, dtype=bi.DT_BF16),
+    "f32-rope-swiglu-deconly": dict(act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=False),
+    "bf16-rope-swiglu-deconly": dict(act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=False, dtype=bi.DT_BF16,
+                                     truncate=True),
+    "f32-wide": dict(d=256, heads=3, d_head=32, d_ff=160, vocab=1000, n_src=40),
+}
+_rigs = {}
+
+
+def rig(name):
+    if name not in _rigs:
+        _rigs[name] = Rig(bi.toy_pair(**TOY_VARIANTS[name]))
+    return _rigs[name]
+
+
+@pytest.mark.parametrize("name", list(TOY_VARIANTS))
+@pytest.mark.parametrize("fb,rb,nm", [(0.5, 2.0, 10), (0.2, 0.7, 3)])
+def test_toy_teacher_forced_logits_and_decisions(name, fb, rb, nm):
+    R = rig(name)
+    ref = oracle.bild_generate(R.req, fb, rb, nm, R.cfg.max_new, keep_logits=True)
+    st = R.state(R.cfg.max_new, nm)
+    st.encode(R.src)
+    worst = parity.teacher_forced(st, ref, R.n0, fb, rb, R.cfg)
+    print(name, worst)
+
+
+@pytest.mark.parametrize("name", list(TOY_VARIANTS))
+def test_toy_free_running_generate(name):
+    R = rig(name)
+    for fb, rb, nm in ((0.5, 2.0, 10), (0.2, 0.7, 3), (0.0, 0.5, 6)):
+        ref = oracle.bild_generate(R.req, fb, rb, nm, R.cfg.max_new)
+        st = R.state(R.cfg.max_new, nm)
+        toks, stats = st.generate(R.src, fb, rb, R.cfg.max_new)
+        res = parity.compare_generation(toks, stats, ref, fb, rb)
+        print(name, fb, rb, nm, res, stats)
+
+
+@pytest.mark.parametrize("name", ["f32-relu-tied", "bf16-trunc-geglu", "bf16-rope-swiglu-deconly"])
+def test_limiting_cases_on_the_gpu(name):
+    R = rig(name)
+    n = R.cfg.max_new
+    st = R.state(n, 0)
+    small_greedy = st.greedy(pkg.SMALL, R.src, n)
+    large_greedy = st.greedy(pkg.LARGE, R.src, n)
+    ref_s = oracle.greedy(R.req, "small", n)
+    ref_l = oracle.greedy(R.req, "large", n)
+    parity.compare_generation(small_greedy, None, ref_s)
+    parity.compare_generation(large_greedy, None, ref_l)
+    # alpha_FB = 0 and no cap: small-model greedy, the large model never runs
+    toks, stats = st.generate(R.src, 0.0, 2.0, n)
+    assert toks == small_greedy and stats["large_calls"] == 0
+    # alpha_FB > 1: always fall back -> large-model greedy for any alpha_RB
+    st10 = R.state(n, 10)
+    for rb in (-1.0, 0.5, INF):
+        toks, stats = st10.generate(R.src, 2.0, rb, n)
+        assert toks == large_greedy and stats["rollbacks"] == 0 and stats["large_calls"] == n
+    # alpha_RB < 0: every reviewed draft is rejected; the reviewed part is large-model greedy
+    toks, stats = st10.generate(R.src, 0.0, -1.0, n)
+    ds = st10.lengths()["draft_start"] - R.n0
+    assert ds > 0 and toks[:ds] == large_greedy[:ds]
+
+
+@pytest.mark.parametrize("name", ["f32-relu-tied", "bf16-trunc-geglu", "f32-rope-swiglu-deconly"])
+def test_review_pass_equals_sequential_steps(name):
+    """One pass over n+1 rows gives the distributions of n+1 single-row passes (Section 3.2)."""
+    R = rig(name)
+    tol = parity.logit_tol(R.cfg)
+    block = [int(t) for t in bi.make_tokens(R.cfg.large.vocab, 9, seed=11)]
+    st = R.state(40, 10)
+    st.encode(R.src)
+    st.debug_enable_logits(True)
+    out, r, nll = st.large_verify(INF, draft=block)          # never roll back: all rows are kept
+    assert r == len(block)
+    rows = [st.debug_logits(pkg.LARGE, i) for i in range(len(block) + 1)]
+    # oracle: the same rows from the definition
+    y = R.req.initial() + block
+    z = R.req.large.logits_full(y, R.req.cross_l)[len(y) - len(block) - 1:]
+    assert np.max(np.abs(np.stack(rows) - z)) <= tol
+    # the same block, one row at a time
+    st2 = R.state(40, 10)
+    st2.encode(R.src)
+    st2.debug_enable_logits(True)
+    for i in range(len(block) + 1):
+        st2.force_tokens(R.n0, block[:i], R.n0 + i)
+        out2, r2, _ = st2.large_verify(INF, draft=[])
+        z1 = st2.debug_logits(pkg.LARGE, 0)
+        # one more row in the same pass only changes the summation order
+        assert np.max(np.abs(z1 - rows[i])) <= (1e-5 if R.cfg.large.dtype == bi.DT_F32 else 5e-3)
+        assert out2[0] == int(np.argmax(z1))
+
+
+def test_truncate_then_continue_equals_fresh_prefix():
+    R = rig("bf16-trunc-geglu")
+    fb, rb, nm, n = 0.3, 1.0, 4, R.cfg.max_new
+    st = R.state(n, nm)
+    toks, _ = st.generate(R.src, fb, rb, n)
+    keep = 7
+    st.seq_truncate(R.n0 + keep)
+    ln = st.lengths()
+    assert ln["y_len"] == R.n0 + keep and ln["len_small"] <= R.n0 + keep - 1 and ln["len_large"] <= ln["draft_start"] - 1
+    # continue with always-fallback: every further token is the large model's greedy choice given its prefix
+    for _ in range(5):
+        tok, flag, _ = st.small_step(2.0)
+        assert flag == 1
+        st.large_verify(rb)
+    seq = st.sequence()
+    assert len(seq) == R.n0 + keep + 5 and seq[R.n0:R.n0 + keep] == toks[:keep]
+    for p in range(R.n0 + keep, len(seq)):
+        z = R.req.large.logits_full(seq[:p], R.req.cross_l)[-1]
+        assert seq[p] == int(np.argmax(z)) or oracle.policy.top2_gap(z) < parity.MARGIN
+
+
+def test_state_errors_on_the_device():
+    R = rig("f32-relu-tied")
+    b = pkg.binding
+    st = R.state(8, 2)
+    with pytest.raises(pkg.BildError) as e:
+        st.small_step(0.5)                                  # before encode
+    assert e.value.code == b.ESTATE
+    with pytest.raises(pkg.BildError) as e:
+        st.encode(list(R.src) + [1])                        # longer than max_src
+    assert e.value.code == b.ECAP
+    with pytest.raises(pkg.BildError) as e:
+        st.encode([R.cfg.large.vocab])                      # token id out of range
+    assert e.value.code == b.EINVAL
+    st.encode(R.src)
+    tok, flag, _ = st.small_step(2.0)
+    assert flag == 1
+    before = st.lengths()
+    with pytest.raises(pkg.BildError) as e:
+        st.small_step(2.0)                                  # nothing unconsumed after a fallback
+    assert e.value.code == b.ESTATE
+    assert st.lengths() == before                           # state unchanged by the failed call
+    with pytest.raises(pkg.BildError) as e:
+        st.kv_truncate(pkg.SMALL, before["len_small"] + 1)
+    assert e.value.code == b.EINVAL
+    with pytest.raises(pkg.BildError) as e:
+        st.large_verify(1.0, draft=[0] * 32)                # more rows than one pass takes
+    assert e.value.code == b.ECAP
+    with pytest.raises(pkg.BildError) as e:
+        st.large_verify(1.0, draft=[R.cfg.large.vocab])
+    assert e.value.code == b.EINVAL
+    assert st.lengths() == before
+    out, r, _ = st.large_verify(1.0)
+    assert r == 0 and len(out) == 1
+    # generation longer than the state's capacity
+    with pytest.raises(pkg.BildError) as e:
+        st.generate(R.src, 0.5, 2.0, 64)
+    assert e.value.code == b.ECAP
+    # mismatched vocabularies cannot be paired
+    other = bi.toy_pair(vocab=R.cfg.large.vocab + 8)
+    ws2, _ = bi.make_pair_weights(other)
+    m2 = parity.make_gpu_model(other.small, ws2)
+    with pytest.raises(pkg.BildError) as e:
+        pkg.Pair(m2, R.pair.large)
+    assert e.value.code == b.EINVAL
+
+
+def test_kv_truncate_recomputes_identically():
+    R = rig("bf16-relu-tied")
+    st = R.state(24, 10)
+    st.encode(R.src)
+    st.debug_enable_logits(True)
+    block = [int(t) for t in bi.make_tokens(R.cfg.large.vocab, 6, seed=3)]
+    st.large_verify(INF, draft=block)
+    a = np.stack([st.debug_logits(pkg.LARGE, i) for i in range(7)])
+    # cut both caches to nothing and review the same block again: bit-identical (deterministic kernels)
+    st.force_tokens(R.n0, block, R.n0)
+    st.kv_truncate(pkg.BOTH, 0)
+    st.large_verify(INF)
+    b2 = np.stack([st.debug_logits(pkg.LARGE, i) for i in range(7)])
+    assert np.array_equal(a, b2)
+
+
+def test_tiny_config_full_parity():
+    """Config 1: fp32, logits within 1e-4, decisions identical."""
+    cfg = bi.tiny_pair()
+    R = Rig(cfg)
+    ref = oracle.bild_generate(R.req, cfg.alpha_fb, cfg.alpha_rb, cfg.n_max, cfg.max_new, keep_logits=True)
+    st = R.state(cfg.max_new, cfg.n_max)
+    st.encode(R.src)
+    worst = parity.teacher_forced(st, ref, R.n0, cfg.alpha_fb, cfg.alpha_rb, cfg)
+    print("tiny teacher-forced", worst, ref.stats)
+    toks, stats = st.generate(R.src, cfg.alpha_fb, cfg.alpha_rb, cfg.max_new)
+    print("tiny free-running", parity.compare_generation(toks, stats, ref, cfg.alpha_fb, cfg.alpha_rb), stats)
+    for fb, rb in ((0.3, 1.0), (0.7, 4.0), (0.0, 0.3)):
+        ref = oracle.bild_generate(R.req, fb, rb, cfg.n_max, cfg.max_new)
+        toks, stats = st.generate(R.src, fb, rb, cfg.max_new)
+        parity.compare_generation(toks, stats, ref, fb, rb)
