@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the BiLD decoding path on one MI355X.
+
+A "step" is one whole BiLD generation (Algorithm 1) of `max_new` tokens for one
+request of the chosen synthetic pair, with the source already encoded and all
+weights resident in HBM.  Prints one JSON line:
+  value        generated tokens / second of the BiLD loop (batch 1)
+  roofline     the weight-streaming GEMM kernel: algorithmic weight bytes per
+               launch / mean launch duration (HIP events on the library's
+               stream, taken in a second run of the same K steps), vs 8 TB/s
+  cpu_baseline the CPU oracle timed on this host on the same workload
+plus per-pass achieved GB/s (algorithmic bytes of one decoder pass / its time),
+large-model-only greedy tokens/s and the BiLD-vs-large-only speedup.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="t5", choices=["tiny", "t5", "mt5", "llama"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--alpha-fb", type=float, default=None)
+    ap.add_argument("--alpha-rb", type=float, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (--gpus 1); multi-GPU execution is not part of it.")
+        return 2
+
+    import numpy as np
+
+    import bild_inputs as bi
+    import paper_2302_07863_amd as pkg
+
+    pkg.lib()  # fails loudly if the HIP library has not been built
+    cfg = bi.PAIRS[args.workload]()
+    fb = cfg.alpha_fb if args.alpha_fb is None else args.alpha_fb
+    rb = cfg.alpha_rb if args.alpha_rb is None else args.alpha_rb
+    t0 = time.time()
+    ws, wl = bi.make_pair_weights(cfg)
+    src = bi.make_source(cfg)
+    log(f"[bench] weights generated in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    small = pkg.Model(pkg.config_from_shape(cfg.small), [ws[n] for n in bi.tensor_names(cfg.small)])
+    large = pkg.Model(pkg.config_from_shape(cfg.large), [wl[n] for n in bi.tensor_names(cfg.large)])
+    pair = pkg.Pair(small, large)
+    n0 = len(src) if cfg.decoder_only else 1
+    st = pkg.State(pair, len(src), n0 + cfg.max_new + 2, cfg.n_max)
+    log(f"[bench] models uploaded in {time.time() - t0:.1f}s")
+
+    t0 = time.perf_counter()
+    st.encode(src)
+    encode_ms = (time.perf_counter() - t0) * 1e3
+
+    def one_step():
+        st.seq_truncate(n0)          # back to <s> / the prompt; caches cut to match
+        return st.generate(None, fb, rb, cfg.max_new)
+
+    for _ in range(args.warmup):
+        toks, stats = one_step()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        toks, stats = one_step()
+    dt = time.perf_counter() - t0
+    n_tok = len(toks)
+    tok_s = args.steps * n_tok / dt
+    log(f"[bench] BiLD: {tok_s:.1f} tok/s, {dt / args.steps * 1e3:.2f} ms/step, stats {stats}")
+
+    # large-model-only greedy on the same request (vanilla inference, the paper's reference point)
+    def large_only():
+        st.seq_truncate(n0)
+        return st.greedy(pkg.LARGE, None, cfg.max_new)
+
+    large_only()
+    reps = max(2, args.steps // 4)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        gl = large_only()
+    large_tok_s = reps * len(gl) / (time.perf_counter() - t0)
+    log(f"[bench] large-only greedy: {large_tok_s:.1f} tok/s")
+
+    # per-pass achieved bandwidth at the end-of-generation cache length
+    toks, stats = one_step()
+    ln = st.lengths()
+    passes = {}
+    for name, which, rows in (("small_step", pkg.SMALL, 1), ("large_step", pkg.LARGE, 1),
+                              ("large_verify_11", pkg.LARGE, 11)):
+        t_cache = ln["y_len"] - rows
+        have = st.lengths()["len_small" if which == pkg.SMALL else "len_large"]
+        st.kv_truncate(which, min(have, t_cache))
+        ms = st.bench_pass(which, rows, 50)
+        nbytes = st.pass_bytes(which, t_cache, rows)
+        passes[name] = dict(rows=rows, t_cache=t_cache, ms=round(ms, 4), bytes=nbytes,
+                            gbs=round(nbytes / ms / 1e6, 1), frac_of_peak=round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4))
+        log(f"[bench] {name}: {passes[name]}")
+
+    # roofline of the dominant kernel: same K steps again with every GEMM launch bracketed by HIP events
+    st.profile_begin(1 << 18)
+    for _ in range(args.steps):
+        one_step()
+    prof = st.profile_end()
+    tot_l = sum(prof[k]["launches"] for k in prof if k != "dropped")
+    tot_b = sum(prof[k]["bytes"] for k in prof if k != "dropped")
+    tot_ms = sum(prof[k]["ms"] for k in prof if k != "dropped")
+    achieved = tot_b / tot_ms / 1e6 if tot_ms > 0 else 0.0
+    roofline = dict(bound="hbm", kernel="gemm_kernel<bf16>" if cfg.large.dtype == bi.DT_BF16 else "gemm_kernel<f32>",
+                    achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
+                    traffic=None, launches=tot_l, mean_launch_us=round(tot_ms / max(tot_l, 1) * 1e3, 3),
+                    mean_bytes_per_launch=int(tot_b / max(tot_l, 1)),
+                    by_class={k: dict(launches=v["launches"], gbs=round(v["bytes"] / v["ms"] / 1e6, 1) if v["ms"] else 0,
+                                      mean_us=round(v["ms"] / max(v["launches"], 1) * 1e3, 3))
+                              for k, v in prof.items() if k != "dropped"})
+    log(f"[bench] roofline {roofline}")
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        compact = args.workload == "llama"
+        t0 = time.time()
+        req = oracle.Request(oracle.Model(cfg.small, ws, compact), oracle.Model(cfg.large, wl, compact), src,
+                             cfg.decoder_only)
+        log(f"[bench] oracle set up + encoded in {time.time() - t0:.1f}s")
+        n_cpu = cfg.max_new if args.workload != "llama" else 8
+        t0 = time.perf_counter()
+        ref = oracle.bild_generate(req, fb, rb, cfg.n_max, n_cpu)
+        cdt = time.perf_counter() - t0
+        cpu = dict(value=round(len(ref.tokens) / cdt, 2), unit="tokens/s", cores=int(cores), kind="oracle",
+                   sample=f"one BiLD generation of {n_cpu} tokens on the same request (float64 numpy, decode only)",
+                   tokens_equal_gpu=bool(ref.tokens == toks[:len(ref.tokens)]))
+        log(f"[bench] cpu oracle {cpu}")
+
+    out = {
+        "metric": "generated tokens/sec (batch 1, BiLD loop)",
+        "value": round(tok_s, 2),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(dt / args.steps * 1e3, 3),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg.large.dtype == bi.DT_BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.small.name}+{cfg.large.name}, src {len(src)} tokens, "
+                               f"{cfg.max_new} new tokens, alpha_FB={fb}, alpha_RB={rb}, n_max={cfg.n_max}",
+                   "tokens_per_step": n_tok},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "bild_stats": stats,
+        "large_only_tokens_per_s": round(large_tok_s, 2),
+        "speedup_vs_large_only": round(tok_s / large_tok_s, 3),
+        "encode_ms": round(encode_ms, 2),
+        "passes": passes,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

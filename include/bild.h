@@ -182,7 +182,9 @@ int bild_force_tokens(bild_state* s, int first, const int32_t* tokens, int n, in
 /* Algorithm 1 end to end: encode(src), then small steps / large reviews until
  * max_new tokens exist or the last token equals eos (eos < 0: none).  out
  * (capacity max_new) receives the generated tokens without <s> / the prompt.
- * Equals the composition of the calls above. */
+ * Equals the composition of the calls above.  src == NULL skips the encode step
+ * and continues from the state as it is (max_new then counts all tokens after
+ * the initial <s> / prompt); the same holds for bild_greedy. */
 int bild_generate(bild_state* s, const int32_t* src, int n_src, float alpha_fb, float alpha_rb, int max_new,
                   int32_t eos, int32_t* out, int32_t* n_out, bild_stats* stats /* nullable */);
 
@@ -200,6 +202,27 @@ int bild_get_sequence(bild_state* s, int32_t* out, int cap, int32_t* n);
  * of model `which`).  Off by default: the product path never materialises logits. */
 int bild_debug_enable_logits(bild_state* s, int enable);
 int bild_debug_logits(bild_state* s, int which, int row, float* out_vocab);
+
+/* Measurement helpers (no effect on results).
+ * bild_bench_pass: brings model `which` up to y_len - rows consumed tokens (needs
+ * y_len - len >= rows), then runs `reps` identical passes over the last `rows`
+ * tokens of y, LM head and statistics included, WITHOUT committing anything, and
+ * returns the mean time of one pass in milliseconds from HIP events on the
+ * state's stream.
+ * bild_profile_begin/end: between the two calls every weight-streaming GEMM launch
+ * is bracketed by HIP events (at most max_records launches are recorded);
+ * end() waits for the stream and sums, per model [0 small, 1 large] and per
+ * class [0 layer GEMMs, 1 LM head]: launches, milliseconds and algorithmic bytes
+ * (bytes of the weight matrix each launch streams). */
+typedef struct bild_profile {
+    int64_t launches[2][2];
+    int64_t bytes[2][2];
+    double  ms[2][2];
+    int32_t dropped;        /* launches not recorded because max_records was reached */
+} bild_profile;
+int bild_bench_pass(bild_state* s, int which, int rows, int reps, float* ms_per_pass);
+int bild_profile_begin(bild_state* s, int max_records);
+int bild_profile_end(bild_state* s, bild_profile* out);
 
 /* Algorithmic bytes one pass of model `which` must read at cache length t_cache
  * with `rows` new rows (weights + LM head + self K/V + cross K/V). */

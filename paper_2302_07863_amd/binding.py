@@ -33,6 +33,11 @@ class Stats(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class Profile(C.Structure):
+    _fields_ = [("launches", (C.c_int64 * 2) * 2), ("bytes", (C.c_int64 * 2) * 2), ("ms", (C.c_double * 2) * 2),
+                ("dropped", C.c_int32)]
+
+
 class BildError(RuntimeError):
     def __init__(self, code: int, what: str):
         super().__init__(f"{what}: {code} ({strerror(code)})")
@@ -65,6 +70,9 @@ _SIGS = {
     "bild_get_sequence": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int32)]),
     "bild_debug_enable_logits": (C.c_int, [C.c_void_p, C.c_int]),
     "bild_debug_logits": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
+    "bild_bench_pass": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float)]),
+    "bild_profile_begin": (C.c_int, [C.c_void_p, C.c_int]),
+    "bild_profile_end": (C.c_int, [C.c_void_p, C.POINTER(Profile)]),
     "bild_pass_bytes": (C.c_int64, [C.c_void_p, C.c_int, C.c_int, C.c_int]),
     "bild_strerror": (C.c_char_p, [C.c_int]),
 }
@@ -194,18 +202,19 @@ class State:
                "bild_force_tokens")
 
     def generate(self, src, alpha_fb: float, alpha_rb: float, max_new: int, eos: int = -1):
-        a = _i32(src)
+        """src=None continues from the encoded state without re-encoding."""
+        a = _i32(src if src is not None else [])
         out = np.zeros(max(max_new, 1), dtype=np.int32)
         n, st = C.c_int32(), Stats()
-        _check(lib().bild_generate(self.h, a.ctypes.data, len(a), alpha_fb, alpha_rb, max_new, eos, out.ctypes.data,
+        _check(lib().bild_generate(self.h, a.ctypes.data if src is not None else None, len(a), alpha_fb, alpha_rb, max_new, eos, out.ctypes.data,
                                    C.byref(n), C.byref(st)), "bild_generate")
         return out[:n.value].tolist(), st.as_dict()
 
     def greedy(self, which: int, src, max_new: int, eos: int = -1):
-        a = _i32(src)
+        a = _i32(src if src is not None else [])
         out = np.zeros(max(max_new, 1), dtype=np.int32)
         n = C.c_int32()
-        _check(lib().bild_greedy(self.h, which, a.ctypes.data, len(a), max_new, eos, out.ctypes.data, C.byref(n)),
+        _check(lib().bild_greedy(self.h, which, a.ctypes.data if src is not None else None, len(a), max_new, eos, out.ctypes.data, C.byref(n)),
                "bild_greedy")
         return out[:n.value].tolist()
 
@@ -227,6 +236,24 @@ class State:
         v = self.pair.large.cfg.vocab
         out = np.zeros(v, dtype=np.float32)
         _check(lib().bild_debug_logits(self.h, which, row, out.ctypes.data), "bild_debug_logits")
+        return out
+
+    def bench_pass(self, which: int, rows: int, reps: int) -> float:
+        ms = C.c_float()
+        _check(lib().bild_bench_pass(self.h, which, rows, reps, C.byref(ms)), "bild_bench_pass")
+        return ms.value
+
+    def profile_begin(self, max_records: int = 65536):
+        _check(lib().bild_profile_begin(self.h, max_records), "bild_profile_begin")
+
+    def profile_end(self) -> dict:
+        p = Profile()
+        _check(lib().bild_profile_end(self.h, C.byref(p)), "bild_profile_end")
+        out = {}
+        for mi, mn in enumerate(("small", "large")):
+            for ci, cn in enumerate(("layers", "lm_head")):
+                out[f"{mn}.{cn}"] = dict(launches=p.launches[mi][ci], bytes=p.bytes[mi][ci], ms=p.ms[mi][ci])
+        out["dropped"] = p.dropped
         return out
 
     def pass_bytes(self, which: int, t_cache: int, rows: int = 1) -> int:

@@ -88,12 +88,19 @@ struct bild_state {
     hipStream_t stream = nullptr;
     bool own_stream = false;
     int max_src = 0, max_len = 0, n_max = 0;
+    int cap_len = 0, cap_src = 0;  // cache capacities: max_len / max_src rounded up to 32 rows
     // host mirror of the control block (kept exact by reading back after every pass)
     int y_len = 0, draft_start = 0, len[2] = {0, 0}, n_src = 0, n0 = 0;
     bool encoded = false;
     bool debug_logits = false;
     std::vector<void*> allocs;
     std::vector<void*> host_allocs;
+    // event bracketing of GEMM launches (measurement only)
+    bool prof_on = false;
+    int prof_cap = 0, prof_used = 0, prof_dropped = 0;
+    std::vector<hipEvent_t> prof_ev;
+    struct ProfRec { int model, cls; int64_t bytes; };
+    std::vector<ProfRec> prof_rec;
 };
 
 namespace {
@@ -288,6 +295,7 @@ extern "C" int bild_state_destroy(bild_state* s) {
     if (s->stream) (void)hipStreamSynchronize(s->stream);
     for (void* p : s->allocs) (void)hipFree(p);
     for (void* p : s->host_allocs) (void)hipHostFree(p);
+    for (hipEvent_t e : s->prof_ev) (void)hipEventDestroy(e);
     if (s->own_stream && s->stream) (void)hipStreamDestroy(s->stream);
     delete s;
     return BILD_OK;
@@ -304,6 +312,8 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
     s->max_src = max_src;
     s->max_len = max_len;
     s->n_max = n_max;
+    s->cap_len = (max_len + 31) / 32 * 32;
+    s->cap_src = (max_src + 31) / 32 * 32;
     int rc = BILD_OK;
 #define AL(ptr, bytes)                                            \
     do {                                                          \
@@ -338,11 +348,20 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         M.m = m;
         const size_t I = m->inner(), d = m->cfg.d_model, F = m->cfg.d_ff, L = m->cfg.n_dec_layers;
         const size_t esz = m->esz();
-        AL(M.kcache, L * (size_t)max_len * I * esz);
-        AL(M.vcache, L * (size_t)max_len * I * esz);
+        // every K/V buffer starts zeroed: rows past the valid length must hold finite values
+#define ALZ(ptr, bytes)                                                              \
+    do {                                                                             \
+        AL(ptr, bytes);                                                              \
+        if (hipMemsetAsync((ptr), 0, (bytes), s->stream) != hipSuccess) {            \
+            bild_state_destroy(s);                                                   \
+            return BILD_EHIP;                                                        \
+        }                                                                            \
+    } while (0)
+        ALZ(M.kcache, L * (size_t)s->cap_len * I * esz);
+        ALZ(M.vcache, L * (size_t)s->cap_len * I * esz);
         if (m->cfg.cross_attn) {
-            AL(M.ck, L * (size_t)max_src * I * esz);
-            AL(M.cv, L * (size_t)max_src * I * esz);
+            ALZ(M.ck, L * (size_t)s->cap_src * I * esz);
+            ALZ(M.cv, L * (size_t)s->cap_src * I * esz);
         }
         AL(M.x, sizeof(float) * kMaxRows * d);
         AL(M.q, sizeof(float) * kMaxRows * I);
@@ -357,10 +376,11 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         if (m->cfg.n_enc_layers > 0) {
             AL(M.enc_x, sizeof(float) * (size_t)max_src * d);
             AL(M.enc_q, sizeof(float) * (size_t)max_src * I);
-            AL(M.enc_k, (size_t)max_src * I * esz);
-            AL(M.enc_v, (size_t)max_src * I * esz);
+            ALZ(M.enc_k, (size_t)s->cap_src * I * esz);
+            ALZ(M.enc_v, (size_t)s->cap_src * I * esz);
         }
     }
+#undef ALZ
 #undef AL
     if (hipMemsetAsync(s->ctl, 0, sizeof(Ctl), s->stream) != hipSuccess ||
         hipStreamSynchronize(s->stream) != hipSuccess) {
@@ -404,6 +424,15 @@ int pick_splits(const ModelState& M, int nkeys, int heads) {
     return sp;
 }
 
+int pick_attn_waves(int dtype, int d_head, int T, int nkeys, int splits) {
+    // one 32-key block per wave where possible, bounded by the LDS the merge needs
+    const int blocks = ((nkeys + 31) / 32 + splits - 1) / splits;
+    int nw = 1;
+    while (nw < 8 && nw < blocks) nw *= 2;
+    while (nw > 1 && attn_lds_bytes(dtype, d_head, T, nw) > 96 * 1024) nw /= 2;
+    return nw;
+}
+
 GemmArgs gemm_base(const bild_model* m, const TMat& W, const float* x, int ldx, int T, const float* gain) {
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
@@ -421,10 +450,31 @@ GemmArgs gemm_base(const bild_model* m, const TMat& W, const float* x, int ldx, 
     return g;
 }
 
+int launch_gemm_profiled(bild_state* s, const bild_model* m, const GemmArgs& g) {
+    if (!s->prof_on) {
+        HIPC(launch_gemm(g, m->cfg.dtype, s->stream));
+        return BILD_OK;
+    }
+    if (s->prof_used >= s->prof_cap) {
+        s->prof_dropped++;
+        HIPC(launch_gemm(g, m->cfg.dtype, s->stream));
+        return BILD_OK;
+    }
+    const int i = s->prof_used++;
+    HIPC(hipEventRecord(s->prof_ev[2 * i], s->stream));
+    HIPC(launch_gemm(g, m->cfg.dtype, s->stream));
+    HIPC(hipEventRecord(s->prof_ev[2 * i + 1], s->stream));
+    bild_state::ProfRec r;
+    r.model = (m == s->pair->m[1]) ? 1 : 0;
+    r.cls = g.epi == EPI_LMHEAD ? 1 : 0;
+    r.bytes = (int64_t)g.W.n * g.W.k * m->esz();
+    s->prof_rec.push_back(r);
+    return BILD_OK;
+}
+
 int run_gemm(bild_state* s, const bild_model* m, GemmArgs& g) {
     gemm_pick_shape(g, m->cfg.dtype);
-    HIPC(launch_gemm(g, m->cfg.dtype, s->stream));
-    return BILD_OK;
+    return launch_gemm_profiled(s, m, g);
 }
 
 // One decoder pass of model w over rows y[len .. len+T): embed, layers, and (lm_rows > 0)
@@ -453,8 +503,8 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, float alpha
     const float att_scale = 1.f / std::sqrt((float)c.d_head);
     for (int l = 0; l < c.n_dec_layers; ++l) {
         const LayerW& L = m->dec[l];
-        char* kc = M.kcache + (size_t)l * s->max_len * I * esz;
-        char* vc = M.vcache + (size_t)l * s->max_len * I * esz;
+        char* kc = M.kcache + (size_t)l * s->cap_len * I * esz;
+        char* vc = M.vcache + (size_t)l * s->cap_len * I * esz;
         {
             GemmArgs g = gemm_base(m, L.wqkv, M.x, d, T, L.ln1);
             g.epi = EPI_QKV;
@@ -462,6 +512,7 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, float alpha
             g.q_out = M.q;
             g.k_cache = kc;
             g.v_cache = vc;
+            g.vcap = s->cap_len;
             g.pos_ptr = len_ptr;
             g.rope = c.pos == BILD_POS_ROPE;
             int rc = run_gemm(s, m, g);
@@ -474,7 +525,9 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, float alpha
             a.T = T; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
             a.causal = 1;
             a.base_ptr = len_ptr;
+            a.vcap = s->cap_len;
             a.splits = pick_splits(M, s->len[w] + T, c.n_heads);
+            a.nw = pick_attn_waves(dt, c.d_head, T, s->len[w] + T, a.splits);
             a.part_o = M.att_o; a.part_ml = M.att_ml;
             a.scale = att_scale;
             HIPC(launch_attention(a, dt, s->stream));
@@ -500,13 +553,15 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, float alpha
                 AttnArgs a;
                 std::memset(&a, 0, sizeof(a));
                 a.q = M.q;
-                a.k = M.ck + (size_t)l * s->max_src * I * esz;
-                a.v = M.cv + (size_t)l * s->max_src * I * esz;
+                a.k = M.ck + (size_t)l * s->cap_src * I * esz;
+                a.v = M.cv + (size_t)l * s->cap_src * I * esz;
+                a.vcap = s->cap_src;
                 a.out = M.a;
                 a.T = T; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
                 a.causal = 0;
                 a.nkeys_ptr = &s->ctl->n_src;
                 a.splits = pick_splits(M, s->n_src, c.n_heads);
+                a.nw = pick_attn_waves(dt, c.d_head, T, s->n_src, a.splits);
                 a.part_o = M.att_o; a.part_ml = M.att_ml;
                 a.scale = att_scale;
                 HIPC(launch_attention(a, dt, s->stream));
@@ -559,7 +614,10 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, float alpha
         g.row_off = 0;
         gemm_pick_shape(g, dt);
         if ((int)gemm_num_blocks(g) > M.nparts_cap) return BILD_ECAP;
-        HIPC(launch_gemm(g, dt, s->stream));
+        {
+            int rc = launch_gemm_profiled(s, m, g);
+            if (rc) return rc;
+        }
         f.part = M.part;
         f.nparts = (int)gemm_num_blocks(g);
         f.zt = M.zt;
@@ -611,6 +669,7 @@ int run_encoder(bild_state* s, int w) {
             g.q_out = M.enc_q + (size_t)r0 * I;
             g.k_cache = M.enc_k;
             g.v_cache = M.enc_v;
+            g.vcap = s->cap_src;
             g.pos_add = r0;
             g.rope = c.pos == BILD_POS_ROPE;
             int rc = run_gemm(s, m, g);
@@ -624,7 +683,9 @@ int run_encoder(bild_state* s, int w) {
             a.T = T; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
             a.causal = 0;
             a.nkeys_fixed = S;
+            a.vcap = s->cap_src;
             a.splits = 1;
+            a.nw = pick_attn_waves(dt, c.d_head, T, S, 1);
             a.scale = att_scale;
             HIPC(launch_attention(a, dt, s->stream));
             GemmArgs g = gemm_base(m, L.wo, M.a, I, T, nullptr);
@@ -663,12 +724,13 @@ int run_encoder(bild_state* s, int w) {
                 g.epi = EPI_QKV;
                 g.q_dim = 0;
                 g.i_dim = Iu;
-                g.k_cache = U.ck + (size_t)l * s->max_src * Iu * esz;
-                g.v_cache = U.cv + (size_t)l * s->max_src * Iu * esz;
+                g.k_cache = U.ck + (size_t)l * s->cap_src * Iu * esz;
+                g.v_cache = U.cv + (size_t)l * s->cap_src * Iu * esz;
+                g.vcap = s->cap_src;
                 g.pos_add = r0;
                 g.rope = 0;
-                gemm_pick_shape(g, mu->cfg.dtype);
-                HIPC(launch_gemm(g, mu->cfg.dtype, s->stream));
+                int rc = run_gemm(s, mu, g);
+                if (rc) return rc;
             }
         }
     }
@@ -845,9 +907,14 @@ extern "C" int bild_get_sequence(bild_state* s, int32_t* out, int cap, int32_t* 
 
 extern "C" int bild_generate(bild_state* s, const int32_t* src, int n_src, float alpha_fb, float alpha_rb,
                              int max_new, int32_t eos, int32_t* out, int32_t* n_out, bild_stats* stats) {
-    if (!s || !src || !out || !n_out || max_new < 0) return BILD_EINVAL;
-    int rc = bild_encode(s, src, n_src);
-    if (rc) return rc;
+    if (!s || !out || !n_out || max_new < 0) return BILD_EINVAL;
+    int rc = BILD_OK;
+    if (src) {
+        rc = bild_encode(s, src, n_src);
+        if (rc) return rc;
+    } else if (!s->encoded) {
+        return BILD_ESTATE;
+    }
     if (s->n0 + max_new > s->max_len) return BILD_ECAP;
     bild_stats st;
     std::memset(&st, 0, sizeof(st));
@@ -890,9 +957,14 @@ extern "C" int bild_generate(bild_state* s, const int32_t* src, int n_src, float
 
 extern "C" int bild_greedy(bild_state* s, int which, const int32_t* src, int n_src, int max_new, int32_t eos,
                            int32_t* out, int32_t* n_out) {
-    if (!s || !src || !out || !n_out || max_new < 0 || which < 1 || which > 2) return BILD_EINVAL;
-    int rc = bild_encode(s, src, n_src);
-    if (rc) return rc;
+    if (!s || !out || !n_out || max_new < 0 || which < 1 || which > 2) return BILD_EINVAL;
+    int rc = BILD_OK;
+    if (src) {
+        rc = bild_encode(s, src, n_src);
+        if (rc) return rc;
+    } else if (!s->encoded) {
+        return BILD_ESTATE;
+    }
     if (s->n0 + max_new > s->max_len) return BILD_ECAP;
     const int w = which - 1;
     int last = -1;
@@ -935,6 +1007,64 @@ extern "C" int bild_debug_logits(bild_state* s, int which, int row, float* out) 
     const size_t V = M.m->cfg.vocab;
     HIPC(hipMemcpyAsync(out, M.dbg + (size_t)row * V, sizeof(float) * V, hipMemcpyDeviceToHost, s->stream));
     HIPC(hipStreamSynchronize(s->stream));
+    return BILD_OK;
+}
+
+extern "C" int bild_bench_pass(bild_state* s, int which, int rows, int reps, float* ms_per_pass) {
+    if (!s || !ms_per_pass || which < 1 || which > 2 || rows < 1 || rows > kMaxRows || reps < 1) return BILD_EINVAL;
+    if (!s->encoded) return BILD_ESTATE;
+    const int w = which - 1;
+    if (s->y_len - s->len[w] < rows) return BILD_ESTATE;
+    int rc = catch_up(s, w, s->y_len - rows);  // the timed passes cover exactly the last `rows` tokens
+    if (rc) return rc;
+    hipEvent_t e0, e1;
+    HIPC(hipEventCreate(&e0));
+    HIPC(hipEventCreate(&e1));
+    rc = decoder_pass(s, w, rows, rows, 4, 0.f);  // warm-up
+    if (rc == BILD_OK && hipEventRecord(e0, s->stream) != hipSuccess) rc = BILD_EHIP;
+    for (int i = 0; i < reps && rc == BILD_OK; ++i) rc = decoder_pass(s, w, rows, rows, 4, 0.f);
+    if (rc == BILD_OK && hipEventRecord(e1, s->stream) != hipSuccess) rc = BILD_EHIP;
+    if (rc == BILD_OK && hipEventSynchronize(e1) != hipSuccess) rc = BILD_EHIP;
+    float ms = 0.f;
+    if (rc == BILD_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = BILD_EHIP;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    *ms_per_pass = ms / (float)reps;
+    return BILD_OK;
+}
+
+extern "C" int bild_profile_begin(bild_state* s, int max_records) {
+    if (!s || max_records < 1 || max_records > (1 << 20)) return BILD_EINVAL;
+    if (s->prof_on) return BILD_ESTATE;
+    while ((int)s->prof_ev.size() < 2 * max_records) {
+        hipEvent_t e;
+        HIPC(hipEventCreate(&e));
+        s->prof_ev.push_back(e);
+    }
+    s->prof_cap = max_records;
+    s->prof_used = 0;
+    s->prof_dropped = 0;
+    s->prof_rec.clear();
+    s->prof_on = true;
+    return BILD_OK;
+}
+
+extern "C" int bild_profile_end(bild_state* s, bild_profile* out) {
+    if (!s || !out) return BILD_EINVAL;
+    if (!s->prof_on) return BILD_ESTATE;
+    s->prof_on = false;
+    HIPC(hipStreamSynchronize(s->stream));
+    std::memset(out, 0, sizeof(*out));
+    for (int i = 0; i < s->prof_used; ++i) {
+        float ms = 0.f;
+        HIPC(hipEventElapsedTime(&ms, s->prof_ev[2 * i], s->prof_ev[2 * i + 1]));
+        const auto& r = s->prof_rec[i];
+        out->launches[r.model][r.cls] += 1;
+        out->bytes[r.model][r.cls] += r.bytes;
+        out->ms[r.model][r.cls] += ms;
+    }
+    out->dropped = s->prof_dropped;
     return BILD_OK;
 }
 

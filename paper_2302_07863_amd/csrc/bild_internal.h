@@ -76,7 +76,8 @@ struct GemmArgs {
     int i_dim;      // inner dim I; K features follow q, V features follow K
     float* q_out;   // [T][I] fp32
     void* k_cache;  // [capacity][I] in the model dtype
-    void* v_cache;
+    void* v_cache;  // transposed: [I][vcap], position contiguous
+    int vcap;
     const int* pos_ptr;  // position of row 0 = (pos_ptr ? *pos_ptr : 0) + pos_add
     int pos_add;
     int rope;
@@ -94,15 +95,18 @@ struct GemmArgs {
     float* dbg;          // nullable [T][vocab] full logits (tests only)
     int row_off;         // row index of x row 0 within the pass (for part / zt / dbg / targets)
     // launch shape
-    int wk;  // the 4 waves of a workgroup split k wk ways (1, 2 or 4)
-    int rw;  // feature tiles per wave (1 or 2)
-    int kc;  // inputs staged in LDS per chunk
+    int wk;   // input slices per workgroup
+    int nwv;  // waves per workgroup = wk * feature groups (4 or 8)
+    int rw;   // feature tiles per wave (1, or 2 for gated FFNs)
+    int kc;   // inputs staged in LDS per chunk
 };
 
 struct AttnArgs {
     const float* q;  // [T][I]
     const void* k;   // [capacity][I]
-    const void* v;
+    const void* v;   // transposed: [I][vcap]
+    int vcap;
+    int nw;          // waves per workgroup
     float* out;      // [T][I]
     int T, heads, d_head, i_dim;
     int causal;                // 1: row t sees keys <= base + t
@@ -147,6 +151,7 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st);
 hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st);
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st);
 size_t gemm_num_blocks(const GemmArgs& a);
+size_t attn_lds_bytes(int dtype, int d_head, int T, int nw);
 void gemm_pick_shape(GemmArgs& a, int dtype);
 
 // host-side re-layout (layout.cpp)

@@ -84,59 +84,129 @@ __device__ __forceinline__ float gelu_tanh_f(float u) {
 __device__ __forceinline__ float silu_f(float u) { return u / (1.f + expf(-u)); }
 
 // =====================================================================================
-// Skinny GEMM.  Workgroup = 4 wavefronts.  The waves are arranged as (4/wk) feature
-// groups x wk input slices; each wave owns rw feature tiles (16 features each) and
-// walks the input tiles of its slice.  LDS layout (dynamic):
-//   [0, xs)        staged activations of the current input chunk
-//   red            cross-wave partial sums when wk > 1      (4 x 4 x 64 float4)
-//   ssq[4][32]     per-wave sums of squares for the RMSNorm
-//   rs[32]         per-row 1/rms
-//   wstat[4][32]   per-wave softmax partials (LM head)
+// Skinny GEMM.  A workgroup has nwv = wk * wr wavefronts arranged as wr feature groups
+// x wk input slices; each wave owns RW feature tiles (16 features each) and walks the
+// input tiles of its slice, U tiles per batch so that one batch of loads covers one
+// round trip to HBM.  The first batch is issued before anything else in the kernel
+// (weights do not depend on the activations), so the activation staging, the barrier
+// and the residual read overlap with the first weight loads.  LDS layout (dynamic):
+//   (at most 8 waves per workgroup, so that a wave may use 256 registers)
+//   [0, xs)            staged activations of the current input chunk
+//   red                cross-wave partial sums when wk > 1   (nwv x nacc x 64 float4)
+//   ssq[nwv][32]       per-wave sums of squares for the RMSNorm
+//   rs[32]             per-row 1/rms
+//   wstat[nwv][32]     per-wave softmax partials (LM head)
 // =====================================================================================
-constexpr int kRedBytes = 4 * 4 * 64 * 16;
-constexpr int kTailBytes = kRedBytes + 4 * 32 * 4 + 32 * 4 + 4 * 32 * 16;
-
 __host__ __device__ inline int xs_row_stride(int dt, int kc) { return dt ? (kc + 8) * 2 : (kc + 4) * 4; }
 __host__ __device__ inline int xs_bytes(int dt, int kc, int T) { return T * xs_row_stride(dt, kc) * (dt ? 2 : 1); }
+__host__ __device__ inline int gemm_red_bytes(int nwv, int nacc) { return nwv * nacc * 64 * 16; }
+__host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
+    return gemm_red_bytes(nwv, nacc) + nwv * 32 * 4 + 32 * 4 + nwv * 32 * 16;
+}
 
-template <int DT>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
+template <int DT, int RW>
+__global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int KT = DT ? 32 : 16;
+    constexpr int U = RW == 1 ? 8 : 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nthr = blockDim.x, NWV = nthr >> 6;
     const int T = a.T, K = a.W.k, KC = a.kc;
-    const int WK = a.wk, WR = 4 / WK, RW = a.rw;
+    const int WK = a.wk, WR = NWV / WK;
     const int wkid = wave % WK, wrid = wave / WK;
     const int tile0 = ((int)blockIdx.x * WR + wrid) * RW;
     const int NT = (T + 15) >> 4;
+    const int nacc = RW * NT;
     const int rstride = xs_row_stride(DT, KC);
     char* xs_hi = smem;
     char* xs_lo = smem + T * rstride;  // bf16 only
     char* tail = smem + xs_bytes(DT, KC, T);
     f32x4* red = (f32x4*)tail;
-    float* ssq = (float*)(tail + kRedBytes);
-    float* rs = ssq + 128;
+    float* ssq = (float*)(tail + gemm_red_bytes(NWV, nacc));
+    float* rs = ssq + NWV * 32;
     StatPart* wstat = (StatPart*)(rs + 32);
 
     const bool norm = a.gain != nullptr;
-    const bool few = T < 4;  // few rows: all waves share each row, split along k
-    const bool valid0 = tile0 < a.W.tn;
-    const bool valid1 = (RW == 2) && (tile0 + 1 < a.W.tn);
-    const char* wbase0 = (const char*)a.W.w + ((size_t)tile0 * a.W.tk) * kTileBytes + lane * 16;
-    const char* wbase1 = wbase0 + (size_t)a.W.tk * kTileBytes;
-
-    if (tid < 128) ssq[tid] = 0.f;
-
-    f32x4 acc[2][2];
+    const bool few = T < 4;  // few rows: all waves share each row and split it along k
+    const bool owner = (wkid == 0);
+    bool valid[RW];
+    const char* wbase[RW];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int r = 0; r < RW; ++r) {
+        valid[r] = tile0 + r < a.W.tn;
+        wbase[r] = (const char*)a.W.w + ((size_t)(tile0 + r) * a.W.tk) * kTileBytes + lane * 16;
+    }
+    const int tok_l = lane & 15, kq = lane >> 4;
+
+    // ---- first batch of weight tiles and the residual values: issued before anything else ----
+    uint4 A[RW][U];
+    {
+        const int nkt0 = min(KC, K) / KT;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int u = 0; u < U; ++u) {
+            const int kt = wkid + u * WK;
+#pragma unroll
+            for (int r = 0; r < RW; ++r)
+                A[r][u] = (valid[r] && kt < nkt0) ? *(const uint4*)(wbase[r] + (size_t)kt * kTileBytes)
+                                                  : make_uint4(0, 0, 0, 0);
+        }
+    }
+    float4 old[RW][2];
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            old[r][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
+            const int t = nt * 16 + tok_l;
+            if (a.epi == EPI_RESID && owner && valid[r] && t < T)
+                old[r][nt] = *(const float4*)(a.out + (size_t)t * a.ldo + (tile0 + r) * 16 + kq * 4);
+        }
+
+    for (int i = tid; i < NWV * 32; i += nthr) ssq[i] = 0.f;
+
+    f32x4 acc[RW][2];
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     float ss[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) ss[j] = 0.f;
 
-    const int tok_l = lane & 15, kq = lane >> 4;
+    auto compute = [&](const uint4 (&At)[RW], int ktl) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            if (nt < NT) {
+                const int t = nt * 16 + tok_l;
+                if (DT) {
+                    uint4 bh = make_uint4(0, 0, 0, 0), bl = make_uint4(0, 0, 0, 0);
+                    if (t < T) {
+                        bh = *(const uint4*)(xs_hi + t * rstride + (ktl * 32 + kq * 8) * 2);
+                        bl = *(const uint4*)(xs_lo + t * rstride + (ktl * 32 + kq * 8) * 2);
+                    }
+                    const bf16x8 Bh = __builtin_bit_cast(bf16x8, bh), Bl = __builtin_bit_cast(bf16x8, bl);
+#pragma unroll
+                    for (int r = 0; r < RW; ++r) {
+                        const bf16x8 Aw = __builtin_bit_cast(bf16x8, At[r]);
+                        acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bh, acc[r][nt], 0, 0, 0);
+                        acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bl, acc[r][nt], 0, 0, 0);
+                    }
+                } else {
+                    float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (t < T) b = *(const float4*)(xs_hi + t * rstride + (ktl * 16 + kq * 4) * 4);
+                    const float bb[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+                    for (int r = 0; r < RW; ++r) {
+                        const float aa[4] = {__uint_as_float(At[r].x), __uint_as_float(At[r].y),
+                                             __uint_as_float(At[r].z), __uint_as_float(At[r].w)};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j], bb[j], acc[r][nt], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    };
 
     for (int k0 = 0; k0 < K; k0 += KC) {
         const int kc_len = min(KC, K - k0);
@@ -144,10 +214,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
         // ---- stage x[:, k0 : k0+kc_len] (times the norm gain) into LDS ----
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int t = few ? j : wave + 4 * j;
+            const int t = few ? j : wave + NWV * j;
             if (t < T) {
                 const float* xr = a.x + (size_t)t * a.ldx + k0;
-                const int start = few ? tid : lane, step = few ? 256 : 64;
+                const int start = few ? tid : lane, step = few ? nthr : 64;
                 for (int k4 = start; k4 < (kc_len >> 2); k4 += step) {
                     float4 v = *(const float4*)(xr + k4 * 4);
                     if (norm) {
@@ -168,70 +238,39 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
             }
         }
         __syncthreads();
-        // ---- stream this wave's weight tiles of the chunk ----
+        // ---- this wave's weight tiles of the chunk, U per batch ----
         const int kt_base = k0 / KT, nkt = kc_len / KT;
-        auto compute = [&](const uint4& A0, const uint4& A1, int ktl) {
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
-                if (nt < NT) {
-                    const int t = nt * 16 + tok_l;
-                    if (DT) {
-                        uint4 bh = make_uint4(0, 0, 0, 0), bl = make_uint4(0, 0, 0, 0);
-                        if (t < T) {
-                            bh = *(const uint4*)(xs_hi + t * rstride + (ktl * 32 + kq * 8) * 2);
-                            bl = *(const uint4*)(xs_lo + t * rstride + (ktl * 32 + kq * 8) * 2);
-                        }
-                        const bf16x8 Bh = __builtin_bit_cast(bf16x8, bh), Bl = __builtin_bit_cast(bf16x8, bl);
-                        if (valid0) {
-                            const bf16x8 A = __builtin_bit_cast(bf16x8, A0);
-                            acc[0][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, Bh, acc[0][nt], 0, 0, 0);
-                            acc[0][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, Bl, acc[0][nt], 0, 0, 0);
-                        }
-                        if (valid1) {
-                            const bf16x8 A = __builtin_bit_cast(bf16x8, A1);
-                            acc[1][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, Bh, acc[1][nt], 0, 0, 0);
-                            acc[1][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, Bl, acc[1][nt], 0, 0, 0);
-                        }
-                    } else {
-                        float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
-                        if (t < T) b = *(const float4*)(xs_hi + t * rstride + (ktl * 16 + kq * 4) * 4);
-                        const float bb[4] = {b.x, b.y, b.z, b.w};
-                        if (valid0) {
-                            const float aa[4] = {__uint_as_float(A0.x), __uint_as_float(A0.y), __uint_as_float(A0.z),
-                                                 __uint_as_float(A0.w)};
-#pragma unroll
-                            for (int j = 0; j < 4; ++j)
-                                acc[0][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j], bb[j], acc[0][nt], 0, 0, 0);
-                        }
-                        if (valid1) {
-                            const float aa[4] = {__uint_as_float(A1.x), __uint_as_float(A1.y), __uint_as_float(A1.z),
-                                                 __uint_as_float(A1.w)};
-#pragma unroll
-                            for (int j = 0; j < 4; ++j)
-                                acc[1][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j], bb[j], acc[1][nt], 0, 0, 0);
-                        }
-                    }
-                }
-            }
-        };
         int kt = wkid;
-        constexpr int U = 4;
-        for (; kt + (U - 1) * WK < nkt; kt += U * WK) {
-            uint4 A0[U], A1[U];
+        if (k0 == 0) {  // the batch fetched at kernel entry
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const size_t off = (size_t)(kt_base + kt + u * WK) * kTileBytes;
-                A0[u] = valid0 ? *(const uint4*)(wbase0 + off) : make_uint4(0, 0, 0, 0);
-                A1[u] = valid1 ? *(const uint4*)(wbase1 + off) : make_uint4(0, 0, 0, 0);
+                if (kt + u * WK < nkt) {
+                    uint4 At[RW];
+#pragma unroll
+                    for (int r = 0; r < RW; ++r) At[r] = A[r][u];
+                    compute(At, kt + u * WK);
+                }
+            }
+            kt += U * WK;
+        }
+        for (; kt < nkt; kt += U * WK) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int k1 = kt + u * WK;
+#pragma unroll
+                for (int r = 0; r < RW; ++r)
+                    A[r][u] = (valid[r] && k1 < nkt) ? *(const uint4*)(wbase[r] + (size_t)(kt_base + k1) * kTileBytes)
+                                                     : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) compute(A0[u], A1[u], kt + u * WK);
-        }
-        for (; kt < nkt; kt += WK) {
-            const size_t off = (size_t)(kt_base + kt) * kTileBytes;
-            const uint4 A0 = valid0 ? *(const uint4*)(wbase0 + off) : make_uint4(0, 0, 0, 0);
-            const uint4 A1 = valid1 ? *(const uint4*)(wbase1 + off) : make_uint4(0, 0, 0, 0);
-            compute(A0, A1, kt);
+            for (int u = 0; u < U; ++u) {
+                if (kt + u * WK < nkt) {
+                    uint4 At[RW];
+#pragma unroll
+                    for (int r = 0; r < RW; ++r) At[r] = A[r][u];
+                    compute(At, kt + u * WK);
+                }
+            }
         }
     }
 
@@ -239,31 +278,35 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
     if (norm) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int t = few ? j : wave + 4 * j;
+            const int t = few ? j : wave + NWV * j;
             const float v = wave_sum(ss[j]);
             if (t < T && lane == 0) ssq[wave * 32 + t] = v;
         }
     }
-    if (WK > 1 && wkid > 0) {
+    if (WK > 1 && !owner) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int r = 0; r < RW; ++r)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) red[(wave * 4 + i * 2 + j) * 64 + lane] = acc[i][j];
+            for (int j = 0; j < 2; ++j)
+                if (j < NT) red[(wave * nacc + r * NT + j) * 64 + lane] = acc[r][j];
     }
     __syncthreads();
-    if (tid < T)
-        rs[tid] = norm ? rsqrtf((ssq[tid] + ssq[32 + tid] + ssq[64 + tid] + ssq[96 + tid]) / (float)K + a.eps) : 1.f;
-    if (WK > 1 && wkid == 0) {
+    if (tid < T) {
+        float sum = 0.f;
+        for (int w = 0; w < NWV; ++w) sum += ssq[w * 32 + tid];
+        rs[tid] = norm ? rsqrtf(sum / (float)K + a.eps) : 1.f;
+    }
+    if (WK > 1 && owner) {
         for (int w2 = 1; w2 < WK; ++w2)
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int r = 0; r < RW; ++r)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] += red[((wave + w2) * 4 + i * 2 + j) * 64 + lane];
+                for (int j = 0; j < 2; ++j)
+                    if (j < NT) acc[r][j] += red[((wave + w2) * nacc + r * NT + j) * 64 + lane];
     }
     __syncthreads();
 
     // ---- epilogue: lane holds features f = tile*16 + kq*4 + v for row t = nt*16 + tok_l ----
-    const bool owner = (wkid == 0);
     const int pos0 = (a.pos_ptr ? *a.pos_ptr : 0) + a.pos_add;
     Stat st[2] = {stat_neutral(), stat_neutral()};
 #pragma unroll
@@ -271,13 +314,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
         const int t = nt * 16 + tok_l;
         if (nt >= NT || t >= T || !owner) continue;
         const float r = rs[t];
-        if (a.epi == EPI_ACT && a.act != BILD_ACT_RELU) {
-            if (valid0 && valid1) {  // tile0 even: gate tile, tile0+1: linear branch of the same features
+        if (RW == 2 && a.epi == EPI_ACT) {  // gated FFN: tile0 holds the gate, tile0+1 the linear branch
+            if (valid[0] && valid[RW - 1]) {
                 const int f0 = (tile0 >> 1) * 16 + kq * 4;
                 float o[4];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const float g = acc[0][nt][v] * r, u = acc[1][nt][v] * r;
+                    const float g = acc[0][nt][v] * r, u = acc[RW - 1][nt][v] * r;
                     o[v] = (a.act == BILD_ACT_GATED_GELU ? gelu_tanh_f(g) : silu_f(g)) * u;
                 }
                 *(float4*)(a.out + (size_t)t * a.ldo + f0) = make_float4(o[0], o[1], o[2], o[3]);
@@ -285,8 +328,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
             continue;
         }
 #pragma unroll
-        for (int rwi = 0; rwi < 2; ++rwi) {
-            if (!(rwi == 0 ? valid0 : valid1)) continue;
+        for (int rwi = 0; rwi < RW; ++rwi) {
+            if (!valid[rwi]) continue;
             const int n0 = (tile0 + rwi) * 16 + kq * 4;
             float v4[4] = {acc[rwi][nt][0] * r, acc[rwi][nt][1] * r, acc[rwi][nt][2] * r, acc[rwi][nt][3] * r};
             switch (a.epi) {
@@ -294,10 +337,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
                     *(float4*)(a.out + (size_t)t * a.ldo + n0) = make_float4(v4[0], v4[1], v4[2], v4[3]);
                     break;
                 case EPI_RESID: {
-                    float4* p = (float4*)(a.out + (size_t)t * a.ldo + n0);
-                    float4 o = *p;
-                    o.x += v4[0]; o.y += v4[1]; o.z += v4[2]; o.w += v4[3];
-                    *p = o;
+                    const float4 o = old[rwi][nt];
+                    *(float4*)(a.out + (size_t)t * a.ldo + n0) =
+                        make_float4(o.x + v4[0], o.y + v4[1], o.z + v4[2], o.w + v4[3]);
                 } break;
                 case EPI_ACT:
                     *(float4*)(a.out + (size_t)t * a.ldo + n0) =
@@ -321,14 +363,22 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
                     }
                     if (seg == 0) {
                         *(float4*)(a.q_out + (size_t)t * a.i_dim + nn) = make_float4(v4[0], v4[1], v4[2], v4[3]);
-                    } else {
-                        void* cache = seg == 1 ? a.k_cache : a.v_cache;
+                    } else if (seg == 1) {  // K: [position][I]
                         const size_t e = (size_t)pos * a.i_dim + nn;
                         if (DT)
-                            *(uint2*)((uint16_t*)cache + e) =
+                            *(uint2*)((uint16_t*)a.k_cache + e) =
                                 make_uint2(f2bf(v4[0]) | (f2bf(v4[1]) << 16), f2bf(v4[2]) | (f2bf(v4[3]) << 16));
                         else
-                            *(float4*)((float*)cache + e) = make_float4(v4[0], v4[1], v4[2], v4[3]);
+                            *(float4*)((float*)a.k_cache + e) = make_float4(v4[0], v4[1], v4[2], v4[3]);
+                    } else {  // V: transposed, [I][vcap] with the position contiguous
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const size_t e = (size_t)(nn + v) * a.vcap + pos;
+                            if (DT)
+                                ((uint16_t*)a.v_cache)[e] = (uint16_t)f2bf(v4[v]);
+                            else
+                                ((float*)a.v_cache)[e] = v4[v];
+                        }
                     }
                 } break;
                 case EPI_LMHEAD: {
@@ -364,7 +414,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
         __syncthreads();
         if (tid < T) {
             Stat r = stat_neutral();
-            for (int w = 0; w < 4; ++w) {
+            for (int w = 0; w < NWV; ++w) {
                 const StatPart sp = wstat[w * 32 + tid];
                 r = stat_merge(r, Stat{sp.m, sp.s, sp.idx});
             }
@@ -379,187 +429,313 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     const int kt = dtype ? 32 : 16;
     const bool gated = a.epi == EPI_ACT && a.act != BILD_ACT_RELU;
     a.rw = gated ? 2 : 1;
+    const int nacc = a.rw * ((a.T + 15) / 16);
     int kc = 16384 / a.T - 8;
     kc = (kc / 128) * 128;
     if (kc < 128) kc = 128;
     if (kc > a.W.k) kc = a.W.k;
     a.kc = kc;
-    int wk = 1;
+    // input slices: about 8 tiles (one batch of loads) per wave
     const int tiles_chunk = kc / kt;
-    while (wk < 4 && (a.W.tn + (4 / wk) * a.rw - 1) / ((4 / wk) * a.rw) < 512 && tiles_chunk / (wk * 2) >= 2) wk *= 2;
+    int wk = 1;
+    while (wk < 8 && tiles_chunk / wk > 8) wk *= 2;
+    while (wk > 1 && wk * nacc > 32) wk /= 2;  // bound the LDS reduction area
+    // feature groups: as many as keep >= 512 workgroups, at least 4 waves per workgroup
+    int wr = std::max(1, 4 / wk);
+    for (int c = wr * 2; c * wk <= 8 && c * wk * nacc <= 32; c *= 2)
+        if ((a.W.tn + c * a.rw - 1) / (c * a.rw) >= 512) wr = c;
     a.wk = wk;
+    a.nwv = wk * wr;
 }
 
 size_t gemm_num_blocks(const GemmArgs& a) {
-    const int per = (4 / a.wk) * a.rw;
+    const int per = (a.nwv / a.wk) * a.rw;
     return (size_t)(a.W.tn + per - 1) / per;
 }
 
-template <int DT>
-__global__ void attn_kernel(const AttnArgs a);
+template <int DT, int DH32>
+__global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a);
 
-// Both big kernels may ask for more than the default 64 KiB of dynamic LDS.
+// The big kernels may ask for more than the default 64 KiB of dynamic LDS.
 static hipError_t raise_lds_limits() {
     static hipError_t done = [] {
         const int lim = 128 * 1024;
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)gemm_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)attn_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)attn_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-        return e;
+        const void* fns[] = {(const void*)gemm_kernel<0, 1>, (const void*)gemm_kernel<0, 2>,
+                             (const void*)gemm_kernel<1, 1>, (const void*)gemm_kernel<1, 2>,
+                             (const void*)attn_kernel<0, 1>, (const void*)attn_kernel<0, 2>,
+                             (const void*)attn_kernel<0, 4>, (const void*)attn_kernel<1, 1>,
+                             (const void*)attn_kernel<1, 2>, (const void*)attn_kernel<1, 4>};
+        for (const void* f : fns) {
+            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
     }();
     return done;
 }
 
 hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
-    const size_t smem = (size_t)xs_bytes(dtype, a.kc, a.T) + kTailBytes;
-    const dim3 grid((unsigned)gemm_num_blocks(a));
-    if (dtype)
-        hipLaunchKernelGGL(gemm_kernel<1>, grid, dim3(256), smem, st, a);
-    else
-        hipLaunchKernelGGL(gemm_kernel<0>, grid, dim3(256), smem, st, a);
+    const int nacc = a.rw * ((a.T + 15) / 16);
+    const size_t smem = (size_t)xs_bytes(dtype, a.kc, a.T) + gemm_tail_bytes(a.nwv, nacc);
+    const dim3 grid((unsigned)gemm_num_blocks(a)), block(64 * a.nwv);
+    if (dtype) {
+        if (a.rw == 2)
+            hipLaunchKernelGGL((gemm_kernel<1, 2>), grid, block, smem, st, a);
+        else
+            hipLaunchKernelGGL((gemm_kernel<1, 1>), grid, block, smem, st, a);
+    } else {
+        if (a.rw == 2)
+            hipLaunchKernelGGL((gemm_kernel<0, 2>), grid, block, smem, st, a);
+        else
+            hipLaunchKernelGGL((gemm_kernel<0, 1>), grid, block, smem, st, a);
+    }
     return hipGetLastError();
 }
 
 // =====================================================================================
-// Attention over a position-major cache [position][I].  One workgroup per (head, key
-// split); all T query rows share each K/V load.  Keys are processed 256 at a time:
-// one thread per key computes the T scores, the waves update the running (max, sum)
-// of their rows, then threads re-map to (key part, head dim) for the P V product.
+// KV-cache attention on the matrix cores.  K is stored [position][I]; V is stored
+// transposed, [I][capacity], so that both products contract over a contiguous axis:
+//   S^T[key][row] = K[key][:] . q[row][:]      A = K tile (16 keys x 32 dims), B = q^T
+//   O^T[dim][row] += V^T[dim][key] P[key][row] A = V^T tile (16 dims x 32 keys), B = P
+// One workgroup per (head, key split); its waves take 32-key blocks round robin and keep
+// a running (max, sum, O) per query row, merged across waves in LDS at the end.  The score
+// tile leaves the MFMA with lane (row, g) holding keys 4g..4g+3 of each 16-key tile, which
+// is exactly the B-operand order of the second product if its contraction index 8g+j is
+// read as "key 4g+j of the first tile (j<4) / of the second tile (j>=4)" - so the
+// probabilities never move between lanes; the V^T loads follow the same key order.
+// q and P are real-valued: bf16 models split them into high and low bf16 parts.
+// Cache rows beyond the valid length are finite (zero-filled at allocation, or stale
+// values of discarded tokens), so a probability of exactly 0 removes them.
 // =====================================================================================
-template <int DT>
-__global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
+template <int DT, int DH32>
+__global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int DHP = DH32 * 32;   // head dim padded to the k-step of the first product
+    constexpr int DT16 = DH32 * 2;   // 16-wide output tiles along the head dim
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nthr = blockDim.x, nw = nthr >> 6;
     const int T = a.T, dh = a.d_head, I = a.i_dim;
     const int h = blockIdx.x, sp = blockIdx.y;
-    float* q_s = (float*)smem;              // [T][dh]
-    float* S = q_s + T * dh;                // [T][256]
-    float* m_s = S + T * 256;               // [T]
-    float* l_s = m_s + kMaxRows;            // [T]
-    float* f_s = l_s + kMaxRows;            // [T]
-    float* red = f_s + kMaxRows;            // [nparts][T][dh]
+    const int NT = (T + 15) >> 4;
+    const int tok_l = lane & 15, g = lane >> 4;
+    const int qstride = DT ? (DHP + 8) * 2 : (DHP + 4) * 4;
+    char* q_hi = smem;
+    char* q_lo = smem + NT * 16 * qstride;  // bf16 only
+    char* comb = smem + NT * 16 * qstride * (DT ? 2 : 1);
+    float* cm = (float*)comb;                 // [nw][32]
+    float* cl = cm + nw * 32;                 // [nw][32]
+    f32x4* co = (f32x4*)(cl + nw * 32);       // [nw][NT][DT16][64]
 
     const int base = a.causal ? (*a.base_ptr + a.base_add) : 0;
     const int nkeys = a.causal ? base + T : (a.nkeys_ptr ? *a.nkeys_ptr : a.nkeys_fixed);
-    int per = (nkeys + a.splits - 1) / a.splits;
-    per = ((per + 255) / 256) * 256;
-    const int k_begin = min(nkeys, sp * per), k_end = min(nkeys, k_begin + per);
+    const int nblk = (nkeys + 31) >> 5;
+    const int bps = (nblk + a.splits - 1) / a.splits;
+    const int blk_begin = min(nblk, sp * bps), blk_end = min(nblk, blk_begin + bps);
 
-    for (int i = tid; i < T * dh; i += 256) q_s[i] = a.q[(size_t)(i / dh) * I + h * dh + (i % dh)] * a.scale;
-    if (tid < T) {
-        m_s[tid] = -INFINITY;
-        l_s[tid] = 0.f;
+    // ---- stage q * scale (zero padded to NT*16 rows x DHP dims) ----
+    for (int i = tid; i < NT * 16 * (DHP / 4); i += nthr) {
+        const int t = i / (DHP / 4), d4 = (i % (DHP / 4)) * 4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (t < T && d4 < dh) {
+            v = *(const float4*)(a.q + (size_t)t * I + h * dh + d4);
+            v.x *= a.scale; v.y *= a.scale; v.z *= a.scale; v.w *= a.scale;
+        }
+        if (DT) {
+            const uint32_t h0 = f2bf(v.x), h1 = f2bf(v.y), h2 = f2bf(v.z), h3 = f2bf(v.w);
+            const uint32_t l0 = f2bf(v.x - bf2f(h0)), l1 = f2bf(v.y - bf2f(h1));
+            const uint32_t l2 = f2bf(v.z - bf2f(h2)), l3 = f2bf(v.w - bf2f(h3));
+            *(uint2*)(q_hi + t * qstride + d4 * 2) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+            *(uint2*)(q_lo + t * qstride + d4 * 2) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+        } else {
+            *(float4*)(q_hi + t * qstride + d4 * 4) = v;
+        }
     }
-    const int nparts = 256 / dh;
-    const int pd = tid % dh, part = tid / dh;
-    float acc[kMaxRows];
-#pragma unroll
-    for (int t = 0; t < kMaxRows; ++t) acc[t] = 0.f;
     __syncthreads();
 
-    for (int c0 = k_begin; c0 < k_end; c0 += 256) {
-        const int key = c0 + tid;
-        const bool kvalid = key < k_end;
-        // ---- scores of this thread's key against every row ----
-        float s[kMaxRows];
+    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    f32x4 O[2][DT16];
 #pragma unroll
-        for (int t = 0; t < kMaxRows; ++t) s[t] = 0.f;
-        if (kvalid) {
-            for (int seg = 0; seg < dh; seg += 8) {
-                float kf[8];
-                if (DT) {
-                    const uint4 u = *(const uint4*)((const uint16_t*)a.k + (size_t)key * I + h * dh + seg);
-                    kf[0] = bf2f(u.x & 0xFFFF); kf[1] = bf2f(u.x >> 16);
-                    kf[2] = bf2f(u.y & 0xFFFF); kf[3] = bf2f(u.y >> 16);
-                    kf[4] = bf2f(u.z & 0xFFFF); kf[5] = bf2f(u.z >> 16);
-                    kf[6] = bf2f(u.w & 0xFFFF); kf[7] = bf2f(u.w >> 16);
-                } else {
-                    const float4 u0 = *(const float4*)((const float*)a.k + (size_t)key * I + h * dh + seg);
-                    const float4 u1 = *(const float4*)((const float*)a.k + (size_t)key * I + h * dh + seg + 4);
-                    kf[0] = u0.x; kf[1] = u0.y; kf[2] = u0.z; kf[3] = u0.w;
-                    kf[4] = u1.x; kf[5] = u1.y; kf[6] = u1.z; kf[7] = u1.w;
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int dt = 0; dt < DT16; ++dt) O[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const size_t esz = DT ? 2 : 4;
+    for (int blk = blk_begin + wave; blk < blk_end; blk += nw) {
+        const int key0 = blk * 32;
+        // ---- loads: K rows of both 16-key tiles, V^T columns of the same 32 keys ----
+        uint4 Kr[2][DT ? DH32 : DH32 * 2];
+        uint4 Vr[DT16][DT ? 1 : 2];
+#pragma unroll
+        for (int ab = 0; ab < 2; ++ab) {
+            const char* krow = (const char*)a.k + ((size_t)(key0 + ab * 16 + tok_l) * I + h * dh) * esz;
+            if (DT) {
+#pragma unroll
+                for (int ks = 0; ks < DH32; ++ks) {
+                    const int d0 = ks * 32 + g * 8;
+                    Kr[ab][ks] = d0 < dh ? *(const uint4*)(krow + d0 * 2) : make_uint4(0, 0, 0, 0);
                 }
+            } else {
 #pragma unroll
-                for (int t = 0; t < kMaxRows; ++t) {
-                    if (t < T) {
-                        const float4 qa = *(const float4*)(q_s + t * dh + seg);
-                        const float4 qb = *(const float4*)(q_s + t * dh + seg + 4);
-                        s[t] += qa.x * kf[0] + qa.y * kf[1] + qa.z * kf[2] + qa.w * kf[3] + qb.x * kf[4] + qb.y * kf[5] +
-                                qb.z * kf[6] + qb.w * kf[7];
+                for (int ks = 0; ks < DH32 * 2; ++ks) {
+                    const int d0 = ks * 16 + g * 4;
+                    Kr[ab][ks] = d0 < dh ? *(const uint4*)(krow + d0 * 4) : make_uint4(0, 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT16; ++dt) {
+            const int d = dt * 16 + tok_l;
+            const char* vrow = (const char*)a.v + ((size_t)(h * dh + d) * a.vcap + key0 + g * 4) * esz;
+            if (DT) {
+                uint2 va = make_uint2(0, 0), vb = make_uint2(0, 0);
+                if (d < dh) {
+                    va = *(const uint2*)vrow;
+                    vb = *(const uint2*)(vrow + 16 * 2);
+                }
+                Vr[dt][0] = make_uint4(va.x, va.y, vb.x, vb.y);
+            } else {
+                Vr[dt][0] = d < dh ? *(const uint4*)vrow : make_uint4(0, 0, 0, 0);
+                Vr[dt][1] = d < dh ? *(const uint4*)(vrow + 16 * 4) : make_uint4(0, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            if (nt >= NT) continue;
+            const int t = nt * 16 + tok_l;
+            // ---- scores of this row against the 32 keys ----
+            f32x4 s[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+            if (DT) {
+#pragma unroll
+                for (int ks = 0; ks < DH32; ++ks) {
+                    const bf16x8 Bh = __builtin_bit_cast(bf16x8, *(const uint4*)(q_hi + t * qstride + (ks * 32 + g * 8) * 2));
+                    const bf16x8 Bl = __builtin_bit_cast(bf16x8, *(const uint4*)(q_lo + t * qstride + (ks * 32 + g * 8) * 2));
+#pragma unroll
+                    for (int ab = 0; ab < 2; ++ab) {
+                        const bf16x8 Ak = __builtin_bit_cast(bf16x8, Kr[ab][ks]);
+                        s[ab] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Ak, Bh, s[ab], 0, 0, 0);
+                        s[ab] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Ak, Bl, s[ab], 0, 0, 0);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < DH32 * 2; ++ks) {
+                    const float4 b = *(const float4*)(q_hi + t * qstride + (ks * 16 + g * 4) * 4);
+                    const float bb[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+                    for (int ab = 0; ab < 2; ++ab) {
+                        const float aa[4] = {__uint_as_float(Kr[ab][ks].x), __uint_as_float(Kr[ab][ks].y),
+                                             __uint_as_float(Kr[ab][ks].z), __uint_as_float(Kr[ab][ks].w)};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            s[ab] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j], bb[j], s[ab], 0, 0, 0);
+                    }
+                }
+            }
+            // ---- mask, running max / sum ----
+            const int lim = a.causal ? min(nkeys - 1, base + t) : nkeys - 1;  // last visible key of this row
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int ab = 0; ab < 2; ++ab)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int key = key0 + ab * 16 + g * 4 + v;
+                    if (key > lim || t >= T) s[ab][v] = -INFINITY;
+                    tmax = fmaxf(tmax, s[ab][v]);
+                }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const float m_new = fmaxf(m_run[nt], tmax);
+            const float f = (m_run[nt] == -INFINITY) ? 0.f : expf(m_run[nt] - m_new);
+            float p[2][4], psum = 0.f;
+#pragma unroll
+            for (int ab = 0; ab < 2; ++ab)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    p[ab][v] = (m_new == -INFINITY) ? 0.f : expf(s[ab][v] - m_new);
+                    psum += p[ab][v];
+                }
+            psum += __shfl_xor(psum, 16, 64);
+            psum += __shfl_xor(psum, 32, 64);
+            l_run[nt] = l_run[nt] * f + psum;
+            m_run[nt] = m_new;
+            // ---- O = O * f + V^T P ----
+            if (DT) {
+                uint32_t ph[8], pl[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float pv = p[j >> 2][j & 3];
+                    ph[j] = f2bf(pv);
+                    pl[j] = f2bf(pv - bf2f(ph[j]));
+                }
+                const bf16x8 Ph = __builtin_bit_cast(
+                    bf16x8, make_uint4(ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16), ph[4] | (ph[5] << 16), ph[6] | (ph[7] << 16)));
+                const bf16x8 Pl = __builtin_bit_cast(
+                    bf16x8, make_uint4(pl[0] | (pl[1] << 16), pl[2] | (pl[3] << 16), pl[4] | (pl[5] << 16), pl[6] | (pl[7] << 16)));
+#pragma unroll
+                for (int dt = 0; dt < DT16; ++dt) {
+                    O[nt][dt] *= f;
+                    const bf16x8 Av = __builtin_bit_cast(bf16x8, Vr[dt][0]);
+                    O[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Av, Ph, O[nt][dt], 0, 0, 0);
+                    O[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Av, Pl, O[nt][dt], 0, 0, 0);
+                }
+            } else {
+#pragma unroll
+                for (int dt = 0; dt < DT16; ++dt) {
+                    O[nt][dt] *= f;
+#pragma unroll
+                    for (int ab = 0; ab < 2; ++ab) {
+                        const uint4 vv = Vr[dt][DT ? 0 : ab];
+                        const float aa[4] = {__uint_as_float(vv.x), __uint_as_float(vv.y), __uint_as_float(vv.z),
+                                             __uint_as_float(vv.w)};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            O[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j], p[ab][j], O[nt][dt], 0, 0, 0);
                     }
                 }
             }
         }
-#pragma unroll
-        for (int t = 0; t < kMaxRows; ++t)
-            if (t < T) S[t * 256 + tid] = (kvalid && (!a.causal || key <= base + t)) ? s[t] : -INFINITY;
-        __syncthreads();
-        // ---- running max / sum per row; scores become probabilities relative to the new max ----
-        for (int t = wave; t < T; t += 4) {
-            float v[4], mx = -INFINITY;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                v[i] = S[t * 256 + lane + 64 * i];
-                mx = fmaxf(mx, v[i]);
-            }
-            mx = wave_max(mx);
-            const float m_old = m_s[t], m_new = fmaxf(m_old, mx);
-            float sum = 0.f;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float p = (m_new == -INFINITY) ? 0.f : expf(v[i] - m_new);
-                S[t * 256 + lane + 64 * i] = p;
-                sum += p;
-            }
-            sum = wave_sum(sum);
-            if (lane == 0) {
-                const float f = (m_old == -INFINITY) ? 0.f : expf(m_old - m_new);
-                f_s[t] = f;
-                l_s[t] = l_s[t] * f + sum;
-                m_s[t] = m_new;
-            }
-        }
-        __syncthreads();
-        // ---- acc[t][pd] += sum over this part's keys of P[t][key] * V[key][pd] ----
-        if (part < nparts) {
-#pragma unroll
-            for (int t = 0; t < kMaxRows; ++t)
-                if (t < T) acc[t] *= f_s[t];
-            const int nk = min(256, k_end - c0);
-            for (int kk = part; kk < nk; kk += nparts) {
-                const size_t e = (size_t)(c0 + kk) * I + h * dh + pd;
-                const float vv = DT ? bf2f(((const uint16_t*)a.v)[e]) : ((const float*)a.v)[e];
-#pragma unroll
-                for (int t = 0; t < kMaxRows; ++t)
-                    if (t < T) acc[t] += S[t * 256 + kk] * vv;
-            }
-        }
-        __syncthreads();
     }
-    if (part < nparts) {
+
+    // ---- merge the waves' partial results ----
 #pragma unroll
-        for (int t = 0; t < kMaxRows; ++t)
-            if (t < T) red[(part * T + t) * dh + pd] = acc[t];
+    for (int nt = 0; nt < 2; ++nt) {
+        if (nt >= NT) continue;
+        if (g == 0) {
+            cm[wave * 32 + nt * 16 + tok_l] = m_run[nt];
+            cl[wave * 32 + nt * 16 + tok_l] = l_run[nt];
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT16; ++dt) co[((wave * NT + nt) * DT16 + dt) * 64 + lane] = O[nt][dt];
     }
     __syncthreads();
-    for (int i = tid; i < T * dh; i += 256) {
-        const int t = i / dh, d = i % dh;
-        float o = 0.f;
-        for (int p = 0; p < nparts; ++p) o += red[(p * T + t) * dh + d];
-        if (a.splits == 1)
-            a.out[(size_t)t * I + h * dh + d] = o / l_s[t];
-        else
-            a.part_o[((size_t)sp * T + t) * I + h * dh + d] = o;
-    }
-    if (a.splits > 1 && tid < T) {
-        float* ml = a.part_ml + (((size_t)sp * T + tid) * a.heads + h) * 2;
-        ml[0] = m_s[tid];
-        ml[1] = l_s[tid];
+    for (int qd = wave; qd < NT * DT16; qd += nw) {
+        const int nt = qd / DT16, dt = qd % DT16;
+        const int t = nt * 16 + tok_l, d0 = dt * 16 + g * 4;
+        float M = -INFINITY;
+        for (int w = 0; w < nw; ++w) M = fmaxf(M, cm[w * 32 + nt * 16 + tok_l]);
+        float Lsum = 0.f;
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int w = 0; w < nw; ++w) {
+            const float mw = cm[w * 32 + nt * 16 + tok_l];
+            const float wgt = (mw == -INFINITY) ? 0.f : expf(mw - M);
+            Lsum += cl[w * 32 + nt * 16 + tok_l] * wgt;
+            acc += co[((w * NT + nt) * DT16 + dt) * 64 + lane] * wgt;
+        }
+        if (t < T && d0 < dh) {
+            if (a.splits == 1) {
+                const float inv = 1.f / Lsum;
+                *(float4*)(a.out + (size_t)t * I + h * dh + d0) =
+                    make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+            } else {
+                *(float4*)(a.part_o + ((size_t)sp * T + t) * I + h * dh + d0) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+                if (dt == 0 && g == 0) {
+                    float* ml = a.part_ml + (((size_t)sp * T + t) * a.heads + h) * 2;
+                    ml[0] = M;
+                    ml[1] = Lsum;
+                }
+            }
+        }
     }
 }
 
@@ -580,16 +756,24 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) {
     }
 }
 
+size_t attn_lds_bytes(int dtype, int d_head, int T, int nw) {
+    const int dh32 = d_head <= 32 ? 1 : (d_head <= 64 ? 2 : 4), dhp = dh32 * 32, nt = (T + 15) / 16;
+    const size_t q = (size_t)nt * 16 * (dtype ? (dhp + 8) * 2 * 2 : (dhp + 4) * 4);
+    return q + (size_t)nw * 32 * 4 * 2 + (size_t)nw * nt * (dh32 * 2) * 64 * 16;
+}
+
 hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
     if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
-    const int nparts = 256 / a.d_head;
-    const size_t smem = sizeof(float) * ((size_t)a.T * a.d_head + (size_t)a.T * 256 + 3 * kMaxRows +
-                                         (size_t)nparts * a.T * a.d_head);
-    const dim3 grid(a.heads, a.splits);
-    if (dtype)
-        hipLaunchKernelGGL(attn_kernel<1>, grid, dim3(256), smem, st, a);
-    else
-        hipLaunchKernelGGL(attn_kernel<0>, grid, dim3(256), smem, st, a);
+    const int dh32 = a.d_head <= 32 ? 1 : (a.d_head <= 64 ? 2 : 4);
+    const size_t smem = attn_lds_bytes(dtype, a.d_head, a.T, a.nw);
+    const dim3 grid(a.heads, a.splits), block(64 * a.nw);
+#define BILD_ATTN(DTV, DHV) hipLaunchKernelGGL((attn_kernel<DTV, DHV>), grid, block, smem, st, a)
+    if (dtype) {
+        if (dh32 == 1) BILD_ATTN(1, 1); else if (dh32 == 2) BILD_ATTN(1, 2); else BILD_ATTN(1, 4);
+    } else {
+        if (dh32 == 1) BILD_ATTN(0, 1); else if (dh32 == 2) BILD_ATTN(0, 2); else BILD_ATTN(0, 4);
+    }
+#undef BILD_ATTN
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.splits == 1) return e;
     hipLaunchKernelGGL(attn_merge_kernel, dim3(a.T), dim3(256), 0, st, a);
@@ -637,6 +821,7 @@ hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st) {
 //           y <- y[:draft_start + r] + [argmax of row r]; cache lengths follow
 //   mode 2  plain greedy: always append
 //   mode 3  no LM head: only advance the cache length by the rows consumed
+//   mode 4  measurement: merge the statistics, commit nothing
 // =====================================================================================
 __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
     __shared__ float rm[kMaxRows], rsum[kMaxRows];
@@ -667,6 +852,7 @@ __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
         return;
     }
     for (int t = 0; t < a.T; ++t) c->res_rowtok[t] = ridx[t];
+    if (a.mode == 4) return;
     if (a.mode == 0 || a.mode == 2) {
         const int tok = ridx[a.T - 1];
         const float pmax = 1.f / rsum[a.T - 1];
