@@ -4,7 +4,10 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <array>
 #include <cmath>
+#include <cstdlib>
+#include <map>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -82,7 +85,12 @@ struct bild_state {
     const bild_pair* pair = nullptr;
     ModelState ms[2];
     Ctl* ctl = nullptr;   // device
-    Ctl* hctl = nullptr;  // pinned host mirror of the last readback
+    Ctl* hctl = nullptr;  // pinned host mirror of the control block, written by the policy kernel
+    Ctl* hctl_dev = nullptr;  // the same buffer as the device sees it
+    float* halpha = nullptr;  // pinned staging for threshold updates
+    float alpha_fb = -1.f, alpha_rb = -1.f;  // thresholds currently in the device control block
+    bool use_graphs = true;
+    std::map<std::array<int, 6>, hipGraphExec_t> graphs;  // captured passes by (model, rows, lm rows, mode, key bucket, debug)
     int* y = nullptr;     // device [max_len + 1]
     int* src = nullptr;   // device [max_src]
     hipStream_t stream = nullptr;
@@ -296,6 +304,7 @@ extern "C" int bild_state_destroy(bild_state* s) {
     for (void* p : s->allocs) (void)hipFree(p);
     for (void* p : s->host_allocs) (void)hipHostFree(p);
     for (hipEvent_t e : s->prof_ev) (void)hipEventDestroy(e);
+    for (auto& kv : s->graphs) (void)hipGraphExecDestroy(kv.second);
     if (s->own_stream && s->stream) (void)hipStreamDestroy(s->stream);
     delete s;
     return BILD_OK;
@@ -314,6 +323,10 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
     s->n_max = n_max;
     s->cap_len = (max_len + 31) / 32 * 32;
     s->cap_src = (max_src + 31) / 32 * 32;
+    if (kernels_init() != hipSuccess) {
+        delete s;
+        return BILD_EHIP;
+    }
     int rc = BILD_OK;
 #define AL(ptr, bytes)                                            \
     do {                                                          \
@@ -336,12 +349,23 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
     AL(s->y, sizeof(int) * (size_t)(max_len + 1));
     AL(s->src, sizeof(int) * (size_t)max_src);
     void* h = nullptr;
-    if (hipHostMalloc(&h, sizeof(Ctl), hipHostMallocDefault) != hipSuccess) {
+    if (hipHostMalloc(&h, sizeof(Ctl) + 64, hipHostMallocMapped) != hipSuccess) {
         bild_state_destroy(s);
         return BILD_ENOMEM;
     }
     s->host_allocs.push_back(h);
     s->hctl = (Ctl*)h;
+    s->halpha = (float*)((char*)h + sizeof(Ctl));
+    void* hd = nullptr;
+    if (hipHostGetDevicePointer(&hd, h, 0) != hipSuccess) {
+        bild_state_destroy(s);
+        return BILD_EHIP;
+    }
+    s->hctl_dev = (Ctl*)hd;
+    {
+        const char* ng = std::getenv("BILD_NO_GRAPH");
+        s->use_graphs = !(ng && ng[0] == '1');
+    }
     for (int w = 0; w < 2; ++w) {
         ModelState& M = s->ms[w];
         const bild_model* m = p->m[w];
@@ -402,13 +426,28 @@ int push_ctl(bild_state* s) {
     h->len[1] = s->len[1];
     h->n_src = s->n_src;
     h->n_max = s->n_max;
+    h->alpha_fb = s->alpha_fb;
+    h->alpha_rb = s->alpha_rb;
     HIPC(hipMemcpyAsync(s->ctl, h, sizeof(Ctl), hipMemcpyHostToDevice, s->stream));
     HIPC(hipStreamSynchronize(s->stream));
     return BILD_OK;
 }
 
+// Thresholds live in the device control block so that captured passes need no new arguments.
+int set_alpha(bild_state* s, float fb, float rb) {
+    // compare bit patterns so that +-inf and every other value round-trip exactly
+    if (std::memcmp(&fb, &s->alpha_fb, 4) == 0 && std::memcmp(&rb, &s->alpha_rb, 4) == 0) return BILD_OK;
+    HIPC(hipStreamSynchronize(s->stream));  // the staging buffer may still be in use by an earlier copy
+    s->halpha[0] = fb;
+    s->halpha[1] = rb;
+    HIPC(hipMemcpyAsync(&s->ctl->alpha_fb, s->halpha, 8, hipMemcpyHostToDevice, s->stream));
+    s->alpha_fb = fb;
+    s->alpha_rb = rb;
+    return BILD_OK;
+}
+
+// Waits for the stream; the policy kernel has mirrored the control block into pinned host memory.
 int pull_ctl(bild_state* s) {
-    HIPC(hipMemcpyAsync(s->hctl, s->ctl, sizeof(Ctl), hipMemcpyDeviceToHost, s->stream));
     HIPC(hipStreamSynchronize(s->stream));
     s->y_len = s->hctl->y_len;
     s->draft_start = s->hctl->draft_start;
@@ -480,7 +519,7 @@ int run_gemm(bild_state* s, const bild_model* m, GemmArgs& g) {
 // One decoder pass of model w over rows y[len .. len+T): embed, layers, and (lm_rows > 0)
 // the LM head over the last lm_rows rows followed by the policy `mode`; lm_rows == 0
 // only advances the cache (catch-up / prefill).
-int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, float alpha) {
+int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hint) {
     ModelState& M = s->ms[w];
     const bild_model* m = M.m;
     const bild_model_config& c = m->cfg;
@@ -526,8 +565,8 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, float alpha
             a.causal = 1;
             a.base_ptr = len_ptr;
             a.vcap = s->cap_len;
-            a.splits = pick_splits(M, s->len[w] + T, c.n_heads);
-            a.nw = pick_attn_waves(dt, c.d_head, T, s->len[w] + T, a.splits);
+            a.splits = pick_splits(M, key_hint, c.n_heads);
+            a.nw = pick_attn_waves(dt, c.d_head, T, key_hint, a.splits);
             a.part_o = M.att_o; a.part_ml = M.att_ml;
             a.scale = att_scale;
             HIPC(launch_attention(a, dt, s->stream));
@@ -598,8 +637,8 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, float alpha
     f.y = s->y;
     f.which = w;
     f.rows_consumed = T;
-    f.alpha = alpha;
     f.y_cap = s->max_len;
+    f.host_mirror = s->hctl_dev;
     if (lm_rows > 0) {
         GemmArgs g = gemm_base(m, m->head, M.x + (size_t)(T - lm_rows) * d, d, lm_rows, m->dec_final);
         g.epi = EPI_LMHEAD;
@@ -623,7 +662,6 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, float alpha
         f.zt = M.zt;
         f.T = lm_rows;
         f.mode = mode;
-        M.last_rows = lm_rows;
     } else {
         f.mode = 3;
     }
@@ -631,11 +669,45 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, float alpha
     return BILD_OK;
 }
 
+int key_bucket(int nkeys) {
+    int b = 64;
+    while (b < nkeys) b *= 2;
+    return b;
+}
+
+// One pass, replayed from a captured graph when possible.  Launch parameters that depend on the cache
+// length are chosen per power-of-two bucket of the key count, so a graph stays valid while the
+// sequence grows inside its bucket; everything else the kernels need they read from the control block.
+int run_pass(bild_state* s, int w, int T, int lm_rows, int mode) {
+    const int bucket = key_bucket(s->len[w] + T);
+    if (lm_rows > 0) s->ms[w].last_rows = lm_rows;
+    if (!s->use_graphs || s->prof_on || mode == 3) return decoder_pass(s, w, T, lm_rows, mode, bucket);
+    const std::array<int, 6> key = {w, T, lm_rows, mode, bucket, s->debug_logits ? 1 : 0};
+    auto it = s->graphs.find(key);
+    if (it == s->graphs.end()) {
+        hipGraph_t g = nullptr;
+        HIPC(hipStreamBeginCapture(s->stream, hipStreamCaptureModeThreadLocal));
+        const int rc = decoder_pass(s, w, T, lm_rows, mode, bucket);
+        const hipError_t e = hipStreamEndCapture(s->stream, &g);
+        if (rc != BILD_OK || e != hipSuccess) {
+            if (g) (void)hipGraphDestroy(g);
+            return rc != BILD_OK ? rc : BILD_EHIP;
+        }
+        hipGraphExec_t ge = nullptr;
+        const hipError_t e2 = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(g);
+        if (e2 != hipSuccess) return BILD_EHIP;
+        it = s->graphs.emplace(key, ge).first;
+    }
+    HIPC(hipGraphLaunch(it->second, s->stream));
+    return BILD_OK;
+}
+
 // Brings model w's cache up to `target` consumed rows with LM-head-less passes.
 int catch_up(bild_state* s, int w, int target) {
     while (s->len[w] < target) {
         const int T = std::min(kMaxRows, target - s->len[w]);
-        int rc = decoder_pass(s, w, T, 0, 3, 0.f);
+        int rc = run_pass(s, w, T, 0, 3);
         if (rc) return rc;
         s->len[w] += T;  // the device advances the same amount
     }
@@ -790,9 +862,11 @@ extern "C" int bild_small_step(bild_state* s, float alpha_fb, int32_t* token, in
     if (!s->encoded) return BILD_ESTATE;
     if (s->len[0] >= s->y_len) return BILD_ESTATE;  // nothing unconsumed
     if (s->y_len >= s->max_len) return BILD_ECAP;
-    int rc = catch_up(s, 0, s->y_len - 1);
+    int rc = set_alpha(s, alpha_fb, s->alpha_rb);
     if (rc) return rc;
-    rc = decoder_pass(s, 0, 1, 1, 0, alpha_fb);
+    rc = catch_up(s, 0, s->y_len - 1);
+    if (rc) return rc;
+    rc = run_pass(s, 0, 1, 1, 0);
     if (rc) return rc;
     rc = pull_ctl(s);
     if (rc) return rc;
@@ -827,10 +901,12 @@ extern "C" int bild_large_verify(bild_state* s, const int32_t* draft, int n, flo
         if (s->y_len + 1 > s->max_len) return BILD_ECAP;
     }
     if (s->len[1] > s->draft_start - 1) return BILD_ESTATE;
-    int rc = catch_up(s, 1, s->draft_start - 1);
+    int rc = set_alpha(s, s->alpha_fb, alpha_rb);
+    if (rc) return rc;
+    rc = catch_up(s, 1, s->draft_start - 1);
     if (rc) return rc;
     const int ds = s->draft_start;
-    rc = decoder_pass(s, 1, n + 1, n + 1, 1, alpha_rb);
+    rc = run_pass(s, 1, n + 1, n + 1, 1);
     if (rc) return rc;
     rc = pull_ctl(s);
     if (rc) return rc;
@@ -971,7 +1047,7 @@ extern "C" int bild_greedy(bild_state* s, int which, const int32_t* src, int n_s
     while (s->y_len - s->n0 < max_new && !(s->y_len > s->n0 && last == eos && eos >= 0)) {
         rc = catch_up(s, w, s->y_len - 1);
         if (rc) return rc;
-        rc = decoder_pass(s, w, 1, 1, 2, 0.f);
+        rc = run_pass(s, w, 1, 1, 2);
         if (rc) return rc;
         rc = pull_ctl(s);
         if (rc) return rc;
@@ -1020,9 +1096,9 @@ extern "C" int bild_bench_pass(bild_state* s, int which, int rows, int reps, flo
     hipEvent_t e0, e1;
     HIPC(hipEventCreate(&e0));
     HIPC(hipEventCreate(&e1));
-    rc = decoder_pass(s, w, rows, rows, 4, 0.f);  // warm-up
+    rc = run_pass(s, w, rows, rows, 4);  // warm-up (and graph capture)
     if (rc == BILD_OK && hipEventRecord(e0, s->stream) != hipSuccess) rc = BILD_EHIP;
-    for (int i = 0; i < reps && rc == BILD_OK; ++i) rc = decoder_pass(s, w, rows, rows, 4, 0.f);
+    for (int i = 0; i < reps && rc == BILD_OK; ++i) rc = run_pass(s, w, rows, rows, 4);
     if (rc == BILD_OK && hipEventRecord(e1, s->stream) != hipSuccess) rc = BILD_EHIP;
     if (rc == BILD_OK && hipEventSynchronize(e1) != hipSuccess) rc = BILD_EHIP;
     float ms = 0.f;

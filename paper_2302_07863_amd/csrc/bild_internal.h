@@ -34,7 +34,9 @@ struct Ctl {
     int len[2];       // consumed rows per model: [0] small, [1] large
     int n_src;        // source length (cross-attention keys) or prompt length
     int n_max;
-    // results of the last pass, copied to the host after it
+    float alpha_fb;   // thresholds of the two policies (Sections 3.3, 3.4), read by the policy kernel
+    float alpha_rb;
+    // results of the last pass, mirrored to the host after it
     int res_tok;
     int res_flag;
     int res_r;
@@ -99,6 +101,7 @@ struct GemmArgs {
     int nwv;  // waves per workgroup = wk * feature groups (4 or 8)
     int rw;   // feature tiles per wave (1, or 2 for gated FFNs)
     int kc;   // inputs staged in LDS per chunk
+    unsigned long long* trace;  // kernel-internal time stamps (only read when built with BILD_TRACE)
 };
 
 struct AttnArgs {
@@ -139,10 +142,10 @@ struct FinishArgs {
     int T;       // rows that went through the LM head
     int row_off; // first such row within the pass
     int which;   // 0 small, 1 large
-    int mode;    // 0 small step, 1 verify, 2 plain greedy (always append)
+    int mode;    // 0 small step, 1 verify, 2 plain greedy (always append), 3 advance only, 4 measure
     int rows_consumed;  // rows the pass consumed (cache advance)
-    float alpha;
     int y_cap;
+    Ctl* host_mirror;   // device-visible pinned host copy of the control block, written last
 };
 
 // launch wrappers (kernels.hip); each returns the hipError_t of the launch
@@ -150,6 +153,7 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st);
 hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st);
 hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st);
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st);
+hipError_t kernels_init();  // one-time function attributes; call before any stream capture
 size_t gemm_num_blocks(const GemmArgs& a);
 size_t attn_lds_bytes(int dtype, int d_head, int T, int nw);
 void gemm_pick_shape(GemmArgs& a, int dtype);

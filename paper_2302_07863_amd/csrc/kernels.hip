@@ -35,15 +35,31 @@ __device__ __forceinline__ uint32_t f2bf(float f) {  // fp32 -> bf16 bits, neare
 }
 __device__ __forceinline__ float bf2f(uint32_t h) { return __uint_as_float(h << 16); }
 
+// Wavefront reductions on the data-parallel-primitive path (no LDS crossbar):
+// two quad permutes, two row mirrors, then row broadcasts carry the row totals
+// upward so that lane 63 holds the result, which is read back as a uniform value.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f(float fill, float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, fill), __builtin_bit_cast(int, v),
+                                                                  CTRL, ROW_MASK, 0xF, false));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    v += dpp_f<0xB1, 0xF>(0.f, v);   // quad_perm [1,0,3,2]
+    v += dpp_f<0x4E, 0xF>(0.f, v);   // quad_perm [2,3,0,1]
+    v += dpp_f<0x141, 0xF>(0.f, v);  // row_half_mirror
+    v += dpp_f<0x140, 0xF>(0.f, v);  // row_mirror: every lane of a 16-lane row holds the row total
+    v += dpp_f<0x142, 0xA>(0.f, v);  // row_bcast15 into rows 1 and 3
+    v += dpp_f<0x143, 0xC>(0.f, v);  // row_bcast31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+    v = fmaxf(v, dpp_f<0xB1, 0xF>(-INFINITY, v));
+    v = fmaxf(v, dpp_f<0x4E, 0xF>(-INFINITY, v));
+    v = fmaxf(v, dpp_f<0x141, 0xF>(-INFINITY, v));
+    v = fmaxf(v, dpp_f<0x140, 0xF>(-INFINITY, v));
+    v = fmaxf(v, dpp_f<0x142, 0xA>(-INFINITY, v));
+    v = fmaxf(v, dpp_f<0x143, 0xC>(-INFINITY, v));
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 // ---- online softmax statistics ------------------------------------------------------
@@ -104,7 +120,7 @@ __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
     return gemm_red_bytes(nwv, nacc) + nwv * 32 * 4 + 32 * 4 + nwv * 32 * 16;
 }
 
-template <int DT, int RW>
+template <int DT, int RW, int EPI, int ROPE>
 __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int KT = DT ? 32 : 16;
@@ -137,20 +153,29 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
         wbase[r] = (const char*)a.W.w + ((size_t)(tile0 + r) * a.W.tk) * kTileBytes + lane * 16;
     }
     const int tok_l = lane & 15, kq = lane >> 4;
+#ifdef BILD_TRACE
+    unsigned long long* tr = (a.trace && blockIdx.x == gridDim.x / 2 && tid == 0) ? a.trace : nullptr;
+#define STAMP(i) do { if (tr) tr[i] = wall_clock64(); } while (0)
+#else
+#define STAMP(i) do { } while (0)
+#endif
+    STAMP(0);
 
     // ---- first batch of weight tiles and the residual values: issued before anything else ----
-    uint4 A[RW][U];
-    {
-        const int nkt0 = min(KC, K) / KT;
+    // Two register buffers of U tiles each: while one is consumed the next batch is in flight.
+    uint4 B0[RW][U], B1[RW][U];
+    const int S = U * WK;  // tiles between consecutive batches of this wave
+    auto load_batch = [&](uint4 (&B)[RW][U], int kt_abs, int kt_end) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int kt = wkid + u * WK;
+            const int kt = kt_abs + u * WK;
 #pragma unroll
             for (int r = 0; r < RW; ++r)
-                A[r][u] = (valid[r] && kt < nkt0) ? *(const uint4*)(wbase[r] + (size_t)kt * kTileBytes)
-                                                  : make_uint4(0, 0, 0, 0);
+                B[r][u] = (valid[r] && kt < kt_end) ? *(const uint4*)(wbase[r] + (size_t)kt * kTileBytes)
+                                                    : make_uint4(0, 0, 0, 0);
         }
-    }
+    };
+    load_batch(B0, wkid, min(KC, K) / KT);
     float4 old[RW][2];
 #pragma unroll
     for (int r = 0; r < RW; ++r)
@@ -158,9 +183,20 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
         for (int nt = 0; nt < 2; ++nt) {
             old[r][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
             const int t = nt * 16 + tok_l;
-            if (a.epi == EPI_RESID && owner && valid[r] && t < T)
+            if (EPI == EPI_RESID && owner && valid[r] && t < T)
                 old[r][nt] = *(const float4*)(a.out + (size_t)t * a.ldo + (tile0 + r) * 16 + kq * 4);
         }
+
+    const int pos0 = (a.pos_ptr ? *a.pos_ptr : 0) + a.pos_add;
+    int tgt[2] = {-1, -1};
+    if (EPI == EPI_LMHEAD) {
+        const int ylen = *a.ylen_ptr;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const int ti = pos0 + nt * 16 + tok_l + 1;
+            if (nt * 16 + tok_l < T && ti < ylen) tgt[nt] = a.y[ti];
+        }
+    }
 
     for (int i = tid; i < NWV * 32; i += nthr) ssq[i] = 0.f;
 
@@ -177,13 +213,12 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
             if (nt < NT) {
-                const int t = nt * 16 + tok_l;
+                // rows past T read a valid row instead: an MFMA column only feeds its own output column,
+                // and those columns are never stored
+                const int t = min(nt * 16 + tok_l, T - 1);
                 if (DT) {
-                    uint4 bh = make_uint4(0, 0, 0, 0), bl = make_uint4(0, 0, 0, 0);
-                    if (t < T) {
-                        bh = *(const uint4*)(xs_hi + t * rstride + (ktl * 32 + kq * 8) * 2);
-                        bl = *(const uint4*)(xs_lo + t * rstride + (ktl * 32 + kq * 8) * 2);
-                    }
+                    const uint4 bh = *(const uint4*)(xs_hi + t * rstride + (ktl * 32 + kq * 8) * 2);
+                    const uint4 bl = *(const uint4*)(xs_lo + t * rstride + (ktl * 32 + kq * 8) * 2);
                     const bf16x8 Bh = __builtin_bit_cast(bf16x8, bh), Bl = __builtin_bit_cast(bf16x8, bl);
 #pragma unroll
                     for (int r = 0; r < RW; ++r) {
@@ -192,8 +227,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
                         acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bl, acc[r][nt], 0, 0, 0);
                     }
                 } else {
-                    float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (t < T) b = *(const float4*)(xs_hi + t * rstride + (ktl * 16 + kq * 4) * 4);
+                    const float4 b = *(const float4*)(xs_hi + t * rstride + (ktl * 16 + kq * 4) * 4);
                     const float bb[4] = {b.x, b.y, b.z, b.w};
 #pragma unroll
                     for (int r = 0; r < RW; ++r) {
@@ -208,6 +242,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
         }
     };
 
+    int par = 0;  // which register buffer holds the batch to consume next
     for (int k0 = 0; k0 < K; k0 += KC) {
         const int kc_len = min(KC, K - k0);
         if (k0) __syncthreads();  // readers of the previous chunk are done
@@ -218,6 +253,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
             if (t < T) {
                 const float* xr = a.x + (size_t)t * a.ldx + k0;
                 const int start = few ? tid : lane, step = few ? nthr : 64;
+#pragma unroll 4
                 for (int k4 = start; k4 < (kc_len >> 2); k4 += step) {
                     float4 v = *(const float4*)(xr + k4 * 4);
                     if (norm) {
@@ -237,50 +273,55 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
                 }
             }
         }
+        STAMP(1);
         __syncthreads();
-        // ---- this wave's weight tiles of the chunk, U per batch ----
+        STAMP(2);
+        // ---- this wave's weight tiles of the chunk: compute one batch while the next one loads ----
         const int kt_base = k0 / KT, nkt = kc_len / KT;
-        int kt = wkid;
-        if (k0 == 0) {  // the batch fetched at kernel entry
+        const int kn_base = (k0 + KC) / KT, nkt_next = (k0 + KC < K) ? min(KC, K - k0 - KC) / KT : 0;
+        auto compute_batch = [&](uint4 (&B)[RW][U], int kt) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (kt + u * WK < nkt) {
                     uint4 At[RW];
 #pragma unroll
-                    for (int r = 0; r < RW; ++r) At[r] = A[r][u];
+                    for (int r = 0; r < RW; ++r) At[r] = B[r][u];
                     compute(At, kt + u * WK);
                 }
             }
-            kt += U * WK;
-        }
-        for (; kt < nkt; kt += U * WK) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int k1 = kt + u * WK;
-#pragma unroll
-                for (int r = 0; r < RW; ++r)
-                    A[r][u] = (valid[r] && k1 < nkt) ? *(const uint4*)(wbase[r] + (size_t)(kt_base + k1) * kTileBytes)
-                                                     : make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (kt + u * WK < nkt) {
-                    uint4 At[RW];
-#pragma unroll
-                    for (int r = 0; r < RW; ++r) At[r] = A[r][u];
-                    compute(At, kt + u * WK);
-                }
+        };
+        // the batch for kt = wkid is already in flight (kernel entry, or the end of the previous chunk)
+        for (int kt = wkid; kt < nkt; kt += 2 * S) {
+            if (par == 0) {
+                if (kt + S < nkt) load_batch(B1, kt_base + kt + S, kt_base + nkt);
+                else if (nkt_next) load_batch(B1, kn_base + wkid, kn_base + nkt_next);
+                compute_batch(B0, kt);
+                if (kt + S >= nkt) { par = 1; break; }
+                if (kt + 2 * S < nkt) load_batch(B0, kt_base + kt + 2 * S, kt_base + nkt);
+                else if (nkt_next) load_batch(B0, kn_base + wkid, kn_base + nkt_next);
+                compute_batch(B1, kt + S);
+            } else {
+                if (kt + S < nkt) load_batch(B0, kt_base + kt + S, kt_base + nkt);
+                else if (nkt_next) load_batch(B0, kn_base + wkid, kn_base + nkt_next);
+                compute_batch(B1, kt);
+                if (kt + S >= nkt) { par = 0; break; }
+                if (kt + 2 * S < nkt) load_batch(B1, kt_base + kt + 2 * S, kt_base + nkt);
+                else if (nkt_next) load_batch(B1, kn_base + wkid, kn_base + nkt_next);
+                compute_batch(B0, kt + S);
             }
         }
     }
 
+    STAMP(3);
     // ---- RMSNorm row scales and cross-wave k reduction ----
     if (norm) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int t = few ? j : wave + NWV * j;
-            const float v = wave_sum(ss[j]);
-            if (t < T && lane == 0) ssq[wave * 32 + t] = v;
+            if (t < T) {  // wave-uniform
+                const float v = wave_sum(ss[j]);
+                if (lane == 0) ssq[wave * 32 + t] = v;
+            }
         }
     }
     if (WK > 1 && !owner) {
@@ -291,30 +332,38 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
                 if (j < NT) red[(wave * nacc + r * NT + j) * 64 + lane] = acc[r][j];
     }
     __syncthreads();
-    if (tid < T) {
-        float sum = 0.f;
-        for (int w = 0; w < NWV; ++w) sum += ssq[w * 32 + tid];
-        rs[tid] = norm ? rsqrtf(sum / (float)K + a.eps) : 1.f;
-    }
-    if (WK > 1 && owner) {
-        for (int w2 = 1; w2 < WK; ++w2)
+    float rsc[2] = {1.f, 1.f};  // 1/rms of this lane's rows
+    if (owner) {
+        if (norm) {
 #pragma unroll
-            for (int r = 0; r < RW; ++r)
+            for (int nt = 0; nt < 2; ++nt) {
+                if (nt < NT) {
+                    const int t = min(nt * 16 + tok_l, T - 1);
+                    float sum = 0.f;
+                    for (int w = 0; w < NWV; ++w) sum += ssq[w * 32 + t];
+                    rsc[nt] = rsqrtf(sum / (float)K + a.eps);
+                }
+            }
+        }
+        if (WK > 1) {
+            for (int w2 = 1; w2 < WK; ++w2)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    if (j < NT) acc[r][j] += red[((wave + w2) * nacc + r * NT + j) * 64 + lane];
+                for (int r = 0; r < RW; ++r)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        if (j < NT) acc[r][j] += red[((wave + w2) * nacc + r * NT + j) * 64 + lane];
+        }
     }
-    __syncthreads();
 
+    STAMP(4);
     // ---- epilogue: lane holds features f = tile*16 + kq*4 + v for row t = nt*16 + tok_l ----
-    const int pos0 = (a.pos_ptr ? *a.pos_ptr : 0) + a.pos_add;
     Stat st[2] = {stat_neutral(), stat_neutral()};
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
         const int t = nt * 16 + tok_l;
         if (nt >= NT || t >= T || !owner) continue;
-        const float r = rs[t];
-        if (RW == 2 && a.epi == EPI_ACT) {  // gated FFN: tile0 holds the gate, tile0+1 the linear branch
+        const float r = rsc[nt];
+        if (RW == 2 && EPI == EPI_ACT) {  // gated FFN: tile0 holds the gate, tile0+1 the linear branch
             if (valid[0] && valid[RW - 1]) {
                 const int f0 = (tile0 >> 1) * 16 + kq * 4;
                 float o[4];
@@ -332,7 +381,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
             if (!valid[rwi]) continue;
             const int n0 = (tile0 + rwi) * 16 + kq * 4;
             float v4[4] = {acc[rwi][nt][0] * r, acc[rwi][nt][1] * r, acc[rwi][nt][2] * r, acc[rwi][nt][3] * r};
-            switch (a.epi) {
+            switch (EPI) {
                 case EPI_STORE:
                     *(float4*)(a.out + (size_t)t * a.ldo + n0) = make_float4(v4[0], v4[1], v4[2], v4[3]);
                     break;
@@ -349,7 +398,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
                     const int pos = pos0 + t;
                     const int seg = n0 < a.q_dim ? 0 : (n0 < a.q_dim + a.i_dim ? 1 : 2);
                     const int nn = n0 - (seg == 0 ? 0 : (seg == 1 ? a.q_dim : a.q_dim + a.i_dim));
-                    if (a.rope && seg < 2) {
+                    if (ROPE && seg < 2) {
                         const int hd = nn % a.d_head;
 #pragma unroll
                         for (int p2 = 0; p2 < 2; ++p2) {
@@ -383,15 +432,13 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
                 } break;
                 case EPI_LMHEAD: {
                     const int row = a.row_off + t;
-                    const int ti = pos0 + t + 1;
-                    const int tgt = (ti < *a.ylen_ptr) ? a.y[ti] : -1;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int n = n0 + v;
                         if (n < a.vocab) {
                             const float z = v4[v] * a.scale;
                             stat_push(st[nt], z, n);
-                            if (n == tgt) a.zt[row] = z;
+                            if (n == tgt[nt]) a.zt[row] = z;
                             if (a.dbg) a.dbg[(size_t)row * a.vocab + n] = z;
                         }
                     }
@@ -399,7 +446,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
             }
         }
     }
-    if (a.epi == EPI_LMHEAD) {
+    if (EPI == EPI_LMHEAD) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
             st[nt] = stat_merge(st[nt], stat_shfl_xor(st[nt], 16));
@@ -423,6 +470,8 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
             a.part[(size_t)blockIdx.x * kMaxRows + a.row_off + tid] = o;
         }
     }
+    STAMP(5);
+#undef STAMP
 }
 
 void gemm_pick_shape(GemmArgs& a, int dtype) {
@@ -430,16 +479,21 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     const bool gated = a.epi == EPI_ACT && a.act != BILD_ACT_RELU;
     a.rw = gated ? 2 : 1;
     const int nacc = a.rw * ((a.T + 15) / 16);
-    int kc = 16384 / a.T - 8;
-    kc = (kc / 128) * 128;
-    if (kc < 128) kc = 128;
-    if (kc > a.W.k) kc = a.W.k;
+    // input chunks staged in LDS: at most 64 KiB, balanced so that every chunk has the same tile count +-1
+    int kc_max = 16384 / a.T - 8;
+    kc_max = std::max(128, (kc_max / 128) * 128);
+    const int nch = (a.W.k + kc_max - 1) / kc_max;
+    int kc = ((a.W.k + nch - 1) / nch + kt - 1) / kt * kt;
     a.kc = kc;
-    // input slices: about 8 tiles (one batch of loads) per wave
-    const int tiles_chunk = kc / kt;
+    const int tiles_last = (a.W.k - (nch - 1) * kc) / kt;
+    const int tiles_chunk = std::min(kc / kt, tiles_last);
+    // input slices: small matrices are latency bound -> about one batch (8 tiles) per wave;
+    // large ones are bandwidth bound -> about 4096 waves in all, each streaming a long run
+    const long total_tiles = (long)a.W.tn * a.W.tk;
+    const int per_wave = (int)std::max<long>(8, (total_tiles / 4096 + 7) / 8 * 8);
     int wk = 1;
-    while (wk < 8 && tiles_chunk / wk > 8) wk *= 2;
-    while (wk > 1 && wk * nacc > 32) wk /= 2;  // bound the LDS reduction area
+    while (wk < 8 && a.W.tk / wk > per_wave) wk *= 2;
+    while (wk > 1 && (wk * nacc > 32 || wk > tiles_chunk)) wk /= 2;
     // feature groups: as many as keep >= 512 workgroups, at least 4 waves per workgroup
     int wr = std::max(1, 4 / wk);
     for (int c = wr * 2; c * wk <= 8 && c * wk * nacc <= 32; c *= 2)
@@ -460,11 +514,16 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a);
 static hipError_t raise_lds_limits() {
     static hipError_t done = [] {
         const int lim = 128 * 1024;
-        const void* fns[] = {(const void*)gemm_kernel<0, 1>, (const void*)gemm_kernel<0, 2>,
-                             (const void*)gemm_kernel<1, 1>, (const void*)gemm_kernel<1, 2>,
+#define BILD_G(DTV) \
+    (const void*)gemm_kernel<DTV, 1, EPI_STORE, 0>, (const void*)gemm_kernel<DTV, 1, EPI_RESID, 0>, \
+    (const void*)gemm_kernel<DTV, 1, EPI_QKV, 0>, (const void*)gemm_kernel<DTV, 1, EPI_QKV, 1>, \
+    (const void*)gemm_kernel<DTV, 1, EPI_ACT, 0>, (const void*)gemm_kernel<DTV, 2, EPI_ACT, 0>, \
+    (const void*)gemm_kernel<DTV, 1, EPI_LMHEAD, 0>
+        const void* fns[] = {BILD_G(0), BILD_G(1),
                              (const void*)attn_kernel<0, 1>, (const void*)attn_kernel<0, 2>,
                              (const void*)attn_kernel<0, 4>, (const void*)attn_kernel<1, 1>,
                              (const void*)attn_kernel<1, 2>, (const void*)attn_kernel<1, 4>};
+#undef BILD_G
         for (const void* f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
             if (e != hipSuccess) return e;
@@ -474,22 +533,30 @@ static hipError_t raise_lds_limits() {
     return done;
 }
 
+hipError_t kernels_init() { return raise_lds_limits(); }
+
 hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
     const int nacc = a.rw * ((a.T + 15) / 16);
     const size_t smem = (size_t)xs_bytes(dtype, a.kc, a.T) + gemm_tail_bytes(a.nwv, nacc);
     const dim3 grid((unsigned)gemm_num_blocks(a)), block(64 * a.nwv);
-    if (dtype) {
-        if (a.rw == 2)
-            hipLaunchKernelGGL((gemm_kernel<1, 2>), grid, block, smem, st, a);
-        else
-            hipLaunchKernelGGL((gemm_kernel<1, 1>), grid, block, smem, st, a);
-    } else {
-        if (a.rw == 2)
-            hipLaunchKernelGGL((gemm_kernel<0, 2>), grid, block, smem, st, a);
-        else
-            hipLaunchKernelGGL((gemm_kernel<0, 1>), grid, block, smem, st, a);
+#define BILD_L(DTV, RWV, EPIV, ROPEV) hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a)
+#define BILD_D(DTV)                                                              \
+    switch (a.epi) {                                                             \
+        case EPI_STORE: BILD_L(DTV, 1, EPI_STORE, 0); break;                     \
+        case EPI_RESID: BILD_L(DTV, 1, EPI_RESID, 0); break;                     \
+        case EPI_QKV:                                                            \
+            if (a.rope) BILD_L(DTV, 1, EPI_QKV, 1); else BILD_L(DTV, 1, EPI_QKV, 0); \
+            break;                                                               \
+        case EPI_ACT:                                                            \
+            if (a.rw == 2) BILD_L(DTV, 2, EPI_ACT, 0); else BILD_L(DTV, 1, EPI_ACT, 0); \
+            break;                                                               \
+        case EPI_LMHEAD: BILD_L(DTV, 1, EPI_LMHEAD, 0); break;                   \
+        default: return hipErrorInvalidValue;                                    \
     }
+    if (dtype) { BILD_D(1) } else { BILD_D(0) }
+#undef BILD_D
+#undef BILD_L
     return hipGetLastError();
 }
 
@@ -826,71 +893,83 @@ hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st) {
 __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
     __shared__ float rm[kMaxRows], rsum[kMaxRows];
     __shared__ int ridx[kMaxRows];
+    __shared__ StatPart wpart[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Ctl* c = a.ctl;
     if (a.mode != 3) {
-        for (int t = wave; t < a.T; t += 4) {
+        for (int t = 0; t < a.T; ++t) {  // all 256 threads share each row's partials
             Stat r = stat_neutral();
-            for (int p = lane; p < a.nparts; p += 64) {
+            for (int p = tid; p < a.nparts; p += 256) {
                 const StatPart sp = a.part[(size_t)p * kMaxRows + a.row_off + t];
                 r = stat_merge(r, Stat{sp.m, sp.s, sp.idx});
             }
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) r = stat_merge(r, stat_shfl_xor(r, o));
-            if (lane == 0) {
-                rm[t] = r.m;
-                rsum[t] = r.s;
-                ridx[t] = r.idx;
+            if (lane == 0) wpart[wave] = StatPart{r.m, r.s, r.idx, 0};
+            __syncthreads();
+            if (tid == 0) {
+                Stat f = stat_neutral();
+                for (int w = 0; w < 4; ++w) f = stat_merge(f, Stat{wpart[w].m, wpart[w].s, wpart[w].idx});
+                rm[t] = f.m;
+                rsum[t] = f.s;
+                ridx[t] = f.idx;
+            }
+            __syncthreads();
+        }
+    }
+    if (tid == 0) {
+        const int w = a.which;
+        const int y_len = c->y_len, ds = c->draft_start, n_max = c->n_max;
+        if (a.mode == 3) {
+            c->len[w] += a.rows_consumed;
+        } else {
+            for (int t = 0; t < a.T; ++t) c->res_rowtok[t] = ridx[t];
+            if (a.mode == 0 || a.mode == 2) {
+                const int tok = ridx[a.T - 1];
+                const float pmax = 1.f / rsum[a.T - 1];
+                const bool low = (a.mode == 0) && (pmax < c->alpha_fb);
+                const bool forced = (a.mode == 0) && n_max > 0 && (y_len - ds) >= n_max;
+                const bool fb = low || forced;
+                c->len[w] += a.rows_consumed;
+                if (!fb && y_len < a.y_cap) {
+                    a.y[y_len] = tok;
+                    c->y_len = y_len + 1;
+                    if (a.mode == 2) c->draft_start = y_len + 1;
+                }
+                c->res_tok = tok;
+                c->res_flag = (fb ? 1 : 0) | ((forced && !low) ? 2 : 0);
+                c->res_pmax = pmax;
+            } else if (a.mode == 1) {  // review of n = T - 1 drafts
+                const int n = a.T - 1;
+                const float alpha = c->alpha_rb;
+                int r = n;
+                for (int i = 0; i < n; ++i) {
+                    const float nll = (rm[i] + logf(rsum[i])) - a.zt[a.row_off + i];
+                    c->res_nll[i] = nll;
+                    if (r == n && nll > alpha) r = i;
+                }
+                const int tok = ridx[r];
+                a.y[ds + r] = tok;
+                c->y_len = ds + r + 1;
+                c->len[1] = ds + r;
+                c->len[0] = min(c->len[0], ds + r);
+                c->draft_start = ds + r + 1;
+                c->res_r = r;
+                c->res_n = n;
+                c->res_tok = tok;
+                c->res_pmax = 1.f / rsum[r];
+                c->res_flag = 0;
             }
         }
+        __threadfence();
     }
     __syncthreads();
-    if (tid != 0) return;
-    const int w = a.which;
-    if (a.mode == 3) {
-        c->len[w] += a.rows_consumed;
-        return;
+    // mirror the control block into pinned host memory for the caller
+    if (a.host_mirror) {
+        const int words = sizeof(Ctl) / 4;
+        for (int i = tid; i < words; i += 256)
+            ((volatile int*)a.host_mirror)[i] = __hip_atomic_load((int*)c + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    for (int t = 0; t < a.T; ++t) c->res_rowtok[t] = ridx[t];
-    if (a.mode == 4) return;
-    if (a.mode == 0 || a.mode == 2) {
-        const int tok = ridx[a.T - 1];
-        const float pmax = 1.f / rsum[a.T - 1];
-        const int pending = c->y_len - c->draft_start;
-        const bool low = (a.mode == 0) && (pmax < a.alpha);
-        const bool forced = (a.mode == 0) && c->n_max > 0 && pending >= c->n_max;
-        const bool fb = low || forced;
-        c->len[w] += a.rows_consumed;
-        if (!fb && c->y_len < a.y_cap) {
-            a.y[c->y_len] = tok;
-            c->y_len += 1;
-            if (a.mode == 2) c->draft_start = c->y_len;
-        }
-        c->res_tok = tok;
-        c->res_flag = (fb ? 1 : 0) | ((forced && !low) ? 2 : 0);
-        c->res_pmax = pmax;
-        return;
-    }
-    // review of n = T - 1 drafts
-    const int n = a.T - 1;
-    int r = n;
-    for (int i = 0; i < n; ++i) {
-        const float nll = (rm[i] + logf(rsum[i])) - a.zt[a.row_off + i];
-        c->res_nll[i] = nll;
-        if (r == n && nll > a.alpha) r = i;
-    }
-    const int tok = ridx[r];
-    const int ds = c->draft_start;
-    a.y[ds + r] = tok;
-    c->y_len = ds + r + 1;
-    c->len[1] = c->y_len - 1;
-    c->len[0] = min(c->len[0], c->y_len - 1);
-    c->draft_start = c->y_len;
-    c->res_r = r;
-    c->res_n = n;
-    c->res_tok = tok;
-    c->res_pmax = 1.f / rsum[r];
-    c->res_flag = 0;
 }
 
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st) {
