@@ -226,3 +226,41 @@ def test_tiny_config_full_parity():
         ref = oracle.bild_generate(R.req, fb, rb, cfg.n_max, cfg.max_new)
         toks, stats = st.generate(R.src, fb, rb, cfg.max_new)
         parity.compare_generation(toks, stats, ref, fb, rb)
+
+
+# ---------------------------------------------------------------------------------------------
+# Full-size configurations, in the launch configuration bench.py times.  The oracle runs the same
+# request end to end (it finishes in about a minute per configuration on the host cores).
+def _full_size(cfg, max_new, n_src=None, compact=False, thresholds=None):
+    R = Rig(cfg, n_src=n_src, compact=compact)
+    fb, rb = thresholds or (cfg.alpha_fb, cfg.alpha_rb)
+    ref = oracle.bild_generate(R.req, fb, rb, cfg.n_max, max_new, keep_logits=True)
+    st = R.state(max_new, cfg.n_max)
+    st.encode(R.src)
+    worst = parity.teacher_forced(st, ref, R.n0, fb, rb, cfg)
+    print(cfg.name, "teacher-forced", worst, ref.stats, flush=True)
+    for rec in ref.trace:
+        rec.pop("z", None)
+    toks, stats = st.generate(R.src, fb, rb, max_new)
+    res = parity.compare_generation(toks, stats, ref, fb, rb)
+    print(cfg.name, "free-running", res, stats, flush=True)
+    return R, st
+
+
+@pytest.mark.timeout(900)
+def test_t5_config_full_size():
+    """Config 2: T5-small + T5-large shapes, bf16, 512 source tokens, 64 new tokens."""
+    cfg = bi.t5_pair()
+    R, st = _full_size(cfg, cfg.max_new)
+    # the other thresholds of the sweep, free-running
+    for fb, rb in ((0.3, 1.0), (0.7, 4.0)):
+        ref = oracle.bild_generate(R.req, fb, rb, cfg.n_max, 32)
+        toks, stats = st.generate(R.src, fb, rb, 32)
+        print("t5", fb, rb, parity.compare_generation(toks, stats, ref, fb, rb), stats, flush=True)
+
+
+@pytest.mark.timeout(900)
+def test_mt5_config_full_size():
+    """Config 3: mT5 shapes, 250k vocabulary (the LM head dominates), gated-GELU, 6 heads of the small model."""
+    cfg = bi.mt5_pair()
+    _full_size(cfg, 32)
