@@ -6,8 +6,8 @@ request of the chosen synthetic pair, with the source already encoded and all
 weights resident in HBM.  Prints one JSON line:
   value        generated tokens / second of the BiLD loop (batch 1)
   roofline     the weight-streaming GEMM kernel: algorithmic weight bytes per
-               launch / mean launch duration (HIP events on the library's
-               stream, taken in a second run of the same K steps), vs 8 TB/s
+               launch / mean launch duration (its launches replayed alone between
+               two HIP events on the library's stream), vs 8 TB/s
   cpu_baseline the CPU oracle timed on this host on the same workload
 plus per-pass achieved GB/s (algorithmic bytes of one decoder pass / its time),
 large-model-only greedy tokens/s and the BiLD-vs-large-only speedup.
@@ -112,22 +112,26 @@ def main() -> int:
                             gbs=round(nbytes / ms / 1e6, 1), frac_of_peak=round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4))
         log(f"[bench] {name}: {passes[name]}")
 
-    # roofline of the dominant kernel: same K steps again with every GEMM launch bracketed by HIP events
-    st.profile_begin(1 << 18)
-    for _ in range(args.steps):
-        one_step()
-    prof = st.profile_end()
-    tot_l = sum(prof[k]["launches"] for k in prof if k != "dropped")
-    tot_b = sum(prof[k]["bytes"] for k in prof if k != "dropped")
-    tot_ms = sum(prof[k]["ms"] for k in prof if k != "dropped")
-    achieved = tot_b / tot_ms / 1e6 if tot_ms > 0 else 0.0
-    roofline = dict(bound="hbm", kernel="gemm_kernel<bf16>" if cfg.large.dtype == bi.DT_BF16 else "gemm_kernel<f32>",
+    # Roofline of the dominant kernel (the weight-streaming GEMM): its launches replayed alone, in pass
+    # order and from the same captured graphs, between two HIP events on the library's stream; weighted by
+    # the pass mix of the timed BiLD steps (small passes of 1 row, large passes of the mean review length).
+    rows_l = max(1, round(stats["rows_verified"] / max(stats["large_calls"], 1)))
+    g_s = st.bench_gemm(pkg.SMALL, 1, 50)
+    g_l = st.bench_gemm(pkg.LARGE, rows_l, 50)
+    n_s, n_l = stats["small_steps"], stats["large_calls"]
+    tot_l = n_s * g_s["launches"] + n_l * g_l["launches"]
+    tot_b = n_s * g_s["bytes"] + n_l * g_l["bytes"]
+    tot_ms = n_s * g_s["ms_per_pass"] + n_l * g_l["ms_per_pass"]
+    achieved = tot_b / tot_ms / 1e6
+    roofline = dict(bound="hbm", kernel="bild::gemm_kernel<bf16,...>" if cfg.large.dtype == bi.DT_BF16 else "bild::gemm_kernel<f32,...>",
                     achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
-                    traffic=None, launches=tot_l, mean_launch_us=round(tot_ms / max(tot_l, 1) * 1e3, 3),
-                    mean_bytes_per_launch=int(tot_b / max(tot_l, 1)),
-                    by_class={k: dict(launches=v["launches"], gbs=round(v["bytes"] / v["ms"] / 1e6, 1) if v["ms"] else 0,
-                                      mean_us=round(v["ms"] / max(v["launches"], 1) * 1e3, 3))
-                              for k, v in prof.items() if k != "dropped"})
+                    traffic=None, launches_per_step=tot_l, mean_launch_us=round(tot_ms / tot_l * 1e3, 3),
+                    mean_bytes_per_launch=int(tot_b / tot_l),
+                    small_pass=dict(launches=g_s["launches"], us_per_launch=round(g_s["ms_per_pass"] / g_s["launches"] * 1e3, 3),
+                                    gbs=round(g_s["bytes"] / g_s["ms_per_pass"] / 1e6, 1)),
+                    large_pass=dict(rows=rows_l, launches=g_l["launches"],
+                                    us_per_launch=round(g_l["ms_per_pass"] / g_l["launches"] * 1e3, 3),
+                                    gbs=round(g_l["bytes"] / g_l["ms_per_pass"] / 1e6, 1)))
     log(f"[bench] roofline {roofline}")
 
     cpu = None

@@ -221,6 +221,13 @@ typedef struct bild_profile {
     int32_t dropped;        /* launches not recorded because max_records was reached */
 } bild_profile;
 int bild_bench_pass(bild_state* s, int which, int rows, int reps, float* ms_per_pass);
+/* Like bild_bench_pass, but each pass launches ONLY its weight-streaming GEMM kernels (the
+ * dominant kernel), back to back in pass order, so that ms_per_pass / launches is the mean
+ * duration of one GEMM launch (including the gap to the next launch) and bytes the
+ * algorithmic weight bytes the launches of one pass stream.  The activations the GEMMs read
+ * are stale; only the timing is meaningful. */
+int bild_bench_gemm(bild_state* s, int which, int rows, int reps, float* ms_per_pass, int64_t* launches,
+                    int64_t* bytes);
 int bild_profile_begin(bild_state* s, int max_records);
 int bild_profile_end(bild_state* s, bild_profile* out);
 

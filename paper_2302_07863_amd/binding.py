@@ -71,6 +71,8 @@ _SIGS = {
     "bild_debug_enable_logits": (C.c_int, [C.c_void_p, C.c_int]),
     "bild_debug_logits": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
     "bild_bench_pass": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float)]),
+    "bild_bench_gemm": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int64),
+                                  C.POINTER(C.c_int64)]),
     "bild_profile_begin": (C.c_int, [C.c_void_p, C.c_int]),
     "bild_profile_end": (C.c_int, [C.c_void_p, C.POINTER(Profile)]),
     "bild_pass_bytes": (C.c_int64, [C.c_void_p, C.c_int, C.c_int, C.c_int]),
@@ -242,6 +244,11 @@ class State:
         ms = C.c_float()
         _check(lib().bild_bench_pass(self.h, which, rows, reps, C.byref(ms)), "bild_bench_pass")
         return ms.value
+
+    def bench_gemm(self, which: int, rows: int, reps: int) -> dict:
+        ms, n, b = C.c_float(), C.c_int64(), C.c_int64()
+        _check(lib().bild_bench_gemm(self.h, which, rows, reps, C.byref(ms), C.byref(n), C.byref(b)), "bild_bench_gemm")
+        return dict(ms_per_pass=ms.value, launches=n.value, bytes=b.value)
 
     def profile_begin(self, max_records: int = 65536):
         _check(lib().bild_profile_begin(self.h, max_records), "bild_profile_begin")

@@ -90,6 +90,8 @@ struct bild_state {
     float* halpha = nullptr;  // pinned staging for threshold updates
     float alpha_fb = -1.f, alpha_rb = -1.f;  // thresholds currently in the device control block
     bool use_graphs = true;
+    bool gemm_only = false;       // measurement: a pass launches only its weight-streaming GEMMs
+    int64_t gemm_count = 0, gemm_bytes = 0;  // tallied while a pass is being issued
     std::map<std::array<int, 6>, hipGraphExec_t> graphs;  // captured passes by (model, rows, lm rows, mode, key bucket, debug)
     int* y = nullptr;     // device [max_len + 1]
     int* src = nullptr;   // device [max_src]
@@ -490,6 +492,8 @@ GemmArgs gemm_base(const bild_model* m, const TMat& W, const float* x, int ldx, 
 }
 
 int launch_gemm_profiled(bild_state* s, const bild_model* m, const GemmArgs& g) {
+    s->gemm_count += 1;
+    s->gemm_bytes += (int64_t)g.W.n * g.W.k * m->esz();
     if (!s->prof_on) {
         HIPC(launch_gemm(g, m->cfg.dtype, s->stream));
         return BILD_OK;
@@ -538,7 +542,7 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
     e.sinusoidal = c.pos == BILD_POS_SINUSOIDAL;
     e.embed_scale = c.embed_scale;
     e.x = M.x;
-    HIPC(launch_embed(e, dt, s->stream));
+    if (!s->gemm_only) HIPC(launch_embed(e, dt, s->stream));
     const float att_scale = 1.f / std::sqrt((float)c.d_head);
     for (int l = 0; l < c.n_dec_layers; ++l) {
         const LayerW& L = m->dec[l];
@@ -569,7 +573,7 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
             a.nw = pick_attn_waves(dt, c.d_head, T, key_hint, a.splits);
             a.part_o = M.att_o; a.part_ml = M.att_ml;
             a.scale = att_scale;
-            HIPC(launch_attention(a, dt, s->stream));
+            if (!s->gemm_only) HIPC(launch_attention(a, dt, s->stream));
         }
         {
             GemmArgs g = gemm_base(m, L.wo, M.a, I, T, nullptr);
@@ -603,7 +607,7 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
                 a.nw = pick_attn_waves(dt, c.d_head, T, s->n_src, a.splits);
                 a.part_o = M.att_o; a.part_ml = M.att_ml;
                 a.scale = att_scale;
-                HIPC(launch_attention(a, dt, s->stream));
+                if (!s->gemm_only) HIPC(launch_attention(a, dt, s->stream));
             }
             {
                 GemmArgs g = gemm_base(m, L.cwo, M.a, I, T, nullptr);
@@ -665,7 +669,7 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
     } else {
         f.mode = 3;
     }
-    HIPC(launch_finish(f, s->stream));
+    if (!s->gemm_only) HIPC(launch_finish(f, s->stream));
     return BILD_OK;
 }
 
@@ -682,7 +686,7 @@ int run_pass(bild_state* s, int w, int T, int lm_rows, int mode) {
     const int bucket = key_bucket(s->len[w] + T);
     if (lm_rows > 0) s->ms[w].last_rows = lm_rows;
     if (!s->use_graphs || s->prof_on || mode == 3) return decoder_pass(s, w, T, lm_rows, mode, bucket);
-    const std::array<int, 6> key = {w, T, lm_rows, mode, bucket, s->debug_logits ? 1 : 0};
+    const std::array<int, 6> key = {w, T, lm_rows, mode, bucket, (s->debug_logits ? 1 : 0) | (s->gemm_only ? 2 : 0)};
     auto it = s->graphs.find(key);
     if (it == s->graphs.end()) {
         hipGraph_t g = nullptr;
@@ -1101,6 +1105,41 @@ extern "C" int bild_bench_pass(bild_state* s, int which, int rows, int reps, flo
     for (int i = 0; i < reps && rc == BILD_OK; ++i) rc = run_pass(s, w, rows, rows, 4);
     if (rc == BILD_OK && hipEventRecord(e1, s->stream) != hipSuccess) rc = BILD_EHIP;
     if (rc == BILD_OK && hipEventSynchronize(e1) != hipSuccess) rc = BILD_EHIP;
+    float ms = 0.f;
+    if (rc == BILD_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = BILD_EHIP;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    *ms_per_pass = ms / (float)reps;
+    return BILD_OK;
+}
+
+extern "C" int bild_bench_gemm(bild_state* s, int which, int rows, int reps, float* ms_per_pass, int64_t* launches,
+                               int64_t* bytes) {
+    if (!s || !ms_per_pass || !launches || !bytes || which < 1 || which > 2 || rows < 1 || rows > kMaxRows || reps < 1)
+        return BILD_EINVAL;
+    if (!s->encoded) return BILD_ESTATE;
+    const int w = which - 1;
+    if (s->y_len - s->len[w] < rows) return BILD_ESTATE;
+    int rc = catch_up(s, w, s->y_len - rows);
+    if (rc) return rc;
+    hipEvent_t e0, e1;
+    HIPC(hipEventCreate(&e0));
+    HIPC(hipEventCreate(&e1));
+    s->gemm_only = true;
+    s->gemm_count = s->gemm_bytes = 0;
+    const bool graphs = s->use_graphs;
+    s->use_graphs = false;
+    rc = decoder_pass(s, w, rows, rows, 4, key_bucket(s->len[w] + rows));  // count the launches of one pass
+    s->use_graphs = graphs;
+    *launches = s->gemm_count;
+    *bytes = s->gemm_bytes;
+    if (rc == BILD_OK) rc = run_pass(s, w, rows, rows, 4);  // warm-up / capture
+    if (rc == BILD_OK && hipEventRecord(e0, s->stream) != hipSuccess) rc = BILD_EHIP;
+    for (int i = 0; i < reps && rc == BILD_OK; ++i) rc = run_pass(s, w, rows, rows, 4);
+    if (rc == BILD_OK && hipEventRecord(e1, s->stream) != hipSuccess) rc = BILD_EHIP;
+    if (rc == BILD_OK && hipEventSynchronize(e1) != hipSuccess) rc = BILD_EHIP;
+    s->gemm_only = false;
     float ms = 0.f;
     if (rc == BILD_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = BILD_EHIP;
     (void)hipEventDestroy(e0);

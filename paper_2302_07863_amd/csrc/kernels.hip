@@ -113,6 +113,9 @@ __device__ __forceinline__ float silu_f(float u) { return u / (1.f + expf(-u)); 
 //   rs[32]             per-row 1/rms
 //   wstat[nwv][32]     per-wave softmax partials (LM head)
 // =====================================================================================
+// weight tiles a wave loads per batch (split over its RW feature tiles); two batches are in flight
+__host__ __device__ constexpr int gemm_batch(int rw, int nt) { return (nt == 1 ? 12 : 8) / rw; }
+
 __host__ __device__ inline int xs_row_stride(int dt, int kc) { return dt ? (kc + 8) * 2 : (kc + 4) * 4; }
 __host__ __device__ inline int xs_bytes(int dt, int kc, int T) { return T * xs_row_stride(dt, kc) * (dt ? 2 : 1); }
 __host__ __device__ inline int gemm_red_bytes(int nwv, int nacc) { return nwv * nacc * 64 * 16; }
@@ -120,18 +123,17 @@ __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
     return gemm_red_bytes(nwv, nacc) + nwv * 32 * 4 + 32 * 4 + nwv * 32 * 16;
 }
 
-template <int DT, int RW, int EPI, int ROPE>
+template <int DT, int RW, int EPI, int ROPE, int NT>
 __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int KT = DT ? 32 : 16;
-    constexpr int U = RW == 1 ? 8 : 4;
+    constexpr int U = gemm_batch(RW, NT);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthr = blockDim.x, NWV = nthr >> 6;
     const int T = a.T, K = a.W.k, KC = a.kc;
     const int WK = a.wk, WR = NWV / WK;
     const int wkid = wave % WK, wrid = wave / WK;
     const int tile0 = ((int)blockIdx.x * WR + wrid) * RW;
-    const int NT = (T + 15) >> 4;
     const int nacc = RW * NT;
     const int rstride = xs_row_stride(DT, KC);
     char* xs_hi = smem;
@@ -150,7 +152,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
         valid[r] = tile0 + r < a.W.tn;
-        wbase[r] = (const char*)a.W.w + ((size_t)(tile0 + r) * a.W.tk) * kTileBytes + lane * 16;
+        wbase[r] = (const char*)a.W.w + ((size_t)min(tile0 + r, a.W.tn - 1) * a.W.tk) * kTileBytes + lane * 16;
     }
     const int tok_l = lane & 15, kq = lane >> 4;
 #ifdef BILD_TRACE
@@ -165,14 +167,20 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     // Two register buffers of U tiles each: while one is consumed the next batch is in flight.
     uint4 B0[RW][U], B1[RW][U];
     const int S = U * WK;  // tiles between consecutive batches of this wave
+    // Branch-free: a tile outside the wave's range is read from a clamped (valid) address and zeroed,
+    // and a zero tile adds nothing in the MFMA, so neither the loads nor the math need guards.
     auto load_batch = [&](uint4 (&B)[RW][U], int kt_abs, int kt_end) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int kt = kt_abs + u * WK;
+            const int ktc = min(kt, kt_end - 1);
 #pragma unroll
-            for (int r = 0; r < RW; ++r)
-                B[r][u] = (valid[r] && kt < kt_end) ? *(const uint4*)(wbase[r] + (size_t)kt * kTileBytes)
-                                                    : make_uint4(0, 0, 0, 0);
+            for (int r = 0; r < RW; ++r) {
+                uint4 v = *(const uint4*)(wbase[r] + (size_t)ktc * kTileBytes);
+                const bool ok = valid[r] && kt < kt_end;
+                v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
+                B[r][u] = v;
+            }
         }
     };
     load_batch(B0, wkid, min(KC, K) / KT);
@@ -198,21 +206,18 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
         }
     }
 
-    for (int i = tid; i < NWV * 32; i += nthr) ssq[i] = 0.f;
+    if (lane < 32) ssq[wave * 32 + lane] = 0.f;  // each wave owns (and later accumulates into) its own row
 
     f32x4 acc[RW][2];
 #pragma unroll
     for (int r = 0; r < RW; ++r)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float ss[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) ss[j] = 0.f;
 
     auto compute = [&](const uint4 (&At)[RW], int ktl) {
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            if (nt < NT) {
+        for (int nt = 0; nt < NT; ++nt) {
+            {
                 // rows past T read a valid row instead: an MFMA column only feeds its own output column,
                 // and those columns are never stored
                 const int t = min(nt * 16 + tok_l, T - 1);
@@ -242,35 +247,57 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
         }
     };
 
-    int par = 0;  // which register buffer holds the batch to consume next
     for (int k0 = 0; k0 < K; k0 += KC) {
         const int kc_len = min(KC, K - k0);
         if (k0) __syncthreads();  // readers of the previous chunk are done
         // ---- stage x[:, k0 : k0+kc_len] (times the norm gain) into LDS ----
-#pragma unroll
+        // few rows: every wave takes a k-slice of every row; otherwise whole rows are dealt to the waves
         for (int j = 0; j < 8; ++j) {
             const int t = few ? j : wave + NWV * j;
-            if (t < T) {
-                const float* xr = a.x + (size_t)t * a.ldx + k0;
-                const int start = few ? tid : lane, step = few ? nthr : 64;
-#pragma unroll 4
-                for (int k4 = start; k4 < (kc_len >> 2); k4 += step) {
-                    float4 v = *(const float4*)(xr + k4 * 4);
-                    if (norm) {
-                        ss[j] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-                        const float4 g = *(const float4*)(a.gain + k0 + k4 * 4);
-                        v.x *= g.x; v.y *= g.y; v.z *= g.z; v.w *= g.w;
-                    }
-                    if (DT) {
-                        const uint32_t h0 = f2bf(v.x), h1 = f2bf(v.y), h2 = f2bf(v.z), h3 = f2bf(v.w);
-                        const uint32_t l0 = f2bf(v.x - bf2f(h0)), l1 = f2bf(v.y - bf2f(h1));
-                        const uint32_t l2 = f2bf(v.z - bf2f(h2)), l3 = f2bf(v.w - bf2f(h3));
-                        *(uint2*)(xs_hi + t * rstride + k4 * 8) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-                        *(uint2*)(xs_lo + t * rstride + k4 * 8) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
-                    } else {
-                        *(float4*)(xs_hi + t * rstride + k4 * 16) = v;
-                    }
+            if (t >= T) break;  // wave-uniform
+            const float* xr = a.x + (size_t)t * a.ldx + k0;
+            const int start = few ? tid : lane, step = few ? nthr : 64;
+            const int n4 = kc_len >> 2;
+            float ssj = 0.f;
+            auto put = [&](int k4, float4 w, const float4& gg) {
+                if (norm) {
+                    ssj += w.x * w.x + w.y * w.y + w.z * w.z + w.w * w.w;
+                    w.x *= gg.x; w.y *= gg.y; w.z *= gg.z; w.w *= gg.w;
                 }
+                if (DT) {
+                    const uint32_t h0 = f2bf(w.x), h1 = f2bf(w.y), h2 = f2bf(w.z), h3 = f2bf(w.w);
+                    const uint32_t l0 = f2bf(w.x - bf2f(h0)), l1 = f2bf(w.y - bf2f(h1));
+                    const uint32_t l2 = f2bf(w.z - bf2f(h2)), l3 = f2bf(w.w - bf2f(h3));
+                    *(uint2*)(xs_hi + t * rstride + k4 * 8) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+                    *(uint2*)(xs_lo + t * rstride + k4 * 8) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+                } else {
+                    *(float4*)(xs_hi + t * rstride + k4 * 16) = w;
+                }
+            };
+            if (n4 <= 2 * step) {  // short rows: at most two elements per thread
+                const int ka = start, kb2 = start + step;
+                float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va, ga = va, gb = va;
+                if (ka < n4) { va = *(const float4*)(xr + ka * 4); if (norm) ga = *(const float4*)(a.gain + k0 + ka * 4); }
+                if (kb2 < n4) { vb = *(const float4*)(xr + kb2 * 4); if (norm) gb = *(const float4*)(a.gain + k0 + kb2 * 4); }
+                if (ka < n4) put(ka, va, ga);
+                if (kb2 < n4) put(kb2, vb, gb);
+            } else {
+                for (int kb = start; kb < n4; kb += step * 8) {
+                    float4 v[8], g[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {  // all loads of the round first
+                        const int k4 = min(kb + u * step, n4 - 1);
+                        v[u] = *(const float4*)(xr + k4 * 4);
+                        g[u] = norm ? *(const float4*)(a.gain + k0 + k4 * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (kb + u * step < n4) put(kb + u * step, v[u], g[u]);
+                }
+            }
+            if (norm) {  // this wave's share of sum x^2 of row t, accumulated over the chunks
+                const float tot = wave_sum(ssj);
+                if (lane == 0) ssq[wave * 32 + t] += tot;
             }
         }
         STAMP(1);
@@ -282,48 +309,39 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
         auto compute_batch = [&](uint4 (&B)[RW][U], int kt) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (kt + u * WK < nkt) {
-                    uint4 At[RW];
+                uint4 At[RW];
 #pragma unroll
-                    for (int r = 0; r < RW; ++r) At[r] = B[r][u];
-                    compute(At, kt + u * WK);
-                }
+                for (int r = 0; r < RW; ++r) At[r] = B[r][u];
+                compute(At, min(kt + u * WK, nkt - 1));  // a tile past the end is all zero
             }
         };
-        // the batch for kt = wkid is already in flight (kernel entry, or the end of the previous chunk)
-        for (int kt = wkid; kt < nkt; kt += 2 * S) {
-            if (par == 0) {
-                if (kt + S < nkt) load_batch(B1, kt_base + kt + S, kt_base + nkt);
-                else if (nkt_next) load_batch(B1, kn_base + wkid, kn_base + nkt_next);
+        // the batch for kt = wkid is already in flight in B0 (kernel entry, or the end of the previous chunk)
+        for (int kt = wkid;; kt += 2 * S) {
+            {
+                const bool in_chunk = kt + S < nkt;
+                if (in_chunk || nkt_next)
+                    load_batch(B1, in_chunk ? kt_base + kt + S : kn_base + wkid, in_chunk ? kt_base + nkt : kn_base + nkt_next);
                 compute_batch(B0, kt);
-                if (kt + S >= nkt) { par = 1; break; }
-                if (kt + 2 * S < nkt) load_batch(B0, kt_base + kt + 2 * S, kt_base + nkt);
-                else if (nkt_next) load_batch(B0, kn_base + wkid, kn_base + nkt_next);
+                if (!in_chunk) {  // the next chunk's first batch (if any) went to B1: hand it over
+#pragma unroll
+                    for (int r = 0; r < RW; ++r)
+#pragma unroll
+                        for (int u = 0; u < U; ++u) B0[r][u] = B1[r][u];
+                    break;
+                }
+            }
+            {
+                const bool in_chunk = kt + 2 * S < nkt;
+                if (in_chunk || nkt_next)
+                    load_batch(B0, in_chunk ? kt_base + kt + 2 * S : kn_base + wkid, in_chunk ? kt_base + nkt : kn_base + nkt_next);
                 compute_batch(B1, kt + S);
-            } else {
-                if (kt + S < nkt) load_batch(B0, kt_base + kt + S, kt_base + nkt);
-                else if (nkt_next) load_batch(B0, kn_base + wkid, kn_base + nkt_next);
-                compute_batch(B1, kt);
-                if (kt + S >= nkt) { par = 0; break; }
-                if (kt + 2 * S < nkt) load_batch(B1, kt_base + kt + 2 * S, kt_base + nkt);
-                else if (nkt_next) load_batch(B1, kn_base + wkid, kn_base + nkt_next);
-                compute_batch(B0, kt + S);
+                if (!in_chunk) break;  // the next chunk's first batch is already in B0
             }
         }
     }
 
     STAMP(3);
     // ---- RMSNorm row scales and cross-wave k reduction ----
-    if (norm) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int t = few ? j : wave + NWV * j;
-            if (t < T) {  // wave-uniform
-                const float v = wave_sum(ss[j]);
-                if (lane == 0) ssq[wave * 32 + t] = v;
-            }
-        }
-    }
     if (WK > 1 && !owner) {
 #pragma unroll
         for (int r = 0; r < RW; ++r)
@@ -480,17 +498,18 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     a.rw = gated ? 2 : 1;
     const int nacc = a.rw * ((a.T + 15) / 16);
     // input chunks staged in LDS: at most 64 KiB, balanced so that every chunk has the same tile count +-1
-    int kc_max = 16384 / a.T - 8;
+    int kc_max = 24576 / a.T - 8;  // up to 96 KiB of staged activations
     kc_max = std::max(128, (kc_max / 128) * 128);
     const int nch = (a.W.k + kc_max - 1) / kc_max;
     int kc = ((a.W.k + nch - 1) / nch + kt - 1) / kt * kt;
     a.kc = kc;
     const int tiles_last = (a.W.k - (nch - 1) * kc) / kt;
     const int tiles_chunk = std::min(kc / kt, tiles_last);
-    // input slices: small matrices are latency bound -> about one batch (8 tiles) per wave;
+    // input slices: small matrices are latency bound -> at most one batch of tiles per wave;
     // large ones are bandwidth bound -> about 4096 waves in all, each streaming a long run
     const long total_tiles = (long)a.W.tn * a.W.tk;
-    const int per_wave = (int)std::max<long>(8, (total_tiles / 4096 + 7) / 8 * 8);
+    const int batch = gemm_batch(a.rw, (a.T + 15) / 16);
+    const int per_wave = (int)std::max<long>(batch, (total_tiles / 4096 + batch - 1) / batch * batch);
     int wk = 1;
     while (wk < 8 && a.W.tk / wk > per_wave) wk *= 2;
     while (wk > 1 && (wk * nacc > 32 || wk > tiles_chunk)) wk /= 2;
@@ -514,15 +533,17 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a);
 static hipError_t raise_lds_limits() {
     static hipError_t done = [] {
         const int lim = 128 * 1024;
-#define BILD_G(DTV) \
-    (const void*)gemm_kernel<DTV, 1, EPI_STORE, 0>, (const void*)gemm_kernel<DTV, 1, EPI_RESID, 0>, \
-    (const void*)gemm_kernel<DTV, 1, EPI_QKV, 0>, (const void*)gemm_kernel<DTV, 1, EPI_QKV, 1>, \
-    (const void*)gemm_kernel<DTV, 1, EPI_ACT, 0>, (const void*)gemm_kernel<DTV, 2, EPI_ACT, 0>, \
-    (const void*)gemm_kernel<DTV, 1, EPI_LMHEAD, 0>
+#define BILD_G1(DTV, NTV) \
+    (const void*)gemm_kernel<DTV, 1, EPI_STORE, 0, NTV>, (const void*)gemm_kernel<DTV, 1, EPI_RESID, 0, NTV>, \
+    (const void*)gemm_kernel<DTV, 1, EPI_QKV, 0, NTV>, (const void*)gemm_kernel<DTV, 1, EPI_QKV, 1, NTV>, \
+    (const void*)gemm_kernel<DTV, 1, EPI_ACT, 0, NTV>, (const void*)gemm_kernel<DTV, 2, EPI_ACT, 0, NTV>, \
+    (const void*)gemm_kernel<DTV, 1, EPI_LMHEAD, 0, NTV>
+#define BILD_G(DTV) BILD_G1(DTV, 1), BILD_G1(DTV, 2)
         const void* fns[] = {BILD_G(0), BILD_G(1),
                              (const void*)attn_kernel<0, 1>, (const void*)attn_kernel<0, 2>,
                              (const void*)attn_kernel<0, 4>, (const void*)attn_kernel<1, 1>,
                              (const void*)attn_kernel<1, 2>, (const void*)attn_kernel<1, 4>};
+#undef BILD_G1
 #undef BILD_G
         for (const void* f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
@@ -540,7 +561,13 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     const int nacc = a.rw * ((a.T + 15) / 16);
     const size_t smem = (size_t)xs_bytes(dtype, a.kc, a.T) + gemm_tail_bytes(a.nwv, nacc);
     const dim3 grid((unsigned)gemm_num_blocks(a)), block(64 * a.nwv);
-#define BILD_L(DTV, RWV, EPIV, ROPEV) hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a)
+#define BILD_L(DTV, RWV, EPIV, ROPEV)                                                              \
+    do {                                                                                            \
+        if (a.T > 16)                                                                               \
+            hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 2>), grid, block, smem, st, a);  \
+        else                                                                                        \
+            hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 1>), grid, block, smem, st, a);  \
+    } while (0)
 #define BILD_D(DTV)                                                              \
     switch (a.epi) {                                                             \
         case EPI_STORE: BILD_L(DTV, 1, EPI_STORE, 0); break;                     \
@@ -600,25 +627,26 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
     const int bps = (nblk + a.splits - 1) / a.splits;
     const int blk_begin = min(nblk, sp * bps), blk_end = min(nblk, blk_begin + bps);
 
-    // ---- stage q * scale (zero padded to NT*16 rows x DHP dims) ----
-    for (int i = tid; i < NT * 16 * (DHP / 4); i += nthr) {
-        const int t = i / (DHP / 4), d4 = (i % (DHP / 4)) * 4;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (t < T && d4 < dh) {
-            v = *(const float4*)(a.q + (size_t)t * I + h * dh + d4);
-            v.x *= a.scale; v.y *= a.scale; v.z *= a.scale; v.w *= a.scale;
+    // ---- stage q * scale (zero padded to NT*16 rows x DHP dims); issued after the first K/V loads ----
+    auto stage_q = [&]() {
+        for (int i = tid; i < NT * 16 * (DHP / 4); i += nthr) {
+            const int t = i / (DHP / 4), d4 = (i % (DHP / 4)) * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (t < T && d4 < dh) {
+                v = *(const float4*)(a.q + (size_t)t * I + h * dh + d4);
+                v.x *= a.scale; v.y *= a.scale; v.z *= a.scale; v.w *= a.scale;
+            }
+            if (DT) {
+                const uint32_t h0 = f2bf(v.x), h1 = f2bf(v.y), h2 = f2bf(v.z), h3 = f2bf(v.w);
+                const uint32_t l0 = f2bf(v.x - bf2f(h0)), l1 = f2bf(v.y - bf2f(h1));
+                const uint32_t l2 = f2bf(v.z - bf2f(h2)), l3 = f2bf(v.w - bf2f(h3));
+                *(uint2*)(q_hi + t * qstride + d4 * 2) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+                *(uint2*)(q_lo + t * qstride + d4 * 2) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+            } else {
+                *(float4*)(q_hi + t * qstride + d4 * 4) = v;
+            }
         }
-        if (DT) {
-            const uint32_t h0 = f2bf(v.x), h1 = f2bf(v.y), h2 = f2bf(v.z), h3 = f2bf(v.w);
-            const uint32_t l0 = f2bf(v.x - bf2f(h0)), l1 = f2bf(v.y - bf2f(h1));
-            const uint32_t l2 = f2bf(v.z - bf2f(h2)), l3 = f2bf(v.w - bf2f(h3));
-            *(uint2*)(q_hi + t * qstride + d4 * 2) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-            *(uint2*)(q_lo + t * qstride + d4 * 2) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
-        } else {
-            *(float4*)(q_hi + t * qstride + d4 * 4) = v;
-        }
-    }
-    __syncthreads();
+    };
 
     float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
     f32x4 O[2][DT16];
@@ -628,11 +656,10 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
         for (int dt = 0; dt < DT16; ++dt) O[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const size_t esz = DT ? 2 : 4;
-    for (int blk = blk_begin + wave; blk < blk_end; blk += nw) {
+    constexpr int KN = DT ? DH32 : DH32 * 2, VN = DT ? 1 : 2;
+    auto load_kv = [&](uint4 (&Kr)[2][KN], uint4 (&Vr)[DT16][VN], int blk) {
         const int key0 = blk * 32;
         // ---- loads: K rows of both 16-key tiles, V^T columns of the same 32 keys ----
-        uint4 Kr[2][DT ? DH32 : DH32 * 2];
-        uint4 Vr[DT16][DT ? 1 : 2];
 #pragma unroll
         for (int ab = 0; ab < 2; ++ab) {
             const char* krow = (const char*)a.k + ((size_t)(key0 + ab * 16 + tok_l) * I + h * dh) * esz;
@@ -666,6 +693,9 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
                 Vr[dt][1] = d < dh ? *(const uint4*)(vrow + 16 * 4) : make_uint4(0, 0, 0, 0);
             }
         }
+    };
+    auto process = [&](uint4 (&Kr)[2][KN], uint4 (&Vr)[DT16][VN], int blk) {
+        const int key0 = blk * 32;
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
             if (nt >= NT) continue;
@@ -760,6 +790,29 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
                             O[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j], p[ab][j], O[nt][dt], 0, 0, 0);
                     }
                 }
+            }
+        }
+    };
+    // two register buffers: the next 32-key block loads while the current one is processed
+    {
+        uint4 K0[2][KN], V0[DT16][VN];
+        int blk = blk_begin + wave;
+        if (blk < blk_end) load_kv(K0, V0, blk);
+        stage_q();
+        __syncthreads();
+        if constexpr (DH32 <= 2) {
+            uint4 K1[2][KN], V1[DT16][VN];
+            for (; blk < blk_end; blk += 2 * nw) {
+                if (blk + nw < blk_end) load_kv(K1, V1, blk + nw);
+                process(K0, V0, blk);
+                if (blk + nw >= blk_end) break;
+                if (blk + 2 * nw < blk_end) load_kv(K0, V0, blk + 2 * nw);
+                process(K1, V1, blk + nw);
+            }
+        } else {  // 128-wide heads: one buffer, the registers are needed for the output tiles
+            for (; blk < blk_end; blk += nw) {
+                process(K0, V0, blk);
+                if (blk + nw < blk_end) load_kv(K0, V0, blk + nw);
             }
         }
     }
