@@ -38,6 +38,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="t5", choices=["tiny", "t5", "mt5", "llama"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="counter-collection run: one 1 GiB device copy of known size, then --steps BiLD steps; "
+                         "no timing, no JSON (run under rocprofv3 --pmc with BILD_NO_GRAPH=1)")
     ap.add_argument("--alpha-fb", type=float, default=None)
     ap.add_argument("--alpha-rb", type=float, default=None)
     args = ap.parse_args()
@@ -69,6 +72,16 @@ def main() -> int:
     t0 = time.perf_counter()
     st.encode(src)
     encode_ms = (time.perf_counter() - t0) * 1e3
+
+    if args.pmc_probe:
+        st.probe_copy(1 << 30, 3)          # bild::probe_copy_kernel: reads 1 GiB and writes 1 GiB per launch
+        for _ in range(args.steps):
+            st.seq_truncate(n0)
+            st.generate(None, fb, rb, cfg.max_new)
+        tally = st.gemm_tally()
+        log(f"[bench] pmc probe done: gemm launches issued {tally['launches']}, algorithmic weight bytes "
+            f"{tally['bytes']}, mean {tally['bytes'] / max(tally['launches'], 1):.0f} B/launch")
+        return 0
 
     def one_step():
         st.seq_truncate(n0)          # back to <s> / the prompt; caches cut to match
@@ -123,9 +136,16 @@ def main() -> int:
     tot_b = n_s * g_s["bytes"] + n_l * g_l["bytes"]
     tot_ms = n_s * g_s["ms_per_pass"] + n_l * g_l["ms_per_pass"]
     achieved = tot_b / tot_ms / 1e6
+    # HBM bytes per GEMM launch from hardware counters: taken from the committed rocprofv3 --pmc summary
+    traffic = None
+    pmc_file = os.path.join(ROOT, "profiles", f"gemm_{cfg.name}_pmc.txt")
+    if os.path.exists(pmc_file):
+        for line in open(pmc_file):
+            if line.startswith("traffic_bytes_per_launch="):
+                traffic = int(line.split("=")[1])
     roofline = dict(bound="hbm", kernel="bild::gemm_kernel<bf16,...>" if cfg.large.dtype == bi.DT_BF16 else "bild::gemm_kernel<f32,...>",
                     achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
-                    traffic=None, launches_per_step=tot_l, mean_launch_us=round(tot_ms / tot_l * 1e3, 3),
+                    traffic=traffic, launches_per_step=tot_l, mean_launch_us=round(tot_ms / tot_l * 1e3, 3),
                     mean_bytes_per_launch=int(tot_b / tot_l),
                     small_pass=dict(launches=g_s["launches"], us_per_launch=round(g_s["ms_per_pass"] / g_s["launches"] * 1e3, 3),
                                     gbs=round(g_s["bytes"] / g_s["ms_per_pass"] / 1e6, 1)),

@@ -228,6 +228,13 @@ int bild_bench_pass(bild_state* s, int which, int rows, int reps, float* ms_per_
  * are stale; only the timing is meaningful. */
 int bild_bench_gemm(bild_state* s, int which, int rows, int reps, float* ms_per_pass, int64_t* launches,
                     int64_t* bytes);
+/* Runs `reps` launches of a plain device-to-device copy kernel (bild::probe_copy_kernel) of
+ * `bytes` bytes (a multiple of 16) on temporary buffers: it reads `bytes` and writes `bytes`,
+ * the known quantity against which hardware byte counters are scaled. */
+int bild_probe_copy(bild_state* s, int64_t bytes, int reps);
+/* GEMM launches ISSUED by the host since the last reset and the algorithmic weight bytes they stream
+ * (replays of captured graphs are not counted: meaningful when graph replay is disabled). */
+int bild_gemm_tally(bild_state* s, int64_t* launches, int64_t* bytes, int reset);
 int bild_profile_begin(bild_state* s, int max_records);
 int bild_profile_end(bild_state* s, bild_profile* out);
 

@@ -73,6 +73,8 @@ _SIGS = {
     "bild_bench_pass": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float)]),
     "bild_bench_gemm": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int64),
                                   C.POINTER(C.c_int64)]),
+    "bild_gemm_tally": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_int]),
+    "bild_probe_copy": (C.c_int, [C.c_void_p, C.c_int64, C.c_int]),
     "bild_profile_begin": (C.c_int, [C.c_void_p, C.c_int]),
     "bild_profile_end": (C.c_int, [C.c_void_p, C.POINTER(Profile)]),
     "bild_pass_bytes": (C.c_int64, [C.c_void_p, C.c_int, C.c_int, C.c_int]),
@@ -249,6 +251,14 @@ class State:
         ms, n, b = C.c_float(), C.c_int64(), C.c_int64()
         _check(lib().bild_bench_gemm(self.h, which, rows, reps, C.byref(ms), C.byref(n), C.byref(b)), "bild_bench_gemm")
         return dict(ms_per_pass=ms.value, launches=n.value, bytes=b.value)
+
+    def gemm_tally(self, reset: bool = False) -> dict:
+        n, b = C.c_int64(), C.c_int64()
+        _check(lib().bild_gemm_tally(self.h, C.byref(n), C.byref(b), int(reset)), "bild_gemm_tally")
+        return dict(launches=n.value, bytes=b.value)
+
+    def probe_copy(self, nbytes: int, reps: int = 1):
+        _check(lib().bild_probe_copy(self.h, nbytes, reps), "bild_probe_copy")
 
     def profile_begin(self, max_records: int = 65536):
         _check(lib().bild_profile_begin(self.h, max_records), "bild_profile_begin")

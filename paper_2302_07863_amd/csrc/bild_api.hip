@@ -1149,6 +1149,32 @@ extern "C" int bild_bench_gemm(bild_state* s, int which, int rows, int reps, flo
     return BILD_OK;
 }
 
+extern "C" int bild_gemm_tally(bild_state* s, int64_t* launches, int64_t* bytes, int reset) {
+    if (!s || !launches || !bytes) return BILD_EINVAL;
+    *launches = s->gemm_count;
+    *bytes = s->gemm_bytes;
+    if (reset) s->gemm_count = s->gemm_bytes = 0;
+    return BILD_OK;
+}
+
+extern "C" int bild_probe_copy(bild_state* s, int64_t bytes, int reps) {
+    if (!s || bytes < 16 || bytes % 16 || reps < 1) return BILD_EINVAL;
+    void *a = nullptr, *b = nullptr;
+    if (hipMalloc(&a, (size_t)bytes) != hipSuccess) return BILD_ENOMEM;
+    if (hipMalloc(&b, (size_t)bytes) != hipSuccess) {
+        (void)hipFree(a);
+        return BILD_ENOMEM;
+    }
+    int rc = BILD_OK;
+    if (hipMemsetAsync(a, 1, (size_t)bytes, s->stream) != hipSuccess) rc = BILD_EHIP;
+    for (int i = 0; i < reps && rc == BILD_OK; ++i)
+        if (launch_probe_copy(a, b, (size_t)bytes, s->stream) != hipSuccess) rc = BILD_EHIP;
+    if (hipStreamSynchronize(s->stream) != hipSuccess) rc = BILD_EHIP;
+    (void)hipFree(a);
+    (void)hipFree(b);
+    return rc;
+}
+
 extern "C" int bild_profile_begin(bild_state* s, int max_records) {
     if (!s || max_records < 1 || max_records > (1 << 20)) return BILD_EINVAL;
     if (s->prof_on) return BILD_ESTATE;

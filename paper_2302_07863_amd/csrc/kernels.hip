@@ -1025,6 +1025,16 @@ __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
     }
 }
 
+// Plain copy of known size: the reference against which hardware byte counters are scaled.
+__global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st) {
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(4096), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, bytes / 16);
+    return hipGetLastError();
+}
+
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(256), 0, st, a);
     return hipGetLastError();

@@ -1,0 +1,72 @@
+"""Turns rocprofv3 CSV output into the short text summaries kept under profiles/.
+
+  python -m paper_2302_07863_amd.profsum stats  <kernel_stats.csv>
+  python -m paper_2302_07863_amd.profsum pmc    <fetch counter_collection.csv> <write counter_collection.csv>
+
+`stats` groups the template instantiations of one kernel under one name and prints calls,
+total and mean duration.  `pmc` scales FETCH_SIZE / WRITE_SIZE per dispatch by what the same
+counters read for bild::probe_copy_kernel, a plain copy of known size (1 GiB read, 1 GiB written).
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import re
+import sys
+
+PROBE_BYTES = 1 << 30
+
+
+def _group(name: str) -> str:
+    name = name.split("(")[0].replace("void ", "").strip()
+    return re.sub(r"<.*>$", "<*>", name)
+
+
+def stats(path: str) -> str:
+    agg = collections.defaultdict(lambda: [0, 0])
+    for r in csv.DictReader(open(path)):
+        g = agg[_group(r["Name"])]
+        g[0] += int(r["Calls"])
+        g[1] += int(r["TotalDurationNs"])
+    total = sum(v[1] for v in agg.values())
+    lines = [f"{'kernel':34s} {'calls':>8s} {'total_ms':>10s} {'mean_us':>9s} {'share':>7s}"]
+    for k, (n, t) in sorted(agg.items(), key=lambda kv: -kv[1][1]):
+        lines.append(f"{k:34s} {n:8d} {t / 1e6:10.2f} {t / n / 1e3:9.2f} {100.0 * t / total:6.1f}%")
+    return "\n".join(lines)
+
+
+def _pmc(path: str):
+    agg = collections.defaultdict(lambda: [0, 0.0])
+    for r in csv.DictReader(open(path)):
+        g = agg[_group(r["Kernel_Name"])]
+        g[0] += 1
+        g[1] += float(r["Counter_Value"])
+    return agg
+
+
+def pmc(fetch_path: str, write_path: str) -> str:
+    f, w = _pmc(fetch_path), _pmc(write_path)
+    probe = "bild::probe_copy_kernel"
+    sf = PROBE_BYTES / (f[probe][1] / f[probe][0])
+    sw = PROBE_BYTES / (w[probe][1] / w[probe][0])
+    lines = [f"scale: FETCH_SIZE count = {sf:.1f} B, WRITE_SIZE count = {sw:.1f} B "
+             f"(from {probe}: {PROBE_BYTES} B read and written per launch)",
+             f"{'kernel':34s} {'dispatches':>10s} {'fetch_B/launch':>15s} {'write_B/launch':>15s}"]
+    for k in sorted(f, key=lambda k: -f[k][1]):
+        n = f[k][0]
+        fb = f[k][1] / n * sf
+        wb = (w[k][1] / w[k][0] * sw) if k in w else 0.0
+        lines.append(f"{k:34s} {n:10d} {fb:15.0f} {wb:15.0f}")
+        if k.startswith("bild::gemm_kernel"):
+            lines.append(f"traffic_bytes_per_launch={fb + wb:.0f}")
+    return "\n".join(lines)
+
+
+if __name__ == "__main__":
+    if len(sys.argv) >= 3 and sys.argv[1] == "stats":
+        print(stats(sys.argv[2]))
+    elif len(sys.argv) >= 4 and sys.argv[1] == "pmc":
+        print(pmc(sys.argv[2], sys.argv[3]))
+    else:
+        print(__doc__)
+        sys.exit(2)
