@@ -191,7 +191,7 @@ CAL = {
     "tiny": (8.0, 8.0, 12.0),
     "t5": (2.0, 4.0, 36.0),
     "mt5": (2.0, 4.0, 36.0),
-    "llama": (2.0, 4.0, 36.0),
+    "llama": (0.9, 4.0, 50.0),
 }
 
 PAIRS = {"tiny": tiny_pair, "t5": t5_pair, "mt5": mt5_pair, "llama": llama_pair}

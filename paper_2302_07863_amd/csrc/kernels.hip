@@ -505,13 +505,14 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     a.kc = kc;
     const int tiles_last = (a.W.k - (nch - 1) * kc) / kt;
     const int tiles_chunk = std::min(kc / kt, tiles_last);
-    // input slices: small matrices are latency bound -> at most one batch of tiles per wave;
-    // large ones are bandwidth bound -> about 4096 waves in all, each streaming a long run
-    const long total_tiles = (long)a.W.tn * a.W.tk;
+    // input slices per workgroup.  Latency rule (small matrices): at most one batch of tiles per wave.
+    // Parallelism rule (large ones): no more slices than it takes to field about 1536 waves, so that a
+    // wave streams a long contiguous run (measured best on 32128x1024, 22016x4096 and 4096x11008).
     const int batch = gemm_batch(a.rw, (a.T + 15) / 16);
-    const int per_wave = (int)std::max<long>(batch, (total_tiles / 4096 + batch - 1) / batch * batch);
-    int wk = 1;
-    while (wk < 8 && a.W.tk / wk > per_wave) wk *= 2;
+    int wk_lat = 1, wk_par = 1;
+    while (wk_lat < 8 && a.W.tk / wk_lat > batch) wk_lat *= 2;
+    while (wk_par < 8 && (long)a.W.tn * wk_par < 1536) wk_par *= 2;
+    int wk = std::min(wk_lat, wk_par);
     while (wk > 1 && (wk * nacc > 32 || wk > tiles_chunk)) wk /= 2;
     // feature groups: as many as keep >= 512 workgroups, at least 4 waves per workgroup
     int wr = std::max(1, 4 / wk);

@@ -264,3 +264,104 @@ def test_mt5_config_full_size():
     """Config 3: mT5 shapes, 250k vocabulary (the LM head dominates), gated-GELU, 6 heads of the small model."""
     cfg = bi.mt5_pair()
     _full_size(cfg, 32)
+
+
+# ---------------------------------------------------------------------------------------------
+# Decoder-only, 128-wide heads, long prompt: the shape family of configs 4 and 5 at a size the
+# oracle finishes in seconds.  Covers prompt prefill in 32-row chunks, RoPE at large positions,
+# key-split attention (cache > 512 rows) and review blocks of 1..32 rows with truncation between.
+def _llama_mini():
+    from dataclasses import replace
+    cfg = bi.llama_pair()
+    large = replace(cfg.large, n_dec=3, d=512, heads=4, d_ff=1408, vocab=4000, name="llama-mini-large")
+    small = replace(cfg.small, n_dec=2, d=256, heads=2, d_ff=704, vocab=4000, name="llama-mini-small")
+    return replace(cfg, name="llama-mini", small=small, large=large, n_src=700, max_new=24)
+
+
+def test_llama_shaped_prefill_and_generation():
+    cfg = _llama_mini()
+    R = Rig(cfg)
+    fb, rb = 0.5, 2.0
+    ref = oracle.bild_generate(R.req, fb, rb, cfg.n_max, cfg.max_new, keep_logits=True)
+    st = R.state(cfg.max_new, cfg.n_max)
+    st.encode(R.src)
+    ln = st.lengths()
+    assert ln["y_len"] == len(R.src) and ln["len_small"] == ln["len_large"] == len(R.src) - 1
+    worst = parity.teacher_forced(st, ref, R.n0, fb, rb, cfg)
+    print("llama-mini", worst, ref.stats, flush=True)
+    toks, stats = st.generate(R.src, fb, rb, cfg.max_new)
+    print(parity.compare_generation(toks, stats, ref, fb, rb), stats, flush=True)
+
+
+def test_review_stress_blocks_and_random_truncation():
+    """Config-5 style: large_verify alone over forced blocks of n+1 in {1,4,8,16,32} rows on a long cache, with
+    kv_truncate to random positions in between; every row's logits against the no-cache definition."""
+    cfg = _llama_mini()
+    R = Rig(cfg)
+    tol = parity.logit_tol(cfg)
+    rng = np.random.default_rng(5)
+    st = pkg.State(R.pair, len(R.src), len(R.src) + 80, 31)
+    st.encode(R.src)
+    st.debug_enable_logits(True)
+    n0 = R.n0
+    for n in (0, 3, 7, 15, 31, 7):
+        block = [int(t) for t in bi.make_tokens(cfg.large.vocab, n, seed=100 + n)]
+        out, r, nll = st.large_verify(INF, draft=block)            # never roll back
+        assert r == n and out[:n] == block
+        seq = st.sequence()
+        y = seq[:-1]                                               # what the pass saw
+        z = R.req.large.logits_full(y, [])[len(y) - n - 1:]
+        for i in (0, n // 2, n):
+            zi = st.debug_logits(pkg.LARGE, i)
+            assert np.max(np.abs(zi - z[i])) <= tol, (n, i)
+            assert abs(float(nll[i]) - oracle.policy.nll(z[i], block[i])) <= 2 * tol if i < n else True
+        assert out[n] == int(np.argmax(z[n])) or oracle.policy.top2_gap(z[n]) < parity.MARGIN
+        # cut the large cache at a random row inside the prompt and the sequence back to the prompt:
+        # the next review recomputes the cut rows (catch-up) before it reviews its block
+        cut = int(rng.integers(1, n0 - 1))
+        st.force_tokens(n0, [], n0)
+        st.kv_truncate(pkg.LARGE, cut)
+        assert st.lengths()["len_large"] == cut
+
+
+def test_head_dim_128_and_64_bf16_toys():
+    for dh, heads in ((128, 1), (64, 2)):
+        cfg = bi.toy_pair(dtype=bi.DT_BF16, act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=True, d=128,
+                          heads=heads, d_head=dh, d_ff=160, vocab=333, n_src=40)
+        R = Rig(cfg)
+        ref = oracle.bild_generate(R.req, 0.4, 1.0, 5, cfg.max_new, keep_logits=True)
+        st = R.state(cfg.max_new, 5)
+        st.encode(R.src)
+        print(dh, parity.teacher_forced(st, ref, R.n0, 0.4, 1.0, cfg), ref.stats, flush=True)
+
+
+@pytest.mark.timeout(1500)
+@pytest.mark.skipif(__import__("os").environ.get("BILD_TEST_7B") != "1",
+                    reason="7B-shaped pair: ~60 s of weight generation and a float64 oracle over 13 GB of weights; "
+                           "run with BILD_TEST_7B=1")
+def test_llama_config_full_width_sampled_rows():
+    """Config 4 at its full widths (32 layers, d 4096, 32 heads of 128, FFN 11008, vocab 32000) on a shortened
+    prompt: the rows of one review pass and of one small step against the oracle, element by element."""
+    from dataclasses import replace
+    cfg = replace(bi.llama_pair(), n_src=48, max_new=8)
+    R = Rig(cfg, compact=True)
+    tol = parity.logit_tol(cfg)
+    st = R.state(cfg.max_new + 8, cfg.n_max)
+    st.encode(R.src)
+    st.debug_enable_logits(True)
+    block = [int(t) for t in bi.make_tokens(cfg.large.vocab, 5, seed=9)]
+    out, r, nll = st.large_verify(INF, draft=block)
+    y = list(R.src) + block
+    z = R.req.large.logits_full(y, [])[len(y) - 6:]
+    for i in range(6):
+        zi = st.debug_logits(pkg.LARGE, i)
+        print("large row", i, float(np.max(np.abs(zi - z[i]))), flush=True)
+        assert np.max(np.abs(zi - z[i])) <= tol
+    assert out[5] == int(np.argmax(z[5])) or oracle.policy.top2_gap(z[5]) < parity.MARGIN
+    tok, flag, pmax = st.small_step(0.5)
+    seq = st.sequence()
+    pre = seq if flag else seq[:-1]
+    zs = R.req.small.logits_full(pre, [])[-1]
+    zg = st.debug_logits(pkg.SMALL, 0)
+    print("small row", float(np.max(np.abs(zg - zs))), flush=True)
+    assert np.max(np.abs(zg - zs)) <= tol and abs(pmax - oracle.policy.max_prob(zs)) <= 2 * tol
