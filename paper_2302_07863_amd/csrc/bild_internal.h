@@ -121,6 +121,7 @@ struct AttnArgs {
     float* part_o;             // [splits][T][I]   unnormalised partial outputs
     float* part_ml;            // [splits][T][heads][2] (max, sum)
     float scale;
+    unsigned long long* trace;  // kernel-internal time stamps (only read when built with BILD_TRACE)
 };
 
 struct EmbedArgs {

@@ -622,6 +622,13 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
     float* cl = cm + nw * 32;                 // [nw][32]
     f32x4* co = (f32x4*)(cl + nw * 32);       // [nw][NT][DT16][64]
 
+#ifdef BILD_TRACE
+    unsigned long long* tr = (a.trace && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) ? a.trace : nullptr;
+#define ASTAMP(i) do { if (tr) tr[i] = wall_clock64(); } while (0)
+#else
+#define ASTAMP(i) do { } while (0)
+#endif
+    ASTAMP(0);
     const int base = a.causal ? (*a.base_ptr + a.base_add) : 0;
     const int nkeys = a.causal ? base + T : (a.nkeys_ptr ? *a.nkeys_ptr : a.nkeys_fixed);
     const int nblk = (nkeys + 31) >> 5;
@@ -799,8 +806,10 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
         uint4 K0[2][KN], V0[DT16][VN];
         int blk = blk_begin + wave;
         if (blk < blk_end) load_kv(K0, V0, blk);
+        ASTAMP(1);
         stage_q();
         __syncthreads();
+        ASTAMP(2);
         if constexpr (DH32 <= 2) {
             uint4 K1[2][KN], V1[DT16][VN];
             for (; blk < blk_end; blk += 2 * nw) {
@@ -818,6 +827,7 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
         }
     }
 
+    ASTAMP(3);
     // ---- merge the waves' partial results ----
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
@@ -830,6 +840,7 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
         for (int dt = 0; dt < DT16; ++dt) co[((wave * NT + nt) * DT16 + dt) * 64 + lane] = O[nt][dt];
     }
     __syncthreads();
+    ASTAMP(4);
     for (int qd = wave; qd < NT * DT16; qd += nw) {
         const int nt = qd / DT16, dt = qd % DT16;
         const int t = nt * 16 + tok_l, d0 = dt * 16 + g * 4;
@@ -858,6 +869,8 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
             }
         }
     }
+    ASTAMP(5);
+#undef ASTAMP
 }
 
 __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) {
