@@ -102,6 +102,7 @@ struct GemmArgs {
     int rw;   // feature tiles per wave (1, or 2 for gated FFNs)
     int kc;   // inputs staged in LDS per chunk
     unsigned long long* trace;  // kernel-internal time stamps (only read when built with BILD_TRACE)
+    int trace_block;            // which feature-tile group records them
 };
 
 struct AttnArgs {

@@ -123,9 +123,10 @@ __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
     return gemm_red_bytes(nwv, nacc) + nwv * 32 * 4 + 32 * 4 + nwv * 32 * 16;
 }
 
+// `vblock` is the index of the feature-tile group this call handles (blockIdx.x in the one-kernel-per-stage
+// launches, a loop index in the persistent pass kernel); `smem` is the workgroup's dynamic LDS.
 template <int DT, int RW, int EPI, int ROPE, int NT>
-__global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+__device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, char* smem) {
     constexpr int KT = DT ? 32 : 16;
     constexpr int U = gemm_batch(RW, NT);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -133,7 +134,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     const int T = a.T, K = a.W.k, KC = a.kc;
     const int WK = a.wk, WR = NWV / WK;
     const int wkid = wave % WK, wrid = wave / WK;
-    const int tile0 = ((int)blockIdx.x * WR + wrid) * RW;
+    const int tile0 = (vblock * WR + wrid) * RW;
     const int nacc = RW * NT;
     const int rstride = xs_row_stride(DT, KC);
     char* xs_hi = smem;
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     }
     const int tok_l = lane & 15, kq = lane >> 4;
 #ifdef BILD_TRACE
-    unsigned long long* tr = (a.trace && blockIdx.x == gridDim.x / 2 && tid == 0) ? a.trace : nullptr;
+    unsigned long long* tr = (a.trace && vblock == a.trace_block && tid == 0) ? a.trace : nullptr;
 #define STAMP(i) do { if (tr) tr[i] = wall_clock64(); } while (0)
 #else
 #define STAMP(i) do { } while (0)
@@ -485,11 +486,17 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
             }
             StatPart o;
             o.m = r.m; o.s = r.s; o.idx = r.idx; o.pad = 0;
-            a.part[(size_t)blockIdx.x * kMaxRows + a.row_off + tid] = o;
+            a.part[(size_t)vblock * kMaxRows + a.row_off + tid] = o;
         }
     }
     STAMP(5);
 #undef STAMP
+}
+
+template <int DT, int RW, int EPI, int ROPE, int NT>
+__global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    gemm_body<DT, RW, EPI, ROPE, NT>(a, (int)blockIdx.x, smem);
 }
 
 void gemm_pick_shape(GemmArgs& a, int dtype) {
@@ -604,14 +611,13 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
 // values of discarded tokens), so a probability of exactly 0 removes them.
 // =====================================================================================
 template <int DT, int DH32>
-__global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+__device__ __forceinline__ void attn_body(const AttnArgs& a, const int vblock, char* smem) {
     constexpr int DHP = DH32 * 32;   // head dim padded to the k-step of the first product
     constexpr int DT16 = DH32 * 2;   // 16-wide output tiles along the head dim
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthr = blockDim.x, nw = nthr >> 6;
     const int T = a.T, dh = a.d_head, I = a.i_dim;
-    const int h = blockIdx.x, sp = blockIdx.y;
+    const int h = vblock % a.heads, sp = vblock / a.heads;
     const int NT = (T + 15) >> 4;
     const int tok_l = lane & 15, g = lane >> 4;
     const int qstride = DT ? (DHP + 8) * 2 : (DHP + 4) * 4;
@@ -623,7 +629,7 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
     f32x4* co = (f32x4*)(cl + nw * 32);       // [nw][NT][DT16][64]
 
 #ifdef BILD_TRACE
-    unsigned long long* tr = (a.trace && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) ? a.trace : nullptr;
+    unsigned long long* tr = (a.trace && vblock == 0 && tid == 0) ? a.trace : nullptr;
 #define ASTAMP(i) do { if (tr) tr[i] = wall_clock64(); } while (0)
 #else
 #define ASTAMP(i) do { } while (0)
@@ -873,9 +879,15 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
 #undef ASTAMP
 }
 
-__global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) {
-    const int t = blockIdx.x, I = a.i_dim;
-    for (int n = threadIdx.x; n < I; n += 256) {
+template <int DT, int DH32>
+__global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    attn_body<DT, DH32>(a, (int)(blockIdx.x + blockIdx.y * gridDim.x), smem);
+}
+
+__device__ __forceinline__ void attn_merge_body(const AttnArgs& a, const int t) {
+    const int I = a.i_dim;
+    for (int n = threadIdx.x; n < I; n += blockDim.x) {
         const int h = n / a.d_head;
         float M = -INFINITY;
         for (int sp = 0; sp < a.splits; ++sp) M = fmaxf(M, a.part_ml[(((size_t)sp * a.T + t) * a.heads + h) * 2]);
@@ -889,6 +901,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) {
         a.out[(size_t)t * I + n] = O / L;
     }
 }
+
+__global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) { attn_merge_body(a, (int)blockIdx.x); }
 
 size_t attn_lds_bytes(int dtype, int d_head, int T, int nw) {
     const int dh32 = d_head <= 32 ? 1 : (d_head <= 64 ? 2 : 4), dhp = dh32 * 32, nt = (T + 15) / 16;
@@ -918,15 +932,14 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
 // Embedding gather from the tiled matrix (+ sinusoidal position).
 // =====================================================================================
 template <int DT>
-__global__ __launch_bounds__(256) void embed_kernel(const EmbedArgs a) {
+__device__ __forceinline__ void embed_body(const EmbedArgs& a, const int t) {
     constexpr int KT = DT ? 32 : 16, PL = KT / 4;
-    const int t = blockIdx.x;
     const int base = (a.base_ptr ? *a.base_ptr : 0) + a.base_add;
     const int tok = a.tokens[base + t];
     const int row = (int)(((long long)tok + a.tie_shift) % a.vocab);
     const int pos = base + t;
     const double lg = log2(10000.0);
-    for (int k = threadIdx.x; k < a.d; k += 256) {
+    for (int k = threadIdx.x; k < a.d; k += blockDim.x) {
         const size_t tile = (size_t)(row >> 4) * a.E.tk + (k / KT);
         const int ln = (row & 15) + 16 * ((k % KT) / PL), j = k % PL;
         const char* p = (const char*)a.E.w + tile * kTileBytes + ln * 16;
@@ -939,6 +952,9 @@ __global__ __launch_bounds__(256) void embed_kernel(const EmbedArgs a) {
         a.x[(size_t)t * a.d + k] = v;
     }
 }
+
+template <int DT>
+__global__ __launch_bounds__(256) void embed_kernel(const EmbedArgs a) { embed_body<DT>(a, (int)blockIdx.x); }
 
 hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st) {
     if (dtype)
@@ -957,16 +973,21 @@ hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st) {
 //   mode 3  no LM head: only advance the cache length by the rows consumed
 //   mode 4  measurement: merge the statistics, commit nothing
 // =====================================================================================
-__global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
-    __shared__ float rm[kMaxRows], rsum[kMaxRows];
-    __shared__ int ridx[kMaxRows];
-    __shared__ StatPart wpart[4];
+// LDS use of finish_body (from the start of the workgroup's LDS)
+constexpr int kFinishLds = 3 * kMaxRows * 4 + 8 * 16;
+
+__device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
+    float* rm = (float*)lds;
+    float* rsum = rm + kMaxRows;
+    int* ridx = (int*)(rsum + kMaxRows);
+    StatPart* wpart = (StatPart*)(ridx + kMaxRows);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nthr = blockDim.x, nwv = nthr >> 6;
     Ctl* c = a.ctl;
     if (a.mode != 3) {
-        for (int t = 0; t < a.T; ++t) {  // all 256 threads share each row's partials
+        for (int t = 0; t < a.T; ++t) {  // all threads share each row's partials
             Stat r = stat_neutral();
-            for (int p = tid; p < a.nparts; p += 256) {
+            for (int p = tid; p < a.nparts; p += nthr) {
                 const StatPart sp = a.part[(size_t)p * kMaxRows + a.row_off + t];
                 r = stat_merge(r, Stat{sp.m, sp.s, sp.idx});
             }
@@ -976,7 +997,7 @@ __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
             __syncthreads();
             if (tid == 0) {
                 Stat f = stat_neutral();
-                for (int w = 0; w < 4; ++w) f = stat_merge(f, Stat{wpart[w].m, wpart[w].s, wpart[w].idx});
+                for (int w = 0; w < nwv; ++w) f = stat_merge(f, Stat{wpart[w].m, wpart[w].s, wpart[w].idx});
                 rm[t] = f.m;
                 rsum[t] = f.s;
                 ridx[t] = f.idx;
@@ -1034,9 +1055,14 @@ __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
     // mirror the control block into pinned host memory for the caller
     if (a.host_mirror) {
         const int words = sizeof(Ctl) / 4;
-        for (int i = tid; i < words; i += 256)
+        for (int i = tid; i < words; i += nthr)
             ((volatile int*)a.host_mirror)[i] = __hip_atomic_load((int*)c + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+}
+
+__global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
+    __shared__ __attribute__((aligned(16))) char lds[kFinishLds];
+    finish_body(a, lds);
 }
 
 // Plain copy of known size: the reference against which hardware byte counters are scaled.
