@@ -47,6 +47,10 @@ struct bild_model {
     int inner() const { return cfg.n_heads * cfg.d_head; }
     int esz() const { return cfg.dtype == BILD_DT_BF16 ? 2 : 4; }
     bool gated() const { return cfg.act != BILD_ACT_RELU; }
+    size_t layer_weight_bytes() const {  // weight matrices of one decoder layer
+        const size_t d = cfg.d_model, I = inner(), F = cfg.d_ff;
+        return (4 * d * I * (cfg.cross_attn ? 2 : 1) + (gated() ? 3 : 2) * d * F) * esz();
+    }
 };
 
 struct bild_pair {
@@ -93,6 +97,18 @@ struct bild_state {
     bool gemm_only = false;       // measurement: a pass launches only its weight-streaming GEMMs
     int64_t gemm_count = 0, gemm_bytes = 0;  // tallied while a pass is being issued
     std::map<std::array<int, 6>, hipGraphExec_t> graphs;  // captured passes by (model, rows, lm rows, mode, key bucket, debug)
+    // persistent pass kernel: stage lists by (model, rows, key bucket, gemm-only), barrier state, settings
+    struct PassProg { Stage* dev = nullptr; int nstages = 0; int G = 0; size_t lds = 0; int64_t gemms = 0, gemm_bytes = 0; };
+    std::map<std::array<int, 4>, PassProg> progs;
+    PassSync* psync = nullptr;
+    bool resident[2] = {false, false};  // model w runs its layers in the persistent kernel
+    int resident_G[2] = {0, 0};
+    unsigned long long* ptrace_dev = nullptr;
+    unsigned long long* ptrace = nullptr;  // pinned; stage time stamps of the last persistent pass (tracing builds)
+    int ptrace_wg = 0;
+    int ptrace_stages = 0;
+    std::vector<int> ptrace_kinds;
+    int spin_limit = 1 << 20;  // barrier polls (about a microsecond each) before a wait gives up
     int* y = nullptr;     // device [max_len + 1]
     int* src = nullptr;   // device [max_src]
     hipStream_t stream = nullptr;
@@ -368,6 +384,40 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         const char* ng = std::getenv("BILD_NO_GRAPH");
         s->use_graphs = !(ng && ng[0] == '1');
     }
+#ifdef BILD_TRACE
+    {
+        void* t = nullptr;
+        if (hipHostMalloc(&t, 8 * 8 * 1024, hipHostMallocMapped) == hipSuccess) {
+            s->host_allocs.push_back(t);
+            std::memset(t, 0, 8 * 8 * 1024);
+            s->ptrace = (unsigned long long*)t;
+            void* td = nullptr;
+            if (hipHostGetDevicePointer(&td, t, 0) == hipSuccess) s->ptrace_dev = (unsigned long long*)td;
+            const char* tw = std::getenv("BILD_TRACE_WG");
+            s->ptrace_wg = tw ? std::atoi(tw) : 0;
+        }
+    }
+#endif
+    AL(s->psync, sizeof(PassSync));
+    if (hipMemsetAsync(s->psync, 0, sizeof(PassSync), s->stream) != hipSuccess) {
+        bild_state_destroy(s);
+        return BILD_EHIP;
+    }
+    {
+        // BILD_RESIDENT=1 runs the layers of a pass in the persistent kernel instead of one kernel per
+        // stage.  Off by default: on this chip a workgroup streams at most about 28 GB/s, so bandwidth
+        // needs all 256 CUs, and a grid barrier over that many workgroups plus the cross-XCD hand-over of
+        // the activations costs more than a kernel boundary does (measured; see the design notes).
+        const char* e = std::getenv("BILD_RESIDENT");
+        const char* eg = std::getenv("BILD_RESIDENT_G");
+        const char* es = std::getenv("BILD_BARRIER_SPIN");
+        if (es) s->spin_limit = std::max(-1, std::atoi(es));  // -1: every barrier wait gives up at once (error-path tests)
+        for (int w = 0; w < 2; ++w) {
+            const bild_model* m = p->m[w];
+            s->resident[w] = e && e[0] == '1';
+            s->resident_G[w] = eg ? std::min(256, std::max(1, std::atoi(eg))) : (m->cfg.d_model >= 1024 ? 64 : 32);
+        }
+    }
     for (int w = 0; w < 2; ++w) {
         ModelState& M = s->ms[w];
         const bild_model* m = p->m[w];
@@ -451,6 +501,13 @@ int set_alpha(bild_state* s, float fb, float rb) {
 // Waits for the stream; the policy kernel has mirrored the control block into pinned host memory.
 int pull_ctl(bild_state* s) {
     HIPC(hipStreamSynchronize(s->stream));
+    if (s->hctl->fault) {
+        // a grid barrier of the persistent kernel gave up: its counters are meaningless now
+        (void)hipMemset(s->psync, 0, sizeof(PassSync));
+        (void)hipMemset(&s->ctl->fault, 0, sizeof(int));
+        s->hctl->fault = 0;
+        return BILD_EHIP;
+    }
     s->y_len = s->hctl->y_len;
     s->draft_start = s->hctl->draft_start;
     s->len[0] = s->hctl->len[0];
@@ -459,9 +516,13 @@ int pull_ctl(bild_state* s) {
 }
 
 int pick_splits(const ModelState& M, int nkeys, int heads) {
-    // enough workgroups to cover the chip once the key range is long
+    // A workgroup streams about 128 KiB of K/V in one memory round trip (measured); beyond that its time
+    // grows with the bytes.  Splitting the keys costs a merge kernel of its own, so split only until a
+    // workgroup's share is down to that size.
+    const bild_model_config& c = M.m->cfg;
+    const size_t per_head = (size_t)nkeys * c.d_head * 2 * M.m->esz();
     int sp = 1;
-    while (sp < M.max_splits && heads * sp < 256 && nkeys / (sp * 2) >= 256) sp *= 2;
+    while (sp < M.max_splits && heads * sp < 512 && per_head / sp > ((size_t)160 << 10)) sp *= 2;
     return sp;
 }
 
@@ -520,10 +581,65 @@ int run_gemm(bild_state* s, const bild_model* m, GemmArgs& g) {
     return launch_gemm_profiled(s, m, g);
 }
 
-// One decoder pass of model w over rows y[len .. len+T): embed, layers, and (lm_rows > 0)
-// the LM head over the last lm_rows rows followed by the policy `mode`; lm_rows == 0
-// only advances the cache (catch-up / prefill).
-int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hint) {
+// Where the stages of a pass go: launched one kernel each (prog == nullptr), or appended to the
+// stage list of the persistent kernel with launch shapes for its G resident workgroups.
+struct StageSink {
+    std::vector<Stage>* prog = nullptr;
+    int G = 0;
+    size_t lds = 0;  // largest LDS need among the appended stages
+};
+
+int emit_gemm(bild_state* s, const bild_model* m, GemmArgs& g, StageSink& sink) {
+    if (!sink.prog) {
+        gemm_pick_shape(g, m->cfg.dtype);
+        return launch_gemm_profiled(s, m, g);
+    }
+    gemm_pick_shape_resident(g, m->cfg.dtype, sink.G);
+    s->gemm_count += 1;
+    s->gemm_bytes += (int64_t)g.W.n * g.W.k * m->esz();
+    Stage st;
+    std::memset((void*)&st, 0, sizeof(st));
+    st.kind = ST_GEMM;
+    st.nblocks = (int)gemm_num_blocks(g);
+    st.g = g;
+    sink.lds = std::max(sink.lds, gemm_lds_bytes(g, m->cfg.dtype));
+    sink.prog->push_back(st);
+    return BILD_OK;
+}
+
+int emit_attention(bild_state* s, const ModelState& M, AttnArgs& a, int nkeys, StageSink& sink) {
+    const int dt = M.m->cfg.dtype;
+    if (!sink.prog) {
+        a.splits = pick_splits(M, nkeys, a.heads);
+        a.nw = pick_attn_waves(dt, a.d_head, a.T, nkeys, a.splits);
+        if (!s->gemm_only) HIPC(launch_attention(a, dt, s->stream));
+        return BILD_OK;
+    }
+    if (s->gemm_only) return BILD_OK;
+    // 8 waves per workgroup; split the keys only when a wave would otherwise walk more than four
+    // 32-key blocks and workgroups are free, because a split costs a merge stage and its barrier
+    a.nw = 8;
+    int sp = 1;
+    const int nblk = (nkeys + 31) / 32;
+    while (sp * 2 <= M.max_splits && a.heads * sp * 2 <= sink.G && nblk > sp * 8 * 4) sp *= 2;
+    a.splits = sp;
+    Stage st;
+    std::memset((void*)&st, 0, sizeof(st));
+    st.kind = ST_ATTN;
+    st.nblocks = a.heads * sp;
+    st.a = a;
+    sink.lds = std::max(sink.lds, attn_lds_bytes(dt, a.d_head, a.T, a.nw));
+    sink.prog->push_back(st);
+    if (sp > 1) {
+        st.kind = ST_ATTN_MERGE;
+        st.nblocks = a.T;
+        sink.prog->push_back(st);
+    }
+    return BILD_OK;
+}
+
+// Embedding and all decoder layers of model w over rows y[len .. len+T).
+int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
     ModelState& M = s->ms[w];
     const bild_model* m = M.m;
     const bild_model_config& c = m->cfg;
@@ -531,7 +647,7 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
     const size_t esz = m->esz();
     const int* len_ptr = &s->ctl->len[w];
     EmbedArgs e;
-    std::memset(&e, 0, sizeof(e));
+    std::memset((void*)&e, 0, sizeof(e));
     e.E = m->emb;
     e.tokens = s->y;
     e.base_ptr = len_ptr;
@@ -542,7 +658,18 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
     e.sinusoidal = c.pos == BILD_POS_SINUSOIDAL;
     e.embed_scale = c.embed_scale;
     e.x = M.x;
-    if (!s->gemm_only) HIPC(launch_embed(e, dt, s->stream));
+    if (!s->gemm_only) {
+        if (sink.prog) {
+            Stage st;
+            std::memset((void*)&st, 0, sizeof(st));
+            st.kind = ST_EMBED;
+            st.nblocks = T;
+            st.e = e;
+            sink.prog->push_back(st);
+        } else {
+            HIPC(launch_embed(e, dt, s->stream));
+        }
+    }
     const float att_scale = 1.f / std::sqrt((float)c.d_head);
     for (int l = 0; l < c.n_dec_layers; ++l) {
         const LayerW& L = m->dec[l];
@@ -558,29 +685,28 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
             g.vcap = s->cap_len;
             g.pos_ptr = len_ptr;
             g.rope = c.pos == BILD_POS_ROPE;
-            int rc = run_gemm(s, m, g);
+            int rc = emit_gemm(s, m, g, sink);
             if (rc) return rc;
         }
         {
             AttnArgs a;
-            std::memset(&a, 0, sizeof(a));
+            std::memset((void*)&a, 0, sizeof(a));
             a.q = M.q; a.k = kc; a.v = vc; a.out = M.a;
             a.T = T; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
             a.causal = 1;
             a.base_ptr = len_ptr;
             a.vcap = s->cap_len;
-            a.splits = pick_splits(M, key_hint, c.n_heads);
-            a.nw = pick_attn_waves(dt, c.d_head, T, key_hint, a.splits);
             a.part_o = M.att_o; a.part_ml = M.att_ml;
             a.scale = att_scale;
-            if (!s->gemm_only) HIPC(launch_attention(a, dt, s->stream));
+            int rc = emit_attention(s, M, a, key_hint, sink);
+            if (rc) return rc;
         }
         {
             GemmArgs g = gemm_base(m, L.wo, M.a, I, T, nullptr);
             g.epi = EPI_RESID;
             g.out = M.x;
             g.ldo = d;
-            int rc = run_gemm(s, m, g);
+            int rc = emit_gemm(s, m, g, sink);
             if (rc) return rc;
         }
         if (c.cross_attn) {
@@ -589,12 +715,12 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
                 g.epi = EPI_STORE;
                 g.out = M.q;
                 g.ldo = I;
-                int rc = run_gemm(s, m, g);
+                int rc = emit_gemm(s, m, g, sink);
                 if (rc) return rc;
             }
             {
                 AttnArgs a;
-                std::memset(&a, 0, sizeof(a));
+                std::memset((void*)&a, 0, sizeof(a));
                 a.q = M.q;
                 a.k = M.ck + (size_t)l * s->cap_src * I * esz;
                 a.v = M.cv + (size_t)l * s->cap_src * I * esz;
@@ -603,18 +729,17 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
                 a.T = T; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
                 a.causal = 0;
                 a.nkeys_ptr = &s->ctl->n_src;
-                a.splits = pick_splits(M, s->n_src, c.n_heads);
-                a.nw = pick_attn_waves(dt, c.d_head, T, s->n_src, a.splits);
                 a.part_o = M.att_o; a.part_ml = M.att_ml;
                 a.scale = att_scale;
-                if (!s->gemm_only) HIPC(launch_attention(a, dt, s->stream));
+                int rc = emit_attention(s, M, a, s->n_src, sink);
+                if (rc) return rc;
             }
             {
                 GemmArgs g = gemm_base(m, L.cwo, M.a, I, T, nullptr);
                 g.epi = EPI_RESID;
                 g.out = M.x;
                 g.ldo = d;
-                int rc = run_gemm(s, m, g);
+                int rc = emit_gemm(s, m, g, sink);
                 if (rc) return rc;
             }
         }
@@ -623,7 +748,7 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
             g.epi = EPI_ACT;
             g.out = M.h;
             g.ldo = F;
-            int rc = run_gemm(s, m, g);
+            int rc = emit_gemm(s, m, g, sink);
             if (rc) return rc;
         }
         {
@@ -631,12 +756,95 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
             g.epi = EPI_RESID;
             g.out = M.x;
             g.ldo = d;
-            int rc = run_gemm(s, m, g);
+            int rc = emit_gemm(s, m, g, sink);
             if (rc) return rc;
         }
     }
+    return BILD_OK;
+}
+
+// The stage list of (model, rows, key bucket) for the persistent kernel, built and uploaded on first
+// use.  nstages == 0 marks a pass whose stages do not fit the kernel's LDS: it takes the other path.
+// Must first be called outside stream capture (the upload is a blocking copy).
+int get_program(bild_state* s, int w, int T, int key_hint, const bild_state::PassProg** out) {
+    const std::array<int, 4> key = {w, T, key_hint, s->gemm_only ? 1 : 0};
+    auto it = s->progs.find(key);
+    if (it == s->progs.end()) {
+        std::vector<Stage> prog;
+        StageSink sink;
+        sink.prog = &prog;
+        sink.G = s->resident_G[w];
+        const int64_t c0 = s->gemm_count, b0 = s->gemm_bytes;
+        int rc = emit_layers(s, w, T, key_hint, sink);
+        s->gemm_count = c0;  // tallied again by the pass that runs the list
+        s->gemm_bytes = b0;
+        if (rc) return rc;
+#ifdef BILD_TRACE
+        if (const char* ts = std::getenv("BILD_TRACE_STAGE")) {  // in-body stamps of one stage, kept after the per-stage ones
+            const int i = std::atoi(ts);
+            if (i >= 0 && i < (int)prog.size() && s->ptrace_dev) {
+                if (prog[i].kind == ST_GEMM) { prog[i].g.trace = s->ptrace_dev + 8 * 1000; prog[i].g.trace_block = s->ptrace_wg; }
+                if (prog[i].kind == ST_ATTN) prog[i].a.trace = s->ptrace_dev + 8 * 1000;
+            }
+        }
+#endif
+        bild_state::PassProg pp;
+        if (!prog.empty() && kPassArgLds + sink.lds <= pass_lds_limit()) {
+            void* d = nullptr;
+            rc = dev_alloc(s->allocs, &d, prog.size() * sizeof(Stage));
+            if (rc) return rc;
+            HIPC(hipMemcpy(d, prog.data(), prog.size() * sizeof(Stage), hipMemcpyHostToDevice));
+            pp.dev = (Stage*)d;
+            pp.nstages = (int)prog.size();
+            pp.G = sink.G;
+            pp.lds = sink.lds;
+            for (const Stage& st : prog)
+                if (st.kind == ST_GEMM) {
+                    pp.gemms += 1;
+                    pp.gemm_bytes += (int64_t)st.g.W.n * st.g.W.k * s->ms[w].m->esz();
+                }
+        }
+        it = s->progs.emplace(key, pp).first;
+    }
+    *out = &it->second;
+    return BILD_OK;
+}
+
+// One decoder pass of model w over rows y[len .. len+T): embed, layers, and (lm_rows > 0)
+// the LM head over the last lm_rows rows followed by the policy `mode`; lm_rows == 0
+// only advances the cache (catch-up / prefill).
+int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hint) {
+    ModelState& M = s->ms[w];
+    const bild_model* m = M.m;
+    const bild_model_config& c = m->cfg;
+    const int d = c.d_model, dt = c.dtype;
+    const int* len_ptr = &s->ctl->len[w];
+    const bild_state::PassProg* pp = nullptr;
+    if (s->resident[w] && !s->prof_on) {
+        int rc = get_program(s, w, T, key_hint, &pp);
+        if (rc) return rc;
+        if (pp->nstages == 0) pp = nullptr;
+    }
+    if (pp) {
+        PassArgs pa;
+        pa.prog = pp->dev;
+        pa.nstages = pp->nstages;
+        pa.sync = s->psync;
+        pa.fault = &s->ctl->fault;
+        pa.spin_limit = s->spin_limit;
+        pa.trace = s->ptrace_dev;
+        pa.trace_wg = s->ptrace_wg;
+        s->ptrace_stages = pp->nstages;
+        HIPC(launch_pass(pa, dt, T, c.d_head, pp->G, pp->lds, s->stream));
+        s->gemm_count += pp->gemms;
+        s->gemm_bytes += pp->gemm_bytes;
+    } else {
+        StageSink direct;
+        int rc = emit_layers(s, w, T, key_hint, direct);
+        if (rc) return rc;
+    }
     FinishArgs f;
-    std::memset(&f, 0, sizeof(f));
+    std::memset((void*)&f, 0, sizeof(f));
     f.ctl = s->ctl;
     f.y = s->y;
     f.which = w;
@@ -689,6 +897,11 @@ int run_pass(bild_state* s, int w, int T, int lm_rows, int mode) {
     const std::array<int, 6> key = {w, T, lm_rows, mode, bucket, (s->debug_logits ? 1 : 0) | (s->gemm_only ? 2 : 0)};
     auto it = s->graphs.find(key);
     if (it == s->graphs.end()) {
+        if (s->resident[w]) {  // the stage list is uploaded with a blocking copy: not inside a capture
+            const bild_state::PassProg* pp = nullptr;
+            const int rc = get_program(s, w, T, bucket, &pp);
+            if (rc) return rc;
+        }
         hipGraph_t g = nullptr;
         HIPC(hipStreamBeginCapture(s->stream, hipStreamCaptureModeThreadLocal));
         const int rc = decoder_pass(s, w, T, lm_rows, mode, bucket);
@@ -1111,6 +1324,32 @@ extern "C" int bild_bench_pass(bild_state* s, int which, int rows, int reps, flo
     (void)hipEventDestroy(e1);
     if (rc) return rc;
     *ms_per_pass = ms / (float)reps;
+#ifdef BILD_TRACE
+    if (s->ptrace && s->resident[w] && s->ptrace_stages > 1) {
+        // stamps (10 ns ticks): 0 stage start, 1 body done, 2 workgroup barrier, 3 release, 4 all arrived, 5 acquire, 6 out
+        double sum[7] = {0, 0, 0, 0, 0, 0, 0};
+        const int n = std::min(s->ptrace_stages, 1024) - 1;
+        for (int i = 0; i < n; ++i) {
+            const unsigned long long* t = s->ptrace + (size_t)i * 8;
+            for (int j = 1; j <= 6; ++j) sum[j] += (double)(t[j] - t[j - 1]) * 0.01;
+            sum[0] += (double)(s->ptrace[(size_t)(i + 1) * 8] - t[6]) * 0.01;
+            if (i < 20)
+                std::fprintf(stderr, "[trace] stage %3d body %.2f sync %.2f release %.2f arrive+wait %.2f acquire %.2f sync %.2f next %.2f us\n", i,
+                             (t[1] - t[0]) * 0.01, (t[2] - t[1]) * 0.01, (t[3] - t[2]) * 0.01, (t[4] - t[3]) * 0.01,
+                             (t[5] - t[4]) * 0.01, (t[6] - t[5]) * 0.01, (s->ptrace[(size_t)(i + 1) * 8] - t[6]) * 0.01);
+        }
+        if (std::getenv("BILD_TRACE_STAGE")) {
+            const int i = std::atoi(std::getenv("BILD_TRACE_STAGE"));
+            const unsigned long long* b = s->ptrace + 8 * 1000;
+            const unsigned long long t0 = s->ptrace[(size_t)i * 8];
+            std::fprintf(stderr, "[trace] inside stage %d (us after stage start): entry %.2f staged %.2f synced %.2f streamed %.2f reduced %.2f end %.2f\n", i,
+                         (double)(long long)(b[0] - t0) * 0.01, (double)(long long)(b[1] - t0) * 0.01, (double)(long long)(b[2] - t0) * 0.01,
+                         (double)(long long)(b[3] - t0) * 0.01, (double)(long long)(b[4] - t0) * 0.01, (double)(long long)(b[5] - t0) * 0.01);
+        }
+        std::fprintf(stderr, "[trace] model %d rows %d wg %d: %d stages; mean us: body %.2f sync %.2f release %.2f arrive+wait %.2f acquire %.2f sync %.2f next-start %.2f\n",
+                     w, rows, s->ptrace_wg, n + 1, sum[1] / n, sum[2] / n, sum[3] / n, sum[4] / n, sum[5] / n, sum[6] / n, sum[0] / n);
+    }
+#endif
     return BILD_OK;
 }
 

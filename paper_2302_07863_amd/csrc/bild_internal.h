@@ -42,7 +42,7 @@ struct Ctl {
     int res_r;
     int res_n;
     float res_pmax;
-    int pad;
+    int fault;        // set by the persistent pass kernel when a grid barrier gave up waiting
     float res_nll[kMaxRows];
     int res_rowtok[kMaxRows];  // argmax of every row of the last pass
 };
@@ -149,6 +149,45 @@ struct FinishArgs {
     int y_cap;
     Ctl* host_mirror;   // device-visible pinned host copy of the control block, written last
 };
+
+// ---- persistent pass kernel: one launch walks a device-resident list of stages, its workgroups
+// meeting at a grid barrier between stages (pass_kernel.hip) ----
+enum StageKind : int { ST_EMBED = 0, ST_GEMM = 1, ST_ATTN = 2, ST_ATTN_MERGE = 3 };
+
+struct Stage {
+    int kind;
+    int nblocks;  // units of work of the stage; workgroup b takes units b, b + G, ...
+    int pad[2];
+    GemmArgs g;   // ST_GEMM
+    AttnArgs a;   // ST_ATTN, ST_ATTN_MERGE
+    EmbedArgs e;  // ST_EMBED
+};
+
+// Barrier state of one request.  `arrivals` only ever grows (compared modulo 2^32); `epoch` is its
+// value when the previous launch ended, read by every workgroup of the next launch as its base.
+struct PassSync {
+    unsigned arrivals;
+    unsigned pad0[31];
+    unsigned epoch;
+    unsigned pad1[31];
+};
+
+struct PassArgs {
+    const Stage* prog;
+    int nstages;
+    PassSync* sync;
+    int* fault;      // set to 1 if a barrier wait ran out (then every workgroup leaves early)
+    int spin_limit;  // polls before a barrier wait gives up
+    unsigned long long* trace;  // [nstages][8] time stamps of workgroup trace_wg (only read when built with BILD_TRACE)
+    int trace_wg;
+};
+
+constexpr int kPassArgLds = 0;  // LDS the pass kernel keeps for itself ahead of the stages' own
+hipError_t launch_pass(const PassArgs& p, int dtype, int T, int d_head, int G, size_t stage_lds, hipStream_t st);
+size_t pass_lds_limit();
+// launch shape of a GEMM stage inside the persistent kernel (always 8 waves; at most G units if possible)
+void gemm_pick_shape_resident(GemmArgs& a, int dtype, int G);
+size_t gemm_lds_bytes(const GemmArgs& a, int dtype);
 
 // launch wrappers (kernels.hip); each returns the hipError_t of the launch
 hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st);

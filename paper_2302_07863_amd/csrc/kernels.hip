@@ -35,6 +35,22 @@ __device__ __forceinline__ uint32_t f2bf(float f) {  // fp32 -> bf16 bits, neare
 }
 __device__ __forceinline__ float bf2f(uint32_t h) { return __uint_as_float(h << 16); }
 
+// Two fp32 values as (high, low) bf16 pairs, a in the low half-words: high = bf16(v) to nearest even,
+// low = bf16(v - high), by the packed conversion instruction of gfx950.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    const f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ void split_bf16x2(float a, float b, uint32_t& hi, uint32_t& lo) {
+    const f32x2 v = {a, b};
+    const bf16x2 h = __builtin_convertvector(v, bf16x2);
+    const f32x2 r = v - __builtin_convertvector(h, f32x2);
+    hi = __builtin_bit_cast(uint32_t, h);
+    lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2));
+}
+
 // Wavefront reductions on the data-parallel-primitive path (no LDS crossbar):
 // two quad permutes, two row mirrors, then row broadcasts carry the row totals
 // upward so that lane 63 holds the result, which is read back as a uniform value.
@@ -99,6 +115,57 @@ __device__ __forceinline__ float gelu_tanh_f(float u) {
 }
 __device__ __forceinline__ float silu_f(float u) { return u / (1.f + expf(-u)); }
 
+
+// ---- activation traffic ---------------------------------------------------------------
+// COH = false: ordinary loads and stores (the kernel boundary makes them visible).
+// COH = true (persistent pass kernel): activations pass between workgroups that may sit on
+// different XCDs inside ONE launch, so they move as relaxed agent-scope atomics, which read and
+// write the device-coherent level instead of an XCD's private copy; no cache-wide write-back or
+// invalidate is needed then.  8 bytes is the widest such access.
+template <bool COH>
+__device__ __forceinline__ float4 ld_act4(const float* p) {
+    if constexpr (COH) {
+        const unsigned long long a = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long b = __hip_atomic_load((const unsigned long long*)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return make_float4(__uint_as_float((uint32_t)a), __uint_as_float((uint32_t)(a >> 32)),
+                           __uint_as_float((uint32_t)b), __uint_as_float((uint32_t)(b >> 32)));
+    } else {
+        return *(const float4*)p;
+    }
+}
+template <bool COH>
+__device__ __forceinline__ float ld_act(const float* p) {
+    if constexpr (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else return *p;
+}
+template <bool COH>
+__device__ __forceinline__ void st_u64(void* p, uint32_t lo, uint32_t hi) {
+    if constexpr (COH)
+        __hip_atomic_store((unsigned long long*)p, (unsigned long long)lo | ((unsigned long long)hi << 32), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    else
+        *(uint2*)p = make_uint2(lo, hi);
+}
+template <bool COH>
+__device__ __forceinline__ void st_act4(float* p, const float4 v) {
+    if constexpr (COH) {
+        st_u64<true>(p, __float_as_uint(v.x), __float_as_uint(v.y));
+        st_u64<true>(p + 2, __float_as_uint(v.z), __float_as_uint(v.w));
+    } else {
+        *(float4*)p = v;
+    }
+}
+template <bool COH>
+__device__ __forceinline__ void st_act(float* p, float v) {
+    if constexpr (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+template <bool COH>
+__device__ __forceinline__ void st_u16(uint16_t* p, uint16_t v) {
+    if constexpr (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+
 // =====================================================================================
 // Skinny GEMM.  A workgroup has nwv = wk * wr wavefronts arranged as wr feature groups
 // x wk input slices; each wave owns RW feature tiles (16 features each) and walks the
@@ -125,10 +192,11 @@ __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
 
 // `vblock` is the index of the feature-tile group this call handles (blockIdx.x in the one-kernel-per-stage
 // launches, a loop index in the persistent pass kernel); `smem` is the workgroup's dynamic LDS.
-template <int DT, int RW, int EPI, int ROPE, int NT>
-__device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, char* smem) {
+// The argument block may live in the kernel-argument segment or (persistent kernel) in constant-address-space
+// device memory, hence the template parameter A.
+template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, NT), bool COH = false, class A>
+__device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* smem) {
     constexpr int KT = DT ? 32 : 16;
-    constexpr int U = gemm_batch(RW, NT);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthr = blockDim.x, NWV = nthr >> 6;
     const int T = a.T, K = a.W.k, KC = a.kc;
@@ -145,6 +213,9 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
     float* rs = ssq + NWV * 32;
     StatPart* wstat = (StatPart*)(rs + 32);
 
+    // EPI / ROPE below zero: taken from the arguments at run time (the persistent pass kernel)
+    const int epi = EPI < 0 ? a.epi : EPI;
+    const bool rope = ROPE < 0 ? a.rope != 0 : ROPE != 0;
     const bool norm = a.gain != nullptr;
     const bool few = T < 4;  // few rows: all waves share each row and split it along k
     const bool owner = (wkid == 0);
@@ -192,13 +263,13 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
         for (int nt = 0; nt < 2; ++nt) {
             old[r][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
             const int t = nt * 16 + tok_l;
-            if (EPI == EPI_RESID && owner && valid[r] && t < T)
-                old[r][nt] = *(const float4*)(a.out + (size_t)t * a.ldo + (tile0 + r) * 16 + kq * 4);
+            if (epi == EPI_RESID && owner && valid[r] && t < T)
+                old[r][nt] = ld_act4<COH>(a.out + (size_t)t * a.ldo + (tile0 + r) * 16 + kq * 4);
         }
 
     const int pos0 = (a.pos_ptr ? *a.pos_ptr : 0) + a.pos_add;
     int tgt[2] = {-1, -1};
-    if (EPI == EPI_LMHEAD) {
+    if (epi == EPI_LMHEAD) {
         const int ylen = *a.ylen_ptr;
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
@@ -252,53 +323,87 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
         const int kc_len = min(KC, K - k0);
         if (k0) __syncthreads();  // readers of the previous chunk are done
         // ---- stage x[:, k0 : k0+kc_len] (times the norm gain) into LDS ----
-        // few rows: every wave takes a k-slice of every row; otherwise whole rows are dealt to the waves
-        for (int j = 0; j < 8; ++j) {
-            const int t = few ? j : wave + NWV * j;
-            if (t >= T) break;  // wave-uniform
-            const float* xr = a.x + (size_t)t * a.ldx + k0;
-            const int start = few ? tid : lane, step = few ? nthr : 64;
-            const int n4 = kc_len >> 2;
-            float ssj = 0.f;
-            auto put = [&](int k4, float4 w, const float4& gg) {
-                if (norm) {
-                    ssj += w.x * w.x + w.y * w.y + w.z * w.z + w.w * w.w;
-                    w.x *= gg.x; w.y *= gg.y; w.z *= gg.z; w.w *= gg.w;
-                }
-                if (DT) {
-                    const uint32_t h0 = f2bf(w.x), h1 = f2bf(w.y), h2 = f2bf(w.z), h3 = f2bf(w.w);
-                    const uint32_t l0 = f2bf(w.x - bf2f(h0)), l1 = f2bf(w.y - bf2f(h1));
-                    const uint32_t l2 = f2bf(w.z - bf2f(h2)), l3 = f2bf(w.w - bf2f(h3));
-                    *(uint2*)(xs_hi + t * rstride + k4 * 8) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-                    *(uint2*)(xs_lo + t * rstride + k4 * 8) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
-                } else {
-                    *(float4*)(xs_hi + t * rstride + k4 * 16) = w;
-                }
-            };
-            if (n4 <= 2 * step) {  // short rows: at most two elements per thread
-                const int ka = start, kb2 = start + step;
-                float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va, ga = va, gb = va;
-                if (ka < n4) { va = *(const float4*)(xr + ka * 4); if (norm) ga = *(const float4*)(a.gain + k0 + ka * 4); }
-                if (kb2 < n4) { vb = *(const float4*)(xr + kb2 * 4); if (norm) gb = *(const float4*)(a.gain + k0 + kb2 * 4); }
-                if (ka < n4) put(ka, va, ga);
-                if (kb2 < n4) put(kb2, vb, gb);
+        const int n4 = kc_len >> 2;
+        // writes one float4 of row t and returns its sum of squares (for the RMSNorm)
+        auto put = [&](int t, int k4, float4 w, const float4& gg) -> float {
+            float ss = 0.f;
+            if (norm) {
+                ss = w.x * w.x + w.y * w.y + w.z * w.z + w.w * w.w;
+                w.x *= gg.x; w.y *= gg.y; w.z *= gg.z; w.w *= gg.w;
+            }
+            if (DT) {
+                uint32_t h01, l01, h23, l23;
+                split_bf16x2(w.x, w.y, h01, l01);
+                split_bf16x2(w.z, w.w, h23, l23);
+                *(uint2*)(xs_hi + t * rstride + k4 * 8) = make_uint2(h01, h23);
+                *(uint2*)(xs_lo + t * rstride + k4 * 8) = make_uint2(l01, l23);
             } else {
-                for (int kb = start; kb < n4; kb += step * 8) {
-                    float4 v[8], g[8];
+                *(float4*)(xs_hi + t * rstride + k4 * 16) = w;
+            }
+            return ss;
+        };
+        if (T > 1 && (n4 & 63) == 0) {
+            // Several rows whose chunk is a whole number of wavefront-wide pieces: the rows are laid end to
+            // end and dealt to all threads, which spreads the conversion work evenly and lets one round of
+            // loads (8 per thread, issued together) cover 8 * nthr pieces; 64 consecutive pieces share a row.
+            const int total = T * n4;
+            const unsigned magic = 0xFFFFFFFFu / (unsigned)n4 + 1u;  // e / n4 == umulhi(e, magic) for e < 2^32 / n4
+            for (int eb = tid; eb < total; eb += nthr * 8) {
+                float4 v[8], g[8];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {  // all loads of the round first
-                        const int k4 = min(kb + u * step, n4 - 1);
-                        v[u] = *(const float4*)(xr + k4 * 4);
-                        g[u] = norm ? *(const float4*)(a.gain + k0 + k4 * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int u = 0; u < 8; ++u) {
+                    const int e = min(eb + u * nthr, total - 1);
+                    const int t = (int)__umulhi((unsigned)e, magic), k4 = e - t * n4;
+                    v[u] = ld_act4<COH>(a.x + (size_t)t * a.ldx + k0 + k4 * 4);
+                    g[u] = norm ? *(const float4*)(a.gain + k0 + k4 * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int e = eb + u * nthr;
+                    if (e < total) {  // wave-uniform: total and the wave's first piece are multiples of 64
+                        const int t = (int)__umulhi((unsigned)e, magic), k4 = e - t * n4;
+                        const float ss = put(t, k4, v[u], g[u]);
+                        if (norm) {
+                            const float tot = wave_sum(ss);
+                            if (lane == 0) ssq[wave * 32 + t] += tot;
+                        }
                     }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        if (kb + u * step < n4) put(kb + u * step, v[u], g[u]);
                 }
             }
-            if (norm) {  // this wave's share of sum x^2 of row t, accumulated over the chunks
-                const float tot = wave_sum(ssj);
-                if (lane == 0) ssq[wave * 32 + t] += tot;
+        } else {
+            // one row, or ragged chunks: few rows - every wave takes a k-slice of every row; otherwise whole
+            // rows are dealt to the waves
+            for (int j = 0; j < 8; ++j) {
+                const int t = few ? j : wave + NWV * j;
+                if (t >= T) break;  // wave-uniform
+                const float* xr = a.x + (size_t)t * a.ldx + k0;
+                const int start = few ? tid : lane, step = few ? nthr : 64;
+                float ssj = 0.f;
+                if (n4 <= 2 * step) {  // short rows: at most two elements per thread
+                    const int ka = start, kb2 = start + step;
+                    float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va, ga = va, gb = va;
+                    if (ka < n4) { va = ld_act4<COH>(xr + ka * 4); if (norm) ga = *(const float4*)(a.gain + k0 + ka * 4); }
+                    if (kb2 < n4) { vb = ld_act4<COH>(xr + kb2 * 4); if (norm) gb = *(const float4*)(a.gain + k0 + kb2 * 4); }
+                    if (ka < n4) ssj += put(t, ka, va, ga);
+                    if (kb2 < n4) ssj += put(t, kb2, vb, gb);
+                } else {
+                    for (int kb = start; kb < n4; kb += step * 8) {
+                        float4 v[8], g[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {  // all loads of the round first
+                            const int k4 = min(kb + u * step, n4 - 1);
+                            v[u] = ld_act4<COH>(xr + k4 * 4);
+                            g[u] = norm ? *(const float4*)(a.gain + k0 + k4 * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            if (kb + u * step < n4) ssj += put(t, kb + u * step, v[u], g[u]);
+                    }
+                }
+                if (norm) {  // this wave's share of sum x^2 of row t, accumulated over the chunks
+                    const float tot = wave_sum(ssj);
+                    if (lane == 0) ssq[wave * 32 + t] += tot;
+                }
             }
         }
         STAMP(1);
@@ -391,7 +496,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
                     const float g = acc[0][nt][v] * r, u = acc[RW - 1][nt][v] * r;
                     o[v] = (a.act == BILD_ACT_GATED_GELU ? gelu_tanh_f(g) : silu_f(g)) * u;
                 }
-                *(float4*)(a.out + (size_t)t * a.ldo + f0) = make_float4(o[0], o[1], o[2], o[3]);
+                st_act4<COH>(a.out + (size_t)t * a.ldo + f0, make_float4(o[0], o[1], o[2], o[3]));
             }
             continue;
         }
@@ -400,24 +505,23 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
             if (!valid[rwi]) continue;
             const int n0 = (tile0 + rwi) * 16 + kq * 4;
             float v4[4] = {acc[rwi][nt][0] * r, acc[rwi][nt][1] * r, acc[rwi][nt][2] * r, acc[rwi][nt][3] * r};
-            switch (EPI) {
+            switch (epi) {
                 case EPI_STORE:
-                    *(float4*)(a.out + (size_t)t * a.ldo + n0) = make_float4(v4[0], v4[1], v4[2], v4[3]);
+                    st_act4<COH>(a.out + (size_t)t * a.ldo + n0, make_float4(v4[0], v4[1], v4[2], v4[3]));
                     break;
                 case EPI_RESID: {
                     const float4 o = old[rwi][nt];
-                    *(float4*)(a.out + (size_t)t * a.ldo + n0) =
-                        make_float4(o.x + v4[0], o.y + v4[1], o.z + v4[2], o.w + v4[3]);
+                    st_act4<COH>(a.out + (size_t)t * a.ldo + n0, make_float4(o.x + v4[0], o.y + v4[1], o.z + v4[2], o.w + v4[3]));
                 } break;
                 case EPI_ACT:
-                    *(float4*)(a.out + (size_t)t * a.ldo + n0) =
-                        make_float4(fmaxf(v4[0], 0.f), fmaxf(v4[1], 0.f), fmaxf(v4[2], 0.f), fmaxf(v4[3], 0.f));
+                    st_act4<COH>(a.out + (size_t)t * a.ldo + n0,
+                                 make_float4(fmaxf(v4[0], 0.f), fmaxf(v4[1], 0.f), fmaxf(v4[2], 0.f), fmaxf(v4[3], 0.f)));
                     break;
                 case EPI_QKV: {
                     const int pos = pos0 + t;
                     const int seg = n0 < a.q_dim ? 0 : (n0 < a.q_dim + a.i_dim ? 1 : 2);
                     const int nn = n0 - (seg == 0 ? 0 : (seg == 1 ? a.q_dim : a.q_dim + a.i_dim));
-                    if (ROPE && seg < 2) {
+                    if (rope && seg < 2) {
                         const int hd = nn % a.d_head;
 #pragma unroll
                         for (int p2 = 0; p2 < 2; ++p2) {
@@ -430,22 +534,21 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
                         }
                     }
                     if (seg == 0) {
-                        *(float4*)(a.q_out + (size_t)t * a.i_dim + nn) = make_float4(v4[0], v4[1], v4[2], v4[3]);
+                        st_act4<COH>(a.q_out + (size_t)t * a.i_dim + nn, make_float4(v4[0], v4[1], v4[2], v4[3]));
                     } else if (seg == 1) {  // K: [position][I]
                         const size_t e = (size_t)pos * a.i_dim + nn;
                         if (DT)
-                            *(uint2*)((uint16_t*)a.k_cache + e) =
-                                make_uint2(f2bf(v4[0]) | (f2bf(v4[1]) << 16), f2bf(v4[2]) | (f2bf(v4[3]) << 16));
+                            st_u64<COH>((uint16_t*)a.k_cache + e, pack_bf16x2(v4[0], v4[1]), pack_bf16x2(v4[2], v4[3]));
                         else
-                            *(float4*)((float*)a.k_cache + e) = make_float4(v4[0], v4[1], v4[2], v4[3]);
+                            st_act4<COH>((float*)a.k_cache + e, make_float4(v4[0], v4[1], v4[2], v4[3]));
                     } else {  // V: transposed, [I][vcap] with the position contiguous
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
                             const size_t e = (size_t)(nn + v) * a.vcap + pos;
                             if (DT)
-                                ((uint16_t*)a.v_cache)[e] = (uint16_t)f2bf(v4[v]);
+                                st_u16<COH>((uint16_t*)a.v_cache + e, (uint16_t)f2bf(v4[v]));
                             else
-                                ((float*)a.v_cache)[e] = v4[v];
+                                st_act<COH>((float*)a.v_cache + e, v4[v]);
                         }
                     }
                 } break;
@@ -465,7 +568,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
             }
         }
     }
-    if (EPI == EPI_LMHEAD) {
+    if (epi == EPI_LMHEAD) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
             st[nt] = stat_merge(st[nt], stat_shfl_xor(st[nt], 16));
@@ -499,19 +602,25 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     gemm_body<DT, RW, EPI, ROPE, NT>(a, (int)blockIdx.x, smem);
 }
 
-void gemm_pick_shape(GemmArgs& a, int dtype) {
+#ifndef BILD_DEVICE_ONLY
+// Rows-per-wave, chunk length and tiles per chunk of a GEMM: what both launch-shape rules start from.
+static int gemm_pick_chunks(GemmArgs& a, int dtype) {
     const int kt = dtype ? 32 : 16;
     const bool gated = a.epi == EPI_ACT && a.act != BILD_ACT_RELU;
     a.rw = gated ? 2 : 1;
-    const int nacc = a.rw * ((a.T + 15) / 16);
-    // input chunks staged in LDS: at most 64 KiB, balanced so that every chunk has the same tile count +-1
-    int kc_max = 24576 / a.T - 8;  // up to 96 KiB of staged activations
+    // input chunks staged in LDS: at most 96 KiB, balanced so that every chunk has the same tile count +-1
+    int kc_max = 24576 / a.T - 8;
     kc_max = std::max(128, (kc_max / 128) * 128);
     const int nch = (a.W.k + kc_max - 1) / kc_max;
-    int kc = ((a.W.k + nch - 1) / nch + kt - 1) / kt * kt;
+    const int kc = ((a.W.k + nch - 1) / nch + kt - 1) / kt * kt;
     a.kc = kc;
     const int tiles_last = (a.W.k - (nch - 1) * kc) / kt;
-    const int tiles_chunk = std::min(kc / kt, tiles_last);
+    return std::min(kc / kt, tiles_last);
+}
+
+void gemm_pick_shape(GemmArgs& a, int dtype) {
+    const int tiles_chunk = gemm_pick_chunks(a, dtype);
+    const int nacc = a.rw * ((a.T + 15) / 16);
     // input slices per workgroup.  Latency rule (small matrices): at most one batch of tiles per wave.
     // Parallelism rule (large ones): no more slices than it takes to field about 1536 waves, so that a
     // wave streams a long contiguous run (measured best on 32128x1024, 22016x4096 and 4096x11008).
@@ -521,12 +630,28 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     while (wk_par < 8 && (long)a.W.tn * wk_par < 1536) wk_par *= 2;
     int wk = std::min(wk_lat, wk_par);
     while (wk > 1 && (wk * nacc > 32 || wk > tiles_chunk)) wk /= 2;
-    // feature groups: as many as keep >= 512 workgroups, at least 4 waves per workgroup
-    int wr = std::max(1, 4 / wk);
+    // feature groups: as many as keep >= 512 workgroups; at least 4 waves per workgroup, 8 when there are
+    // several rows (staging the activations is then the longer part, and it is shared by all waves)
+    int wr = std::max(1, (a.T >= 4 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
     for (int c = wr * 2; c * wk <= 8 && c * wk * nacc <= 32; c *= 2)
         if ((a.W.tn + c * a.rw - 1) / (c * a.rw) >= 512) wr = c;
     a.wk = wk;
     a.nwv = wk * wr;
+}
+
+// Inside the persistent kernel every workgroup has 8 waves and there are G of them: take the most
+// input slices (shortest run per wave) that still give every feature-tile group a workgroup of its own.
+void gemm_pick_shape_resident(GemmArgs& a, int dtype, int G) {
+    const int tiles_chunk = gemm_pick_chunks(a, dtype);
+    a.nwv = 8;
+    int wk = 8;
+    while (wk > 1 && (wk > tiles_chunk || (a.W.tn + (8 / wk) * a.rw - 1) / ((8 / wk) * a.rw) > G)) wk /= 2;
+    a.wk = wk;
+}
+
+size_t gemm_lds_bytes(const GemmArgs& a, int dtype) {
+    const int nacc = a.rw * ((a.T + 15) / 16);
+    return (size_t)xs_bytes(dtype, a.kc, a.T) + gemm_tail_bytes(a.nwv, nacc);
 }
 
 size_t gemm_num_blocks(const GemmArgs& a) {
@@ -562,12 +687,30 @@ static hipError_t raise_lds_limits() {
     return done;
 }
 
-hipError_t kernels_init() { return raise_lds_limits(); }
+// persistent pass kernel: one translation unit per storage type (pass_kernel.hip)
+hipError_t launch_pass_dt0(const PassArgs& p, int nt, int dh32, int G, size_t lds, hipStream_t st);
+hipError_t launch_pass_dt1(const PassArgs& p, int nt, int dh32, int G, size_t lds, hipStream_t st);
+hipError_t pass_kernels_init_dt0(int lds_limit);
+hipError_t pass_kernels_init_dt1(int lds_limit);
+
+size_t pass_lds_limit() { return 128 * 1024; }
+
+hipError_t kernels_init() {
+    if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
+    if (hipError_t e = pass_kernels_init_dt0((int)pass_lds_limit()); e != hipSuccess) return e;
+    return pass_kernels_init_dt1((int)pass_lds_limit());
+}
+
+hipError_t launch_pass(const PassArgs& p, int dtype, int T, int d_head, int G, size_t stage_lds, hipStream_t st) {
+    const size_t lds = kPassArgLds + stage_lds;
+    if (lds > pass_lds_limit() || G < 1 || p.nstages < 1) return hipErrorInvalidValue;
+    const int nt = T > 16 ? 2 : 1, dh32 = d_head <= 32 ? 1 : (d_head <= 64 ? 2 : 4);
+    return dtype ? launch_pass_dt1(p, nt, dh32, G, lds, st) : launch_pass_dt0(p, nt, dh32, G, lds, st);
+}
 
 hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
-    const int nacc = a.rw * ((a.T + 15) / 16);
-    const size_t smem = (size_t)xs_bytes(dtype, a.kc, a.T) + gemm_tail_bytes(a.nwv, nacc);
+    const size_t smem = gemm_lds_bytes(a, dtype);
     const dim3 grid((unsigned)gemm_num_blocks(a)), block(64 * a.nwv);
 #define BILD_L(DTV, RWV, EPIV, ROPEV)                                                              \
     do {                                                                                            \
@@ -595,6 +738,8 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     return hipGetLastError();
 }
 
+#endif  // BILD_DEVICE_ONLY
+
 // =====================================================================================
 // KV-cache attention on the matrix cores.  K is stored [position][I]; V is stored
 // transposed, [I][capacity], so that both products contract over a contiguous axis:
@@ -610,8 +755,8 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
 // Cache rows beyond the valid length are finite (zero-filled at allocation, or stale
 // values of discarded tokens), so a probability of exactly 0 removes them.
 // =====================================================================================
-template <int DT, int DH32>
-__device__ __forceinline__ void attn_body(const AttnArgs& a, const int vblock, char* smem) {
+template <int DT, int DH32, bool COH = false, class A>
+__device__ __forceinline__ void attn_body(const A& a, const int vblock, char* smem) {
     constexpr int DHP = DH32 * 32;   // head dim padded to the k-step of the first product
     constexpr int DT16 = DH32 * 2;   // 16-wide output tiles along the head dim
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -647,15 +792,15 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int vblock, c
             const int t = i / (DHP / 4), d4 = (i % (DHP / 4)) * 4;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (t < T && d4 < dh) {
-                v = *(const float4*)(a.q + (size_t)t * I + h * dh + d4);
+                v = ld_act4<COH>(a.q + (size_t)t * I + h * dh + d4);
                 v.x *= a.scale; v.y *= a.scale; v.z *= a.scale; v.w *= a.scale;
             }
             if (DT) {
-                const uint32_t h0 = f2bf(v.x), h1 = f2bf(v.y), h2 = f2bf(v.z), h3 = f2bf(v.w);
-                const uint32_t l0 = f2bf(v.x - bf2f(h0)), l1 = f2bf(v.y - bf2f(h1));
-                const uint32_t l2 = f2bf(v.z - bf2f(h2)), l3 = f2bf(v.w - bf2f(h3));
-                *(uint2*)(q_hi + t * qstride + d4 * 2) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-                *(uint2*)(q_lo + t * qstride + d4 * 2) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+                uint32_t h01, l01, h23, l23;
+                split_bf16x2(v.x, v.y, h01, l01);
+                split_bf16x2(v.z, v.w, h23, l23);
+                *(uint2*)(q_hi + t * qstride + d4 * 2) = make_uint2(h01, h23);
+                *(uint2*)(q_lo + t * qstride + d4 * 2) = make_uint2(l01, l23);
             } else {
                 *(float4*)(q_hi + t * qstride + d4 * 4) = v;
             }
@@ -772,17 +917,11 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int vblock, c
             m_run[nt] = m_new;
             // ---- O = O * f + V^T P ----
             if (DT) {
-                uint32_t ph[8], pl[8];
+                uint32_t ph[4], pl[4];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float pv = p[j >> 2][j & 3];
-                    ph[j] = f2bf(pv);
-                    pl[j] = f2bf(pv - bf2f(ph[j]));
-                }
-                const bf16x8 Ph = __builtin_bit_cast(
-                    bf16x8, make_uint4(ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16), ph[4] | (ph[5] << 16), ph[6] | (ph[7] << 16)));
-                const bf16x8 Pl = __builtin_bit_cast(
-                    bf16x8, make_uint4(pl[0] | (pl[1] << 16), pl[2] | (pl[3] << 16), pl[4] | (pl[5] << 16), pl[6] | (pl[7] << 16)));
+                for (int j = 0; j < 4; ++j) split_bf16x2(p[j >> 1][(j & 1) * 2], p[j >> 1][(j & 1) * 2 + 1], ph[j], pl[j]);
+                const bf16x8 Ph = __builtin_bit_cast(bf16x8, make_uint4(ph[0], ph[1], ph[2], ph[3]));
+                const bf16x8 Pl = __builtin_bit_cast(bf16x8, make_uint4(pl[0], pl[1], pl[2], pl[3]));
 #pragma unroll
                 for (int dt = 0; dt < DT16; ++dt) {
                     O[nt][dt] *= f;
@@ -863,14 +1002,13 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int vblock, c
         if (t < T && d0 < dh) {
             if (a.splits == 1) {
                 const float inv = 1.f / Lsum;
-                *(float4*)(a.out + (size_t)t * I + h * dh + d0) =
-                    make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+                st_act4<COH>(a.out + (size_t)t * I + h * dh + d0, make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv));
             } else {
-                *(float4*)(a.part_o + ((size_t)sp * T + t) * I + h * dh + d0) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+                st_act4<COH>(a.part_o + ((size_t)sp * T + t) * I + h * dh + d0, make_float4(acc[0], acc[1], acc[2], acc[3]));
                 if (dt == 0 && g == 0) {
                     float* ml = a.part_ml + (((size_t)sp * T + t) * a.heads + h) * 2;
-                    ml[0] = M;
-                    ml[1] = Lsum;
+                    st_act<COH>(ml, M);
+                    st_act<COH>(ml + 1, Lsum);
                 }
             }
         }
@@ -885,23 +1023,26 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
     attn_body<DT, DH32>(a, (int)(blockIdx.x + blockIdx.y * gridDim.x), smem);
 }
 
-__device__ __forceinline__ void attn_merge_body(const AttnArgs& a, const int t) {
+template <bool COH = false, class A>
+__device__ __forceinline__ void attn_merge_body(const A& a, const int t) {
     const int I = a.i_dim;
     for (int n = threadIdx.x; n < I; n += blockDim.x) {
         const int h = n / a.d_head;
         float M = -INFINITY;
-        for (int sp = 0; sp < a.splits; ++sp) M = fmaxf(M, a.part_ml[(((size_t)sp * a.T + t) * a.heads + h) * 2]);
+        for (int sp = 0; sp < a.splits; ++sp) M = fmaxf(M, ld_act<COH>(a.part_ml + (((size_t)sp * a.T + t) * a.heads + h) * 2));
         float L = 0.f, O = 0.f;
         for (int sp = 0; sp < a.splits; ++sp) {
             const float* ml = a.part_ml + (((size_t)sp * a.T + t) * a.heads + h) * 2;
-            const float w = (ml[0] == -INFINITY) ? 0.f : expf(ml[0] - M);
-            L += ml[1] * w;
-            O += a.part_o[((size_t)sp * a.T + t) * I + n] * w;
+            const float m0 = ld_act<COH>(ml);
+            const float w = (m0 == -INFINITY) ? 0.f : expf(m0 - M);
+            L += ld_act<COH>(ml + 1) * w;
+            O += ld_act<COH>(a.part_o + ((size_t)sp * a.T + t) * I + n) * w;
         }
-        a.out[(size_t)t * I + n] = O / L;
+        st_act<COH>(a.out + (size_t)t * I + n, O / L);
     }
 }
 
+#ifndef BILD_DEVICE_ONLY
 __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) { attn_merge_body(a, (int)blockIdx.x); }
 
 size_t attn_lds_bytes(int dtype, int d_head, int T, int nw) {
@@ -928,11 +1069,13 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
     return hipGetLastError();
 }
 
+#endif  // BILD_DEVICE_ONLY
+
 // =====================================================================================
 // Embedding gather from the tiled matrix (+ sinusoidal position).
 // =====================================================================================
-template <int DT>
-__device__ __forceinline__ void embed_body(const EmbedArgs& a, const int t) {
+template <int DT, bool COH = false, class A>
+__device__ __forceinline__ void embed_body(const A& a, const int t) {
     constexpr int KT = DT ? 32 : 16, PL = KT / 4;
     const int base = (a.base_ptr ? *a.base_ptr : 0) + a.base_add;
     const int tok = a.tokens[base + t];
@@ -949,13 +1092,14 @@ __device__ __forceinline__ void embed_body(const EmbedArgs& a, const int t) {
             const double ang = (double)pos * exp2(-(double)(2 * (k >> 1)) / (double)a.d * lg);
             v += (float)((k & 1) ? cos(ang) : sin(ang));
         }
-        a.x[(size_t)t * a.d + k] = v;
+        st_act<COH>(a.x + (size_t)t * a.d + k, v);
     }
 }
 
 template <int DT>
 __global__ __launch_bounds__(256) void embed_kernel(const EmbedArgs a) { embed_body<DT>(a, (int)blockIdx.x); }
 
+#ifndef BILD_DEVICE_ONLY
 hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st) {
     if (dtype)
         hipLaunchKernelGGL(embed_kernel<1>, dim3(a.T), dim3(256), 0, st, a);
@@ -963,6 +1107,8 @@ hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st) {
         hipLaunchKernelGGL(embed_kernel<0>, dim3(a.T), dim3(256), 0, st, a);
     return hipGetLastError();
 }
+
+#endif  // BILD_DEVICE_ONLY
 
 // =====================================================================================
 // Merge of the LM-head partials + policy + commit.  One workgroup.
@@ -1060,6 +1206,7 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
     }
 }
 
+#ifndef BILD_DEVICE_ONLY
 __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[kFinishLds];
     finish_body(a, lds);
@@ -1079,5 +1226,7 @@ hipError_t launch_finish(const FinishArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(256), 0, st, a);
     return hipGetLastError();
 }
+
+#endif  // BILD_DEVICE_ONLY
 
 }  // namespace bild
