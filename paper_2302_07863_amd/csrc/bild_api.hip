@@ -67,7 +67,8 @@ struct ModelState {
     char* vcache = nullptr;
     char* ck = nullptr;      // cross [L][max_src][I]
     char* cv = nullptr;
-    float *x = nullptr, *q = nullptr, *a = nullptr, *h = nullptr;  // [32][d], [32][I], [32][I], [32][F]
+    float *x = nullptr, *q = nullptr, *a = nullptr, *h = nullptr;  // [rows_cap][d], [rows_cap][I], [rows_cap][I], [rows_cap][F]
+    int rows_cap = kMaxRows;  // rows one decoder pass may carry (the whole prompt for decoder-only prefill)
     StatPart* part = nullptr;
     int nparts_cap = 0;
     float* zt = nullptr;
@@ -78,6 +79,8 @@ struct ModelState {
     // encoder scratch (models with an encoder)
     float* enc_x = nullptr;   // [max_src][d]
     float* enc_q = nullptr;   // [max_src][I]
+    float* enc_a = nullptr;   // [max_src][I]
+    float* enc_h = nullptr;   // [max_src][F]
     char* enc_k = nullptr;    // [max_src][I]
     char* enc_v = nullptr;
     int last_rows = 0;        // rows of the last LM-head pass (for debug logits)
@@ -439,10 +442,12 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
             ALZ(M.ck, L * (size_t)s->cap_src * I * esz);
             ALZ(M.cv, L * (size_t)s->cap_src * I * esz);
         }
-        AL(M.x, sizeof(float) * kMaxRows * d);
-        AL(M.q, sizeof(float) * kMaxRows * I);
-        AL(M.a, sizeof(float) * kMaxRows * I);
-        AL(M.h, sizeof(float) * kMaxRows * F);
+        // a decoder-only model prefills its whole prompt in one pass of many row blocks
+        M.rows_cap = p->decoder_only ? std::max(kMaxRows, max_src) : kMaxRows;
+        AL(M.x, sizeof(float) * M.rows_cap * d);
+        AL(M.q, sizeof(float) * M.rows_cap * I);
+        AL(M.a, sizeof(float) * M.rows_cap * I);
+        AL(M.h, sizeof(float) * M.rows_cap * F);
         M.nparts_cap = (m->head.tn + 0) / 1 + 1;  // at most one partial per feature tile
         AL(M.part, sizeof(StatPart) * (size_t)M.nparts_cap * kMaxRows);
         AL(M.zt, sizeof(float) * kMaxRows);
@@ -452,6 +457,8 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         if (m->cfg.n_enc_layers > 0) {
             AL(M.enc_x, sizeof(float) * (size_t)max_src * d);
             AL(M.enc_q, sizeof(float) * (size_t)max_src * I);
+            AL(M.enc_a, sizeof(float) * (size_t)max_src * I);
+            AL(M.enc_h, sizeof(float) * (size_t)max_src * F);
             ALZ(M.enc_k, (size_t)s->cap_src * I * esz);
             ALZ(M.enc_v, (size_t)s->cap_src * I * esz);
         }
@@ -610,8 +617,8 @@ int emit_gemm(bild_state* s, const bild_model* m, GemmArgs& g, StageSink& sink) 
 int emit_attention(bild_state* s, const ModelState& M, AttnArgs& a, int nkeys, StageSink& sink) {
     const int dt = M.m->cfg.dtype;
     if (!sink.prog) {
-        a.splits = pick_splits(M, nkeys, a.heads);
-        a.nw = pick_attn_waves(dt, a.d_head, a.T, nkeys, a.splits);
+        a.splits = a.T > kMaxRows ? 1 : pick_splits(M, nkeys, a.heads);  // row blocks and key splits do not combine
+        a.nw = pick_attn_waves(dt, a.d_head, std::min(a.T, kMaxRows), nkeys, a.splits);
         if (!s->gemm_only) HIPC(launch_attention(a, dt, s->stream));
         return BILD_OK;
     }
@@ -820,7 +827,7 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
     const int d = c.d_model, dt = c.dtype;
     const int* len_ptr = &s->ctl->len[w];
     const bild_state::PassProg* pp = nullptr;
-    if (s->resident[w] && !s->prof_on) {
+    if (s->resident[w] && !s->prof_on && T <= kMaxRows) {
         int rc = get_program(s, w, T, key_hint, &pp);
         if (rc) return rc;
         if (pp->nstages == 0) pp = nullptr;
@@ -897,7 +904,7 @@ int run_pass(bild_state* s, int w, int T, int lm_rows, int mode) {
     const std::array<int, 6> key = {w, T, lm_rows, mode, bucket, (s->debug_logits ? 1 : 0) | (s->gemm_only ? 2 : 0)};
     auto it = s->graphs.find(key);
     if (it == s->graphs.end()) {
-        if (s->resident[w]) {  // the stage list is uploaded with a blocking copy: not inside a capture
+        if (s->resident[w] && T <= kMaxRows) {  // the stage list is uploaded with a blocking copy: not inside a capture
             const bild_state::PassProg* pp = nullptr;
             const int rc = get_program(s, w, T, bucket, &pp);
             if (rc) return rc;
@@ -923,7 +930,7 @@ int run_pass(bild_state* s, int w, int T, int lm_rows, int mode) {
 // Brings model w's cache up to `target` consumed rows with LM-head-less passes.
 int catch_up(bild_state* s, int w, int target) {
     while (s->len[w] < target) {
-        const int T = std::min(kMaxRows, target - s->len[w]);
+        const int T = std::min(s->ms[w].rows_cap, target - s->len[w]);
         int rc = run_pass(s, w, T, 0, 3);
         if (rc) return rc;
         s->len[w] += T;  // the device advances the same amount
@@ -939,61 +946,64 @@ int run_encoder(bild_state* s, int w) {
     const bild_model_config& c = m->cfg;
     const int d = c.d_model, I = m->inner(), F = c.d_ff, dt = c.dtype, S = s->n_src;
     const float att_scale = 1.f / std::sqrt((float)c.d_head);
-    for (int r0 = 0; r0 < S; r0 += kMaxRows) {
-        const int T = std::min(kMaxRows, S - r0);
+    // every launch covers all S source rows (row blocks of kMaxRows inside the kernels)
+    {
         EmbedArgs e;
-        std::memset(&e, 0, sizeof(e));
-        e.E = m->emb; e.tokens = s->src; e.base_add = r0; e.T = T; e.d = d; e.vocab = c.vocab;
+        std::memset((void*)&e, 0, sizeof(e));
+        e.E = m->emb; e.tokens = s->src; e.T = S; e.d = d; e.vocab = c.vocab;
         e.tie_shift = c.tie_shift; e.sinusoidal = c.pos == BILD_POS_SINUSOIDAL; e.embed_scale = c.embed_scale;
-        e.x = M.enc_x + (size_t)r0 * d;
+        e.x = M.enc_x;
         HIPC(launch_embed(e, dt, s->stream));
     }
     for (int l = 0; l < c.n_enc_layers; ++l) {
         const LayerW& L = m->enc[l];
-        for (int r0 = 0; r0 < S; r0 += kMaxRows) {
-            const int T = std::min(kMaxRows, S - r0);
-            GemmArgs g = gemm_base(m, L.wqkv, M.enc_x + (size_t)r0 * d, d, T, L.ln1);
+        {
+            GemmArgs g = gemm_base(m, L.wqkv, M.enc_x, d, S, L.ln1);
             g.epi = EPI_QKV;
             g.q_dim = I;
-            g.q_out = M.enc_q + (size_t)r0 * I;
+            g.q_out = M.enc_q;
             g.k_cache = M.enc_k;
             g.v_cache = M.enc_v;
             g.vcap = s->cap_src;
-            g.pos_add = r0;
             g.rope = c.pos == BILD_POS_ROPE;
             int rc = run_gemm(s, m, g);
             if (rc) return rc;
         }
-        for (int r0 = 0; r0 < S; r0 += kMaxRows) {
-            const int T = std::min(kMaxRows, S - r0);
+        {
             AttnArgs a;
-            std::memset(&a, 0, sizeof(a));
-            a.q = M.enc_q + (size_t)r0 * I; a.k = M.enc_k; a.v = M.enc_v; a.out = M.a;
-            a.T = T; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
+            std::memset((void*)&a, 0, sizeof(a));
+            a.q = M.enc_q; a.k = M.enc_k; a.v = M.enc_v; a.out = M.enc_a;
+            a.T = S; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
             a.causal = 0;
             a.nkeys_fixed = S;
             a.vcap = s->cap_src;
             a.splits = 1;
-            a.nw = pick_attn_waves(dt, c.d_head, T, S, 1);
+            a.nw = pick_attn_waves(dt, c.d_head, std::min(S, kMaxRows), S, 1);
             a.scale = att_scale;
             HIPC(launch_attention(a, dt, s->stream));
-            GemmArgs g = gemm_base(m, L.wo, M.a, I, T, nullptr);
+        }
+        {
+            GemmArgs g = gemm_base(m, L.wo, M.enc_a, I, S, nullptr);
             g.epi = EPI_RESID;
-            g.out = M.enc_x + (size_t)r0 * d;
+            g.out = M.enc_x;
             g.ldo = d;
             int rc = run_gemm(s, m, g);
             if (rc) return rc;
-            GemmArgs g1 = gemm_base(m, L.win, M.enc_x + (size_t)r0 * d, d, T, L.ln2);
-            g1.epi = EPI_ACT;
-            g1.out = M.h;
-            g1.ldo = F;
-            rc = run_gemm(s, m, g1);
+        }
+        {
+            GemmArgs g = gemm_base(m, L.win, M.enc_x, d, S, L.ln2);
+            g.epi = EPI_ACT;
+            g.out = M.enc_h;
+            g.ldo = F;
+            int rc = run_gemm(s, m, g);
             if (rc) return rc;
-            GemmArgs g2 = gemm_base(m, L.wout, M.h, F, T, nullptr);
-            g2.epi = EPI_RESID;
-            g2.out = M.enc_x + (size_t)r0 * d;
-            g2.ldo = d;
-            rc = run_gemm(s, m, g2);
+        }
+        {
+            GemmArgs g = gemm_base(m, L.wout, M.enc_h, F, S, nullptr);
+            g.epi = EPI_RESID;
+            g.out = M.enc_x;
+            g.ldo = d;
+            int rc = run_gemm(s, m, g);
             if (rc) return rc;
         }
     }
@@ -1006,21 +1016,17 @@ int run_encoder(bild_state* s, int w) {
         const int Iu = mu->inner();
         const size_t esz = mu->esz();
         for (int l = 0; l < mu->cfg.n_dec_layers; ++l) {
-            for (int r0 = 0; r0 < S; r0 += kMaxRows) {
-                const int T = std::min(kMaxRows, S - r0);
-                GemmArgs g = gemm_base(mu, mu->dec[l].cwkv, M.enc_x + (size_t)r0 * d, d, T, m->enc_final);
-                g.eps = m->cfg.norm_eps;
-                g.epi = EPI_QKV;
-                g.q_dim = 0;
-                g.i_dim = Iu;
-                g.k_cache = U.ck + (size_t)l * s->cap_src * Iu * esz;
-                g.v_cache = U.cv + (size_t)l * s->cap_src * Iu * esz;
-                g.vcap = s->cap_src;
-                g.pos_add = r0;
-                g.rope = 0;
-                int rc = run_gemm(s, mu, g);
-                if (rc) return rc;
-            }
+            GemmArgs g = gemm_base(mu, mu->dec[l].cwkv, M.enc_x, d, S, m->enc_final);
+            g.eps = m->cfg.norm_eps;
+            g.epi = EPI_QKV;
+            g.q_dim = 0;
+            g.i_dim = Iu;
+            g.k_cache = U.ck + (size_t)l * s->cap_src * Iu * esz;
+            g.v_cache = U.cv + (size_t)l * s->cap_src * Iu * esz;
+            g.vcap = s->cap_src;
+            g.rope = 0;
+            int rc = run_gemm(s, mu, g);
+            if (rc) return rc;
         }
     }
     return BILD_OK;

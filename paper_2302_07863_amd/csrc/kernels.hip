@@ -602,6 +602,22 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     gemm_body<DT, RW, EPI, ROPE, NT>(a, (int)blockIdx.x, smem);
 }
 
+// More than kMaxRows rows (encoder, prompt prefill): blockIdx.y picks a block of kMaxRows rows and the same
+// body runs on it.  The blocks of one feature group re-read its weight tiles, which by then sit in L2 or
+// the memory-side cache, so HBM still streams every weight about once.
+template <int DT, int RW, int EPI, int ROPE>
+__global__ __launch_bounds__(512) void gemm_rows_kernel(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    GemmArgs b = a;
+    const int r0 = (int)blockIdx.y * kMaxRows;
+    b.T = min(kMaxRows, a.T - r0);
+    b.x = a.x + (size_t)r0 * a.ldx;
+    if (a.out) b.out = a.out + (size_t)r0 * a.ldo;
+    if (a.q_out) b.q_out = a.q_out + (size_t)r0 * a.i_dim;
+    b.pos_add = a.pos_add + r0;
+    gemm_body<DT, RW, EPI, ROPE, 2>(b, (int)blockIdx.x, smem);
+}
+
 #ifndef BILD_DEVICE_ONLY
 // Rows-per-wave, chunk length and tiles per chunk of a GEMM: what both launch-shape rules start from.
 static int gemm_pick_chunks(GemmArgs& a, int dtype) {
@@ -609,7 +625,8 @@ static int gemm_pick_chunks(GemmArgs& a, int dtype) {
     const bool gated = a.epi == EPI_ACT && a.act != BILD_ACT_RELU;
     a.rw = gated ? 2 : 1;
     // input chunks staged in LDS: at most 96 KiB, balanced so that every chunk has the same tile count +-1
-    int kc_max = 24576 / a.T - 8;
+    const int Tb = std::min(a.T, kMaxRows);  // rows one workgroup handles (more rows: more row blocks)
+    int kc_max = 24576 / Tb - 8;
     kc_max = std::max(128, (kc_max / 128) * 128);
     const int nch = (a.W.k + kc_max - 1) / kc_max;
     const int kc = ((a.W.k + nch - 1) / nch + kt - 1) / kt * kt;
@@ -620,11 +637,12 @@ static int gemm_pick_chunks(GemmArgs& a, int dtype) {
 
 void gemm_pick_shape(GemmArgs& a, int dtype) {
     const int tiles_chunk = gemm_pick_chunks(a, dtype);
-    const int nacc = a.rw * ((a.T + 15) / 16);
+    const int Tb = std::min(a.T, kMaxRows);
+    const int nacc = a.rw * ((Tb + 15) / 16);
     // input slices per workgroup.  Latency rule (small matrices): at most one batch of tiles per wave.
     // Parallelism rule (large ones): no more slices than it takes to field about 1536 waves, so that a
     // wave streams a long contiguous run (measured best on 32128x1024, 22016x4096 and 4096x11008).
-    const int batch = gemm_batch(a.rw, (a.T + 15) / 16);
+    const int batch = gemm_batch(a.rw, (Tb + 15) / 16);
     int wk_lat = 1, wk_par = 1;
     while (wk_lat < 8 && a.W.tk / wk_lat > batch) wk_lat *= 2;
     while (wk_par < 8 && (long)a.W.tn * wk_par < 1536) wk_par *= 2;
@@ -633,8 +651,9 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     // feature groups: as many as keep >= 512 workgroups; at least 4 waves per workgroup, 8 when there are
     // several rows (staging the activations is then the longer part, and it is shared by all waves)
     int wr = std::max(1, (a.T >= 4 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
+    const int row_blocks = (a.T + kMaxRows - 1) / kMaxRows;
     for (int c = wr * 2; c * wk <= 8 && c * wk * nacc <= 32; c *= 2)
-        if ((a.W.tn + c * a.rw - 1) / (c * a.rw) >= 512) wr = c;
+        if ((a.W.tn + c * a.rw - 1) / (c * a.rw) * row_blocks >= 512) wr = c;
     a.wk = wk;
     a.nwv = wk * wr;
 }
@@ -650,8 +669,9 @@ void gemm_pick_shape_resident(GemmArgs& a, int dtype, int G) {
 }
 
 size_t gemm_lds_bytes(const GemmArgs& a, int dtype) {
-    const int nacc = a.rw * ((a.T + 15) / 16);
-    return (size_t)xs_bytes(dtype, a.kc, a.T) + gemm_tail_bytes(a.nwv, nacc);
+    const int Tb = std::min(a.T, kMaxRows);
+    const int nacc = a.rw * ((Tb + 15) / 16);
+    return (size_t)xs_bytes(dtype, a.kc, Tb) + gemm_tail_bytes(a.nwv, nacc);
 }
 
 size_t gemm_num_blocks(const GemmArgs& a) {
@@ -661,6 +681,8 @@ size_t gemm_num_blocks(const GemmArgs& a) {
 
 template <int DT, int DH32>
 __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a);
+template <int DT, int DH32>
+__global__ __launch_bounds__(512) void attn_rows_kernel(const AttnArgs a);
 
 // The big kernels may ask for more than the default 64 KiB of dynamic LDS.
 static hipError_t raise_lds_limits() {
@@ -671,13 +693,21 @@ static hipError_t raise_lds_limits() {
     (const void*)gemm_kernel<DTV, 1, EPI_QKV, 0, NTV>, (const void*)gemm_kernel<DTV, 1, EPI_QKV, 1, NTV>, \
     (const void*)gemm_kernel<DTV, 1, EPI_ACT, 0, NTV>, (const void*)gemm_kernel<DTV, 2, EPI_ACT, 0, NTV>, \
     (const void*)gemm_kernel<DTV, 1, EPI_LMHEAD, 0, NTV>
-#define BILD_G(DTV) BILD_G1(DTV, 1), BILD_G1(DTV, 2)
+#define BILD_G(DTV) BILD_G1(DTV, 1), BILD_G1(DTV, 2), BILD_R(DTV)
+#define BILD_R(DTV) \
+    (const void*)gemm_rows_kernel<DTV, 1, EPI_STORE, 0>, (const void*)gemm_rows_kernel<DTV, 1, EPI_RESID, 0>, \
+    (const void*)gemm_rows_kernel<DTV, 1, EPI_QKV, 0>, (const void*)gemm_rows_kernel<DTV, 1, EPI_QKV, 1>, \
+    (const void*)gemm_rows_kernel<DTV, 1, EPI_ACT, 0>, (const void*)gemm_rows_kernel<DTV, 2, EPI_ACT, 0>
         const void* fns[] = {BILD_G(0), BILD_G(1),
+                             (const void*)attn_rows_kernel<0, 1>, (const void*)attn_rows_kernel<0, 2>,
+                             (const void*)attn_rows_kernel<0, 4>, (const void*)attn_rows_kernel<1, 1>,
+                             (const void*)attn_rows_kernel<1, 2>, (const void*)attn_rows_kernel<1, 4>,
                              (const void*)attn_kernel<0, 1>, (const void*)attn_kernel<0, 2>,
                              (const void*)attn_kernel<0, 4>, (const void*)attn_kernel<1, 1>,
                              (const void*)attn_kernel<1, 2>, (const void*)attn_kernel<1, 4>};
 #undef BILD_G1
 #undef BILD_G
+#undef BILD_R
         for (const void* f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
             if (e != hipSuccess) return e;
@@ -711,10 +741,14 @@ hipError_t launch_pass(const PassArgs& p, int dtype, int T, int d_head, int G, s
 hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
     const size_t smem = gemm_lds_bytes(a, dtype);
-    const dim3 grid((unsigned)gemm_num_blocks(a)), block(64 * a.nwv);
+    const unsigned row_blocks = (unsigned)((a.T + kMaxRows - 1) / kMaxRows);
+    if (row_blocks > 1 && a.epi == EPI_LMHEAD) return hipErrorInvalidValue;  // softmax partials are per pass
+    const dim3 grid((unsigned)gemm_num_blocks(a), row_blocks), block(64 * a.nwv);
 #define BILD_L(DTV, RWV, EPIV, ROPEV)                                                              \
     do {                                                                                            \
-        if (a.T > 16)                                                                               \
+        if (row_blocks > 1)                                                                         \
+            hipLaunchKernelGGL((gemm_rows_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a); \
+        else if (a.T > 16)                                                                          \
             hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 2>), grid, block, smem, st, a);  \
         else                                                                                        \
             hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 1>), grid, block, smem, st, a);  \
@@ -729,7 +763,12 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
         case EPI_ACT:                                                            \
             if (a.rw == 2) BILD_L(DTV, 2, EPI_ACT, 0); else BILD_L(DTV, 1, EPI_ACT, 0); \
             break;                                                               \
-        case EPI_LMHEAD: BILD_L(DTV, 1, EPI_LMHEAD, 0); break;                   \
+        case EPI_LMHEAD:                                                         \
+            if (a.T > 16)                                                        \
+                hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPI_LMHEAD, 0, 2>), grid, block, smem, st, a); \
+            else                                                                 \
+                hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPI_LMHEAD, 0, 1>), grid, block, smem, st, a); \
+            break;                                                               \
         default: return hipErrorInvalidValue;                                    \
     }
     if (dtype) { BILD_D(1) } else { BILD_D(0) }
@@ -1023,6 +1062,19 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
     attn_body<DT, DH32>(a, (int)(blockIdx.x + blockIdx.y * gridDim.x), smem);
 }
 
+// More than kMaxRows query rows: blockIdx.z picks the block of rows (key splits are not combined with it).
+template <int DT, int DH32>
+__global__ __launch_bounds__(512) void attn_rows_kernel(const AttnArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    AttnArgs b = a;
+    const int r0 = (int)blockIdx.z * kMaxRows;
+    b.T = min(kMaxRows, a.T - r0);
+    b.q = a.q + (size_t)r0 * a.i_dim;
+    b.out = a.out + (size_t)r0 * a.i_dim;
+    b.base_add = a.base_add + r0;
+    attn_body<DT, DH32>(b, (int)blockIdx.x, smem);
+}
+
 template <bool COH = false, class A>
 __device__ __forceinline__ void attn_merge_body(const A& a, const int t) {
     const int I = a.i_dim;
@@ -1054,9 +1106,17 @@ size_t attn_lds_bytes(int dtype, int d_head, int T, int nw) {
 hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
     if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
     const int dh32 = a.d_head <= 32 ? 1 : (a.d_head <= 64 ? 2 : 4);
-    const size_t smem = attn_lds_bytes(dtype, a.d_head, a.T, a.nw);
-    const dim3 grid(a.heads, a.splits), block(64 * a.nw);
-#define BILD_ATTN(DTV, DHV) hipLaunchKernelGGL((attn_kernel<DTV, DHV>), grid, block, smem, st, a)
+    const unsigned row_blocks = (unsigned)((a.T + kMaxRows - 1) / kMaxRows);
+    if (row_blocks > 1 && a.splits != 1) return hipErrorInvalidValue;
+    const size_t smem = attn_lds_bytes(dtype, a.d_head, std::min(a.T, kMaxRows), a.nw);
+    const dim3 grid(a.heads, a.splits, row_blocks), block(64 * a.nw);
+#define BILD_ATTN(DTV, DHV)                                                               \
+    do {                                                                                  \
+        if (row_blocks > 1)                                                               \
+            hipLaunchKernelGGL((attn_rows_kernel<DTV, DHV>), grid, block, smem, st, a);   \
+        else                                                                              \
+            hipLaunchKernelGGL((attn_kernel<DTV, DHV>), grid, block, smem, st, a);        \
+    } while (0)
     if (dtype) {
         if (dh32 == 1) BILD_ATTN(1, 1); else if (dh32 == 2) BILD_ATTN(1, 2); else BILD_ATTN(1, 4);
     } else {
@@ -1068,7 +1128,6 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
     hipLaunchKernelGGL(attn_merge_kernel, dim3(a.T), dim3(256), 0, st, a);
     return hipGetLastError();
 }
-
 #endif  // BILD_DEVICE_ONLY
 
 // =====================================================================================
