@@ -648,12 +648,22 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     while (wk_par < 8 && (long)a.W.tn * wk_par < 1536) wk_par *= 2;
     int wk = std::min(wk_lat, wk_par);
     while (wk > 1 && (wk * nacc > 32 || wk > tiles_chunk)) wk /= 2;
+    const int row_blocks = (a.T + kMaxRows - 1) / kMaxRows;
+    if (row_blocks > 1) {
+        // Many rows: the staged activations are the larger stream, and every feature tile of a workgroup
+        // reuses them, so take as many feature tiles per workgroup (8 waves) as still leave one workgroup
+        // per CU; the remaining waves split the inputs.
+        int wr = 8;
+        while (wr > 1 && ((a.W.tn + wr * a.rw - 1) / (wr * a.rw)) * row_blocks < 256) wr /= 2;
+        a.wk = std::max(1, std::min(8 / wr, tiles_chunk));
+        a.nwv = a.wk * wr;
+        return;
+    }
     // feature groups: as many as keep >= 512 workgroups; at least 4 waves per workgroup, 8 when there are
     // several rows (staging the activations is then the longer part, and it is shared by all waves)
     int wr = std::max(1, (a.T >= 4 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
-    const int row_blocks = (a.T + kMaxRows - 1) / kMaxRows;
     for (int c = wr * 2; c * wk <= 8 && c * wk * nacc <= 32; c *= 2)
-        if ((a.W.tn + c * a.rw - 1) / (c * a.rw) * row_blocks >= 512) wr = c;
+        if ((a.W.tn + c * a.rw - 1) / (c * a.rw) >= 512) wr = c;
     a.wk = wk;
     a.nwv = wk * wr;
 }
