@@ -451,7 +451,7 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         M.nparts_cap = (m->head.tn + 0) / 1 + 1;  // at most one partial per feature tile
         AL(M.part, sizeof(StatPart) * (size_t)M.nparts_cap * kMaxRows);
         AL(M.zt, sizeof(float) * kMaxRows);
-        M.max_splits = std::max(1, std::min(64, (std::max(max_len, max_src) + 511) / 512));
+        M.max_splits = std::max(8, std::min(64, (std::max(max_len, max_src) + 511) / 512));
         AL(M.att_o, sizeof(float) * (size_t)M.max_splits * kMaxRows * I);
         AL(M.att_ml, sizeof(float) * (size_t)M.max_splits * kMaxRows * m->cfg.n_heads * 2);
         if (m->cfg.n_enc_layers > 0) {
@@ -522,14 +522,19 @@ int pull_ctl(bild_state* s) {
     return BILD_OK;
 }
 
-int pick_splits(const ModelState& M, int nkeys, int heads) {
-    // A workgroup streams about 128 KiB of K/V in one memory round trip (measured); beyond that its time
-    // grows with the bytes.  Splitting the keys costs a merge kernel of its own, so split only until a
-    // workgroup's share is down to that size.
+int pick_splits(const ModelState& M, int nkeys, int heads, int T) {
+    // A workgroup's time grows with the K/V bytes it streams (about 2 us for 32 KiB, 3 us for 128 KiB,
+    // then in proportion: a CU sustains under 30 GB/s).  With few rows the partials of a split are merged
+    // for free by the consumer projection, so split down to about 32 KiB per workgroup; otherwise a split
+    // costs a merge kernel and only pays above about 160 KiB.
     const bild_model_config& c = M.m->cfg;
     const size_t per_head = (size_t)nkeys * c.d_head * 2 * M.m->esz();
+    const size_t want = (T <= 4 ? 32 : (T <= 8 ? 64 : 160)) << 10;
     int sp = 1;
-    while (sp < M.max_splits && heads * sp < 512 && per_head / sp > ((size_t)160 << 10)) sp *= 2;
+    while (sp < M.max_splits && heads * sp < 512 && per_head / sp > want) {
+        if (T <= 8 && (sp * 2 * T > 16 || sp * 2 > 8)) break;  // stay within what the consumer merges
+        sp *= 2;
+    }
     return sp;
 }
 
@@ -614,11 +619,18 @@ int emit_gemm(bild_state* s, const bild_model* m, GemmArgs& g, StageSink& sink) 
     return BILD_OK;
 }
 
-int emit_attention(bild_state* s, const ModelState& M, AttnArgs& a, int nkeys, StageSink& sink) {
+// `deferred` receives the number of key splits whose partials the following output projection must merge
+// (1: the attention output is complete).
+int emit_attention(bild_state* s, const ModelState& M, AttnArgs& a, int nkeys, StageSink& sink, int* deferred) {
     const int dt = M.m->cfg.dtype;
+    *deferred = 1;
     if (!sink.prog) {
-        a.splits = a.T > kMaxRows ? 1 : pick_splits(M, nkeys, a.heads);  // row blocks and key splits do not combine
+        a.splits = a.T > kMaxRows ? 1 : pick_splits(M, nkeys, a.heads, a.T);  // row blocks and key splits do not combine
         a.nw = pick_attn_waves(dt, a.d_head, std::min(a.T, kMaxRows), nkeys, a.splits);
+        // few rows and few splits: the projection that consumes the output merges the partials while it
+        // stages them, which saves the merge kernel
+        a.defer_merge = a.splits > 1 && a.splits <= 8 && a.splits * a.T <= 16;
+        if (a.defer_merge) *deferred = a.splits;
         if (!s->gemm_only) HIPC(launch_attention(a, dt, s->stream));
         return BILD_OK;
     }
@@ -678,6 +690,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
         }
     }
     const float att_scale = 1.f / std::sqrt((float)c.d_head);
+    int merge_splits = 1;
     for (int l = 0; l < c.n_dec_layers; ++l) {
         const LayerW& L = m->dec[l];
         char* kc = M.kcache + (size_t)l * s->cap_len * I * esz;
@@ -705,7 +718,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
             a.vcap = s->cap_len;
             a.part_o = M.att_o; a.part_ml = M.att_ml;
             a.scale = att_scale;
-            int rc = emit_attention(s, M, a, key_hint, sink);
+            int rc = emit_attention(s, M, a, key_hint, sink, &merge_splits);
             if (rc) return rc;
         }
         {
@@ -713,6 +726,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
             g.epi = EPI_RESID;
             g.out = M.x;
             g.ldo = d;
+            if (merge_splits > 1) { g.mg_splits = merge_splits; g.mg_o = M.att_o; g.mg_ml = M.att_ml; g.mg_heads = c.n_heads; }
             int rc = emit_gemm(s, m, g, sink);
             if (rc) return rc;
         }
@@ -738,7 +752,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
                 a.nkeys_ptr = &s->ctl->n_src;
                 a.part_o = M.att_o; a.part_ml = M.att_ml;
                 a.scale = att_scale;
-                int rc = emit_attention(s, M, a, s->n_src, sink);
+                int rc = emit_attention(s, M, a, s->n_src, sink, &merge_splits);
                 if (rc) return rc;
             }
             {
@@ -746,6 +760,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
                 g.epi = EPI_RESID;
                 g.out = M.x;
                 g.ldo = d;
+                if (merge_splits > 1) { g.mg_splits = merge_splits; g.mg_o = M.att_o; g.mg_ml = M.att_ml; g.mg_heads = c.n_heads; }
                 int rc = emit_gemm(s, m, g, sink);
                 if (rc) return rc;
             }

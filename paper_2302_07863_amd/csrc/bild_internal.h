@@ -96,6 +96,12 @@ struct GemmArgs {
     float* zt;           // [kMaxRows] logit of each row's target
     float* dbg;          // nullable [T][vocab] full logits (tests only)
     int row_off;         // row index of x row 0 within the pass (for part / zt / dbg / targets)
+    // x given as key-split attention partials (mg_splits > 1): x[t][n] = sum_s w_s O_s[t][n] / sum_s w_s L_s,
+    // w_s = exp(m_s - max_s m_s), with (m_s, L_s) per (row, head n / d_head); the GEMM merges them while staging
+    int mg_splits;
+    const float* mg_o;   // [mg_splits][T][ldx] unnormalised outputs
+    const float* mg_ml;  // [mg_splits][T][mg_heads][2]
+    int mg_heads;
     // launch shape
     int wk;   // input slices per workgroup
     int nwv;  // waves per workgroup = wk * feature groups (4 or 8)
@@ -119,6 +125,7 @@ struct AttnArgs {
     const int* nkeys_ptr;      // non-causal: number of keys = *nkeys_ptr (or nkeys_fixed if null)
     int nkeys_fixed;
     int splits;                // key ranges handled by separate workgroups
+    int defer_merge;           // splits > 1: leave the partials for the consumer GEMM to merge (no merge kernel)
     float* part_o;             // [splits][T][I]   unnormalised partial outputs
     float* part_ml;            // [splits][T][heads][2] (max, sum)
     float scale;

@@ -194,12 +194,13 @@ __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
 // launches, a loop index in the persistent pass kernel); `smem` is the workgroup's dynamic LDS.
 // The argument block may live in the kernel-argument segment or (persistent kernel) in constant-address-space
 // device memory, hence the template parameter A.
-template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, NT), bool COH = false, class A>
+template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, NT), bool COH = false, bool MG = false,
+          bool ONE = false, class A>
 __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* smem) {
     constexpr int KT = DT ? 32 : 16;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthr = blockDim.x, NWV = nthr >> 6;
-    const int T = a.T, K = a.W.k, KC = a.kc;
+    const int T = ONE ? 1 : a.T, K = a.W.k, KC = a.kc;
     const int WK = a.wk, WR = NWV / WK;
     const int wkid = wave % WK, wrid = wave / WK;
     const int tile0 = (vblock * WR + wrid) * RW;
@@ -324,6 +325,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
         if (k0) __syncthreads();  // readers of the previous chunk are done
         // ---- stage x[:, k0 : k0+kc_len] (times the norm gain) into LDS ----
         const int n4 = kc_len >> 2;
+        auto ldx = [&](int t, int k4) -> float4 { return ld_act4<COH>(a.x + (size_t)t * a.ldx + k0 + k4 * 4); };
         // writes one float4 of row t and returns its sum of squares (for the RMSNorm)
         auto put = [&](int t, int k4, float4 w, const float4& gg) -> float {
             float ss = 0.f;
@@ -342,7 +344,51 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             }
             return ss;
         };
-        if (T > 1 && (n4 & 63) == 0) {
+        if (MG && a.mg_splits > 1) {
+            // x arrives as key-split attention partials (no norm in front of an output projection): every
+            // piece is sum_s w_s O_s / sum_s w_s L_s with w_s = exp(m_s - max m) of its (row, head)
+            const int total = T * n4;
+            const unsigned magic = 0xFFFFFFFFu / (unsigned)n4 + 1u;
+            const int S = a.mg_splits;  // at most 8
+            for (int e = tid; e < total; e += nthr) {
+                const int t = (int)__umulhi((unsigned)e, magic), k4 = e - t * n4;
+                const int kk = k0 + k4 * 4;
+                const float* ml = a.mg_ml + ((size_t)t * a.mg_heads + kk / a.d_head) * 2;
+                const size_t ml_stride = (size_t)T * a.mg_heads * 2, o_stride = (size_t)T * a.ldx;
+                const float* op = a.mg_o + (size_t)t * a.ldx + kk;
+                float m[8];
+                float M = -INFINITY;
+#pragma unroll
+                for (int sp = 0; sp < 8; ++sp) {
+                    m[sp] = sp < S ? ld_act<COH>(ml + min(sp, S - 1) * ml_stride) : -INFINITY;
+                    M = fmaxf(M, m[sp]);
+                }
+                float L = 0.f;
+                float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int g4 = 0; g4 < 2; ++g4) {
+                    if (g4 * 4 < S) {
+                        float l[4];
+                        float4 o[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int sc = min(g4 * 4 + u, S - 1);
+                            l[u] = ld_act<COH>(ml + sc * ml_stride + 1);
+                            o[u] = ld_act4<COH>(op + sc * o_stride);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const float mm = m[g4 * 4 + u];
+                            const float w = (mm == -INFINITY) ? 0.f : expf(mm - M);
+                            L += l[u] * w;
+                            r.x += o[u].x * w; r.y += o[u].y * w; r.z += o[u].z * w; r.w += o[u].w * w;
+                        }
+                    }
+                }
+                const float inv = 1.f / L;
+                put(t, k4, make_float4(r.x * inv, r.y * inv, r.z * inv, r.w * inv), r);
+            }
+        } else if (T > 1 && (n4 & 63) == 0) {
             // Several rows whose chunk is a whole number of wavefront-wide pieces: the rows are laid end to
             // end and dealt to all threads, which spreads the conversion work evenly and lets one round of
             // loads (8 per thread, issued together) cover 8 * nthr pieces; 64 consecutive pieces share a row.
@@ -354,7 +400,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                 for (int u = 0; u < 8; ++u) {
                     const int e = min(eb + u * nthr, total - 1);
                     const int t = (int)__umulhi((unsigned)e, magic), k4 = e - t * n4;
-                    v[u] = ld_act4<COH>(a.x + (size_t)t * a.ldx + k0 + k4 * 4);
+                    v[u] = ldx(t, k4);
                     g[u] = norm ? *(const float4*)(a.gain + k0 + k4 * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
 #pragma unroll
@@ -376,14 +422,13 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             for (int j = 0; j < 8; ++j) {
                 const int t = few ? j : wave + NWV * j;
                 if (t >= T) break;  // wave-uniform
-                const float* xr = a.x + (size_t)t * a.ldx + k0;
                 const int start = few ? tid : lane, step = few ? nthr : 64;
                 float ssj = 0.f;
                 if (n4 <= 2 * step) {  // short rows: at most two elements per thread
                     const int ka = start, kb2 = start + step;
                     float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va, ga = va, gb = va;
-                    if (ka < n4) { va = ld_act4<COH>(xr + ka * 4); if (norm) ga = *(const float4*)(a.gain + k0 + ka * 4); }
-                    if (kb2 < n4) { vb = ld_act4<COH>(xr + kb2 * 4); if (norm) gb = *(const float4*)(a.gain + k0 + kb2 * 4); }
+                    if (ka < n4) { va = ldx(t, ka); if (norm) ga = *(const float4*)(a.gain + k0 + ka * 4); }
+                    if (kb2 < n4) { vb = ldx(t, kb2); if (norm) gb = *(const float4*)(a.gain + k0 + kb2 * 4); }
                     if (ka < n4) ssj += put(t, ka, va, ga);
                     if (kb2 < n4) ssj += put(t, kb2, vb, gb);
                 } else {
@@ -392,7 +437,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
 #pragma unroll
                         for (int u = 0; u < 8; ++u) {  // all loads of the round first
                             const int k4 = min(kb + u * step, n4 - 1);
-                            v[u] = ld_act4<COH>(xr + k4 * 4);
+                            v[u] = ldx(t, k4);
                             g[u] = norm ? *(const float4*)(a.gain + k0 + k4 * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
                         }
 #pragma unroll
@@ -602,6 +647,21 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     gemm_body<DT, RW, EPI, ROPE, NT>(a, (int)blockIdx.x, smem);
 }
 
+// The single-row pass (the small model's step, the large model's plain step): the row count is a
+// compile-time 1, which removes the multi-row staging paths from the code.
+template <int DT, int RW, int EPI, int ROPE>
+__global__ __launch_bounds__(512) void gemm_row_kernel(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    gemm_body<DT, RW, EPI, ROPE, 1, gemm_batch(RW, 1), false, false, true>(a, (int)blockIdx.x, smem);
+}
+
+// Output projection whose input is still in key-split attention partials (merged while staging).
+template <int DT, int NT>
+__global__ __launch_bounds__(512) void gemm_merge_kernel(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    gemm_body<DT, 1, EPI_RESID, 0, NT, gemm_batch(1, NT), false, true>(a, (int)blockIdx.x, smem);
+}
+
 // More than kMaxRows rows (encoder, prompt prefill): blockIdx.y picks a block of kMaxRows rows and the same
 // body runs on it.  The blocks of one feature group re-read its weight tiles, which by then sit in L2 or
 // the memory-side cache, so HBM still streams every weight about once.
@@ -705,10 +765,16 @@ static hipError_t raise_lds_limits() {
     (const void*)gemm_kernel<DTV, 1, EPI_LMHEAD, 0, NTV>
 #define BILD_G(DTV) BILD_G1(DTV, 1), BILD_G1(DTV, 2), BILD_R(DTV)
 #define BILD_R(DTV) \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_STORE, 0>, (const void*)gemm_row_kernel<DTV, 1, EPI_RESID, 0>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0>, (const void*)gemm_row_kernel<DTV, 2, EPI_ACT, 0>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0>, \
     (const void*)gemm_rows_kernel<DTV, 1, EPI_STORE, 0>, (const void*)gemm_rows_kernel<DTV, 1, EPI_RESID, 0>, \
     (const void*)gemm_rows_kernel<DTV, 1, EPI_QKV, 0>, (const void*)gemm_rows_kernel<DTV, 1, EPI_QKV, 1>, \
     (const void*)gemm_rows_kernel<DTV, 1, EPI_ACT, 0>, (const void*)gemm_rows_kernel<DTV, 2, EPI_ACT, 0>
         const void* fns[] = {BILD_G(0), BILD_G(1),
+                             (const void*)gemm_merge_kernel<0, 1>, (const void*)gemm_merge_kernel<0, 2>,
+                             (const void*)gemm_merge_kernel<1, 1>, (const void*)gemm_merge_kernel<1, 2>,
                              (const void*)attn_rows_kernel<0, 1>, (const void*)attn_rows_kernel<0, 2>,
                              (const void*)attn_rows_kernel<0, 4>, (const void*)attn_rows_kernel<1, 1>,
                              (const void*)attn_rows_kernel<1, 2>, (const void*)attn_rows_kernel<1, 4>,
@@ -753,11 +819,25 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     const size_t smem = gemm_lds_bytes(a, dtype);
     const unsigned row_blocks = (unsigned)((a.T + kMaxRows - 1) / kMaxRows);
     if (row_blocks > 1 && a.epi == EPI_LMHEAD) return hipErrorInvalidValue;  // softmax partials are per pass
+    if (a.mg_splits > 1) {
+        if (a.mg_splits > 8 || a.gain || row_blocks > 1 || a.epi != EPI_RESID || a.rw != 1) return hipErrorInvalidValue;
+        const dim3 grid1((unsigned)gemm_num_blocks(a)), block1(64 * a.nwv);
+        if (dtype) {
+            if (a.T > 16) hipLaunchKernelGGL((gemm_merge_kernel<1, 2>), grid1, block1, smem, st, a);
+            else hipLaunchKernelGGL((gemm_merge_kernel<1, 1>), grid1, block1, smem, st, a);
+        } else {
+            if (a.T > 16) hipLaunchKernelGGL((gemm_merge_kernel<0, 2>), grid1, block1, smem, st, a);
+            else hipLaunchKernelGGL((gemm_merge_kernel<0, 1>), grid1, block1, smem, st, a);
+        }
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)gemm_num_blocks(a), row_blocks), block(64 * a.nwv);
 #define BILD_L(DTV, RWV, EPIV, ROPEV)                                                              \
     do {                                                                                            \
         if (row_blocks > 1)                                                                         \
             hipLaunchKernelGGL((gemm_rows_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a); \
+        else if (a.T == 1)                                                                          \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a); \
         else if (a.T > 16)                                                                          \
             hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 2>), grid, block, smem, st, a);  \
         else                                                                                        \
@@ -774,7 +854,9 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
             if (a.rw == 2) BILD_L(DTV, 2, EPI_ACT, 0); else BILD_L(DTV, 1, EPI_ACT, 0); \
             break;                                                               \
         case EPI_LMHEAD:                                                         \
-            if (a.T > 16)                                                        \
+            if (a.T == 1)                                                        \
+                hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0>), grid, block, smem, st, a); \
+            else if (a.T > 16)                                                   \
                 hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPI_LMHEAD, 0, 2>), grid, block, smem, st, a); \
             else                                                                 \
                 hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPI_LMHEAD, 0, 1>), grid, block, smem, st, a); \
@@ -1134,7 +1216,7 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
     }
 #undef BILD_ATTN
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || a.splits == 1) return e;
+    if (e != hipSuccess || a.splits == 1 || a.defer_merge) return e;
     hipLaunchKernelGGL(attn_merge_kernel, dim3(a.T), dim3(256), 0, st, a);
     return hipGetLastError();
 }
