@@ -74,6 +74,7 @@ def main() -> int:
     encode_ms = (time.perf_counter() - t0) * 1e3
 
     if args.pmc_probe:
+        st.gemm_tally(reset=True)          # count the decode GEMMs only (the encoder's row-block GEMMs are another kernel)
         st.probe_copy(1 << 30, 3)          # bild::probe_copy_kernel: reads 1 GiB and writes 1 GiB per launch
         for _ in range(args.steps):
             st.seq_truncate(n0)
@@ -143,7 +144,9 @@ def main() -> int:
         for line in open(pmc_file):
             if line.startswith("traffic_bytes_per_launch="):
                 traffic = int(line.split("=")[1])
-    roofline = dict(bound="hbm", kernel="bild::gemm_kernel<bf16,...>" if cfg.large.dtype == bi.DT_BF16 else "bild::gemm_kernel<f32,...>",
+    # one device function behind three thin launch wrappers (any rows / one row / merging attention partials)
+    roofline = dict(bound="hbm", kernel="bild::gemm_kernel, gemm_row_kernel, gemm_merge_kernel (one body, %s)" %
+                    ("bf16" if cfg.large.dtype == bi.DT_BF16 else "f32"),
                     achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
                     traffic=traffic, launches_per_step=tot_l, mean_launch_us=round(tot_ms / tot_l * 1e3, 3),
                     mean_bytes_per_launch=int(tot_b / tot_l),

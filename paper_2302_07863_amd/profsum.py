@@ -17,9 +17,18 @@ import sys
 PROBE_BYTES = 1 << 30
 
 
+# The decode GEMM is one device function behind three launch wrappers (any row count, exactly one row,
+# input still in key-split attention partials); they are summed under one name.  The encoder / prefill
+# wrapper (row blocks, bild::gemm_rows_kernel) works in another regime and stays separate.
+_DECODE_GEMM = ("bild::gemm_kernel", "bild::gemm_row_kernel", "bild::gemm_merge_kernel")
+
+
 def _group(name: str) -> str:
     name = name.split("(")[0].replace("void ", "").strip()
-    return re.sub(r"<.*>$", "<*>", name)
+    base = re.sub(r"<.*>$", "", name)
+    if base in _DECODE_GEMM:
+        return "bild::gemm_kernel<*>"
+    return base + "<*>" if "<" in name else name
 
 
 def stats(path: str) -> str:
