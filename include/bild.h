@@ -27,6 +27,16 @@
  *                     into its KV cache (cache row p holds K/V of y[p])
  * A pass of a model consumes rows y[len..y_len) at positions len.. and yields,
  * for each row, the distribution of the token that follows it.
+ *
+ * Environment (read when a bild_state is created)
+ *   BILD_NO_GRAPH=1      launch every kernel of a pass directly instead of replaying a captured
+ *                        HIP graph (needed under rocprofv3, which cannot follow graph launches)
+ *   BILD_RESIDENT=1      run embedding + layers of a pass in ONE persistent kernel with grid
+ *                        barriers (experimental, slower on this chip; BILD_RESIDENT_G sets the
+ *                        number of resident workgroups, BILD_BARRIER_SPIN the polls a barrier
+ *                        wait may take, -1 = give up at once).  A barrier that gives up ends the
+ *                        kernel normally and the call returns BILD_EHIP; the request must then be
+ *                        encoded again.
  */
 #ifndef BILD_H
 #define BILD_H
@@ -41,7 +51,7 @@ extern "C" {
 #define BILD_EINVAL (-1) /* bad argument (null pointer, size out of range, token id >= vocab, unsupported shape) */
 #define BILD_ESTATE (-2) /* call not valid in the current state (e.g. step before encode, nothing to consume) */
 #define BILD_ECAP   (-3) /* capacity exceeded (source longer than max_src, sequence longer than max_len, n > max rows) */
-#define BILD_EHIP   (-4) /* a HIP runtime call failed */
+#define BILD_EHIP   (-4) /* a HIP runtime call failed, or a grid barrier of the persistent kernel gave up */
 #define BILD_ENOMEM (-5) /* host or device allocation failed */
 
 #define BILD_ACT_RELU        0 /* relu(x W_in) W_out                       */

@@ -410,7 +410,8 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         // BILD_RESIDENT=1 runs the layers of a pass in the persistent kernel instead of one kernel per
         // stage.  Off by default: on this chip a workgroup streams at most about 28 GB/s, so bandwidth
         // needs all 256 CUs, and a grid barrier over that many workgroups plus the cross-XCD hand-over of
-        // the activations costs more than a kernel boundary does (measured; see the design notes).
+        // the activations costs more than a kernel boundary does (measured: 2.7 ms against 1.2 ms per
+        // T5-large-shaped pass).
         const char* e = std::getenv("BILD_RESIDENT");
         const char* eg = std::getenv("BILD_RESIDENT_G");
         const char* es = std::getenv("BILD_BARRIER_SPIN");
@@ -651,7 +652,7 @@ int emit_attention(bild_state* s, const ModelState& M, AttnArgs& a, int nkeys, S
     sink.prog->push_back(st);
     if (sp > 1) {
         st.kind = ST_ATTN_MERGE;
-        st.nblocks = a.T;
+        st.nblocks = (a.T * (a.i_dim / 4) + 255) / 256;
         sink.prog->push_back(st);
     }
     return BILD_OK;

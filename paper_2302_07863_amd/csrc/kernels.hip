@@ -1,11 +1,15 @@
 // HIP kernels of the BiLD decoding path for gfx950 (CDNA4, wave64).
 //
-//   gemm_kernel      weight-streaming skinny GEMM  y[T][N] = f(x[T][K]) W^T for T <= 32 rows
+//   gemm_body        weight-streaming skinny GEMM  y[T][N] = f(x[T][K]) W^T for T <= 32 rows
 //                    (T = 1: the small model's autoregressive step; T = n+1: the large
 //                    model's non-autoregressive review, Section 3.2), with the RMSNorm of
 //                    the input fused in front and the consumer (K/V cache append + RoPE,
 //                    activation, residual add, LM-head softmax statistics) fused behind.
-//   attn_kernel      KV-cache attention for T query rows of one head.
+//                    Launched as gemm_kernel (any T <= 32), gemm_row_kernel (T = 1 at compile
+//                    time), gemm_merge_kernel (input still in key-split attention partials)
+//                    and gemm_rows_kernel (encoder / prompt prefill: blocks of 32 rows).
+//   attn_body        KV-cache attention for T query rows of one head (attn_kernel; attn_rows_kernel
+//                    for more than 32 query rows; attn_merge_kernel joins key splits).
 //   embed_kernel     embedding gather + sinusoidal position.
 //   finish_kernel    merges the LM-head partial statistics and applies the fallback /
 //                    rollback policy (Sections 3.3, 3.4; Algorithm 1), committing y and
@@ -1167,23 +1171,48 @@ __global__ __launch_bounds__(512) void attn_rows_kernel(const AttnArgs a) {
     attn_body<DT, DH32>(b, (int)blockIdx.x, smem);
 }
 
+// Joins the key splits of attention: out[t][n] = sum_s w_s O_s[t][n] / sum_s w_s L_s with w_s = exp(m_s - max m) of
+// (row t, head of n).  Unit `u` covers 256 float4 pieces of the [T][I] output; every thread owns one piece and issues
+// the loads of all splits together (eight at a time).
 template <bool COH = false, class A>
-__device__ __forceinline__ void attn_merge_body(const A& a, const int t) {
-    const int I = a.i_dim;
-    for (int n = threadIdx.x; n < I; n += blockDim.x) {
-        const int h = n / a.d_head;
-        float M = -INFINITY;
-        for (int sp = 0; sp < a.splits; ++sp) M = fmaxf(M, ld_act<COH>(a.part_ml + (((size_t)sp * a.T + t) * a.heads + h) * 2));
-        float L = 0.f, O = 0.f;
-        for (int sp = 0; sp < a.splits; ++sp) {
-            const float* ml = a.part_ml + (((size_t)sp * a.T + t) * a.heads + h) * 2;
-            const float m0 = ld_act<COH>(ml);
-            const float w = (m0 == -INFINITY) ? 0.f : expf(m0 - M);
-            L += ld_act<COH>(ml + 1) * w;
-            O += ld_act<COH>(a.part_o + ((size_t)sp * a.T + t) * I + n) * w;
-        }
-        st_act<COH>(a.out + (size_t)t * I + n, O / L);
+__device__ __forceinline__ void attn_merge_body(const A& a, const int u) {
+    const int I = a.i_dim, n4 = I >> 2;
+    const int e = u * 256 + (int)threadIdx.x;
+    if (threadIdx.x >= 256 || e >= a.T * n4) return;
+    const int t = e / n4, n = (e - t * n4) * 4;
+    const int h = n / a.d_head;
+    const size_t ml_stride = (size_t)a.T * a.heads * 2, o_stride = (size_t)a.T * I;
+    const float* ml = a.part_ml + ((size_t)t * a.heads + h) * 2;
+    const float* op = a.part_o + (size_t)t * I + n;
+    float M = -INFINITY;
+    for (int s0 = 0; s0 < a.splits; s0 += 8) {
+        float m[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) m[k] = ld_act<COH>(ml + min(s0 + k, a.splits - 1) * ml_stride);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) M = fmaxf(M, m[k]);
     }
+    float L = 0.f;
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = 0; s0 < a.splits; s0 += 8) {
+        float m[8], l[8];
+        float4 o[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int sc = min(s0 + k, a.splits - 1);
+            m[k] = ld_act<COH>(ml + sc * ml_stride);
+            l[k] = ld_act<COH>(ml + sc * ml_stride + 1);
+            o[k] = ld_act4<COH>(op + sc * o_stride);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float w = (s0 + k < a.splits && m[k] != -INFINITY) ? expf(m[k] - M) : 0.f;
+            L += l[k] * w;
+            r.x += o[k].x * w; r.y += o[k].y * w; r.z += o[k].z * w; r.w += o[k].w * w;
+        }
+    }
+    const float inv = 1.f / L;
+    st_act4<COH>(a.out + (size_t)t * I + n, make_float4(r.x * inv, r.y * inv, r.z * inv, r.w * inv));
 }
 
 #ifndef BILD_DEVICE_ONLY
@@ -1217,7 +1246,7 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
 #undef BILD_ATTN
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.splits == 1 || a.defer_merge) return e;
-    hipLaunchKernelGGL(attn_merge_kernel, dim3(a.T), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(attn_merge_kernel, dim3((a.T * (a.i_dim / 4) + 255) / 256), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 #endif  // BILD_DEVICE_ONLY
@@ -1271,36 +1300,38 @@ hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st) {
 //   mode 4  measurement: merge the statistics, commit nothing
 // =====================================================================================
 // LDS use of finish_body (from the start of the workgroup's LDS)
-constexpr int kFinishLds = 3 * kMaxRows * 4 + 8 * 16;
+constexpr int kFinishLds = 3 * kMaxRows * 4;
 
 __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
     float* rm = (float*)lds;
     float* rsum = rm + kMaxRows;
     int* ridx = (int*)(rsum + kMaxRows);
-    StatPart* wpart = (StatPart*)(ridx + kMaxRows);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthr = blockDim.x, nwv = nthr >> 6;
     Ctl* c = a.ctl;
     if (a.mode != 3) {
-        for (int t = 0; t < a.T; ++t) {  // all threads share each row's partials
+        // rows are dealt to the waves; a wave's lanes share the partials of its row (eight loads in flight
+        // per lane), so the rows of a review merge side by side and a single row costs one round trip
+        for (int t = wave; t < a.T; t += nwv) {
             Stat r = stat_neutral();
-            for (int p = tid; p < a.nparts; p += nthr) {
-                const StatPart sp = a.part[(size_t)p * kMaxRows + a.row_off + t];
-                r = stat_merge(r, Stat{sp.m, sp.s, sp.idx});
+            for (int p0 = lane; p0 < a.nparts; p0 += 64 * 8) {
+                StatPart sp[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    sp[k] = a.part[(size_t)min(p0 + k * 64, a.nparts - 1) * kMaxRows + a.row_off + t];
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (p0 + k * 64 < a.nparts) r = stat_merge(r, Stat{sp[k].m, sp[k].s, sp[k].idx});
             }
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) r = stat_merge(r, stat_shfl_xor(r, o));
-            if (lane == 0) wpart[wave] = StatPart{r.m, r.s, r.idx, 0};
-            __syncthreads();
-            if (tid == 0) {
-                Stat f = stat_neutral();
-                for (int w = 0; w < nwv; ++w) f = stat_merge(f, Stat{wpart[w].m, wpart[w].s, wpart[w].idx});
-                rm[t] = f.m;
-                rsum[t] = f.s;
-                ridx[t] = f.idx;
+            if (lane == 0) {
+                rm[t] = r.m;
+                rsum[t] = r.s;
+                ridx[t] = r.idx;
             }
-            __syncthreads();
         }
+        __syncthreads();
     }
     if (tid == 0) {
         const int w = a.which;
