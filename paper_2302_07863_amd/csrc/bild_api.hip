@@ -523,19 +523,23 @@ int pull_ctl(bild_state* s) {
     return BILD_OK;
 }
 
-int pick_splits(const ModelState& M, int nkeys, int heads, int T) {
-    // A workgroup's time grows with the K/V bytes it streams (about 2 us for 32 KiB, 3 us for 128 KiB,
-    // then in proportion: a CU sustains under 30 GB/s).  With few rows the partials of a split are merged
-    // for free by the consumer projection, so split down to about 32 KiB per workgroup; otherwise a split
-    // costs a merge kernel and only pays above about 160 KiB.
+// Key splits of one attention launch and whether the consumer projection merges them (`defer`).
+// A workgroup's time grows with the K/V bytes it streams (about 2 us for 32 KiB, 3 us for 128 KiB, then in
+// proportion: a CU sustains under 30 GB/s).  Partials merged by the consumer cost no kernel but it reads
+// splits x rows of them, so that route is limited to 8 splits and splits * rows <= 16; the merge kernel
+// costs about 5 us and therefore only pays when it brings a workgroup from above 160 KiB down to 128 KiB.
+int pick_splits(const ModelState& M, int nkeys, int heads, int T, bool* defer) {
     const bild_model_config& c = M.m->cfg;
     const size_t per_head = (size_t)nkeys * c.d_head * 2 * M.m->esz();
-    const size_t want = (T <= 4 ? 32 : (T <= 8 ? 64 : 160)) << 10;
-    int sp = 1;
-    while (sp < M.max_splits && heads * sp < 512 && per_head / sp > want) {
-        if (T <= 8 && (sp * 2 * T > 16 || sp * 2 > 8)) break;  // stay within what the consumer merges
-        sp *= 2;
-    }
+    const size_t want = (size_t)(T <= 4 ? 32 : (T <= 8 ? 64 : 128)) << 10;
+    auto fits = [&](int sp) { return sp <= M.max_splits && heads * sp <= 512; };
+    int d_sp = 1;  // deferred route: as many splits as it allows, up to the wanted size
+    while (per_head / d_sp > want && d_sp * 2 <= 8 && d_sp * 2 * T <= 16 && fits(d_sp * 2)) d_sp *= 2;
+    *defer = d_sp > 1;
+    if (per_head / d_sp <= ((size_t)160 << 10)) return d_sp;
+    int sp = d_sp;
+    while (per_head / sp > ((size_t)128 << 10) && fits(sp * 2)) sp *= 2;
+    if (sp > d_sp) *defer = false;
     return sp;
 }
 
@@ -626,11 +630,10 @@ int emit_attention(bild_state* s, const ModelState& M, AttnArgs& a, int nkeys, S
     const int dt = M.m->cfg.dtype;
     *deferred = 1;
     if (!sink.prog) {
-        a.splits = a.T > kMaxRows ? 1 : pick_splits(M, nkeys, a.heads, a.T);  // row blocks and key splits do not combine
+        bool defer = false;
+        a.splits = a.T > kMaxRows ? 1 : pick_splits(M, nkeys, a.heads, a.T, &defer);  // row blocks and key splits do not combine
         a.nw = pick_attn_waves(dt, a.d_head, std::min(a.T, kMaxRows), nkeys, a.splits);
-        // few rows and few splits: the projection that consumes the output merges the partials while it
-        // stages them, which saves the merge kernel
-        a.defer_merge = a.splits > 1 && a.splits <= 8 && a.splits * a.T <= 16;
+        a.defer_merge = a.splits > 1 && defer;
         if (a.defer_merge) *deferred = a.splits;
         if (!s->gemm_only) HIPC(launch_attention(a, dt, s->stream));
         return BILD_OK;
