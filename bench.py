@@ -36,7 +36,10 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="t5", choices=["tiny", "t5", "mt5", "llama"])
+    ap.add_argument("--workload", default="t5", choices=["tiny", "t5", "mt5", "llama", "t5ee"])
+    ap.add_argument("--shared-trunk", action="store_true",
+                    help="early-exit workloads (tiny, t5ee): build the pair from the large model alone, so the two "
+                         "models share the trunk's K/V cache and a large pass runs the upper layers only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter-collection run: one 1 GiB device copy of known size, then --steps BiLD steps; "
@@ -62,9 +65,15 @@ def main() -> int:
     src = bi.make_source(cfg)
     log(f"[bench] weights generated in {time.time() - t0:.1f}s")
     t0 = time.time()
-    small = pkg.Model(pkg.config_from_shape(cfg.small), [ws[n] for n in bi.tensor_names(cfg.small)])
     large = pkg.Model(pkg.config_from_shape(cfg.large), [wl[n] for n in bi.tensor_names(cfg.large)])
-    pair = pkg.Pair(small, large)
+    if args.shared_trunk:
+        if not cfg.early_exit:
+            log(f"bench.py: --shared-trunk needs a workload whose small model is a prefix of the large one, not {cfg.name}")
+            return 2
+        pair = pkg.Pair.early_exit(large, cfg.small.n_dec, cfg.small.logit_scale)
+    else:
+        small = pkg.Model(pkg.config_from_shape(cfg.small), [ws[n] for n in bi.tensor_names(cfg.small)])
+        pair = pkg.Pair(small, large)
     n0 = len(src) if cfg.decoder_only else 1
     st = pkg.State(pair, len(src), n0 + cfg.max_new + 2, cfg.n_max)
     log(f"[bench] models uploaded in {time.time() - t0:.1f}s")
@@ -130,7 +139,14 @@ def main() -> int:
     # order and from the same captured graphs, between two HIP events on the library's stream; weighted by
     # the pass mix of the timed BiLD steps (small passes of 1 row, large passes of the mean review length).
     rows_l = max(1, round(stats["rows_verified"] / max(stats["large_calls"], 1)))
+
+    def uncovered(which, rows):  # leave exactly `rows` tokens unconsumed by model `which`
+        have = st.lengths()
+        st.kv_truncate(which, min(have["len_small" if which == pkg.SMALL else "len_large"], have["y_len"] - rows))
+
+    uncovered(pkg.SMALL, 1)
     g_s = st.bench_gemm(pkg.SMALL, 1, 50)
+    uncovered(pkg.LARGE, rows_l)
     g_l = st.bench_gemm(pkg.LARGE, rows_l, 50)
     n_s, n_l = stats["small_steps"], stats["large_calls"]
     tot_l = n_s * g_s["launches"] + n_l * g_l["launches"]
@@ -193,7 +209,8 @@ def main() -> int:
         "dtype": "bf16" if cfg.large.dtype == bi.DT_BF16 else "f32",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.small.name}+{cfg.large.name}, src {len(src)} tokens, "
-                               f"{cfg.max_new} new tokens, alpha_FB={fb}, alpha_RB={rb}, n_max={cfg.n_max}",
+                               f"{cfg.max_new} new tokens, alpha_FB={fb}, alpha_RB={rb}, n_max={cfg.n_max}"
+                               + (", shared trunk (early-exit pair)" if args.shared_trunk else ""),
                    "tokens_per_step": n_tok},
         "roofline": roofline,
         "cpu_baseline": cpu,

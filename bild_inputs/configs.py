@@ -104,6 +104,7 @@ class PairConfig:
     weight_std: float = 0.02
     gain_jitter: float = 0.0   # norm gains are 1 + jitter*N(0,1); 0 in the benchmark configs
     decoder_only: bool = False
+    early_exit: bool = False   # the small model is a prefix of the large one (same widths, first n_dec layers, shared head)
     alpha_fb_sweep: tuple = ()
     alpha_rb_sweep: tuple = ()
 
@@ -125,7 +126,7 @@ def tiny_pair() -> PairConfig:
                        cross=True, logit_scale=ls_l, embed_scale=es, tie_shift=331)
     small = replace(large, name="tiny-small", n_enc=0, n_dec=2, logit_scale=ls_s)
     return PairConfig("tiny", small, large, n_src=32, max_new=32, alpha_fb=0.5, alpha_rb=2.0,
-                      src_dist="uniform")
+                      src_dist="uniform", early_exit=True)
 
 
 def t5_pair() -> PairConfig:
@@ -135,6 +136,15 @@ def t5_pair() -> PairConfig:
     large = _t5("t5-large", 24, 1024, 16, 4096, ACT_RELU, 32128, True, DT_BF16, ls_l, es)
     return PairConfig("t5", small, large, n_src=512, max_new=64, alpha_fb=0.5, alpha_rb=2.0,
                       alpha_fb_sweep=(0.3, 0.5, 0.7), alpha_rb_sweep=(1.0, 2.0, 4.0))
+
+
+def t5_early_exit_pair() -> PairConfig:
+    """Early-exit arrangement (Section 4.4) at config 2's large shape: the small model is the first six
+    decoder layers of the T5-large-shaped model with its final norm and head."""
+    ls_s, ls_l, es = CAL["t5ee"]
+    large = _t5("t5-large", 24, 1024, 16, 4096, ACT_RELU, 32128, True, DT_BF16, ls_l, es)
+    small = replace(large, name="t5-large-first6", n_enc=0, n_dec=6, logit_scale=ls_s)
+    return PairConfig("t5ee", small, large, n_src=512, max_new=64, alpha_fb=0.5, alpha_rb=2.0, early_exit=True)
 
 
 def mt5_pair() -> PairConfig:
@@ -192,6 +202,7 @@ CAL = {
     "t5": (2.0, 4.0, 36.0),
     "mt5": (2.0, 4.0, 36.0),
     "llama": (0.9, 4.0, 50.0),
+    "t5ee": (1.65, 4.0, 36.0),
 }
 
-PAIRS = {"tiny": tiny_pair, "t5": t5_pair, "mt5": mt5_pair, "llama": llama_pair}
+PAIRS = {"tiny": tiny_pair, "t5": t5_pair, "mt5": mt5_pair, "llama": llama_pair, "t5ee": t5_early_exit_pair}

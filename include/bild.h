@@ -132,6 +132,16 @@ int bild_model_destroy(bild_model* m);
  * large one's (it then attends to the large model's encoder output, the early-exit
  * arrangement of Section 4.4).  The pair borrows the models: destroy it first. */
 int bild_pair_create(bild_model* small_model, bild_model* large_model, bild_pair** out);
+
+/* Early-exit pair (Section 4.4, "Early Exiting Strategy in the BiLD Framework"): the small model IS the
+ * first k decoder layers of `large` followed by the large model's final norm and its LM head (the shared
+ * prediction head), with a logit scale of its own.  No weights are copied.  A state of such a pair keeps
+ * ONE K/V cache for those k layers and remembers the hidden state each consumed token left after layer k,
+ * so a pass of the large model runs layers k..L-1 only; if the trunk has not yet consumed the rows a
+ * large pass needs, the library runs it first.  Results equal those of bild_pair_create on a separately
+ * uploaded copy of the first k layers up to summation order.  1 <= k < n_dec_layers, else BILD_EINVAL.
+ * The pair borrows `large`: destroy the pair first. */
+int bild_pair_create_early_exit(bild_model* large_model, int k, float small_logit_scale, bild_pair** out);
 int bild_pair_destroy(bild_pair* p);
 
 /* Allocates the per-request device state: room for max_src source/prompt tokens

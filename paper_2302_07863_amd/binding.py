@@ -51,6 +51,7 @@ _SIGS = {
     "bild_model_create": (C.c_int, [C.POINTER(ModelConfig), C.POINTER(C.c_void_p), C.c_int, C.POINTER(C.c_void_p)]),
     "bild_model_destroy": (C.c_int, [C.c_void_p]),
     "bild_pair_create": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]),
+    "bild_pair_create_early_exit": (C.c_int, [C.c_void_p, C.c_int, C.c_float, C.POINTER(C.c_void_p)]),
     "bild_pair_destroy": (C.c_int, [C.c_void_p]),
     "bild_state_create": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_void_p)]),
     "bild_state_destroy": (C.c_int, [C.c_void_p]),
@@ -147,6 +148,15 @@ class Pair:
         h = C.c_void_p()
         _check(lib().bild_pair_create(small.h, large.h, C.byref(h)), "bild_pair_create")
         self.h, self.small, self.large = h, small, large
+
+    @classmethod
+    def early_exit(cls, large: Model, k: int, small_logit_scale: float) -> "Pair":
+        """The small model is the first k decoder layers of `large` with the shared head."""
+        h = C.c_void_p()
+        _check(lib().bild_pair_create_early_exit(large.h, k, small_logit_scale, C.byref(h)), "bild_pair_create_early_exit")
+        self = cls.__new__(cls)
+        self.h, self.small, self.large = h, None, large
+        return self
 
     def close(self):
         if self.h:

@@ -57,6 +57,8 @@ struct bild_pair {
     bild_model* m[2];  // [0] small, [1] large
     bool decoder_only;
     bool small_borrows_encoder;
+    int trunk_layers = 0;        // > 0: early-exit pair, m[0] is a view of m[1]'s first trunk_layers decoder layers
+    bild_model* view = nullptr;  // that view (owned by the pair; it owns no device memory)
 };
 
 namespace {
@@ -103,6 +105,7 @@ struct bild_state {
     // persistent pass kernel: stage lists by (model, rows, key bucket, gemm-only), barrier state, settings
     struct PassProg { Stage* dev = nullptr; int nstages = 0; int G = 0; size_t lds = 0; int64_t gemms = 0, gemm_bytes = 0; };
     std::map<std::array<int, 4>, PassProg> progs;
+    float* trunk_x = nullptr;  // early-exit pair: [cap_len][d] hidden state after the trunk's last layer, by position
     PassSync* psync = nullptr;
     bool resident[2] = {false, false};  // model w runs its layers in the persistent kernel
     int resident_G[2] = {0, 0};
@@ -312,8 +315,38 @@ extern "C" int bild_pair_create(bild_model* s, bild_model* l, bild_pair** out) {
     return BILD_OK;
 }
 
+extern "C" int bild_pair_create_early_exit(bild_model* l, int k, float small_logit_scale, bild_pair** out) {
+    if (!l || !out) return BILD_EINVAL;
+    if (k < 1 || k >= l->cfg.n_dec_layers || !(small_logit_scale > 0.f)) return BILD_EINVAL;
+    if (l->cfg.cross_attn && l->cfg.n_enc_layers < 1) return BILD_EINVAL;
+    bild_model* v = new (std::nothrow) bild_model();
+    bild_pair* p = new (std::nothrow) bild_pair();
+    if (!v || !p) {
+        delete v;
+        delete p;
+        return BILD_ENOMEM;
+    }
+    v->cfg = l->cfg;
+    v->cfg.n_dec_layers = k;
+    v->cfg.n_enc_layers = 0;  // it attends to the large model's encoder output
+    v->cfg.logit_scale = small_logit_scale;
+    v->emb = l->emb;
+    v->head = l->head;
+    v->dec_final = l->dec_final;
+    v->dec.assign(l->dec.begin(), l->dec.begin() + k);
+    p->m[0] = v;
+    p->m[1] = l;
+    p->decoder_only = !l->cfg.cross_attn;
+    p->small_borrows_encoder = l->cfg.cross_attn != 0;
+    p->trunk_layers = k;
+    p->view = v;
+    *out = p;
+    return BILD_OK;
+}
+
 extern "C" int bild_pair_destroy(bild_pair* p) {
     if (!p) return BILD_EINVAL;
+    delete p->view;  // a view owns no device memory
     delete p;
     return BILD_OK;
 }
@@ -437,11 +470,16 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
             return BILD_EHIP;                                                        \
         }                                                                            \
     } while (0)
-        ALZ(M.kcache, L * (size_t)s->cap_len * I * esz);
-        ALZ(M.vcache, L * (size_t)s->cap_len * I * esz);
-        if (m->cfg.cross_attn) {
-            ALZ(M.ck, L * (size_t)s->cap_src * I * esz);
-            ALZ(M.cv, L * (size_t)s->cap_src * I * esz);
+        if (w == 0 && p->trunk_layers > 0) {
+            // early-exit pair: the trunk's layers are the large model's first layers, one cache serves both
+            // (filled in below, once the large model's buffers exist)
+        } else {
+            ALZ(M.kcache, L * (size_t)s->cap_len * I * esz);
+            ALZ(M.vcache, L * (size_t)s->cap_len * I * esz);
+            if (m->cfg.cross_attn) {
+                ALZ(M.ck, L * (size_t)s->cap_src * I * esz);
+                ALZ(M.cv, L * (size_t)s->cap_src * I * esz);
+            }
         }
         // a decoder-only model prefills its whole prompt in one pass of many row blocks
         M.rows_cap = p->decoder_only ? std::max(kMaxRows, max_src) : kMaxRows;
@@ -463,6 +501,14 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
             ALZ(M.enc_k, (size_t)s->cap_src * I * esz);
             ALZ(M.enc_v, (size_t)s->cap_src * I * esz);
         }
+    }
+    if (p->trunk_layers > 0) {
+        s->ms[0].kcache = s->ms[1].kcache;
+        s->ms[0].vcache = s->ms[1].vcache;
+        s->ms[0].ck = s->ms[1].ck;
+        s->ms[0].cv = s->ms[1].cv;
+        AL(s->trunk_x, sizeof(float) * (size_t)s->cap_len * p->m[1]->cfg.d_model);
+        s->resident[0] = s->resident[1] = false;  // the persistent kernel does not know the trunk hand-over
     }
 #undef ALZ
 #undef AL
@@ -681,8 +727,22 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
     e.sinusoidal = c.pos == BILD_POS_SINUSOIDAL;
     e.embed_scale = c.embed_scale;
     e.x = M.x;
+    // Early-exit pair: the large model's pass starts from the hidden state the trunk (model 0) left for these
+    // rows and runs the layers above the trunk only.
+    const int trunk = s->pair->trunk_layers;
+    const bool above_trunk = trunk > 0 && w == 1;
+    const int layer0 = above_trunk ? trunk : 0;
     if (!s->gemm_only) {
-        if (sink.prog) {
+        if (above_trunk) {
+            RowCopyArgs rc;
+            std::memset((void*)&rc, 0, sizeof(rc));
+            rc.src = s->trunk_x;
+            rc.src_row_ptr = len_ptr;
+            rc.dst = M.x;
+            rc.d = d;
+            rc.T = T;
+            HIPC(launch_row_copy(rc, s->stream));
+        } else if (sink.prog) {
             Stage st;
             std::memset((void*)&st, 0, sizeof(st));
             st.kind = ST_EMBED;
@@ -695,7 +755,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
     }
     const float att_scale = 1.f / std::sqrt((float)c.d_head);
     int merge_splits = 1;
-    for (int l = 0; l < c.n_dec_layers; ++l) {
+    for (int l = layer0; l < c.n_dec_layers; ++l) {
         const LayerW& L = m->dec[l];
         char* kc = M.kcache + (size_t)l * s->cap_len * I * esz;
         char* vc = M.vcache + (size_t)l * s->cap_len * I * esz;
@@ -785,6 +845,16 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
             int rc = emit_gemm(s, m, g, sink);
             if (rc) return rc;
         }
+    }
+    if (trunk > 0 && w == 0 && !s->gemm_only) {  // remember what the trunk produced for these positions
+        RowCopyArgs rc;
+        std::memset((void*)&rc, 0, sizeof(rc));
+        rc.src = M.x;
+        rc.dst = s->trunk_x;
+        rc.dst_row_ptr = len_ptr;
+        rc.d = d;
+        rc.T = T;
+        HIPC(launch_row_copy(rc, s->stream));
     }
     return BILD_OK;
 }
@@ -916,7 +986,14 @@ int key_bucket(int nkeys) {
 // One pass, replayed from a captured graph when possible.  Launch parameters that depend on the cache
 // length are chosen per power-of-two bucket of the key count, so a graph stays valid while the
 // sequence grows inside its bucket; everything else the kernels need they read from the control block.
+int catch_up(bild_state* s, int w, int target);
+
 int run_pass(bild_state* s, int w, int T, int lm_rows, int mode) {
+    if (s->pair->trunk_layers > 0 && w == 1 && s->len[0] < s->len[1] + T) {
+        // early-exit pair: the upper layers continue from what the trunk left for these rows
+        const int rc = catch_up(s, 0, s->len[1] + T);
+        if (rc) return rc;
+    }
     const int bucket = key_bucket(s->len[w] + T);
     if (lm_rows > 0) s->ms[w].last_rows = lm_rows;
     if (!s->use_graphs || s->prof_on || mode == 3) return decoder_pass(s, w, T, lm_rows, mode, bucket);
@@ -1030,6 +1107,7 @@ int run_encoder(bild_state* s, int w) {
     for (int u = 0; u < 2; ++u) {
         const bool uses = (u == w) || (u == 0 && w == 1 && s->pair->small_borrows_encoder);
         if (!uses) continue;
+        if (u == 0 && s->pair->trunk_layers > 0) continue;  // a view of the large model: the same cross K/V memory
         ModelState& U = s->ms[u];
         const bild_model* mu = U.m;
         const int Iu = mu->inner();
@@ -1477,7 +1555,9 @@ extern "C" int64_t bild_pass_bytes(const bild_state* s, int which, int t_cache, 
     if (!s || which < 1 || which > 2) return BILD_EINVAL;
     const bild_model* m = s->ms[which - 1].m;
     const bild_model_config& c = m->cfg;
-    const int64_t d = c.d_model, I = m->inner(), F = c.d_ff, L = c.n_dec_layers, B = m->esz();
+    const int64_t d = c.d_model, I = m->inner(), F = c.d_ff, B = m->esz();
+    // an early-exit pair's large pass runs the layers above the trunk only
+    const int64_t L = c.n_dec_layers - (which == 2 ? s->pair->trunk_layers : 0);
     const int64_t attn = 4 * d * I * (c.cross_attn ? 2 : 1);
     const int64_t ffn = (m->gated() ? 3 : 2) * d * F;
     int64_t elems = L * (attn + ffn) + (int64_t)c.vocab * d + L * 2 * I * (int64_t)(t_cache + rows);

@@ -142,6 +142,17 @@ struct EmbedArgs {
     float* x;  // [T][d]
 };
 
+// Copies T rows of d floats: dst[dst_row + t] = src[src_row + t], each row index = (*ptr or 0) + add.
+// Carries the hidden state between the shared trunk and the upper layers of an early-exit pair.
+struct RowCopyArgs {
+    const float* src;
+    float* dst;
+    const int* src_row_ptr;
+    const int* dst_row_ptr;
+    int src_row_add, dst_row_add;
+    int d, T;
+};
+
 struct FinishArgs {
     Ctl* ctl;
     int* y;
@@ -201,6 +212,7 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st);
 hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st);
 hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st);
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st);
+hipError_t launch_row_copy(const RowCopyArgs& a, hipStream_t st);
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 hipError_t kernels_init();  // one-time function attributes; call before any stream capture
 size_t gemm_num_blocks(const GemmArgs& a);

@@ -1394,6 +1394,19 @@ __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
     finish_body(a, lds);
 }
 
+__global__ __launch_bounds__(256) void row_copy_kernel(const RowCopyArgs a) {
+    const int t = (int)blockIdx.x;
+    const float4* src = (const float4*)(a.src + (size_t)((a.src_row_ptr ? *a.src_row_ptr : 0) + a.src_row_add + t) * a.d);
+    float4* dst = (float4*)(a.dst + (size_t)((a.dst_row_ptr ? *a.dst_row_ptr : 0) + a.dst_row_add + t) * a.d);
+    for (int i = threadIdx.x; i < a.d / 4; i += blockDim.x) dst[i] = src[i];
+}
+
+hipError_t launch_row_copy(const RowCopyArgs& a, hipStream_t st) {
+    if (a.T < 1 || a.d % 4) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(row_copy_kernel, dim3(a.T), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
 // Plain copy of known size: the reference against which hardware byte counters are scaled.
 __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];

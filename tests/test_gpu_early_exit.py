@@ -1,0 +1,109 @@
+"""GPU parity of the early-exit pair (Section 4.4): the small model is a prefix of the large one, one K/V
+cache serves both and the large model's pass starts above the trunk.  The oracle knows nothing of the
+sharing: it runs the two models separately, which is the definition the shared path must reach."""
+import numpy as np
+import pytest
+
+import bild_inputs as bi
+import oracle
+import paper_2302_07863_amd as pkg
+from tests import parity
+from tests.test_gpu_parity import Rig, TOY_VARIANTS, INF
+
+pytestmark = pytest.mark.gpu
+
+
+class EERig(Rig):
+    """Like Rig, but the GPU pair is built from the large model alone."""
+
+    def __init__(self, cfg):
+        super().__init__(cfg)
+        assert cfg.small.d == cfg.large.d and cfg.small.n_dec < cfg.large.n_dec
+        self.plain_pair = self.pair
+        self.large_gpu = parity.make_gpu_model(cfg.large, self.wl)
+        self.pair = pkg.Pair.early_exit(self.large_gpu, cfg.small.n_dec, cfg.small.logit_scale)
+
+
+def _prefix_toy(name):
+    kw = dict(TOY_VARIANTS[name])
+    assert not kw.get("truncate")
+    return bi.toy_pair(n_small=2, n_large=4, **kw)
+
+
+@pytest.mark.parametrize("name", ["f32-relu-tied", "bf16-relu-tied", "f32-geglu-untied", "f32-rope-swiglu-deconly"])
+def test_early_exit_toy_parity(name):
+    R = EERig(_prefix_toy(name))
+    for fb, rb, nm in ((0.5, 2.0, 10), (0.2, 0.7, 3), (0.0, 0.5, 6)):
+        ref = oracle.bild_generate(R.req, fb, rb, nm, R.cfg.max_new, keep_logits=True)
+        st = R.state(R.cfg.max_new, nm)
+        st.encode(R.src)
+        worst = parity.teacher_forced(st, ref, R.n0, fb, rb, R.cfg)
+        toks, stats = st.generate(R.src, fb, rb, R.cfg.max_new)
+        print(name, worst, parity.compare_generation(toks, stats, ref, fb, rb))
+
+
+def test_early_exit_tiny_config():
+    """Config 1 is an early-exit pair by construction (small = the large model's first two layers)."""
+    cfg = bi.tiny_pair()
+    R = EERig(cfg)
+    ref = oracle.bild_generate(R.req, cfg.alpha_fb, cfg.alpha_rb, cfg.n_max, cfg.max_new, keep_logits=True)
+    st = R.state(cfg.max_new, cfg.n_max)
+    st.encode(R.src)
+    print(parity.teacher_forced(st, ref, R.n0, cfg.alpha_fb, cfg.alpha_rb, cfg))
+    for fb, rb in ((cfg.alpha_fb, cfg.alpha_rb), (0.3, 1.0), (0.7, 4.0), (0.0, 0.3), (2.0, INF)):
+        ref = oracle.bild_generate(R.req, fb, rb, cfg.n_max, cfg.max_new)
+        toks, stats = st.generate(R.src, fb, rb, cfg.max_new)
+        print(fb, rb, parity.compare_generation(toks, stats, ref, fb, rb), stats)
+
+
+def test_early_exit_large_only_and_truncation():
+    """Large-only greedy decoding (the trunk is caught up before every upper pass) and review passes after
+    cutting either cache at random rows give the logits of the no-cache definition."""
+    cfg = _prefix_toy("bf16-relu-tied")
+    R = EERig(cfg)
+    tol = parity.logit_tol(cfg)
+    st = pkg.State(R.pair, len(R.src), R.n0 + 60, 31)
+    ref_large = oracle.greedy(R.req, "large", 12)
+    assert st.greedy(pkg.LARGE, R.src, 12) == ref_large.tokens
+    st.encode(R.src)
+    st.debug_enable_logits(True)
+    rng = np.random.default_rng(3)
+    kept = []                                   # verified tokens after the start symbol
+    for n in (5, 0, 9, 17, 3):
+        block = [int(t) for t in bi.make_tokens(cfg.large.vocab, n, seed=40 + n)]
+        out, r, nll = st.large_verify(INF, draft=block)
+        assert r == n and out[:n] == block
+        y = R.req.initial() + kept + block
+        z = R.req.large.logits_full(y, R.req.cross_l)[len(y) - n - 1:]
+        rows = np.stack([st.debug_logits(pkg.LARGE, i) for i in range(n + 1)])
+        assert np.max(np.abs(rows - z)) <= tol, n
+        assert out[n] == int(np.argmax(z[n])) or oracle.policy.top2_gap(z[n]) < parity.MARGIN
+        kept = kept + block + [out[n]]
+        # keep a random prefix of the sequence and cut the two caches at independent random rows
+        keep = int(rng.integers(0, len(kept) + 1))
+        kept = kept[:keep]
+        st.seq_truncate(R.n0 + keep)
+        ln = st.lengths()
+        st.kv_truncate(pkg.SMALL, min(ln["len_small"], int(rng.integers(0, R.n0 + keep))))
+        st.kv_truncate(pkg.LARGE, min(ln["len_large"], int(rng.integers(0, R.n0 + keep))))
+
+
+@pytest.mark.timeout(900)
+def test_t5_early_exit_full_size_shared_trunk():
+    """T5-large shape with its first six decoder layers as the small model, in the launch configuration
+    `bench.py --workload t5ee --shared-trunk` times: every logit and decision against the oracle."""
+    cfg = bi.PAIRS["t5ee"]()
+    R = EERig(cfg)
+    fb, rb = cfg.alpha_fb, cfg.alpha_rb
+    ref = oracle.bild_generate(R.req, fb, rb, cfg.n_max, cfg.max_new, keep_logits=True)
+    st = R.state(cfg.max_new, cfg.n_max)
+    st.encode(R.src)
+    print("t5ee teacher-forced", parity.teacher_forced(st, ref, R.n0, fb, rb, cfg), ref.stats, flush=True)
+    for rec in ref.trace:
+        rec.pop("z", None)
+    toks, stats = st.generate(R.src, fb, rb, cfg.max_new)
+    print("t5ee free-running", parity.compare_generation(toks, stats, ref, fb, rb), stats, flush=True)
+    # the large pass of the shared pair reads the upper layers only
+    plain = pkg.State(R.plain_pair, len(R.src), R.n0 + 8, cfg.n_max)
+    plain.encode(R.src)
+    assert st.pass_bytes(pkg.LARGE, 10, 1) < 0.8 * plain.pass_bytes(pkg.LARGE, 10, 1)
