@@ -159,3 +159,11 @@ def make_tokens(vocab: int, n: int, seed: int) -> np.ndarray:
     """Uniform token ids for forced draft blocks in stress tests."""
     rng = np.random.Generator(np.random.Philox(np.random.SeedSequence([seed, 2])))
     return rng.integers(0, vocab, size=n, dtype=np.int64).astype(np.int32)
+
+
+def make_uniforms(n: int, seed: int, stream: int) -> np.ndarray:
+    """n uniform numbers in [0, 1) for the sampling variant, one per sequence position; `stream`
+    separates the small model's draws (0) from the large model's (1).  Each is k / 2^24 for an
+    integer k, so float32 and float64 hold exactly the same value."""
+    rng = np.random.Generator(np.random.Philox(np.random.SeedSequence([seed, 3, stream])))
+    return (rng.integers(0, 1 << 24, size=n, dtype=np.int64).astype(np.float64) / float(1 << 24)).astype(np.float32)

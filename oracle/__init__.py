@@ -10,6 +10,7 @@ pinned by tests that run without a GPU.  The token values produced on the
 benchmark configurations themselves are PARITY UNPINNED beyond those checks:
 the paper prints no worked trace, so the oracle is the sole authority there.
 """
-from . import bild, model, policy
+from . import bild, model, policy, sampling
 from .bild import Request, Result, Stats, bild_generate, greedy
 from .model import DecoderCache, Model
+from .sampling import Sampler

@@ -117,17 +117,19 @@ class _Cached:
 
 
 def greedy(req: Request, which: str, max_new: int, eos: int = -1, cached: bool = True,
-           keep_logits: bool = False) -> Result:
+           keep_logits: bool = False, sampler=None) -> Result:
     """Vanilla inference: one model alone, autoregressive argmax (the baseline
-    every speedup in the paper is normalised to when which == 'large')."""
+    every speedup in the paper is normalised to when which == 'large'); with a
+    sampler, each token is drawn instead (Appendix, BiLD with Sampling)."""
     y = req.initial()
     n0 = len(y)
     ev = _Cached(req, which, n0 + max_new + 1) if cached else _Definition(req, which)
     trace = []
     while len(y) - n0 < max_new and not (len(y) > n0 and y[-1] == eos):
         z = ev.next_logits(y)
-        tok = policy.argmax_lowest(z)
-        trace.append(dict(kind=which, pos=len(y), tok=tok, pmax=policy.max_prob(z), gap=policy.top2_gap(z)))
+        tok, dm = (policy.argmax_lowest(z), None) if sampler is None else sampler.pick(which, z, len(y))
+        trace.append(dict(kind=which, pos=len(y), tok=tok, pmax=policy.max_prob(z), gap=policy.top2_gap(z),
+                          draw_margin=dm))
         if keep_logits:
             trace[-1]["z"] = z
         y.append(tok)
@@ -135,9 +137,12 @@ def greedy(req: Request, which: str, max_new: int, eos: int = -1, cached: bool =
 
 
 def bild_generate(req: Request, alpha_fb: float, alpha_rb: float, n_max: int, max_new: int,
-                  eos: int = -1, cached: bool = True, keep_logits: bool = False) -> Result:
+                  eos: int = -1, cached: bool = True, keep_logits: bool = False, sampler=None) -> Result:
     """Algorithm 1.  keep_logits stores every evaluated logit row in the trace
-    (for element-wise comparison against another implementation)."""
+    (for element-wise comparison against another implementation).  With a
+    sampler (oracle.sampling.Sampler) both models draw their tokens instead of
+    taking the argmax; the two policies are unchanged (Appendix, BiLD with
+    Sampling)."""
     y = req.initial()
     n0 = len(y)
     src_small = [False] * n0
@@ -153,9 +158,10 @@ def bild_generate(req: Request, alpha_fb: float, alpha_rb: float, n_max: int, ma
         pmax = policy.max_prob(z_s)
         low_conf = policy.fallback(z_s, alpha_fb)
         forced = n_max > 0 and n >= n_max
-        tok_s = policy.argmax_lowest(z_s)
+        tok_s, dm_s = (policy.argmax_lowest(z_s), None) if sampler is None else sampler.pick("small", z_s, len(y))
         trace.append(dict(kind="small", pos=len(y), tok=tok_s, pmax=pmax, gap=policy.top2_gap(z_s),
-                          fallback=bool(low_conf or forced), forced=bool(forced and not low_conf)))
+                          fallback=bool(low_conf or forced), forced=bool(forced and not low_conf),
+                          draw_margin=dm_s))
         if keep_logits:
             trace[-1]["z"] = z_s
         if not (low_conf or forced):
@@ -175,10 +181,11 @@ def bild_generate(req: Request, alpha_fb: float, alpha_rb: float, n_max: int, ma
             if policy.rollback(z_l[i], y[draft_start + i], alpha_rb):
                 r = i
                 break
-        tok_l = policy.argmax_lowest(z_l[r])
+        tok_l, dm_l = ((policy.argmax_lowest(z_l[r]), None) if sampler is None
+                       else sampler.pick("large", z_l[r], draft_start + r))
         trace.append(dict(kind="large", draft_start=draft_start, n=n, r=r, tok=tok_l, nll=nlls,
                           gaps=[policy.top2_gap(z_l[i]) for i in range(r + 1)],
-                          pmax=policy.max_prob(z_l[r])))
+                          pmax=policy.max_prob(z_l[r]), draw_margin=dm_l))
         if keep_logits:
             trace[-1]["z"] = z_l
         if r < n:
