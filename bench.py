@@ -44,6 +44,9 @@ def main() -> int:
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter-collection run: one 1 GiB device copy of known size, then --steps BiLD steps; "
                          "no timing, no JSON (run under rocprofv3 --pmc with BILD_NO_GRAPH=1)")
+    ap.add_argument("--top-p", type=float, default=0.0,
+                    help="> 0: the sampling variant, both models draw from the nucleus of this mass (uniform numbers "
+                         "from the seeded input generator)")
     ap.add_argument("--alpha-fb", type=float, default=None)
     ap.add_argument("--alpha-rb", type=float, default=None)
     args = ap.parse_args()
@@ -78,6 +81,11 @@ def main() -> int:
     st = pkg.State(pair, len(src), n0 + cfg.max_new + 2, cfg.n_max)
     log(f"[bench] models uploaded in {time.time() - t0:.1f}s")
 
+    sampler_u = None
+    if args.top_p > 0:
+        n_u = n0 + cfg.max_new + 2
+        sampler_u = (bi.make_uniforms(n_u, cfg.input_seed, 0), bi.make_uniforms(n_u, cfg.input_seed, 1))
+        st.set_sampling(args.top_p, *sampler_u)
     t0 = time.perf_counter()
     st.encode(src)
     encode_ms = (time.perf_counter() - t0) * 1e3
@@ -188,7 +196,8 @@ def main() -> int:
         log(f"[bench] oracle set up + encoded in {time.time() - t0:.1f}s")
         n_cpu = cfg.max_new if args.workload != "llama" else 8
         t0 = time.perf_counter()
-        ref = oracle.bild_generate(req, fb, rb, cfg.n_max, n_cpu)
+        smp = oracle.Sampler(args.top_p, *sampler_u) if sampler_u else None
+        ref = oracle.bild_generate(req, fb, rb, cfg.n_max, n_cpu, sampler=smp)
         cdt = time.perf_counter() - t0
         cpu = dict(value=round(len(ref.tokens) / cdt, 2), unit="tokens/s", cores=int(cores), kind="oracle",
                    sample=f"one BiLD generation of {n_cpu} tokens on the same request (float64 numpy, decode only)",
@@ -210,7 +219,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.small.name}+{cfg.large.name}, src {len(src)} tokens, "
                                f"{cfg.max_new} new tokens, alpha_FB={fb}, alpha_RB={rb}, n_max={cfg.n_max}"
-                               + (", shared trunk (early-exit pair)" if args.shared_trunk else ""),
+                               + (", shared trunk (early-exit pair)" if args.shared_trunk else "")
+                               + (f", nucleus sampling top_p={args.top_p}" if args.top_p > 0 else ""),
                    "tokens_per_step": n_tok},
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -180,6 +180,16 @@ int bild_small_step(bild_state* s, float alpha_fb, int32_t* token, int32_t* fall
 int bild_large_verify(bild_state* s, const int32_t* draft, int n, float alpha_rb, int32_t* out_tokens,
                       int32_t* n_out, int32_t* rollback_pos, float* nll);
 
+/* Sampling variant (Appendix, "BiLD with Sampling"): with top_p in (0, 1] every token either model commits
+ * is DRAWN from the nucleus of its distribution instead of being the argmax; the fallback and the rollback
+ * tests are unchanged.  Nucleus: the smallest set of most likely tokens whose probability reaches top_p,
+ * plus any token tied with its least likely member.  Draw: the members are walked in increasing token id and
+ * the first whose running probability exceeds u * P(nucleus) is taken.  The uniform numbers are the caller's:
+ * u_small[p] / u_large[p] in [0, 1) is used when the small / large model commits the token at position p of
+ * the sequence (host arrays of n >= max_len floats, copied).  top_p <= 0 switches back to argmax (the arrays
+ * may then be NULL).  BILD_EINVAL for top_p > 1, a missing array, n < max_len or a number outside [0, 1). */
+int bild_set_sampling(bild_state* s, float top_p, const float* u_small, const float* u_large, int n);
+
 /* Lowers a cache length: which = 1 small, 2 large, 3 both; the cache(s) keep
  * their first pos rows (O(1): only a length changes).  BILD_EINVAL if pos exceeds
  * the current length of a selected cache.  y is not changed; a later pass simply

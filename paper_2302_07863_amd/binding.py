@@ -60,6 +60,7 @@ _SIGS = {
                                   C.POINTER(C.c_float)]),
     "bild_large_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.POINTER(C.c_int32),
                                     C.POINTER(C.c_int32), C.c_void_p]),
+    "bild_set_sampling": (C.c_int, [C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_int]),
     "bild_kv_truncate": (C.c_int, [C.c_void_p, C.c_int, C.c_int]),
     "bild_seq_truncate": (C.c_int, [C.c_void_p, C.c_int]),
     "bild_force_tokens": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int]),
@@ -206,6 +207,16 @@ class State:
 
     def kv_truncate(self, which: int, pos: int):
         _check(lib().bild_kv_truncate(self.h, which, pos), "bild_kv_truncate")
+
+    def set_sampling(self, top_p: float, u_small=None, u_large=None):
+        """top_p <= 0 returns to argmax decoding."""
+        if top_p <= 0:
+            _check(lib().bild_set_sampling(self.h, float(top_p), None, None, 0), "bild_set_sampling")
+            return
+        a = np.ascontiguousarray(u_small, dtype=np.float32)
+        b = np.ascontiguousarray(u_large, dtype=np.float32)
+        _check(lib().bild_set_sampling(self.h, float(top_p), a.ctypes.data, b.ctypes.data, min(len(a), len(b))),
+               "bild_set_sampling")
 
     def seq_truncate(self, n_keep: int):
         _check(lib().bild_seq_truncate(self.h, n_keep), "bild_seq_truncate")

@@ -105,6 +105,8 @@ struct bild_state {
     // persistent pass kernel: stage lists by (model, rows, key bucket, gemm-only), barrier state, settings
     struct PassProg { Stage* dev = nullptr; int nstages = 0; int G = 0; size_t lds = 0; int64_t gemms = 0, gemm_bytes = 0; };
     std::map<std::array<int, 4>, PassProg> progs;
+    float top_p = 0.f;         // > 0: sampling variant, tokens are drawn from the nucleus
+    float* u_dev[2] = {nullptr, nullptr};  // uniform number per sequence position, per model
     float* trunk_x = nullptr;  // early-exit pair: [cap_len][d] hidden state after the trunk's last layer, by position
     PassSync* psync = nullptr;
     bool resident[2] = {false, false};  // model w runs its layers in the persistent kernel
@@ -957,7 +959,7 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
         g.ylen_ptr = &s->ctl->y_len;
         g.part = M.part;
         g.zt = M.zt;
-        g.dbg = s->debug_logits ? M.dbg : nullptr;
+        g.dbg = (s->debug_logits || s->top_p > 0.f) ? M.dbg : nullptr;  // the draw of the sampling variant reads the logits
         g.row_off = 0;
         gemm_pick_shape(g, dt);
         if ((int)gemm_num_blocks(g) > M.nparts_cap) return BILD_ECAP;
@@ -970,6 +972,12 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
         f.zt = M.zt;
         f.T = lm_rows;
         f.mode = mode;
+        if (s->top_p > 0.f) {
+            f.top_p = s->top_p;
+            f.logits = M.dbg;
+            f.vocab = c.vocab;
+            f.u = s->u_dev[w];
+        }
     } else {
         f.mode = 3;
     }
@@ -997,7 +1005,7 @@ int run_pass(bild_state* s, int w, int T, int lm_rows, int mode) {
     const int bucket = key_bucket(s->len[w] + T);
     if (lm_rows > 0) s->ms[w].last_rows = lm_rows;
     if (!s->use_graphs || s->prof_on || mode == 3) return decoder_pass(s, w, T, lm_rows, mode, bucket);
-    const std::array<int, 6> key = {w, T, lm_rows, mode, bucket, (s->debug_logits ? 1 : 0) | (s->gemm_only ? 2 : 0)};
+    const std::array<int, 6> key = {w, T, lm_rows, mode, bucket, (s->debug_logits ? 1 : 0) | (s->gemm_only ? 2 : 0) | (s->top_p > 0.f ? 4 : 0)};
     auto it = s->graphs.find(key);
     if (it == s->graphs.end()) {
         if (s->resident[w] && T <= kMaxRows) {  // the stage list is uploaded with a blocking copy: not inside a capture
@@ -1382,16 +1390,57 @@ extern "C" int bild_greedy(bild_state* s, int which, const int32_t* src, int n_s
     return BILD_OK;
 }
 
+namespace {
+int alloc_logit_buffers(bild_state* s) {
+    for (int w = 0; w < 2; ++w) {
+        if (s->ms[w].dbg) continue;
+        int rc = dev_alloc(s->allocs, (void**)&s->ms[w].dbg, sizeof(float) * kMaxRows * (size_t)s->ms[w].m->cfg.vocab);
+        if (rc) return rc;
+    }
+    return BILD_OK;
+}
+}  // namespace
+
 extern "C" int bild_debug_enable_logits(bild_state* s, int enable) {
     if (!s) return BILD_EINVAL;
     if (enable) {
-        for (int w = 0; w < 2; ++w) {
-            if (s->ms[w].dbg) continue;
-            int rc = dev_alloc(s->allocs, (void**)&s->ms[w].dbg, sizeof(float) * kMaxRows * (size_t)s->ms[w].m->cfg.vocab);
-            if (rc) return rc;
-        }
+        int rc = alloc_logit_buffers(s);
+        if (rc) return rc;
     }
     s->debug_logits = enable != 0;
+    return BILD_OK;
+}
+
+extern "C" int bild_set_sampling(bild_state* s, float top_p, const float* u_small, const float* u_large, int n) {
+    if (!s) return BILD_EINVAL;
+    // captured passes carry top_p by value: a new value starts from fresh captures
+    auto drop_graphs = [&]() {
+        (void)hipStreamSynchronize(s->stream);
+        for (auto& kv : s->graphs) (void)hipGraphExecDestroy(kv.second);
+        s->graphs.clear();
+    };
+    if (!(top_p > 0.f)) {  // back to argmax
+        if (s->top_p > 0.f) drop_graphs();
+        s->top_p = 0.f;
+        return BILD_OK;
+    }
+    if (top_p > 1.f || !u_small || !u_large || n < s->max_len) return BILD_EINVAL;
+    const float* us[2] = {u_small, u_large};
+    for (int w = 0; w < 2; ++w)
+        for (int i = 0; i < s->max_len; ++i)
+            if (!(us[w][i] >= 0.f && us[w][i] < 1.f)) return BILD_EINVAL;
+    int rc = alloc_logit_buffers(s);
+    if (rc) return rc;
+    HIPC(hipStreamSynchronize(s->stream));
+    for (int w = 0; w < 2; ++w) {
+        if (!s->u_dev[w]) {
+            rc = dev_alloc(s->allocs, (void**)&s->u_dev[w], sizeof(float) * (size_t)(s->max_len + 1));
+            if (rc) return rc;
+        }
+        HIPC(hipMemcpy(s->u_dev[w], us[w], sizeof(float) * (size_t)s->max_len, hipMemcpyHostToDevice));
+    }
+    if (s->top_p != top_p) drop_graphs();
+    s->top_p = top_p;
     return BILD_OK;
 }
 

@@ -166,6 +166,11 @@ struct FinishArgs {
     int rows_consumed;  // rows the pass consumed (cache advance)
     int y_cap;
     Ctl* host_mirror;   // device-visible pinned host copy of the control block, written last
+    // sampling variant (top_p > 0): the committed token is drawn from the nucleus of its row instead of the argmax
+    float top_p;
+    const float* logits;  // [rows][vocab] logits of the pass (row_off applies)
+    int vocab;
+    const float* u;       // uniform number per sequence position, for the model of this pass
 };
 
 // ---- persistent pass kernel: one launch walks a device-resident list of stages, its workgroups

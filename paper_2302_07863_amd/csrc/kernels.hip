@@ -1301,7 +1301,179 @@ hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st) {
 // =====================================================================================
 // LDS use of finish_body (from the start of the workgroup's LDS)
 constexpr int kFinishLds = 3 * kMaxRows * 4;
+// LDS of the sampling variant behind that: 16 waves x 16 bins, 1024 per-thread masses, a few scalars
+constexpr int kDrawLds = 16 * 16 * 4 + 1024 * 4 + 128;
 
+// Order-preserving integer image of a float: a < b  <=>  key(a) < key(b).
+__device__ __forceinline__ uint32_t float_key(float f) {
+    const uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Nucleus draw of the sampling variant (Appendix, BiLD with Sampling), by the whole workgroup (at most
+// 1024 threads).  Nucleus = every token whose probability is at least that of the least likely member of
+// the smallest top set reaching top_p; the draw walks the members in increasing id until their running mass
+// exceeds u * mass.  The threshold is found exactly, as an integer key, by a radix search of 4 bits per
+// sweep over the logits: with e_i = exp(z_i - m), K is the largest key with sum_{key_i >= K} e_i >= top_p * sum e_i.
+// Returns the token to every thread.  `ws` is kDrawLds bytes of LDS.
+__device__ __forceinline__ int nucleus_draw(const float* __restrict__ z, int V, float m, float top_p, float u, char* ws) {
+    float* bins = (float*)ws;              // [16 waves][16]
+    float* tmass = bins + 16 * 16;         // [1024]
+    float* sc = tmass + 1024;              // scalars
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nthr = blockDim.x, nwv = nthr >> 6;
+    uint32_t K = 0;
+    float target = 0.f, mass = 0.f;
+    // A row of up to 32 logits per thread stays in registers for all sweeps (one batch of loads); longer rows
+    // are re-read from L2 every sweep, eight loads at a time.
+    constexpr int CACHED = 32;
+    const bool cached = V <= CACHED * nthr;
+    float zc[CACHED];
+    if (cached) {
+#pragma unroll
+        for (int c = 0; c < CACHED; ++c) {
+            const int i = tid + c * nthr;
+            zc[c] = i < V ? z[i] : -INFINITY;  // -inf: weight exp(-inf) = 0 and the lowest key
+        }
+    }
+    for (int shift = 28; shift >= 0; shift -= 4) {
+        float h[16], sure = 0.f;  // sure: members of every candidate of this sweep (their key is 16 steps or more above K)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) h[j] = 0.f;
+        auto take = [&](float zi) {
+            const uint32_t k = float_key(zi);
+            if (k >= K) {  // below K: excluded for good; the set still in play shrinks with every sweep
+                const uint32_t q = (k - K) >> shift;
+                const float e = expf(zi - m);
+                if (q >= 16u) {
+                    sure += e;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) h[j] += (q == (uint32_t)j) ? e : 0.f;
+                }
+            }
+        };
+        if (cached) {
+#pragma unroll
+            for (int c = 0; c < CACHED; ++c) take(zc[c]);
+        } else {
+            for (int i0 = tid; i0 < V; i0 += nthr * 8) {
+                float v[8];
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    const int i = i0 + c * nthr;
+                    v[c] = i < V ? z[i] : -INFINITY;
+                }
+#pragma unroll
+                for (int c = 0; c < 8; ++c) take(v[c]);
+            }
+        }
+        h[15] += sure;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float t = wave_sum(h[j]);
+            if (lane == 0) bins[wave * 16 + j] = t;
+        }
+        __syncthreads();
+        if (tid < 16) {  // bin totals over the waves, one bin per thread
+            float t = 0.f;
+            for (int w = 0; w < nwv; ++w) t += bins[w * 16 + tid];
+            sc[8 + tid] = t;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            if (shift == 28) {
+                float all = 0.f;
+                for (int j = 0; j < 16; ++j) all += sc[8 + j];
+                sc[2] = top_p * all;
+            }
+            const float tgt = sc[2];
+            float above = 0.f;  // mass of the members of candidate j = sum of bins j..15
+            int pick = 0;
+            float pick_mass = 0.f;
+            for (int j = 15; j >= 0; --j) {
+                above += sc[8 + j];
+                if (j == 0 || above >= tgt) {
+                    pick = j;
+                    pick_mass = above;
+                    break;
+                }
+            }
+            sc[0] = __uint_as_float((uint32_t)pick);
+            sc[1] = pick_mass;
+        }
+        __syncthreads();
+        K += __float_as_uint(sc[0]) << shift;
+        mass = sc[1];
+        target = sc[2];
+        __syncthreads();
+    }
+    (void)target;
+    // ---- the draw: every thread owns a run of consecutive ids ----
+    const int chunk = (V + nthr - 1) / nthr;
+    const int i0 = min(tid * chunk, V), i1 = min(i0 + chunk, V);
+    float mine = 0.f;
+    for (int i = i0; i < i1; ++i) {
+        const float zi = z[i];
+        if (float_key(zi) >= K) mine += expf(zi - m);
+    }
+    tmass[tid] = mine;
+    const float wsum = wave_sum(mine);
+    if (lane == 0) bins[wave] = wsum;
+    __syncthreads();
+    if (tid == 0) {
+        const float t = u * mass;
+        float run = 0.f;
+        int w = 0;
+        for (; w < nwv - 1; ++w) {  // the wave whose ids hold the target mass
+            if (run + bins[w] > t) break;
+            run += bins[w];
+        }
+        int th = w * 64;
+        const int th_end = w * 64 + 63;
+        for (; th < th_end; ++th) {
+            if (run + tmass[th] > t) break;
+            run += tmass[th];
+        }
+        sc[3] = __uint_as_float((uint32_t)th);
+        sc[4] = run;
+        sc[5] = t;
+        sc[6] = __uint_as_float(0xFFFFFFFFu);
+    }
+    __syncthreads();
+    const int owner = (int)__float_as_uint(sc[3]);
+    if (tid == owner) {
+        float run = sc[4];
+        const float t = sc[5];
+        int tok = -1, last = -1;
+        for (int i = i0; i < i1; ++i) {
+            const float zi = z[i];
+            if (float_key(zi) >= K) {
+                last = i;
+                run += expf(zi - m);
+                if (run > t) {
+                    tok = i;
+                    break;
+                }
+            }
+        }
+        sc[6] = __uint_as_float((uint32_t)(tok >= 0 ? tok : last));
+    }
+    __syncthreads();
+    int tok = (int)__float_as_uint(sc[6]);
+    if (tok < 0) {  // rounding left the target beyond the last member: take the highest member id
+        int best = -1;
+        for (int i = tid; i < V; i += nthr)
+            if (float_key(z[i]) >= K) best = max(best, i);
+        for (int o = 32; o > 0; o >>= 1) best = max(best, __shfl_xor(best, o, 64));
+        if (lane == 0) bins[wave] = __int_as_float(best);
+        __syncthreads();
+        for (int w = 0; w < nwv; ++w) tok = max(tok, __float_as_int(bins[w]));
+    }
+    return tok;
+}
+
+template <bool SAMPLE>
 __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
     float* rm = (float*)lds;
     float* rsum = rm + kMaxRows;
@@ -1333,6 +1505,32 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
         }
         __syncthreads();
     }
+    // Sampling variant: the token that will be committed is drawn by the whole workgroup from the row the
+    // policy selects (the last row of a step; row r of a review), at the position it will occupy.
+    int drawn = -1;
+    if (SAMPLE && a.top_p > 0.f && a.mode <= 2) {
+        int* sel = (int*)(lds + kFinishLds);  // [0] row, [1] position
+        if (tid == 0) {
+            int row = a.T - 1, pos = c->y_len;
+            if (a.mode == 1) {
+                const int n = a.T - 1;
+                const float alpha = c->alpha_rb;
+                row = n;
+                for (int i = 0; i < n; ++i)
+                    if ((rm[i] + logf(rsum[i])) - a.zt[a.row_off + i] > alpha) {
+                        row = i;
+                        break;
+                    }
+                pos = c->draft_start + row;
+            }
+            sel[0] = row;
+            sel[1] = pos;
+        }
+        __syncthreads();
+        const int row = sel[0], pos = sel[1];
+        drawn = nucleus_draw(a.logits + (size_t)(a.row_off + row) * a.vocab, a.vocab, rm[row], a.top_p, a.u[pos],
+                             lds + kFinishLds + 16);
+    }
     if (tid == 0) {
         const int w = a.which;
         const int y_len = c->y_len, ds = c->draft_start, n_max = c->n_max;
@@ -1341,7 +1539,7 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
         } else {
             for (int t = 0; t < a.T; ++t) c->res_rowtok[t] = ridx[t];
             if (a.mode == 0 || a.mode == 2) {
-                const int tok = ridx[a.T - 1];
+                const int tok = drawn >= 0 ? drawn : ridx[a.T - 1];
                 const float pmax = 1.f / rsum[a.T - 1];
                 const bool low = (a.mode == 0) && (pmax < c->alpha_fb);
                 const bool forced = (a.mode == 0) && n_max > 0 && (y_len - ds) >= n_max;
@@ -1364,7 +1562,7 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
                     c->res_nll[i] = nll;
                     if (r == n && nll > alpha) r = i;
                 }
-                const int tok = ridx[r];
+                const int tok = drawn >= 0 ? drawn : ridx[r];
                 a.y[ds + r] = tok;
                 c->y_len = ds + r + 1;
                 c->len[1] = ds + r;
@@ -1391,7 +1589,12 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
 #ifndef BILD_DEVICE_ONLY
 __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[kFinishLds];
-    finish_body(a, lds);
+    finish_body<false>(a, lds);
+}
+
+__global__ __launch_bounds__(1024) void finish_sample_kernel(const FinishArgs a) {
+    __shared__ __attribute__((aligned(16))) char lds[kFinishLds + 16 + kDrawLds];
+    finish_body<true>(a, lds);
 }
 
 __global__ __launch_bounds__(256) void row_copy_kernel(const RowCopyArgs a) {
@@ -1418,6 +1621,11 @@ hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream
 }
 
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st) {
+    if (a.top_p > 0.f && a.mode <= 2) {
+        if (!a.logits || !a.u || a.vocab < 1) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(finish_sample_kernel, dim3(1), dim3(1024), 0, st, a);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(256), 0, st, a);
     return hipGetLastError();
 }

@@ -1,0 +1,155 @@
+"""GPU parity of the sampling variant (Appendix, "BiLD with Sampling"): both models draw their tokens from
+the nucleus of their distribution, with the uniform numbers passed in from the seeded input generator, and
+the drawn tokens / flags / rollback indices are compared with the oracle step by step.
+
+Margin rule: a difference is excused only where the ORACLE's own decision was marginal - u * mass within
+`margin` (relative) of a running-mass boundary or the nucleus cut within `margin` of top_p, or one of the
+usual threshold margins.  fp32 models use 1e-3; bf16 models 4x their logit tolerance, because a logit
+error of that size moves every probability by as much."""
+import numpy as np
+import pytest
+
+import bild_inputs as bi
+import oracle
+import paper_2302_07863_amd as pkg
+from tests import parity
+from tests.test_gpu_parity import Rig, TOY_VARIANTS
+
+pytestmark = pytest.mark.gpu
+TOP_P = 0.8
+
+
+def _uniforms(cfg, n):
+    return bi.make_uniforms(n, cfg.input_seed, 0), bi.make_uniforms(n, cfg.input_seed, 1)
+
+
+def _margin(cfg):
+    return parity.MARGIN if cfg.large.dtype == bi.DT_F32 else 4 * parity.logit_tol(cfg)
+
+
+def _marginal(rec, fb, rb, margin):
+    if rec.get("draw_margin") is not None and rec["draw_margin"] < margin:
+        return True
+    if rec["kind"] == "small":
+        return abs(rec["pmax"] - fb) < margin
+    return any(abs(v - rb) < margin for v in rec["nll"])
+
+
+def replay(state, ref, n0, fb, rb, margin):
+    """Replays the oracle's trajectory through small_step / large_verify, comparing every drawn token, flag
+    and rollback index; after an excused difference the GPU is forced back onto the oracle's sequence."""
+    y = list(state.sequence())
+    ds = n0
+    excused = steps = 0
+    for rec in ref.trace:
+        steps += 1
+        if rec["kind"] == "small":
+            tok, flag, pmax = state.small_step(fb)
+            if not rec["fallback"]:
+                y.append(rec["tok"])
+            good = bool(flag) == rec["fallback"] and tok == rec["tok"]
+        else:
+            n, r_ref = rec["n"], rec["r"]
+            out, r, nll = state.large_verify(rb)
+            y = y[:ds + r_ref] + [rec["tok"]]
+            good = r == r_ref and out[-1] == rec["tok"]
+            ds = len(y)
+        if not good:
+            assert _marginal(rec, fb, rb, margin), ({k: v for k, v in rec.items() if k != "z"},)
+            excused += 1
+            state.force_tokens(n0, y[n0:], ds)
+    assert state.sequence() == y
+    return dict(steps=steps, excused=excused)
+
+
+def free_running(tokens, stats, ref, n0, fb, rb, margin):
+    if tokens == ref.tokens:
+        for k in ("small_steps", "large_calls", "rows_verified", "rollbacks", "tokens_discarded"):
+            assert stats[k] == getattr(ref.stats, k), k
+        return True
+    first = next((i for i in range(min(len(tokens), len(ref.tokens))) if tokens[i] != ref.tokens[i]),
+                 min(len(tokens), len(ref.tokens)))
+    for rec in ref.trace:                                   # some decision up to that token was marginal
+        pos = rec["pos"] if rec["kind"] == "small" else rec["draft_start"] + rec["r"]
+        if _marginal(rec, fb, rb, margin):
+            return False
+        if pos - n0 > first + 32:
+            break
+    raise AssertionError(f"tokens differ at {first} without a marginal oracle decision")
+
+
+@pytest.mark.parametrize("name", ["f32-relu-tied", "f32-geglu-untied", "f32-rope-swiglu-deconly", "f32-wide",
+                                  "bf16-relu-tied"])
+def test_sampling_toy_parity(name):
+    R = Rig(bi.toy_pair(**TOY_VARIANTS[name]))
+    cfg = R.cfg
+    n = R.n0 + cfg.max_new + 1
+    us, ul = _uniforms(cfg, n)
+    smp = oracle.Sampler(TOP_P, us, ul)
+    for fb, rb, nm in ((0.5, 2.0, 10), (0.2, 0.7, 3)):
+        ref = oracle.bild_generate(R.req, fb, rb, nm, cfg.max_new, sampler=smp)
+        st = R.state(cfg.max_new, nm)
+        st.set_sampling(TOP_P, us, ul)
+        st.encode(R.src)
+        res = replay(st, ref, R.n0, fb, rb, _margin(cfg))
+        toks, stats = st.generate(R.src, fb, rb, cfg.max_new)
+        print(name, fb, rb, res, free_running(toks, stats, ref, R.n0, fb, rb, _margin(cfg)), stats)
+
+
+def test_sampling_tiny_config_and_limits():
+    cfg = bi.tiny_pair()
+    R = Rig(cfg)
+    n = R.n0 + cfg.max_new + 1
+    us, ul = _uniforms(cfg, n)
+    st = R.state(cfg.max_new, cfg.n_max)
+    greedy_toks, greedy_stats = st.generate(R.src, cfg.alpha_fb, cfg.alpha_rb, cfg.max_new)
+    for top_p in (0.8, 0.5, 1.0):
+        smp = oracle.Sampler(top_p, us, ul)
+        ref = oracle.bild_generate(R.req, cfg.alpha_fb, cfg.alpha_rb, cfg.n_max, cfg.max_new, sampler=smp)
+        st.set_sampling(top_p, us, ul)
+        st.encode(R.src)
+        res = replay(st, ref, R.n0, cfg.alpha_fb, cfg.alpha_rb, parity.MARGIN)
+        toks, stats = st.generate(R.src, cfg.alpha_fb, cfg.alpha_rb, cfg.max_new)
+        print("tiny", top_p, res, free_running(toks, stats, ref, R.n0, cfg.alpha_fb, cfg.alpha_rb, parity.MARGIN))
+        assert ref.tokens != greedy_toks
+        # large-only sampling (vanilla inference with draws)
+        g = oracle.greedy(R.req, "large", 16, sampler=smp)
+        got = st.greedy(pkg.LARGE, R.src, 16)
+        assert got == g.tokens or min(r["draw_margin"] for r in g.trace) < parity.MARGIN
+    # a nucleus that only ever holds the most likely token is argmax decoding, and so is switching sampling off
+    st.set_sampling(1e-9, us, ul)
+    assert st.generate(R.src, cfg.alpha_fb, cfg.alpha_rb, cfg.max_new) == (greedy_toks, greedy_stats)
+    st.set_sampling(TOP_P, us, ul)
+    st.set_sampling(0.0)
+    assert st.generate(R.src, cfg.alpha_fb, cfg.alpha_rb, cfg.max_new) == (greedy_toks, greedy_stats)
+
+
+def test_sampling_argument_errors():
+    R = Rig(bi.toy_pair())
+    st = R.state(R.cfg.max_new, 4)
+    n = R.n0 + R.cfg.max_new + 1
+    us, ul = _uniforms(R.cfg, n)
+    for bad in (lambda: st.set_sampling(1.5, us, ul), lambda: st.set_sampling(0.8, us[:3], ul[:3]),
+                lambda: st.set_sampling(0.8, us + 1.0, ul)):
+        with pytest.raises(pkg.BildError) as e:
+            bad()
+        assert e.value.code == -1
+    toks, _ = st.generate(R.src, 0.5, 2.0, 8)               # still usable, still greedy
+    assert toks == oracle.bild_generate(R.req, 0.5, 2.0, 4, 8).tokens
+
+
+@pytest.mark.timeout(900)
+def test_sampling_t5_full_size():
+    """Config 2 at full size with nucleus sampling: 32k-wide rows, bf16."""
+    cfg = bi.t5_pair()
+    R = Rig(cfg)
+    n = R.n0 + cfg.max_new + 1
+    us, ul = _uniforms(cfg, n)
+    smp = oracle.Sampler(TOP_P, us, ul)
+    ref = oracle.bild_generate(R.req, cfg.alpha_fb, cfg.alpha_rb, cfg.n_max, cfg.max_new, sampler=smp)
+    st = R.state(cfg.max_new, cfg.n_max)
+    st.set_sampling(TOP_P, us, ul)
+    st.encode(R.src)
+    res = replay(st, ref, R.n0, cfg.alpha_fb, cfg.alpha_rb, _margin(cfg))
+    print("t5 sampled", res, ref.stats, flush=True)
+    assert res["excused"] <= res["steps"] // 4
