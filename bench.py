@@ -228,6 +228,8 @@ def main() -> int:
         "large_only_tokens_per_s": round(large_tok_s, 2),
         "speedup_vs_large_only": round(tok_s / large_tok_s, 3),
         "encode_ms": round(encode_ms, 2),
+        # per request, the paper's "end-to-end latency per example": encode (or prompt prefill) + generation
+        "end_to_end_tokens_per_s": round(n_tok / (encode_ms * 1e-3 + dt / args.steps), 2),
         "passes": passes,
     }
     print(json.dumps(out), flush=True)

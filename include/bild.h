@@ -272,6 +272,18 @@ int bild_profile_end(bild_state* s, bild_profile* out);
  * with `rows` new rows (weights + LM head + self K/V + cross K/V). */
 int64_t bild_pass_bytes(const bild_state* s, int which, int t_cache, int rows);
 
+/* Host logic exposed for tests (no device work).
+ * bild_debug_tile_matrix: re-lays a row-major matrix into the streaming tile order the kernels read
+ * (1 KiB tiles of 16 features x 32 inputs for bf16, x 16 for fp32; inside a tile the 16 bytes of lane l hold
+ * feature l % 16, inputs (l / 16) * KT/4 .. +KT/4-1; tiles of a feature block contiguous along the inputs; features
+ * beyond n are zero).  src is [k][n] if src_is_k_by_n else [n][k]; dst has bild_debug_tiled_bytes(n, k, dtype) bytes.
+ * bild_debug_gemm_shape: the launch shape the library would choose for a projection of n features x k inputs over
+ * `rows` rows: out = {input slices per workgroup, waves per workgroup, feature tiles per wave, inputs per LDS chunk,
+ * feature-group workgroups, row blocks, dynamic LDS bytes, LDS limit}. */
+int64_t bild_debug_tiled_bytes(int n, int k, int dtype);
+int bild_debug_tile_matrix(const float* src, int src_is_k_by_n, int n, int k, int dtype, void* dst);
+int bild_debug_gemm_shape(int n, int k, int rows, int gated, int lm_head, int dtype, int32_t out[8]);
+
 const char* bild_strerror(int code);
 
 #ifdef __cplusplus

@@ -76,6 +76,9 @@ _SIGS = {
     "bild_bench_gemm": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int64),
                                   C.POINTER(C.c_int64)]),
     "bild_gemm_tally": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_int]),
+    "bild_debug_tiled_bytes": (C.c_int64, [C.c_int, C.c_int, C.c_int]),
+    "bild_debug_tile_matrix": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "bild_debug_gemm_shape": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32)]),
     "bild_probe_copy": (C.c_int, [C.c_void_p, C.c_int64, C.c_int]),
     "bild_profile_begin": (C.c_int, [C.c_void_p, C.c_int]),
     "bild_profile_end": (C.c_int, [C.c_void_p, C.POINTER(Profile)]),
@@ -296,3 +299,22 @@ class State:
 
     def pass_bytes(self, which: int, t_cache: int, rows: int = 1) -> int:
         return int(lib().bild_pass_bytes(self.h, which, t_cache, rows))
+
+
+def tile_matrix(src: np.ndarray, src_is_k_by_n: bool, dtype: int) -> np.ndarray:
+    """Host re-layout of a matrix into the kernels' streaming tile order (bytes)."""
+    a = np.ascontiguousarray(src, dtype=np.float32)
+    k, n = a.shape if src_is_k_by_n else a.shape[::-1]
+    nbytes = int(lib().bild_debug_tiled_bytes(n, k, dtype))
+    if nbytes < 0:
+        raise BildError(nbytes, "bild_debug_tiled_bytes")
+    out = np.zeros(nbytes, dtype=np.uint8)
+    _check(lib().bild_debug_tile_matrix(a.ctypes.data, int(src_is_k_by_n), n, k, dtype, out.ctypes.data), "bild_debug_tile_matrix")
+    return out
+
+
+def gemm_shape(n: int, k: int, rows: int, gated: bool = False, lm_head: bool = False, dtype: int = 1) -> dict:
+    out = (C.c_int32 * 8)()
+    _check(lib().bild_debug_gemm_shape(n, k, rows, int(gated), int(lm_head), dtype, out), "bild_debug_gemm_shape")
+    keys = ("wk", "nwv", "rw", "kc", "blocks", "row_blocks", "lds", "lds_limit")
+    return dict(zip(keys, [int(v) for v in out]))

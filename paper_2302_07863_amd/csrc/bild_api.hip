@@ -1614,6 +1614,42 @@ extern "C" int64_t bild_pass_bytes(const bild_state* s, int which, int t_cache, 
     return elems * B;
 }
 
+extern "C" int64_t bild_debug_tiled_bytes(int n, int k, int dtype) {
+    if (n < 1 || k < 32 || k % 32 || dtype < 0 || dtype > 1) return BILD_EINVAL;
+    return (int64_t)tiled_bytes(n, k, dtype);
+}
+
+extern "C" int bild_debug_tile_matrix(const float* src, int src_is_k_by_n, int n, int k, int dtype, void* dst) {
+    if (!src || !dst || n < 1 || k < 32 || k % 32 || dtype < 0 || dtype > 1) return BILD_EINVAL;
+    tile_matrix(src, src_is_k_by_n != 0, n, k, dtype, dst);
+    return BILD_OK;
+}
+
+extern "C" int bild_debug_gemm_shape(int n, int k, int rows, int gated, int lm_head, int dtype, int32_t out[8]) {
+    if (!out || n < 1 || k < 32 || k % 32 || rows < 1 || dtype < 0 || dtype > 1) return BILD_EINVAL;
+    if (lm_head && rows > kMaxRows) return BILD_EINVAL;
+    GemmArgs g;
+    std::memset((void*)&g, 0, sizeof(g));
+    const int kt = dtype ? 32 : 16;
+    g.W.n = gated ? 2 * n : n;  // gate and linear branch interleaved by tile
+    g.W.k = k;
+    g.W.tn = (g.W.n + 15) / 16;
+    g.W.tk = k / kt;
+    g.T = rows;
+    g.epi = lm_head ? EPI_LMHEAD : (gated ? EPI_ACT : EPI_STORE);
+    g.act = gated ? BILD_ACT_SWIGLU : BILD_ACT_RELU;
+    gemm_pick_shape(g, dtype);
+    out[0] = g.wk;
+    out[1] = g.nwv;
+    out[2] = g.rw;
+    out[3] = g.kc;
+    out[4] = (int32_t)gemm_num_blocks(g);
+    out[5] = (rows + kMaxRows - 1) / kMaxRows;
+    out[6] = (int32_t)gemm_lds_bytes(g, dtype);
+    out[7] = 128 * 1024;
+    return BILD_OK;
+}
+
 extern "C" const char* bild_strerror(int code) {
     switch (code) {
         case BILD_OK: return "ok";

@@ -688,9 +688,11 @@ static int gemm_pick_chunks(GemmArgs& a, int dtype) {
     const int kt = dtype ? 32 : 16;
     const bool gated = a.epi == EPI_ACT && a.act != BILD_ACT_RELU;
     a.rw = gated ? 2 : 1;
-    // input chunks staged in LDS: at most 96 KiB, balanced so that every chunk has the same tile count +-1
+    // input chunks staged in LDS: at most 96 KiB and never more than the limit leaves beside the largest
+    // reduction area (8 waves), balanced so that every chunk has the same tile count +-1
     const int Tb = std::min(a.T, kMaxRows);  // rows one workgroup handles (more rows: more row blocks)
-    int kc_max = 24576 / Tb - 8;
+    const int budget = std::min(96 * 1024, 128 * 1024 - gemm_tail_bytes(8, a.rw * ((Tb + 15) / 16)));
+    int kc_max = budget / (4 * Tb) - 8;      // 4 bytes of LDS per staged input for either storage type
     kc_max = std::max(128, (kc_max / 128) * 128);
     const int nch = (a.W.k + kc_max - 1) / kc_max;
     const int kc = ((a.W.k + nch - 1) / nch + kt - 1) / kt * kt;

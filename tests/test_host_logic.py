@@ -1,0 +1,77 @@
+"""Host logic of the library, without a GPU: the weight re-layout against the documented tile order written
+out independently in numpy, and invariants of the GEMM launch shapes over the shapes of every configuration."""
+import numpy as np
+import pytest
+
+import bild_inputs as bi
+from paper_2302_07863_amd import binding as b
+
+
+def _bf16_bits(x):
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return (((u + 0x7FFF + ((u >> 16) & 1)) >> 16) & 0xFFFF).astype(np.uint16)
+
+
+def _expected_tiles(w_n_by_k, dtype):
+    """Tile order from its description: tiles of 16 features x KT inputs, 1 KiB each, feature blocks outermost and
+    tiles of a block contiguous along the inputs; lane l of a tile owns feature l % 16 and KT/4 consecutive inputs
+    starting at (l // 16) * KT/4."""
+    n, k = w_n_by_k.shape
+    kt = 32 if dtype == bi.DT_BF16 else 16
+    per = kt // 4
+    tn = (n + 15) // 16
+    padded = np.zeros((tn * 16, k), dtype=np.float32)
+    padded[:n] = w_n_by_k
+    t = padded.reshape(tn, 16, k // kt, 4, per)          # [block, feature, k tile, lane group, j]
+    t = t.transpose(0, 2, 3, 1, 4)                          # [block, k tile, lane group, feature, j] = lanes in order
+    flat = np.ascontiguousarray(t).reshape(-1)
+    return _bf16_bits(flat).view(np.uint8) if dtype == bi.DT_BF16 else flat.view(np.uint8)
+
+
+@pytest.mark.parametrize("dtype", [bi.DT_F32, bi.DT_BF16])
+@pytest.mark.parametrize("n,k", [(16, 32), (40, 96), (200, 64), (33, 160)])
+def test_tile_matrix_matches_the_documented_order(dtype, n, k):
+    rng = np.random.default_rng(n * 1000 + k)
+    w = rng.normal(size=(n, k)).astype(np.float32)
+    want = _expected_tiles(w, dtype)
+    assert np.array_equal(b.tile_matrix(w, False, dtype), want)
+    assert np.array_equal(b.tile_matrix(np.ascontiguousarray(w.T), True, dtype), want)      # math layout [k][n]
+    assert len(want) == ((n + 15) // 16) * (k // (32 if dtype == bi.DT_BF16 else 16)) * 1024
+
+
+def _projections(shape):
+    d, i, f = shape.d, shape.inner, shape.d_ff
+    out = [(3 * i, d, False, False), (i, d, False, False), (d, i, False, False), (f, d, shape.gated, False),
+           (d, f, False, False), (shape.vocab, d, False, True)]
+    if shape.cross:
+        out.append((2 * i, d, False, False))
+    return out
+
+
+@pytest.mark.parametrize("pair", sorted(bi.PAIRS))
+def test_gemm_launch_shapes_are_consistent(pair):
+    """Every projection of every configuration, for 1..32 rows and for row-block launches: the waves of a workgroup
+    factor into input slices x feature groups, the feature-group workgroups cover every feature tile exactly once,
+    the LDS request fits, and the staged chunk is a whole number of input tiles."""
+    cfg = bi.PAIRS[pair]()
+    for shape in (cfg.small, cfg.large):
+        kt = 32 if shape.dtype == bi.DT_BF16 else 16
+        for n, k, gated, head in _projections(shape):
+            for rows in (1, 2, 3, 4, 7, 11, 16, 17, 32) + (() if head else (33, 512, 1000)):
+                s = b.gemm_shape(n, k, rows, gated, head, shape.dtype)
+                tiles = ((2 * n if gated else n) + 15) // 16
+                assert s["nwv"] in (1, 2, 4, 8) and s["nwv"] % s["wk"] == 0, (n, k, rows, s)
+                assert s["rw"] == (2 if gated else 1)
+                per_wg = (s["nwv"] // s["wk"]) * s["rw"]
+                assert (s["blocks"] - 1) * per_wg < tiles <= s["blocks"] * per_wg, (n, k, rows, s)
+                assert s["row_blocks"] == (rows + 31) // 32
+                assert 0 < s["lds"] <= s["lds_limit"], (n, k, rows, s)
+                assert s["kc"] % kt == 0 and s["kc"] >= kt
+                assert s["wk"] <= max(1, min(s["kc"], k) // kt)
+
+
+def test_debug_calls_reject_bad_arguments():
+    lib = b.lib()
+    assert lib.bild_debug_tiled_bytes(0, 32, 0) == b.EINVAL
+    assert lib.bild_debug_tiled_bytes(16, 40, 1) == b.EINVAL
+    assert lib.bild_debug_gemm_shape(16, 32, 0, 0, 0, 0, None) == b.EINVAL
