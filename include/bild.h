@@ -283,6 +283,9 @@ int64_t bild_pass_bytes(const bild_state* s, int which, int t_cache, int rows);
 int64_t bild_debug_tiled_bytes(int n, int k, int dtype);
 int bild_debug_tile_matrix(const float* src, int src_is_k_by_n, int n, int k, int dtype, void* dst);
 int bild_debug_gemm_shape(int n, int k, int rows, int gated, int lm_head, int dtype, int32_t out[8]);
+/* The launch shape of attention for `rows` query rows over nkeys cached keys: out = {key splits, 1 if the consumer
+ * projection merges the split partials (no merge kernel), waves per workgroup, dynamic LDS bytes}. */
+int bild_debug_attn_shape(int heads, int d_head, int rows, int nkeys, int max_splits, int dtype, int32_t out[4]);
 
 const char* bild_strerror(int code);
 

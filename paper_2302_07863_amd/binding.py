@@ -78,6 +78,7 @@ _SIGS = {
     "bild_gemm_tally": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_int]),
     "bild_debug_tiled_bytes": (C.c_int64, [C.c_int, C.c_int, C.c_int]),
     "bild_debug_tile_matrix": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "bild_debug_attn_shape": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32)]),
     "bild_debug_gemm_shape": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32)]),
     "bild_probe_copy": (C.c_int, [C.c_void_p, C.c_int64, C.c_int]),
     "bild_profile_begin": (C.c_int, [C.c_void_p, C.c_int]),
@@ -318,3 +319,9 @@ def gemm_shape(n: int, k: int, rows: int, gated: bool = False, lm_head: bool = F
     _check(lib().bild_debug_gemm_shape(n, k, rows, int(gated), int(lm_head), dtype, out), "bild_debug_gemm_shape")
     keys = ("wk", "nwv", "rw", "kc", "blocks", "row_blocks", "lds", "lds_limit")
     return dict(zip(keys, [int(v) for v in out]))
+
+
+def attn_shape(heads: int, d_head: int, rows: int, nkeys: int, max_splits: int = 8, dtype: int = 1) -> dict:
+    out = (C.c_int32 * 4)()
+    _check(lib().bild_debug_attn_shape(heads, d_head, rows, nkeys, max_splits, dtype, out), "bild_debug_attn_shape")
+    return dict(zip(("splits", "defer", "waves", "lds"), [int(v) for v in out]))

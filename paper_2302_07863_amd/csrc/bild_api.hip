@@ -576,11 +576,10 @@ int pull_ctl(bild_state* s) {
 // proportion: a CU sustains under 30 GB/s).  Partials merged by the consumer cost no kernel but it reads
 // splits x rows of them, so that route is limited to 8 splits and splits * rows <= 16; the merge kernel
 // costs about 5 us and therefore only pays when it brings a workgroup from above 160 KiB down to 128 KiB.
-int pick_splits(const ModelState& M, int nkeys, int heads, int T, bool* defer) {
-    const bild_model_config& c = M.m->cfg;
-    const size_t per_head = (size_t)nkeys * c.d_head * 2 * M.m->esz();
+int pick_splits_raw(int d_head, int esz, int max_splits, int nkeys, int heads, int T, bool* defer) {
+    const size_t per_head = (size_t)nkeys * d_head * 2 * esz;
     const size_t want = (size_t)(T <= 4 ? 32 : (T <= 8 ? 64 : 128)) << 10;
-    auto fits = [&](int sp) { return sp <= M.max_splits && heads * sp <= 512; };
+    auto fits = [&](int sp) { return sp <= max_splits && heads * sp <= 512; };
     int d_sp = 1;  // deferred route: as many splits as it allows, up to the wanted size
     while (per_head / d_sp > want && d_sp * 2 <= 8 && d_sp * 2 * T <= 16 && fits(d_sp * 2)) d_sp *= 2;
     *defer = d_sp > 1;
@@ -589,6 +588,10 @@ int pick_splits(const ModelState& M, int nkeys, int heads, int T, bool* defer) {
     while (per_head / sp > ((size_t)128 << 10) && fits(sp * 2)) sp *= 2;
     if (sp > d_sp) *defer = false;
     return sp;
+}
+
+int pick_splits(const ModelState& M, int nkeys, int heads, int T, bool* defer) {
+    return pick_splits_raw(M.m->cfg.d_head, M.m->esz(), M.max_splits, nkeys, heads, T, defer);
 }
 
 int pick_attn_waves(int dtype, int d_head, int T, int nkeys, int splits) {
@@ -1647,6 +1650,19 @@ extern "C" int bild_debug_gemm_shape(int n, int k, int rows, int gated, int lm_h
     out[5] = (rows + kMaxRows - 1) / kMaxRows;
     out[6] = (int32_t)gemm_lds_bytes(g, dtype);
     out[7] = 128 * 1024;
+    return BILD_OK;
+}
+
+extern "C" int bild_debug_attn_shape(int heads, int d_head, int rows, int nkeys, int max_splits, int dtype, int32_t out[4]) {
+    if (!out || heads < 1 || d_head < 8 || d_head > 128 || rows < 1 || nkeys < 1 || max_splits < 1 || dtype < 0 || dtype > 1)
+        return BILD_EINVAL;
+    bool defer = false;
+    const int sp = rows > kMaxRows ? 1 : pick_splits_raw(d_head, dtype ? 2 : 4, max_splits, nkeys, heads, rows, &defer);
+    const int nw = pick_attn_waves(dtype, d_head, std::min(rows, kMaxRows), nkeys, sp);
+    out[0] = sp;
+    out[1] = (sp > 1 && defer) ? 1 : 0;
+    out[2] = nw;
+    out[3] = (int32_t)attn_lds_bytes(dtype, d_head, std::min(rows, kMaxRows), nw);
     return BILD_OK;
 }
 

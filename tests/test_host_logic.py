@@ -70,6 +70,30 @@ def test_gemm_launch_shapes_are_consistent(pair):
                 assert s["wk"] <= max(1, min(s["kc"], k) // kt)
 
 
+@pytest.mark.parametrize("pair", sorted(bi.PAIRS))
+def test_attention_launch_shapes_are_consistent(pair):
+    """Key splits stay within the partial buffers and the grid the kernels assume; partials are left to the consumer
+    projection only in the range it merges (at most 8 splits, splits x rows <= 16); the LDS request fits; a workgroup
+    that is not split further streams at most about 160 KiB unless the split limits are exhausted."""
+    cfg = bi.PAIRS[pair]()
+    for shape in (cfg.small, cfg.large):
+        esz = 2 if shape.dtype == bi.DT_BF16 else 4
+        for nkeys in (1, 31, 64, 128, 512, 1024, 2048, 4096):
+            for rows in (1, 2, 4, 5, 8, 9, 11, 16, 32, 33, 700):
+                for max_splits in (8, 16, 64):
+                    s = b.attn_shape(shape.heads, shape.d_head, rows, nkeys, max_splits, shape.dtype)
+                    assert 1 <= s["splits"] <= max_splits and shape.heads * s["splits"] <= max(512, shape.heads)
+                    assert s["splits"] & (s["splits"] - 1) == 0
+                    if rows > 32:
+                        assert s["splits"] == 1
+                    if s["defer"]:
+                        assert 1 < s["splits"] <= 8 and s["splits"] * rows <= 16
+                    assert s["waves"] in (1, 2, 4, 8) and 0 < s["lds"] <= 128 * 1024
+                    per_wg = nkeys * shape.d_head * 2 * esz / s["splits"]
+                    if per_wg > 160 * 1024 and rows <= 32 and not s["defer"]:
+                        assert s["splits"] * 2 > max_splits or shape.heads * s["splits"] * 2 > 512
+
+
 def test_debug_calls_reject_bad_arguments():
     lib = b.lib()
     assert lib.bild_debug_tiled_bytes(0, 32, 0) == b.EINVAL
