@@ -26,6 +26,8 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 
+#include <type_traits>
+
 #include "bild_internal.h"
 
 namespace bild {
@@ -398,6 +400,37 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             // loads (8 per thread, issued together) cover 8 * nthr pieces; 64 consecutive pieces share a row.
             const int total = T * n4;
             const unsigned magic = 0xFFFFFFFFu / (unsigned)n4 + 1u;  // e / n4 == umulhi(e, magic) for e < 2^32 / n4
+            // two to four rows: at most two pieces per thread and exactly the loads needed; more rows: rounds of
+            // eight loads (a four-piece variant beside it made the common two-to-four-row passes slower)
+            auto few_pieces = [&](auto pieces) {
+                constexpr int P = decltype(pieces)::value;
+                float4 v[P], g[P];
+                int tt[P], kk[P];
+#pragma unroll
+                for (int u = 0; u < P; ++u) {
+                    const int e = tid + u * nthr;
+                    v[u] = g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    tt[u] = (int)__umulhi((unsigned)min(e, total - 1), magic);
+                    kk[u] = min(e, total - 1) - tt[u] * n4;
+                    if (e < total) {
+                        v[u] = ldx(tt[u], kk[u]);
+                        if (norm) g[u] = *(const float4*)(a.gain + k0 + kk[u] * 4);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < P; ++u) {
+                    if (tid + u * nthr < total) {  // wave-uniform, like the row index
+                        const float ss = put(tt[u], kk[u], v[u], g[u]);
+                        if (norm) {
+                            const float tot = wave_sum(ss);
+                            if (lane == 0) ssq[wave * 32 + tt[u]] += tot;
+                        }
+                    }
+                }
+            };
+            if (total <= 2 * nthr) {
+                few_pieces(std::integral_constant<int, 2>{});
+            } else
             for (int eb = tid; eb < total; eb += nthr * 8) {
                 float4 v[8], g[8];
 #pragma unroll
@@ -727,7 +760,7 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     }
     // feature groups: as many as keep >= 512 workgroups; at least 4 waves per workgroup, 8 when there are
     // several rows (staging the activations is then the longer part, and it is shared by all waves)
-    int wr = std::max(1, (a.T >= 4 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
+    int wr = std::max(1, (a.T >= 3 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
     for (int c = wr * 2; c * wk <= 8 && c * wk * nacc <= 32; c *= 2)
         if ((a.W.tn + c * a.rw - 1) / (c * a.rw) >= 512) wr = c;
     a.wk = wk;
