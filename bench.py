@@ -181,6 +181,20 @@ def main() -> int:
                                     gbs=round(g_l["bytes"] / g_l["ms_per_pass"] / 1e6, 1)))
     log(f"[bench] roofline {roofline}")
 
+    # The third line of the report: these passes are chains of dependent stages, so beside the bandwidth roofline stands
+    # stage count x the cost of a launch that does nothing.
+    launch_us = st.probe_launch(2000)
+
+    def stages(shape):
+        return 1 + shape.n_dec * (8 if shape.cross else 5) + 2     # embed, layer pieces, LM head, policy
+
+    stage_latency = dict(empty_launch_us=round(launch_us, 3),
+                         small_pass=dict(stages=stages(cfg.small), launch_floor_ms=round(stages(cfg.small) * launch_us * 1e-3, 4),
+                                         measured_ms=passes["small_step"]["ms"]),
+                         large_pass=dict(stages=stages(cfg.large), launch_floor_ms=round(stages(cfg.large) * launch_us * 1e-3, 4),
+                                         measured_ms=passes["large_step"]["ms"]))
+    log(f"[bench] stage latency {stage_latency}")
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -223,6 +237,7 @@ def main() -> int:
                                + (f", nucleus sampling top_p={args.top_p}" if args.top_p > 0 else ""),
                    "tokens_per_step": n_tok},
         "roofline": roofline,
+        "stage_latency": stage_latency,
         "cpu_baseline": cpu,
         "bild_stats": stats,
         "large_only_tokens_per_s": round(large_tok_s, 2),

@@ -262,6 +262,9 @@ int bild_bench_gemm(bild_state* s, int which, int rows, int reps, float* ms_per_
  * `bytes` bytes (a multiple of 16) on temporary buffers: it reads `bytes` and writes `bytes`,
  * the known quantity against which hardware byte counters are scaled. */
 int bild_probe_copy(bild_state* s, int64_t bytes, int reps);
+/* Mean time of `reps` back-to-back launches of a kernel that does nothing (one workgroup per CU) on the state's
+ * stream, in microseconds: the cost of a dependent stage by itself, against which the stage count of a pass is read. */
+int bild_probe_launch(bild_state* s, int reps, float* us_per_launch);
 /* GEMM launches ISSUED by the host since the last reset and the algorithmic weight bytes they stream
  * (replays of captured graphs are not counted: meaningful when graph replay is disabled). */
 int bild_gemm_tally(bild_state* s, int64_t* launches, int64_t* bytes, int reset);

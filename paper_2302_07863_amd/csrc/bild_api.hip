@@ -1551,6 +1551,27 @@ extern "C" int bild_gemm_tally(bild_state* s, int64_t* launches, int64_t* bytes,
     return BILD_OK;
 }
 
+extern "C" int bild_probe_launch(bild_state* s, int reps, float* us_per_launch) {
+    if (!s || reps < 1 || !us_per_launch) return BILD_EINVAL;
+    hipEvent_t e0, e1;
+    HIPC(hipEventCreate(&e0));
+    HIPC(hipEventCreate(&e1));
+    int rc = BILD_OK;
+    for (int i = 0; i < 16 && rc == BILD_OK; ++i)
+        if (launch_probe_empty(s->stream) != hipSuccess) rc = BILD_EHIP;
+    if (rc == BILD_OK && hipEventRecord(e0, s->stream) != hipSuccess) rc = BILD_EHIP;
+    for (int i = 0; i < reps && rc == BILD_OK; ++i)
+        if (launch_probe_empty(s->stream) != hipSuccess) rc = BILD_EHIP;
+    if (rc == BILD_OK && hipEventRecord(e1, s->stream) != hipSuccess) rc = BILD_EHIP;
+    if (rc == BILD_OK && hipEventSynchronize(e1) != hipSuccess) rc = BILD_EHIP;
+    float ms = 0.f;
+    if (rc == BILD_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = BILD_EHIP;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc == BILD_OK) *us_per_launch = ms * 1e3f / (float)reps;
+    return rc;
+}
+
 extern "C" int bild_probe_copy(bild_state* s, int64_t bytes, int reps) {
     if (!s || bytes < 16 || bytes % 16 || reps < 1) return BILD_EINVAL;
     void *a = nullptr, *b = nullptr;

@@ -1650,6 +1650,14 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// A kernel that does nothing on one workgroup per CU: what a dependent launch costs by itself.
+__global__ __launch_bounds__(256) void probe_empty_kernel() {}
+
+hipError_t launch_probe_empty(hipStream_t st) {
+    hipLaunchKernelGGL(probe_empty_kernel, dim3(256), dim3(256), 0, st);
+    return hipGetLastError();
+}
+
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st) {
     hipLaunchKernelGGL(probe_copy_kernel, dim3(4096), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, bytes / 16);
     return hipGetLastError();

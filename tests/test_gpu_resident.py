@@ -63,3 +63,16 @@ def test_resident_barrier_gives_up_cleanly(resident, monkeypatch):
     ref = oracle.bild_generate(R.req, 0.5, 2.0, 4, R.cfg.max_new)
     toks, stats = st2.generate(R.src, 0.5, 2.0, R.cfg.max_new)
     parity.compare_generation(toks, stats, ref, 0.5, 2.0)
+
+
+def test_plain_launches_without_graph_replay(monkeypatch):
+    """BILD_NO_GRAPH=1 (the configuration profiles are taken in): every kernel launched directly, same results."""
+    monkeypatch.setenv("BILD_NO_GRAPH", "1")
+    R = Rig(bi.toy_pair(**TOY_VARIANTS["bf16-trunc-geglu"]))
+    for fb, rb, nm in ((0.5, 2.0, 10), (0.2, 0.7, 3)):
+        ref = oracle.bild_generate(R.req, fb, rb, nm, R.cfg.max_new, keep_logits=True)
+        st = R.state(R.cfg.max_new, nm)
+        st.encode(R.src)
+        print(parity.teacher_forced(st, ref, R.n0, fb, rb, R.cfg))
+        toks, stats = st.generate(R.src, fb, rb, R.cfg.max_new)
+        print(parity.compare_generation(toks, stats, ref, fb, rb))
