@@ -47,6 +47,9 @@ def main() -> int:
     ap.add_argument("--top-p", type=float, default=0.0,
                     help="> 0: the sampling variant, both models draw from the nucleus of this mass (uniform numbers "
                          "from the seeded input generator)")
+    ap.add_argument("--probe-stream", action="store_true",
+                    help="no benchmark: print how fast 1..256 workgroups stream private regions of 32 KiB..1 MiB "
+                         "(the per-compute-unit bandwidth the launch shapes are built around)")
     ap.add_argument("--alpha-fb", type=float, default=None)
     ap.add_argument("--alpha-rb", type=float, default=None)
     args = ap.parse_args()
@@ -89,6 +92,15 @@ def main() -> int:
     t0 = time.perf_counter()
     st.encode(src)
     encode_ms = (time.perf_counter() - t0) * 1e3
+
+    if args.probe_stream:
+        print("groups  KiB/group   us/launch   GB/s per group   GB/s total")
+        for groups in (1, 8, 32, 64, 128, 256, 512):
+            for kib in (32, 64, 128, 256, 512, 1024):
+                us = st.probe_stream(groups, kib, 8)
+                print(f"{groups:6d} {kib:10d} {us:11.2f} {kib * 1.024 / us * 1e0:16.1f} {groups * kib * 1.024 / us:12.1f}", flush=True)
+        print(f"empty launch: {st.probe_launch(2000):.2f} us")
+        return 0
 
     if args.pmc_probe:
         st.gemm_tally(reset=True)          # count the decode GEMMs only (the encoder's row-block GEMMs are another kernel)

@@ -265,6 +265,11 @@ int bild_probe_copy(bild_state* s, int64_t bytes, int reps);
 /* Mean time of `reps` back-to-back launches of a kernel that does nothing (one workgroup per CU) on the state's
  * stream, in microseconds: the cost of a dependent stage by itself, against which the stage count of a pass is read. */
 int bild_probe_launch(bild_state* s, int reps, float* us_per_launch);
+/* Mean time (microseconds, launch included) of a kernel in which `groups` workgroups of 8 waves each stream a private
+ * contiguous region of kib_per_group KiB that no earlier launch touched: the streaming rate of one compute unit
+ * (groups = 1) and how the total grows with the number of workgroups.  reps <= 64; the probe allocates
+ * groups * kib_per_group KiB * (reps + 1) for its own use (at most 16 GiB, else BILD_EINVAL) and frees it. */
+int bild_probe_stream(bild_state* s, int groups, int kib_per_group, int reps, float* us_per_launch);
 /* GEMM launches ISSUED by the host since the last reset and the algorithmic weight bytes they stream
  * (replays of captured graphs are not counted: meaningful when graph replay is disabled). */
 int bild_gemm_tally(bild_state* s, int64_t* launches, int64_t* bytes, int reset);

@@ -76,6 +76,7 @@ _SIGS = {
     "bild_bench_gemm": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int64),
                                   C.POINTER(C.c_int64)]),
     "bild_gemm_tally": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_int]),
+    "bild_probe_stream": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float)]),
     "bild_probe_launch": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_float)]),
     "bild_debug_tiled_bytes": (C.c_int64, [C.c_int, C.c_int, C.c_int]),
     "bild_debug_tile_matrix": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
@@ -282,6 +283,11 @@ class State:
         n, b = C.c_int64(), C.c_int64()
         _check(lib().bild_gemm_tally(self.h, C.byref(n), C.byref(b), int(reset)), "bild_gemm_tally")
         return dict(launches=n.value, bytes=b.value)
+
+    def probe_stream(self, groups: int, kib_per_group: int, reps: int = 8) -> float:
+        us = C.c_float()
+        _check(lib().bild_probe_stream(self.h, groups, kib_per_group, reps, C.byref(us)), "bild_probe_stream")
+        return us.value
 
     def probe_launch(self, reps: int = 2000) -> float:
         us = C.c_float()

@@ -1572,6 +1572,43 @@ extern "C" int bild_probe_launch(bild_state* s, int reps, float* us_per_launch) 
     return rc;
 }
 
+extern "C" int bild_probe_stream(bild_state* s, int groups, int kib_per_group, int reps, float* us_per_launch) {
+    if (!s || !us_per_launch || groups < 1 || groups > 4096 || kib_per_group < 1 || kib_per_group > (1 << 16) || reps < 1 || reps > 64)
+        return BILD_EINVAL;
+    // every launch reads a region no earlier launch touched, so nothing comes from a cache
+    const size_t per_launch = (size_t)groups * kib_per_group * 1024;
+    if (per_launch * (size_t)(reps + 1) > ((size_t)16 << 30)) return BILD_EINVAL;
+    void *buf = nullptr, *sink = nullptr;
+    if (hipMalloc(&buf, per_launch * (reps + 1)) != hipSuccess) return BILD_ENOMEM;
+    if (hipMalloc(&sink, 64) != hipSuccess) {
+        (void)hipFree(buf);
+        return BILD_ENOMEM;
+    }
+    int rc = BILD_OK;
+    if (hipMemsetAsync(buf, 0, per_launch * (reps + 1), s->stream) != hipSuccess) rc = BILD_EHIP;
+    if (rc == BILD_OK && launch_probe_stream(buf, (size_t)kib_per_group, groups, sink, s->stream) != hipSuccess) rc = BILD_EHIP;  // warm-up
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (rc == BILD_OK && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)) rc = BILD_EHIP;
+    float total_ms = 0.f;
+    // one bracket around all launches: launches on one stream run one after the other, so the mean holds the same
+    // launch-to-launch gap a stage of a pass pays, and not the cost of the events
+    if (rc == BILD_OK && hipEventRecord(e0, s->stream) != hipSuccess) rc = BILD_EHIP;
+    for (int i = 0; i < reps && rc == BILD_OK; ++i) {
+        const char* region = (const char*)buf + per_launch * (size_t)(i + 1);
+        if (launch_probe_stream(region, (size_t)kib_per_group, groups, sink, s->stream) != hipSuccess) rc = BILD_EHIP;
+    }
+    if (rc == BILD_OK && (hipEventRecord(e1, s->stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                          hipEventElapsedTime(&total_ms, e0, e1) != hipSuccess))
+        rc = BILD_EHIP;
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipStreamSynchronize(s->stream);
+    (void)hipFree(buf);
+    (void)hipFree(sink);
+    if (rc == BILD_OK) *us_per_launch = total_ms * 1e3f / (float)reps;
+    return rc;
+}
+
 extern "C" int bild_probe_copy(bild_state* s, int64_t bytes, int reps) {
     if (!s || bytes < 16 || bytes % 16 || reps < 1) return BILD_EINVAL;
     void *a = nullptr, *b = nullptr;

@@ -220,6 +220,7 @@ hipError_t launch_finish(const FinishArgs& a, hipStream_t st);
 hipError_t launch_row_copy(const RowCopyArgs& a, hipStream_t st);
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 hipError_t launch_probe_empty(hipStream_t st);
+hipError_t launch_probe_stream(const void* src, size_t kib_per_group, int groups, void* sink, hipStream_t st);
 hipError_t kernels_init();  // one-time function attributes; call before any stream capture
 size_t gemm_num_blocks(const GemmArgs& a);
 size_t attn_lds_bytes(int dtype, int d_head, int T, int nw);

@@ -176,15 +176,17 @@ __device__ __forceinline__ void st_u16(uint16_t* p, uint16_t v) {
 // Skinny GEMM.  A workgroup has nwv = wk * wr wavefronts arranged as wr feature groups
 // x wk input slices; each wave owns RW feature tiles (16 features each) and walks the
 // input tiles of its slice, U tiles per batch so that one batch of loads covers one
-// round trip to HBM.  The first batch is issued before anything else in the kernel
-// (weights do not depend on the activations), so the activation staging, the barrier
-// and the residual read overlap with the first weight loads.  LDS layout (dynamic):
+// round trip to HBM.  Weights do not depend on the activations: the first two batches
+// are requested right behind the activation loads and before anything is waited for,
+// so the conversion of the activations, the barrier and the residual read all overlap
+// with the weights' trip from memory.  LDS layout (dynamic):
 //   (at most 8 waves per workgroup, so that a wave may use 256 registers)
 //   [0, xs)            staged activations of the current input chunk
 //   red                cross-wave partial sums when wk > 1   (nwv x nacc x 64 float4)
 //   ssq[nwv][32]       per-wave sums of squares for the RMSNorm
 //   rs[32]             per-row 1/rms
 //   wstat[nwv][32]     per-wave softmax partials (LM head)
+//   zblk               64 bytes of zeros
 // =====================================================================================
 // weight tiles a wave loads per batch (split over its RW feature tiles); two batches are in flight
 __host__ __device__ constexpr int gemm_batch(int rw, int nt) { return (nt == 1 ? 12 : 8) / rw; }
@@ -193,7 +195,7 @@ __host__ __device__ inline int xs_row_stride(int dt, int kc) { return dt ? (kc +
 __host__ __device__ inline int xs_bytes(int dt, int kc, int T) { return T * xs_row_stride(dt, kc) * (dt ? 2 : 1); }
 __host__ __device__ inline int gemm_red_bytes(int nwv, int nacc) { return nwv * nacc * 64 * 16; }
 __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
-    return gemm_red_bytes(nwv, nacc) + nwv * 32 * 4 + 32 * 4 + nwv * 32 * 16;
+    return gemm_red_bytes(nwv, nacc) + nwv * 32 * 4 + 32 * 4 + nwv * 32 * 16 + 64;
 }
 
 // `vblock` is the index of the feature-tile group this call handles (blockIdx.x in the one-kernel-per-stage
@@ -204,7 +206,9 @@ template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, NT),
           bool ONE = false, class A>
 __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* smem) {
     constexpr int KT = DT ? 32 : 16;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the wave index through readfirstlane: the compiler then knows that it - and every tile index, weight address and
+    // range test derived from it - is the same in all lanes, and keeps them in scalar registers
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nthr = blockDim.x, NWV = nthr >> 6;
     const int T = ONE ? 1 : a.T, K = a.W.k, KC = a.kc;
     const int WK = a.wk, WR = NWV / WK;
@@ -219,11 +223,15 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
     float* ssq = (float*)(tail + gemm_red_bytes(NWV, nacc));
     float* rs = ssq + NWV * 32;
     StatPart* wstat = (StatPart*)(rs + 32);
+    char* zblk = (char*)(wstat + NWV * 32);  // 64 bytes of zeros: the activation operand of a tile past the range
 
     // EPI / ROPE below zero: taken from the arguments at run time (the persistent pass kernel)
     const int epi = EPI < 0 ? a.epi : EPI;
     const bool rope = ROPE < 0 ? a.rope != 0 : ROPE != 0;
-    const bool norm = a.gain != nullptr;
+    // Every projection that adds to the residual stream reads un-normalised input and every other one reads through an
+    // RMSNorm, so with a compile-time epilogue the presence of the norm is a compile-time fact as well (the launcher
+    // rejects anything else); a run-time test here would make the gain loads conditional.
+    const bool norm = EPI < 0 ? a.gain != nullptr : EPI != EPI_RESID;
     const bool few = T < 4;  // few rows: all waves share each row and split it along k
     const bool owner = (wkid == 0);
     bool valid[RW];
@@ -231,7 +239,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
         valid[r] = tile0 + r < a.W.tn;
-        wbase[r] = (const char*)a.W.w + ((size_t)min(tile0 + r, a.W.tn - 1) * a.W.tk) * kTileBytes + lane * 16;
+        wbase[r] = (const char*)a.W.w + ((size_t)min(tile0 + r, a.W.tn - 1) * a.W.tk) * kTileBytes;  // scalar; the lane part is added per load
     }
     const int tok_l = lane & 15, kq = lane >> 4;
 #ifdef BILD_TRACE
@@ -242,37 +250,39 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
 #endif
     STAMP(0);
 
-    // ---- first batch of weight tiles and the residual values: issued before anything else ----
-    // Two register buffers of U tiles each: while one is consumed the next batch is in flight.
+    // ---- weight tiles: two register buffers of U tiles each, requested without any guard ----
+    // A tile past the wave's range is read from a clamped (valid) address and cancelled on the activation
+    // side (compute() reads a block of zeros for it), so no instruction touches a weight register between
+    // its load and its MFMA, and the requests of a batch stay in flight across everything in between.
+    // The memory counter retires loads in the order they were issued: whatever is needed first is requested
+    // first.  One-chunk launches (the latency-bound ones) therefore request the activations, then both weight
+    // buffers, and only then wait for the activations; the weights arrive while those are converted.
     uint4 B0[RW][U], B1[RW][U];
     const int S = U * WK;  // tiles between consecutive batches of this wave
-    // Branch-free: a tile outside the wave's range is read from a clamped (valid) address and zeroed,
-    // and a zero tile adds nothing in the MFMA, so neither the loads nor the math need guards.
-    auto load_batch = [&](uint4 (&B)[RW][U], int kt_abs, int kt_end) {
+    const unsigned lane16 = (unsigned)lane * 16u;  // scalar base + 32-bit lane offset: one address register for all loads
+    auto request = [&](uint4 (&B)[RW][U], int kt_abs, int kt_end) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int kt = kt_abs + u * WK;
-            const int ktc = min(kt, kt_end - 1);
+            const int ktc = min(kt_abs + u * WK, kt_end - 1);
 #pragma unroll
-            for (int r = 0; r < RW; ++r) {
-                uint4 v = *(const uint4*)(wbase[r] + (size_t)ktc * kTileBytes);
-                const bool ok = valid[r] && kt < kt_end;
-                v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
-                B[r][u] = v;
-            }
+            for (int r = 0; r < RW; ++r) B[r][u] = *(const uint4*)(wbase[r] + (size_t)ktc * kTileBytes + lane16);
         }
     };
-    load_batch(B0, wkid, min(KC, K) / KT);
+
+    // residual values: unconditional loads from clamped addresses (a conditional load would have to be waited
+    // for where the branches join, that is, here)
     float4 old[RW][2];
 #pragma unroll
     for (int r = 0; r < RW; ++r)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            old[r][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
-            const int t = nt * 16 + tok_l;
-            if (epi == EPI_RESID && owner && valid[r] && t < T)
-                old[r][nt] = ld_act4<COH>(a.out + (size_t)t * a.ldo + (tile0 + r) * 16 + kq * 4);
-        }
+        for (int nt = 0; nt < 2; ++nt) old[r][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (epi == EPI_RESID) {
+#pragma unroll
+        for (int r = 0; r < RW; ++r)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                old[r][nt] = ld_act4<COH>(a.out + (size_t)min(nt * 16 + tok_l, T - 1) * a.ldo + min(tile0 + r, a.W.tn - 1) * 16 + kq * 4);
+    }
 
     const int pos0 = (a.pos_ptr ? *a.pos_ptr : 0) + a.pos_add;
     int tgt[2] = {-1, -1};
@@ -286,52 +296,75 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
     }
 
     if (lane < 32) ssq[wave * 32 + lane] = 0.f;  // each wave owns (and later accumulates into) its own row
+    if (tid < 4) ((uint4*)zblk)[tid] = make_uint4(0u, 0u, 0u, 0u);
 
-    f32x4 acc[RW][2];
+    // two accumulators per output tile (bf16: one for the high parts, one for the low parts of the activations),
+    // so that consecutive MFMAs do not wait for each other; they are added once at the end
+    f32x4 acc[RW][2], acc2[RW][2];
 #pragma unroll
     for (int r = 0; r < RW; ++r)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < 2; ++j) acc[r][j] = acc2[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto compute = [&](const uint4 (&At)[RW], int ktl) {
+    const int zoff = (int)(zblk - xs_hi) + kq * 16;
+    auto compute = [&](const uint4 (&At)[RW], int ktl, bool ok) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            {
-                // rows past T read a valid row instead: an MFMA column only feeds its own output column,
-                // and those columns are never stored
-                const int t = min(nt * 16 + tok_l, T - 1);
-                if (DT) {
-                    const uint4 bh = *(const uint4*)(xs_hi + t * rstride + (ktl * 32 + kq * 8) * 2);
-                    const uint4 bl = *(const uint4*)(xs_lo + t * rstride + (ktl * 32 + kq * 8) * 2);
-                    const bf16x8 Bh = __builtin_bit_cast(bf16x8, bh), Bl = __builtin_bit_cast(bf16x8, bl);
+            // rows past T read a valid row instead: an MFMA column only feeds its own output column,
+            // and those columns are never stored
+            const int t = min(nt * 16 + tok_l, T - 1);
+            if (DT) {
+                const int off = ok ? t * rstride + (ktl * 32 + kq * 8) * 2 : zoff;
+                const int offl = ok ? off + T * rstride : zoff;
+                const uint4 bh = *(const uint4*)(xs_hi + off);
+                const uint4 bl = *(const uint4*)(xs_hi + offl);
+                const bf16x8 Bh = __builtin_bit_cast(bf16x8, bh), Bl = __builtin_bit_cast(bf16x8, bl);
 #pragma unroll
-                    for (int r = 0; r < RW; ++r) {
-                        const bf16x8 Aw = __builtin_bit_cast(bf16x8, At[r]);
-                        acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bh, acc[r][nt], 0, 0, 0);
-                        acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bl, acc[r][nt], 0, 0, 0);
-                    }
-                } else {
-                    const float4 b = *(const float4*)(xs_hi + t * rstride + (ktl * 16 + kq * 4) * 4);
-                    const float bb[4] = {b.x, b.y, b.z, b.w};
+                for (int r = 0; r < RW; ++r) {
+                    const bf16x8 Aw = __builtin_bit_cast(bf16x8, At[r]);
+                    acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bh, acc[r][nt], 0, 0, 0);
+                    acc2[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bl, acc2[r][nt], 0, 0, 0);
+                }
+            } else {
+                const int off = ok ? t * rstride + (ktl * 16 + kq * 4) * 4 : zoff;
+                const float4 b = *(const float4*)(xs_hi + off);
+                const float bb[4] = {b.x, b.y, b.z, b.w};
 #pragma unroll
-                    for (int r = 0; r < RW; ++r) {
-                        const float aa[4] = {__uint_as_float(At[r].x), __uint_as_float(At[r].y),
-                                             __uint_as_float(At[r].z), __uint_as_float(At[r].w)};
+                for (int r = 0; r < RW; ++r) {
+                    const float aa[4] = {__uint_as_float(At[r].x), __uint_as_float(At[r].y),
+                                         __uint_as_float(At[r].z), __uint_as_float(At[r].w)};
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j], bb[j], acc[r][nt], 0, 0, 0);
+                    for (int j = 0; j < 4; j += 2) {
+                        acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j], bb[j], acc[r][nt], 0, 0, 0);
+                        acc2[r][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j + 1], bb[j + 1], acc2[r][nt], 0, 0, 0);
                     }
                 }
             }
         }
     };
+    // one batch against the chunk staged in LDS; kt is the wave's first tile of the batch within the chunk
+    auto compute_batch = [&](uint4 (&B)[RW][U], int kt, int nkt) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            uint4 At[RW];
+#pragma unroll
+            for (int r = 0; r < RW; ++r) At[r] = B[r][u];
+            compute(At, kt + u * WK, kt + u * WK < nkt);
+        }
+    };
 
-    for (int k0 = 0; k0 < K; k0 += KC) {
-        const int kc_len = min(KC, K - k0);
-        if (k0) __syncthreads();  // readers of the previous chunk are done
-        // ---- stage x[:, k0 : k0+kc_len] (times the norm gain) into LDS ----
+    // ---- stage x[:, k0 : k0+kc_len] (times the norm gain) into LDS ----
+    // Every load is unconditional (clamped index) and every round first requests all its loads, then calls
+    // `hook` (first round only), then converts: the hook is where a one-chunk launch requests its weights.
+    const float* gsrc = norm ? a.gain : a.x;  // run-time norm flag only: the "gain" values are then read but not used
+    auto noop = [] {};
+    auto stage = [&](const int k0, const int kc_len, auto&& hook) {
         const int n4 = kc_len >> 2;
         auto ldx = [&](int t, int k4) -> float4 { return ld_act4<COH>(a.x + (size_t)t * a.ldx + k0 + k4 * 4); };
+        auto ldg = [&](int k4) -> float4 {
+            if (EPI >= 0 && !norm) return make_float4(0.f, 0.f, 0.f, 0.f);
+            return *(const float4*)(gsrc + k0 + k4 * 4);
+        };
         // writes one float4 of row t and returns its sum of squares (for the RMSNorm)
         auto put = [&](int t, int k4, float4 w, const float4& gg) -> float {
             float ss = 0.f;
@@ -355,178 +388,192 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             // piece is sum_s w_s O_s / sum_s w_s L_s with w_s = exp(m_s - max m) of its (row, head)
             const int total = T * n4;
             const unsigned magic = 0xFFFFFFFFu / (unsigned)n4 + 1u;
-            const int S = a.mg_splits;  // at most 8
-            for (int e = tid; e < total; e += nthr) {
+            const int SP = a.mg_splits;  // at most 8
+            auto piece = [&](int eraw, auto&& hk) {
+                const int e = min(eraw, total - 1);
                 const int t = (int)__umulhi((unsigned)e, magic), k4 = e - t * n4;
                 const int kk = k0 + k4 * 4;
                 const float* ml = a.mg_ml + ((size_t)t * a.mg_heads + kk / a.d_head) * 2;
                 const size_t ml_stride = (size_t)T * a.mg_heads * 2, o_stride = (size_t)T * a.ldx;
                 const float* op = a.mg_o + (size_t)t * a.ldx + kk;
-                float m[8];
+                float m[8], l[8];
+                float4 o[8];
+#pragma unroll
+                for (int sp = 0; sp < 8; ++sp) {
+                    const int sc = min(sp, SP - 1);
+                    m[sp] = ld_act<COH>(ml + sc * ml_stride);
+                    l[sp] = ld_act<COH>(ml + sc * ml_stride + 1);
+                    o[sp] = ld_act4<COH>(op + sc * o_stride);
+                }
+                hk();
                 float M = -INFINITY;
 #pragma unroll
                 for (int sp = 0; sp < 8; ++sp) {
-                    m[sp] = sp < S ? ld_act<COH>(ml + min(sp, S - 1) * ml_stride) : -INFINITY;
+                    m[sp] = sp < SP ? m[sp] : -INFINITY;
                     M = fmaxf(M, m[sp]);
                 }
                 float L = 0.f;
                 float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-                for (int g4 = 0; g4 < 2; ++g4) {
-                    if (g4 * 4 < S) {
-                        float l[4];
-                        float4 o[4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const int sc = min(g4 * 4 + u, S - 1);
-                            l[u] = ld_act<COH>(ml + sc * ml_stride + 1);
-                            o[u] = ld_act4<COH>(op + sc * o_stride);
-                        }
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const float mm = m[g4 * 4 + u];
-                            const float w = (mm == -INFINITY) ? 0.f : expf(mm - M);
-                            L += l[u] * w;
-                            r.x += o[u].x * w; r.y += o[u].y * w; r.z += o[u].z * w; r.w += o[u].w * w;
-                        }
-                    }
+                for (int sp = 0; sp < 8; ++sp) {
+                    const float w = (m[sp] == -INFINITY) ? 0.f : expf(m[sp] - M);
+                    L += l[sp] * w;
+                    r.x += o[sp].x * w; r.y += o[sp].y * w; r.z += o[sp].z * w; r.w += o[sp].w * w;
                 }
                 const float inv = 1.f / L;
+                // a thread without a piece of its own rewrites the last piece with the same value: the loads above
+                // must not become conditional, or the compiler moves them behind the hook
                 put(t, k4, make_float4(r.x * inv, r.y * inv, r.z * inv, r.w * inv), r);
-            }
+            };
+            piece(tid, hook);
+            for (int e = tid + nthr; e < total; e += nthr) piece(e, noop);
         } else if (T > 1 && (n4 & 63) == 0) {
             // Several rows whose chunk is a whole number of wavefront-wide pieces: the rows are laid end to
             // end and dealt to all threads, which spreads the conversion work evenly and lets one round of
-            // loads (8 per thread, issued together) cover 8 * nthr pieces; 64 consecutive pieces share a row.
+            // loads (up to 8 per thread, issued together) cover 8 * nthr pieces; 64 consecutive pieces share a row.
             const int total = T * n4;
             const unsigned magic = 0xFFFFFFFFu / (unsigned)n4 + 1u;  // e / n4 == umulhi(e, magic) for e < 2^32 / n4
-            // two to four rows: at most two pieces per thread and exactly the loads needed; more rows: rounds of
-            // eight loads (a four-piece variant beside it made the common two-to-four-row passes slower)
-            auto few_pieces = [&](auto pieces) {
-                constexpr int P = decltype(pieces)::value;
+            auto pieces = [&](auto np, int eb, auto&& hk) {
+                constexpr int P = decltype(np)::value;
                 float4 v[P], g[P];
                 int tt[P], kk[P];
 #pragma unroll
                 for (int u = 0; u < P; ++u) {
-                    const int e = tid + u * nthr;
-                    v[u] = g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    tt[u] = (int)__umulhi((unsigned)min(e, total - 1), magic);
-                    kk[u] = min(e, total - 1) - tt[u] * n4;
-                    if (e < total) {
-                        v[u] = ldx(tt[u], kk[u]);
-                        if (norm) g[u] = *(const float4*)(a.gain + k0 + kk[u] * 4);
-                    }
+                    const int e = min(eb + u * nthr, total - 1);
+                    tt[u] = (int)__umulhi((unsigned)e, magic);
+                    kk[u] = e - tt[u] * n4;
+                    v[u] = ldx(tt[u], kk[u]);
+                    g[u] = ldg(kk[u]);
                 }
+                hk();
+                // Every piece is converted and written, also the clamped duplicates past the end (same value to the
+                // same place, counted as zero in the sum of squares): a conditional use would let the compiler move
+                // the loads behind the hook.
 #pragma unroll
                 for (int u = 0; u < P; ++u) {
-                    if (tid + u * nthr < total) {  // wave-uniform, like the row index
-                        const float ss = put(tt[u], kk[u], v[u], g[u]);
-                        if (norm) {
-                            const float tot = wave_sum(ss);
-                            if (lane == 0) ssq[wave * 32 + tt[u]] += tot;
-                        }
+                    const float ss = put(tt[u], kk[u], v[u], g[u]);
+                    if (norm) {
+                        const float tot = wave_sum(eb + u * nthr < total ? ss : 0.f);
+                        if (lane == 0) ssq[wave * 32 + tt[u]] += tot;
                     }
                 }
             };
+            // two to four rows: at most two pieces per thread; more rows: rounds of eight loads (a four-piece
+            // variant beside them made the common two-to-four-row passes slower)
             if (total <= 2 * nthr) {
-                few_pieces(std::integral_constant<int, 2>{});
-            } else
-            for (int eb = tid; eb < total; eb += nthr * 8) {
-                float4 v[8], g[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int e = min(eb + u * nthr, total - 1);
-                    const int t = (int)__umulhi((unsigned)e, magic), k4 = e - t * n4;
-                    v[u] = ldx(t, k4);
-                    g[u] = norm ? *(const float4*)(a.gain + k0 + k4 * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int e = eb + u * nthr;
-                    if (e < total) {  // wave-uniform: total and the wave's first piece are multiples of 64
-                        const int t = (int)__umulhi((unsigned)e, magic), k4 = e - t * n4;
-                        const float ss = put(t, k4, v[u], g[u]);
-                        if (norm) {
-                            const float tot = wave_sum(ss);
-                            if (lane == 0) ssq[wave * 32 + t] += tot;
-                        }
-                    }
-                }
+                pieces(std::integral_constant<int, 2>{}, tid, hook);
+            } else {
+                pieces(std::integral_constant<int, 8>{}, tid, hook);
+                for (int eb = tid + nthr * 8; eb < total; eb += nthr * 8) pieces(std::integral_constant<int, 8>{}, eb, noop);
             }
         } else {
             // one row, or ragged chunks: few rows - every wave takes a k-slice of every row; otherwise whole
             // rows are dealt to the waves
-            for (int j = 0; j < 8; ++j) {
-                const int t = few ? j : wave + NWV * j;
-                if (t >= T) break;  // wave-uniform
+            auto row = [&](int j, auto&& hk) {
+                const int traw = few ? j : wave + NWV * j;
+                const bool act = traw < T;  // wave-uniform
+                const int t = min(traw, T - 1);
                 const int start = few ? tid : lane, step = few ? nthr : 64;
                 float ssj = 0.f;
                 if (n4 <= 2 * step) {  // short rows: at most two elements per thread
                     const int ka = start, kb2 = start + step;
-                    float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va, ga = va, gb = va;
-                    if (ka < n4) { va = ldx(t, ka); if (norm) ga = *(const float4*)(a.gain + k0 + ka * 4); }
-                    if (kb2 < n4) { vb = ldx(t, kb2); if (norm) gb = *(const float4*)(a.gain + k0 + kb2 * 4); }
-                    if (ka < n4) ssj += put(t, ka, va, ga);
-                    if (kb2 < n4) ssj += put(t, kb2, vb, gb);
+                    const int ca = min(ka, n4 - 1), cb = min(kb2, n4 - 1);
+                    const float4 va = ldx(t, ca), ga = ldg(ca), vb = ldx(t, cb), gb = ldg(cb);
+                    hk();
+                    // unconditional conversions and writes (duplicates carry the same value and count as zero)
+                    const float sa = put(t, ca, va, ga), sb = put(t, cb, vb, gb);
+                    ssj += (act && ka < n4 ? sa : 0.f) + (act && kb2 < n4 ? sb : 0.f);
                 } else {
-                    for (int kb = start; kb < n4; kb += step * 8) {
+                    auto rnd = [&](int kb, auto&& hk2) {
                         float4 v[8], g[8];
 #pragma unroll
                         for (int u = 0; u < 8; ++u) {  // all loads of the round first
                             const int k4 = min(kb + u * step, n4 - 1);
                             v[u] = ldx(t, k4);
-                            g[u] = norm ? *(const float4*)(a.gain + k0 + k4 * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+                            g[u] = ldg(k4);
                         }
+                        hk2();
 #pragma unroll
-                        for (int u = 0; u < 8; ++u)
-                            if (kb + u * step < n4) ssj += put(t, kb + u * step, v[u], g[u]);
-                    }
+                        for (int u = 0; u < 8; ++u) {
+                            const float su = put(t, min(kb + u * step, n4 - 1), v[u], g[u]);
+                            ssj += (act && kb + u * step < n4) ? su : 0.f;
+                        }
+                    };
+                    rnd(start, hk);
+                    for (int kb = start + step * 8; kb < n4; kb += step * 8) rnd(kb, noop);
                 }
-                if (norm) {  // this wave's share of sum x^2 of row t, accumulated over the chunks
+                if (norm && act) {  // this wave's share of sum x^2 of row t, accumulated over the chunks
                     const float tot = wave_sum(ssj);
                     if (lane == 0) ssq[wave * 32 + t] += tot;
                 }
+            };
+            row(0, hook);
+            for (int j = 1; j < 8; ++j) {
+                if ((few ? j : wave + NWV * j) >= T) break;  // wave-uniform
+                row(j, noop);
             }
         }
+    };
+
+    const int nkt0 = min(KC, K) / KT;
+    if (K <= KC) {
+        // ---- one chunk: activations, then both weight buffers, then everything else ----
+        stage(0, K, [&] {
+            request(B0, wkid, nkt0);
+            request(B1, wkid + S, nkt0);
+        });
         STAMP(1);
         __syncthreads();
         STAMP(2);
-        // ---- this wave's weight tiles of the chunk: compute one batch while the next one loads ----
-        const int kt_base = k0 / KT, nkt = kc_len / KT;
-        const int kn_base = (k0 + KC) / KT, nkt_next = (k0 + KC < K) ? min(KC, K - k0 - KC) / KT : 0;
-        auto compute_batch = [&](uint4 (&B)[RW][U], int kt) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint4 At[RW];
-#pragma unroll
-                for (int r = 0; r < RW; ++r) At[r] = B[r][u];
-                compute(At, min(kt + u * WK, nkt - 1));  // a tile past the end is all zero
-            }
-        };
-        // the batch for kt = wkid is already in flight in B0 (kernel entry, or the end of the previous chunk)
         for (int kt = wkid;; kt += 2 * S) {
-            {
-                const bool in_chunk = kt + S < nkt;
-                if (in_chunk || nkt_next)
-                    load_batch(B1, in_chunk ? kt_base + kt + S : kn_base + wkid, in_chunk ? kt_base + nkt : kn_base + nkt_next);
-                compute_batch(B0, kt);
-                if (!in_chunk) {  // the next chunk's first batch (if any) went to B1: hand it over
+            compute_batch(B0, kt, nkt0);
+            if (kt + S >= nkt0) break;
+            if (kt + 2 * S < nkt0) request(B0, kt + 2 * S, nkt0);
+            compute_batch(B1, kt + S, nkt0);
+            if (kt + 2 * S >= nkt0) break;
+            if (kt + 3 * S < nkt0) request(B1, kt + 3 * S, nkt0);
+        }
+    } else {
+        request(B0, wkid, nkt0);
+        for (int k0 = 0; k0 < K; k0 += KC) {
+            const int kc_len = min(KC, K - k0);
+            if (k0) __syncthreads();  // readers of the previous chunk are done
+            stage(k0, kc_len, noop);
+            STAMP(1);
+            __syncthreads();
+            STAMP(2);
+            // ---- this wave's weight tiles of the chunk: compute one batch while the next one loads ----
+            const int kt_base = k0 / KT, nkt = kc_len / KT;
+            const int kn_base = (k0 + KC) / KT, nkt_next = (k0 + KC < K) ? min(KC, K - k0 - KC) / KT : 0;
+            // the batch for kt = wkid is already in flight in B0 (kernel entry, or the end of the previous chunk)
+            for (int kt = wkid;; kt += 2 * S) {
+                {
+                    const bool in_chunk = kt + S < nkt;
+                    if (in_chunk || nkt_next)
+                        request(B1, in_chunk ? kt_base + kt + S : kn_base + wkid, in_chunk ? kt_base + nkt : kn_base + nkt_next);
+                    compute_batch(B0, kt, nkt);
+                    if (!in_chunk) {  // the next chunk's first batch (if any) went to B1: hand it over
 #pragma unroll
-                    for (int r = 0; r < RW; ++r)
+                        for (int r = 0; r < RW; ++r)
 #pragma unroll
-                        for (int u = 0; u < U; ++u) B0[r][u] = B1[r][u];
-                    break;
+                            for (int u = 0; u < U; ++u) B0[r][u] = B1[r][u];
+                        break;
+                    }
                 }
-            }
-            {
-                const bool in_chunk = kt + 2 * S < nkt;
-                if (in_chunk || nkt_next)
-                    load_batch(B0, in_chunk ? kt_base + kt + 2 * S : kn_base + wkid, in_chunk ? kt_base + nkt : kn_base + nkt_next);
-                compute_batch(B1, kt + S);
-                if (!in_chunk) break;  // the next chunk's first batch is already in B0
+                {
+                    const bool in_chunk = kt + 2 * S < nkt;
+                    if (in_chunk || nkt_next)
+                        request(B0, in_chunk ? kt_base + kt + 2 * S : kn_base + wkid, in_chunk ? kt_base + nkt : kn_base + nkt_next);
+                    compute_batch(B1, kt + S, nkt);
+                    if (!in_chunk) break;  // the next chunk's first batch is already in B0
+                }
             }
         }
     }
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[r][j] += acc2[r][j];
 
     STAMP(3);
     // ---- RMSNorm row scales and cross-wave k reduction ----
@@ -858,6 +905,7 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     const size_t smem = gemm_lds_bytes(a, dtype);
     const unsigned row_blocks = (unsigned)((a.T + kMaxRows - 1) / kMaxRows);
     if (row_blocks > 1 && a.epi == EPI_LMHEAD) return hipErrorInvalidValue;  // softmax partials are per pass
+    if ((a.gain != nullptr) != (a.epi != EPI_RESID)) return hipErrorInvalidValue;  // the kernels fix the norm by the epilogue
     if (a.mg_splits > 1) {
         if (a.mg_splits > 8 || a.gain || row_blocks > 1 || a.epi != EPI_RESID || a.rw != 1) return hipErrorInvalidValue;
         const dim3 grid1((unsigned)gemm_num_blocks(a)), block1(64 * a.nwv);
@@ -929,7 +977,7 @@ template <int DT, int DH32, bool COH = false, class A>
 __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* smem) {
     constexpr int DHP = DH32 * 32;   // head dim padded to the k-step of the first product
     constexpr int DT16 = DH32 * 2;   // 16-wide output tiles along the head dim
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
     const int nthr = blockDim.x, nw = nthr >> 6;
     const int T = a.T, dh = a.d_head, I = a.i_dim;
     const int h = vblock % a.heads, sp = vblock / a.heads;
@@ -956,15 +1004,19 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
     const int bps = (nblk + a.splits - 1) / a.splits;
     const int blk_begin = min(nblk, sp * bps), blk_end = min(nblk, blk_begin + bps);
 
-    // ---- stage q * scale (zero padded to NT*16 rows x DHP dims); issued after the first K/V loads ----
-    auto stage_q = [&]() {
-        for (int i = tid; i < NT * 16 * (DHP / 4); i += nthr) {
+    // ---- stage q * scale (zero padded to NT*16 rows x DHP dims) ----
+    // The memory counter retires loads in issue order, so q (needed first, and warm) is requested before the first
+    // K/V block: `hook` runs between the requests of the first round and their conversion.  The loads are
+    // unconditional (clamped address, value selected afterwards), else they would be waited for where the branches join.
+    auto stage_q = [&](auto&& hook) {
+        const int npieces = NT * 16 * (DHP / 4);
+        auto piece = [&](int i, auto&& hk) {
             const int t = i / (DHP / 4), d4 = (i % (DHP / 4)) * 4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (t < T && d4 < dh) {
-                v = ld_act4<COH>(a.q + (size_t)t * I + h * dh + d4);
-                v.x *= a.scale; v.y *= a.scale; v.z *= a.scale; v.w *= a.scale;
-            }
+            const bool real = t < T && d4 < dh;
+            float4 v = ld_act4<COH>(a.q + (size_t)min(t, T - 1) * I + h * dh + min(d4, dh - 4));
+            hk();
+            v.x = real ? v.x * a.scale : 0.f; v.y = real ? v.y * a.scale : 0.f;
+            v.z = real ? v.z * a.scale : 0.f; v.w = real ? v.w * a.scale : 0.f;
             if (DT) {
                 uint32_t h01, l01, h23, l23;
                 split_bf16x2(v.x, v.y, h01, l01);
@@ -974,7 +1026,10 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
             } else {
                 *(float4*)(q_hi + t * qstride + d4 * 4) = v;
             }
-        }
+        };
+        // a thread past the end redoes the last piece (same value to the same place), so that its load stays unconditional
+        piece(min(tid, npieces - 1), hook);
+        for (int i = tid + nthr; i < npieces; i += nthr) piece(i, [] {});
     };
 
     float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
@@ -995,31 +1050,29 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
             if (DT) {
 #pragma unroll
                 for (int ks = 0; ks < DH32; ++ks) {
-                    const int d0 = ks * 32 + g * 8;
-                    Kr[ab][ks] = d0 < dh ? *(const uint4*)(krow + d0 * 2) : make_uint4(0, 0, 0, 0);
+                    // dims past the head read a clamped (valid) address: q is zero there and the cache is finite
+                    const int d0 = min(ks * 32 + g * 8, dh - 8);
+                    Kr[ab][ks] = *(const uint4*)(krow + d0 * 2);
                 }
             } else {
 #pragma unroll
                 for (int ks = 0; ks < DH32 * 2; ++ks) {
-                    const int d0 = ks * 16 + g * 4;
-                    Kr[ab][ks] = d0 < dh ? *(const uint4*)(krow + d0 * 4) : make_uint4(0, 0, 0, 0);
+                    const int d0 = min(ks * 16 + g * 4, dh - 4);
+                    Kr[ab][ks] = *(const uint4*)(krow + d0 * 4);
                 }
             }
         }
 #pragma unroll
         for (int dt = 0; dt < DT16; ++dt) {
-            const int d = dt * 16 + tok_l;
+            // output dims past the head are never stored: their V^T rows read a clamped (valid) row
+            const int d = min(dt * 16 + tok_l, dh - 1);
             const char* vrow = (const char*)a.v + ((size_t)(h * dh + d) * a.vcap + key0 + g * 4) * esz;
             if (DT) {
-                uint2 va = make_uint2(0, 0), vb = make_uint2(0, 0);
-                if (d < dh) {
-                    va = *(const uint2*)vrow;
-                    vb = *(const uint2*)(vrow + 16 * 2);
-                }
+                const uint2 va = *(const uint2*)vrow, vb = *(const uint2*)(vrow + 16 * 2);
                 Vr[dt][0] = make_uint4(va.x, va.y, vb.x, vb.y);
             } else {
-                Vr[dt][0] = d < dh ? *(const uint4*)vrow : make_uint4(0, 0, 0, 0);
-                Vr[dt][1] = d < dh ? *(const uint4*)(vrow + 16 * 4) : make_uint4(0, 0, 0, 0);
+                Vr[dt][0] = *(const uint4*)vrow;
+                Vr[dt][1] = *(const uint4*)(vrow + 16 * 4);
             }
         }
     };
@@ -1120,9 +1173,10 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
     {
         uint4 K0[2][KN], V0[DT16][VN];
         int blk = blk_begin + wave;
-        if (blk < blk_end) load_kv(K0, V0, blk);
+        // a wave without a block requests block 0 of the cache all the same (valid memory, never processed): the
+        // request sits between q's loads and their use and must not be conditional
+        stage_q([&] { load_kv(K0, V0, blk < blk_end ? blk : 0); });
         ASTAMP(1);
-        stage_q();
         __syncthreads();
         ASTAMP(2);
         if constexpr (DH32 <= 2) {
@@ -1655,6 +1709,27 @@ __global__ __launch_bounds__(256) void probe_empty_kernel() {}
 
 hipError_t launch_probe_empty(hipStream_t st) {
     hipLaunchKernelGGL(probe_empty_kernel, dim3(256), dim3(256), 0, st);
+    return hipGetLastError();
+}
+
+// Every workgroup (8 waves) streams a private contiguous region, 16 tiles of 1 KiB per wave in flight: how fast
+// ONE compute unit can pull from HBM, and how the total grows with the number of workgroups.
+__global__ __launch_bounds__(512) void probe_stream_kernel(const uint4* __restrict__ p, size_t tiles_per_wg, uint4* sink) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint4* base = p + (size_t)blockIdx.x * tiles_per_wg * 64 + lane;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (size_t t = wave; t < tiles_per_wg; t += 8 * 16) {
+        uint4 v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = base[min(t + (size_t)u * 8, tiles_per_wg - 1) * 64];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+    }
+    if (acc.x == 0x12345678u && acc.y == 0x9abcdefu) sink[0] = acc;  // keeps the loads alive; never true for zeroed memory
+}
+
+hipError_t launch_probe_stream(const void* src, size_t kib_per_group, int groups, void* sink, hipStream_t st) {
+    hipLaunchKernelGGL(probe_stream_kernel, dim3(groups), dim3(512), 0, st, (const uint4*)src, kib_per_group, (uint4*)sink);
     return hipGetLastError();
 }
 
