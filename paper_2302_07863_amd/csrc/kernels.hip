@@ -189,7 +189,8 @@ __device__ __forceinline__ void st_u16(uint16_t* p, uint16_t v) {
 //   zblk               64 bytes of zeros
 // =====================================================================================
 // weight tiles a wave loads per batch (split over its RW feature tiles); two batches are in flight
-__host__ __device__ constexpr int gemm_batch(int rw, int nt) { return (nt == 1 ? 12 : 8) / rw; }
+// (12 in the single-row kernel; 8 with several rows, whose staging needs the registers)
+__host__ __device__ constexpr int gemm_batch(int rw, bool one_row) { return (one_row ? 12 : 8) / rw; }
 
 __host__ __device__ inline int xs_row_stride(int dt, int kc) { return dt ? (kc + 8) * 2 : (kc + 4) * 4; }
 __host__ __device__ inline int xs_bytes(int dt, int kc, int T) { return T * xs_row_stride(dt, kc) * (dt ? 2 : 1); }
@@ -202,7 +203,7 @@ __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
 // launches, a loop index in the persistent pass kernel); `smem` is the workgroup's dynamic LDS.
 // The argument block may live in the kernel-argument segment or (persistent kernel) in constant-address-space
 // device memory, hence the template parameter A.
-template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, NT), bool COH = false, bool MG = false,
+template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, false), bool COH = false, bool MG = false,
           bool ONE = false, class A>
 __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* smem) {
     constexpr int KT = DT ? 32 : 16;
@@ -298,8 +299,9 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
     if (lane < 32) ssq[wave * 32 + lane] = 0.f;  // each wave owns (and later accumulates into) its own row
     if (tid < 4) ((uint4*)zblk)[tid] = make_uint4(0u, 0u, 0u, 0u);
 
-    // two accumulators per output tile (bf16: one for the high parts, one for the low parts of the activations),
-    // so that consecutive MFMAs do not wait for each other; they are added once at the end
+    // up to 16 rows: two accumulators per output tile (bf16: one for the high parts, one for the low parts of the
+    // activations), so that consecutive MFMAs do not wait for each other; they are added once at the end.  More rows
+    // have two independent tiles anyway.
     f32x4 acc[RW][2], acc2[RW][2];
 #pragma unroll
     for (int r = 0; r < RW; ++r)
@@ -323,7 +325,8 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                 for (int r = 0; r < RW; ++r) {
                     const bf16x8 Aw = __builtin_bit_cast(bf16x8, At[r]);
                     acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bh, acc[r][nt], 0, 0, 0);
-                    acc2[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bl, acc2[r][nt], 0, 0, 0);
+                    if (NT == 1) acc2[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bl, acc2[r][nt], 0, 0, 0);
+                    else acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bl, acc[r][nt], 0, 0, 0);
                 }
             } else {
                 const int off = ok ? t * rstride + (ktl * 16 + kq * 4) * 4 : zoff;
@@ -336,7 +339,8 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
 #pragma unroll
                     for (int j = 0; j < 4; j += 2) {
                         acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j], bb[j], acc[r][nt], 0, 0, 0);
-                        acc2[r][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j + 1], bb[j + 1], acc2[r][nt], 0, 0, 0);
+                        if (NT == 1) acc2[r][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j + 1], bb[j + 1], acc2[r][nt], 0, 0, 0);
+                        else acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[j + 1], bb[j + 1], acc[r][nt], 0, 0, 0);
                     }
                 }
             }
@@ -357,7 +361,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
     // Every load is unconditional (clamped index) and every round first requests all its loads, then calls
     // `hook` (first round only), then converts: the hook is where a one-chunk launch requests its weights.
     const float* gsrc = norm ? a.gain : a.x;  // run-time norm flag only: the "gain" values are then read but not used
-    auto noop = [] {};
+    auto noop = [](bool) {};
     auto stage = [&](const int k0, const int kc_len, auto&& hook) {
         const int n4 = kc_len >> 2;
         auto ldx = [&](int t, int k4) -> float4 { return ld_act4<COH>(a.x + (size_t)t * a.ldx + k0 + k4 * 4); };
@@ -405,7 +409,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                     l[sp] = ld_act<COH>(ml + sc * ml_stride + 1);
                     o[sp] = ld_act4<COH>(op + sc * o_stride);
                 }
-                hk();
+                hk(true);
                 float M = -INFINITY;
 #pragma unroll
                 for (int sp = 0; sp < 8; ++sp) {
@@ -433,8 +437,12 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             // loads (up to 8 per thread, issued together) cover 8 * nthr pieces; 64 consecutive pieces share a row.
             const int total = T * n4;
             const unsigned magic = 0xFFFFFFFFu / (unsigned)n4 + 1u;  // e / n4 == umulhi(e, magic) for e < 2^32 / n4
-            auto pieces = [&](auto np, int eb, auto&& hk) {
+            // EAGER: every piece is converted and written, also the clamped duplicates past the end (same value to
+            // the same place, counted as zero in the sum of squares), so that no load becomes conditional and the
+            // compiler cannot move it behind the hook.  Otherwise pieces past the end are skipped.
+            auto pieces = [&](auto np, auto eager, int eb, auto&& hk) {
                 constexpr int P = decltype(np)::value;
+                constexpr bool EAGER = decltype(eager)::value;
                 float4 v[P], g[P];
                 int tt[P], kk[P];
 #pragma unroll
@@ -445,26 +453,31 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                     v[u] = ldx(tt[u], kk[u]);
                     g[u] = ldg(kk[u]);
                 }
-                hk();
-                // Every piece is converted and written, also the clamped duplicates past the end (same value to the
-                // same place, counted as zero in the sum of squares): a conditional use would let the compiler move
-                // the loads behind the hook.
+                hk(true);
 #pragma unroll
                 for (int u = 0; u < P; ++u) {
-                    const float ss = put(tt[u], kk[u], v[u], g[u]);
-                    if (norm) {
-                        const float tot = wave_sum(eb + u * nthr < total ? ss : 0.f);
-                        if (lane == 0) ssq[wave * 32 + tt[u]] += tot;
+                    const bool in = eb + u * nthr < total;  // wave-uniform: total and the wave's first piece are multiples of 64
+                    if (EAGER || in) {
+                        const float ss = put(tt[u], kk[u], v[u], g[u]);
+                        if (norm) {
+                            const float tot = wave_sum(in ? ss : 0.f);
+                            if (lane == 0) ssq[wave * 32 + tt[u]] += tot;
+                        }
                     }
                 }
             };
-            // two to four rows: at most two pieces per thread; more rows: rounds of eight loads (a four-piece
-            // variant beside them made the common two-to-four-row passes slower)
+            // Up to four pieces per thread (two to eight rows of the common widths): activations first, weights
+            // behind them.  More rows: the conversions are the longer part and a round of eight loads with the
+            // weights behind it does not fit the register file, so the weights are requested first and the
+            // rounds skip what they do not need.
             if (total <= 2 * nthr) {
-                pieces(std::integral_constant<int, 2>{}, tid, hook);
+                pieces(std::integral_constant<int, 2>{}, std::true_type{}, tid, hook);
+            } else if (total <= 4 * nthr) {
+                pieces(std::integral_constant<int, 4>{}, std::true_type{}, tid, hook);
             } else {
-                pieces(std::integral_constant<int, 8>{}, tid, hook);
-                for (int eb = tid + nthr * 8; eb < total; eb += nthr * 8) pieces(std::integral_constant<int, 8>{}, eb, noop);
+                hook(false);
+                for (int eb = tid; eb < total; eb += nthr * 8)
+                    pieces(std::integral_constant<int, 8>{}, std::false_type{}, eb, noop);
             }
         } else {
             // one row, or ragged chunks: few rows - every wave takes a k-slice of every row; otherwise whole
@@ -479,7 +492,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                     const int ka = start, kb2 = start + step;
                     const int ca = min(ka, n4 - 1), cb = min(kb2, n4 - 1);
                     const float4 va = ldx(t, ca), ga = ldg(ca), vb = ldx(t, cb), gb = ldg(cb);
-                    hk();
+                    hk(true);
                     // unconditional conversions and writes (duplicates carry the same value and count as zero)
                     const float sa = put(t, ca, va, ga), sb = put(t, cb, vb, gb);
                     ssj += (act && ka < n4 ? sa : 0.f) + (act && kb2 < n4 ? sb : 0.f);
@@ -492,7 +505,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                             v[u] = ldx(t, k4);
                             g[u] = ldg(k4);
                         }
-                        hk2();
+                        hk2(true);
 #pragma unroll
                         for (int u = 0; u < 8; ++u) {
                             const float su = put(t, min(kb + u * step, n4 - 1), v[u], g[u]);
@@ -507,7 +520,12 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                     if (lane == 0) ssq[wave * 32 + t] += tot;
                 }
             };
-            row(0, hook);
+            if (ONE) {
+                row(0, hook);  // one row: this is the whole staging
+            } else {           // ragged widths with several rows (rare): weights first, like the long multi-row case
+                hook(false);
+                row(0, noop);
+            }
             for (int j = 1; j < 8; ++j) {
                 if ((few ? j : wave + NWV * j) >= T) break;  // wave-uniform
                 row(j, noop);
@@ -518,10 +536,15 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
     const int nkt0 = min(KC, K) / KT;
     if (K <= KC) {
         // ---- one chunk: activations, then both weight buffers, then everything else ----
-        stage(0, K, [&] {
+        // hook(true): both buffers go out behind the activation loads; hook(false) (long staging, which needs the
+        // registers): the first buffer goes out ahead of the staging and the second one after it
+        bool second_out = false;
+        stage(0, K, [&](bool both) {
             request(B0, wkid, nkt0);
-            request(B1, wkid + S, nkt0);
+            if (both) request(B1, wkid + S, nkt0);
+            second_out = both;
         });
+        if (!second_out) request(B1, wkid + S, nkt0);
         STAMP(1);
         __syncthreads();
         STAMP(2);
@@ -736,14 +759,14 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
 template <int DT, int RW, int EPI, int ROPE>
 __global__ __launch_bounds__(512) void gemm_row_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    gemm_body<DT, RW, EPI, ROPE, 1, gemm_batch(RW, 1), false, false, true>(a, (int)blockIdx.x, smem);
+    gemm_body<DT, RW, EPI, ROPE, 1, gemm_batch(RW, true), false, false, true>(a, (int)blockIdx.x, smem);
 }
 
 // Output projection whose input is still in key-split attention partials (merged while staging).
 template <int DT, int NT>
 __global__ __launch_bounds__(512) void gemm_merge_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    gemm_body<DT, 1, EPI_RESID, 0, NT, gemm_batch(1, NT), false, true>(a, (int)blockIdx.x, smem);
+    gemm_body<DT, 1, EPI_RESID, 0, NT, gemm_batch(1, false), false, true>(a, (int)blockIdx.x, smem);
 }
 
 // More than kMaxRows rows (encoder, prompt prefill): blockIdx.y picks a block of kMaxRows rows and the same
@@ -788,7 +811,7 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     // input slices per workgroup.  Latency rule (small matrices): at most one batch of tiles per wave.
     // Parallelism rule (large ones): no more slices than it takes to field about 1536 waves, so that a
     // wave streams a long contiguous run (measured best on 32128x1024, 22016x4096 and 4096x11008).
-    const int batch = gemm_batch(a.rw, (Tb + 15) / 16);
+    const int batch = gemm_batch(a.rw, a.T == 1);
     int wk_lat = 1, wk_par = 1;
     while (wk_lat < 8 && a.W.tk / wk_lat > batch) wk_lat *= 2;
     while (wk_par < 8 && (long)a.W.tn * wk_par < 1536) wk_par *= 2;
@@ -807,7 +830,8 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     }
     // feature groups: as many as keep >= 512 workgroups; at least 4 waves per workgroup, 8 when there are
     // several rows (staging the activations is then the longer part, and it is shared by all waves)
-    int wr = std::max(1, (a.T >= 3 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
+    static const int w8_rows = [] { const char* e = std::getenv("BILD_W8_ROWS"); return e ? std::atoi(e) : 9; }();
+    int wr = std::max(1, (a.T >= w8_rows && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
     for (int c = wr * 2; c * wk <= 8 && c * wk * nacc <= 32; c *= 2)
         if ((a.W.tn + c * a.rw - 1) / (c * a.rw) >= 512) wr = c;
     a.wk = wk;
