@@ -783,7 +783,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
             a.q = M.q; a.k = kc; a.v = vc; a.out = M.a;
             a.T = T; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
             a.causal = 1;
-            a.base_ptr = len_ptr;
+            a.len_ptr = len_ptr;
             a.vcap = s->cap_len;
             a.part_o = M.att_o; a.part_ml = M.att_ml;
             a.scale = att_scale;
@@ -818,7 +818,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
                 a.out = M.a;
                 a.T = T; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
                 a.causal = 0;
-                a.nkeys_ptr = &s->ctl->n_src;
+                a.len_ptr = &s->ctl->n_src;
                 a.part_o = M.att_o; a.part_ml = M.att_ml;
                 a.scale = att_scale;
                 int rc = emit_attention(s, M, a, s->n_src, sink, &merge_splits);
@@ -1083,6 +1083,7 @@ int run_encoder(bild_state* s, int w) {
             a.T = S; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
             a.causal = 0;
             a.nkeys_fixed = S;
+            a.len_ptr = &s->ctl->n_src;  // not used with a fixed count, but the kernel reads it
             a.vcap = s->cap_src;
             a.splits = 1;
             a.nw = pick_attn_waves(dt, c.d_head, std::min(S, kMaxRows), S, 1);

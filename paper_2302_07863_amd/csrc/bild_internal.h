@@ -120,9 +120,8 @@ struct AttnArgs {
     float* out;      // [T][I]
     int T, heads, d_head, i_dim;
     int causal;                // 1: row t sees keys <= base + t
-    const int* base_ptr;       // causal: base = *base_ptr + base_add = position of row 0
-    int base_add;
-    const int* nkeys_ptr;      // non-causal: number of keys = *nkeys_ptr (or nkeys_fixed if null)
+    const int* len_ptr;        // never null.  causal: base = *len_ptr + base_add = position of row 0;
+    int base_add;              // non-causal: number of keys = nkeys_fixed if > 0, else *len_ptr
     int nkeys_fixed;
     int splits;                // key ranges handled by separate workgroups
     int defer_merge;           // splits > 1: leave the partials for the consumer GEMM to merge (no merge kernel)

@@ -1022,11 +1022,18 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
 #define ASTAMP(i) do { } while (0)
 #endif
     ASTAMP(0);
-    const int base = a.causal ? (*a.base_ptr + a.base_add) : 0;
-    const int nkeys = a.causal ? base + T : (a.nkeys_ptr ? *a.nkeys_ptr : a.nkeys_fixed);
-    const int nblk = (nkeys + 31) >> 5;
-    const int bps = (nblk + a.splits - 1) / a.splits;
-    const int blk_begin = min(nblk, sp * bps), blk_end = min(nblk, blk_begin + bps);
+    // One unconditional scalar load of the length (the launcher guarantees the pointer): it is requested here and
+    // first used behind q's vector loads, so the two trips to memory overlap.
+    const int len_v = *a.len_ptr;
+    int base = 0, nkeys = 0, blk_begin = 0, blk_end = 0;
+    auto ranges = [&]() {
+        base = a.causal ? len_v + a.base_add : 0;
+        nkeys = a.causal ? base + T : (a.nkeys_fixed > 0 ? a.nkeys_fixed : len_v);
+        const int nblk = (nkeys + 31) >> 5;
+        const int bps = (nblk + a.splits - 1) / a.splits;
+        blk_begin = min(nblk, sp * bps);
+        blk_end = min(nblk, blk_begin + bps);
+    };
 
     // ---- stage q * scale (zero padded to NT*16 rows x DHP dims) ----
     // The memory counter retires loads in issue order, so q (needed first, and warm) is requested before the first
@@ -1196,10 +1203,14 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
     // two register buffers: the next 32-key block loads while the current one is processed
     {
         uint4 K0[2][KN], V0[DT16][VN];
-        int blk = blk_begin + wave;
+        int blk = 0;
         // a wave without a block requests block 0 of the cache all the same (valid memory, never processed): the
         // request sits between q's loads and their use and must not be conditional
-        stage_q([&] { load_kv(K0, V0, blk < blk_end ? blk : 0); });
+        stage_q([&] {
+            ranges();
+            blk = blk_begin + wave;
+            load_kv(K0, V0, blk < blk_end ? blk : 0);
+        });
         ASTAMP(1);
         __syncthreads();
         ASTAMP(2);
@@ -1341,7 +1352,7 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
     if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
     const int dh32 = a.d_head <= 32 ? 1 : (a.d_head <= 64 ? 2 : 4);
     const unsigned row_blocks = (unsigned)((a.T + kMaxRows - 1) / kMaxRows);
-    if (row_blocks > 1 && a.splits != 1) return hipErrorInvalidValue;
+    if ((row_blocks > 1 && a.splits != 1) || !a.len_ptr) return hipErrorInvalidValue;
     const size_t smem = attn_lds_bytes(dtype, a.d_head, std::min(a.T, kMaxRows), a.nw);
     const dim3 grid(a.heads, a.splits, row_blocks), block(64 * a.nw);
 #define BILD_ATTN(DTV, DHV)                                                               \
