@@ -573,12 +573,14 @@ int pull_ctl(bild_state* s) {
 
 // Key splits of one attention launch and whether the consumer projection merges them (`defer`).
 // A workgroup's time grows with the K/V bytes it streams (about 2 us for 32 KiB, 3 us for 128 KiB, then in
-// proportion: a CU sustains under 30 GB/s).  Partials merged by the consumer cost no kernel but it reads
-// splits x rows of them, so that route is limited to 8 splits and splits * rows <= 16; the merge kernel
-// costs about 5 us and therefore only pays when it brings a workgroup from above 160 KiB down to 128 KiB.
+// proportion).  Partials merged by the consumer cost no kernel but it reads splits x rows of them and spends
+// an exponential per split and piece: measured on 512 keys of 64 dims, four splits of 32 KiB win up to four
+// rows (1051 against 1127 us per single-row pass of 24 layers) and lose from five rows on (1497 against 1412 us
+// at eight rows), so the route is taken for at most four rows.  The merge kernel costs about 5 us and therefore
+// only pays when it brings a workgroup from above 160 KiB down to 128 KiB.
 int pick_splits_raw(int d_head, int esz, int max_splits, int nkeys, int heads, int T, bool* defer) {
     const size_t per_head = (size_t)nkeys * d_head * 2 * esz;
-    const size_t want = (size_t)(T <= 4 ? 32 : (T <= 8 ? 64 : 128)) << 10;
+    const size_t want = (size_t)(T <= 4 ? 32 : 128) << 10;
     auto fits = [&](int sp) { return sp <= max_splits && heads * sp <= 512; };
     int d_sp = 1;  // deferred route: as many splits as it allows, up to the wanted size
     while (per_head / d_sp > want && d_sp * 2 <= 8 && d_sp * 2 * T <= 16 && fits(d_sp * 2)) d_sp *= 2;

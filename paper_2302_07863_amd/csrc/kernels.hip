@@ -466,14 +466,17 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                     }
                 }
             };
-            // Up to four pieces per thread (two to eight rows of the common widths): activations first, weights
-            // behind them.  More rows: the conversions are the longer part and a round of eight loads with the
+            // Up to eight pieces per thread: activations first, weights behind them.  More rows: the conversions are the longer part and a round of eight loads with the
             // weights behind it does not fit the register file, so the weights are requested first and the
             // rounds skip what they do not need.
             if (total <= 2 * nthr) {
                 pieces(std::integral_constant<int, 2>{}, std::true_type{}, tid, hook);
             } else if (total <= 4 * nthr) {
                 pieces(std::integral_constant<int, 4>{}, std::true_type{}, tid, hook);
+            } else if (NT == 1 && total <= 6 * nthr) {  // (above 16 rows the second accumulator set needs the registers)
+                pieces(std::integral_constant<int, 6>{}, std::true_type{}, tid, hook);
+            } else if (NT == 1 && total <= 8 * nthr) {
+                pieces(std::integral_constant<int, 8>{}, std::true_type{}, tid, hook);
             } else {
                 hook(false);
                 for (int eb = tid; eb < total; eb += nthr * 8)
