@@ -573,17 +573,21 @@ int pull_ctl(bild_state* s) {
 
 // Key splits of one attention launch and whether the consumer projection merges them (`defer`).
 // A workgroup's time grows with the K/V bytes it streams (about 2 us for 32 KiB, 3 us for 128 KiB, then in
-// proportion).  Partials merged by the consumer cost no kernel but it reads splits x rows of them and spends
-// an exponential per split and piece: measured on 512 keys of 64 dims, four splits of 32 KiB win up to four
-// rows (1051 against 1127 us per single-row pass of 24 layers) and lose from five rows on (1497 against 1412 us
-// at eight rows), so the route is taken for at most four rows.  The merge kernel costs about 5 us and therefore
-// only pays when it brings a workgroup from above 160 KiB down to 128 KiB.
+// proportion).  Partials merged by the consumer cost no kernel: it works out the normalised weights once per
+// (row, head) and then reads `splits` float4 per piece.  Measured on 512 keys of 64 dims, 24 layers: four
+// splits of 32 KiB against none: 1055 / 1127 us per single-row pass, 1319 / 1351 us at 8 rows, 1585 / 1649 us at
+// 16 rows, so the route is taken up to 16 rows (bounds: 8 splits, rows * heads <= 256, rows * heads * splits <= 1024
+// - what the consumer's threads and its weight table in LDS hold).  The merge kernel costs about 5 us and therefore only pays when it
+// brings a workgroup from above 160 KiB down to 128 KiB.
 int pick_splits_raw(int d_head, int esz, int max_splits, int nkeys, int heads, int T, bool* defer) {
     const size_t per_head = (size_t)nkeys * d_head * 2 * esz;
-    const size_t want = (size_t)(T <= 4 ? 32 : 128) << 10;
+    const size_t want = (size_t)(T <= 16 ? 32 : 128) << 10;
     auto fits = [&](int sp) { return sp <= max_splits && heads * sp <= 512; };
     int d_sp = 1;  // deferred route: as many splits as it allows, up to the wanted size
-    while (per_head / d_sp > want && d_sp * 2 <= 8 && d_sp * 2 * T <= 16 && fits(d_sp * 2)) d_sp *= 2;
+    // the consumer keeps one (row, head) pair per thread (at least 256 threads) and a table of splits x pairs
+    // weights in the 4 KiB its smallest reduction area has
+    const bool mergeable = T <= 16 && heads * T <= 256;
+    while (per_head / d_sp > want && d_sp * 2 <= 8 && mergeable && heads * T * d_sp * 2 <= 1024 && fits(d_sp * 2)) d_sp *= 2;
     *defer = d_sp > 1;
     if (per_head / d_sp <= ((size_t)160 << 10)) return d_sp;
     int sp = d_sp;

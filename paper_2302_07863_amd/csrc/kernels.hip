@@ -203,7 +203,7 @@ __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
 // launches, a loop index in the persistent pass kernel); `smem` is the workgroup's dynamic LDS.
 // The argument block may live in the kernel-argument segment or (persistent kernel) in constant-address-space
 // device memory, hence the template parameter A.
-template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, false), bool COH = false, bool MG = false,
+template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, false), bool COH = false, int MG = 0,
           bool ONE = false, class A>
 __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* smem) {
     constexpr int KT = DT ? 32 : 16;
@@ -387,50 +387,69 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             }
             return ss;
         };
-        if (MG && a.mg_splits > 1) {
-            // x arrives as key-split attention partials (no norm in front of an output projection): every
-            // piece is sum_s w_s O_s / sum_s w_s L_s with w_s = exp(m_s - max m) of its (row, head)
+        if (MG > 0) {
+            // x arrives as MG key-split attention partials (no norm in front of an output projection): every piece is
+            // sum_s w_s O_s / sum_s w_s L_s with w_s = exp(m_s - max m) of its (row, head).  The normalised weights are
+            // worked out once per (row, head) - one pair per thread - and handed over in LDS (the reduction area is
+            // free until the MFMAs are done); a piece then costs MG loads and MG multiply-adds.
+            constexpr int SP = MG > 0 ? MG : 1;  // (1 only where this branch is dead code)
+            constexpr int P = SP == 8 ? 2 : 4;  // pieces per round: P * SP float4 loads in flight per thread
             const int total = T * n4;
             const unsigned magic = 0xFFFFFFFFu / (unsigned)n4 + 1u;
-            const int SP = a.mg_splits;  // at most 8
-            auto piece = [&](int eraw, auto&& hk) {
-                const int e = min(eraw, total - 1);
-                const int t = (int)__umulhi((unsigned)e, magic), k4 = e - t * n4;
-                const int kk = k0 + k4 * 4;
-                const float* ml = a.mg_ml + ((size_t)t * a.mg_heads + kk / a.d_head) * 2;
-                const size_t ml_stride = (size_t)T * a.mg_heads * 2, o_stride = (size_t)T * a.ldx;
-                const float* op = a.mg_o + (size_t)t * a.ldx + kk;
-                float m[8], l[8];
-                float4 o[8];
+            const int npairs = T * a.mg_heads;  // at most the thread count (checked at launch)
+            const size_t ml_stride = (size_t)npairs * 2, o_stride = (size_t)T * a.ldx;
+            float* wts = (float*)red;  // [npairs][SP]
+            const int pr = min(tid, npairs - 1);  // a thread past the end redoes the last pair (same values)
+            float m[SP], l[SP];
 #pragma unroll
-                for (int sp = 0; sp < 8; ++sp) {
-                    const int sc = min(sp, SP - 1);
-                    m[sp] = ld_act<COH>(ml + sc * ml_stride);
-                    l[sp] = ld_act<COH>(ml + sc * ml_stride + 1);
-                    o[sp] = ld_act4<COH>(op + sc * o_stride);
+            for (int sp = 0; sp < SP; ++sp) {
+                m[sp] = ld_act<COH>(a.mg_ml + sp * ml_stride + (size_t)pr * 2);
+                l[sp] = ld_act<COH>(a.mg_ml + sp * ml_stride + (size_t)pr * 2 + 1);
+            }
+            auto round = [&](auto first, int eb, auto&& hk) {
+                float4 o[P][SP];
+                int tt[P], kk[P];
+#pragma unroll
+                for (int u = 0; u < P; ++u) {
+                    const int e = min(eb + u * nthr, total - 1);
+                    tt[u] = (int)__umulhi((unsigned)e, magic);
+                    kk[u] = e - tt[u] * n4;
+                    const float* op = a.mg_o + (size_t)tt[u] * a.ldx + k0 + kk[u] * 4;
+#pragma unroll
+                    for (int sp = 0; sp < SP; ++sp) o[u][sp] = ld_act4<COH>(op + sp * o_stride);
                 }
                 hk(true);
-                float M = -INFINITY;
+                if (decltype(first)::value) {
+                    float M = -INFINITY;
 #pragma unroll
-                for (int sp = 0; sp < 8; ++sp) {
-                    m[sp] = sp < SP ? m[sp] : -INFINITY;
-                    M = fmaxf(M, m[sp]);
-                }
-                float L = 0.f;
-                float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+                    for (int sp = 0; sp < SP; ++sp) M = fmaxf(M, m[sp]);
+                    float w[SP], L = 0.f;
 #pragma unroll
-                for (int sp = 0; sp < 8; ++sp) {
-                    const float w = (m[sp] == -INFINITY) ? 0.f : expf(m[sp] - M);
-                    L += l[sp] * w;
-                    r.x += o[sp].x * w; r.y += o[sp].y * w; r.z += o[sp].z * w; r.w += o[sp].w * w;
+                    for (int sp = 0; sp < SP; ++sp) {
+                        w[sp] = (m[sp] == -INFINITY) ? 0.f : expf(m[sp] - M);
+                        L += l[sp] * w[sp];
+                    }
+                    const float inv = 1.f / L;
+#pragma unroll
+                    for (int sp = 0; sp < SP; ++sp) wts[pr * SP + sp] = w[sp] * inv;
+                    __syncthreads();
                 }
-                const float inv = 1.f / L;
-                // a thread without a piece of its own rewrites the last piece with the same value: the loads above
-                // must not become conditional, or the compiler moves them behind the hook
-                put(t, k4, make_float4(r.x * inv, r.y * inv, r.z * inv, r.w * inv), r);
+                // every piece is combined and written, also the clamped duplicates past the end (same value to the same
+                // place): the loads above must not become conditional, or the compiler moves them behind the hook
+#pragma unroll
+                for (int u = 0; u < P; ++u) {
+                    const float* wp = wts + (tt[u] * a.mg_heads + (k0 + kk[u] * 4) / a.d_head) * SP;
+                    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                    for (int sp = 0; sp < SP; ++sp) {
+                        const float w = wp[sp];
+                        r.x += o[u][sp].x * w; r.y += o[u][sp].y * w; r.z += o[u][sp].z * w; r.w += o[u][sp].w * w;
+                    }
+                    put(tt[u], kk[u], r, r);
+                }
             };
-            piece(tid, hook);
-            for (int e = tid + nthr; e < total; e += nthr) piece(e, noop);
+            round(std::true_type{}, tid, hook);
+            for (int eb = tid + P * nthr; eb < total; eb += P * nthr) round(std::false_type{}, eb, noop);
         } else if (T > 1 && (n4 & 63) == 0) {
             // Several rows whose chunk is a whole number of wavefront-wide pieces: the rows are laid end to
             // end and dealt to all threads, which spreads the conversion work evenly and lets one round of
@@ -766,10 +785,10 @@ __global__ __launch_bounds__(512) void gemm_row_kernel(const GemmArgs a) {
 }
 
 // Output projection whose input is still in key-split attention partials (merged while staging).
-template <int DT, int NT>
+template <int DT, int SPLITS>
 __global__ __launch_bounds__(512) void gemm_merge_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    gemm_body<DT, 1, EPI_RESID, 0, NT, gemm_batch(1, false), false, true>(a, (int)blockIdx.x, smem);
+    gemm_body<DT, 1, EPI_RESID, 0, 1, gemm_batch(1, false), false, SPLITS>(a, (int)blockIdx.x, smem);
 }
 
 // More than kMaxRows rows (encoder, prompt prefill): blockIdx.y picks a block of kMaxRows rows and the same
@@ -886,8 +905,9 @@ static hipError_t raise_lds_limits() {
     (const void*)gemm_rows_kernel<DTV, 1, EPI_QKV, 0>, (const void*)gemm_rows_kernel<DTV, 1, EPI_QKV, 1>, \
     (const void*)gemm_rows_kernel<DTV, 1, EPI_ACT, 0>, (const void*)gemm_rows_kernel<DTV, 2, EPI_ACT, 0>
         const void* fns[] = {BILD_G(0), BILD_G(1),
-                             (const void*)gemm_merge_kernel<0, 1>, (const void*)gemm_merge_kernel<0, 2>,
-                             (const void*)gemm_merge_kernel<1, 1>, (const void*)gemm_merge_kernel<1, 2>,
+                             (const void*)gemm_merge_kernel<0, 2>, (const void*)gemm_merge_kernel<0, 4>,
+                             (const void*)gemm_merge_kernel<0, 8>, (const void*)gemm_merge_kernel<1, 2>,
+                             (const void*)gemm_merge_kernel<1, 4>, (const void*)gemm_merge_kernel<1, 8>,
                              (const void*)attn_rows_kernel<0, 1>, (const void*)attn_rows_kernel<0, 2>,
                              (const void*)attn_rows_kernel<0, 4>, (const void*)attn_rows_kernel<1, 1>,
                              (const void*)attn_rows_kernel<1, 2>, (const void*)attn_rows_kernel<1, 4>,
@@ -934,15 +954,20 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     if (row_blocks > 1 && a.epi == EPI_LMHEAD) return hipErrorInvalidValue;  // softmax partials are per pass
     if ((a.gain != nullptr) != (a.epi != EPI_RESID)) return hipErrorInvalidValue;  // the kernels fix the norm by the epilogue
     if (a.mg_splits > 1) {
-        if (a.mg_splits > 8 || a.gain || row_blocks > 1 || a.epi != EPI_RESID || a.rw != 1) return hipErrorInvalidValue;
+        // merged staging: 2, 4 or 8 splits, up to 16 rows, one (row, head) pair per thread, weights in the reduction area
+        const int sp = a.mg_splits, npairs = a.T * a.mg_heads;
+        if ((sp != 2 && sp != 4 && sp != 8) || a.gain || a.T > 16 || a.epi != EPI_RESID || a.rw != 1 || a.mg_heads < 1 ||
+            npairs > 64 * a.nwv || (size_t)npairs * sp * 4 > (size_t)gemm_red_bytes(a.nwv, 1))
+            return hipErrorInvalidValue;
         const dim3 grid1((unsigned)gemm_num_blocks(a)), block1(64 * a.nwv);
-        if (dtype) {
-            if (a.T > 16) hipLaunchKernelGGL((gemm_merge_kernel<1, 2>), grid1, block1, smem, st, a);
-            else hipLaunchKernelGGL((gemm_merge_kernel<1, 1>), grid1, block1, smem, st, a);
-        } else {
-            if (a.T > 16) hipLaunchKernelGGL((gemm_merge_kernel<0, 2>), grid1, block1, smem, st, a);
-            else hipLaunchKernelGGL((gemm_merge_kernel<0, 1>), grid1, block1, smem, st, a);
-        }
+#define BILD_MG(DTV)                                                                           \
+    do {                                                                                        \
+        if (sp == 2) hipLaunchKernelGGL((gemm_merge_kernel<DTV, 2>), grid1, block1, smem, st, a); \
+        else if (sp == 4) hipLaunchKernelGGL((gemm_merge_kernel<DTV, 4>), grid1, block1, smem, st, a); \
+        else hipLaunchKernelGGL((gemm_merge_kernel<DTV, 8>), grid1, block1, smem, st, a);       \
+    } while (0)
+        if (dtype) BILD_MG(1); else BILD_MG(0);
+#undef BILD_MG
         return hipGetLastError();
     }
     const dim3 grid((unsigned)gemm_num_blocks(a), row_blocks), block(64 * a.nwv);

@@ -73,7 +73,8 @@ def test_gemm_launch_shapes_are_consistent(pair):
 @pytest.mark.parametrize("pair", sorted(bi.PAIRS))
 def test_attention_launch_shapes_are_consistent(pair):
     """Key splits stay within the partial buffers and the grid the kernels assume; partials are left to the consumer
-    projection only in the range it merges (at most 8 splits, splits x rows <= 16); the LDS request fits; a workgroup
+    projection only in the range it merges (at most 8 splits and 16 rows, one (row, head) pair per thread of a 256-thread
+    workgroup, a weight table of at most 4 KiB); the LDS request fits; a workgroup
     that is not split further streams at most about 160 KiB unless the split limits are exhausted."""
     cfg = bi.PAIRS[pair]()
     for shape in (cfg.small, cfg.large):
@@ -87,7 +88,8 @@ def test_attention_launch_shapes_are_consistent(pair):
                     if rows > 32:
                         assert s["splits"] == 1
                     if s["defer"]:
-                        assert 1 < s["splits"] <= 8 and s["splits"] * rows <= 16
+                        assert 1 < s["splits"] <= 8 and rows <= 16 and rows * shape.heads <= 256
+                        assert rows * shape.heads * s["splits"] * 4 <= 4096
                     assert s["waves"] in (1, 2, 4, 8) and 0 < s["lds"] <= 128 * 1024
                     per_wg = nkeys * shape.d_head * 2 * esz / s["splits"]
                     if per_wg > 160 * 1024 and rows <= 32 and not s["defer"]:
