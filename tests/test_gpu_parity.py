@@ -335,6 +335,20 @@ def test_head_dim_128_and_64_bf16_toys():
         print(dh, parity.teacher_forced(st, ref, R.n0, 0.4, 1.0, cfg), ref.stats, flush=True)
 
 
+def test_two_way_key_splits_merged_by_the_output_projection():
+    """Cross-attention over a source whose K/V per head are between one and two split sizes (32 KiB): two key splits,
+    merged while the output projection stages its input - bf16 (200 keys) and fp32 (100 keys) storage."""
+    for dtype, n_src in ((bi.DT_BF16, 200), (bi.DT_F32, 100)):
+        assert pkg.binding.attn_shape(2, 64, 1, n_src, 8, 1 if dtype == bi.DT_BF16 else 0)["splits"] == 2
+        cfg = bi.toy_pair(dtype=dtype, act=bi.ACT_RELU, pos=bi.POS_SINUSOIDAL, cross=True, tied=False, d=128, heads=2, d_head=64,
+                          d_ff=192, vocab=211, n_src=n_src)
+        R = Rig(cfg)
+        ref = oracle.bild_generate(R.req, 0.4, 1.0, 6, cfg.max_new, keep_logits=True)
+        st = R.state(cfg.max_new, 6)
+        st.encode(R.src)
+        print(dtype, parity.teacher_forced(st, ref, R.n0, 0.4, 1.0, cfg), ref.stats, flush=True)
+
+
 @pytest.mark.timeout(1500)
 @pytest.mark.skipif(__import__("os").environ.get("BILD_TEST_7B") != "1",
                     reason="7B-shaped pair: ~60 s of weight generation and a float64 oracle over 13 GB of weights; "
