@@ -189,8 +189,9 @@ __device__ __forceinline__ void st_u16(uint16_t* p, uint16_t v) {
 //   zblk               64 bytes of zeros
 // =====================================================================================
 // weight tiles a wave loads per batch (split over its RW feature tiles); two batches are in flight
-// (12 in the single-row kernel; 8 with several rows, whose staging needs the registers)
-__host__ __device__ constexpr int gemm_batch(int rw, bool one_row) { return (one_row ? 12 : 8) / rw; }
+// (12 in the single-row kernel; 8 with several rows, whose staging needs the registers; 6 above 16 rows, where the
+// second set of row tiles needs more)
+__host__ __device__ constexpr int gemm_batch(int rw, bool one_row, int nt = 1) { return (one_row ? 12 : (nt > 1 ? 6 : 8)) / rw; }
 
 __host__ __device__ inline int xs_row_stride(int dt, int kc) { return dt ? (kc + 8) * 2 : (kc + 4) * 4; }
 __host__ __device__ inline int xs_bytes(int dt, int kc, int T) { return T * xs_row_stride(dt, kc) * (dt ? 2 : 1); }
@@ -203,7 +204,7 @@ __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
 // launches, a loop index in the persistent pass kernel); `smem` is the workgroup's dynamic LDS.
 // The argument block may live in the kernel-argument segment or (persistent kernel) in constant-address-space
 // device memory, hence the template parameter A.
-template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, false), bool COH = false, int MG = 0,
+template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, false, NT), bool COH = false, int MG = 0,
           bool ONE = false, class A>
 __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* smem) {
     constexpr int KT = DT ? 32 : 16;
@@ -419,6 +420,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                     for (int sp = 0; sp < SP; ++sp) o[u][sp] = ld_act4<COH>(op + sp * o_stride);
                 }
                 hk(true);
+                __builtin_amdgcn_sched_barrier(0);  // nothing that uses a loaded value may move above the requests
                 if (decltype(first)::value) {
                     float M = -INFINITY;
 #pragma unroll
@@ -473,6 +475,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                     g[u] = ldg(kk[u]);
                 }
                 hk(true);
+                __builtin_amdgcn_sched_barrier(0);  // the scheduler otherwise pulls the first conversion above the later requests
 #pragma unroll
                 for (int u = 0; u < P; ++u) {
                     const bool in = eb + u * nthr < total;  // wave-uniform: total and the wave's first piece are multiples of 64
@@ -515,6 +518,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                     const int ca = min(ka, n4 - 1), cb = min(kb2, n4 - 1);
                     const float4 va = ldx(t, ca), ga = ldg(ca), vb = ldx(t, cb), gb = ldg(cb);
                     hk(true);
+                    __builtin_amdgcn_sched_barrier(0);  // (as above)
                     // unconditional conversions and writes (duplicates carry the same value and count as zero)
                     const float sa = put(t, ca, va, ga), sb = put(t, cb, vb, gb);
                     ssj += (act && ka < n4 ? sa : 0.f) + (act && kb2 < n4 ? sb : 0.f);
@@ -528,6 +532,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                             g[u] = ldg(k4);
                         }
                         hk2(true);
+                        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                         for (int u = 0; u < 8; ++u) {
                             const float su = put(t, min(kb + u * step, n4 - 1), v[u], g[u]);
@@ -833,7 +838,7 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     // input slices per workgroup.  Latency rule (small matrices): at most one batch of tiles per wave.
     // Parallelism rule (large ones): no more slices than it takes to field about 1536 waves, so that a
     // wave streams a long contiguous run (measured best on 32128x1024, 22016x4096 and 4096x11008).
-    const int batch = gemm_batch(a.rw, a.T == 1);
+    const int batch = gemm_batch(a.rw, a.T == 1, (Tb + 15) / 16);
     int wk_lat = 1, wk_par = 1;
     while (wk_lat < 8 && a.W.tk / wk_lat > batch) wk_lat *= 2;
     while (wk_par < 8 && (long)a.W.tn * wk_par < 1536) wk_par *= 2;
@@ -1074,6 +1079,7 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
             const bool real = t < T && d4 < dh;
             float4 v = ld_act4<COH>(a.q + (size_t)min(t, T - 1) * I + h * dh + min(d4, dh - 4));
             hk();
+            __builtin_amdgcn_sched_barrier(0);  // the conversion of q stays behind the K/V requests
             v.x = real ? v.x * a.scale : 0.f; v.y = real ? v.y * a.scale : 0.f;
             v.z = real ? v.z * a.scale : 0.f; v.w = real ? v.w * a.scale : 0.f;
             if (DT) {
