@@ -817,7 +817,10 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const GemmArgs a) {
 static int gemm_pick_chunks(GemmArgs& a, int dtype) {
     const int kt = dtype ? 32 : 16;
     const bool gated = a.epi == EPI_ACT && a.act != BILD_ACT_RELU;
-    a.rw = gated ? 2 : 1;
+    // A very wide LM head (250k ids) at up to 16 rows: four feature tiles per wave, so that a workgroup streams long
+    // enough for the staging of its activations (the registers allow one workgroup per compute unit) to be a small share.
+    // (measured: 75 -> 52 us on a 250112 x 512 head; no gain on 32128 x 1024 or 32000 x 4096)
+    a.rw = gated ? 2 : (a.epi == EPI_LMHEAD && a.T <= 16 && a.W.tn >= 8192 ? 4 : 1);
     // input chunks staged in LDS: at most 96 KiB and never more than the limit leaves beside the largest
     // reduction area (8 waves), balanced so that every chunk has the same tile count +-1
     const int Tb = std::min(a.T, kMaxRows);  // rows one workgroup handles (more rows: more row blocks)
@@ -855,10 +858,10 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
         a.nwv = a.wk * wr;
         return;
     }
-    // feature groups: as many as keep >= 512 workgroups; at least 4 waves per workgroup, 8 when there are
-    // several rows (staging the activations is then the longer part, and it is shared by all waves)
-    static const int w8_rows = [] { const char* e = std::getenv("BILD_W8_ROWS"); return e ? std::atoi(e) : 9; }();
-    int wr = std::max(1, (a.T >= w8_rows && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
+    // feature groups: as many as keep >= 512 workgroups; at least 4 waves per workgroup, 8 from nine rows on
+    // (staging the activations is then the longer part, and it is shared by all waves; measured on 24 layers of
+    // 1024-wide projections: 4 waves win up to 8 rows, 1365 against 1490 us per pass, 8 waves from 9 rows, 1505 against 1578)
+    int wr = std::max(1, (a.T >= 9 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
     for (int c = wr * 2; c * wk <= 8 && c * wk * nacc <= 32; c *= 2)
         if ((a.W.tn + c * a.rw - 1) / (c * a.rw) >= 512) wr = c;
     a.wk = wk;
@@ -905,7 +908,8 @@ static hipError_t raise_lds_limits() {
     (const void*)gemm_row_kernel<DTV, 1, EPI_STORE, 0>, (const void*)gemm_row_kernel<DTV, 1, EPI_RESID, 0>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0>, (const void*)gemm_row_kernel<DTV, 2, EPI_ACT, 0>, \
-    (const void*)gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0>, (const void*)gemm_row_kernel<DTV, 4, EPI_LMHEAD, 0>, \
+    (const void*)gemm_kernel<DTV, 4, EPI_LMHEAD, 0, 1>, \
     (const void*)gemm_rows_kernel<DTV, 1, EPI_STORE, 0>, (const void*)gemm_rows_kernel<DTV, 1, EPI_RESID, 0>, \
     (const void*)gemm_rows_kernel<DTV, 1, EPI_QKV, 0>, (const void*)gemm_rows_kernel<DTV, 1, EPI_QKV, 1>, \
     (const void*)gemm_rows_kernel<DTV, 1, EPI_ACT, 0>, (const void*)gemm_rows_kernel<DTV, 2, EPI_ACT, 0>
@@ -998,7 +1002,13 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
             if (a.rw == 2) BILD_L(DTV, 2, EPI_ACT, 0); else BILD_L(DTV, 1, EPI_ACT, 0); \
             break;                                                               \
         case EPI_LMHEAD:                                                         \
-            if (a.T == 1)                                                        \
+            if (a.rw == 4 && a.T == 1)                                           \
+                hipLaunchKernelGGL((gemm_row_kernel<DTV, 4, EPI_LMHEAD, 0>), grid, block, smem, st, a); \
+            else if (a.rw == 4 && a.T <= 16)                                     \
+                hipLaunchKernelGGL((gemm_kernel<DTV, 4, EPI_LMHEAD, 0, 1>), grid, block, smem, st, a); \
+            else if (a.rw != 1)                                                  \
+                return hipErrorInvalidValue;                                     \
+            else if (a.T == 1)                                                   \
                 hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0>), grid, block, smem, st, a); \
             else if (a.T > 16)                                                   \
                 hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPI_LMHEAD, 0, 2>), grid, block, smem, st, a); \
