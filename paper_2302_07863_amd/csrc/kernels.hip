@@ -864,6 +864,11 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     int wr = std::max(1, (a.T >= 9 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
     for (int c = wr * 2; c * wk <= 8 && c * wk * nacc <= 32; c *= 2)
         if ((a.W.tn + c * a.rw - 1) / (c * a.rw) >= 512) wr = c;
+    // Between one and two workgroups per compute unit the chip ends up half with two and half with one of them:
+    // halve the workgroups instead (12288 x 4096 at one row: 384 workgroups 23.4 us, 768 of half the size 21.5 us; with
+    // several rows the doubled staging costs more than the balance gains).
+    const int blocks = (a.W.tn + wr * a.rw - 1) / (wr * a.rw);
+    if (wr > 1 && blocks > 256 && blocks < 512 && a.epi != EPI_LMHEAD && a.T == 1) wr /= 2;
     a.wk = wk;
     a.nwv = wk * wr;
 }
