@@ -858,10 +858,11 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
         a.nwv = a.wk * wr;
         return;
     }
-    // feature groups: as many as keep >= 512 workgroups; at least 4 waves per workgroup, 8 from nine rows on
-    // (staging the activations is then the longer part, and it is shared by all waves; measured on 24 layers of
-    // 1024-wide projections: 4 waves win up to 8 rows, 1365 against 1490 us per pass, 8 waves from 9 rows, 1505 against 1578)
-    int wr = std::max(1, (a.T >= 9 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
+    // feature groups: as many as keep >= 512 workgroups; at least 4 waves per workgroup, 8 once a thread of a 4-wave
+    // workgroup would stage more than eight pieces (staging the activations is then the longer part, and it is shared
+    // by all waves; measured on 24 layers of 1024-wide projections: 4 waves win up to 8 rows, 1365 against 1490 us per
+    // pass, 8 waves from 9 rows, 1505 against 1578)
+    int wr = std::max(1, ((long)a.T * a.W.k > 8192 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
     for (int c = wr * 2; c * wk <= 8 && c * wk * nacc <= 32; c *= 2)
         if ((a.W.tn + c * a.rw - 1) / (c * a.rw) >= 512) wr = c;
     // Between one and two workgroups per compute unit the chip ends up half with two and half with one of them:
