@@ -97,6 +97,23 @@ def test_attention_launch_shapes_are_consistent(pair):
                         assert s["splits"] * 2 > max_splits or shape.heads * s["splits"] * 2 > 512
 
 
+def test_launch_shape_rules_at_their_boundaries():
+    """The measured thresholds of the GEMM launch shapes: eight-wave workgroups once a thread of a four-wave workgroup
+    would stage more than eight pieces (rows x inputs > 8192); single-row launches never field between one and two
+    workgroups per compute unit; a very wide LM head takes four feature tiles per wave up to 16 rows."""
+    assert b.gemm_shape(1024, 1024, 8)["nwv"] == 4 and b.gemm_shape(1024, 1024, 9)["nwv"] == 8
+    assert b.gemm_shape(512, 512, 16)["nwv"] == 4 and b.gemm_shape(512, 512, 17)["nwv"] == 8
+    one, two = b.gemm_shape(12288, 4096, 1), b.gemm_shape(12288, 4096, 2)
+    assert one["blocks"] == 768 and one["nwv"] == 2 and two["blocks"] == 384 and two["nwv"] == 4
+    for n, k in ((1024, 1024), (3072, 1024), (4096, 1024), (1024, 4096), (12288, 4096), (22016, 4096), (4096, 11008)):
+        blocks = b.gemm_shape(n, k, 1)["blocks"]
+        assert not 256 < blocks < 512, (n, k, blocks)
+    wide = b.gemm_shape(250112, 512, 1, False, True)
+    assert wide["rw"] == 4 and wide["blocks"] * wide["nwv"] * 4 >= 250112 // 16
+    assert b.gemm_shape(250112, 512, 17, False, True)["rw"] == 1
+    assert b.gemm_shape(32128, 1024, 1, False, True)["rw"] == 1
+
+
 def test_debug_calls_reject_bad_arguments():
     lib = b.lib()
     assert lib.bild_debug_tiled_bytes(0, 32, 0) == b.EINVAL
