@@ -1714,7 +1714,7 @@ extern "C" int bild_debug_gemm_shape(int n, int k, int rows, int gated, int lm_h
     out[4] = (int32_t)gemm_num_blocks(g);
     out[5] = (rows + kMaxRows - 1) / kMaxRows;
     out[6] = (int32_t)gemm_lds_bytes(g, dtype);
-    out[7] = 128 * 1024;
+    out[7] = 160 * 1024;
     return BILD_OK;
 }
 

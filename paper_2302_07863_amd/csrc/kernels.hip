@@ -813,6 +813,10 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const GemmArgs a) {
 }
 
 #ifndef BILD_DEVICE_ONLY
+// LDS a GEMM workgroup may ask for (a gfx950 compute unit has 160 KiB) and the share of it the staged chunk may take:
+// a longer chunk means fewer chunk boundaries, at each of which the weight stream of the workgroup pauses for the staging.
+constexpr int kGemmLdsLimit = 160 * 1024;
+constexpr int kGemmStageBudget = 144 * 1024;
 // Rows-per-wave, chunk length and tiles per chunk of a GEMM: what both launch-shape rules start from.
 static int gemm_pick_chunks(GemmArgs& a, int dtype) {
     const int kt = dtype ? 32 : 16;
@@ -824,7 +828,7 @@ static int gemm_pick_chunks(GemmArgs& a, int dtype) {
     // input chunks staged in LDS: at most 96 KiB and never more than the limit leaves beside the largest
     // reduction area (8 waves), balanced so that every chunk has the same tile count +-1
     const int Tb = std::min(a.T, kMaxRows);  // rows one workgroup handles (more rows: more row blocks)
-    const int budget = std::min(96 * 1024, 128 * 1024 - gemm_tail_bytes(8, a.rw * ((Tb + 15) / 16)));
+    const int budget = std::min(kGemmStageBudget, kGemmLdsLimit - gemm_tail_bytes(8, a.rw * ((Tb + 15) / 16)));
     int kc_max = budget / (4 * Tb) - 8;      // 4 bytes of LDS per staged input for either storage type
     kc_max = std::max(128, (kc_max / 128) * 128);
     const int nch = (a.W.k + kc_max - 1) / kc_max;
@@ -903,7 +907,7 @@ __global__ __launch_bounds__(512) void attn_rows_kernel(const AttnArgs a);
 // The big kernels may ask for more than the default 64 KiB of dynamic LDS.
 static hipError_t raise_lds_limits() {
     static hipError_t done = [] {
-        const int lim = 128 * 1024;
+        const int lim = kGemmLdsLimit;
 #define BILD_G1(DTV, NTV) \
     (const void*)gemm_kernel<DTV, 1, EPI_STORE, 0, NTV>, (const void*)gemm_kernel<DTV, 1, EPI_RESID, 0, NTV>, \
     (const void*)gemm_kernel<DTV, 1, EPI_QKV, 0, NTV>, (const void*)gemm_kernel<DTV, 1, EPI_QKV, 1, NTV>, \
