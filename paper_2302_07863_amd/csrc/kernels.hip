@@ -15,8 +15,9 @@
 //                    rollback policy (Sections 3.3, 3.4; Algorithm 1), committing y and
 //                    the cache lengths on the device.
 //
-// The path is bound by HBM bandwidth: every weight byte is read once per pass and the
-// arithmetic per byte is tiny.  Weights therefore sit in HBM in the exact register order
+// The path is bound by memory: every weight byte is read once per pass and the arithmetic
+// per byte is tiny - by HBM bandwidth where the matrices are large (7B-class widths), by the
+// latency of each stage's first cold access where they are small (T5-class).  Weights sit in HBM in the exact register order
 // of the matrix-core A operand (see bild::TMat) so that one wavefront load instruction
 // moves 1 KiB of contiguous memory straight into MFMA operand registers; activations
 // (a few KiB) are staged once per workgroup in LDS as the B operand.  bf16 models keep
