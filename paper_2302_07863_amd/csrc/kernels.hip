@@ -206,7 +206,7 @@ __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
 // The argument block may live in the kernel-argument segment or (persistent kernel) in constant-address-space
 // device memory, hence the template parameter A.
 template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, false, NT), bool COH = false, int MG = 0,
-          bool ONE = false, class A>
+          bool ONE = false, bool TWO = true, class A>
 __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* smem) {
     constexpr int KT = DT ? 32 : 16;
     // the wave index through readfirstlane: the compiler then knows that it - and every tile index, weight address and
@@ -566,23 +566,28 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
         // ---- one chunk: activations, then both weight buffers, then everything else ----
         // hook(true): both buffers go out behind the activation loads; hook(false) (long staging, which needs the
         // registers): the first buffer goes out ahead of the staging and the second one after it
+        // TWO = false (launcher: no wave has more than one batch of tiles): the second buffer does not exist
         bool second_out = false;
         stage(0, K, [&](bool both) {
             request(B0, wkid, nkt0);
-            if (both) request(B1, wkid + S, nkt0);
+            if (TWO && both) request(B1, wkid + S, nkt0);
             second_out = both;
         });
-        if (!second_out) request(B1, wkid + S, nkt0);
+        if (TWO && !second_out) request(B1, wkid + S, nkt0);
         STAMP(1);
         __syncthreads();
         STAMP(2);
-        for (int kt = wkid;; kt += 2 * S) {
-            compute_batch(B0, kt, nkt0);
-            if (kt + S >= nkt0) break;
-            if (kt + 2 * S < nkt0) request(B0, kt + 2 * S, nkt0);
-            compute_batch(B1, kt + S, nkt0);
-            if (kt + 2 * S >= nkt0) break;
-            if (kt + 3 * S < nkt0) request(B1, kt + 3 * S, nkt0);
+        if (!TWO) {
+            compute_batch(B0, wkid, nkt0);
+        } else {
+            for (int kt = wkid;; kt += 2 * S) {
+                compute_batch(B0, kt, nkt0);
+                if (kt + S >= nkt0) break;
+                if (kt + 2 * S < nkt0) request(B0, kt + 2 * S, nkt0);
+                compute_batch(B1, kt + S, nkt0);
+                if (kt + 2 * S >= nkt0) break;
+                if (kt + 3 * S < nkt0) request(B1, kt + 3 * S, nkt0);
+            }
         }
     } else {
         request(B0, wkid, nkt0);
@@ -776,25 +781,34 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
 #undef STAMP
 }
 
-template <int DT, int RW, int EPI, int ROPE, int NT>
+// SHORT: no wave has more than one batch of tiles - the second weight buffer does not exist (see gemm_row_kernel).
+template <int DT, int RW, int EPI, int ROPE, int NT, bool SHORT = false>
 __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    gemm_body<DT, RW, EPI, ROPE, NT>(a, (int)blockIdx.x, smem);
+    gemm_body<DT, RW, EPI, ROPE, NT, gemm_batch(RW, false, NT), false, 0, false, !SHORT>(a, (int)blockIdx.x, smem);
 }
 
 // The single-row pass (the small model's step, the large model's plain step): the row count is a
 // compile-time 1, which removes the multi-row staging paths from the code.
-template <int DT, int RW, int EPI, int ROPE>
+// Padding tiles are not free: a batch slot past the wave's range still costs a load of a clamped tile and, in the
+// first buffer, two MFMAs, and on the latency-bound shapes that is most of a wave's instructions (measured on the T5
+// pair: 236 -> 206 us per small-model step and 1048 -> 962 us per large-model step once the 512- and 1024-wide inputs
+// stopped padding 8 tiles per wave to 24).  VAR picks the batch geometry by the tiles a wave has:
+//   1: at most 8   - one batch of 8, no second buffer
+//   2: at most 16  - two batches of 8
+//   0: more        - batches of 12 (more bytes in flight for the bandwidth-bound shapes)
+constexpr int kShortBatch = 8;
+template <int DT, int RW, int EPI, int ROPE, int VAR = 0>
 __global__ __launch_bounds__(512) void gemm_row_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    gemm_body<DT, RW, EPI, ROPE, 1, gemm_batch(RW, true), false, false, true>(a, (int)blockIdx.x, smem);
+    gemm_body<DT, RW, EPI, ROPE, 1, VAR ? kShortBatch / RW : gemm_batch(RW, true), false, 0, true, VAR != 1>(a, (int)blockIdx.x, smem);
 }
 
 // Output projection whose input is still in key-split attention partials (merged while staging).
-template <int DT, int SPLITS>
+template <int DT, int SPLITS, bool SHORT = false>
 __global__ __launch_bounds__(512) void gemm_merge_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    gemm_body<DT, 1, EPI_RESID, 0, 1, gemm_batch(1, false), false, SPLITS>(a, (int)blockIdx.x, smem);
+    gemm_body<DT, 1, EPI_RESID, 0, 1, gemm_batch(1, false), false, SPLITS, false, !SHORT>(a, (int)blockIdx.x, smem);
 }
 
 // More than kMaxRows rows (encoder, prompt prefill): blockIdx.y picks a block of kMaxRows rows and the same
@@ -920,6 +934,15 @@ static hipError_t raise_lds_limits() {
     (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0>, (const void*)gemm_row_kernel<DTV, 2, EPI_ACT, 0>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0>, (const void*)gemm_row_kernel<DTV, 4, EPI_LMHEAD, 0>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_STORE, 0, 1>, (const void*)gemm_row_kernel<DTV, 1, EPI_RESID, 0, 1>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0, 1>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1, 1>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0, 1>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_STORE, 0, 2>, (const void*)gemm_row_kernel<DTV, 1, EPI_RESID, 0, 2>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0, 2>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1, 2>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0, 2>, \
+    (const void*)gemm_kernel<DTV, 1, EPI_STORE, 0, 1, true>, (const void*)gemm_kernel<DTV, 1, EPI_RESID, 0, 1, true>, \
+    (const void*)gemm_kernel<DTV, 1, EPI_QKV, 0, 1, true>, (const void*)gemm_kernel<DTV, 1, EPI_QKV, 1, 1, true>, \
+    (const void*)gemm_kernel<DTV, 1, EPI_ACT, 0, 1, true>, \
     (const void*)gemm_kernel<DTV, 4, EPI_LMHEAD, 0, 1>, \
     (const void*)gemm_rows_kernel<DTV, 1, EPI_STORE, 0>, (const void*)gemm_rows_kernel<DTV, 1, EPI_RESID, 0>, \
     (const void*)gemm_rows_kernel<DTV, 1, EPI_QKV, 0>, (const void*)gemm_rows_kernel<DTV, 1, EPI_QKV, 1>, \
@@ -928,6 +951,9 @@ static hipError_t raise_lds_limits() {
                              (const void*)gemm_merge_kernel<0, 2>, (const void*)gemm_merge_kernel<0, 4>,
                              (const void*)gemm_merge_kernel<0, 8>, (const void*)gemm_merge_kernel<1, 2>,
                              (const void*)gemm_merge_kernel<1, 4>, (const void*)gemm_merge_kernel<1, 8>,
+                             (const void*)gemm_merge_kernel<0, 2, true>, (const void*)gemm_merge_kernel<0, 4, true>,
+                             (const void*)gemm_merge_kernel<0, 8, true>, (const void*)gemm_merge_kernel<1, 2, true>,
+                             (const void*)gemm_merge_kernel<1, 4, true>, (const void*)gemm_merge_kernel<1, 8, true>,
                              (const void*)attn_rows_kernel<0, 1>, (const void*)attn_rows_kernel<0, 2>,
                              (const void*)attn_rows_kernel<0, 4>, (const void*)attn_rows_kernel<1, 1>,
                              (const void*)attn_rows_kernel<1, 2>, (const void*)attn_rows_kernel<1, 4>,
@@ -980,25 +1006,37 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
             npairs > 64 * a.nwv || (size_t)npairs * sp * 4 > (size_t)gemm_red_bytes(a.nwv, 1))
             return hipErrorInvalidValue;
         const dim3 grid1((unsigned)gemm_num_blocks(a)), block1(64 * a.nwv);
-#define BILD_MG(DTV)                                                                           \
+#define BILD_MG(DTV, SH)                                                                       \
     do {                                                                                        \
-        if (sp == 2) hipLaunchKernelGGL((gemm_merge_kernel<DTV, 2>), grid1, block1, smem, st, a); \
-        else if (sp == 4) hipLaunchKernelGGL((gemm_merge_kernel<DTV, 4>), grid1, block1, smem, st, a); \
-        else hipLaunchKernelGGL((gemm_merge_kernel<DTV, 8>), grid1, block1, smem, st, a);       \
+        if (sp == 2) hipLaunchKernelGGL((gemm_merge_kernel<DTV, 2, SH>), grid1, block1, smem, st, a); \
+        else if (sp == 4) hipLaunchKernelGGL((gemm_merge_kernel<DTV, 4, SH>), grid1, block1, smem, st, a); \
+        else hipLaunchKernelGGL((gemm_merge_kernel<DTV, 8, SH>), grid1, block1, smem, st, a);   \
     } while (0)
-        if (dtype) BILD_MG(1); else BILD_MG(0);
+        // (one batch of tiles per wave at most: no second weight buffer, see gemm_row_kernel)
+        const bool sh = a.W.k <= a.kc && (a.W.tk + a.wk - 1) / a.wk <= gemm_batch(1, false);
+        if (dtype) { if (sh) BILD_MG(1, true); else BILD_MG(1, false); }
+        else { if (sh) BILD_MG(0, true); else BILD_MG(0, false); }
 #undef BILD_MG
         return hipGetLastError();
     }
     const dim3 grid((unsigned)gemm_num_blocks(a), row_blocks), block(64 * a.nwv);
+    // tiles the busiest wave has: picks the batch geometry (see gemm_row_kernel)
+    const bool one_chunk = a.W.k <= a.kc;
+    const int per_wave = (a.W.tk + a.wk - 1) / a.wk;
 #define BILD_L(DTV, RWV, EPIV, ROPEV)                                                              \
     do {                                                                                            \
         if (row_blocks > 1)                                                                         \
             hipLaunchKernelGGL((gemm_rows_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a); \
+        else if (a.T == 1 && RWV == 1 && one_chunk && per_wave <= kShortBatch)                      \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 1>), grid, block, smem, st, a); \
+        else if (a.T == 1 && RWV == 1 && one_chunk && per_wave <= 2 * kShortBatch)                  \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 2>), grid, block, smem, st, a); \
         else if (a.T == 1)                                                                          \
             hipLaunchKernelGGL((gemm_row_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a); \
         else if (a.T > 16)                                                                          \
             hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 2>), grid, block, smem, st, a);  \
+        else if (RWV == 1 && one_chunk && per_wave <= gemm_batch(1, false))                         \
+            hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPIV, ROPEV, 1, true>), grid, block, smem, st, a); \
         else                                                                                        \
             hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 1>), grid, block, smem, st, a);  \
     } while (0)
