@@ -206,7 +206,7 @@ __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
 // The argument block may live in the kernel-argument segment or (persistent kernel) in constant-address-space
 // device memory, hence the template parameter A.
 template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, false, NT), bool COH = false, int MG = 0,
-          bool ONE = false, bool TWO = true, class A>
+          bool ONE = false, bool TWO = true, int TCAP = 0, class A>
 __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* smem) {
     constexpr int KT = DT ? 32 : 16;
     // the wave index through readfirstlane: the compiler then knows that it - and every tile index, weight address and
@@ -496,6 +496,8 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                 pieces(std::integral_constant<int, 2>{}, std::true_type{}, tid, hook);
             } else if (total <= 4 * nthr) {
                 pieces(std::integral_constant<int, 4>{}, std::true_type{}, tid, hook);
+            } else if (TCAP > 0) {
+                // (the few-rows kernel: the launcher guarantees four pieces per thread at most)
             } else if (NT == 1 && total <= 6 * nthr) {  // (above 16 rows the second accumulator set needs the registers)
                 pieces(std::integral_constant<int, 6>{}, std::true_type{}, tid, hook);
             } else if (NT == 1 && total <= 8 * nthr) {
@@ -589,7 +591,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                 if (kt + 3 * S < nkt0) request(B1, kt + 3 * S, nkt0);
             }
         }
-    } else {
+    } else if (TCAP == 0) {  // (the few-rows kernel is launched on single-chunk inputs only)
         request(B0, wkid, nkt0);
         for (int k0 = 0; k0 < K; k0 += KC) {
             const int kc_len = min(KC, K - k0);
@@ -804,6 +806,16 @@ __global__ __launch_bounds__(512) void gemm_row_kernel(const GemmArgs a) {
     gemm_body<DT, RW, EPI, ROPE, 1, VAR ? kShortBatch / RW : gemm_batch(RW, true), false, 0, true, VAR != 1>(a, (int)blockIdx.x, smem);
 }
 
+// Two to four rows (the bulk of the large model's review passes) on a single-chunk input: the same body without the
+// staging rounds for more rows and without the multi-chunk loop.  Run through the general kernel a pass of these row
+// counts costs about 0.7 us more per projection (measured: one row through gemm_kernel 1018 us per T5-large pass,
+// through gemm_row_kernel 911 us), which is code size and register pressure, not work.
+template <int DT, int RW, int EPI, int ROPE, bool SHORT>
+__global__ __launch_bounds__(512) void gemm_few_kernel(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    gemm_body<DT, RW, EPI, ROPE, 1, gemm_batch(RW, false, 1), false, 0, false, !SHORT, 4>(a, (int)blockIdx.x, smem);
+}
+
 // Output projection whose input is still in key-split attention partials (merged while staging).
 template <int DT, int SPLITS, bool SHORT = false>
 __global__ __launch_bounds__(512) void gemm_merge_kernel(const GemmArgs a) {
@@ -940,6 +952,12 @@ static hipError_t raise_lds_limits() {
     (const void*)gemm_row_kernel<DTV, 1, EPI_STORE, 0, 2>, (const void*)gemm_row_kernel<DTV, 1, EPI_RESID, 0, 2>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0, 2>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1, 2>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0, 2>, \
+    (const void*)gemm_few_kernel<DTV, 1, EPI_STORE, 0, true>, (const void*)gemm_few_kernel<DTV, 1, EPI_RESID, 0, true>, \
+    (const void*)gemm_few_kernel<DTV, 1, EPI_QKV, 0, true>, (const void*)gemm_few_kernel<DTV, 1, EPI_QKV, 1, true>, \
+    (const void*)gemm_few_kernel<DTV, 1, EPI_ACT, 0, true>, \
+    (const void*)gemm_few_kernel<DTV, 1, EPI_STORE, 0, false>, (const void*)gemm_few_kernel<DTV, 1, EPI_RESID, 0, false>, \
+    (const void*)gemm_few_kernel<DTV, 1, EPI_QKV, 0, false>, (const void*)gemm_few_kernel<DTV, 1, EPI_QKV, 1, false>, \
+    (const void*)gemm_few_kernel<DTV, 1, EPI_ACT, 0, false>, \
     (const void*)gemm_kernel<DTV, 1, EPI_STORE, 0, 1, true>, (const void*)gemm_kernel<DTV, 1, EPI_RESID, 0, 1, true>, \
     (const void*)gemm_kernel<DTV, 1, EPI_QKV, 0, 1, true>, (const void*)gemm_kernel<DTV, 1, EPI_QKV, 1, 1, true>, \
     (const void*)gemm_kernel<DTV, 1, EPI_ACT, 0, 1, true>, \
@@ -1023,6 +1041,9 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     // tiles the busiest wave has: picks the batch geometry (see gemm_row_kernel)
     const bool one_chunk = a.W.k <= a.kc;
     const int per_wave = (a.W.tk + a.wk - 1) / a.wk;
+    // two to four rows, one chunk, and either ragged rows (dealt row by row) or at most four staged pieces per thread
+    const int n4 = a.W.k / 4;
+    const bool few_ok = a.T >= 2 && a.T <= 4 && one_chunk && ((n4 & 63) != 0 || a.T * n4 <= 4 * 64 * a.nwv);
 #define BILD_L(DTV, RWV, EPIV, ROPEV)                                                              \
     do {                                                                                            \
         if (row_blocks > 1)                                                                         \
@@ -1035,6 +1056,10 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
             hipLaunchKernelGGL((gemm_row_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a); \
         else if (a.T > 16)                                                                          \
             hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 2>), grid, block, smem, st, a);  \
+        else if (RWV == 1 && few_ok && per_wave <= gemm_batch(1, false))                            \
+            hipLaunchKernelGGL((gemm_few_kernel<DTV, 1, EPIV, ROPEV, true>), grid, block, smem, st, a); \
+        else if (RWV == 1 && few_ok)                                                                \
+            hipLaunchKernelGGL((gemm_few_kernel<DTV, 1, EPIV, ROPEV, false>), grid, block, smem, st, a); \
         else if (RWV == 1 && one_chunk && per_wave <= gemm_batch(1, false))                         \
             hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPIV, ROPEV, 1, true>), grid, block, smem, st, a); \
         else                                                                                        \
