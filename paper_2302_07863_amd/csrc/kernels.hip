@@ -190,9 +190,10 @@ __device__ __forceinline__ void st_u16(uint16_t* p, uint16_t v) {
 //   zblk               64 bytes of zeros
 // =====================================================================================
 // weight tiles a wave loads per batch (split over its RW feature tiles); two batches are in flight
-// (12 in the single-row kernel; 8 with several rows, whose staging needs the registers; 6 above 16 rows, where the
-// second set of row tiles needs more)
-__host__ __device__ constexpr int gemm_batch(int rw, bool one_row, int nt = 1) { return (one_row ? 12 : (nt > 1 ? 6 : 8)) / rw; }
+// (12 in the single-row kernel; 8 with several rows, whose staging needs the registers; 4 above 16 rows, where the
+// second set of row tiles needs more and the per-wave tile counts of the row-block launches - 4, 8, 16, 32 - then
+// split into whole batches; see gemm_row_kernel on what padding slots cost)
+__host__ __device__ constexpr int gemm_batch(int rw, bool one_row, int nt = 1) { return (one_row ? 12 : (nt > 1 ? 4 : 8)) / rw; }
 
 __host__ __device__ inline int xs_row_stride(int dt, int kc) { return dt ? (kc + 8) * 2 : (kc + 4) * 4; }
 __host__ __device__ inline int xs_bytes(int dt, int kc, int T) { return T * xs_row_stride(dt, kc) * (dt ? 2 : 1); }
@@ -946,6 +947,7 @@ static hipError_t raise_lds_limits() {
     (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0>, (const void*)gemm_row_kernel<DTV, 2, EPI_ACT, 0>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0>, (const void*)gemm_row_kernel<DTV, 4, EPI_LMHEAD, 0>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0, 2>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_STORE, 0, 1>, (const void*)gemm_row_kernel<DTV, 1, EPI_RESID, 0, 1>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0, 1>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1, 1>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0, 1>, \
@@ -1050,7 +1052,7 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
             hipLaunchKernelGGL((gemm_rows_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a); \
         else if (a.T == 1 && RWV == 1 && one_chunk && per_wave <= kShortBatch)                      \
             hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 1>), grid, block, smem, st, a); \
-        else if (a.T == 1 && RWV == 1 && one_chunk && per_wave <= 2 * kShortBatch)                  \
+        else if (a.T == 1 && RWV == 1 && one_chunk && (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))) \
             hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 2>), grid, block, smem, st, a); \
         else if (a.T == 1)                                                                          \
             hipLaunchKernelGGL((gemm_row_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a); \
@@ -1082,6 +1084,8 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
                 hipLaunchKernelGGL((gemm_kernel<DTV, 4, EPI_LMHEAD, 0, 1>), grid, block, smem, st, a); \
             else if (a.rw != 1)                                                  \
                 return hipErrorInvalidValue;                                     \
+            else if (a.T == 1 && one_chunk && per_wave <= 32 && per_wave % kShortBatch == 0) /* batches of 8 fit exactly */ \
+                hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0, 2>), grid, block, smem, st, a); \
             else if (a.T == 1)                                                   \
                 hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0>), grid, block, smem, st, a); \
             else if (a.T > 16)                                                   \
