@@ -396,7 +396,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             // worked out once per (row, head) - one pair per thread - and handed over in LDS (the reduction area is
             // free until the MFMAs are done); a piece then costs MG loads and MG multiply-adds.
             constexpr int SP = MG > 0 ? MG : 1;  // (1 only where this branch is dead code)
-            constexpr int P = SP == 8 ? 2 : 4;  // pieces per round: P * SP float4 loads in flight per thread
+            constexpr int PMAX = SP == 8 ? 2 : 4;  // pieces per round at most: P * SP float4 loads in flight per thread
             const int total = T * n4;
             const unsigned magic = 0xFFFFFFFFu / (unsigned)n4 + 1u;
             const int npairs = T * a.mg_heads;  // at most the thread count (checked at launch)
@@ -409,7 +409,8 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                 m[sp] = ld_act<COH>(a.mg_ml + sp * ml_stride + (size_t)pr * 2);
                 l[sp] = ld_act<COH>(a.mg_ml + sp * ml_stride + (size_t)pr * 2 + 1);
             }
-            auto round = [&](auto first, int eb, auto&& hk) {
+            auto round = [&](auto np, auto first, int eb, auto&& hk) {
+                constexpr int P = decltype(np)::value;
                 float4 o[P][SP];
                 int tt[P], kk[P];
 #pragma unroll
@@ -452,8 +453,18 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                     put(tt[u], kk[u], r, r);
                 }
             };
-            round(std::true_type{}, tid, hook);
-            for (int eb = tid + P * nthr; eb < total; eb += P * nthr) round(std::false_type{}, eb, noop);
+            // the first round takes as many pieces as the rows need (a padding piece costs SP loads and a conversion)
+            if (total <= nthr) {
+                round(std::integral_constant<int, 1>{}, std::true_type{}, tid, hook);
+            } else if (total <= 2 * nthr || PMAX == 2) {
+                round(std::integral_constant<int, 2>{}, std::true_type{}, tid, hook);
+                for (int eb = tid + 2 * nthr; eb < total; eb += 2 * nthr)
+                    round(std::integral_constant<int, 2>{}, std::false_type{}, eb, noop);
+            } else {
+                round(std::integral_constant<int, PMAX>{}, std::true_type{}, tid, hook);
+                for (int eb = tid + PMAX * nthr; eb < total; eb += PMAX * nthr)
+                    round(std::integral_constant<int, PMAX>{}, std::false_type{}, eb, noop);
+            }
         } else if (T > 1 && (n4 & 63) == 0) {
             // Several rows whose chunk is a whole number of wavefront-wide pieces: the rows are laid end to
             // end and dealt to all threads, which spreads the conversion work evenly and lets one round of
@@ -495,6 +506,8 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             // rounds skip what they do not need.
             if (total <= 2 * nthr) {
                 pieces(std::integral_constant<int, 2>{}, std::true_type{}, tid, hook);
+            } else if (TCAP > 0 && total <= 3 * nthr) {  // (only in the few-rows kernel: every variant here costs the others)
+                pieces(std::integral_constant<int, 3>{}, std::true_type{}, tid, hook);
             } else if (total <= 4 * nthr) {
                 pieces(std::integral_constant<int, 4>{}, std::true_type{}, tid, hook);
             } else if (TCAP > 0) {
@@ -517,7 +530,14 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                 const int t = min(traw, T - 1);
                 const int start = few ? tid : lane, step = few ? nthr : 64;
                 float ssj = 0.f;
-                if (n4 <= 2 * step) {  // short rows: at most two elements per thread
+                if (n4 <= step) {  // at most one element per thread (a padding second one would cost a load and a conversion)
+                    const int ca = min(start, n4 - 1);
+                    const float4 va = ldx(t, ca), ga = ldg(ca);
+                    hk(true);
+                    __builtin_amdgcn_sched_barrier(0);  // (as above)
+                    const float sa = put(t, ca, va, ga);
+                    ssj += (act && start < n4) ? sa : 0.f;
+                } else if (n4 <= 2 * step) {  // short rows: at most two elements per thread
                     const int ka = start, kb2 = start + step;
                     const int ca = min(ka, n4 - 1), cb = min(kb2, n4 - 1);
                     const float4 va = ldx(t, ca), ga = ldg(ca), vb = ldx(t, cb), gb = ldg(cb);
