@@ -181,7 +181,7 @@ def main() -> int:
             if line.startswith("traffic_bytes_per_launch="):
                 traffic = int(line.split("=")[1])
     # one device function behind three thin launch wrappers (any rows / one row / merging attention partials)
-    roofline = dict(bound="hbm", kernel="bild::gemm_kernel, gemm_row_kernel, gemm_merge_kernel (one body, %s)" %
+    roofline = dict(bound="hbm", kernel="bild::gemm_kernel, gemm_row_kernel, gemm_few_kernel, gemm_merge_kernel (one body, %s)" %
                     ("bf16" if cfg.large.dtype == bi.DT_BF16 else "f32"),
                     achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
                     traffic=traffic, launches_per_step=tot_l, mean_launch_us=round(tot_ms / tot_l * 1e3, 3),

@@ -17,10 +17,10 @@ import sys
 PROBE_BYTES = 1 << 30
 
 
-# The decode GEMM is one device function behind three launch wrappers (any row count, exactly one row,
-# input still in key-split attention partials); they are summed under one name.  The encoder / prefill
+# The decode GEMM is one device function behind four launch wrappers (any row count, exactly one row, two to
+# four rows, input still in key-split attention partials); they are summed under one name.  The encoder / prefill
 # wrapper (row blocks, bild::gemm_rows_kernel) works in another regime and stays separate.
-_DECODE_GEMM = ("bild::gemm_kernel", "bild::gemm_row_kernel", "bild::gemm_merge_kernel")
+_DECODE_GEMM = ("bild::gemm_kernel", "bild::gemm_row_kernel", "bild::gemm_few_kernel", "bild::gemm_merge_kernel")
 
 
 def _group(name: str) -> str:
