@@ -1747,6 +1747,10 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthr = blockDim.x, nwv = nthr >> 6;
     Ctl* c = a.ctl;
+    // the control words the policy needs, requested now (nothing in this kernel writes them before they are used): their
+    // trip from memory overlaps with the partials' instead of following it
+    const int c_ylen = c->y_len, c_ds = c->draft_start, c_nmax = c->n_max, c_len0 = c->len[0], c_lenw = c->len[a.which];
+    const float c_afb = c->alpha_fb, c_arb = c->alpha_rb;
     if (a.mode != 3) {
         // rows are dealt to the waves; a wave's lanes share the partials of its row (eight loads in flight
         // per lane), so the rows of a review merge side by side and a single row costs one round trip
@@ -1777,17 +1781,17 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
     if (SAMPLE && a.top_p > 0.f && a.mode <= 2) {
         int* sel = (int*)(lds + kFinishLds);  // [0] row, [1] position
         if (tid == 0) {
-            int row = a.T - 1, pos = c->y_len;
+            int row = a.T - 1, pos = c_ylen;
             if (a.mode == 1) {
                 const int n = a.T - 1;
-                const float alpha = c->alpha_rb;
+                const float alpha = c_arb;
                 row = n;
                 for (int i = 0; i < n; ++i)
                     if ((rm[i] + logf(rsum[i])) - a.zt[a.row_off + i] > alpha) {
                         row = i;
                         break;
                     }
-                pos = c->draft_start + row;
+                pos = c_ds + row;
             }
             sel[0] = row;
             sel[1] = pos;
@@ -1799,18 +1803,18 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
     }
     if (tid == 0) {
         const int w = a.which;
-        const int y_len = c->y_len, ds = c->draft_start, n_max = c->n_max;
+        const int y_len = c_ylen, ds = c_ds, n_max = c_nmax;
         if (a.mode == 3) {
-            c->len[w] += a.rows_consumed;
+            c->len[w] = c_lenw + a.rows_consumed;
         } else {
             for (int t = 0; t < a.T; ++t) c->res_rowtok[t] = ridx[t];
             if (a.mode == 0 || a.mode == 2) {
                 const int tok = drawn >= 0 ? drawn : ridx[a.T - 1];
                 const float pmax = 1.f / rsum[a.T - 1];
-                const bool low = (a.mode == 0) && (pmax < c->alpha_fb);
+                const bool low = (a.mode == 0) && (pmax < c_afb);
                 const bool forced = (a.mode == 0) && n_max > 0 && (y_len - ds) >= n_max;
                 const bool fb = low || forced;
-                c->len[w] += a.rows_consumed;
+                c->len[w] = c_lenw + a.rows_consumed;
                 if (!fb && y_len < a.y_cap) {
                     a.y[y_len] = tok;
                     c->y_len = y_len + 1;
@@ -1821,7 +1825,7 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
                 c->res_pmax = pmax;
             } else if (a.mode == 1) {  // review of n = T - 1 drafts
                 const int n = a.T - 1;
-                const float alpha = c->alpha_rb;
+                const float alpha = c_arb;
                 int r = n;
                 for (int i = 0; i < n; ++i) {
                     const float nll = (rm[i] + logf(rsum[i])) - a.zt[a.row_off + i];
@@ -1832,7 +1836,7 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
                 a.y[ds + r] = tok;
                 c->y_len = ds + r + 1;
                 c->len[1] = ds + r;
-                c->len[0] = min(c->len[0], ds + r);
+                c->len[0] = min(c_len0, ds + r);
                 c->draft_start = ds + r + 1;
                 c->res_r = r;
                 c->res_n = n;
