@@ -974,6 +974,7 @@ static hipError_t raise_lds_limits() {
     (const void*)gemm_row_kernel<DTV, 1, EPI_STORE, 0, 2>, (const void*)gemm_row_kernel<DTV, 1, EPI_RESID, 0, 2>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0, 2>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1, 2>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0, 2>, \
+    (const void*)gemm_row_kernel<DTV, 2, EPI_ACT, 0, 1>, (const void*)gemm_row_kernel<DTV, 2, EPI_ACT, 0, 2>, \
     (const void*)gemm_few_kernel<DTV, 1, EPI_STORE, 0, true>, (const void*)gemm_few_kernel<DTV, 1, EPI_RESID, 0, true>, \
     (const void*)gemm_few_kernel<DTV, 1, EPI_QKV, 0, true>, (const void*)gemm_few_kernel<DTV, 1, EPI_QKV, 1, true>, \
     (const void*)gemm_few_kernel<DTV, 1, EPI_ACT, 0, true>, \
@@ -1070,6 +1071,10 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     do {                                                                                            \
         if (row_blocks > 1)                                                                         \
             hipLaunchKernelGGL((gemm_rows_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a); \
+        else if (a.T == 1 && RWV == 2 && one_chunk && per_wave <= kShortBatch / 2)                  \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 1>), grid, block, smem, st, a); \
+        else if (a.T == 1 && RWV == 2 && one_chunk && (per_wave <= kShortBatch || (per_wave % 4 == 0 && per_wave % 6 != 0))) \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 2>), grid, block, smem, st, a); \
         else if (a.T == 1 && RWV == 1 && one_chunk && per_wave <= kShortBatch)                      \
             hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 1>), grid, block, smem, st, a); \
         else if (a.T == 1 && RWV == 1 && one_chunk && (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))) \
