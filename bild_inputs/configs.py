@@ -14,7 +14,7 @@ from dataclasses import dataclass, field, replace
 from typing import Optional
 
 ACT_RELU, ACT_GATED_GELU, ACT_SWIGLU = 0, 1, 2
-POS_SINUSOIDAL, POS_ROPE = 0, 1
+POS_SINUSOIDAL, POS_ROPE, POS_RELATIVE = 0, 1, 2
 DT_F32, DT_BF16 = 0, 1
 
 
@@ -39,6 +39,8 @@ class ModelShape:
     rope_base: float = 10000.0
     bos: int = 0
     tie_shift: int = 0  # input embedding of token t is row (t + tie_shift) mod vocab of the embedding matrix
+    rel_max_dist: int = 0   # POS_RELATIVE: key-query distances are clamped to [-rel_max_dist, rel_max_dist]
+    rel_buckets: int = 0    # POS_RELATIVE: distinct values per head in a synthetic bias table (log-spaced ties)
 
     @property
     def inner(self) -> int:
@@ -109,11 +111,12 @@ class PairConfig:
     alpha_rb_sweep: tuple = ()
 
 
-def _t5(name, n_layers, d, heads, d_ff, act, vocab, tied, dtype, logit_scale, embed_scale):
+def _t5(name, n_layers, d, heads, d_ff, act, vocab, tied, dtype, logit_scale, embed_scale, relative=False):
     return ModelShape(name=name, n_enc=n_layers, n_dec=n_layers, d=d, heads=heads, d_head=64,
-                      d_ff=d_ff, act=act, pos=POS_SINUSOIDAL, vocab=vocab, tied=tied, dtype=dtype,
-                      cross=True, logit_scale=logit_scale, embed_scale=embed_scale,
-                      tie_shift=7919 if tied else 0)
+                      d_ff=d_ff, act=act, pos=POS_RELATIVE if relative else POS_SINUSOIDAL, vocab=vocab, tied=tied,
+                      dtype=dtype, cross=True, logit_scale=logit_scale, embed_scale=embed_scale,
+                      tie_shift=7919 if tied else 0, rel_max_dist=128 if relative else 0,
+                      rel_buckets=32 if relative else 0)
 
 
 def tiny_pair() -> PairConfig:
@@ -136,6 +139,16 @@ def t5_pair() -> PairConfig:
     large = _t5("t5-large", 24, 1024, 16, 4096, ACT_RELU, 32128, True, DT_BF16, ls_l, es)
     return PairConfig("t5", small, large, n_src=512, max_new=64, alpha_fb=0.5, alpha_rb=2.0,
                       alpha_fb_sweep=(0.3, 0.5, 0.7), alpha_rb_sweep=(1.0, 2.0, 4.0))
+
+
+def t5_relative_pair() -> PairConfig:
+    """Config 2's shapes with the position scheme of the T5 family: no position added to the embedding, a
+    learned bias on the self-attention scores indexed by the clamped key-query distance (128), 32 log-spaced
+    distinct values per head.  Thresholds are config 2's; the small model's logit scale is calibrated separately."""
+    ls_s, ls_l, es = CAL["t5rel"]
+    small = _t5("t5-small-rel", 6, 512, 8, 2048, ACT_RELU, 32128, True, DT_BF16, ls_s, es, relative=True)
+    large = _t5("t5-large-rel", 24, 1024, 16, 4096, ACT_RELU, 32128, True, DT_BF16, ls_l, es, relative=True)
+    return PairConfig("t5rel", small, large, n_src=512, max_new=64, alpha_fb=0.5, alpha_rb=2.0)
 
 
 def t5_early_exit_pair() -> PairConfig:
@@ -173,7 +186,7 @@ def llama_pair() -> PairConfig:
 def toy_pair(dtype=DT_F32, act=ACT_RELU, pos=POS_SINUSOIDAL, cross=True, tied=True,
              d=64, heads=2, d_head=16, d_ff=96, vocab=200, n_small=1, n_large=3,
              truncate=False, logit_scale=16.0, embed_scale=14.0, gain_jitter=0.1,
-             n_src=9, max_new=24, tie_shift=37) -> PairConfig:
+             n_src=9, max_new=24, tie_shift=37, rel_max_dist=5, rel_buckets=6) -> PairConfig:
     """Unit-test pair, small enough for the no-cache oracle and for brute
     force.  Norm gains are jittered so that a dropped gain shows up, widths are
     deliberately not powers of two and `heads*d_head != d`."""
@@ -181,7 +194,9 @@ def toy_pair(dtype=DT_F32, act=ACT_RELU, pos=POS_SINUSOIDAL, cross=True, tied=Tr
     mul = 2 if truncate else 1          # a truncated pair: the large model is twice as wide as the small one
     large = ModelShape("toy-large", n_enc=n_enc, n_dec=n_large, d=d * mul, heads=heads * mul, d_head=d_head,
                        d_ff=d_ff * mul, act=act, pos=pos, vocab=vocab, tied=tied, dtype=dtype, cross=cross,
-                       logit_scale=logit_scale, embed_scale=embed_scale, tie_shift=tie_shift if tied else 0)
+                       logit_scale=logit_scale, embed_scale=embed_scale, tie_shift=tie_shift if tied else 0,
+                       rel_max_dist=rel_max_dist if pos == POS_RELATIVE else 0,
+                       rel_buckets=rel_buckets if pos == POS_RELATIVE else 0)
     if truncate:
         small = replace(large, name="toy-small", n_enc=min(1, n_enc), n_dec=n_small, d=d, heads=heads, d_ff=d_ff)
     else:
@@ -203,6 +218,8 @@ CAL = {
     "mt5": (2.0, 4.0, 36.0),
     "llama": (0.9, 4.0, 50.0),
     "t5ee": (1.65, 4.0, 36.0),
+    "t5rel": (1.63, 4.0, 36.0),
 }
 
-PAIRS = {"tiny": tiny_pair, "t5": t5_pair, "mt5": mt5_pair, "llama": llama_pair, "t5ee": t5_early_exit_pair}
+PAIRS = {"tiny": tiny_pair, "t5": t5_pair, "mt5": mt5_pair, "llama": llama_pair, "t5ee": t5_early_exit_pair,
+         "t5rel": t5_relative_pair}

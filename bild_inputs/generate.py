@@ -8,6 +8,8 @@ bf16-representable values, and sliced.  Every tensor is an fp32 numpy array in
 
 Tensor names (l = layer index):
   emb, head (absent when tied), enc_final_norm, dec_final_norm
+  enc_rel_bias, dec_rel_bias (relative-position models only): [heads][2*rel_max_dist + 1] fp32, entry
+  [h][r + rel_max_dist] is the score bias of head h for a key r positions after the query
   enc.l.{ln1,wq,wk,wv,wo,ln2,w_in,w_up,w_out}
   dec.l.{ln1,wq,wk,wv,wo,lnc,cwq,cwk,cwv,cwo,ln2,w_in,w_up,w_out}
 `w_in` is the gate projection of a gated FFN and `w_up` its linear branch
@@ -17,7 +19,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from .configs import DT_BF16, ModelShape, PairConfig
+from .configs import DT_BF16, POS_RELATIVE, ModelShape, PairConfig
 
 
 def to_bf16_values(a: np.ndarray) -> np.ndarray:
@@ -37,6 +39,10 @@ def tensor_names(m: ModelShape) -> list[str]:
     if m.n_enc:
         names.append("enc_final_norm")
     names.append("dec_final_norm")
+    if m.pos == POS_RELATIVE:
+        if m.n_enc:
+            names.append("enc_rel_bias")
+        names.append("dec_rel_bias")
     for l in range(m.n_enc):
         names += [f"enc.{l}.{k}" for k in ("ln1", "wq", "wk", "wv", "wo", "ln2", "w_in")]
         if m.gated:
@@ -58,6 +64,8 @@ def tensor_shape(m: ModelShape, name: str) -> tuple:
     d, i, f, v = m.d, m.inner, m.d_ff, m.vocab
     if leaf in ("emb", "head"):
         return (v, d)
+    if leaf in ("enc_rel_bias", "dec_rel_bias"):
+        return (m.heads, 2 * m.rel_max_dist + 1)
     if leaf in ("enc_final_norm", "dec_final_norm", "ln1", "ln2", "lnc"):
         return (d,)
     if leaf in ("wq", "wk", "wv", "cwq", "cwk", "cwv"):
@@ -84,6 +92,30 @@ def _stable_id(name: str) -> int:
     return h & 0x7FFFFFFF
 
 
+def distance_ties(max_dist: int, buckets: int, two_sided: bool) -> np.ndarray:
+    """Which entries of a synthetic relative-position table share a value: for every signed distance
+    r in [-max_dist, max_dist] the index of the drawn value it takes.  The tie pattern is the T5 family's
+    log-spaced one: with `half` = buckets (one-sided tables) or buckets/2 (two-sided: the second half serves
+    r > 0), distances |r| < half/2 have a value of their own and larger ones share a value over ranges whose
+    ends grow geometrically up to max_dist.  Integer arithmetic only, so the pattern is exact."""
+    half = buckets // 2 if two_sided else buckets
+    exact = max(1, half // 2)
+    steps = half - exact
+    out = np.zeros(2 * max_dist + 1, dtype=np.int64)
+    for r in range(-max_dist, max_dist + 1):
+        n = abs(r) if two_sided else max(-r, 0)
+        if n < exact:
+            b = n
+        else:
+            # largest j with (n/exact)^steps >= (max_dist/exact)^j
+            j = 0
+            while j < steps and n ** steps * exact ** (j + 1) >= exact ** steps * max_dist ** (j + 1):
+                j += 1
+            b = min(half - 1, exact + j)
+        out[r + max_dist] = b + (half if two_sided and r > 0 else 0)
+    return out
+
+
 def make_weights(m: ModelShape, seed: int, std: float = 0.02, gain_jitter: float = 0.0) -> dict:
     """N(0, std) matrices (bf16-representable when the model stores bf16) and
     norm gains 1 + gain_jitter*N(0,1), each from its own Philox stream."""
@@ -91,7 +123,11 @@ def make_weights(m: ModelShape, seed: int, std: float = 0.02, gain_jitter: float
     for name in tensor_names(m):
         rng = np.random.Generator(np.random.Philox(np.random.SeedSequence([seed, _stable_id(name)])))
         shape = tensor_shape(m, name)
-        if _is_gain(name):
+        if name in ("enc_rel_bias", "dec_rel_bias"):
+            # N(0, 1) values: score biases of the size of the scores themselves (not rounded: the table stays fp32)
+            drawn = rng.standard_normal((m.heads, m.rel_buckets), dtype=np.float32)
+            out[name] = np.ascontiguousarray(drawn[:, distance_ties(m.rel_max_dist, m.rel_buckets, name == "enc_rel_bias")])
+        elif _is_gain(name):
             g = np.ones(shape, dtype=np.float32)
             if gain_jitter:
                 g += (gain_jitter * rng.standard_normal(shape, dtype=np.float32)).astype(np.float32)
@@ -110,6 +146,7 @@ def truncate_weights(large: ModelShape, wl: dict, small: ModelShape) -> dict:
     assert small.d <= large.d and small.inner <= large.inner and small.d_ff <= large.d_ff
     assert small.n_dec <= large.n_dec and small.n_enc <= large.n_enc
     assert small.vocab == large.vocab and small.d_head == large.d_head
+    assert small.pos == large.pos and small.rel_max_dist == large.rel_max_dist and small.heads <= large.heads
     d, i, f = small.d, small.inner, small.d_ff
     out = {}
     for name in tensor_names(small):
@@ -117,6 +154,8 @@ def truncate_weights(large: ModelShape, wl: dict, small: ModelShape) -> dict:
         leaf = name.split(".")[-1]
         if leaf in ("emb", "head"):
             t = src[:, :d]
+        elif leaf in ("enc_rel_bias", "dec_rel_bias"):
+            t = src[:small.heads]
         elif _is_gain(name):
             t = src[:d]
         elif leaf in ("wq", "wk", "wv", "cwq", "cwk", "cwv"):

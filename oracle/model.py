@@ -23,6 +23,12 @@ Model contract (the paper fixes none of this; it is the benchmark's choice):
   attn     per head softmax(q k^T / sqrt(d_head)) v ; decoder self-attention is
            causal, encoder self-attention and cross-attention are not
   RoPE     on q and k, pairs (2i, 2i+1) rotated by position * base^(-2i/d_head)
+  relative no position enters the embedding; every self-attention score (encoder and
+           decoder, all layers of a stack sharing one table) gets
+           bias[head][clip(key position - query position, -D, D) + D] added before the
+           softmax, D = rel_max_dist.  Cross-attention has no bias.  (The position
+           scheme of the T5 family; its log-spaced buckets are a tie pattern inside
+           the table and need no arithmetic here.)
   ffn      relu(x W_in) W_out, or (act(x W_in) * (x W_up)) W_out with
            act = tanh-approximated GELU, or SiLU
   sublayer x <- x + f(norm(x)); decoder order self-attn, cross-attn, ffn
@@ -36,7 +42,7 @@ from __future__ import annotations
 import numpy as np
 
 ACT_RELU, ACT_GATED_GELU, ACT_SWIGLU = 0, 1, 2
-POS_SINUSOIDAL, POS_ROPE = 0, 1
+POS_SINUSOIDAL, POS_ROPE, POS_RELATIVE = 0, 1, 2
 DT_F32, DT_BF16 = 0, 1
 
 
@@ -82,14 +88,21 @@ def silu(u: np.ndarray) -> np.ndarray:
 
 
 def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, heads: int, d_head: int,
-              q_pos: np.ndarray | None) -> np.ndarray:
-    """q: [T, I], k, v: [P, I].  Row r may see key p iff q_pos is None (not
-    causal) or p <= q_pos[r].  Returns [T, I]."""
+              q_pos: np.ndarray | None, rel_bias: np.ndarray | None = None,
+              row_pos: np.ndarray | None = None) -> np.ndarray:
+    """q: [T, I], k, v: [P, I]; key p sits at position p.  Row r may see key p iff
+    q_pos is None (not causal) or p <= q_pos[r].  rel_bias [heads, 2D+1], if given,
+    adds rel_bias[h, clip(p - row_pos[r], -D, D) + D] to the score of (r, p).  Returns [T, I]."""
     t, p = q.shape[0], k.shape[0]
     out = np.empty((t, heads * d_head), dtype=np.float64)
+    if rel_bias is not None:
+        dmax = (rel_bias.shape[1] - 1) // 2
+        rel_idx = np.clip(np.arange(p)[None, :] - np.asarray(row_pos)[:, None], -dmax, dmax) + dmax
     for h in range(heads):
         sl = slice(h * d_head, (h + 1) * d_head)
         s = q[:, sl] @ k[:, sl].T / np.sqrt(float(d_head))
+        if rel_bias is not None:
+            s = s + np.asarray(rel_bias[h], dtype=np.float64)[rel_idx]
         if q_pos is not None:
             s = np.where(np.arange(p)[None, :] <= q_pos[:, None], s, -np.inf)
         s = s - s.max(axis=1, keepdims=True)
@@ -126,6 +139,9 @@ class Model:
             return rope(a, positions, self.s.heads, self.s.d_head, self.s.rope_base)
         return a
 
+    def _rel(self, name: str):
+        return self.w[name] if self.s.pos == POS_RELATIVE else None
+
     def ffn(self, pre: str, xn: np.ndarray) -> np.ndarray:
         u = xn @ self.w[pre + "w_in"]
         if self.s.act == ACT_RELU:
@@ -152,7 +168,7 @@ class Model:
             q = self._qk_pos(xn @ self.w[p + "wq"], pos)
             k = self._store(self._qk_pos(xn @ self.w[p + "wk"], pos))
             v = self._store(xn @ self.w[p + "wv"])
-            x = x + attention(q, k, v, s.heads, s.d_head, None) @ self.w[p + "wo"]
+            x = x + attention(q, k, v, s.heads, s.d_head, None, self._rel("enc_rel_bias"), pos) @ self.w[p + "wo"]
             x = x + self.ffn(p, rmsnorm(x, self.w[p + "ln2"], s.eps))
         return rmsnorm(x, self.w["enc_final_norm"], s.eps)
 
@@ -176,7 +192,7 @@ class Model:
             q = self._qk_pos(xn @ self.w[p + "wq"], pos)
             k = self._store(self._qk_pos(xn @ self.w[p + "wk"], pos))
             v = self._store(xn @ self.w[p + "wv"])
-            x = x + attention(q, k, v, s.heads, s.d_head, pos) @ self.w[p + "wo"]
+            x = x + attention(q, k, v, s.heads, s.d_head, pos, self._rel("dec_rel_bias"), pos) @ self.w[p + "wo"]
             if s.cross:
                 xn = rmsnorm(x, self.w[p + "lnc"], s.eps)
                 ck, cv = cross[l]
@@ -213,7 +229,7 @@ class DecoderCache:
             q = m._qk_pos(xn @ m.w[p + "wq"], pos)
             self.k[l][t0:t0 + t] = m._store(m._qk_pos(xn @ m.w[p + "wk"], pos))
             self.v[l][t0:t0 + t] = m._store(xn @ m.w[p + "wv"])
-            a = attention(q, self.k[l][:t0 + t], self.v[l][:t0 + t], s.heads, s.d_head, pos)
+            a = attention(q, self.k[l][:t0 + t], self.v[l][:t0 + t], s.heads, s.d_head, pos, m._rel("dec_rel_bias"), pos)
             x = x + a @ m.w[p + "wo"]
             if s.cross:
                 xn = rmsnorm(x, m.w[p + "lnc"], s.eps)

@@ -105,6 +105,98 @@ def test_attention_zero_query_is_prefix_mean():
         assert np.allclose(out[r], v[:r + 1].mean(axis=0))
 
 
+def _one_hot_table(heads, dmax, offsets):
+    """Bias table that is 0 at one signed distance per head and -1e9 elsewhere."""
+    t = np.full((heads, 2 * dmax + 1), -1e9)
+    for h, r in enumerate(offsets):
+        t[h, r + dmax] = 0.0
+    return t
+
+
+def test_relative_bias_selects_keys_by_signed_distance():
+    """Closed forms.  A table that admits a single distance turns attention into a shift of V: head 0
+    looks one key back, head 1 two keys ahead (not causal).  Rows whose admitted key does not exist see
+    every key at the same (huge negative) bias and q = 0, i.e. the plain mean."""
+    heads, dh, p, dmax = 2, 4, 9, 3
+    v = RNG.standard_normal((p, heads * dh))
+    k = RNG.standard_normal((p, heads * dh))
+    q = 0.3 * RNG.standard_normal((p, heads * dh))     # finite scores cannot compete with 1e9
+    pos = np.arange(p)
+    out = om.attention(q, k, v, heads, dh, None, _one_hot_table(heads, dmax, (-1, 2)), pos)
+    for r in range(1, p):
+        assert np.allclose(out[r, :dh], v[r - 1, :dh], atol=1e-9)
+    for r in range(p - 2):
+        assert np.allclose(out[r, dh:], v[r + 2, dh:], atol=1e-9)
+    out0 = om.attention(np.zeros_like(q), k, v, heads, dh, None, _one_hot_table(heads, dmax, (-1, 2)), pos)
+    assert np.allclose(out0[0, :dh], v[:, :dh].mean(axis=0))
+    assert np.allclose(out0[p - 1, dh:], v[:, dh:].mean(axis=0))
+
+
+def test_relative_bias_clamps_far_distances_and_respects_the_causal_mask():
+    """Admitting only the clamped end of the table (-D) gives the mean over every key at least D back;
+    under the causal mask an admitted FUTURE distance never shows, so the row falls back to the mean of
+    its visible prefix; row positions are absolute (a block of new rows at the end of a cache)."""
+    heads, dh, p, dmax, t = 2, 4, 12, 3, 5
+    v = RNG.standard_normal((p, heads * dh))
+    k = RNG.standard_normal((p, heads * dh))
+    pos = np.arange(p - t, p)
+    out = om.attention(np.zeros((t, heads * dh)), k, v, heads, dh, pos, _one_hot_table(heads, dmax, (-dmax, 1)), pos)
+    for i, r in enumerate(pos):
+        assert np.allclose(out[i, :dh], v[:r - dmax + 1, :dh].mean(axis=0))
+        assert np.allclose(out[i, dh:], v[:r + 1, dh:].mean(axis=0))
+
+
+def test_relative_bias_matches_library_sdpa_with_an_additive_mask():
+    heads, dh, t, p, dmax = 3, 8, 4, 11, 2
+    q, k, v = (RNG.standard_normal((n, heads * dh)) for n in (t, p, p))
+    table = RNG.standard_normal((heads, 2 * dmax + 1))
+    qpos = np.arange(p - t, p)
+    add = np.zeros((heads, t, p))
+    for h in range(heads):
+        for r in range(t):
+            for c in range(p):
+                add[h, r, c] = table[h, min(max(c - int(qpos[r]), -dmax), dmax) + dmax] if c <= qpos[r] else -np.inf
+    ref = _sdpa(q, k, v, heads, dh, torch.from_numpy(add))
+    assert np.allclose(om.attention(q, k, v, heads, dh, qpos, table, qpos), ref, rtol=1e-12, atol=1e-13)
+
+
+def test_relative_models_see_order_only_through_the_table():
+    """With an all-zero table a relative-position encoder is permutation equivariant (nothing else
+    carries position); with the drawn table it is not."""
+    cfg = bi.toy_pair(pos=bi.POS_RELATIVE)
+    _, wl = bi.make_pair_weights(cfg)
+    src = bi.make_source(cfg)
+    perm = np.random.default_rng(3).permutation(len(src))
+    m = om.Model(cfg.large, wl)
+    assert not np.allclose(m.encode(src[perm]), m.encode(src)[perm], atol=1e-6)
+    wz = dict(wl, enc_rel_bias=np.zeros_like(wl["enc_rel_bias"]))
+    mz = om.Model(cfg.large, wz)
+    assert np.allclose(mz.encode(src[perm]), mz.encode(src)[perm], rtol=1e-10, atol=1e-12)
+
+
+def test_synthetic_bias_tables_tie_distances_in_log_spaced_ranges():
+    from bild_inputs.generate import distance_ties
+    one = distance_ties(128, 32, False)
+    back = one[:129][::-1]                                 # distances 0, 1, ..., 128 behind the query
+    assert list(back[:16]) == list(range(16)) and back[128] == 31 and np.all(np.diff(back) >= 0)
+    assert len(set(back)) == 32 and np.all(one[129:] == 0)
+    widths = np.bincount(back)[16:31]
+    assert widths[-1] >= 4 * widths[0] and np.all(widths[8:] > widths[:7].max() - 1)   # ranges grow with distance
+    assert back[112] == 30 and back[113] == 31             # 16 * 8^(15/16) = 112.4: the last value starts at 113
+    two = distance_ties(128, 32, True)
+    assert np.array_equal(two[129:] - 16, two[:128][::-1]) and two[128] == 0 and len(set(two)) == 31
+    cfg = bi.toy_pair(pos=bi.POS_RELATIVE, truncate=True)
+    ws, wl = bi.make_pair_weights(cfg)
+    for name, two_sided in (("enc_rel_bias", True), ("dec_rel_bias", False)):
+        tab = wl[name]
+        ties = distance_ties(cfg.large.rel_max_dist, cfg.large.rel_buckets, two_sided)
+        assert tab.shape == (cfg.large.heads, 2 * cfg.large.rel_max_dist + 1) and tab.dtype == np.float32
+        for a in range(len(ties)):
+            for b in range(len(ties)):
+                assert (ties[a] == ties[b]) == bool(np.all(tab[:, a] == tab[:, b]))
+        assert np.array_equal(ws[name], tab[:cfg.small.heads])
+
+
 # ------------------------------------------------------- wiring vs torch modules
 def _torch_decoder(shape, w, y, cross_src):
     """A pre-norm decoder assembled from library modules (nn.MultiheadAttention,
@@ -222,6 +314,9 @@ VARIANTS = [
     dict(act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=False),
     dict(act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=False, dtype=bi.DT_BF16),
     dict(truncate=True, dtype=bi.DT_BF16),
+    dict(pos=bi.POS_RELATIVE),
+    dict(pos=bi.POS_RELATIVE, truncate=True, dtype=bi.DT_BF16, act=bi.ACT_GATED_GELU),
+    dict(pos=bi.POS_RELATIVE, cross=False, tied=False),
 ]
 
 
