@@ -36,7 +36,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="t5", choices=["tiny", "t5", "mt5", "llama", "t5ee"])
+    ap.add_argument("--workload", default="t5", choices=["tiny", "t5", "mt5", "llama", "t5ee", "t5rel"])
     ap.add_argument("--shared-trunk", action="store_true",
                     help="early-exit workloads (tiny, t5ee): build the pair from the large model alone, so the two "
                          "models share the trunk's K/V cache and a large pass runs the upper layers only")

@@ -59,6 +59,7 @@ extern "C" {
 #define BILD_ACT_SWIGLU      2 /* (silu(x W_in) * (x W_up)) W_out          */
 #define BILD_POS_SINUSOIDAL  0 /* PE added to the embedding                */
 #define BILD_POS_ROPE        1 /* rotary on q and k, pairs (2i, 2i+1)      */
+#define BILD_POS_RELATIVE    2 /* learned bias on self-attention scores by clamped key-query distance */
 #define BILD_DT_F32          0
 #define BILD_DT_BF16         1 /* weights and cached K/V stored as bf16    */
 
@@ -66,7 +67,8 @@ extern "C" {
 
 /* Architecture of one network.  The paper fixes only layer counts and widths
  * (Table 2); the rest is this benchmark's model contract:
- *   x = embed_scale*E[(tok+tie_shift) mod vocab] (+ sinusoidal PE); pre-RMSNorm
+ *   x = embed_scale*E[(tok+tie_shift) mod vocab] (+ sinusoidal PE; relative-position
+ *   models add nothing here and bias their self-attention scores instead); pre-RMSNorm
  *   sublayers x += f(norm(x)) in the order self-attn, cross-attn, FFN; scores
  *   scaled by 1/sqrt(d_head); logits = logit_scale * norm(x) E_out^T.
  * d_model, n_heads*d_head and d_ff must be multiples of 32. */
@@ -89,6 +91,7 @@ typedef struct bild_model_config {
     float   embed_scale;
     float   norm_eps;
     float   rope_base;
+    int32_t rel_max_dist;   /* BILD_POS_RELATIVE: distances are clamped to [-rel_max_dist, rel_max_dist] */
 } bild_model_config;
 
 /* Counters of one bild_generate call (Table 4 reports fallback and rollback
@@ -115,6 +118,9 @@ int bild_model_num_tensors(const bild_model_config* cfg);
  * (entries that do not exist for the config are simply absent from the list):
  *   emb [vocab][d]; head [vocab][d] (only if !tied_head);
  *   enc_final_norm [d] (only if n_enc_layers > 0); dec_final_norm [d];
+ *   (BILD_POS_RELATIVE only) enc_rel_bias (only if n_enc_layers > 0), dec_rel_bias: [n_heads][2*rel_max_dist+1],
+ *     entry [h][r + rel_max_dist] is added to the self-attention score of head h for a key r positions after
+ *     the query (r clamped to +-rel_max_dist); one table per stack, shared by its layers; kept in fp32;
  *   per encoder layer: ln1 [d], wq [d][I], wk [d][I], wv [d][I], wo [I][d], ln2 [d],
  *                      w_in [d][F], w_up [d][F] (gated only), w_out [F][d];
  *   per decoder layer: ln1, wq, wk, wv, wo, then (cross_attn only) lnc [d], cwq [d][I],

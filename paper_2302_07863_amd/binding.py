@@ -21,7 +21,8 @@ class ModelConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_enc_layers", "n_dec_layers", "d_model", "n_heads", "d_head", "d_ff", "act", "pos", "vocab",
         "tied_head", "dtype", "cross_attn", "bos", "tie_shift")] + [
-        (n, C.c_float) for n in ("logit_scale", "embed_scale", "norm_eps", "rope_base")]
+        (n, C.c_float) for n in ("logit_scale", "embed_scale", "norm_eps", "rope_base")] + [
+        ("rel_max_dist", C.c_int32)]
 
 
 class Stats(C.Structure):
@@ -127,7 +128,8 @@ def config_from_shape(shape) -> ModelConfig:
                        d_head=shape.d_head, d_ff=shape.d_ff, act=shape.act, pos=shape.pos, vocab=shape.vocab,
                        tied_head=int(shape.tied), dtype=shape.dtype, cross_attn=int(shape.cross), bos=shape.bos,
                        tie_shift=shape.tie_shift, logit_scale=shape.logit_scale, embed_scale=shape.embed_scale,
-                       norm_eps=shape.eps, rope_base=shape.rope_base)
+                       norm_eps=shape.eps, rope_base=shape.rope_base,
+                       rel_max_dist=getattr(shape, "rel_max_dist", 0))
 
 
 class Model:

@@ -41,6 +41,8 @@ struct bild_model {
     TMat emb, head;
     const float* enc_final = nullptr;
     const float* dec_final = nullptr;
+    const float* enc_rel = nullptr;  // relative-position models: [heads][2*rel_max_dist + 1] score biases of the
+    const float* dec_rel = nullptr;  // encoder's / decoder's self-attention, shared by all layers of the stack
     std::vector<LayerW> enc, dec;
     std::vector<void*> allocs;
     size_t device_bytes = 0;
@@ -154,11 +156,12 @@ bool config_ok(const bild_model_config& c) {
     if (c.d_model < 32 || c.d_model % 32 || c.d_ff < 32 || c.d_ff % 32) return false;
     if (c.n_heads < 1 || c.d_head < 8 || c.d_head > 128 || c.d_head % 8) return false;
     if ((c.n_heads * c.d_head) % 32) return false;
-    if (c.act < 0 || c.act > 2 || c.pos < 0 || c.pos > 1 || c.dtype < 0 || c.dtype > 1) return false;
+    if (c.act < 0 || c.act > 2 || c.pos < 0 || c.pos > 2 || c.dtype < 0 || c.dtype > 1) return false;
     if (c.vocab < 1 || c.bos < 0 || c.bos >= c.vocab) return false;
     if (c.n_enc_layers > 0 && !c.cross_attn) return false;
     if (!(c.norm_eps >= 0.f) || !(c.rope_base > 0.f)) return false;
     if (c.tie_shift < 0) return false;
+    if (c.pos == BILD_POS_RELATIVE && (c.rel_max_dist < 1 || c.rel_max_dist > 4096)) return false;
     return true;
 }
 
@@ -218,6 +221,7 @@ extern "C" int bild_model_num_tensors(const bild_model_config* c) {
     if (!c || !config_ok(*c)) return BILD_EINVAL;
     const int gated = c->act != BILD_ACT_RELU;
     int n = 1 + (c->tied_head ? 0 : 1) + (c->n_enc_layers > 0 ? 1 : 0) + 1;
+    if (c->pos == BILD_POS_RELATIVE) n += (c->n_enc_layers > 0 ? 1 : 0) + 1;
     n += c->n_enc_layers * (8 + gated);
     n += c->n_dec_layers * (8 + gated + (c->cross_attn ? 5 : 0));
     return n;
@@ -259,6 +263,11 @@ extern "C" int bild_model_create(const bild_model_config* cfg, const float* cons
         UP(upload_matrix(m, t[i++], false, V, d, &m->head));
     if (cfg->n_enc_layers > 0) UP(upload_vec(m, t[i++], d, &m->enc_final));
     UP(upload_vec(m, t[i++], d, &m->dec_final));
+    if (cfg->pos == BILD_POS_RELATIVE) {
+        const int nrel = cfg->n_heads * (2 * cfg->rel_max_dist + 1);
+        if (cfg->n_enc_layers > 0) UP(upload_vec(m, t[i++], nrel, &m->enc_rel));
+        UP(upload_vec(m, t[i++], nrel, &m->dec_rel));
+    }
     m->enc.resize(cfg->n_enc_layers);
     for (auto& L : m->enc) {
         UP(upload_vec(m, t[i], d, &L.ln1));
@@ -335,6 +344,7 @@ extern "C" int bild_pair_create_early_exit(bild_model* l, int k, float small_log
     v->emb = l->emb;
     v->head = l->head;
     v->dec_final = l->dec_final;
+    v->dec_rel = l->dec_rel;
     v->dec.assign(l->dec.begin(), l->dec.begin() + k);
     p->m[0] = v;
     p->m[1] = l;
@@ -453,7 +463,7 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         if (es) s->spin_limit = std::max(-1, std::atoi(es));  // -1: every barrier wait gives up at once (error-path tests)
         for (int w = 0; w < 2; ++w) {
             const bild_model* m = p->m[w];
-            s->resident[w] = e && e[0] == '1';
+            s->resident[w] = e && e[0] == '1' && m->cfg.pos != BILD_POS_RELATIVE;  // the persistent kernel has no score bias
             s->resident_G[w] = eg ? std::min(256, std::max(1, std::atoi(eg))) : (m->cfg.d_model >= 1024 ? 64 : 32);
         }
     }
@@ -790,6 +800,8 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
             a.T = T; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
             a.causal = 1;
             a.len_ptr = len_ptr;
+            a.rel_bias = m->dec_rel;
+            a.rel_d = c.rel_max_dist;
             a.vcap = s->cap_len;
             a.part_o = M.att_o; a.part_ml = M.att_ml;
             a.scale = att_scale;
@@ -1089,6 +1101,8 @@ int run_encoder(bild_state* s, int w) {
             a.T = S; a.heads = c.n_heads; a.d_head = c.d_head; a.i_dim = I;
             a.causal = 0;
             a.nkeys_fixed = S;
+            a.rel_bias = m->enc_rel;
+            a.rel_d = c.rel_max_dist;
             a.len_ptr = &s->ctl->n_src;  // not used with a fixed count, but the kernel reads it
             a.vcap = s->cap_src;
             a.splits = 1;

@@ -128,6 +128,10 @@ struct AttnArgs {
     float* part_o;             // [splits][T][I]   unnormalised partial outputs
     float* part_ml;            // [splits][T][heads][2] (max, sum)
     float scale;
+    // relative-position models: score(row, key) += rel_bias[head][clamp(key_pos - row_pos, -rel_d, rel_d) + rel_d];
+    // row_pos = base + t (causal) or base_add + t (not causal).  Null: no bias.
+    const float* rel_bias;      // [heads][2*rel_d + 1]
+    int rel_d;
     unsigned long long* trace;  // kernel-internal time stamps (only read when built with BILD_TRACE)
 };
 

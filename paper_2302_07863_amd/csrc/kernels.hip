@@ -947,9 +947,9 @@ size_t gemm_num_blocks(const GemmArgs& a) {
     return (size_t)(a.W.tn + per - 1) / per;
 }
 
-template <int DT, int DH32>
+template <int DT, int DH32, bool REL = false>
 __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a);
-template <int DT, int DH32>
+template <int DT, int DH32, bool REL = false>
 __global__ __launch_bounds__(512) void attn_rows_kernel(const AttnArgs a);
 
 // The big kernels may ask for more than the default 64 KiB of dynamic LDS.
@@ -1000,7 +1000,13 @@ static hipError_t raise_lds_limits() {
                              (const void*)attn_rows_kernel<1, 2>, (const void*)attn_rows_kernel<1, 4>,
                              (const void*)attn_kernel<0, 1>, (const void*)attn_kernel<0, 2>,
                              (const void*)attn_kernel<0, 4>, (const void*)attn_kernel<1, 1>,
-                             (const void*)attn_kernel<1, 2>, (const void*)attn_kernel<1, 4>};
+                             (const void*)attn_kernel<1, 2>, (const void*)attn_kernel<1, 4>,
+                             (const void*)attn_rows_kernel<0, 1, true>, (const void*)attn_rows_kernel<0, 2, true>,
+                             (const void*)attn_rows_kernel<0, 4, true>, (const void*)attn_rows_kernel<1, 1, true>,
+                             (const void*)attn_rows_kernel<1, 2, true>, (const void*)attn_rows_kernel<1, 4, true>,
+                             (const void*)attn_kernel<0, 1, true>, (const void*)attn_kernel<0, 2, true>,
+                             (const void*)attn_kernel<0, 4, true>, (const void*)attn_kernel<1, 1, true>,
+                             (const void*)attn_kernel<1, 2, true>, (const void*)attn_kernel<1, 4, true>};
 #undef BILD_G1
 #undef BILD_G
 #undef BILD_R
@@ -1143,7 +1149,7 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
 // Cache rows beyond the valid length are finite (zero-filled at allocation, or stale
 // values of discarded tokens), so a probability of exactly 0 removes them.
 // =====================================================================================
-template <int DT, int DH32, bool COH = false, class A>
+template <int DT, int DH32, bool COH = false, bool REL = false, class A>
 __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* smem) {
     constexpr int DHP = DH32 * 32;   // head dim padded to the k-step of the first product
     constexpr int DT16 = DH32 * 2;   // 16-wide output tiles along the head dim
@@ -1160,6 +1166,9 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
     float* cm = (float*)comb;                 // [nw][32]
     float* cl = cm + nw * 32;                 // [nw][32]
     f32x4* co = (f32x4*)(cl + nw * 32);       // [nw][NT][DT16][64]
+    // relative-position models: this head's row of the bias table, [2*rel_d + 1], behind the merge buffers
+    float* relb = REL ? (float*)(co + nw * NT * DT16 * 64) : nullptr;
+    const int nrel = REL ? 2 * a.rel_d + 1 : 1;
 
 #ifdef BILD_TRACE
     unsigned long long* tr = (a.trace && vblock == 0 && tid == 0) ? a.trace : nullptr;
@@ -1297,6 +1306,13 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int key = key0 + ab * 16 + g * 4 + v;
+                    if constexpr (REL) {
+                        // learned bias of the clamped signed distance key - query, one row of the table per head;
+                        // the clamp keeps the index inside the table for padded rows and keys past the end as well
+                        const int qpos = (a.causal ? base : a.base_add) + t;
+                        const int dist = max(-a.rel_d, min(a.rel_d, key - qpos));
+                        s[ab][v] += relb[a.rel_d + dist];
+                    }
                     if (key > lim || t >= T) s[ab][v] = -INFINITY;
                     tmax = fmaxf(tmax, s[ab][v]);
                 }
@@ -1353,11 +1369,19 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
         int blk = 0;
         // a wave without a block requests block 0 of the cache all the same (valid memory, never processed): the
         // request sits between q's loads and their use and must not be conditional
+        // the bias row (small, shared by every pass, so warm) is requested ahead of q and stored with it, so that its
+        // store does not wait for the K/V block requested in between
+        float rel_first = 0.f;
+        if constexpr (REL) rel_first = a.rel_bias[h * nrel + min(tid, nrel - 1)];
         stage_q([&] {
             ranges();
             blk = blk_begin + wave;
             load_kv(K0, V0, blk < blk_end ? blk : 0);
         });
+        if constexpr (REL) {
+            relb[min(tid, nrel - 1)] = rel_first;  // threads past the end rewrite the last entry with its own value
+            for (int i = tid + nthr; i < nrel; i += nthr) relb[i] = a.rel_bias[h * nrel + i];
+        }
         ASTAMP(1);
         __syncthreads();
         ASTAMP(2);
@@ -1423,14 +1447,14 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
 #undef ASTAMP
 }
 
-template <int DT, int DH32>
+template <int DT, int DH32, bool REL>
 __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    attn_body<DT, DH32>(a, (int)(blockIdx.x + blockIdx.y * gridDim.x), smem);
+    attn_body<DT, DH32, false, REL>(a, (int)(blockIdx.x + blockIdx.y * gridDim.x), smem);
 }
 
 // More than kMaxRows query rows: blockIdx.z picks the block of rows (key splits are not combined with it).
-template <int DT, int DH32>
+template <int DT, int DH32, bool REL>
 __global__ __launch_bounds__(512) void attn_rows_kernel(const AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     AttnArgs b = a;
@@ -1439,7 +1463,7 @@ __global__ __launch_bounds__(512) void attn_rows_kernel(const AttnArgs a) {
     b.q = a.q + (size_t)r0 * a.i_dim;
     b.out = a.out + (size_t)r0 * a.i_dim;
     b.base_add = a.base_add + r0;
-    attn_body<DT, DH32>(b, (int)blockIdx.x, smem);
+    attn_body<DT, DH32, false, REL>(b, (int)blockIdx.x, smem);
 }
 
 // Joins the key splits of attention: out[t][n] = sum_s w_s O_s[t][n] / sum_s w_s L_s with w_s = exp(m_s - max m) of
@@ -1500,14 +1524,21 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
     const int dh32 = a.d_head <= 32 ? 1 : (a.d_head <= 64 ? 2 : 4);
     const unsigned row_blocks = (unsigned)((a.T + kMaxRows - 1) / kMaxRows);
     if ((row_blocks > 1 && a.splits != 1) || !a.len_ptr) return hipErrorInvalidValue;
-    const size_t smem = attn_lds_bytes(dtype, a.d_head, std::min(a.T, kMaxRows), a.nw);
+    if (a.rel_bias && a.rel_d < 1) return hipErrorInvalidValue;
+    const size_t smem = attn_lds_bytes(dtype, a.d_head, std::min(a.T, kMaxRows), a.nw) +
+                        (a.rel_bias ? (size_t)(2 * a.rel_d + 1) * 4 : 0);  // + one head's row of the bias table
+    if (smem > (size_t)kGemmLdsLimit) return hipErrorInvalidValue;
     const dim3 grid(a.heads, a.splits, row_blocks), block(64 * a.nw);
-#define BILD_ATTN(DTV, DHV)                                                               \
-    do {                                                                                  \
-        if (row_blocks > 1)                                                               \
-            hipLaunchKernelGGL((attn_rows_kernel<DTV, DHV>), grid, block, smem, st, a);   \
-        else                                                                              \
-            hipLaunchKernelGGL((attn_kernel<DTV, DHV>), grid, block, smem, st, a);        \
+#define BILD_ATTN(DTV, DHV)                                                                     \
+    do {                                                                                        \
+        if (row_blocks > 1 && a.rel_bias)                                                       \
+            hipLaunchKernelGGL((attn_rows_kernel<DTV, DHV, true>), grid, block, smem, st, a);   \
+        else if (row_blocks > 1)                                                                \
+            hipLaunchKernelGGL((attn_rows_kernel<DTV, DHV>), grid, block, smem, st, a);         \
+        else if (a.rel_bias)                                                                    \
+            hipLaunchKernelGGL((attn_kernel<DTV, DHV, true>), grid, block, smem, st, a);        \
+        else                                                                                    \
+            hipLaunchKernelGGL((attn_kernel<DTV, DHV>), grid, block, smem, st, a);              \
     } while (0)
     if (dtype) {
         if (dh32 == 1) BILD_ATTN(1, 1); else if (dh32 == 2) BILD_ATTN(1, 2); else BILD_ATTN(1, 4);

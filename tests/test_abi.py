@@ -47,10 +47,17 @@ def test_tensor_count_follows_the_config():
     assert lib.bild_model_num_tensors(C.byref(_cfg())) == 1 + 1 + 1 + 8 + 13
     assert lib.bild_model_num_tensors(C.byref(_cfg(tied_head=0, act=1))) == 2 + 1 + 1 + 9 + 14
     assert lib.bild_model_num_tensors(C.byref(_cfg(n_enc_layers=0, cross_attn=0, act=2, pos=1))) == 1 + 1 + 9
+    # relative-position models bring one bias table per stack
+    assert lib.bild_model_num_tensors(C.byref(_cfg(pos=2, rel_max_dist=8))) == 1 + 1 + 1 + 2 + 8 + 13
+    assert lib.bild_model_num_tensors(C.byref(_cfg(n_enc_layers=0, cross_attn=0, pos=2, rel_max_dist=8))) == 1 + 1 + 1 + 8
+    import bild_inputs as bi
+    for kw in (dict(pos=bi.POS_RELATIVE), dict(pos=bi.POS_RELATIVE, cross=False, tied=False)):
+        for shape in (bi.toy_pair(**kw).large, bi.toy_pair(**kw).small):
+            assert lib.bild_model_num_tensors(C.byref(pkg.config_from_shape(shape))) == len(bi.tensor_names(shape))
 
 
 @pytest.mark.parametrize("kw", [dict(d_model=48), dict(d_ff=100), dict(d_head=12), dict(d_head=256), dict(act=3),
-                                dict(pos=2), dict(dtype=5), dict(vocab=0), dict(bos=100), dict(n_dec_layers=0),
+                                dict(pos=3), dict(pos=2), dict(pos=2, rel_max_dist=5000), dict(dtype=5), dict(vocab=0), dict(bos=100), dict(n_dec_layers=0),
                                 dict(n_enc_layers=1, cross_attn=0), dict(tie_shift=-1), dict(rope_base=0.0)])
 def test_bad_configs_are_rejected_before_any_device_work(kw):
     lib = pkg.lib()

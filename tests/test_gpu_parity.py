@@ -42,6 +42,13 @@ TOY_VARIANTS = {
     "bf16-rope-swiglu-deconly": dict(act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=False, dtype=bi.DT_BF16,
                                      truncate=True),
     "f32-wide": dict(d=256, heads=3, d_head=32, d_ff=160, vocab=1000, n_src=40),
+    # relative-position scheme: score bias by clamped distance (the source and the generation are both
+    # longer than the clamp of 5); the wide one runs its encoder over more than 32 rows at once
+    "f32-relative": dict(pos=bi.POS_RELATIVE),
+    "bf16-relative-trunc-geglu": dict(pos=bi.POS_RELATIVE, act=bi.ACT_GATED_GELU, truncate=True, dtype=bi.DT_BF16),
+    "f32-relative-deconly": dict(pos=bi.POS_RELATIVE, cross=False, tied=False),
+    "f32-relative-wide": dict(pos=bi.POS_RELATIVE, d=256, heads=3, d_head=32, d_ff=160, vocab=1000, n_src=40,
+                              rel_max_dist=11, rel_buckets=8),
 }
 _rigs = {}
 
@@ -260,6 +267,14 @@ def test_t5_config_full_size():
 
 
 @pytest.mark.timeout(900)
+def test_t5_relative_position_config_full_size():
+    """Config 2's shapes with the T5 family's position scheme (score bias by clamped distance, 128; 32 tied
+    values per head): 512 source tokens through the biased encoder, 32 new tokens."""
+    cfg = bi.PAIRS["t5rel"]()
+    _full_size(cfg, 32)
+
+
+@pytest.mark.timeout(900)
 def test_mt5_config_full_size():
     """Config 3: mT5 shapes, 250k vocabulary (the LM head dominates), gated-GELU, 6 heads of the small model."""
     cfg = bi.mt5_pair()
@@ -347,6 +362,18 @@ def test_two_way_key_splits_merged_by_the_output_projection():
         st = R.state(cfg.max_new, 6)
         st.encode(R.src)
         print(dtype, parity.teacher_forced(st, ref, R.n0, 0.4, 1.0, cfg), ref.stats, flush=True)
+
+
+def test_relative_bias_with_key_splits_and_long_prompt():
+    """Decoder-only relative-position toy with a 300-token prompt: the prefill runs the biased attention over
+    row blocks, the steps after it over a cache long enough for key splits, and nearly every distance is clamped (20)."""
+    cfg = bi.toy_pair(dtype=bi.DT_BF16, act=bi.ACT_SWIGLU, pos=bi.POS_RELATIVE, cross=False, tied=True, d=128,
+                      heads=2, d_head=64, d_ff=160, vocab=333, n_src=300, rel_max_dist=20, rel_buckets=12)
+    R = Rig(cfg)
+    ref = oracle.bild_generate(R.req, 0.4, 1.0, 5, cfg.max_new, keep_logits=True)
+    st = R.state(cfg.max_new, 5)
+    st.encode(R.src)
+    print(parity.teacher_forced(st, ref, R.n0, 0.4, 1.0, cfg), ref.stats, flush=True)
 
 
 @pytest.mark.timeout(1500)
