@@ -32,7 +32,8 @@
  *   BILD_NO_GRAPH=1      launch every kernel of a pass directly instead of replaying a captured
  *                        HIP graph (needed under rocprofv3, which cannot follow graph launches)
  *   BILD_RESIDENT=1      run embedding + layers of a pass in ONE persistent kernel with grid
- *                        barriers (experimental, slower on this chip; BILD_RESIDENT_G sets the
+ *                        barriers (experimental, slower on this chip, ignored for relative-position
+ *                        models, whose score bias it does not know; BILD_RESIDENT_G sets the
  *                        number of resident workgroups, BILD_BARRIER_SPIN the polls a barrier
  *                        wait may take, -1 = give up at once).  A barrier that gives up ends the
  *                        kernel normally and the call returns BILD_EHIP; the request must then be

@@ -1369,18 +1369,25 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
         int blk = 0;
         // a wave without a block requests block 0 of the cache all the same (valid memory, never processed): the
         // request sits between q's loads and their use and must not be conditional
-        // the bias row (small, shared by every pass, so warm) is requested ahead of q and stored with it, so that its
-        // store does not wait for the K/V block requested in between
-        float rel_first = 0.f;
-        if constexpr (REL) rel_first = a.rel_bias[h * nrel + min(tid, nrel - 1)];
+        // The bias row is requested ahead of q and stored with it, so that its store does not wait for the K/V block
+        // requested in between.  A one-wave workgroup needs several pieces per thread for the row: RP of them are requested
+        // together (a loop of load-then-store would pay one trip to memory per piece); indices past the end are clamped, so
+        // such a thread rewrites the last entry with its own value.
+        constexpr int RP = 8;
+        float relv[RP];
+        if constexpr (REL) {
+#pragma unroll
+            for (int p = 0; p < RP; ++p) relv[p] = a.rel_bias[h * nrel + min(tid + p * nthr, nrel - 1)];
+        }
         stage_q([&] {
             ranges();
             blk = blk_begin + wave;
             load_kv(K0, V0, blk < blk_end ? blk : 0);
         });
         if constexpr (REL) {
-            relb[min(tid, nrel - 1)] = rel_first;  // threads past the end rewrite the last entry with its own value
-            for (int i = tid + nthr; i < nrel; i += nthr) relb[i] = a.rel_bias[h * nrel + i];
+#pragma unroll
+            for (int p = 0; p < RP; ++p) relb[min(tid + p * nthr, nrel - 1)] = relv[p];
+            for (int i = tid + RP * nthr; i < nrel; i += nthr) relb[i] = a.rel_bias[h * nrel + i];
         }
         ASTAMP(1);
         __syncthreads();

@@ -30,7 +30,8 @@ def _prefix_toy(name):
     return bi.toy_pair(n_small=2, n_large=4, **kw)
 
 
-@pytest.mark.parametrize("name", ["f32-relu-tied", "bf16-relu-tied", "f32-geglu-untied", "f32-rope-swiglu-deconly"])
+@pytest.mark.parametrize("name", ["f32-relu-tied", "bf16-relu-tied", "f32-geglu-untied", "f32-rope-swiglu-deconly",
+                                  "f32-relative", "f32-relative-deconly"])
 def test_early_exit_toy_parity(name):
     R = EERig(_prefix_toy(name))
     for fb, rb, nm in ((0.5, 2.0, 10), (0.2, 0.7, 3), (0.0, 0.5, 6)):
