@@ -153,6 +153,11 @@ def main() -> int:
         nbytes = st.pass_bytes(which, t_cache, rows)
         passes[name] = dict(rows=rows, t_cache=t_cache, ms=round(ms, 4), bytes=nbytes,
                             gbs=round(nbytes / ms / 1e6, 1), frac_of_peak=round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4))
+        # spread: 100 passes timed one by one (each between its own pair of events, so each includes the gap until
+        # the host has submitted it; `ms` above is the mean of 50 passes submitted back to back)
+        singles = sorted(st.bench_pass(which, rows, 1) for _ in range(100))
+        passes[name].update(single_p10_ms=round(singles[10], 4), single_median_ms=round(singles[50], 4),
+                            single_p90_ms=round(singles[90], 4))
         log(f"[bench] {name}: {passes[name]}")
 
     # Roofline of the dominant kernel (the weight-streaming GEMM): its launches replayed alone, in pass
