@@ -92,6 +92,8 @@ def test_attention_launch_shapes_are_consistent(pair):
                         assert 1 < s["splits"] <= 8 and rows <= 16 and rows * shape.heads <= 256
                         assert rows * shape.heads * s["splits"] * 4 <= 4096
                     assert s["waves"] in (1, 2, 4, 8) and 0 < s["lds"] <= 128 * 1024
+                    if min(rows, 32) <= 16 and shape.d_head <= 64:
+                        assert s["waves"] >= 4      # q is staged in one piece per thread from 256 threads on
                     per_wg = nkeys * shape.d_head * 2 * esz / s["splits"]
                     if per_wg > 160 * 1024 and rows <= 32 and not s["defer"]:
                         assert s["splits"] * 2 > max_splits or shape.heads * s["splits"] * 2 > 512
