@@ -9,6 +9,7 @@
 #include <cstdlib>
 #include <map>
 #include <cstdio>
+#include <chrono>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -97,6 +98,7 @@ struct bild_state {
     ModelState ms[2];
     Ctl* ctl = nullptr;   // device
     Ctl* hctl = nullptr;  // pinned host mirror of the control block, written by the policy kernel
+    int seq_issued = 0;   // passes with a policy kernel enqueued so far (the device counts them in Ctl::seq)
     Ctl* hctl_dev = nullptr;  // the same buffer as the device sees it
     float* halpha = nullptr;  // pinned staging for threshold updates
     float alpha_fb = -1.f, alpha_rb = -1.f;  // thresholds currently in the device control block
@@ -546,6 +548,7 @@ int push_ctl(bild_state* s) {
     h->n_max = s->n_max;
     h->alpha_fb = s->alpha_fb;
     h->alpha_rb = s->alpha_rb;
+    h->seq = s->seq_issued;
     HIPC(hipMemcpyAsync(s->ctl, h, sizeof(Ctl), hipMemcpyHostToDevice, s->stream));
     HIPC(hipStreamSynchronize(s->stream));
     return BILD_OK;
@@ -564,9 +567,27 @@ int set_alpha(bild_state* s, float fb, float rb) {
     return BILD_OK;
 }
 
-// Waits for the stream; the policy kernel has mirrored the control block into pinned host memory.
+// Waits for the last pass; its policy kernel has mirrored the control block into pinned host memory.  The mirror's pass
+// counter is polled first (the kernel writes it last, behind a system-wide fence): that sees the result a few
+// microseconds before the stream's completion reaches the host.  If the count does not arrive in time (a persistent
+// kernel that gave up, a failed launch) the stream is waited for as usual and the two counts are brought together again.
 int pull_ctl(bild_state* s) {
-    HIPC(hipStreamSynchronize(s->stream));
+    bool seen = false;
+    {
+        const volatile int* seq = &s->hctl->seq;
+        const auto t0 = std::chrono::steady_clock::now();
+        for (unsigned spins = 1;; ++spins) {
+            if (*seq == s->seq_issued) {
+                seen = true;
+                break;
+            }
+            if ((spins & 1023) == 0 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(500)) break;
+        }
+    }
+    if (!seen) {
+        HIPC(hipStreamSynchronize(s->stream));
+        s->seq_issued = s->hctl->seq;
+    }
     if (s->hctl->fault) {
         // a grid barrier of the persistent kernel gave up: its counters are meaningless now
         (void)hipMemset(s->psync, 0, sizeof(PassSync));
@@ -1029,7 +1050,11 @@ int run_pass(bild_state* s, int w, int T, int lm_rows, int mode) {
     }
     const int bucket = key_bucket(s->len[w] + T);
     if (lm_rows > 0) s->ms[w].last_rows = lm_rows;
-    if (!s->use_graphs || s->prof_on || mode == 3) return decoder_pass(s, w, T, lm_rows, mode, bucket);
+    if (!s->use_graphs || s->prof_on || mode == 3) {
+        const int rc = decoder_pass(s, w, T, lm_rows, mode, bucket);
+        if (rc == BILD_OK && !s->gemm_only) s->seq_issued += 1;  // its policy kernel will count this pass
+        return rc;
+    }
     const std::array<int, 6> key = {w, T, lm_rows, mode, bucket, (s->debug_logits ? 1 : 0) | (s->gemm_only ? 2 : 0) | (s->top_p > 0.f ? 4 : 0)};
     auto it = s->graphs.find(key);
     if (it == s->graphs.end()) {
@@ -1053,6 +1078,7 @@ int run_pass(bild_state* s, int w, int T, int lm_rows, int mode) {
         it = s->graphs.emplace(key, ge).first;
     }
     HIPC(hipGraphLaunch(it->second, s->stream));
+    if (!s->gemm_only) s->seq_issued += 1;
     return BILD_OK;
 }
 
@@ -1206,6 +1232,7 @@ extern "C" int bild_encode(bild_state* s, const int32_t* src, int n_src) {
             if (rc) return rc;
         }
     }
+    HIPC(hipStreamSynchronize(s->stream));  // the encoder's kernels end with no policy kernel: wait for the stream itself
     rc = pull_ctl(s);
     if (rc) return rc;
     s->encoded = true;

@@ -45,6 +45,7 @@ struct Ctl {
     int fault;        // set by the persistent pass kernel when a grid barrier gave up waiting
     float res_nll[kMaxRows];
     int res_rowtok[kMaxRows];  // argmax of every row of the last pass
+    int seq;          // passes finished so far; the LAST word, and the last one the policy kernel mirrors to the host
 };
 
 // Partial softmax statistics of one row over a slice of the vocabulary.

@@ -1794,6 +1794,7 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
     // trip from memory overlaps with the partials' instead of following it
     const int c_ylen = c->y_len, c_ds = c->draft_start, c_nmax = c->n_max, c_len0 = c->len[0], c_lenw = c->len[a.which];
     const float c_afb = c->alpha_fb, c_arb = c->alpha_rb;
+    const int c_seq = c->seq;
     if (a.mode != 3) {
         // rows are dealt to the waves; a wave's lanes share the partials of its row (eight loads in flight
         // per lane), so the rows of a review merge side by side and a single row costs one round trip
@@ -1891,11 +1892,20 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
         __threadfence();
     }
     __syncthreads();
-    // mirror the control block into pinned host memory for the caller
+    // mirror the control block into pinned host memory for the caller; the pass counter goes last, behind a
+    // system-wide fence, so that a host that sees the new count also sees every other word
     if (a.host_mirror) {
-        const int words = sizeof(Ctl) / 4;
+        static_assert(offsetof(Ctl, seq) == sizeof(Ctl) - 4, "seq must be the last word of the control block");
+        const int words = sizeof(Ctl) / 4 - 1;
         for (int i = tid; i < words; i += nthr)
             ((volatile int*)a.host_mirror)[i] = __hip_atomic_load((int*)c + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence_system();
+        __syncthreads();
+        if (tid == 0) {
+            const int sq = c_seq + 1;
+            c->seq = sq;
+            ((volatile int*)a.host_mirror)[words] = sq;
+        }
     }
 }
 
