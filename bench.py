@@ -41,6 +41,8 @@ def main() -> int:
                     help="early-exit workloads (tiny, t5ee): build the pair from the large model alone, so the two "
                          "models share the trunk's K/V cache and a large pass runs the upper layers only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-spread", action="store_true",
+                    help="skip the 100 single passes per pass type (keeps a profiled run's kernel mix to the timed work)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter-collection run: one 1 GiB device copy of known size, then --steps BiLD steps; "
                          "no timing, no JSON (run under rocprofv3 --pmc with BILD_NO_GRAPH=1)")
@@ -155,9 +157,10 @@ def main() -> int:
                             gbs=round(nbytes / ms / 1e6, 1), frac_of_peak=round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4))
         # spread: 100 passes timed one by one (each between its own pair of events, so each includes the gap until
         # the host has submitted it; `ms` above is the mean of 50 passes submitted back to back)
-        singles = sorted(st.bench_pass(which, rows, 1) for _ in range(100))
-        passes[name].update(single_p10_ms=round(singles[10], 4), single_median_ms=round(singles[50], 4),
-                            single_p90_ms=round(singles[90], 4))
+        if not args.no_spread:
+            singles = sorted(st.bench_pass(which, rows, 1) for _ in range(100))
+            passes[name].update(single_p10_ms=round(singles[10], 4), single_median_ms=round(singles[50], 4),
+                                single_p90_ms=round(singles[90], 4))
         log(f"[bench] {name}: {passes[name]}")
 
     # Roofline of the dominant kernel (the weight-streaming GEMM): its launches replayed alone, in pass
