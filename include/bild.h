@@ -16,6 +16,10 @@
  *   - all device memory is owned by the library behind the opaque handles;
  *   - a handle is not thread-safe; distinct states are independent but calls
  *     on states sharing one stream serialise on it;
+ *   - a call that runs a decoder pass returns once the pass's results have
+ *     reached the host; the stream may still be retiring that pass's last
+ *     kernel, so work the caller adds must go through the same stream or
+ *     wait for it (bild_encode and the bench/profile calls do wait for the stream);
  *   - token ids are int32 in [0, vocab).
  *
  * Sequence model held by a bild_state
