@@ -378,3 +378,157 @@ def test_compact_storage_gives_identical_values():
     a = om.Model(cfg.large, wl).logits_full(y, [])
     b = om.Model(cfg.large, wl, compact=True).logits_full(y, [])
     assert np.allclose(a, b, rtol=1e-13, atol=1e-13)      # same values; only the BLAS call pattern differs
+
+
+# ------------------------------------------- RoPE / decoder-only wiring vs library pieces
+def _polar_rotate(t: torch.Tensor, positions, heads: int, dh: int, base: float) -> torch.Tensor:
+    """Rotary position by an explicit complex multiply: pair (2i, 2i+1) of every head is read as the
+    complex number a + ib and multiplied by the unit number of angle position * base^(-2i/d_head)."""
+    n = t.shape[0]
+    z = torch.view_as_complex(t.reshape(n, heads, dh // 2, 2).contiguous())
+    i = torch.arange(dh // 2, dtype=torch.float64)
+    ang = torch.as_tensor(positions, dtype=torch.float64)[:, None] * base ** (-2.0 * i / dh)[None, :]
+    rot = torch.polar(torch.ones_like(ang), ang)[:, None, :]
+    return torch.view_as_real(z * rot).reshape(n, heads * dh)
+
+
+def _library_bf16(t: torch.Tensor) -> torch.Tensor:
+    return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+
+def _torch_rope_stack(shape, w, tokens, causal: bool, prefix: str, store_bf16: bool):
+    """A pre-norm stack assembled from F.rms_norm, F.linear, F.silu / F.gelu / F.relu and
+    F.scaled_dot_product_attention, with q and k rotated by _polar_rotate and v left alone.  K and V are
+    rounded to bf16 AFTER the rotation when store_bf16.  Calls nothing of the oracle.  Returns the hidden
+    state [n, d] after the last layer (no final norm)."""
+    d, h, dh = shape.d, shape.heads, shape.d_head
+    tw = {k: torch.from_numpy(np.asarray(a, dtype=np.float64)) for k, a in w.items()}
+    n = len(tokens)
+    pos = list(range(n))
+    rows = (torch.tensor(list(tokens), dtype=torch.int64) + shape.tie_shift) % shape.vocab
+    x = shape.embed_scale * F.embedding(rows, tw["emb"])             # rotary models add nothing to the embedding
+    n_layers = shape.n_dec if prefix == "dec" else shape.n_enc
+    mask = torch.tril(torch.ones(n, n, dtype=torch.bool)) if causal else None     # True = visible
+    for l in range(n_layers):
+        p = f"{prefix}.{l}."
+        xn = F.rms_norm(x, (d,), tw[p + "ln1"], eps=shape.eps)
+        q = _polar_rotate(F.linear(xn, tw[p + "wq"].T), pos, h, dh, shape.rope_base)
+        k = _polar_rotate(F.linear(xn, tw[p + "wk"].T), pos, h, dh, shape.rope_base)
+        v = F.linear(xn, tw[p + "wv"].T)
+        if store_bf16:
+            k, v = _library_bf16(k), _library_bf16(v)
+        split = lambda a: a.reshape(n, h, dh).transpose(0, 1)
+        o = F.scaled_dot_product_attention(split(q), split(k), split(v), attn_mask=mask)
+        x = x + F.linear(o.transpose(0, 1).reshape(n, h * dh), tw[p + "wo"].T)
+        xn = F.rms_norm(x, (d,), tw[p + "ln2"], eps=shape.eps)
+        u = F.linear(xn, tw[p + "w_in"].T)
+        if shape.act == bi.ACT_RELU:
+            hid = F.relu(u)
+        else:
+            gate = F.silu(u) if shape.act == bi.ACT_SWIGLU else F.gelu(u, approximate="tanh")
+            hid = gate * F.linear(xn, tw[p + "w_up"].T)
+        x = x + F.linear(hid, tw[p + "w_out"].T)
+    return x, tw
+
+
+def _torch_rope_decoder_logits(shape, w, y, store_bf16):
+    x, tw = _torch_rope_stack(shape, w, y, True, "dec", store_bf16)
+    xn = F.rms_norm(x, (shape.d,), tw["dec_final_norm"], eps=shape.eps)
+    return (shape.logit_scale * F.linear(xn, tw["emb" if shape.tied else "head"])).numpy()
+
+
+@pytest.mark.parametrize("tied", [False, True])
+def test_decoder_only_rope_swiglu_wiring_matches_library_pieces(tied):
+    """The decoder-only RoPE + SwiGLU stack (the shape family of the 7B-shaped configurations) against an
+    assembly of library pieces that never calls the oracle's own rotation: q and k rotated, v not, causal
+    mask, residual order, head.  Both routes of the oracle (definition and cached T-row passes)."""
+    cfg = bi.toy_pair(act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=tied, d=32, heads=3, d_head=8, d_ff=40, vocab=61)
+    _, wl = bi.make_pair_weights(cfg)
+    m = om.Model(cfg.large, wl)
+    y = [0, 13, 60, 2, 2, 31, 7, 19, 44]
+    ref = _torch_rope_decoder_logits(cfg.large, wl, y, store_bf16=False)
+    assert np.allclose(m.logits_full(y, []), ref, rtol=1e-11, atol=1e-11)
+    c = om.DecoderCache(m, [], 16)
+    blocks = np.concatenate([c.step(y[:1]), c.step(y[1:6]), c.step(y[6:])])
+    assert np.allclose(blocks, ref, rtol=1e-11, atol=1e-11)
+
+
+def test_bf16_rope_models_round_k_after_the_rotation_and_leave_q_unrounded():
+    """bf16 storage: K and V are rounded (library conversion) after the rotation; q, the scores and
+    everything else stay unrounded.  Rounding before the rotation, or rounding q too, moves the logits by
+    far more than the tolerance used here."""
+    cfg = bi.toy_pair(act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=False, d=32, heads=3, d_head=8, d_ff=40,
+                      vocab=61, dtype=bi.DT_BF16)
+    _, wl = bi.make_pair_weights(cfg)
+    m = om.Model(cfg.large, wl)
+    y = [5, 13, 60, 2, 9, 31, 7, 19, 44, 3, 3, 58]
+    ref = _torch_rope_decoder_logits(cfg.large, wl, y, store_bf16=True)
+    ours = m.logits_full(y, [])
+    assert np.allclose(ours, ref, rtol=1e-11, atol=1e-11)
+    # the rounding is visible at all (else this test would not tell the orders apart) ...
+    unrounded = _torch_rope_decoder_logits(cfg.large, wl, y, store_bf16=False)
+    assert np.abs(unrounded - ref).max() > 1e-5
+    # ... and so is its place: the same assembly with K rounded BEFORE the rotation differs
+    d, h, dh, s = cfg.large.d, cfg.large.heads, cfg.large.d_head, cfg.large
+    tw = {k: torch.from_numpy(np.asarray(a, dtype=np.float64)) for k, a in wl.items()}
+    xn = F.rms_norm(s.embed_scale * F.embedding((torch.tensor(y) + s.tie_shift) % s.vocab, tw["emb"]), (d,),
+                    tw["dec.0.ln1"], eps=s.eps)
+    k_raw = F.linear(xn, tw["dec.0.wk"].T)
+    pos = list(range(len(y)))
+    after = _library_bf16(_polar_rotate(k_raw, pos, h, dh, s.rope_base)).numpy()
+    before = _polar_rotate(_library_bf16(k_raw), pos, h, dh, s.rope_base).numpy()
+    assert np.abs(after - before).max() > 1e-6
+    c = om.DecoderCache(m, [], 16)
+    c.step(y)
+    assert np.array_equal(c.k[0][:len(y)], after)                      # the cache holds rotate-then-round, bit for bit
+    xv = _library_bf16(F.linear(xn, tw["dec.0.wv"].T)).numpy()
+    assert np.array_equal(c.v[0][:len(y)], xv)                         # V: rounded, never rotated
+
+
+def test_rope_encoder_wiring_matches_library_pieces():
+    """An encoder with rotary positions (bidirectional attention, q and k rotated) against the same assembly."""
+    cfg = bi.toy_pair(pos=bi.POS_ROPE, cross=True, d=32, heads=3, d_head=8, d_ff=40, vocab=61)
+    _, wl = bi.make_pair_weights(cfg)
+    m = om.Model(cfg.large, wl)
+    src = [5, 9, 0, 44, 17, 17, 60]
+    x, tw = _torch_rope_stack(cfg.large, wl, src, False, "enc", store_bf16=False)
+    ref = F.rms_norm(x, (cfg.large.d,), tw["enc_final_norm"], eps=cfg.large.eps).numpy()
+    assert np.allclose(m.encode(src), ref, rtol=1e-11, atol=1e-11)
+
+
+def test_decoder_relative_table_turns_causal_self_attention_into_a_shift():
+    """Which stack gets which table, and where: the DECODER's table admits only the key one position back
+    (every other distance gets -1e9), the encoder's table only the key two ahead.  Causal self-attention of the
+    decoder is then exactly a shift of V by one row (row 0 sees only itself), cross-attention carries no bias
+    at all, and the logits equal those of an assembly of library pieces in which the self-attention is
+    written as that shift."""
+    cfg = bi.toy_pair(pos=bi.POS_RELATIVE, d=32, heads=2, d_head=16, d_ff=40, vocab=50, rel_max_dist=3)
+    _, wl = bi.make_pair_weights(cfg)
+    s = cfg.large
+    wl = dict(wl, dec_rel_bias=_one_hot_table(s.heads, s.rel_max_dist, (-1,) * s.heads),
+              enc_rel_bias=_one_hot_table(s.heads, s.rel_max_dist, (2,) * s.heads))
+    m = om.Model(s, wl)
+    enc = RNG.standard_normal((7, s.d))
+    cross = m.cross_kv(enc)
+    y = [0, 13, 49, 2, 2, 31, 8]
+    n, d, h, dh = len(y), s.d, s.heads, s.d_head
+    tw = {k: torch.from_numpy(np.asarray(a, dtype=np.float64)) for k, a in wl.items()}
+    x = s.embed_scale * F.embedding((torch.tensor(y) + s.tie_shift) % s.vocab, tw["emb"])     # no additive position
+    mem = torch.from_numpy(enc)
+    split = lambda a: a.reshape(a.shape[0], h, dh).transpose(0, 1)
+    for l in range(s.n_dec):
+        p = f"dec.{l}."
+        v = F.linear(F.rms_norm(x, (d,), tw[p + "ln1"], eps=s.eps), tw[p + "wv"].T)
+        shifted = torch.cat([v[:1], v[:-1]], 0)                       # row r takes v[r-1]; row 0 only sees key 0
+        x = x + F.linear(shifted, tw[p + "wo"].T)
+        xn = F.rms_norm(x, (d,), tw[p + "lnc"], eps=s.eps)
+        o = F.scaled_dot_product_attention(split(F.linear(xn, tw[p + "cwq"].T)), split(F.linear(mem, tw[p + "cwk"].T)),
+                                           split(F.linear(mem, tw[p + "cwv"].T)))
+        x = x + F.linear(o.transpose(0, 1).reshape(n, h * dh), tw[p + "cwo"].T)
+        xn = F.rms_norm(x, (d,), tw[p + "ln2"], eps=s.eps)
+        x = x + F.linear(F.relu(F.linear(xn, tw[p + "w_in"].T)), tw[p + "w_out"].T)
+    ref = (s.logit_scale * F.linear(F.rms_norm(x, (d,), tw["dec_final_norm"], eps=s.eps), tw["emb"])).numpy()
+    assert np.allclose(m.logits_full(y, cross), ref, rtol=1e-9, atol=1e-9)
+    c = om.DecoderCache(m, cross, 16)
+    blocks = np.concatenate([c.step(y[:2]), c.step(y[2:3]), c.step(y[3:])])
+    assert np.allclose(blocks, ref, rtol=1e-9, atol=1e-9)
