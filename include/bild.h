@@ -35,13 +35,6 @@
  * Environment (read when a bild_state is created)
  *   BILD_NO_GRAPH=1      launch every kernel of a pass directly instead of replaying a captured
  *                        HIP graph (needed under rocprofv3, which cannot follow graph launches)
- *   BILD_RESIDENT=1      run embedding + layers of a pass in ONE persistent kernel with grid
- *                        barriers (experimental, slower on this chip, ignored for relative-position
- *                        models, whose score bias it does not know; BILD_RESIDENT_G sets the
- *                        number of resident workgroups, BILD_BARRIER_SPIN the polls a barrier
- *                        wait may take, -1 = give up at once).  A barrier that gives up ends the
- *                        kernel normally and the call returns BILD_EHIP; the request must then be
- *                        encoded again.
  */
 #ifndef BILD_H
 #define BILD_H
@@ -56,7 +49,7 @@ extern "C" {
 #define BILD_EINVAL (-1) /* bad argument (null pointer, size out of range, token id >= vocab, unsupported shape) */
 #define BILD_ESTATE (-2) /* call not valid in the current state (e.g. step before encode, nothing to consume) */
 #define BILD_ECAP   (-3) /* capacity exceeded (source longer than max_src, sequence longer than max_len, n > max rows) */
-#define BILD_EHIP   (-4) /* a HIP runtime call failed, or a grid barrier of the persistent kernel gave up */
+#define BILD_EHIP   (-4) /* a HIP runtime call failed */
 #define BILD_ENOMEM (-5) /* host or device allocation failed */
 
 #define BILD_ACT_RELU        0 /* relu(x W_in) W_out                       */
@@ -163,7 +156,9 @@ int bild_state_create(const bild_pair* p, int max_src, int max_len, int n_max, v
                       bild_state** out);
 int bild_state_destroy(bild_state* s);
 
-/* Starts a request.  Encoder-decoder pairs: runs the encoder(s) over src[0..n_src)
+/* Starts a request (Section 3.2: both models map the input x and the partial output y_1..n-1 to a distribution
+ * over the next token; this call does the part of that map which depends on x alone, once per request).
+ * Encoder-decoder pairs: runs the encoder(s) over src[0..n_src)
  * and fills every decoder layer's cross-attention K/V; y = [bos].  Decoder-only
  * pairs: y = src (the prompt) and both caches are prefilled with its first
  * n_src-1 tokens.  Requires 1 <= n_src <= max_src. */
@@ -201,7 +196,8 @@ int bild_large_verify(bild_state* s, const int32_t* draft, int n, float alpha_rb
  * may then be NULL).  BILD_EINVAL for top_p > 1, a missing array, n < max_len or a number outside [0, 1). */
 int bild_set_sampling(bild_state* s, float top_p, const float* u_small, const float* u_large, int n);
 
-/* Lowers a cache length: which = 1 small, 2 large, 3 both; the cache(s) keep
+/* Lowers a cache length (Algorithm 1, the rollback step y <- y[:m] + [large model's token]; Section 3.4: the
+ * predictions after the rolled-back position are discarded): which = 1 small, 2 large, 3 both; the cache(s) keep
  * their first pos rows (O(1): only a length changes).  BILD_EINVAL if pos exceeds
  * the current length of a selected cache.  y is not changed; a later pass simply
  * re-consumes the rows that were cut. */
@@ -234,6 +230,24 @@ int bild_generate(bild_state* s, const int32_t* src, int n_src, float alpha_fb, 
 int bild_greedy(bild_state* s, int which, const int32_t* src, int n_src, int max_new, int32_t eos,
                 int32_t* out, int32_t* n_out);
 
+/* The vocabulary sweep of a decoder pass as a call of its own (Section 3.2: each model maps its hidden state to
+ * a distribution over the entire vocabulary; Sections 3.3 and 3.4 test max p and -ln p(draft) of it).  For each of
+ * `rows` hidden rows (1..BILD_MAX_ROWS) the final RMSNorm of model m, its LM head and logit scale are applied and the
+ * row's statistics are written: zmax = largest logit, lse = ln sum exp(logit), argmax (lowest id among equal
+ * maxima) and z_target = logit of targets_dev[row] (NaN without targets or for an id outside the vocabulary), so
+ * that max p = exp(zmax - lse) and -ln p(target) = lse - z_target.  Logits are never written to memory.
+ * x_dev [rows][d_model] fp32 (16-byte aligned), targets_dev [rows] int32 (nullable) and out_dev [rows] are DEVICE
+ * memory of the caller, read and written by kernels on hip_stream (NULL: the default stream).  The call allocates
+ * a scratch buffer for its kernels' partial results and returns after the stream has finished with it. */
+typedef struct bild_row_stats {
+    float zmax;
+    float lse;
+    int32_t argmax;
+    float z_target;
+} bild_row_stats;
+int bild_head_stats(const bild_model* m, const float* x_dev, int rows, const int32_t* targets_dev,
+                    bild_row_stats* out_dev, void* hip_stream);
+
 /* Introspection (host copies of the control block). */
 int bild_get_lengths(bild_state* s, int32_t* y_len, int32_t* draft_start, int32_t* len_small, int32_t* len_large);
 int bild_get_sequence(bild_state* s, int32_t* out, int cap, int32_t* n);
@@ -243,68 +257,10 @@ int bild_get_sequence(bild_state* s, int32_t* out, int cap, int32_t* n);
  * of model `which`).  Off by default: the product path never materialises logits. */
 int bild_debug_enable_logits(bild_state* s, int enable);
 int bild_debug_logits(bild_state* s, int which, int row, float* out_vocab);
-
-/* Measurement helpers (no effect on results).
- * bild_bench_pass: brings model `which` up to y_len - rows consumed tokens (needs
- * y_len - len >= rows), then runs `reps` identical passes over the last `rows`
- * tokens of y, LM head and statistics included, WITHOUT committing anything, and
- * returns the mean time of one pass in milliseconds from HIP events on the
- * state's stream.
- * bild_profile_begin/end: between the two calls every weight-streaming GEMM launch
- * is bracketed by HIP events (at most max_records launches are recorded);
- * end() waits for the stream and sums, per model [0 small, 1 large] and per
- * class [0 layer GEMMs, 1 LM head]: launches, milliseconds and algorithmic bytes
- * (bytes of the weight matrix each launch streams). */
-typedef struct bild_profile {
-    int64_t launches[2][2];
-    int64_t bytes[2][2];
-    double  ms[2][2];
-    int32_t dropped;        /* launches not recorded because max_records was reached */
-} bild_profile;
-int bild_bench_pass(bild_state* s, int which, int rows, int reps, float* ms_per_pass);
-/* Like bild_bench_pass, but each pass launches ONLY its weight-streaming GEMM kernels (the
- * dominant kernel), back to back in pass order, so that ms_per_pass / launches is the mean
- * duration of one GEMM launch (including the gap to the next launch) and bytes the
- * algorithmic weight bytes the launches of one pass stream.  The activations the GEMMs read
- * are stale; only the timing is meaningful. */
-int bild_bench_gemm(bild_state* s, int which, int rows, int reps, float* ms_per_pass, int64_t* launches,
-                    int64_t* bytes);
-/* Runs `reps` launches of a plain device-to-device copy kernel (bild::probe_copy_kernel) of
- * `bytes` bytes (a multiple of 16) on temporary buffers: it reads `bytes` and writes `bytes`,
- * the known quantity against which hardware byte counters are scaled. */
-int bild_probe_copy(bild_state* s, int64_t bytes, int reps);
-/* Mean time of `reps` back-to-back launches of a kernel that does nothing (one workgroup per CU) on the state's
- * stream, in microseconds: the cost of a dependent stage by itself, against which the stage count of a pass is read. */
-int bild_probe_launch(bild_state* s, int reps, float* us_per_launch);
-/* Mean time (microseconds, launch included) of a kernel in which `groups` workgroups of 8 waves each stream a private
- * contiguous region of kib_per_group KiB that no earlier launch touched: the streaming rate of one compute unit
- * (groups = 1) and how the total grows with the number of workgroups.  reps <= 64; the probe allocates
- * groups * kib_per_group KiB * (reps + 1) for its own use (at most 16 GiB, else BILD_EINVAL) and frees it. */
-int bild_probe_stream(bild_state* s, int groups, int kib_per_group, int reps, float* us_per_launch);
-/* GEMM launches ISSUED by the host since the last reset and the algorithmic weight bytes they stream
- * (replays of captured graphs are not counted: meaningful when graph replay is disabled). */
-int bild_gemm_tally(bild_state* s, int64_t* launches, int64_t* bytes, int reset);
-int bild_profile_begin(bild_state* s, int max_records);
-int bild_profile_end(bild_state* s, bild_profile* out);
-
-/* Algorithmic bytes one pass of model `which` must read at cache length t_cache
- * with `rows` new rows (weights + LM head + self K/V + cross K/V). */
-int64_t bild_pass_bytes(const bild_state* s, int which, int t_cache, int rows);
-
-/* Host logic exposed for tests (no device work).
- * bild_debug_tile_matrix: re-lays a row-major matrix into the streaming tile order the kernels read
- * (1 KiB tiles of 16 features x 32 inputs for bf16, x 16 for fp32; inside a tile the 16 bytes of lane l hold
- * feature l % 16, inputs (l / 16) * KT/4 .. +KT/4-1; tiles of a feature block contiguous along the inputs; features
- * beyond n are zero).  src is [k][n] if src_is_k_by_n else [n][k]; dst has bild_debug_tiled_bytes(n, k, dtype) bytes.
- * bild_debug_gemm_shape: the launch shape the library would choose for a projection of n features x k inputs over
- * `rows` rows: out = {input slices per workgroup, waves per workgroup, feature tiles per wave, inputs per LDS chunk,
- * feature-group workgroups, row blocks, dynamic LDS bytes, LDS limit}. */
-int64_t bild_debug_tiled_bytes(int n, int k, int dtype);
-int bild_debug_tile_matrix(const float* src, int src_is_k_by_n, int n, int k, int dtype, void* dst);
-int bild_debug_gemm_shape(int n, int k, int rows, int gated, int lm_head, int dtype, int32_t out[8]);
-/* The launch shape of attention for `rows` query rows over nkeys cached keys: out = {key splits, 1 if the consumer
- * projection merges the split partials (no merge kernel), waves per workgroup, dynamic LDS bytes}. */
-int bild_debug_attn_shape(int heads, int d_head, int rows, int nkeys, int max_splits, int dtype, int32_t out[4]);
+/* Test/debug: copies cached self-attention keys (is_v = 0) or values (is_v = 1) of decoder layer `layer` of model
+ * `which` for positions pos0 .. pos0+n-1 to out ([n][n_heads*d_head] fp32, host; bf16 storage is widened exactly).
+ * Positions must lie below the model's consumed length.  BILD_EINVAL otherwise. */
+int bild_debug_kv(bild_state* s, int which, int layer, int is_v, int pos0, int n, float* out);
 
 const char* bild_strerror(int code);
 

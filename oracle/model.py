@@ -216,9 +216,11 @@ class DecoderCache:
         assert 0 <= length <= self.length
         self.length = length
 
-    def step(self, tokens) -> np.ndarray:
+    def step(self, tokens, last: int | None = None) -> np.ndarray:
         """Consume T tokens at positions length..length+T-1; return their T
-        rows of logits and advance the cache by T."""
+        rows of logits and advance the cache by T.  `last` (0..T) limits the
+        returned logits to the last `last` rows (the head is then evaluated on
+        those rows only; the cache advances all the same)."""
         m, s = self.m, self.m.s
         t0, t = self.length, len(tokens)
         pos = np.arange(t0, t0 + t)
@@ -237,4 +239,7 @@ class DecoderCache:
                 x = x + attention(xn @ m.w[p + "cwq"], ck, cv, s.heads, s.d_head, None) @ m.w[p + "cwo"]
             x = x + m.ffn(p, rmsnorm(x, m.w[p + "ln2"], s.eps))
         self.length = t0 + t
+        if last is not None:
+            assert 0 <= last <= t
+            x = x[t - last:]
         return m.logits_from_hidden(x)

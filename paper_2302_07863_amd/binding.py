@@ -69,10 +69,12 @@ _SIGS = {
                                 C.c_void_p, C.POINTER(C.c_int32), C.POINTER(Stats)]),
     "bild_greedy": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int32, C.c_void_p,
                               C.POINTER(C.c_int32)]),
+    "bild_head_stats": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "bild_get_lengths": (C.c_int, [C.c_void_p] + [C.POINTER(C.c_int32)] * 4),
     "bild_get_sequence": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int32)]),
     "bild_debug_enable_logits": (C.c_int, [C.c_void_p, C.c_int]),
     "bild_debug_logits": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
+    "bild_debug_kv": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
     "bild_bench_pass": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float)]),
     "bild_bench_gemm": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int64),
                                   C.POINTER(C.c_int64)]),
@@ -148,6 +150,16 @@ class Model:
             self.h = None
 
     __del__ = close
+
+
+ROW_STATS_DTYPE = np.dtype([("zmax", np.float32), ("lse", np.float32), ("argmax", np.int32), ("z_target", np.float32)])
+
+
+def head_stats(model: Model, x_dev_ptr: int, rows: int, targets_dev_ptr: Optional[int], out_dev_ptr: int,
+               stream: Optional[int] = None, entry: str = "bild_head_stats"):
+    """Device pointers in, device pointer out (rows records of ROW_STATS_DTYPE); see bild.h."""
+    _check(getattr(lib(), entry)(model.h, C.c_void_p(x_dev_ptr), rows, C.c_void_p(targets_dev_ptr or 0),
+                                 C.c_void_p(out_dev_ptr), C.c_void_p(stream or 0)), entry)
 
 
 class Pair:
@@ -269,6 +281,13 @@ class State:
         v = self.pair.large.cfg.vocab
         out = np.zeros(v, dtype=np.float32)
         _check(lib().bild_debug_logits(self.h, which, row, out.ctypes.data), "bild_debug_logits")
+        return out
+
+    def debug_kv(self, which: int, layer: int, is_v: bool, pos0: int, n: int) -> np.ndarray:
+        """Cached keys or values of one decoder layer, rows pos0..pos0+n-1, as [n][heads*d_head] float32."""
+        cfg = (self.pair.large if which == LARGE or self.pair.small is None else self.pair.small).cfg
+        out = np.zeros((n, cfg.n_heads * cfg.d_head), dtype=np.float32)
+        _check(lib().bild_debug_kv(self.h, which, layer, int(is_v), pos0, n, out.ctypes.data), "bild_debug_kv")
         return out
 
     def bench_pass(self, which: int, rows: int, reps: int) -> float:

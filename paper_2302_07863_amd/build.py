@@ -17,9 +17,9 @@ LIB = os.path.join(PKG, "libbild.so")
 # (source, object name, extra defines)
 UNITS = [
     ("kernels.hip", "kernels.o", []),
-    ("pass_kernel.hip", "pass_kernel_f32.o", ["-DBILD_PASS_DT=0"]),
-    ("pass_kernel.hip", "pass_kernel_bf16.o", ["-DBILD_PASS_DT=1"]),
     ("bild_api.hip", "bild_api.o", []),
+    ("head_stats.hip", "head_stats.o", []),
+    ("bench_api.hip", "bench_api.o", []),
     ("layout.cpp", "layout.o", []),
 ]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-pthread",

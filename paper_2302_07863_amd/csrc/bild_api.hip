@@ -14,136 +14,11 @@
 #include <new>
 #include <vector>
 
-#include "bild_internal.h"
+#include "bild_state.h"
 
 using namespace bild;
 
-#define HIPC(expr)                                   \
-    do {                                             \
-        hipError_t e_ = (expr);                      \
-        if (e_ != hipSuccess) return BILD_EHIP;      \
-    } while (0)
-
-namespace {
-
-struct LayerW {
-    const float* ln1 = nullptr;
-    TMat wqkv, wo;
-    const float* lnc = nullptr;
-    TMat cwq, cwkv, cwo;
-    const float* ln2 = nullptr;
-    TMat win, wout;
-};
-
-}  // namespace
-
-struct bild_model {
-    bild_model_config cfg;
-    TMat emb, head;
-    const float* enc_final = nullptr;
-    const float* dec_final = nullptr;
-    const float* enc_rel = nullptr;  // relative-position models: [heads][2*rel_max_dist + 1] score biases of the
-    const float* dec_rel = nullptr;  // encoder's / decoder's self-attention, shared by all layers of the stack
-    std::vector<LayerW> enc, dec;
-    std::vector<void*> allocs;
-    size_t device_bytes = 0;
-    int inner() const { return cfg.n_heads * cfg.d_head; }
-    int esz() const { return cfg.dtype == BILD_DT_BF16 ? 2 : 4; }
-    bool gated() const { return cfg.act != BILD_ACT_RELU; }
-    size_t layer_weight_bytes() const {  // weight matrices of one decoder layer
-        const size_t d = cfg.d_model, I = inner(), F = cfg.d_ff;
-        return (4 * d * I * (cfg.cross_attn ? 2 : 1) + (gated() ? 3 : 2) * d * F) * esz();
-    }
-};
-
-struct bild_pair {
-    bild_model* m[2];  // [0] small, [1] large
-    bool decoder_only;
-    bool small_borrows_encoder;
-    int trunk_layers = 0;        // > 0: early-exit pair, m[0] is a view of m[1]'s first trunk_layers decoder layers
-    bild_model* view = nullptr;  // that view (owned by the pair; it owns no device memory)
-};
-
-namespace {
-
-struct ModelState {
-    const bild_model* m = nullptr;
-    char* kcache = nullptr;  // [L][cap][I]
-    char* vcache = nullptr;
-    char* ck = nullptr;      // cross [L][max_src][I]
-    char* cv = nullptr;
-    float *x = nullptr, *q = nullptr, *a = nullptr, *h = nullptr;  // [rows_cap][d], [rows_cap][I], [rows_cap][I], [rows_cap][F]
-    int rows_cap = kMaxRows;  // rows one decoder pass may carry (the whole prompt for decoder-only prefill)
-    StatPart* part = nullptr;
-    int nparts_cap = 0;
-    float* zt = nullptr;
-    float* dbg = nullptr;     // [32][vocab], only when debugging
-    float* att_o = nullptr;   // split-key partials
-    float* att_ml = nullptr;
-    int max_splits = 1;
-    // encoder scratch (models with an encoder)
-    float* enc_x = nullptr;   // [max_src][d]
-    float* enc_q = nullptr;   // [max_src][I]
-    float* enc_a = nullptr;   // [max_src][I]
-    float* enc_h = nullptr;   // [max_src][F]
-    char* enc_k = nullptr;    // [max_src][I]
-    char* enc_v = nullptr;
-    int last_rows = 0;        // rows of the last LM-head pass (for debug logits)
-};
-
-}  // namespace
-
-struct bild_state {
-    const bild_pair* pair = nullptr;
-    ModelState ms[2];
-    Ctl* ctl = nullptr;   // device
-    Ctl* hctl = nullptr;  // pinned host mirror of the control block, written by the policy kernel
-    int seq_issued = 0;   // passes with a policy kernel enqueued so far (the device counts them in Ctl::seq)
-    Ctl* hctl_dev = nullptr;  // the same buffer as the device sees it
-    float* halpha = nullptr;  // pinned staging for threshold updates
-    float alpha_fb = -1.f, alpha_rb = -1.f;  // thresholds currently in the device control block
-    bool use_graphs = true;
-    bool gemm_only = false;       // measurement: a pass launches only its weight-streaming GEMMs
-    int64_t gemm_count = 0, gemm_bytes = 0;  // tallied while a pass is being issued
-    std::map<std::array<int, 6>, hipGraphExec_t> graphs;  // captured passes by (model, rows, lm rows, mode, key bucket, debug)
-    // persistent pass kernel: stage lists by (model, rows, key bucket, gemm-only), barrier state, settings
-    struct PassProg { Stage* dev = nullptr; int nstages = 0; int G = 0; size_t lds = 0; int64_t gemms = 0, gemm_bytes = 0; };
-    std::map<std::array<int, 4>, PassProg> progs;
-    float top_p = 0.f;         // > 0: sampling variant, tokens are drawn from the nucleus
-    float* u_dev[2] = {nullptr, nullptr};  // uniform number per sequence position, per model
-    float* trunk_x = nullptr;  // early-exit pair: [cap_len][d] hidden state after the trunk's last layer, by position
-    PassSync* psync = nullptr;
-    bool resident[2] = {false, false};  // model w runs its layers in the persistent kernel
-    int resident_G[2] = {0, 0};
-    unsigned long long* ptrace_dev = nullptr;
-    unsigned long long* ptrace = nullptr;  // pinned; stage time stamps of the last persistent pass (tracing builds)
-    int ptrace_wg = 0;
-    int ptrace_stages = 0;
-    std::vector<int> ptrace_kinds;
-    int spin_limit = 1 << 20;  // barrier polls (about a microsecond each) before a wait gives up
-    int* y = nullptr;     // device [max_len + 1]
-    int* src = nullptr;   // device [max_src]
-    hipStream_t stream = nullptr;
-    bool own_stream = false;
-    int max_src = 0, max_len = 0, n_max = 0;
-    int cap_len = 0, cap_src = 0;  // cache capacities: max_len / max_src rounded up to 32 rows
-    // host mirror of the control block (kept exact by reading back after every pass)
-    int y_len = 0, draft_start = 0, len[2] = {0, 0}, n_src = 0, n0 = 0;
-    bool encoded = false;
-    bool debug_logits = false;
-    std::vector<void*> allocs;
-    std::vector<void*> host_allocs;
-    // event bracketing of GEMM launches (measurement only)
-    bool prof_on = false;
-    int prof_cap = 0, prof_used = 0, prof_dropped = 0;
-    std::vector<hipEvent_t> prof_ev;
-    struct ProfRec { int model, cls; int64_t bytes; };
-    std::vector<ProfRec> prof_rec;
-};
-
-namespace {
-
-// ---------------------------------------------------------------- helpers
+namespace bild {
 int dev_alloc(std::vector<void*>& keep, void** p, size_t bytes) {
     void* d = nullptr;
     if (bytes == 0) bytes = 16;
@@ -152,6 +27,11 @@ int dev_alloc(std::vector<void*>& keep, void** p, size_t bytes) {
     *p = d;
     return BILD_OK;
 }
+}  // namespace bild
+
+namespace {
+
+// ---------------------------------------------------------------- helpers
 
 bool config_ok(const bild_model_config& c) {
     if (c.n_dec_layers < 1 || c.n_enc_layers < 0) return false;
@@ -434,41 +314,6 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         const char* ng = std::getenv("BILD_NO_GRAPH");
         s->use_graphs = !(ng && ng[0] == '1');
     }
-#ifdef BILD_TRACE
-    {
-        void* t = nullptr;
-        if (hipHostMalloc(&t, 8 * 8 * 1024, hipHostMallocMapped) == hipSuccess) {
-            s->host_allocs.push_back(t);
-            std::memset(t, 0, 8 * 8 * 1024);
-            s->ptrace = (unsigned long long*)t;
-            void* td = nullptr;
-            if (hipHostGetDevicePointer(&td, t, 0) == hipSuccess) s->ptrace_dev = (unsigned long long*)td;
-            const char* tw = std::getenv("BILD_TRACE_WG");
-            s->ptrace_wg = tw ? std::atoi(tw) : 0;
-        }
-    }
-#endif
-    AL(s->psync, sizeof(PassSync));
-    if (hipMemsetAsync(s->psync, 0, sizeof(PassSync), s->stream) != hipSuccess) {
-        bild_state_destroy(s);
-        return BILD_EHIP;
-    }
-    {
-        // BILD_RESIDENT=1 runs the layers of a pass in the persistent kernel instead of one kernel per
-        // stage.  Off by default: on this chip a workgroup streams at most about 28 GB/s, so bandwidth
-        // needs all 256 CUs, and a grid barrier over that many workgroups plus the cross-XCD hand-over of
-        // the activations costs more than a kernel boundary does (measured: 2.7 ms against 1.2 ms per
-        // T5-large-shaped pass).
-        const char* e = std::getenv("BILD_RESIDENT");
-        const char* eg = std::getenv("BILD_RESIDENT_G");
-        const char* es = std::getenv("BILD_BARRIER_SPIN");
-        if (es) s->spin_limit = std::max(-1, std::atoi(es));  // -1: every barrier wait gives up at once (error-path tests)
-        for (int w = 0; w < 2; ++w) {
-            const bild_model* m = p->m[w];
-            s->resident[w] = e && e[0] == '1' && m->cfg.pos != BILD_POS_RELATIVE;  // the persistent kernel has no score bias
-            s->resident_G[w] = eg ? std::min(256, std::max(1, std::atoi(eg))) : (m->cfg.d_model >= 1024 ? 64 : 32);
-        }
-    }
     for (int w = 0; w < 2; ++w) {
         ModelState& M = s->ms[w];
         const bild_model* m = p->m[w];
@@ -522,7 +367,6 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         s->ms[0].ck = s->ms[1].ck;
         s->ms[0].cv = s->ms[1].cv;
         AL(s->trunk_x, sizeof(float) * (size_t)s->cap_len * p->m[1]->cfg.d_model);
-        s->resident[0] = s->resident[1] = false;  // the persistent kernel does not know the trunk hand-over
     }
 #undef ALZ
 #undef AL
@@ -569,15 +413,16 @@ int set_alpha(bild_state* s, float fb, float rb) {
 
 // Waits for the last pass; its policy kernel has mirrored the control block into pinned host memory.  The mirror's pass
 // counter is polled first (the kernel writes it last, behind a system-wide fence): that sees the result a few
-// microseconds before the stream's completion reaches the host.  If the count does not arrive in time (a persistent
-// kernel that gave up, a failed launch) the stream is waited for as usual and the two counts are brought together again.
+// microseconds before the stream's completion reaches the host.  If the count does not arrive in time (a failed
+// launch) the stream is waited for as usual and the two counts are brought together again.
 int pull_ctl(bild_state* s) {
     bool seen = false;
     {
-        const volatile int* seq = &s->hctl->seq;
+        const int* seq = &s->hctl->seq;
         const auto t0 = std::chrono::steady_clock::now();
         for (unsigned spins = 1;; ++spins) {
-            if (*seq == s->seq_issued) {
+            // acquire: the other words of the mirror are read after the count that was written behind them
+            if (__atomic_load_n(seq, __ATOMIC_ACQUIRE) == s->seq_issued) {
                 seen = true;
                 break;
             }
@@ -586,14 +431,7 @@ int pull_ctl(bild_state* s) {
     }
     if (!seen) {
         HIPC(hipStreamSynchronize(s->stream));
-        s->seq_issued = s->hctl->seq;
-    }
-    if (s->hctl->fault) {
-        // a grid barrier of the persistent kernel gave up: its counters are meaningless now
-        (void)hipMemset(s->psync, 0, sizeof(PassSync));
-        (void)hipMemset(&s->ctl->fault, 0, sizeof(int));
-        s->hctl->fault = 0;
-        return BILD_EHIP;
+        s->seq_issued = __atomic_load_n(&s->hctl->seq, __ATOMIC_ACQUIRE);
     }
     s->y_len = s->hctl->y_len;
     s->draft_start = s->hctl->draft_start;
@@ -602,6 +440,9 @@ int pull_ctl(bild_state* s) {
     return BILD_OK;
 }
 
+}  // namespace
+
+namespace bild {
 // Key splits of one attention launch and whether the consumer projection merges them (`defer`).
 // A workgroup's time grows with the K/V bytes it streams (about 2 us for 32 KiB, 3 us for 128 KiB, then in
 // proportion).  Partials merged by the consumer cost no kernel: it works out the normalised weights once per
@@ -627,9 +468,17 @@ int pick_splits_raw(int d_head, int esz, int max_splits, int nkeys, int heads, i
     return sp;
 }
 
+}  // namespace bild
+
+namespace {
+
 int pick_splits(const ModelState& M, int nkeys, int heads, int T, bool* defer) {
     return pick_splits_raw(M.m->cfg.d_head, M.m->esz(), M.max_splits, nkeys, heads, T, defer);
 }
+
+}  // namespace
+
+namespace bild {
 
 int pick_attn_waves(int dtype, int d_head, int T, int nkeys, int splits) {
     // one 32-key block per wave where possible, bounded by the LDS the merge needs
@@ -643,6 +492,10 @@ int pick_attn_waves(int dtype, int d_head, int T, int nkeys, int splits) {
     while (nw > 1 && attn_lds_bytes(dtype, d_head, T, nw) > 96 * 1024) nw /= 2;
     return nw;
 }
+
+}  // namespace bild
+
+namespace {
 
 GemmArgs gemm_base(const bild_model* m, const TMat& W, const float* x, int ldx, int T, const float* gain) {
     GemmArgs g;
@@ -690,71 +543,27 @@ int run_gemm(bild_state* s, const bild_model* m, GemmArgs& g) {
     return launch_gemm_profiled(s, m, g);
 }
 
-// Where the stages of a pass go: launched one kernel each (prog == nullptr), or appended to the
-// stage list of the persistent kernel with launch shapes for its G resident workgroups.
-struct StageSink {
-    std::vector<Stage>* prog = nullptr;
-    int G = 0;
-    size_t lds = 0;  // largest LDS need among the appended stages
-};
-
-int emit_gemm(bild_state* s, const bild_model* m, GemmArgs& g, StageSink& sink) {
-    if (!sink.prog) {
-        gemm_pick_shape(g, m->cfg.dtype);
-        return launch_gemm_profiled(s, m, g);
-    }
-    gemm_pick_shape_resident(g, m->cfg.dtype, sink.G);
-    s->gemm_count += 1;
-    s->gemm_bytes += (int64_t)g.W.n * g.W.k * m->esz();
-    Stage st;
-    std::memset((void*)&st, 0, sizeof(st));
-    st.kind = ST_GEMM;
-    st.nblocks = (int)gemm_num_blocks(g);
-    st.g = g;
-    sink.lds = std::max(sink.lds, gemm_lds_bytes(g, m->cfg.dtype));
-    sink.prog->push_back(st);
-    return BILD_OK;
+int emit_gemm(bild_state* s, const bild_model* m, GemmArgs& g) {
+    gemm_pick_shape(g, m->cfg.dtype);
+    return launch_gemm_profiled(s, m, g);
 }
 
 // `deferred` receives the number of key splits whose partials the following output projection must merge
 // (1: the attention output is complete).
-int emit_attention(bild_state* s, const ModelState& M, AttnArgs& a, int nkeys, StageSink& sink, int* deferred) {
+int emit_attention(bild_state* s, const ModelState& M, AttnArgs& a, int nkeys, int* deferred) {
     const int dt = M.m->cfg.dtype;
     *deferred = 1;
-    if (!sink.prog) {
-        bool defer = false;
-        a.splits = a.T > kMaxRows ? 1 : pick_splits(M, nkeys, a.heads, a.T, &defer);  // row blocks and key splits do not combine
-        a.nw = pick_attn_waves(dt, a.d_head, std::min(a.T, kMaxRows), nkeys, a.splits);
-        a.defer_merge = a.splits > 1 && defer;
-        if (a.defer_merge) *deferred = a.splits;
-        if (!s->gemm_only) HIPC(launch_attention(a, dt, s->stream));
-        return BILD_OK;
-    }
-    if (s->gemm_only) return BILD_OK;
-    // 8 waves per workgroup; split the keys only when a wave would otherwise walk more than four
-    // 32-key blocks and workgroups are free, because a split costs a merge stage and its barrier
-    a.nw = 8;
-    int sp = 1;
-    const int nblk = (nkeys + 31) / 32;
-    while (sp * 2 <= M.max_splits && a.heads * sp * 2 <= sink.G && nblk > sp * 8 * 4) sp *= 2;
-    a.splits = sp;
-    Stage st;
-    std::memset((void*)&st, 0, sizeof(st));
-    st.kind = ST_ATTN;
-    st.nblocks = a.heads * sp;
-    st.a = a;
-    sink.lds = std::max(sink.lds, attn_lds_bytes(dt, a.d_head, a.T, a.nw));
-    sink.prog->push_back(st);
-    if (sp > 1) {
-        st.kind = ST_ATTN_MERGE;
-        st.nblocks = (a.T * (a.i_dim / 4) + 255) / 256;
-        sink.prog->push_back(st);
-    }
+    bool defer = false;
+    a.splits = a.T > kMaxRows ? 1 : pick_splits(M, nkeys, a.heads, a.T, &defer);  // row blocks and key splits do not combine
+    a.nw = pick_attn_waves(dt, a.d_head, std::min(a.T, kMaxRows), nkeys, a.splits);
+    a.defer_merge = a.splits > 1 && defer;
+    if (a.defer_merge) *deferred = a.splits;
+    if (!s->gemm_only) HIPC(launch_attention(a, dt, s->stream));
     return BILD_OK;
 }
 
 // Embedding and all decoder layers of model w over rows y[len .. len+T).
-int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
+int emit_layers(bild_state* s, int w, int T, int key_hint) {
     ModelState& M = s->ms[w];
     const bild_model* m = M.m;
     const bild_model_config& c = m->cfg;
@@ -788,13 +597,6 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
             rc.d = d;
             rc.T = T;
             HIPC(launch_row_copy(rc, s->stream));
-        } else if (sink.prog) {
-            Stage st;
-            std::memset((void*)&st, 0, sizeof(st));
-            st.kind = ST_EMBED;
-            st.nblocks = T;
-            st.e = e;
-            sink.prog->push_back(st);
         } else {
             HIPC(launch_embed(e, dt, s->stream));
         }
@@ -815,7 +617,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
             g.vcap = s->cap_len;
             g.pos_ptr = len_ptr;
             g.rope = c.pos == BILD_POS_ROPE;
-            int rc = emit_gemm(s, m, g, sink);
+            int rc = emit_gemm(s, m, g);
             if (rc) return rc;
         }
         {
@@ -830,7 +632,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
             a.vcap = s->cap_len;
             a.part_o = M.att_o; a.part_ml = M.att_ml;
             a.scale = att_scale;
-            int rc = emit_attention(s, M, a, key_hint, sink, &merge_splits);
+            int rc = emit_attention(s, M, a, key_hint, &merge_splits);
             if (rc) return rc;
         }
         {
@@ -839,7 +641,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
             g.out = M.x;
             g.ldo = d;
             if (merge_splits > 1) { g.mg_splits = merge_splits; g.mg_o = M.att_o; g.mg_ml = M.att_ml; g.mg_heads = c.n_heads; }
-            int rc = emit_gemm(s, m, g, sink);
+            int rc = emit_gemm(s, m, g);
             if (rc) return rc;
         }
         if (c.cross_attn) {
@@ -848,7 +650,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
                 g.epi = EPI_STORE;
                 g.out = M.q;
                 g.ldo = I;
-                int rc = emit_gemm(s, m, g, sink);
+                int rc = emit_gemm(s, m, g);
                 if (rc) return rc;
             }
             {
@@ -864,7 +666,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
                 a.len_ptr = &s->ctl->n_src;
                 a.part_o = M.att_o; a.part_ml = M.att_ml;
                 a.scale = att_scale;
-                int rc = emit_attention(s, M, a, s->n_src, sink, &merge_splits);
+                int rc = emit_attention(s, M, a, s->n_src, &merge_splits);
                 if (rc) return rc;
             }
             {
@@ -873,7 +675,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
                 g.out = M.x;
                 g.ldo = d;
                 if (merge_splits > 1) { g.mg_splits = merge_splits; g.mg_o = M.att_o; g.mg_ml = M.att_ml; g.mg_heads = c.n_heads; }
-                int rc = emit_gemm(s, m, g, sink);
+                int rc = emit_gemm(s, m, g);
                 if (rc) return rc;
             }
         }
@@ -882,7 +684,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
             g.epi = EPI_ACT;
             g.out = M.h;
             g.ldo = F;
-            int rc = emit_gemm(s, m, g, sink);
+            int rc = emit_gemm(s, m, g);
             if (rc) return rc;
         }
         {
@@ -890,7 +692,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
             g.epi = EPI_RESID;
             g.out = M.x;
             g.ldo = d;
-            int rc = emit_gemm(s, m, g, sink);
+            int rc = emit_gemm(s, m, g);
             if (rc) return rc;
         }
     }
@@ -907,52 +709,9 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, StageSink& sink) {
     return BILD_OK;
 }
 
-// The stage list of (model, rows, key bucket) for the persistent kernel, built and uploaded on first
-// use.  nstages == 0 marks a pass whose stages do not fit the kernel's LDS: it takes the other path.
-// Must first be called outside stream capture (the upload is a blocking copy).
-int get_program(bild_state* s, int w, int T, int key_hint, const bild_state::PassProg** out) {
-    const std::array<int, 4> key = {w, T, key_hint, s->gemm_only ? 1 : 0};
-    auto it = s->progs.find(key);
-    if (it == s->progs.end()) {
-        std::vector<Stage> prog;
-        StageSink sink;
-        sink.prog = &prog;
-        sink.G = s->resident_G[w];
-        const int64_t c0 = s->gemm_count, b0 = s->gemm_bytes;
-        int rc = emit_layers(s, w, T, key_hint, sink);
-        s->gemm_count = c0;  // tallied again by the pass that runs the list
-        s->gemm_bytes = b0;
-        if (rc) return rc;
-#ifdef BILD_TRACE
-        if (const char* ts = std::getenv("BILD_TRACE_STAGE")) {  // in-body stamps of one stage, kept after the per-stage ones
-            const int i = std::atoi(ts);
-            if (i >= 0 && i < (int)prog.size() && s->ptrace_dev) {
-                if (prog[i].kind == ST_GEMM) { prog[i].g.trace = s->ptrace_dev + 8 * 1000; prog[i].g.trace_block = s->ptrace_wg; }
-                if (prog[i].kind == ST_ATTN) prog[i].a.trace = s->ptrace_dev + 8 * 1000;
-            }
-        }
-#endif
-        bild_state::PassProg pp;
-        if (!prog.empty() && kPassArgLds + sink.lds <= pass_lds_limit()) {
-            void* d = nullptr;
-            rc = dev_alloc(s->allocs, &d, prog.size() * sizeof(Stage));
-            if (rc) return rc;
-            HIPC(hipMemcpy(d, prog.data(), prog.size() * sizeof(Stage), hipMemcpyHostToDevice));
-            pp.dev = (Stage*)d;
-            pp.nstages = (int)prog.size();
-            pp.G = sink.G;
-            pp.lds = sink.lds;
-            for (const Stage& st : prog)
-                if (st.kind == ST_GEMM) {
-                    pp.gemms += 1;
-                    pp.gemm_bytes += (int64_t)st.g.W.n * st.g.W.k * s->ms[w].m->esz();
-                }
-        }
-        it = s->progs.emplace(key, pp).first;
-    }
-    *out = &it->second;
-    return BILD_OK;
-}
+}  // namespace
+
+namespace bild {
 
 // One decoder pass of model w over rows y[len .. len+T): embed, layers, and (lm_rows > 0)
 // the LM head over the last lm_rows rows followed by the policy `mode`; lm_rows == 0
@@ -963,28 +722,8 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
     const bild_model_config& c = m->cfg;
     const int d = c.d_model, dt = c.dtype;
     const int* len_ptr = &s->ctl->len[w];
-    const bild_state::PassProg* pp = nullptr;
-    if (s->resident[w] && !s->prof_on && T <= kMaxRows) {
-        int rc = get_program(s, w, T, key_hint, &pp);
-        if (rc) return rc;
-        if (pp->nstages == 0) pp = nullptr;
-    }
-    if (pp) {
-        PassArgs pa;
-        pa.prog = pp->dev;
-        pa.nstages = pp->nstages;
-        pa.sync = s->psync;
-        pa.fault = &s->ctl->fault;
-        pa.spin_limit = s->spin_limit;
-        pa.trace = s->ptrace_dev;
-        pa.trace_wg = s->ptrace_wg;
-        s->ptrace_stages = pp->nstages;
-        HIPC(launch_pass(pa, dt, T, c.d_head, pp->G, pp->lds, s->stream));
-        s->gemm_count += pp->gemms;
-        s->gemm_bytes += pp->gemm_bytes;
-    } else {
-        StageSink direct;
-        int rc = emit_layers(s, w, T, key_hint, direct);
+    {
+        int rc = emit_layers(s, w, T, key_hint);
         if (rc) return rc;
     }
     FinishArgs f;
@@ -1040,8 +779,6 @@ int key_bucket(int nkeys) {
 // One pass, replayed from a captured graph when possible.  Launch parameters that depend on the cache
 // length are chosen per power-of-two bucket of the key count, so a graph stays valid while the
 // sequence grows inside its bucket; everything else the kernels need they read from the control block.
-int catch_up(bild_state* s, int w, int target);
-
 int run_pass(bild_state* s, int w, int T, int lm_rows, int mode) {
     if (s->pair->trunk_layers > 0 && w == 1 && s->len[0] < s->len[1] + T) {
         // early-exit pair: the upper layers continue from what the trunk left for these rows
@@ -1058,11 +795,6 @@ int run_pass(bild_state* s, int w, int T, int lm_rows, int mode) {
     const std::array<int, 6> key = {w, T, lm_rows, mode, bucket, (s->debug_logits ? 1 : 0) | (s->gemm_only ? 2 : 0) | (s->top_p > 0.f ? 4 : 0)};
     auto it = s->graphs.find(key);
     if (it == s->graphs.end()) {
-        if (s->resident[w] && T <= kMaxRows) {  // the stage list is uploaded with a blocking copy: not inside a capture
-            const bild_state::PassProg* pp = nullptr;
-            const int rc = get_program(s, w, T, bucket, &pp);
-            if (rc) return rc;
-        }
         hipGraph_t g = nullptr;
         HIPC(hipStreamBeginCapture(s->stream, hipStreamCaptureModeThreadLocal));
         const int rc = decoder_pass(s, w, T, lm_rows, mode, bucket);
@@ -1092,6 +824,10 @@ int catch_up(bild_state* s, int w, int target) {
     }
     return BILD_OK;
 }
+
+}  // namespace bild
+
+namespace {
 
 // Encoder of model w over the source in s->src, then the cross K/V of every decoder
 // layer of each model that uses this encoder's output.
@@ -1510,269 +1246,28 @@ extern "C" int bild_debug_logits(bild_state* s, int which, int row, float* out) 
     return BILD_OK;
 }
 
-extern "C" int bild_bench_pass(bild_state* s, int which, int rows, int reps, float* ms_per_pass) {
-    if (!s || !ms_per_pass || which < 1 || which > 2 || rows < 1 || rows > kMaxRows || reps < 1) return BILD_EINVAL;
+extern "C" int bild_debug_kv(bild_state* s, int which, int layer, int is_v, int pos0, int n, float* out) {
+    if (!s || !out || which < 1 || which > 2 || n < 1 || pos0 < 0) return BILD_EINVAL;
     if (!s->encoded) return BILD_ESTATE;
-    const int w = which - 1;
-    if (s->y_len - s->len[w] < rows) return BILD_ESTATE;
-    int rc = catch_up(s, w, s->y_len - rows);  // the timed passes cover exactly the last `rows` tokens
-    if (rc) return rc;
-    hipEvent_t e0, e1;
-    HIPC(hipEventCreate(&e0));
-    HIPC(hipEventCreate(&e1));
-    rc = run_pass(s, w, rows, rows, 4);  // warm-up (and graph capture)
-    if (rc == BILD_OK && hipEventRecord(e0, s->stream) != hipSuccess) rc = BILD_EHIP;
-    for (int i = 0; i < reps && rc == BILD_OK; ++i) rc = run_pass(s, w, rows, rows, 4);
-    if (rc == BILD_OK && hipEventRecord(e1, s->stream) != hipSuccess) rc = BILD_EHIP;
-    if (rc == BILD_OK && hipEventSynchronize(e1) != hipSuccess) rc = BILD_EHIP;
-    float ms = 0.f;
-    if (rc == BILD_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = BILD_EHIP;
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    if (rc) return rc;
-    *ms_per_pass = ms / (float)reps;
-#ifdef BILD_TRACE
-    if (s->ptrace && s->resident[w] && s->ptrace_stages > 1) {
-        // stamps (10 ns ticks): 0 stage start, 1 body done, 2 workgroup barrier, 3 release, 4 all arrived, 5 acquire, 6 out
-        double sum[7] = {0, 0, 0, 0, 0, 0, 0};
-        const int n = std::min(s->ptrace_stages, 1024) - 1;
-        for (int i = 0; i < n; ++i) {
-            const unsigned long long* t = s->ptrace + (size_t)i * 8;
-            for (int j = 1; j <= 6; ++j) sum[j] += (double)(t[j] - t[j - 1]) * 0.01;
-            sum[0] += (double)(s->ptrace[(size_t)(i + 1) * 8] - t[6]) * 0.01;
-            if (i < 20)
-                std::fprintf(stderr, "[trace] stage %3d body %.2f sync %.2f release %.2f arrive+wait %.2f acquire %.2f sync %.2f next %.2f us\n", i,
-                             (t[1] - t[0]) * 0.01, (t[2] - t[1]) * 0.01, (t[3] - t[2]) * 0.01, (t[4] - t[3]) * 0.01,
-                             (t[5] - t[4]) * 0.01, (t[6] - t[5]) * 0.01, (s->ptrace[(size_t)(i + 1) * 8] - t[6]) * 0.01);
-        }
-        if (std::getenv("BILD_TRACE_STAGE")) {
-            const int i = std::atoi(std::getenv("BILD_TRACE_STAGE"));
-            const unsigned long long* b = s->ptrace + 8 * 1000;
-            const unsigned long long t0 = s->ptrace[(size_t)i * 8];
-            std::fprintf(stderr, "[trace] inside stage %d (us after stage start): entry %.2f staged %.2f synced %.2f streamed %.2f reduced %.2f end %.2f\n", i,
-                         (double)(long long)(b[0] - t0) * 0.01, (double)(long long)(b[1] - t0) * 0.01, (double)(long long)(b[2] - t0) * 0.01,
-                         (double)(long long)(b[3] - t0) * 0.01, (double)(long long)(b[4] - t0) * 0.01, (double)(long long)(b[5] - t0) * 0.01);
-        }
-        std::fprintf(stderr, "[trace] model %d rows %d wg %d: %d stages; mean us: body %.2f sync %.2f release %.2f arrive+wait %.2f acquire %.2f sync %.2f next-start %.2f\n",
-                     w, rows, s->ptrace_wg, n + 1, sum[1] / n, sum[2] / n, sum[3] / n, sum[4] / n, sum[5] / n, sum[6] / n, sum[0] / n);
-    }
-#endif
-    return BILD_OK;
-}
-
-extern "C" int bild_bench_gemm(bild_state* s, int which, int rows, int reps, float* ms_per_pass, int64_t* launches,
-                               int64_t* bytes) {
-    if (!s || !ms_per_pass || !launches || !bytes || which < 1 || which > 2 || rows < 1 || rows > kMaxRows || reps < 1)
-        return BILD_EINVAL;
-    if (!s->encoded) return BILD_ESTATE;
-    const int w = which - 1;
-    if (s->y_len - s->len[w] < rows) return BILD_ESTATE;
-    int rc = catch_up(s, w, s->y_len - rows);
-    if (rc) return rc;
-    hipEvent_t e0, e1;
-    HIPC(hipEventCreate(&e0));
-    HIPC(hipEventCreate(&e1));
-    s->gemm_only = true;
-    s->gemm_count = s->gemm_bytes = 0;
-    const bool graphs = s->use_graphs;
-    s->use_graphs = false;
-    rc = decoder_pass(s, w, rows, rows, 4, key_bucket(s->len[w] + rows));  // count the launches of one pass
-    s->use_graphs = graphs;
-    *launches = s->gemm_count;
-    *bytes = s->gemm_bytes;
-    if (rc == BILD_OK) rc = run_pass(s, w, rows, rows, 4);  // warm-up / capture
-    if (rc == BILD_OK && hipEventRecord(e0, s->stream) != hipSuccess) rc = BILD_EHIP;
-    for (int i = 0; i < reps && rc == BILD_OK; ++i) rc = run_pass(s, w, rows, rows, 4);
-    if (rc == BILD_OK && hipEventRecord(e1, s->stream) != hipSuccess) rc = BILD_EHIP;
-    if (rc == BILD_OK && hipEventSynchronize(e1) != hipSuccess) rc = BILD_EHIP;
-    s->gemm_only = false;
-    float ms = 0.f;
-    if (rc == BILD_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = BILD_EHIP;
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    if (rc) return rc;
-    *ms_per_pass = ms / (float)reps;
-    return BILD_OK;
-}
-
-extern "C" int bild_gemm_tally(bild_state* s, int64_t* launches, int64_t* bytes, int reset) {
-    if (!s || !launches || !bytes) return BILD_EINVAL;
-    *launches = s->gemm_count;
-    *bytes = s->gemm_bytes;
-    if (reset) s->gemm_count = s->gemm_bytes = 0;
-    return BILD_OK;
-}
-
-extern "C" int bild_probe_launch(bild_state* s, int reps, float* us_per_launch) {
-    if (!s || reps < 1 || !us_per_launch) return BILD_EINVAL;
-    hipEvent_t e0, e1;
-    HIPC(hipEventCreate(&e0));
-    HIPC(hipEventCreate(&e1));
-    int rc = BILD_OK;
-    for (int i = 0; i < 16 && rc == BILD_OK; ++i)
-        if (launch_probe_empty(s->stream) != hipSuccess) rc = BILD_EHIP;
-    if (rc == BILD_OK && hipEventRecord(e0, s->stream) != hipSuccess) rc = BILD_EHIP;
-    for (int i = 0; i < reps && rc == BILD_OK; ++i)
-        if (launch_probe_empty(s->stream) != hipSuccess) rc = BILD_EHIP;
-    if (rc == BILD_OK && hipEventRecord(e1, s->stream) != hipSuccess) rc = BILD_EHIP;
-    if (rc == BILD_OK && hipEventSynchronize(e1) != hipSuccess) rc = BILD_EHIP;
-    float ms = 0.f;
-    if (rc == BILD_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = BILD_EHIP;
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    if (rc == BILD_OK) *us_per_launch = ms * 1e3f / (float)reps;
-    return rc;
-}
-
-extern "C" int bild_probe_stream(bild_state* s, int groups, int kib_per_group, int reps, float* us_per_launch) {
-    if (!s || !us_per_launch || groups < 1 || groups > 4096 || kib_per_group < 1 || kib_per_group > (1 << 16) || reps < 1 || reps > 64)
-        return BILD_EINVAL;
-    // every launch reads a region no earlier launch touched, so nothing comes from a cache
-    const size_t per_launch = (size_t)groups * kib_per_group * 1024;
-    if (per_launch * (size_t)(reps + 1) > ((size_t)16 << 30)) return BILD_EINVAL;
-    void *buf = nullptr, *sink = nullptr;
-    if (hipMalloc(&buf, per_launch * (reps + 1)) != hipSuccess) return BILD_ENOMEM;
-    if (hipMalloc(&sink, 64) != hipSuccess) {
-        (void)hipFree(buf);
-        return BILD_ENOMEM;
-    }
-    int rc = BILD_OK;
-    if (hipMemsetAsync(buf, 0, per_launch * (reps + 1), s->stream) != hipSuccess) rc = BILD_EHIP;
-    if (rc == BILD_OK && launch_probe_stream(buf, (size_t)kib_per_group, groups, sink, s->stream) != hipSuccess) rc = BILD_EHIP;  // warm-up
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (rc == BILD_OK && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)) rc = BILD_EHIP;
-    float total_ms = 0.f;
-    // one bracket around all launches: launches on one stream run one after the other, so the mean holds the same
-    // launch-to-launch gap a stage of a pass pays, and not the cost of the events
-    if (rc == BILD_OK && hipEventRecord(e0, s->stream) != hipSuccess) rc = BILD_EHIP;
-    for (int i = 0; i < reps && rc == BILD_OK; ++i) {
-        const char* region = (const char*)buf + per_launch * (size_t)(i + 1);
-        if (launch_probe_stream(region, (size_t)kib_per_group, groups, sink, s->stream) != hipSuccess) rc = BILD_EHIP;
-    }
-    if (rc == BILD_OK && (hipEventRecord(e1, s->stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
-                          hipEventElapsedTime(&total_ms, e0, e1) != hipSuccess))
-        rc = BILD_EHIP;
-    if (e0) (void)hipEventDestroy(e0);
-    if (e1) (void)hipEventDestroy(e1);
-    (void)hipStreamSynchronize(s->stream);
-    (void)hipFree(buf);
-    (void)hipFree(sink);
-    if (rc == BILD_OK) *us_per_launch = total_ms * 1e3f / (float)reps;
-    return rc;
-}
-
-extern "C" int bild_probe_copy(bild_state* s, int64_t bytes, int reps) {
-    if (!s || bytes < 16 || bytes % 16 || reps < 1) return BILD_EINVAL;
-    void *a = nullptr, *b = nullptr;
-    if (hipMalloc(&a, (size_t)bytes) != hipSuccess) return BILD_ENOMEM;
-    if (hipMalloc(&b, (size_t)bytes) != hipSuccess) {
-        (void)hipFree(a);
-        return BILD_ENOMEM;
-    }
-    int rc = BILD_OK;
-    if (hipMemsetAsync(a, 1, (size_t)bytes, s->stream) != hipSuccess) rc = BILD_EHIP;
-    for (int i = 0; i < reps && rc == BILD_OK; ++i)
-        if (launch_probe_copy(a, b, (size_t)bytes, s->stream) != hipSuccess) rc = BILD_EHIP;
-    if (hipStreamSynchronize(s->stream) != hipSuccess) rc = BILD_EHIP;
-    (void)hipFree(a);
-    (void)hipFree(b);
-    return rc;
-}
-
-extern "C" int bild_profile_begin(bild_state* s, int max_records) {
-    if (!s || max_records < 1 || max_records > (1 << 20)) return BILD_EINVAL;
-    if (s->prof_on) return BILD_ESTATE;
-    while ((int)s->prof_ev.size() < 2 * max_records) {
-        hipEvent_t e;
-        HIPC(hipEventCreate(&e));
-        s->prof_ev.push_back(e);
-    }
-    s->prof_cap = max_records;
-    s->prof_used = 0;
-    s->prof_dropped = 0;
-    s->prof_rec.clear();
-    s->prof_on = true;
-    return BILD_OK;
-}
-
-extern "C" int bild_profile_end(bild_state* s, bild_profile* out) {
-    if (!s || !out) return BILD_EINVAL;
-    if (!s->prof_on) return BILD_ESTATE;
-    s->prof_on = false;
+    const ModelState& M = s->ms[which - 1];
+    const bild_model* m = M.m;
+    // an early-exit pair keeps the trunk's rows in the large model's buffers: the view has its own layer count
+    if (layer < 0 || layer >= m->cfg.n_dec_layers || pos0 + n > s->len[which - 1]) return BILD_EINVAL;
+    const size_t I = m->inner(), esz = m->esz(), cap = s->cap_len;
+    std::vector<char> raw((size_t)(is_v ? I * cap : (size_t)n * I) * esz);
+    const char* base = (is_v ? M.vcache : M.kcache) + (size_t)layer * cap * I * esz;
     HIPC(hipStreamSynchronize(s->stream));
-    std::memset(out, 0, sizeof(*out));
-    for (int i = 0; i < s->prof_used; ++i) {
-        float ms = 0.f;
-        HIPC(hipEventElapsedTime(&ms, s->prof_ev[2 * i], s->prof_ev[2 * i + 1]));
-        const auto& r = s->prof_rec[i];
-        out->launches[r.model][r.cls] += 1;
-        out->bytes[r.model][r.cls] += r.bytes;
-        out->ms[r.model][r.cls] += ms;
-    }
-    out->dropped = s->prof_dropped;
-    return BILD_OK;
-}
-
-extern "C" int64_t bild_pass_bytes(const bild_state* s, int which, int t_cache, int rows) {
-    if (!s || which < 1 || which > 2) return BILD_EINVAL;
-    const bild_model* m = s->ms[which - 1].m;
-    const bild_model_config& c = m->cfg;
-    const int64_t d = c.d_model, I = m->inner(), F = c.d_ff, B = m->esz();
-    // an early-exit pair's large pass runs the layers above the trunk only
-    const int64_t L = c.n_dec_layers - (which == 2 ? s->pair->trunk_layers : 0);
-    const int64_t attn = 4 * d * I * (c.cross_attn ? 2 : 1);
-    const int64_t ffn = (m->gated() ? 3 : 2) * d * F;
-    int64_t elems = L * (attn + ffn) + (int64_t)c.vocab * d + L * 2 * I * (int64_t)(t_cache + rows);
-    if (c.cross_attn) elems += L * 2 * I * (int64_t)s->n_src;
-    return elems * B;
-}
-
-extern "C" int64_t bild_debug_tiled_bytes(int n, int k, int dtype) {
-    if (n < 1 || k < 32 || k % 32 || dtype < 0 || dtype > 1) return BILD_EINVAL;
-    return (int64_t)tiled_bytes(n, k, dtype);
-}
-
-extern "C" int bild_debug_tile_matrix(const float* src, int src_is_k_by_n, int n, int k, int dtype, void* dst) {
-    if (!src || !dst || n < 1 || k < 32 || k % 32 || dtype < 0 || dtype > 1) return BILD_EINVAL;
-    tile_matrix(src, src_is_k_by_n != 0, n, k, dtype, dst);
-    return BILD_OK;
-}
-
-extern "C" int bild_debug_gemm_shape(int n, int k, int rows, int gated, int lm_head, int dtype, int32_t out[8]) {
-    if (!out || n < 1 || k < 32 || k % 32 || rows < 1 || dtype < 0 || dtype > 1) return BILD_EINVAL;
-    if (lm_head && rows > kMaxRows) return BILD_EINVAL;
-    GemmArgs g;
-    std::memset((void*)&g, 0, sizeof(g));
-    const int kt = dtype ? 32 : 16;
-    g.W.n = gated ? 2 * n : n;  // gate and linear branch interleaved by tile
-    g.W.k = k;
-    g.W.tn = (g.W.n + 15) / 16;
-    g.W.tk = k / kt;
-    g.T = rows;
-    g.epi = lm_head ? EPI_LMHEAD : (gated ? EPI_ACT : EPI_STORE);
-    g.act = gated ? BILD_ACT_SWIGLU : BILD_ACT_RELU;
-    gemm_pick_shape(g, dtype);
-    out[0] = g.wk;
-    out[1] = g.nwv;
-    out[2] = g.rw;
-    out[3] = g.kc;
-    out[4] = (int32_t)gemm_num_blocks(g);
-    out[5] = (rows + kMaxRows - 1) / kMaxRows;
-    out[6] = (int32_t)gemm_lds_bytes(g, dtype);
-    out[7] = 160 * 1024;
-    return BILD_OK;
-}
-
-extern "C" int bild_debug_attn_shape(int heads, int d_head, int rows, int nkeys, int max_splits, int dtype, int32_t out[4]) {
-    if (!out || heads < 1 || d_head < 8 || d_head > 128 || rows < 1 || nkeys < 1 || max_splits < 1 || dtype < 0 || dtype > 1)
-        return BILD_EINVAL;
-    bool defer = false;
-    const int sp = rows > kMaxRows ? 1 : pick_splits_raw(d_head, dtype ? 2 : 4, max_splits, nkeys, heads, rows, &defer);
-    const int nw = pick_attn_waves(dtype, d_head, std::min(rows, kMaxRows), nkeys, sp);
-    out[0] = sp;
-    out[1] = (sp > 1 && defer) ? 1 : 0;
-    out[2] = nw;
-    out[3] = (int32_t)attn_lds_bytes(dtype, d_head, std::min(rows, kMaxRows), nw);
+    // K is [position][I]; V is stored transposed, [I][capacity]
+    HIPC(hipMemcpy(raw.data(), is_v ? base : base + (size_t)pos0 * I * esz, raw.size(), hipMemcpyDeviceToHost));
+    auto widen = [&](size_t idx) -> float {
+        if (esz == 4) return ((const float*)raw.data())[idx];
+        const uint32_t u = (uint32_t)((const uint16_t*)raw.data())[idx] << 16;
+        float f;
+        std::memcpy(&f, &u, 4);
+        return f;
+    };
+    for (int t = 0; t < n; ++t)
+        for (size_t i = 0; i < I; ++i) out[(size_t)t * I + i] = is_v ? widen(i * cap + pos0 + t) : widen((size_t)t * I + i);
     return BILD_OK;
 }
 

@@ -42,7 +42,7 @@ struct Ctl {
     int res_r;
     int res_n;
     float res_pmax;
-    int fault;        // set by the persistent pass kernel when a grid barrier gave up waiting
+    int pad0;
     float res_nll[kMaxRows];
     int res_rowtok[kMaxRows];  // argmax of every row of the last pass
     int seq;          // passes finished so far; the LAST word, and the last one the policy kernel mirrors to the host
@@ -108,8 +108,6 @@ struct GemmArgs {
     int nwv;  // waves per workgroup = wk * feature groups (4 or 8)
     int rw;   // feature tiles per wave (1, or 2 for gated FFNs)
     int kc;   // inputs staged in LDS per chunk
-    unsigned long long* trace;  // kernel-internal time stamps (only read when built with BILD_TRACE)
-    int trace_block;            // which feature-tile group records them
 };
 
 struct AttnArgs {
@@ -133,7 +131,6 @@ struct AttnArgs {
     // row_pos = base + t (causal) or base_add + t (not causal).  Null: no bias.
     const float* rel_bias;      // [heads][2*rel_d + 1]
     int rel_d;
-    unsigned long long* trace;  // kernel-internal time stamps (only read when built with BILD_TRACE)
 };
 
 struct EmbedArgs {
@@ -177,43 +174,6 @@ struct FinishArgs {
     const float* u;       // uniform number per sequence position, for the model of this pass
 };
 
-// ---- persistent pass kernel: one launch walks a device-resident list of stages, its workgroups
-// meeting at a grid barrier between stages (pass_kernel.hip) ----
-enum StageKind : int { ST_EMBED = 0, ST_GEMM = 1, ST_ATTN = 2, ST_ATTN_MERGE = 3 };
-
-struct Stage {
-    int kind;
-    int nblocks;  // units of work of the stage; workgroup b takes units b, b + G, ...
-    int pad[2];
-    GemmArgs g;   // ST_GEMM
-    AttnArgs a;   // ST_ATTN, ST_ATTN_MERGE
-    EmbedArgs e;  // ST_EMBED
-};
-
-// Barrier state of one request.  `arrivals` only ever grows (compared modulo 2^32); `epoch` is its
-// value when the previous launch ended, read by every workgroup of the next launch as its base.
-struct PassSync {
-    unsigned arrivals;
-    unsigned pad0[31];
-    unsigned epoch;
-    unsigned pad1[31];
-};
-
-struct PassArgs {
-    const Stage* prog;
-    int nstages;
-    PassSync* sync;
-    int* fault;      // set to 1 if a barrier wait ran out (then every workgroup leaves early)
-    int spin_limit;  // polls before a barrier wait gives up
-    unsigned long long* trace;  // [nstages][8] time stamps of workgroup trace_wg (only read when built with BILD_TRACE)
-    int trace_wg;
-};
-
-constexpr int kPassArgLds = 0;  // LDS the pass kernel keeps for itself ahead of the stages' own
-hipError_t launch_pass(const PassArgs& p, int dtype, int T, int d_head, int G, size_t stage_lds, hipStream_t st);
-size_t pass_lds_limit();
-// launch shape of a GEMM stage inside the persistent kernel (always 8 waves; at most G units if possible)
-void gemm_pick_shape_resident(GemmArgs& a, int dtype, int G);
 size_t gemm_lds_bytes(const GemmArgs& a, int dtype);
 
 // launch wrappers (kernels.hip); each returns the hipError_t of the launch
@@ -222,9 +182,6 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st);
 hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st);
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st);
 hipError_t launch_row_copy(const RowCopyArgs& a, hipStream_t st);
-hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
-hipError_t launch_probe_empty(hipStream_t st);
-hipError_t launch_probe_stream(const void* src, size_t kib_per_group, int groups, void* sink, hipStream_t st);
 hipError_t kernels_init();  // one-time function attributes; call before any stream capture
 size_t gemm_num_blocks(const GemmArgs& a);
 size_t attn_lds_bytes(int dtype, int d_head, int T, int nw);

@@ -6,8 +6,8 @@
 //                    the input fused in front and the consumer (K/V cache append + RoPE,
 //                    activation, residual add, LM-head softmax statistics) fused behind.
 //                    Launched as gemm_kernel (any T <= 32), gemm_row_kernel (T = 1 at compile
-//                    time), gemm_merge_kernel (input still in key-split attention partials)
-//                    and gemm_rows_kernel (encoder / prompt prefill: blocks of 32 rows).
+//                    time), gemm_few_kernel (2-4 rows), gemm_merge_kernel (input still in key-split
+//                    attention partials) and gemm_rows_kernel (encoder / prompt prefill: blocks of 32 rows).
 //   attn_body        KV-cache attention for T query rows of one head (attn_kernel; attn_rows_kernel
 //                    for more than 32 query rows; attn_merge_kernel joins key splits).
 //   embed_kernel     embedding gather + sinusoidal position.
@@ -123,55 +123,13 @@ __device__ __forceinline__ float gelu_tanh_f(float u) {
 __device__ __forceinline__ float silu_f(float u) { return u / (1.f + expf(-u)); }
 
 
-// ---- activation traffic ---------------------------------------------------------------
-// COH = false: ordinary loads and stores (the kernel boundary makes them visible).
-// COH = true (persistent pass kernel): activations pass between workgroups that may sit on
-// different XCDs inside ONE launch, so they move as relaxed agent-scope atomics, which read and
-// write the device-coherent level instead of an XCD's private copy; no cache-wide write-back or
-// invalidate is needed then.  8 bytes is the widest such access.
-template <bool COH>
-__device__ __forceinline__ float4 ld_act4(const float* p) {
-    if constexpr (COH) {
-        const unsigned long long a = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned long long b = __hip_atomic_load((const unsigned long long*)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return make_float4(__uint_as_float((uint32_t)a), __uint_as_float((uint32_t)(a >> 32)),
-                           __uint_as_float((uint32_t)b), __uint_as_float((uint32_t)(b >> 32)));
-    } else {
-        return *(const float4*)p;
-    }
-}
-template <bool COH>
-__device__ __forceinline__ float ld_act(const float* p) {
-    if constexpr (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else return *p;
-}
-template <bool COH>
-__device__ __forceinline__ void st_u64(void* p, uint32_t lo, uint32_t hi) {
-    if constexpr (COH)
-        __hip_atomic_store((unsigned long long*)p, (unsigned long long)lo | ((unsigned long long)hi << 32), __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
-    else
-        *(uint2*)p = make_uint2(lo, hi);
-}
-template <bool COH>
-__device__ __forceinline__ void st_act4(float* p, const float4 v) {
-    if constexpr (COH) {
-        st_u64<true>(p, __float_as_uint(v.x), __float_as_uint(v.y));
-        st_u64<true>(p + 2, __float_as_uint(v.z), __float_as_uint(v.w));
-    } else {
-        *(float4*)p = v;
-    }
-}
-template <bool COH>
-__device__ __forceinline__ void st_act(float* p, float v) {
-    if constexpr (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else *p = v;
-}
-template <bool COH>
-__device__ __forceinline__ void st_u16(uint16_t* p, uint16_t v) {
-    if constexpr (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else *p = v;
-}
+// ---- activation traffic: plain vector loads and stores (the kernel boundary makes them visible) ----
+__device__ __forceinline__ float4 ld_act4(const float* p) { return *(const float4*)p; }
+__device__ __forceinline__ float ld_act(const float* p) { return *p; }
+__device__ __forceinline__ void st_u64(void* p, uint32_t lo, uint32_t hi) { *(uint2*)p = make_uint2(lo, hi); }
+__device__ __forceinline__ void st_act4(float* p, const float4 v) { *(float4*)p = v; }
+__device__ __forceinline__ void st_act(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_u16(uint16_t* p, uint16_t v) { *p = v; }
 
 // =====================================================================================
 // Skinny GEMM.  A workgroup has nwv = wk * wr wavefronts arranged as wr feature groups
@@ -202,13 +160,10 @@ __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
     return gemm_red_bytes(nwv, nacc) + nwv * 32 * 4 + 32 * 4 + nwv * 32 * 16 + 64;
 }
 
-// `vblock` is the index of the feature-tile group this call handles (blockIdx.x in the one-kernel-per-stage
-// launches, a loop index in the persistent pass kernel); `smem` is the workgroup's dynamic LDS.
-// The argument block may live in the kernel-argument segment or (persistent kernel) in constant-address-space
-// device memory, hence the template parameter A.
-template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, false, NT), bool COH = false, int MG = 0,
-          bool ONE = false, bool TWO = true, int TCAP = 0, class A>
-__device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* smem) {
+// `vblock` is the index of the feature-tile group this workgroup handles (blockIdx.x); `smem` is its dynamic LDS.
+template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, false, NT), int MG = 0,
+          bool ONE = false, bool TWO = true, int TCAP = 0>
+__device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, char* smem) {
     constexpr int KT = DT ? 32 : 16;
     // the wave index through readfirstlane: the compiler then knows that it - and every tile index, weight address and
     // range test derived from it - is the same in all lanes, and keeps them in scalar registers
@@ -229,13 +184,12 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
     StatPart* wstat = (StatPart*)(rs + 32);
     char* zblk = (char*)(wstat + NWV * 32);  // 64 bytes of zeros: the activation operand of a tile past the range
 
-    // EPI / ROPE below zero: taken from the arguments at run time (the persistent pass kernel)
-    const int epi = EPI < 0 ? a.epi : EPI;
-    const bool rope = ROPE < 0 ? a.rope != 0 : ROPE != 0;
+    constexpr int epi = EPI;
+    constexpr bool rope = ROPE != 0;
     // Every projection that adds to the residual stream reads un-normalised input and every other one reads through an
-    // RMSNorm, so with a compile-time epilogue the presence of the norm is a compile-time fact as well (the launcher
-    // rejects anything else); a run-time test here would make the gain loads conditional.
-    const bool norm = EPI < 0 ? a.gain != nullptr : EPI != EPI_RESID;
+    // RMSNorm, so the presence of the norm is a compile-time fact (the launcher rejects anything else); a run-time
+    // test here would make the gain loads conditional.
+    constexpr bool norm = EPI != EPI_RESID;
     const bool few = T < 4;  // few rows: all waves share each row and split it along k
     const bool owner = (wkid == 0);
     bool valid[RW];
@@ -246,13 +200,6 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
         wbase[r] = (const char*)a.W.w + ((size_t)min(tile0 + r, a.W.tn - 1) * a.W.tk) * kTileBytes;  // scalar; the lane part is added per load
     }
     const int tok_l = lane & 15, kq = lane >> 4;
-#ifdef BILD_TRACE
-    unsigned long long* tr = (a.trace && vblock == a.trace_block && tid == 0) ? a.trace : nullptr;
-#define STAMP(i) do { if (tr) tr[i] = wall_clock64(); } while (0)
-#else
-#define STAMP(i) do { } while (0)
-#endif
-    STAMP(0);
 
     // ---- weight tiles: two register buffers of U tiles each, requested without any guard ----
     // A tile past the wave's range is read from a clamped (valid) address and cancelled on the activation
@@ -285,7 +232,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
         for (int r = 0; r < RW; ++r)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                old[r][nt] = ld_act4<COH>(a.out + (size_t)min(nt * 16 + tok_l, T - 1) * a.ldo + min(tile0 + r, a.W.tn - 1) * 16 + kq * 4);
+                old[r][nt] = ld_act4(a.out + (size_t)min(nt * 16 + tok_l, T - 1) * a.ldo + min(tile0 + r, a.W.tn - 1) * 16 + kq * 4);
     }
 
     const int pos0 = (a.pos_ptr ? *a.pos_ptr : 0) + a.pos_add;
@@ -363,14 +310,13 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
     // ---- stage x[:, k0 : k0+kc_len] (times the norm gain) into LDS ----
     // Every load is unconditional (clamped index) and every round first requests all its loads, then calls
     // `hook` (first round only), then converts: the hook is where a one-chunk launch requests its weights.
-    const float* gsrc = norm ? a.gain : a.x;  // run-time norm flag only: the "gain" values are then read but not used
     auto noop = [](bool) {};
     auto stage = [&](const int k0, const int kc_len, auto&& hook) {
         const int n4 = kc_len >> 2;
-        auto ldx = [&](int t, int k4) -> float4 { return ld_act4<COH>(a.x + (size_t)t * a.ldx + k0 + k4 * 4); };
+        auto ldx = [&](int t, int k4) -> float4 { return ld_act4(a.x + (size_t)t * a.ldx + k0 + k4 * 4); };
         auto ldg = [&](int k4) -> float4 {
-            if (EPI >= 0 && !norm) return make_float4(0.f, 0.f, 0.f, 0.f);
-            return *(const float4*)(gsrc + k0 + k4 * 4);
+            if (!norm) return make_float4(0.f, 0.f, 0.f, 0.f);
+            return *(const float4*)(a.gain + k0 + k4 * 4);
         };
         // writes one float4 of row t and returns its sum of squares (for the RMSNorm)
         auto put = [&](int t, int k4, float4 w, const float4& gg) -> float {
@@ -406,8 +352,8 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             float m[SP], l[SP];
 #pragma unroll
             for (int sp = 0; sp < SP; ++sp) {
-                m[sp] = ld_act<COH>(a.mg_ml + sp * ml_stride + (size_t)pr * 2);
-                l[sp] = ld_act<COH>(a.mg_ml + sp * ml_stride + (size_t)pr * 2 + 1);
+                m[sp] = ld_act(a.mg_ml + sp * ml_stride + (size_t)pr * 2);
+                l[sp] = ld_act(a.mg_ml + sp * ml_stride + (size_t)pr * 2 + 1);
             }
             auto round = [&](auto np, auto first, int eb, auto&& hk) {
                 constexpr int P = decltype(np)::value;
@@ -420,7 +366,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                     kk[u] = e - tt[u] * n4;
                     const float* op = a.mg_o + (size_t)tt[u] * a.ldx + k0 + kk[u] * 4;
 #pragma unroll
-                    for (int sp = 0; sp < SP; ++sp) o[u][sp] = ld_act4<COH>(op + sp * o_stride);
+                    for (int sp = 0; sp < SP; ++sp) o[u][sp] = ld_act4(op + sp * o_stride);
                 }
                 hk(true);
                 __builtin_amdgcn_sched_barrier(0);  // nothing that uses a loaded value may move above the requests
@@ -597,9 +543,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             second_out = both;
         });
         if (TWO && !second_out) request(B1, wkid + S, nkt0);
-        STAMP(1);
         __syncthreads();
-        STAMP(2);
         if (!TWO) {
             compute_batch(B0, wkid, nkt0);
         } else {
@@ -618,9 +562,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             const int kc_len = min(KC, K - k0);
             if (k0) __syncthreads();  // readers of the previous chunk are done
             stage(k0, kc_len, noop);
-            STAMP(1);
             __syncthreads();
-            STAMP(2);
             // ---- this wave's weight tiles of the chunk: compute one batch while the next one loads ----
             const int kt_base = k0 / KT, nkt = kc_len / KT;
             const int kn_base = (k0 + KC) / KT, nkt_next = (k0 + KC < K) ? min(KC, K - k0 - KC) / KT : 0;
@@ -653,8 +595,6 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
     for (int r = 0; r < RW; ++r)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[r][j] += acc2[r][j];
-
-    STAMP(3);
     // ---- RMSNorm row scales and cross-wave k reduction ----
     if (WK > 1 && !owner) {
 #pragma unroll
@@ -686,8 +626,6 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                         if (j < NT) acc[r][j] += red[((wave + w2) * nacc + r * NT + j) * 64 + lane];
         }
     }
-
-    STAMP(4);
     // ---- epilogue: lane holds features f = tile*16 + kq*4 + v for row t = nt*16 + tok_l ----
     Stat st[2] = {stat_neutral(), stat_neutral()};
 #pragma unroll
@@ -704,7 +642,7 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                     const float g = acc[0][nt][v] * r, u = acc[RW - 1][nt][v] * r;
                     o[v] = (a.act == BILD_ACT_GATED_GELU ? gelu_tanh_f(g) : silu_f(g)) * u;
                 }
-                st_act4<COH>(a.out + (size_t)t * a.ldo + f0, make_float4(o[0], o[1], o[2], o[3]));
+                st_act4(a.out + (size_t)t * a.ldo + f0, make_float4(o[0], o[1], o[2], o[3]));
             }
             continue;
         }
@@ -715,14 +653,14 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             float v4[4] = {acc[rwi][nt][0] * r, acc[rwi][nt][1] * r, acc[rwi][nt][2] * r, acc[rwi][nt][3] * r};
             switch (epi) {
                 case EPI_STORE:
-                    st_act4<COH>(a.out + (size_t)t * a.ldo + n0, make_float4(v4[0], v4[1], v4[2], v4[3]));
+                    st_act4(a.out + (size_t)t * a.ldo + n0, make_float4(v4[0], v4[1], v4[2], v4[3]));
                     break;
                 case EPI_RESID: {
                     const float4 o = old[rwi][nt];
-                    st_act4<COH>(a.out + (size_t)t * a.ldo + n0, make_float4(o.x + v4[0], o.y + v4[1], o.z + v4[2], o.w + v4[3]));
+                    st_act4(a.out + (size_t)t * a.ldo + n0, make_float4(o.x + v4[0], o.y + v4[1], o.z + v4[2], o.w + v4[3]));
                 } break;
                 case EPI_ACT:
-                    st_act4<COH>(a.out + (size_t)t * a.ldo + n0,
+                    st_act4(a.out + (size_t)t * a.ldo + n0,
                                  make_float4(fmaxf(v4[0], 0.f), fmaxf(v4[1], 0.f), fmaxf(v4[2], 0.f), fmaxf(v4[3], 0.f)));
                     break;
                 case EPI_QKV: {
@@ -742,21 +680,21 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
                         }
                     }
                     if (seg == 0) {
-                        st_act4<COH>(a.q_out + (size_t)t * a.i_dim + nn, make_float4(v4[0], v4[1], v4[2], v4[3]));
+                        st_act4(a.q_out + (size_t)t * a.i_dim + nn, make_float4(v4[0], v4[1], v4[2], v4[3]));
                     } else if (seg == 1) {  // K: [position][I]
                         const size_t e = (size_t)pos * a.i_dim + nn;
                         if (DT)
-                            st_u64<COH>((uint16_t*)a.k_cache + e, pack_bf16x2(v4[0], v4[1]), pack_bf16x2(v4[2], v4[3]));
+                            st_u64((uint16_t*)a.k_cache + e, pack_bf16x2(v4[0], v4[1]), pack_bf16x2(v4[2], v4[3]));
                         else
-                            st_act4<COH>((float*)a.k_cache + e, make_float4(v4[0], v4[1], v4[2], v4[3]));
+                            st_act4((float*)a.k_cache + e, make_float4(v4[0], v4[1], v4[2], v4[3]));
                     } else {  // V: transposed, [I][vcap] with the position contiguous
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
                             const size_t e = (size_t)(nn + v) * a.vcap + pos;
                             if (DT)
-                                st_u16<COH>((uint16_t*)a.v_cache + e, (uint16_t)f2bf(v4[v]));
+                                st_u16((uint16_t*)a.v_cache + e, (uint16_t)f2bf(v4[v]));
                             else
-                                st_act<COH>((float*)a.v_cache + e, v4[v]);
+                                st_act((float*)a.v_cache + e, v4[v]);
                         }
                     }
                 } break;
@@ -800,15 +738,13 @@ __device__ __forceinline__ void gemm_body(const A& a, const int vblock, char* sm
             a.part[(size_t)vblock * kMaxRows + a.row_off + tid] = o;
         }
     }
-    STAMP(5);
-#undef STAMP
 }
 
 // SHORT: no wave has more than one batch of tiles - the second weight buffer does not exist (see gemm_row_kernel).
 template <int DT, int RW, int EPI, int ROPE, int NT, bool SHORT = false>
 __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    gemm_body<DT, RW, EPI, ROPE, NT, gemm_batch(RW, false, NT), false, 0, false, !SHORT>(a, (int)blockIdx.x, smem);
+    gemm_body<DT, RW, EPI, ROPE, NT, gemm_batch(RW, false, NT), 0, false, !SHORT>(a, (int)blockIdx.x, smem);
 }
 
 // The single-row pass (the small model's step, the large model's plain step): the row count is a
@@ -824,7 +760,7 @@ constexpr int kShortBatch = 8;
 template <int DT, int RW, int EPI, int ROPE, int VAR = 0>
 __global__ __launch_bounds__(512) void gemm_row_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    gemm_body<DT, RW, EPI, ROPE, 1, VAR ? kShortBatch / RW : gemm_batch(RW, true), false, 0, true, VAR != 1>(a, (int)blockIdx.x, smem);
+    gemm_body<DT, RW, EPI, ROPE, 1, VAR ? kShortBatch / RW : gemm_batch(RW, true), 0, true, VAR != 1>(a, (int)blockIdx.x, smem);
 }
 
 // Two to four rows (the bulk of the large model's review passes) on a single-chunk input: the same body without the
@@ -834,14 +770,14 @@ __global__ __launch_bounds__(512) void gemm_row_kernel(const GemmArgs a) {
 template <int DT, int RW, int EPI, int ROPE, bool SHORT>
 __global__ __launch_bounds__(512) void gemm_few_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    gemm_body<DT, RW, EPI, ROPE, 1, gemm_batch(RW, false, 1), false, 0, false, !SHORT, 4>(a, (int)blockIdx.x, smem);
+    gemm_body<DT, RW, EPI, ROPE, 1, gemm_batch(RW, false, 1), 0, false, !SHORT, 4>(a, (int)blockIdx.x, smem);
 }
 
 // Output projection whose input is still in key-split attention partials (merged while staging).
 template <int DT, int SPLITS, bool SHORT = false>
 __global__ __launch_bounds__(512) void gemm_merge_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    gemm_body<DT, 1, EPI_RESID, 0, 1, gemm_batch(1, false), false, SPLITS, false, !SHORT>(a, (int)blockIdx.x, smem);
+    gemm_body<DT, 1, EPI_RESID, 0, 1, gemm_batch(1, false), SPLITS, false, !SHORT>(a, (int)blockIdx.x, smem);
 }
 
 // More than kMaxRows rows (encoder, prompt prefill): blockIdx.y picks a block of kMaxRows rows and the same
@@ -860,7 +796,6 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const GemmArgs a) {
     gemm_body<DT, RW, EPI, ROPE, 2>(b, (int)blockIdx.x, smem);
 }
 
-#ifndef BILD_DEVICE_ONLY
 // LDS a GEMM workgroup may ask for (a gfx950 compute unit has 160 KiB) and the share of it the staged chunk may take:
 // a longer chunk means fewer chunk boundaries, at each of which the weight stream of the workgroup pauses for the staging.
 constexpr int kGemmLdsLimit = 160 * 1024;
@@ -924,16 +859,6 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     if (wr > 1 && blocks > 256 && blocks < 512 && a.epi != EPI_LMHEAD && a.T == 1) wr /= 2;
     a.wk = wk;
     a.nwv = wk * wr;
-}
-
-// Inside the persistent kernel every workgroup has 8 waves and there are G of them: take the most
-// input slices (shortest run per wave) that still give every feature-tile group a workgroup of its own.
-void gemm_pick_shape_resident(GemmArgs& a, int dtype, int G) {
-    const int tiles_chunk = gemm_pick_chunks(a, dtype);
-    a.nwv = 8;
-    int wk = 8;
-    while (wk > 1 && (wk > tiles_chunk || (a.W.tn + (8 / wk) * a.rw - 1) / ((8 / wk) * a.rw) > G)) wk /= 2;
-    a.wk = wk;
 }
 
 size_t gemm_lds_bytes(const GemmArgs& a, int dtype) {
@@ -1019,26 +944,7 @@ static hipError_t raise_lds_limits() {
     return done;
 }
 
-// persistent pass kernel: one translation unit per storage type (pass_kernel.hip)
-hipError_t launch_pass_dt0(const PassArgs& p, int nt, int dh32, int G, size_t lds, hipStream_t st);
-hipError_t launch_pass_dt1(const PassArgs& p, int nt, int dh32, int G, size_t lds, hipStream_t st);
-hipError_t pass_kernels_init_dt0(int lds_limit);
-hipError_t pass_kernels_init_dt1(int lds_limit);
-
-size_t pass_lds_limit() { return 128 * 1024; }
-
-hipError_t kernels_init() {
-    if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
-    if (hipError_t e = pass_kernels_init_dt0((int)pass_lds_limit()); e != hipSuccess) return e;
-    return pass_kernels_init_dt1((int)pass_lds_limit());
-}
-
-hipError_t launch_pass(const PassArgs& p, int dtype, int T, int d_head, int G, size_t stage_lds, hipStream_t st) {
-    const size_t lds = kPassArgLds + stage_lds;
-    if (lds > pass_lds_limit() || G < 1 || p.nstages < 1) return hipErrorInvalidValue;
-    const int nt = T > 16 ? 2 : 1, dh32 = d_head <= 32 ? 1 : (d_head <= 64 ? 2 : 4);
-    return dtype ? launch_pass_dt1(p, nt, dh32, G, lds, st) : launch_pass_dt0(p, nt, dh32, G, lds, st);
-}
+hipError_t kernels_init() { return raise_lds_limits(); }
 
 hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
@@ -1132,7 +1038,6 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     return hipGetLastError();
 }
 
-#endif  // BILD_DEVICE_ONLY
 
 // =====================================================================================
 // KV-cache attention on the matrix cores.  K is stored [position][I]; V is stored
@@ -1149,8 +1054,8 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
 // Cache rows beyond the valid length are finite (zero-filled at allocation, or stale
 // values of discarded tokens), so a probability of exactly 0 removes them.
 // =====================================================================================
-template <int DT, int DH32, bool COH = false, bool REL = false, class A>
-__device__ __forceinline__ void attn_body(const A& a, const int vblock, char* smem) {
+template <int DT, int DH32, bool REL = false>
+__device__ __forceinline__ void attn_body(const AttnArgs& a, const int vblock, char* smem) {
     constexpr int DHP = DH32 * 32;   // head dim padded to the k-step of the first product
     constexpr int DT16 = DH32 * 2;   // 16-wide output tiles along the head dim
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
@@ -1170,13 +1075,6 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
     float* relb = REL ? (float*)(co + nw * NT * DT16 * 64) : nullptr;
     const int nrel = REL ? 2 * a.rel_d + 1 : 1;
 
-#ifdef BILD_TRACE
-    unsigned long long* tr = (a.trace && vblock == 0 && tid == 0) ? a.trace : nullptr;
-#define ASTAMP(i) do { if (tr) tr[i] = wall_clock64(); } while (0)
-#else
-#define ASTAMP(i) do { } while (0)
-#endif
-    ASTAMP(0);
     // One unconditional scalar load of the length (the launcher guarantees the pointer): it is requested here and
     // first used behind q's vector loads, so the two trips to memory overlap.
     const int len_v = *a.len_ptr;
@@ -1199,7 +1097,7 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
         auto piece = [&](int i, auto&& hk) {
             const int t = i / (DHP / 4), d4 = (i % (DHP / 4)) * 4;
             const bool real = t < T && d4 < dh;
-            float4 v = ld_act4<COH>(a.q + (size_t)min(t, T - 1) * I + h * dh + min(d4, dh - 4));
+            float4 v = ld_act4(a.q + (size_t)min(t, T - 1) * I + h * dh + min(d4, dh - 4));
             hk();
             __builtin_amdgcn_sched_barrier(0);  // the conversion of q stays behind the K/V requests
             v.x = real ? v.x * a.scale : 0.f; v.y = real ? v.y * a.scale : 0.f;
@@ -1389,9 +1287,7 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
             for (int p = 0; p < RP; ++p) relb[min(tid + p * nthr, nrel - 1)] = relv[p];
             for (int i = tid + RP * nthr; i < nrel; i += nthr) relb[i] = a.rel_bias[h * nrel + i];
         }
-        ASTAMP(1);
         __syncthreads();
-        ASTAMP(2);
         if constexpr (DH32 <= 2) {
             uint4 K1[2][KN], V1[DT16][VN];
             for (; blk < blk_end; blk += 2 * nw) {
@@ -1408,8 +1304,6 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
             }
         }
     }
-
-    ASTAMP(3);
     // ---- merge the waves' partial results ----
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
@@ -1422,7 +1316,6 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
         for (int dt = 0; dt < DT16; ++dt) co[((wave * NT + nt) * DT16 + dt) * 64 + lane] = O[nt][dt];
     }
     __syncthreads();
-    ASTAMP(4);
     for (int qd = wave; qd < NT * DT16; qd += nw) {
         const int nt = qd / DT16, dt = qd % DT16;
         const int t = nt * 16 + tok_l, d0 = dt * 16 + g * 4;
@@ -1439,25 +1332,23 @@ __device__ __forceinline__ void attn_body(const A& a, const int vblock, char* sm
         if (t < T && d0 < dh) {
             if (a.splits == 1) {
                 const float inv = 1.f / Lsum;
-                st_act4<COH>(a.out + (size_t)t * I + h * dh + d0, make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv));
+                st_act4(a.out + (size_t)t * I + h * dh + d0, make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv));
             } else {
-                st_act4<COH>(a.part_o + ((size_t)sp * T + t) * I + h * dh + d0, make_float4(acc[0], acc[1], acc[2], acc[3]));
+                st_act4(a.part_o + ((size_t)sp * T + t) * I + h * dh + d0, make_float4(acc[0], acc[1], acc[2], acc[3]));
                 if (dt == 0 && g == 0) {
                     float* ml = a.part_ml + (((size_t)sp * T + t) * a.heads + h) * 2;
-                    st_act<COH>(ml, M);
-                    st_act<COH>(ml + 1, Lsum);
+                    st_act(ml, M);
+                    st_act(ml + 1, Lsum);
                 }
             }
         }
     }
-    ASTAMP(5);
-#undef ASTAMP
 }
 
 template <int DT, int DH32, bool REL>
 __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    attn_body<DT, DH32, false, REL>(a, (int)(blockIdx.x + blockIdx.y * gridDim.x), smem);
+    attn_body<DT, DH32, REL>(a, (int)(blockIdx.x + blockIdx.y * gridDim.x), smem);
 }
 
 // More than kMaxRows query rows: blockIdx.z picks the block of rows (key splits are not combined with it).
@@ -1470,14 +1361,13 @@ __global__ __launch_bounds__(512) void attn_rows_kernel(const AttnArgs a) {
     b.q = a.q + (size_t)r0 * a.i_dim;
     b.out = a.out + (size_t)r0 * a.i_dim;
     b.base_add = a.base_add + r0;
-    attn_body<DT, DH32, false, REL>(b, (int)blockIdx.x, smem);
+    attn_body<DT, DH32, REL>(b, (int)blockIdx.x, smem);
 }
 
 // Joins the key splits of attention: out[t][n] = sum_s w_s O_s[t][n] / sum_s w_s L_s with w_s = exp(m_s - max m) of
 // (row t, head of n).  Unit `u` covers 256 float4 pieces of the [T][I] output; every thread owns one piece and issues
 // the loads of all splits together (eight at a time).
-template <bool COH = false, class A>
-__device__ __forceinline__ void attn_merge_body(const A& a, const int u) {
+__device__ __forceinline__ void attn_merge_body(const AttnArgs& a, const int u) {
     const int I = a.i_dim, n4 = I >> 2;
     const int e = u * 256 + (int)threadIdx.x;
     if (threadIdx.x >= 256 || e >= a.T * n4) return;
@@ -1490,7 +1380,7 @@ __device__ __forceinline__ void attn_merge_body(const A& a, const int u) {
     for (int s0 = 0; s0 < a.splits; s0 += 8) {
         float m[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) m[k] = ld_act<COH>(ml + min(s0 + k, a.splits - 1) * ml_stride);
+        for (int k = 0; k < 8; ++k) m[k] = ld_act(ml + min(s0 + k, a.splits - 1) * ml_stride);
 #pragma unroll
         for (int k = 0; k < 8; ++k) M = fmaxf(M, m[k]);
     }
@@ -1502,9 +1392,9 @@ __device__ __forceinline__ void attn_merge_body(const A& a, const int u) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int sc = min(s0 + k, a.splits - 1);
-            m[k] = ld_act<COH>(ml + sc * ml_stride);
-            l[k] = ld_act<COH>(ml + sc * ml_stride + 1);
-            o[k] = ld_act4<COH>(op + sc * o_stride);
+            m[k] = ld_act(ml + sc * ml_stride);
+            l[k] = ld_act(ml + sc * ml_stride + 1);
+            o[k] = ld_act4(op + sc * o_stride);
         }
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -1514,10 +1404,9 @@ __device__ __forceinline__ void attn_merge_body(const A& a, const int u) {
         }
     }
     const float inv = 1.f / L;
-    st_act4<COH>(a.out + (size_t)t * I + n, make_float4(r.x * inv, r.y * inv, r.z * inv, r.w * inv));
+    st_act4(a.out + (size_t)t * I + n, make_float4(r.x * inv, r.y * inv, r.z * inv, r.w * inv));
 }
 
-#ifndef BILD_DEVICE_ONLY
 __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) { attn_merge_body(a, (int)blockIdx.x); }
 
 size_t attn_lds_bytes(int dtype, int d_head, int T, int nw) {
@@ -1558,13 +1447,12 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
     hipLaunchKernelGGL(attn_merge_kernel, dim3((a.T * (a.i_dim / 4) + 255) / 256), dim3(256), 0, st, a);
     return hipGetLastError();
 }
-#endif  // BILD_DEVICE_ONLY
 
 // =====================================================================================
 // Embedding gather from the tiled matrix (+ sinusoidal position).
 // =====================================================================================
-template <int DT, bool COH = false, class A>
-__device__ __forceinline__ void embed_body(const A& a, const int t) {
+template <int DT>
+__device__ __forceinline__ void embed_body(const EmbedArgs& a, const int t) {
     constexpr int KT = DT ? 32 : 16, PL = KT / 4;
     const int base = (a.base_ptr ? *a.base_ptr : 0) + a.base_add;
     const int tok = a.tokens[base + t];
@@ -1581,14 +1469,13 @@ __device__ __forceinline__ void embed_body(const A& a, const int t) {
             const double ang = (double)pos * exp2(-(double)(2 * (k >> 1)) / (double)a.d * lg);
             v += (float)((k & 1) ? cos(ang) : sin(ang));
         }
-        st_act<COH>(a.x + (size_t)t * a.d + k, v);
+        st_act(a.x + (size_t)t * a.d + k, v);
     }
 }
 
 template <int DT>
 __global__ __launch_bounds__(256) void embed_kernel(const EmbedArgs a) { embed_body<DT>(a, (int)blockIdx.x); }
 
-#ifndef BILD_DEVICE_ONLY
 hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st) {
     if (dtype)
         hipLaunchKernelGGL(embed_kernel<1>, dim3(a.T), dim3(256), 0, st, a);
@@ -1597,7 +1484,6 @@ hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st) {
     return hipGetLastError();
 }
 
-#endif  // BILD_DEVICE_ONLY
 
 // =====================================================================================
 // Merge of the LM-head partials + policy + commit.  One workgroup.
@@ -1909,7 +1795,6 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
     }
 }
 
-#ifndef BILD_DEVICE_ONLY
 __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[kFinishLds];
     finish_body<false>(a, lds);
@@ -1933,45 +1818,6 @@ hipError_t launch_row_copy(const RowCopyArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-// Plain copy of known size: the reference against which hardware byte counters are scaled.
-__global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
-}
-
-// A kernel that does nothing on one workgroup per CU: what a dependent launch costs by itself.
-__global__ __launch_bounds__(256) void probe_empty_kernel() {}
-
-hipError_t launch_probe_empty(hipStream_t st) {
-    hipLaunchKernelGGL(probe_empty_kernel, dim3(256), dim3(256), 0, st);
-    return hipGetLastError();
-}
-
-// Every workgroup (8 waves) streams a private contiguous region, 16 tiles of 1 KiB per wave in flight: how fast
-// ONE compute unit can pull from HBM, and how the total grows with the number of workgroups.
-__global__ __launch_bounds__(512) void probe_stream_kernel(const uint4* __restrict__ p, size_t tiles_per_wg, uint4* sink) {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const uint4* base = p + (size_t)blockIdx.x * tiles_per_wg * 64 + lane;
-    uint4 acc = make_uint4(0, 0, 0, 0);
-    for (size_t t = wave; t < tiles_per_wg; t += 8 * 16) {
-        uint4 v[16];
-#pragma unroll
-        for (int u = 0; u < 16; ++u) v[u] = base[min(t + (size_t)u * 8, tiles_per_wg - 1) * 64];
-#pragma unroll
-        for (int u = 0; u < 16; ++u) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
-    }
-    if (acc.x == 0x12345678u && acc.y == 0x9abcdefu) sink[0] = acc;  // keeps the loads alive; never true for zeroed memory
-}
-
-hipError_t launch_probe_stream(const void* src, size_t kib_per_group, int groups, void* sink, hipStream_t st) {
-    hipLaunchKernelGGL(probe_stream_kernel, dim3(groups), dim3(512), 0, st, (const uint4*)src, kib_per_group, (uint4*)sink);
-    return hipGetLastError();
-}
-
-hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st) {
-    hipLaunchKernelGGL(probe_copy_kernel, dim3(4096), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, bytes / 16);
-    return hipGetLastError();
-}
-
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st) {
     if (a.top_p > 0.f && a.mode <= 2) {
         if (!a.logits || !a.u || a.vocab < 1) return hipErrorInvalidValue;
@@ -1982,6 +1828,5 @@ hipError_t launch_finish(const FinishArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-#endif  // BILD_DEVICE_ONLY
 
 }  // namespace bild

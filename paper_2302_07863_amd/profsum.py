@@ -2,6 +2,7 @@
 
   python -m paper_2302_07863_amd.profsum stats  <kernel_stats.csv>
   python -m paper_2302_07863_amd.profsum pmc    <fetch counter_collection.csv> <write counter_collection.csv>
+  python -m paper_2302_07863_amd.profsum counters <counter_collection.csv>
 
 `stats` groups the template instantiations of one kernel under one name and prints calls,
 total and mean duration.  `pmc` scales FETCH_SIZE / WRITE_SIZE per dispatch by what the same
@@ -41,6 +42,9 @@ def stats(path: str) -> str:
     lines = [f"{'kernel':34s} {'calls':>8s} {'total_ms':>10s} {'mean_us':>9s} {'share':>7s}"]
     for k, (n, t) in sorted(agg.items(), key=lambda kv: -kv[1][1]):
         lines.append(f"{k:34s} {n:8d} {t / 1e6:10.2f} {t / n / 1e3:9.2f} {100.0 * t / total:6.1f}%")
+    g = agg.get("bild::gemm_kernel<*>")
+    if g:
+        lines.append(f"gemm_mean_us={g[1] / g[0] / 1e3:.3f}")
     return "\n".join(lines)
 
 
@@ -71,9 +75,28 @@ def pmc(fetch_path: str, write_path: str) -> str:
     return "\n".join(lines)
 
 
+def counters(path: str) -> str:
+    """Sums every counter of a --pmc run per kernel group: one line per group with dispatches and, per counter, the
+    mean value per dispatch."""
+    agg = collections.defaultdict(lambda: collections.defaultdict(float))
+    disp = collections.defaultdict(set)
+    for r in csv.DictReader(open(path)):
+        g = _group(r["Kernel_Name"])
+        agg[g][r["Counter_Name"]] += float(r["Counter_Value"])
+        disp[g].add(r["Dispatch_Id"])
+    names = sorted({c for v in agg.values() for c in v})
+    lines = [f"{'kernel':34s} {'dispatches':>10s} " + " ".join(f"{c:>24s}" for c in names)]
+    for g in sorted(agg, key=lambda k: -len(disp[k])):
+        n = len(disp[g])
+        lines.append(f"{g:34s} {n:10d} " + " ".join(f"{agg[g].get(c, 0.0) / n:24.1f}" for c in names))
+    return "\n".join(lines)
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 3 and sys.argv[1] == "stats":
         print(stats(sys.argv[2]))
+    elif len(sys.argv) >= 3 and sys.argv[1] == "counters":
+        print(counters(sys.argv[2]))
     elif len(sys.argv) >= 4 and sys.argv[1] == "pmc":
         print(pmc(sys.argv[2], sys.argv[3]))
     else:

@@ -37,39 +37,75 @@ def _excused_small(rec, alpha_fb) -> bool:
     return rec["gap"] < MARGIN or abs(rec["pmax"] - alpha_fb) < MARGIN
 
 
-def compare_generation(tokens, stats, ref, alpha_fb=None, alpha_rb=None) -> dict:
-    """Free-running comparison of one whole bild_generate call with the oracle's
-    result.  Returns {'exact': bool, 'matched': n}.  A mismatch is accepted only
-    if some oracle decision up to that point was within MARGIN of a tie or a
-    threshold; otherwise raises."""
+def first_position(ref) -> int:
+    """Length of the initial sequence (<s> or the prompt): the position the oracle's first step fills."""
+    rec = ref.trace[0]
+    return rec["pos"] if "pos" in rec else rec["draft_start"]
+
+
+def marginal_records(ref, position, alpha_fb=None, alpha_rb=None, margin=MARGIN, draw_margin=None) -> list:
+    """The oracle's decisions ABOUT the token at absolute `position` that were within `margin` of going the
+    other way: a small step that proposed (or refused) a token for that position, and every review that judged
+    the draft at that position or emitted the large model's token there.  Decisions about other positions do
+    not count, however marginal.  draw_margin (sampling variant): bar for the distance of u * mass from a
+    running-mass boundary, only for the record that drew the token at that position.
+    position None: every position (used only when the token sequences are identical and just the counters differ)."""
+    out = []
+    for rec in ref.trace:
+        dm = rec.get("draw_margin")
+        if "draft_start" not in rec:         # a small step, or a step of plain greedy decoding by either model
+            if position is not None and rec["pos"] != position:
+                continue
+            if rec["gap"] < margin and dm is None:
+                out.append(rec)
+            elif alpha_fb is not None and "fallback" in rec and abs(rec["pmax"] - alpha_fb) < margin:
+                out.append(rec)
+            elif dm is not None and draw_margin is not None and dm < draw_margin:
+                out.append(rec)
+        else:
+            if position is None:
+                if (rec["gaps"][rec["r"]] < margin and dm is None) or \
+                        (alpha_rb is not None and any(abs(v - alpha_rb) < margin for v in rec["nll"])) or \
+                        (dm is not None and draw_margin is not None and dm < draw_margin):
+                    out.append(rec)
+                continue
+            i = position - rec["draft_start"]
+            if i < 0 or i > rec["r"]:
+                continue
+            if i == rec["r"] and rec["gaps"][i] < margin and dm is None:
+                out.append(rec)
+            elif alpha_rb is not None and i < len(rec["nll"]) and abs(rec["nll"][i] - alpha_rb) < margin:
+                out.append(rec)
+            elif i == rec["r"] and dm is not None and draw_margin is not None and dm < draw_margin:
+                out.append(rec)
+    return out
+
+
+def compare_generation(tokens, stats, ref, alpha_fb=None, alpha_rb=None, draw_margin=None) -> dict:
+    """Free-running comparison of one whole bild_generate (or greedy) call with the oracle's result.
+    Returns {'exact': bool, 'matched': n}.  A mismatch is accepted only if one of the oracle's decisions
+    about the FIRST differing position was itself within MARGIN of a tie or a threshold (see
+    marginal_records); otherwise raises.  Everything after an excused difference is left to the
+    teacher-forced comparison."""
     n = min(len(tokens), len(ref.tokens))
     first = next((i for i in range(n) if tokens[i] != ref.tokens[i]), None)
     if first is None and len(tokens) == len(ref.tokens):
-        if stats is not None:
-            for k in ("small_steps", "large_calls", "rows_verified", "fallbacks_conf", "fallbacks_forced",
-                      "rollbacks", "tokens_discarded"):
-                assert stats[k] == getattr(ref.stats, k), (k, stats[k], getattr(ref.stats, k))
+        keys = ("small_steps", "large_calls", "rows_verified", "fallbacks_conf", "fallbacks_forced", "rollbacks",
+                "tokens_discarded")
+        if stats is not None and any(stats[k] != getattr(ref.stats, k) for k in keys):
+            # The same tokens by a different route (say, a draft the oracle let through by a hair was replaced by
+            # the identical token of the large model): only a marginal decision somewhere can do that.
+            close = marginal_records(ref, None, alpha_fb, alpha_rb, MARGIN, draw_margin)
+            assert close, ("identical tokens, different counters, and no marginal oracle decision anywhere",
+                           {k: (stats[k], getattr(ref.stats, k)) for k in keys})
+            return dict(exact=False, matched=len(tokens))
         return dict(exact=True, matched=len(tokens))
     if first is None:
         first = n
-    # some decision of the oracle at or before the first differing token must have been marginal
-    marginal = False
-    for rec in ref.trace:
-        if rec["kind"] == "small":
-            pos = rec["pos"]
-            if alpha_fb is not None and _excused_small(rec, alpha_fb):
-                marginal = True
-        else:
-            pos = rec["draft_start"] + rec["r"]
-            if min(rec["gaps"]) < MARGIN:
-                marginal = True
-            if alpha_rb is not None and any(abs(v - alpha_rb) < MARGIN for v in rec["nll"]):
-                marginal = True
-        if marginal:
-            break
-        if pos - 1 > first + 64:
-            break
-    assert marginal, f"tokens differ at {first} without a marginal oracle decision: {tokens[first:first+4]} vs {ref.tokens[first:first+4]}"
+    position = first_position(ref) + first       # generated token i sits at absolute position n0 + i
+    close = marginal_records(ref, position, alpha_fb, alpha_rb, MARGIN, draw_margin)
+    assert close, (f"tokens differ at generated index {first} (position {position}) and no oracle decision about that "
+                   f"position was marginal: {tokens[first:first+4]} vs {ref.tokens[first:first+4]}")
     return dict(exact=False, matched=first)
 
 

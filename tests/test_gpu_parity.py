@@ -376,39 +376,169 @@ def test_relative_bias_with_key_splits_and_long_prompt():
     print(parity.teacher_forced(st, ref, R.n0, 0.4, 1.0, cfg), ref.stats, flush=True)
 
 
+def _bf16_step(a):
+    """Spacing of bf16 values at the magnitude of a (8 significant bits)."""
+    return np.ldexp(1.0, np.frexp(np.maximum(np.abs(a), 1e-30))[1] - 8)
+
+
+def _cache_differences(st, which, cache, layers, n):
+    """Per layer (share, worst): the share of cached K/V elements on which the library and the oracle hold
+    different bf16 values, and the largest difference relative to the largest value of its tensor.
+    In layer 0 both sides start from identical inputs, so the values before rounding differ by fp32-vs-float64
+    accumulation noise only (about 1e-7 of the tensor's scale): an element is then either equal or ONE bf16 step
+    off (its value fell on the other side of a rounding boundary), except for elements so small that this
+    noise already spans several of their own steps - asserted here.  Deeper layers inherit the flipped values
+    of the layers below through the hidden state; their differences are reported and bounded by the caller."""
+    out = {}
+    for l in layers:
+        bad = total = 0
+        worst = 0.0
+        for is_v, ref in ((0, cache.k[l][:n]), (1, cache.v[l][:n])):
+            got = st.debug_kv(which, l, bool(is_v), 0, n).astype(np.float64)
+            diff = np.abs(got - ref)
+            scale = float(np.max(np.abs(ref)))
+            if l == 0:
+                step = _bf16_step(np.maximum(np.abs(got), np.abs(ref)))
+                beyond = diff > step * (1 + 1e-6)
+                assert np.all(~beyond | (diff <= 1e-6 * scale)), \
+                    ("layer 0: cached values differ by more than one bf16 step", is_v, float(np.max(diff[beyond])) / scale)
+            bad += int(np.count_nonzero(diff))
+            total += diff.size
+            worst = max(worst, float(np.max(diff)) / scale)
+        out[l] = (bad / total, worst)
+    return out
+
+
 @pytest.mark.timeout(1500)
-@pytest.mark.skipif(__import__("os").environ.get("BILD_TEST_7B") != "1",
-                    reason="7B-shaped pair: ~60 s of weight generation and a float64 oracle over 13 GB of weights; "
-                           "run with BILD_TEST_7B=1")
-def test_llama_config_full_width_sampled_rows():
+def test_llama_config_full_width_logits_exceed_the_bf16_bar_through_storage_rounding_only():
     """Config 4 at its full widths (32 layers, d 4096, 32 heads of 128, FFN 11008, vocab 32000) on a shortened
-    prompt: the rows of one review pass and of one small step against the oracle, element by element."""
+    prompt.  The rows of one review pass and of one small step against the oracle, element by element.
+
+    At this depth and width the large model's logits (magnitude 50-140) do NOT meet the 2e-2 bar of the bf16
+    configurations: they are off by up to about 5e-2.  What this test pins is the cause and its size:
+      * every decision (argmax of the reviewed rows, the small model's token and flag) agrees with the oracle;
+      * in layer 0, where both sides start from identical inputs, the library's cached K/V equal the oracle's
+        except for a few elements in ten thousand (measured: 4e-4) that are exactly ONE bf16 step off: values
+        whose fp32 and float64 results straddle a rounding boundary.  Those flips (2^-8 relative each) enter the
+        hidden state, so deeper layers differ on more and more elements (measured: 2 % in layer 1, 28 % in
+        layer 8, 50 % in layer 31) - but never by more than one bf16 step of the tensor's largest values (2^-7 of
+        the largest magnitude): the noise saturates at the granularity of the storage format;
+      * the same widths with fp32 storage (first 8 layers, so that it stays affordable) agree to 3e-6 of the
+        largest logit, i.e. the arithmetic itself is fp32-accurate;
+      * the logit error stays below 5x the bar (0.1); the small model (16 layers, d 2048) is held to the bar itself."""
     from dataclasses import replace
     cfg = replace(bi.llama_pair(), n_src=48, max_new=8)
     R = Rig(cfg, compact=True)
+    tol = parity.logit_tol(cfg)
     st = R.state(cfg.max_new + 8, cfg.n_max)
     st.encode(R.src)
     st.debug_enable_logits(True)
     block = [int(t) for t in bi.make_tokens(cfg.large.vocab, 5, seed=9)]
     out, r, nll = st.large_verify(INF, draft=block)
     y = list(R.src) + block
-    z = R.req.large.logits_full(y, [])[len(y) - 6:]
-    # Depth x width of this pair push the bf16 storage noise past the 2e-2 bar of the smaller configurations:
-    # a cached K/V value computed in fp32 here and in float64 by the oracle lands on the other side of a
-    # bf16 rounding boundary for ~0.3 % of the elements (2^-8 relative each).  Measured on this shape with
-    # 1 / 4 / 8 / 32 layers: 4e-4 / 9e-3 / 2e-2 / 4.9e-2, growing like sqrt(depth), while the SAME shapes
-    # with fp32 storage agree to 1.2e-4 on logits of magnitude 50-140 (1e-6 relative).  Bar used here: 0.1.
-    tol = 0.1
-    print("max |logit|", float(np.max(np.abs(z))), "tolerance", tol, flush=True)
+    cache = oracle.model.DecoderCache(R.req.large, [], len(y) + 1)
+    z = cache.step(y, last=6)
+    worst = 0.0
     for i in range(6):
         zi = st.debug_logits(pkg.LARGE, i)
-        print("large row", i, float(np.max(np.abs(zi - z[i]))), flush=True)
-        assert np.max(np.abs(zi - z[i])) <= tol
+        err = float(np.max(np.abs(zi - z[i])))
+        worst = max(worst, err)
+        assert int(np.argmax(zi)) == int(np.argmax(z[i])) or oracle.policy.top2_gap(z[i]) < parity.MARGIN
+        if i < 5:
+            assert abs(float(nll[i]) - oracle.policy.nll(z[i], block[i])) <= 5 * 2 * tol
+    print("large: max |logit|", float(np.max(np.abs(z))), "worst logit error", worst, "bar", tol, flush=True)
+    assert worst <= 5 * tol, worst
     assert out[5] == int(np.argmax(z[5])) or oracle.policy.top2_gap(z[5]) < parity.MARGIN
+    diffs = _cache_differences(st, pkg.LARGE, cache, (0, 1, 8, 16, 31), len(y))
+    print("cached K/V against the oracle's, by layer (share of differing elements, largest difference / tensor scale):",
+          diffs, flush=True)
+    assert diffs[0][0] < 2e-3, diffs
+    assert max(w for _, w in diffs.values()) <= 2.0 ** -7, diffs
+    del cache
+    # the small model of the pair: one step
     tok, flag, pmax = st.small_step(0.5)
     seq = st.sequence()
     pre = seq if flag else seq[:-1]
     zs = R.req.small.logits_full(pre, [])[-1]
     zg = st.debug_logits(pkg.SMALL, 0)
-    print("small row", float(np.max(np.abs(zg - zs))), flush=True)
-    assert np.max(np.abs(zg - zs)) <= tol and abs(pmax - oracle.policy.max_prob(zs)) <= 2 * tol
+    err_s = float(np.max(np.abs(zg - zs)))
+    print("small: max |logit|", float(np.max(np.abs(zs))), "logit error", err_s, flush=True)
+    assert err_s <= tol and abs(pmax - oracle.policy.max_prob(zs)) <= 2 * tol
+    assert tok == int(np.argmax(zs)) or oracle.policy.top2_gap(zs) < parity.MARGIN
+    assert bool(flag) == (oracle.policy.max_prob(zs) < 0.5) or abs(oracle.policy.max_prob(zs) - 0.5) < parity.MARGIN
+    # control: the first 8 layers of the same large model with fp32 storage of weights and K/V (the weights hold the
+    # same bf16-representable values): no rounding of K/V on either side, so the difference is arithmetic alone
+    del st
+    shape32 = replace(cfg.large, n_dec=8, dtype=bi.DT_F32, name="llama-large-8-f32")
+    names = bi.tensor_names(shape32)
+    w32 = {n: R.wl[n] for n in names}
+    m32 = parity.make_gpu_model(shape32, w32)
+    small32 = replace(cfg.small, n_dec=1, dtype=bi.DT_F32)
+    ms32 = parity.make_gpu_model(small32, {n: R.ws[n] for n in bi.tensor_names(small32)})
+    pair32 = pkg.Pair(ms32, m32)
+    st32 = pkg.State(pair32, len(R.src), len(R.src) + 16, cfg.n_max)
+    st32.encode(R.src)
+    st32.debug_enable_logits(True)
+    st32.large_verify(INF, draft=block)
+    o32 = oracle.Model(shape32, w32, compact=True)
+    z32 = oracle.model.DecoderCache(o32, [], len(y) + 1).step(y, last=6)
+    rel = max(float(np.max(np.abs(st32.debug_logits(pkg.LARGE, i) - z32[i]))) for i in range(6)) / float(np.max(np.abs(z32)))
+    print("fp32 storage, 8 layers: logit error relative to the largest logit", rel, flush=True)
+    assert rel <= 3e-6, rel
+
+
+@pytest.mark.timeout(1500)
+def test_verify_stress_7b_widths_cache_of_4096_rows():
+    """Config 5 (review-pass stress) at the 7B-shaped large model's full widths with 4 of its layers, so that
+    the oracle stays affordable: a cache of 4095 prompt rows, review passes of T = n+1 in {1, 4, 8, 16, 32} rows
+    (many key splits joined by the merge kernel), the large cache cut back to a random row between passes (the
+    next pass first recomputes the cut rows in row-block launches).  Sampled rows of every pass against the
+    oracle's cached forward; one block also against T single-row passes (Section 3.2: one pass over n tokens
+    equals n sequential steps)."""
+    from dataclasses import replace
+    base = bi.llama_pair()
+    large = replace(base.large, n_dec=4, name="llama-large-4")
+    small = replace(base.small, n_dec=1, name="llama-small-1")
+    cfg = replace(base, name="verify-stress", small=small, large=large, n_src=4096, max_new=40)
+    R = Rig(cfg, compact=True)
+    tol = parity.logit_tol(cfg)
+    n0 = R.n0
+    assert pkg.binding.attn_shape(large.heads, large.d_head, 8, n0 + 8, 8, 1)["splits"] >= 8
+    st = pkg.State(R.pair, n0, n0 + 40, 31)
+    st.encode(R.src)
+    st.debug_enable_logits(True)
+    cache = oracle.model.DecoderCache(R.req.large, [], n0 + 40)
+    prompt = [int(t) for t in R.src]
+    cache.step(prompt[:n0 - 1], last=0)
+    rng = np.random.default_rng(17)
+    worst = 0.0
+    for n in (0, 3, 7, 15, 31, 7):
+        block = [int(t) for t in bi.make_tokens(large.vocab, n, seed=200 + n)]
+        out, r, nll = st.large_verify(INF, draft=block)            # never roll back
+        assert r == n and out[:n] == block
+        have = cache.length
+        z = cache.step(prompt[have:] + block, last=n + 1)           # catches up on rows cut earlier, then the block
+        for i in sorted({0, n // 2, n}):
+            zi = st.debug_logits(pkg.LARGE, i)
+            err = float(np.max(np.abs(zi - z[i])))
+            worst = max(worst, err)
+            assert err <= tol, (n, i, err)
+            if i < n:
+                assert abs(float(nll[i]) - oracle.policy.nll(z[i], block[i])) <= 2 * tol
+        assert out[n] == int(np.argmax(z[n])) or oracle.policy.top2_gap(z[n]) < parity.MARGIN
+        if n == 7:
+            # the same block one row per pass: the distributions of sequential steps
+            rows = [st.debug_logits(pkg.LARGE, i) for i in range(n + 1)]
+            for i in range(n + 1):
+                st.force_tokens(n0, block[:i], n0 + i)
+                out1, _, _ = st.large_verify(INF, draft=[])
+                z1 = st.debug_logits(pkg.LARGE, 0)
+                assert np.max(np.abs(z1 - rows[i])) <= 5e-3, (i, float(np.max(np.abs(z1 - rows[i]))))
+                assert out1[0] == int(np.argmax(z1))
+        # cut the large model's cache at a random row near the end of the prompt, the sequence back to the prompt
+        cut = int(rng.integers(n0 - 300, n0 - 1))
+        st.force_tokens(n0, [], n0)
+        st.kv_truncate(pkg.LARGE, cut)
+        assert st.lengths()["len_large"] == cut
+        cache.truncate(cut)
+    print("verify stress: worst logit error", worst, "bar", tol, flush=True)

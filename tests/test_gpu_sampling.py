@@ -2,10 +2,12 @@
 the nucleus of their distribution, with the uniform numbers passed in from the seeded input generator, and
 the drawn tokens / flags / rollback indices are compared with the oracle step by step.
 
-Margin rule: a difference is excused only where the ORACLE's own decision was marginal - u * mass within
-`margin` (relative) of a running-mass boundary or the nucleus cut within `margin` of top_p, or one of the
-usual threshold margins.  fp32 models use 1e-3; bf16 models 4x their logit tolerance, because a logit
-error of that size moves every probability by as much."""
+Margin rule: a difference is excused only where the ORACLE's own decision about that token was marginal.
+The threshold distances (|max p - alpha_FB|, |nll - alpha_RB|) use the benchmark's 1e-3.  The draw has a
+margin of its own: with every logit within eps of the oracle's, each exp(z_i - m) is within a factor
+exp(+-2 eps) of its value, so the ratio (running mass) / (nucleus mass) that u is compared with - and the
+ratio (top mass) / (total mass) that top_p is compared with - moves by at most 2 eps relative.  eps is the
+logit tolerance of the storage type (1e-4 / 2e-2), so the draw margin is max(1e-3, 2 eps)."""
 import numpy as np
 import pytest
 
@@ -24,15 +26,17 @@ def _uniforms(cfg, n):
 
 
 def _margin(cfg):
-    return parity.MARGIN if cfg.large.dtype == bi.DT_F32 else 4 * parity.logit_tol(cfg)
+    """Draw margin (see the module text)."""
+    return max(parity.MARGIN, 2 * parity.logit_tol(cfg))
 
 
 def _marginal(rec, fb, rb, margin):
+    """Was this oracle step within reach of going the other way?  Thresholds: 1e-3; the draw: `margin`."""
     if rec.get("draw_margin") is not None and rec["draw_margin"] < margin:
         return True
     if rec["kind"] == "small":
-        return abs(rec["pmax"] - fb) < margin
-    return any(abs(v - rb) < margin for v in rec["nll"])
+        return abs(rec["pmax"] - fb) < parity.MARGIN
+    return any(abs(v - rb) < parity.MARGIN for v in rec["nll"])
 
 
 def replay(state, ref, n0, fb, rb, margin):
@@ -63,19 +67,10 @@ def replay(state, ref, n0, fb, rb, margin):
 
 
 def free_running(tokens, stats, ref, n0, fb, rb, margin):
-    if tokens == ref.tokens:
-        for k in ("small_steps", "large_calls", "rows_verified", "rollbacks", "tokens_discarded"):
-            assert stats[k] == getattr(ref.stats, k), k
-        return True
-    first = next((i for i in range(min(len(tokens), len(ref.tokens))) if tokens[i] != ref.tokens[i]),
-                 min(len(tokens), len(ref.tokens)))
-    for rec in ref.trace:                                   # some decision up to that token was marginal
-        pos = rec["pos"] if rec["kind"] == "small" else rec["draft_start"] + rec["r"]
-        if _marginal(rec, fb, rb, margin):
-            return False
-        if pos - n0 > first + 32:
-            break
-    raise AssertionError(f"tokens differ at {first} without a marginal oracle decision")
+    """Whole-generation comparison: identical, or the first differing token traces back to a marginal oracle
+    decision about that very position (parity.compare_generation with the draw margin)."""
+    assert parity.first_position(ref) == n0
+    return parity.compare_generation(tokens, stats, ref, fb, rb, draw_margin=margin)["exact"]
 
 
 @pytest.mark.parametrize("name", ["f32-relu-tied", "f32-geglu-untied", "f32-rope-swiglu-deconly", "f32-wide",
@@ -152,4 +147,27 @@ def test_sampling_t5_full_size():
     st.encode(R.src)
     res = replay(st, ref, R.n0, cfg.alpha_fb, cfg.alpha_rb, _margin(cfg))
     print("t5 sampled", res, ref.stats, flush=True)
-    assert res["excused"] <= res["steps"] // 4
+    assert res["excused"] <= 4
+    toks, stats = st.generate(R.src, cfg.alpha_fb, cfg.alpha_rb, cfg.max_new)
+    print("t5 sampled free-running", free_running(toks, stats, ref, R.n0, cfg.alpha_fb, cfg.alpha_rb, _margin(cfg)), flush=True)
+
+
+def test_sampling_vocabulary_beyond_the_register_cache():
+    """A vocabulary of 40 000 ids (more than 32 768: a row no longer stays in the registers of the 1024 threads
+    that draw, so every radix sweep re-reads it) on a narrow model the oracle finishes in seconds; fp32 and bf16."""
+    for dtype in (bi.DT_F32, bi.DT_BF16):
+        cfg = bi.toy_pair(dtype=dtype, vocab=40000, d=64, heads=2, d_head=16, d_ff=96, max_new=16, tie_shift=4099,
+                          logit_scale=24.0)
+        R = Rig(cfg)
+        n = R.n0 + cfg.max_new + 1
+        us, ul = _uniforms(cfg, n)
+        for top_p in (TOP_P, 1.0):
+            smp = oracle.Sampler(top_p, us, ul)
+            ref = oracle.bild_generate(R.req, 0.15, 3.0, 5, cfg.max_new, sampler=smp)
+            st = R.state(cfg.max_new, 5)
+            st.set_sampling(top_p, us, ul)
+            st.encode(R.src)
+            res = replay(st, ref, R.n0, 0.15, 3.0, _margin(cfg))
+            toks, stats = st.generate(R.src, 0.15, 3.0, cfg.max_new)
+            print("V=40000", dtype, top_p, res, free_running(toks, stats, ref, R.n0, 0.15, 3.0, _margin(cfg)), ref.stats, flush=True)
+            assert res["excused"] <= 3 and len(set(ref.tokens)) > 4      # (every excused step passed the margin rule) a real draw, not one repeated token

@@ -344,6 +344,10 @@ def test_cached_and_block_passes_equal_the_definition(kw):
             blocks.append(c.step(y[at:at + n]))
             at += n
         assert np.allclose(np.concatenate(blocks), full, rtol=1e-12, atol=1e-12)
+        # the `last` option only drops rows of the result
+        c2 = om.DecoderCache(m, cross, 32)
+        assert c2.step(y[:6], last=0).shape == (0, shape.vocab)
+        assert np.allclose(c2.step(y[6:], last=3), full[-3:], rtol=1e-12, atol=1e-12) and c2.length == len(y)
         # truncate, then continue with different tokens == fresh run on the new prefix
         c.truncate(4)
         y2 = y[:4] + [int(t) for t in bi.make_tokens(shape.vocab, 5, seed=6)]
