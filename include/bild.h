@@ -247,6 +247,16 @@ typedef struct bild_row_stats {
 } bild_row_stats;
 int bild_head_stats(const bild_model* m, const float* x_dev, int rows, const int32_t* targets_dev,
                     bild_row_stats* out_dev, void* hip_stream);
+/* bild_head_stats for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, same kernels, same results, but the scratch buffer is a
+ * 4 MiB device array inside the library (one per GPU, held until the process ends), and the call neither allocates
+ * nor frees anything and does not wait for the stream: it returns once its three kernels are enqueued on hip_stream.
+ * Limit: the head's launch must not have more than 8191 workgroups (one 512-byte block of partial statistics each),
+ * else BILD_ECAP; vocabularies up to 250112 at widths of 512 and 1024 are well inside it.  Every call on a GPU uses
+ * that GPU's one array, which keeps the previous call's contents (the call clears what it reads before writing): calls
+ * that overlap on one GPU - two streams, two threads - race; calls on one stream are ordered and safe. */
+int bild_head_stats_static(const bild_model* m, const float* x_dev, int rows, const int32_t* targets_dev,
+                           bild_row_stats* out_dev, void* hip_stream);
 
 /* Introspection (host copies of the control block). */
 int bild_get_lengths(bild_state* s, int32_t* y_len, int32_t* draft_start, int32_t* len_small, int32_t* len_large);

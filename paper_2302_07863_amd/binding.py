@@ -70,6 +70,7 @@ _SIGS = {
     "bild_greedy": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int32, C.c_void_p,
                               C.POINTER(C.c_int32)]),
     "bild_head_stats": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "bild_head_stats_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "bild_get_lengths": (C.c_int, [C.c_void_p] + [C.POINTER(C.c_int32)] * 4),
     "bild_get_sequence": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int32)]),
     "bild_debug_enable_logits": (C.c_int, [C.c_void_p, C.c_int]),

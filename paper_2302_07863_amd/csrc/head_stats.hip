@@ -1,7 +1,9 @@
-// bild_head_stats: the final norm + LM head + softmax statistics of the decoding path (the fused vocabulary
-// sweep of a decoder pass) as a call of its own on hidden rows the caller already holds on the device.  The
-// kernels work through a scratch buffer (per-workgroup partial statistics, the logits of the targets, one
-// length word) that the call allocates with hipMalloc and frees before returning.
+// bild_head_stats / bild_head_stats_static: the final norm + LM head + softmax statistics of the decoding path
+// (the fused vocabulary sweep of a decoder pass) as a call of its own on hidden rows the caller already holds
+// on the device.  Both entry points run the same kernels; they differ only in where the scratch buffer lives
+// (per-workgroup partial statistics, the logits of the targets, one length word):
+//   bild_head_stats         allocates it with hipMalloc for the call and frees it before returning;
+//   bild_head_stats_static  uses a file-scope device array, so the call allocates nothing at all.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -16,6 +18,28 @@ namespace {
 // Scratch layout (bytes): [0, 256) one int (number of target slots); [256, 512) logits of the targets, one float per
 // row; [512, ...) partial statistics, StatPart[workgroups][kMaxRows].
 constexpr size_t kHdrBytes = 512;
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;  // 4 MiB
+constexpr int kStaticMaxParts = (int)((kStaticScratchBytes - kHdrBytes) / (sizeof(StatPart) * kMaxRows));
+
+// One copy per GPU the library runs on, kept until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress: the device address of the array is looked up once per device (scratch_of_device) and that
+// pointer is what kernels and every other call receive.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_of_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BILD_EHIP;
+    void* p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return BILD_EHIP;
+        __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return BILD_OK;
+}
 
 // Writes the number of target slots (rows + 1, or 0 for "no targets") and clears the target logits.
 __global__ __launch_bounds__(64) void head_stats_setup_kernel(int* nslots, float* zt, int value) {
@@ -136,4 +160,15 @@ extern "C" int bild_head_stats(const bild_model* m, const float* x_dev, int rows
     if (hipStreamSynchronize(st) != hipSuccess && rc == BILD_OK) rc = BILD_EHIP;  // the scratch is in use until here
     (void)hipFree(scr);
     return rc;
+}
+
+extern "C" int bild_head_stats_static(const bild_model* m, const float* x_dev, int rows, const int32_t* targets_dev,
+                                      bild_row_stats* out_dev, void* hip_stream) {
+    if (int rc = check_args(m, x_dev, rows, out_dev)) return rc;
+    if (kernels_init() != hipSuccess) return BILD_EHIP;
+    void* scr = nullptr;
+    if (int rc = scratch_of_device(&scr)) return rc;
+    const GemmArgs g = head_gemm(m, x_dev, rows, targets_dev, scr);
+    if ((int)gemm_num_blocks(g) > kStaticMaxParts) return BILD_ECAP;  // more partial statistics than the array holds
+    return head_stats_run(m, x_dev, rows, targets_dev, out_dev, (hipStream_t)hip_stream, scr, g);
 }
