@@ -277,7 +277,7 @@ extern "C" int bild_debug_gemm_shape(int n, int k, int rows, int gated, int lm_h
     out[2] = g.rw;
     out[3] = g.kc;
     out[4] = (int32_t)gemm_num_blocks(g);
-    out[5] = (rows + kMaxRows - 1) / kMaxRows;
+    out[5] = rows >= kDenseMinRows ? (rows + kDenseRows - 1) / kDenseRows : (rows + kMaxRows - 1) / kMaxRows;
     out[6] = (int32_t)gemm_lds_bytes(g, dtype);
     out[7] = 160 * 1024;
     return BILD_OK;

@@ -178,6 +178,14 @@ size_t gemm_lds_bytes(const GemmArgs& a, int dtype);
 
 // launch wrappers (kernels.hip); each returns the hipError_t of the launch
 hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st);
+// kDenseMinRows rows or more: the dense-tile kernel (gemm_dense.hip); launch_gemm forwards to it
+constexpr int kDenseMinRows = 513;
+constexpr int kDenseRows = 64;   // rows per workgroup
+constexpr int kDenseWaves = 4;
+constexpr int kDenseRW = 2;      // feature tiles per wave
+constexpr int dense_kc(int) { return 128; }  // inputs staged per chunk
+size_t dense_lds_bytes(int dt);
+hipError_t launch_gemm_dense(const GemmArgs& a, int dtype, hipStream_t st);
 hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st);
 hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st);
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st);

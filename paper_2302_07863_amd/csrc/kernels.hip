@@ -7,7 +7,8 @@
 //                    activation, residual add, LM-head softmax statistics) fused behind.
 //                    Launched as gemm_kernel (any T <= 32), gemm_row_kernel (T = 1 at compile
 //                    time), gemm_few_kernel (2-4 rows), gemm_merge_kernel (input still in key-split
-//                    attention partials) and gemm_rows_kernel (encoder / prompt prefill: blocks of 32 rows).
+//                    attention partials) and gemm_rows_kernel (an encoder over up to a few hundred rows: blocks of
+//                    32 rows).  Longer passes (prompt prefill) go to the dense-tile kernel of gemm_dense.hip.
 //   attn_body        KV-cache attention for T query rows of one head (attn_kernel; attn_rows_kernel
 //                    for more than 32 query rows; attn_merge_kernel joins key splits).
 //   embed_kernel     embedding gather + sinusoidal position.
@@ -24,112 +25,9 @@
 // activations at fp32 accuracy by splitting each value into a high and a low bf16 part
 // and issuing two MFMAs per weight tile; the matrix cores have an order of magnitude
 // more throughput than the stream needs, so this is free.
-#include <hip/hip_runtime.h>
-#include <math.h>
-
-#include <type_traits>
-
-#include "bild_internal.h"
+#include "kernel_common.h"
 
 namespace bild {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ uint32_t f2bf(float f) {  // fp32 -> bf16 bits, nearest even
-    uint32_t u = __float_as_uint(f);
-    return (u + (((u >> 16) & 1u) + 0x7FFFu)) >> 16;
-}
-__device__ __forceinline__ float bf2f(uint32_t h) { return __uint_as_float(h << 16); }
-
-// Two fp32 values as (high, low) bf16 pairs, a in the low half-words: high = bf16(v) to nearest even,
-// low = bf16(v - high), by the packed conversion instruction of gfx950.
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-    const f32x2 v = {a, b};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
-__device__ __forceinline__ void split_bf16x2(float a, float b, uint32_t& hi, uint32_t& lo) {
-    const f32x2 v = {a, b};
-    const bf16x2 h = __builtin_convertvector(v, bf16x2);
-    const f32x2 r = v - __builtin_convertvector(h, f32x2);
-    hi = __builtin_bit_cast(uint32_t, h);
-    lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2));
-}
-
-// Wavefront reductions on the data-parallel-primitive path (no LDS crossbar):
-// two quad permutes, two row mirrors, then row broadcasts carry the row totals
-// upward so that lane 63 holds the result, which is read back as a uniform value.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_f(float fill, float v) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, fill), __builtin_bit_cast(int, v),
-                                                                  CTRL, ROW_MASK, 0xF, false));
-}
-__device__ __forceinline__ float wave_sum(float v) {
-    v += dpp_f<0xB1, 0xF>(0.f, v);   // quad_perm [1,0,3,2]
-    v += dpp_f<0x4E, 0xF>(0.f, v);   // quad_perm [2,3,0,1]
-    v += dpp_f<0x141, 0xF>(0.f, v);  // row_half_mirror
-    v += dpp_f<0x140, 0xF>(0.f, v);  // row_mirror: every lane of a 16-lane row holds the row total
-    v += dpp_f<0x142, 0xA>(0.f, v);  // row_bcast15 into rows 1 and 3
-    v += dpp_f<0x143, 0xC>(0.f, v);  // row_bcast31 into rows 2 and 3
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-}
-__device__ __forceinline__ float wave_max(float v) {
-    v = fmaxf(v, dpp_f<0xB1, 0xF>(-INFINITY, v));
-    v = fmaxf(v, dpp_f<0x4E, 0xF>(-INFINITY, v));
-    v = fmaxf(v, dpp_f<0x141, 0xF>(-INFINITY, v));
-    v = fmaxf(v, dpp_f<0x140, 0xF>(-INFINITY, v));
-    v = fmaxf(v, dpp_f<0x142, 0xA>(-INFINITY, v));
-    v = fmaxf(v, dpp_f<0x143, 0xC>(-INFINITY, v));
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-}
-
-// ---- online softmax statistics ------------------------------------------------------
-struct Stat {
-    float m, s;
-    int idx;
-};
-__device__ __forceinline__ Stat stat_neutral() { return Stat{-INFINITY, 0.f, 0x7FFFFFFF}; }
-__device__ __forceinline__ void stat_push(Stat& a, float z, int n) {
-    if (z > a.m) {  // strict: equal maxima keep the lower id (ids arrive in increasing order)
-        a.s = a.s * expf(a.m - z) + 1.f;
-        a.m = z;
-        a.idx = n;
-    } else {
-        a.s += expf(z - a.m);
-    }
-}
-__device__ __forceinline__ Stat stat_merge(const Stat& a, const Stat& b) {
-    Stat r;
-    r.m = fmaxf(a.m, b.m);
-    const float sa = (a.m == -INFINITY) ? 0.f : a.s * expf(a.m - r.m);
-    const float sb = (b.m == -INFINITY) ? 0.f : b.s * expf(b.m - r.m);
-    r.s = sa + sb;
-    r.idx = (a.m > b.m || (a.m == b.m && a.idx < b.idx)) ? a.idx : b.idx;
-    return r;
-}
-__device__ __forceinline__ Stat stat_shfl_xor(const Stat& a, int o) {
-    Stat b;
-    b.m = __shfl_xor(a.m, o, 64);
-    b.s = __shfl_xor(a.s, o, 64);
-    b.idx = __shfl_xor(a.idx, o, 64);
-    return b;
-}
-
-__device__ __forceinline__ float gelu_tanh_f(float u) {
-    return 0.5f * u * (1.f + tanhf(0.7978845608028654f * (u + 0.044715f * u * u * u)));
-}
-__device__ __forceinline__ float silu_f(float u) { return u / (1.f + expf(-u)); }
-
-
-// ---- activation traffic: plain vector loads and stores (the kernel boundary makes them visible) ----
-__device__ __forceinline__ float4 ld_act4(const float* p) { return *(const float4*)p; }
-__device__ __forceinline__ float ld_act(const float* p) { return *p; }
-__device__ __forceinline__ void st_u64(void* p, uint32_t lo, uint32_t hi) { *(uint2*)p = make_uint2(lo, hi); }
-__device__ __forceinline__ void st_act4(float* p, const float4 v) { *(float4*)p = v; }
-__device__ __forceinline__ void st_act(float* p, float v) { *p = v; }
-__device__ __forceinline__ void st_u16(uint16_t* p, uint16_t v) { *p = v; }
 
 // =====================================================================================
 // Skinny GEMM.  A workgroup has nwv = wk * wr wavefronts arranged as wr feature groups
@@ -780,9 +678,11 @@ __global__ __launch_bounds__(512) void gemm_merge_kernel(const GemmArgs a) {
     gemm_body<DT, 1, EPI_RESID, 0, 1, gemm_batch(1, false), SPLITS, false, !SHORT>(a, (int)blockIdx.x, smem);
 }
 
-// More than kMaxRows rows (encoder, prompt prefill): blockIdx.y picks a block of kMaxRows rows and the same
-// body runs on it.  The blocks of one feature group re-read its weight tiles, which by then sit in L2 or
-// the memory-side cache, so HBM still streams every weight about once.
+// Between kMaxRows and kDenseMinRows rows (an encoder over a source of a few hundred tokens): blockIdx.y picks a block
+// of kMaxRows rows and the same body runs on it.  The blocks of one feature group re-read its weight tiles, which by
+// then sit in L2 or the memory-side cache, so HBM still streams every weight about once.  At these sizes a projection
+// is a GFLOP or two: too little to fill the dense-tile kernel's 64-row tiles on 256 compute units (measured on 512 rows
+// of 1024..4096-wide projections: 12..40 us per launch there, 12..25 us here); longer passes go to gemm_dense.hip.
 template <int DT, int RW, int EPI, int ROPE>
 __global__ __launch_bounds__(512) void gemm_rows_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -822,6 +722,13 @@ static int gemm_pick_chunks(GemmArgs& a, int dtype) {
 }
 
 void gemm_pick_shape(GemmArgs& a, int dtype) {
+    if (a.T >= kDenseMinRows) {  // many rows (long sources, prompt prefill): the dense-tile kernel has one fixed shape
+        a.wk = 1;
+        a.nwv = kDenseWaves;
+        a.rw = kDenseRW;
+        a.kc = dense_kc(dtype);
+        return;
+    }
     const int tiles_chunk = gemm_pick_chunks(a, dtype);
     const int Tb = std::min(a.T, kMaxRows);
     const int nacc = a.rw * ((Tb + 15) / 16);
@@ -836,7 +743,7 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     while (wk > 1 && (wk * nacc > 32 || wk > tiles_chunk)) wk /= 2;
     const int row_blocks = (a.T + kMaxRows - 1) / kMaxRows;
     if (row_blocks > 1) {
-        // Many rows: the staged activations are the larger stream, and every feature tile of a workgroup
+        // Several row blocks: the staged activations are the larger stream, and every feature tile of a workgroup
         // reuses them, so take as many feature tiles per workgroup (8 waves) as still leave one workgroup
         // per CU; the remaining waves split the inputs.
         int wr = 8;
@@ -862,6 +769,7 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
 }
 
 size_t gemm_lds_bytes(const GemmArgs& a, int dtype) {
+    if (a.T >= kDenseMinRows) return dense_lds_bytes(dtype);
     const int Tb = std::min(a.T, kMaxRows);
     const int nacc = a.rw * ((Tb + 15) / 16);
     return (size_t)xs_bytes(dtype, a.kc, Tb) + gemm_tail_bytes(a.nwv, nacc);
@@ -948,6 +856,7 @@ hipError_t kernels_init() { return raise_lds_limits(); }
 
 hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
+    if (a.T >= kDenseMinRows) return launch_gemm_dense(a, dtype, st);
     const size_t smem = gemm_lds_bytes(a, dtype);
     const unsigned row_blocks = (unsigned)((a.T + kMaxRows - 1) / kMaxRows);
     if (row_blocks > 1 && a.epi == EPI_LMHEAD) return hipErrorInvalidValue;  // softmax partials are per pass

@@ -92,8 +92,45 @@ def counters(path: str) -> str:
     return "\n".join(lines)
 
 
+def verify(path: str) -> str:
+    """Counter run of `bench.py --workload verify`: the dispatch list is cut at every run of bild::probe_empty_kernel
+    (the benchmark launches one before each row count 1, 4, 8, 16, 32); per segment and kernel group the mean of
+    every counter over the dispatches.  MfmaUtil is the profiler's derived counter: matrix-core busy cycles over
+    (GPU active cycles x SIMDs), in percent."""
+    rows = list(csv.DictReader(open(path)))
+    by_disp = collections.OrderedDict()
+    for r in sorted(rows, key=lambda r: int(r["Dispatch_Id"])):
+        d = by_disp.setdefault(int(r["Dispatch_Id"]), dict(kernel=_group(r["Kernel_Name"]), c={}))
+        d["c"][r["Counter_Name"]] = float(r["Counter_Value"])
+    segs, cur, in_sep = [], None, False
+    for d in by_disp.values():
+        if d["kernel"] == "bild::probe_empty_kernel":
+            if not in_sep:
+                cur = collections.defaultdict(list)
+                segs.append(cur)
+            in_sep = True
+            continue
+        in_sep = False
+        if cur is not None:
+            cur[d["kernel"]].append(d["c"])
+    t_values = (1, 4, 8, 16, 32)
+    lines = []
+    for i, seg in enumerate(segs[:len(t_values)]):
+        T = t_values[i]
+        lines.append(f"rows T={T}")
+        for k, ds in sorted(seg.items(), key=lambda kv: -len(kv[1])):
+            names = sorted({c for d in ds for c in d})
+            means = {c: sum(d.get(c, 0.0) for d in ds) / len(ds) for c in names}
+            lines.append(f"  {k:34s} dispatches {len(ds):6d}  " + "  ".join(f"{c}={means[c]:.4g}" for c in names))
+            if k == "bild::gemm_kernel<*>" and "MfmaUtil" in means:
+                lines.append(f"mfma_util_T{T}={means['MfmaUtil'] / 100.0:.5f}")
+    return "\n".join(lines)
+
+
 if __name__ == "__main__":
-    if len(sys.argv) >= 3 and sys.argv[1] == "stats":
+    if len(sys.argv) >= 3 and sys.argv[1] == "verify":
+        print(verify(sys.argv[2]))
+    elif len(sys.argv) >= 3 and sys.argv[1] == "stats":
         print(stats(sys.argv[2]))
     elif len(sys.argv) >= 3 and sys.argv[1] == "counters":
         print(counters(sys.argv[2]))

@@ -376,6 +376,25 @@ def test_relative_bias_with_key_splits_and_long_prompt():
     print(parity.teacher_forced(st, ref, R.n0, 0.4, 1.0, cfg), ref.stats, flush=True)
 
 
+@pytest.mark.parametrize("kw", [
+    dict(n_src=600),                                                                       # fp32, ReLU, encoder + cross K/V
+    dict(n_src=530, dtype=bi.DT_BF16, act=bi.ACT_GATED_GELU, tied=False, truncate=True),   # bf16, gated, both encoders
+    dict(n_src=577, act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=False),          # fp32 prompt prefill with RoPE
+    dict(n_src=640, dtype=bi.DT_BF16, pos=bi.POS_RELATIVE, d=128, heads=2, d_head=64, d_ff=160, vocab=333),
+])
+def test_passes_over_more_than_512_rows_take_the_dense_tile_kernel(kw):
+    """Sources / prompts longer than 512 tokens: the encoder (or the prompt prefill) runs on the dense-tile GEMM,
+    64 rows per workgroup with a ragged last block, in every epilogue it has (Q/K/V split with and without RoPE,
+    cross K/V without queries, residual add, ReLU and gated activation), fp32 and bf16 storage."""
+    cfg = bi.toy_pair(**kw)
+    assert pkg.binding.gemm_shape(cfg.large.d, cfg.large.d, cfg.n_src - 1, False, False, cfg.large.dtype)["kc"] == 128
+    R = Rig(cfg)
+    ref = oracle.bild_generate(R.req, 0.4, 1.0, 5, 12, keep_logits=True)
+    st = R.state(12, 5)
+    st.encode(R.src)
+    print(kw, parity.teacher_forced(st, ref, R.n0, 0.4, 1.0, cfg), ref.stats, flush=True)
+
+
 def _bf16_step(a):
     """Spacing of bf16 values at the magnitude of a (8 significant bits)."""
     return np.ldexp(1.0, np.frexp(np.maximum(np.abs(a), 1e-30))[1] - 8)
