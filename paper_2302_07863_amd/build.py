@@ -18,6 +18,7 @@ LIB = os.path.join(PKG, "libbild.so")
 UNITS = [
     ("kernels.hip", "kernels.o", []),
     ("gemm_dense.hip", "gemm_dense.o", []),
+    ("attention.hip", "attention.o", []),
     ("bild_api.hip", "bild_api.o", []),
     ("head_stats.hip", "head_stats.o", []),
     ("bench_api.hip", "bench_api.o", []),

@@ -191,6 +191,7 @@ hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st);
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st);
 hipError_t launch_row_copy(const RowCopyArgs& a, hipStream_t st);
 hipError_t kernels_init();  // one-time function attributes; call before any stream capture
+hipError_t attention_init();  // (attention.hip; called by kernels_init)
 size_t gemm_num_blocks(const GemmArgs& a);
 size_t attn_lds_bytes(int dtype, int d_head, int T, int nw);
 void gemm_pick_shape(GemmArgs& a, int dtype);
