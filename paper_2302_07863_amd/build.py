@@ -17,6 +17,7 @@ LIB = os.path.join(PKG, "libbild.so")
 # (source, object name, extra defines)
 UNITS = [
     ("kernels.hip", "kernels.o", []),
+    ("gemm_pre.hip", "gemm_pre.o", []),
     ("gemm_dense.hip", "gemm_dense.o", []),
     ("attention.hip", "attention.o", []),
     ("bild_api.hip", "bild_api.o", []),

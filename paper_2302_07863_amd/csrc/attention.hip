@@ -300,7 +300,15 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int vblock, c
         if (t < T && d0 < dh) {
             if (a.splits == 1) {
                 const float inv = 1.f / Lsum;
-                st_act4(a.out + (size_t)t * I + h * dh + d0, make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv));
+                if (DT && a.ob_hi) {
+                    uint32_t h01, l01, h23, l23;
+                    split_bf16x2(acc[0] * inv, acc[1] * inv, h01, l01);
+                    split_bf16x2(acc[2] * inv, acc[3] * inv, h23, l23);
+                    st_u64(a.ob_hi + (size_t)t * I + h * dh + d0, h01, h23);
+                    st_u64(a.ob_lo + (size_t)t * I + h * dh + d0, l01, l23);
+                } else {
+                    st_act4(a.out + (size_t)t * I + h * dh + d0, make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv));
+                }
             } else {
                 st_act4(a.part_o + ((size_t)sp * T + t) * I + h * dh + d0, make_float4(acc[0], acc[1], acc[2], acc[3]));
                 if (dt == 0 && g == 0) {
@@ -372,7 +380,15 @@ __device__ __forceinline__ void attn_merge_body(const AttnArgs& a, const int u) 
         }
     }
     const float inv = 1.f / L;
-    st_act4(a.out + (size_t)t * I + n, make_float4(r.x * inv, r.y * inv, r.z * inv, r.w * inv));
+    if (a.ob_hi) {
+        uint32_t h01, l01, h23, l23;
+        split_bf16x2(r.x * inv, r.y * inv, h01, l01);
+        split_bf16x2(r.z * inv, r.w * inv, h23, l23);
+        st_u64(a.ob_hi + (size_t)t * I + n, h01, h23);
+        st_u64(a.ob_lo + (size_t)t * I + n, l01, l23);
+    } else {
+        st_act4(a.out + (size_t)t * I + n, make_float4(r.x * inv, r.y * inv, r.z * inv, r.w * inv));
+    }
 }
 
 __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) { attn_merge_body(a, (int)blockIdx.x); }

@@ -313,6 +313,7 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
     {
         const char* ng = std::getenv("BILD_NO_GRAPH");
         s->use_graphs = !(ng && ng[0] == '1');
+        if (const char* pm = std::getenv("BILD_PRE_MIN_ROWS")) s->pre_min_rows = std::atoi(pm);  // experiments; > 32 turns the planes off
     }
     for (int w = 0; w < 2; ++w) {
         ModelState& M = s->ms[w];
@@ -346,6 +347,12 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         AL(M.q, sizeof(float) * M.rows_cap * I);
         AL(M.a, sizeof(float) * M.rows_cap * I);
         AL(M.h, sizeof(float) * M.rows_cap * F);
+        if (m->cfg.dtype == BILD_DT_BF16) {
+            AL(M.xb, sizeof(uint16_t) * 2 * kMaxRows * d);
+            AL(M.ab, sizeof(uint16_t) * 2 * kMaxRows * I);
+            AL(M.hb, sizeof(uint16_t) * 2 * kMaxRows * F);
+            AL(M.ssq, sizeof(float) * (kMaxSsqParts + 8) * kMaxRows);
+        }
         M.nparts_cap = (m->head.tn + 0) / 1 + 1;  // at most one partial per feature tile
         AL(M.part, sizeof(StatPart) * (size_t)M.nparts_cap * kMaxRows);
         AL(M.zt, sizeof(float) * kMaxRows);
@@ -563,7 +570,7 @@ int emit_attention(bild_state* s, const ModelState& M, AttnArgs& a, int nkeys, i
 }
 
 // Embedding and all decoder layers of model w over rows y[len .. len+T).
-int emit_layers(bild_state* s, int w, int T, int key_hint) {
+int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
     ModelState& M = s->ms[w];
     const bild_model* m = M.m;
     const bild_model_config& c = m->cfg;
@@ -587,6 +594,33 @@ int emit_layers(bild_state* s, int w, int T, int key_hint) {
     const int trunk = s->pair->trunk_layers;
     const bool above_trunk = trunk > 0 && w == 1;
     const int layer0 = above_trunk ? trunk : 0;
+    // Passes of a few rows of a bf16 model: every producer leaves its output as high / low bf16 planes for the
+    // projection that follows (x times that projection's norm gain, the attention output, the FFN hidden state).
+    // Measured (us per large-model pass, planes / fp32 hand-over): 1024-wide model 2 rows 1002 / 947, 5 rows 1121 / 1148,
+    // 16 rows 1332 / 1429, 32 rows 1831 / 2018; 4096-wide model 2 rows 3398 / 3487, 11 rows 3904 / 4326, 32 rows 5321 / 6384.
+    // Below five rows the narrow models keep the kernels specialised for one and for two to four rows.
+    const int planes_from = s->pre_min_rows > 0 ? s->pre_min_rows : (d >= 2048 ? 2 : 5);
+    const bool planes = dt == BILD_DT_BF16 && T >= planes_from && T <= kMaxRows && M.xb != nullptr;
+    uint16_t *xb_hi = M.xb, *xb_lo = M.xb ? M.xb + (size_t)kMaxRows * d : nullptr;
+    uint16_t *ab_hi = M.ab, *ab_lo = M.ab ? M.ab + (size_t)kMaxRows * I : nullptr;
+    uint16_t *hb_hi = M.hb, *hb_lo = M.hb ? M.hb + (size_t)kMaxRows * F : nullptr;
+    int xb_parts = 0;  // > 0: xb holds the current residual stream, with this many partial sums of squares in M.ssq
+    // the norm gain in front of the projection that reads the residual stream next
+    auto set_in = [&](GemmArgs& g) {  // input from the residual-stream planes, if they are current
+        if (xb_parts > 0) { g.xb_hi = xb_hi; g.xb_lo = xb_lo; g.ssq_part = M.ssq; g.ssq_parts = xb_parts; }
+    };
+    auto set_out = [&](GemmArgs& g, const float* next_gain) {  // residual epilogue: also planes for the next projection
+        if (!planes) return;
+        g.nx_hi = xb_hi; g.nx_lo = xb_lo; g.nx_gain = next_gain; g.nx_ssq = M.ssq; g.nx_ld = d;
+    };
+    auto after_out = [&](const GemmArgs& g) {  // (after gemm_pick_shape) one partial per wave that owns output tiles
+        xb_parts = planes ? (int)gemm_num_blocks(g) * (g.nwv / g.wk) : 0;
+        if (xb_parts > kMaxSsqParts) xb_parts = 0;  // more than a consumer adds up: the next projection converts x itself
+    };
+    if (planes && !above_trunk) {
+        e.nx_hi = xb_hi; e.nx_lo = xb_lo; e.nx_gain = m->dec[layer0].ln1; e.nx_ssq = M.ssq;
+        xb_parts = kEmbedSsqParts;
+    }
     if (!s->gemm_only) {
         if (above_trunk) {
             RowCopyArgs rc;
@@ -617,6 +651,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint) {
             g.vcap = s->cap_len;
             g.pos_ptr = len_ptr;
             g.rope = c.pos == BILD_POS_ROPE;
+            set_in(g);
             int rc = emit_gemm(s, m, g);
             if (rc) return rc;
         }
@@ -632,6 +667,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint) {
             a.vcap = s->cap_len;
             a.part_o = M.att_o; a.part_ml = M.att_ml;
             a.scale = att_scale;
+            if (planes) { a.ob_hi = ab_hi; a.ob_lo = ab_lo; }
             int rc = emit_attention(s, M, a, key_hint, &merge_splits);
             if (rc) return rc;
         }
@@ -641,8 +677,11 @@ int emit_layers(bild_state* s, int w, int T, int key_hint) {
             g.out = M.x;
             g.ldo = d;
             if (merge_splits > 1) { g.mg_splits = merge_splits; g.mg_o = M.att_o; g.mg_ml = M.att_ml; g.mg_heads = c.n_heads; }
+            else if (planes) { g.xb_hi = ab_hi; g.xb_lo = ab_lo; }
+            set_out(g, c.cross_attn ? L.lnc : L.ln2);
             int rc = emit_gemm(s, m, g);
             if (rc) return rc;
+            after_out(g);
         }
         if (c.cross_attn) {
             {
@@ -650,6 +689,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint) {
                 g.epi = EPI_STORE;
                 g.out = M.q;
                 g.ldo = I;
+                set_in(g);
                 int rc = emit_gemm(s, m, g);
                 if (rc) return rc;
             }
@@ -666,6 +706,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint) {
                 a.len_ptr = &s->ctl->n_src;
                 a.part_o = M.att_o; a.part_ml = M.att_ml;
                 a.scale = att_scale;
+                if (planes) { a.ob_hi = ab_hi; a.ob_lo = ab_lo; }
                 int rc = emit_attention(s, M, a, s->n_src, &merge_splits);
                 if (rc) return rc;
             }
@@ -675,8 +716,11 @@ int emit_layers(bild_state* s, int w, int T, int key_hint) {
                 g.out = M.x;
                 g.ldo = d;
                 if (merge_splits > 1) { g.mg_splits = merge_splits; g.mg_o = M.att_o; g.mg_ml = M.att_ml; g.mg_heads = c.n_heads; }
+                else if (planes) { g.xb_hi = ab_hi; g.xb_lo = ab_lo; }
+                set_out(g, L.ln2);
                 int rc = emit_gemm(s, m, g);
                 if (rc) return rc;
+                after_out(g);
             }
         }
         {
@@ -684,16 +728,22 @@ int emit_layers(bild_state* s, int w, int T, int key_hint) {
             g.epi = EPI_ACT;
             g.out = M.h;
             g.ldo = F;
+            set_in(g);
+            // the hidden state goes on as planes only if this projection itself reads planes (one kernel family per pass)
+            const bool h_planes = planes && g.xb_hi != nullptr;
+            if (h_planes) { g.nx_hi = hb_hi; g.nx_lo = hb_lo; g.nx_ld = F; }
             int rc = emit_gemm(s, m, g);
             if (rc) return rc;
-        }
-        {
-            GemmArgs g = gemm_base(m, L.wout, M.h, F, T, nullptr);
-            g.epi = EPI_RESID;
-            g.out = M.x;
-            g.ldo = d;
-            int rc = emit_gemm(s, m, g);
+            GemmArgs g2 = gemm_base(m, L.wout, M.h, F, T, nullptr);
+            g2.epi = EPI_RESID;
+            g2.out = M.x;
+            g2.ldo = d;
+            if (h_planes) { g2.xb_hi = hb_hi; g2.xb_lo = hb_lo; }
+            // the next reader of the residual stream: the following layer's first norm, or the final norm (LM head)
+            if (h_planes) set_out(g2, l + 1 < c.n_dec_layers ? m->dec[l + 1].ln1 : m->dec_final);
+            rc = emit_gemm(s, m, g2);
             if (rc) return rc;
+            if (h_planes) after_out(g2); else xb_parts = 0;
         }
     }
     if (trunk > 0 && w == 0 && !s->gemm_only) {  // remember what the trunk produced for these positions
@@ -706,6 +756,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint) {
         rc.T = T;
         HIPC(launch_row_copy(rc, s->stream));
     }
+    *xb_parts_out = xb_parts;
     return BILD_OK;
 }
 
@@ -722,8 +773,9 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
     const bild_model_config& c = m->cfg;
     const int d = c.d_model, dt = c.dtype;
     const int* len_ptr = &s->ctl->len[w];
+    int xb_parts = 0;  // > 0: the final hidden state also sits in M.xb as bf16 planes (times the final norm's gain)
     {
-        int rc = emit_layers(s, w, T, key_hint);
+        int rc = emit_layers(s, w, T, key_hint, &xb_parts);
         if (rc) return rc;
     }
     FinishArgs f;
@@ -746,6 +798,12 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
         g.zt = M.zt;
         g.dbg = (s->debug_logits || s->top_p > 0.f) ? M.dbg : nullptr;  // the draw of the sampling variant reads the logits
         g.row_off = 0;
+        if (xb_parts > 0) {
+            g.xb_hi = M.xb + (size_t)(T - lm_rows) * d;
+            g.xb_lo = M.xb + (size_t)kMaxRows * d + (size_t)(T - lm_rows) * d;
+            g.ssq_part = M.ssq + (T - lm_rows);
+            g.ssq_parts = xb_parts;
+        }
         gemm_pick_shape(g, dt);
         if ((int)gemm_num_blocks(g) > M.nparts_cap) return BILD_ECAP;
         {

@@ -103,6 +103,17 @@ struct GemmArgs {
     const float* mg_o;   // [mg_splits][T][ldx] unnormalised outputs
     const float* mg_ml;  // [mg_splits][T][mg_heads][2]
     int mg_heads;
+    // bf16 models, passes of a few rows: activations travel between projections as two bf16 planes (high part and
+    // low part of each value, [T][ld]) written once by the producer, with the consumer's norm gain already applied
+    const uint16_t* xb_hi;  // input planes (non-null: x, gain are not read; ldx is their row stride)
+    const uint16_t* xb_lo;
+    const float* ssq_part;  // [ssq_parts][kMaxRows]: partial sums of x^2 per row, one per producer wave (norm only)
+    int ssq_parts;
+    uint16_t* nx_hi;        // output planes for the next projection (EPI_RESID: of out * nx_gain, beside the fp32 out;
+    uint16_t* nx_lo;        //  EPI_ACT: of the activation, instead of the fp32 out)
+    const float* nx_gain;   // EPI_RESID: gain of the norm in front of the next projection
+    float* nx_ssq;          // EPI_RESID: [feature tiles / rw][kMaxRows] sums of out^2 per owner wave
+    int nx_ld;
     // launch shape
     int wk;   // input slices per workgroup
     int nwv;  // waves per workgroup = wk * feature groups (4 or 8)
@@ -131,6 +142,10 @@ struct AttnArgs {
     // row_pos = base + t (causal) or base_add + t (not causal).  Null: no bias.
     const float* rel_bias;      // [heads][2*rel_d + 1]
     int rel_d;
+    // non-null (bf16 models): the finished output goes to these bf16 planes [T][I] (high and low part of each value,
+    // what the output projection stages) instead of `out`; not used while the partials are left to the consumer
+    uint16_t* ob_hi;
+    uint16_t* ob_lo;
 };
 
 struct EmbedArgs {
@@ -141,7 +156,15 @@ struct EmbedArgs {
     int T, d, vocab, tie_shift, sinusoidal;
     float embed_scale;
     float* x;  // [T][d]
+    // non-null (bf16 models): x * nx_gain also as bf16 planes [T][d] for the first projection, and the sum of x^2 of
+    // each row in four parts (one per wave), nx_ssq[wave][kMaxRows]
+    uint16_t* nx_hi;
+    uint16_t* nx_lo;
+    const float* nx_gain;
+    float* nx_ssq;
 };
+constexpr int kEmbedSsqParts = 4;
+constexpr int kMaxSsqParts = 256;  // partial sums of squares a consumer adds per row
 
 // Copies T rows of d floats: dst[dst_row + t] = src[src_row + t], each row index = (*ptr or 0) + add.
 // Carries the hidden state between the shared trunk and the upper layers of an early-exit pair.
@@ -186,6 +209,9 @@ constexpr int kDenseRW = 2;      // feature tiles per wave
 constexpr int dense_kc(int) { return 128; }  // inputs staged per chunk
 size_t dense_lds_bytes(int dt);
 hipError_t launch_gemm_dense(const GemmArgs& a, int dtype, hipStream_t st);
+// bf16 passes whose activations travel as planes (gemm_pre.hip); launch_gemm forwards to it
+hipError_t launch_gemm_pre(const GemmArgs& a, hipStream_t st);
+hipError_t gemm_pre_init();
 hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st);
 hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st);
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st);

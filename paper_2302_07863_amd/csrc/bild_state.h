@@ -77,6 +77,11 @@ struct ModelState {
     char* enc_k = nullptr;    // [max_src][I]
     char* enc_v = nullptr;
     int last_rows = 0;        // rows of the last LM-head pass (for debug logits)
+    // bf16 models: activations of a pass of a few rows as high / low bf16 planes (see GemmArgs::xb_hi)
+    uint16_t* xb = nullptr;   // [2][32][d]   residual stream times the next norm's gain
+    uint16_t* ab = nullptr;   // [2][32][I]   attention output
+    uint16_t* hb = nullptr;   // [2][32][F]   FFN hidden
+    float* ssq = nullptr;     // [d / 16 + 8][32] partial sums of squares beside xb
 };
 
 struct bild_state {
@@ -89,6 +94,7 @@ struct bild_state {
     float* halpha = nullptr;  // pinned staging for threshold updates
     float alpha_fb = -1.f, alpha_rb = -1.f;  // thresholds currently in the device control block
     bool use_graphs = true;
+    int pre_min_rows = 0;         // > 0 (experiments): row count from which a bf16 pass hands activations on as bf16 planes
     bool gemm_only = false;       // measurement: a pass launches only its weight-streaming GEMMs
     int64_t gemm_count = 0, gemm_bytes = 0;  // tallied while a pass is being issued
     std::map<std::array<int, 6>, hipGraphExec_t> graphs;  // captured passes by (model, rows, lm rows, mode, key bucket, debug)

@@ -70,6 +70,40 @@ def test_toy_teacher_forced_logits_and_decisions(name, fb, rb, nm):
     print(name, worst)
 
 
+@pytest.mark.parametrize("name", ["bf16-relu-tied", "bf16-trunc-geglu", "bf16-rope-swiglu-deconly",
+                                  "bf16-relative-trunc-geglu"])
+@pytest.mark.parametrize("first_rows", [1, 2])
+def test_bf16_plane_handover_at_every_row_count(name, first_rows, monkeypatch):
+    """bf16 passes hand activations from kernel to kernel as high / low bf16 planes from some row count on (by
+    default only where that is faster); here from one row / from two rows on, so that every producer and consumer of
+    the planes (embedding, residual projections, attention, merged key splits, FFN, LM head) meets the oracle at the
+    small row counts as well.  The state reads the setting when it is created."""
+    monkeypatch.setenv("BILD_PRE_MIN_ROWS", str(first_rows))
+    R = rig(name)
+    for fb, rb, nm in ((0.5, 2.0, 10), (0.2, 0.7, 3)):
+        ref = oracle.bild_generate(R.req, fb, rb, nm, R.cfg.max_new, keep_logits=True)
+        st = R.state(R.cfg.max_new, nm)
+        st.encode(R.src)
+        worst = parity.teacher_forced(st, ref, R.n0, fb, rb, R.cfg)
+        print(name, first_rows, worst)
+    # blocks of 1..32 rows with the planes against the same blocks without them: same distributions up to rounding order
+    block = [int(t) for t in bi.make_tokens(R.cfg.large.vocab, 31, seed=5)]
+    rows = {}
+    for setting in (str(first_rows), "99"):
+        monkeypatch.setenv("BILD_PRE_MIN_ROWS", setting)
+        st = R.state(40, 10)
+        st.encode(R.src)
+        st.debug_enable_logits(True)
+        out = []
+        for n in (0, 1, 3, 4, 7, 15, 16, 31):
+            st.force_tokens(R.n0, [], R.n0)
+            st.large_verify(INF, draft=block[:n])
+            out.append(np.stack([st.debug_logits(pkg.LARGE, i) for i in range(n + 1)]))
+        rows[setting] = out
+    for a, b in zip(rows[str(first_rows)], rows["99"]):
+        assert np.max(np.abs(a - b)) <= parity.logit_tol(R.cfg)
+
+
 @pytest.mark.parametrize("name", list(TOY_VARIANTS))
 def test_toy_free_running_generate(name):
     R = rig(name)
