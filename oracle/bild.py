@@ -137,12 +137,24 @@ def greedy(req: Request, which: str, max_new: int, eos: int = -1, cached: bool =
 
 
 def bild_generate(req: Request, alpha_fb: float, alpha_rb: float, n_max: int, max_new: int,
-                  eos: int = -1, cached: bool = True, keep_logits: bool = False, sampler=None) -> Result:
+                  eos: int = -1, cached: bool = True, keep_logits: bool = False, sampler=None,
+                  acceptance: str = "threshold") -> Result:
     """Algorithm 1.  keep_logits stores every evaluated logit row in the trace
     (for element-wise comparison against another implementation).  With a
     sampler (oracle.sampling.Sampler) both models draw their tokens instead of
     taking the argmax; the two policies are unchanged (Appendix, BiLD with
-    Sampling)."""
+    Sampling).
+
+    acceptance="rejection" (needs a sampler with u_accept) replaces the rollback
+    test by the rejection-sampling rule of the speculative-decoding methods the
+    paper compares with (Section 4.2; appendix comparison): the first drafted
+    token that the rule refuses is where the review stops, and its replacement is
+    drawn from the normalised positive part of p_L - p_S; alpha_rb is not used.
+    With alpha_fb = 0 and n_max = the window this is those methods' fixed-window
+    procedure."""
+    assert acceptance in ("threshold", "rejection")
+    assert acceptance == "threshold" or (sampler is not None and sampler.u_accept is not None)
+    z_small_at = {}                      # rejection acceptance: the small model's logits at each pending draft position
     y = req.initial()
     n0 = len(y)
     src_small = [False] * n0
@@ -165,6 +177,8 @@ def bild_generate(req: Request, alpha_fb: float, alpha_rb: float, n_max: int, ma
         if keep_logits:
             trace[-1]["z"] = z_s
         if not (low_conf or forced):
+            if acceptance == "rejection":
+                z_small_at[len(y)] = z_s
             y.append(tok_s)
             src_small.append(True)
             continue
@@ -175,17 +189,30 @@ def bild_generate(req: Request, alpha_fb: float, alpha_rb: float, n_max: int, ma
         st.large_calls += 1
         st.rows_verified += n + 1
         nlls = []
+        accept_margins = []
         r = n
         for i in range(n):
-            nlls.append(policy.nll(z_l[i], y[draft_start + i]))
-            if policy.rollback(z_l[i], y[draft_start + i], alpha_rb):
+            q = draft_start + i
+            nlls.append(policy.nll(z_l[i], y[q]))
+            if acceptance == "rejection":
+                ok, am = sampler.accept(z_small_at[q], z_l[i], y[q], q)
+                accept_margins.append(am)
+                refused = not ok
+            else:
+                refused = policy.rollback(z_l[i], y[q], alpha_rb)
+            if refused:
                 r = i
                 break
-        tok_l, dm_l = ((policy.argmax_lowest(z_l[r]), None) if sampler is None
-                       else sampler.pick("large", z_l[r], draft_start + r))
+        if sampler is None:
+            tok_l, dm_l = policy.argmax_lowest(z_l[r]), None
+        elif acceptance == "rejection" and r < n:
+            tok_l, dm_l = sampler.replace(z_small_at[draft_start + r], z_l[r], draft_start + r)
+        else:
+            tok_l, dm_l = sampler.pick("large", z_l[r], draft_start + r)
         trace.append(dict(kind="large", draft_start=draft_start, n=n, r=r, tok=tok_l, nll=nlls,
                           gaps=[policy.top2_gap(z_l[i]) for i in range(r + 1)],
-                          pmax=policy.max_prob(z_l[r]), draw_margin=dm_l))
+                          pmax=policy.max_prob(z_l[r]), draw_margin=dm_l, accept_margins=accept_margins))
+        z_small_at.clear()
         if keep_logits:
             trace[-1]["z"] = z_l
         if r < n:

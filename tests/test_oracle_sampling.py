@@ -125,3 +125,102 @@ def test_sampling_loop_reduces_to_greedy_and_follows_its_definition(kw):
         z = req.large.logits_full(y, req.cross_l)[-1]
         assert tok == sampling.draw(z, 0.8, smp.u["large"][n0 + i])[0]
         y.append(tok)
+
+
+# ---- rejection-sampling acceptance (Section 4.2 / appendix comparison: the rule of the speculative-decoding methods) ----
+
+def test_worked_example_of_the_rejection_rule():
+    # q = (0.5, 0.3, 0.2), p = (0.2, 0.5, 0.3): token 0 is kept with probability 0.2 / 0.5, tokens 1 and 2 always;
+    # the positive part of p - q is (0, 0.2, 0.1), so a refused draft becomes token 1 with probability 2/3
+    zq, zp = _logits([0.5, 0.3, 0.2]), _logits([0.2, 0.5, 0.3])
+    assert sampling.accept(zq, zp, 1.0, 0, 0.39)[0] and not sampling.accept(zq, zp, 1.0, 0, 0.41)[0]
+    assert abs(sampling.accept(zq, zp, 1.0, 0, 0.39)[1] - 0.005) < 1e-12          # |0.39 * 0.5 - 0.2|
+    for u in (0.0, 0.5, 0.999999):
+        assert sampling.accept(zq, zp, 1.0, 1, u)[0] and sampling.accept(zq, zp, 1.0, 2, u)[0]
+    assert [sampling.residual_draw(zq, zp, 1.0, u)[0] for u in (0.0, 0.6, 0.66, 0.67, 0.99)] == [1, 1, 1, 2, 2]
+
+
+def test_rejection_rule_with_a_nucleus_uses_the_renormalised_distributions():
+    # top_p 0.75: the small model's nucleus is {0, 1} -> q = (0.625, 0.375, 0); the large model's is {1, 2} -> p = (0, 0.625, 0.375)
+    zq, zp = _logits([0.5, 0.3, 0.2]), _logits([0.2, 0.5, 0.3])
+    assert np.allclose(sampling.nucleus_probs(zq, 0.75), [0.625, 0.375, 0.0])
+    assert np.allclose(sampling.nucleus_probs(zp, 0.75), [0.0, 0.625, 0.375])
+    assert not sampling.accept(zq, zp, 0.75, 0, 0.0)[0]                            # p(0) = 0: never kept, not even at u = 0
+    assert sampling.accept(zq, zp, 0.75, 1, 0.999)[0]
+    # positive part of p - q = (0, 0.25, 0.375): token 1 up to u = 0.4
+    assert [sampling.residual_draw(zq, zp, 0.75, u)[0] for u in (0.0, 0.39, 0.41, 0.99)] == [1, 1, 2, 2]
+
+
+@pytest.mark.parametrize("seed,top_p", [(0, 1.0), (1, 1.0), (2, 0.8), (3, 0.6)])
+def test_rejection_rule_returns_a_token_distributed_as_the_large_model(seed, top_p):
+    """The property the rule exists for: draft from q, keep or replace, and the result follows p exactly.  Measured
+    through the oracle's own functions on fine grids of the three uniform numbers (draft, acceptance, replacement)."""
+    rng = np.random.default_rng(seed)
+    v, n = 6, 4000
+    zq, zp = rng.normal(size=v) * 1.5, rng.normal(size=v) * 1.5
+    grid = (np.arange(n) + 0.5) / n
+    q_hat = np.bincount([sampling.draw(zq, top_p, u)[0] for u in grid], minlength=v) / n
+    out = np.zeros(v)
+    repl = np.bincount([sampling.residual_draw(zq, zp, top_p, u)[0] for u in grid], minlength=v) / n
+    for x in range(v):
+        if q_hat[x] == 0:
+            continue
+        keep = np.mean([sampling.accept(zq, zp, top_p, x, u)[0] for u in grid])
+        out[x] += q_hat[x] * keep
+        out += q_hat[x] * (1.0 - keep) * repl
+    assert np.max(np.abs(out - sampling.nucleus_probs(zp, top_p))) < 4.0 / n * v
+
+
+def test_identical_distributions_are_never_refused():
+    rng = np.random.default_rng(5)
+    z = rng.normal(size=50) * 2
+    for top_p in (0.5, 0.9, 1.0):
+        members, _, _ = sampling.nucleus(z, top_p)
+        for tok in np.nonzero(members)[0]:
+            assert sampling.accept(z, z, top_p, int(tok), 0.999999)[0]
+
+
+def _rejection_sampler(cfg, top_p, n):
+    return oracle.Sampler(top_p, bi.make_uniforms(n, cfg.input_seed, 0), bi.make_uniforms(n, cfg.input_seed, 1),
+                          bi.make_uniforms(n, cfg.input_seed, 2))
+
+
+@pytest.mark.parametrize("kw", [dict(), dict(act=bi.ACT_SWIGLU, pos=bi.POS_ROPE, cross=False, tied=False)])
+def test_rejection_acceptance_in_the_loop(kw):
+    cfg, req = _request(**kw)
+    n0 = len(req.initial())
+    n = n0 + cfg.max_new + 2
+    smp = _rejection_sampler(cfg, 0.9, n)
+    # fixed window of 4 (alpha_FB = 0): the cached loop equals the definition form
+    a = oracle.bild_generate(req, 0.0, 0.0, 4, cfg.max_new, sampler=smp, acceptance="rejection", keep_logits=True)
+    b = oracle.bild_generate(req, 0.0, 0.0, 4, cfg.max_new, sampler=smp, acceptance="rejection", cached=False)
+    assert a.tokens == b.tokens and a.stats == b.stats
+    assert a.stats.fallbacks_conf == 0 and a.stats.large_calls > 0
+    # every review is the rule applied by hand to the distributions of the definition: kept drafts pass it, the first
+    # refused one fails it and is replaced by the draw from the positive part of p_L - p_S
+    y = req.initial()
+    for rec in a.trace:
+        if rec["kind"] == "small":
+            if not rec["fallback"]:
+                y.append(rec["tok"])
+            continue
+        ds, nd, r = rec["draft_start"], rec["n"], rec["r"]
+        assert len(y) == ds + nd
+        for i in range(min(r + 1, nd)):
+            zs = req.small.logits_full(y[:ds + i], req.cross_s)[-1]
+            zl = req.large.logits_full(y[:ds + i], req.cross_l)[-1]
+            ok = sampling.accept(zs, zl, 0.9, y[ds + i], smp.u_accept[ds + i])[0]
+            assert ok == (i < r)
+        zl = req.large.logits_full(y[:ds + r], req.cross_l)[-1]
+        if r < nd:
+            zs = req.small.logits_full(y[:ds + r], req.cross_s)[-1]
+            assert rec["tok"] == sampling.residual_draw(zs, zl, 0.9, smp.u["large"][ds + r])[0]
+        else:
+            assert rec["tok"] == sampling.draw(zl, 0.9, smp.u["large"][ds + r])[0]
+        y = y[:ds + r] + [rec["tok"]]
+    assert y[n0:] == a.tokens
+    assert a.stats.rollbacks > 0                               # the toy pair does get refused now and then
+    # a pair of identical models never refuses a draft
+    same = oracle.Request(req.large, req.large, bi.make_source(cfg), cfg.decoder_only)
+    c = oracle.bild_generate(same, 0.0, 0.0, 4, cfg.max_new, sampler=smp, acceptance="rejection")
+    assert c.stats.rollbacks == 0 and c.stats.tokens_discarded == 0 and c.stats.large_calls > 0
