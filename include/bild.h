@@ -196,6 +196,22 @@ int bild_large_verify(bild_state* s, const int32_t* draft, int n, float alpha_rb
  * may then be NULL).  BILD_EINVAL for top_p > 1, a missing array, n < max_len or a number outside [0, 1). */
 int bild_set_sampling(bild_state* s, float top_p, const float* u_small, const float* u_large, int n);
 
+/* Acceptance rule of the review (Section 4.2 and the appendix comparison with speculative decoding, Tables 3-4).
+ * BILD_ACCEPT_THRESHOLD (the default) is the paper's rollback policy, Section 3.4: the first draft with
+ * -ln p_L(draft) > alpha_RB is rolled back.  BILD_ACCEPT_REJECTION is the stochastic rule of the methods the paper
+ * compares with; it needs the sampling variant (bild_set_sampling called first, else BILD_ESTATE): with p_S the nucleus
+ * distribution the small model drew a draft x from and p_L the large model's nucleus distribution of the same position,
+ * x is kept iff u_accept[position] * p_S(x) < p_L(x); the first refused draft is replaced by a draw (the large model's
+ * uniform number of that position, ids walked in increasing order) from the normalised positive part of p_L - p_S, and
+ * if none is refused the next token is drawn from p_L as usual; alpha_RB is ignored.  The fallback policy is unchanged
+ * (alpha_FB = 0 with n_max = w gives the fixed window w of those methods).  u_accept: host array of n >= max_len
+ * numbers in [0, 1), copied; may be NULL for BILD_ACCEPT_THRESHOLD.  The library then keeps the small model's logits
+ * of every pending draft (32 x vocabulary floats of device memory).  BILD_EINVAL for an unknown rule, a missing or
+ * short array or a number outside [0, 1). */
+#define BILD_ACCEPT_THRESHOLD 0
+#define BILD_ACCEPT_REJECTION 1
+int bild_set_acceptance(bild_state* s, int rule, const float* u_accept, int n);
+
 /* Lowers a cache length (Algorithm 1, the rollback step y <- y[:m] + [large model's token]; Section 3.4: the
  * predictions after the rolled-back position are discarded): which = 1 small, 2 large, 3 both; the cache(s) keep
  * their first pos rows (O(1): only a length changes).  BILD_EINVAL if pos exceeds

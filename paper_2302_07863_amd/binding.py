@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_PKG, "libbild.so")
 OK, EINVAL, ESTATE, ECAP, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5
 MAX_ROWS = 32
 SMALL, LARGE, BOTH = 1, 2, 3
+ACCEPT_THRESHOLD, ACCEPT_REJECTION = 0, 1
 
 
 class ModelConfig(C.Structure):
@@ -62,6 +63,7 @@ _SIGS = {
     "bild_large_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.POINTER(C.c_int32),
                                     C.POINTER(C.c_int32), C.c_void_p]),
     "bild_set_sampling": (C.c_int, [C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_int]),
+    "bild_set_acceptance": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int]),
     "bild_kv_truncate": (C.c_int, [C.c_void_p, C.c_int, C.c_int]),
     "bild_seq_truncate": (C.c_int, [C.c_void_p, C.c_int]),
     "bild_force_tokens": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int]),
@@ -241,6 +243,14 @@ class State:
 
     def seq_truncate(self, n_keep: int):
         _check(lib().bild_seq_truncate(self.h, n_keep), "bild_seq_truncate")
+
+    def set_acceptance(self, rule: int, u_accept=None):
+        """rule: ACCEPT_THRESHOLD (the paper's rollback policy) or ACCEPT_REJECTION (needs set_sampling first)."""
+        if u_accept is None:
+            _check(lib().bild_set_acceptance(self.h, int(rule), None, 0), "bild_set_acceptance")
+            return
+        a = np.ascontiguousarray(u_accept, dtype=np.float32)
+        _check(lib().bild_set_acceptance(self.h, int(rule), a.ctypes.data, len(a)), "bild_set_acceptance")
 
     def force_tokens(self, first: int, tokens, draft_start: int):
         a = _i32(tokens)

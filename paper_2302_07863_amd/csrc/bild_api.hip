@@ -820,6 +820,12 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
             f.logits = M.dbg;
             f.vocab = c.vocab;
             f.u = s->u_dev[w];
+            if (s->accept_mode == 1) {
+                f.accept_mode = 1;
+                f.u_acc = s->u_acc;
+                f.s_ring = s->s_ring;
+                f.s_draw = s->s_draw;
+            }
         }
     } else {
         f.mode = 3;
@@ -850,7 +856,7 @@ int run_pass(bild_state* s, int w, int T, int lm_rows, int mode) {
         if (rc == BILD_OK && !s->gemm_only) s->seq_issued += 1;  // its policy kernel will count this pass
         return rc;
     }
-    const std::array<int, 6> key = {w, T, lm_rows, mode, bucket, (s->debug_logits ? 1 : 0) | (s->gemm_only ? 2 : 0) | (s->top_p > 0.f ? 4 : 0)};
+    const std::array<int, 6> key = {w, T, lm_rows, mode, bucket, (s->debug_logits ? 1 : 0) | (s->gemm_only ? 2 : 0) | (s->top_p > 0.f ? 4 : 0) | (s->accept_mode ? 8 : 0)};
     auto it = s->graphs.find(key);
     if (it == s->graphs.end()) {
         hipGraph_t g = nullptr;
@@ -1268,9 +1274,10 @@ extern "C" int bild_set_sampling(bild_state* s, float top_p, const float* u_smal
         for (auto& kv : s->graphs) (void)hipGraphExecDestroy(kv.second);
         s->graphs.clear();
     };
-    if (!(top_p > 0.f)) {  // back to argmax
+    if (!(top_p > 0.f)) {  // back to argmax (and to the threshold rule of the review, which is all argmax decoding has)
         if (s->top_p > 0.f) drop_graphs();
         s->top_p = 0.f;
+        s->accept_mode = 0;
         return BILD_OK;
     }
     if (top_p > 1.f || !u_small || !u_large || n < s->max_len) return BILD_EINVAL;
@@ -1290,6 +1297,40 @@ extern "C" int bild_set_sampling(bild_state* s, float top_p, const float* u_smal
     }
     if (s->top_p != top_p) drop_graphs();
     s->top_p = top_p;
+    return BILD_OK;
+}
+
+extern "C" int bild_set_acceptance(bild_state* s, int rule, const float* u_accept, int n) {
+    if (!s || (rule != BILD_ACCEPT_THRESHOLD && rule != BILD_ACCEPT_REJECTION)) return BILD_EINVAL;
+    auto drop_graphs = [&]() {  // captured passes carry the rule by value
+        (void)hipStreamSynchronize(s->stream);
+        for (auto& kv : s->graphs) (void)hipGraphExecDestroy(kv.second);
+        s->graphs.clear();
+    };
+    if (rule == BILD_ACCEPT_THRESHOLD) {
+        if (s->accept_mode != 0) drop_graphs();
+        s->accept_mode = 0;
+        return BILD_OK;
+    }
+    if (!(s->top_p > 0.f)) return BILD_ESTATE;
+    if (!u_accept || n < s->max_len) return BILD_EINVAL;
+    for (int i = 0; i < s->max_len; ++i)
+        if (!(u_accept[i] >= 0.f && u_accept[i] < 1.f)) return BILD_EINVAL;
+    HIPC(hipStreamSynchronize(s->stream));
+    if (!s->u_acc) {
+        const size_t V = (size_t)s->pair->m[0]->cfg.vocab;
+        int rc = dev_alloc(s->allocs, (void**)&s->u_acc, sizeof(float) * (size_t)(s->max_len + 1));
+        if (rc) return rc;
+        rc = dev_alloc(s->allocs, (void**)&s->s_ring, sizeof(float) * (size_t)kMaxRows * V);
+        if (rc) return rc;
+        rc = dev_alloc(s->allocs, (void**)&s->s_draw, sizeof(float4) * (size_t)(s->max_len + 1));
+        if (rc) return rc;
+        HIPC(hipMemset(s->s_ring, 0, sizeof(float) * (size_t)kMaxRows * V));
+        HIPC(hipMemset(s->s_draw, 0, sizeof(float4) * (size_t)(s->max_len + 1)));
+    }
+    HIPC(hipMemcpy(s->u_acc, u_accept, sizeof(float) * (size_t)s->max_len, hipMemcpyHostToDevice));
+    if (s->accept_mode != 1) drop_graphs();
+    s->accept_mode = 1;
     return BILD_OK;
 }
 

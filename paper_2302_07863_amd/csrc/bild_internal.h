@@ -195,6 +195,12 @@ struct FinishArgs {
     const float* logits;  // [rows][vocab] logits of the pass (row_off applies)
     int vocab;
     const float* u;       // uniform number per sequence position, for the model of this pass
+    // rejection-sampling acceptance (accept_mode 1, sampling variant only): the review keeps a draft iff
+    // u_acc[position] * p_S(draft) < p_L(draft) and replaces the first refused one by a draw from max(0, p_L - p_S)
+    int accept_mode;
+    const float* u_acc;   // uniform number per sequence position for the acceptance test
+    float* s_ring;        // [kMaxRows][vocab] the small model's logits of each pending draft, by draft index
+    float4* s_draw;       // [sequence capacity] (max logit, nucleus threshold key, nucleus mass, -) of the small model's row
 };
 
 size_t gemm_lds_bytes(const GemmArgs& a, int dtype);

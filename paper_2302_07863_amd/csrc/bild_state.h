@@ -100,6 +100,10 @@ struct bild_state {
     std::map<std::array<int, 6>, hipGraphExec_t> graphs;  // captured passes by (model, rows, lm rows, mode, key bucket, debug)
     float top_p = 0.f;         // > 0: sampling variant, tokens are drawn from the nucleus
     float* u_dev[2] = {nullptr, nullptr};  // uniform number per sequence position, per model
+    int accept_mode = 0;       // 1: the review uses the rejection-sampling rule (needs top_p > 0)
+    float* u_acc = nullptr;    // uniform number per sequence position for that rule
+    float* s_ring = nullptr;   // [kMaxRows][vocab] the small model's logits of the pending drafts
+    float4* s_draw = nullptr;  // [max_len + 1] (max, threshold key, nucleus mass) of the small model's row per position
     float* trunk_x = nullptr;  // early-exit pair: [cap_len][d] hidden state after the trunk's last layer, by position
     int* y = nullptr;     // device [max_len + 1]
     int* src = nullptr;   // device [max_src]

@@ -405,7 +405,9 @@ __device__ __forceinline__ uint32_t float_key(float f) {
 // exceeds u * mass.  The threshold is found exactly, as an integer key, by a radix search of 4 bits per
 // sweep over the logits: with e_i = exp(z_i - m), K is the largest key with sum_{key_i >= K} e_i >= top_p * sum e_i.
 // Returns the token to every thread.  `ws` is kDrawLds bytes of LDS.
-__device__ __forceinline__ int nucleus_draw(const float* __restrict__ z, int V, float m, float top_p, float u, char* ws) {
+// nucleus_search finds the threshold key and the nucleus' mass (in units of exp(z - m)); weighted_walk draws.
+__device__ __forceinline__ void nucleus_search(const float* __restrict__ z, int V, float m, float top_p, char* ws,
+                                               uint32_t& K_out, float& mass_out) {
     float* bins = (float*)ws;              // [16 waves][16]
     float* tmass = bins + 16 * 16;         // [1024]
     float* sc = tmass + 1024;              // scalars
@@ -498,19 +500,36 @@ __device__ __forceinline__ int nucleus_draw(const float* __restrict__ z, int V, 
         __syncthreads();
     }
     (void)target;
-    // ---- the draw: every thread owns a run of consecutive ids ----
+    K_out = K;
+    mass_out = mass;
+}
+
+// Inverse-CDF draw over the ids of a row, walked in increasing id: the first id whose running weight exceeds
+// u * total.  weight(i) >= 0 is the (unnormalised) probability of id i, the same for every thread; `total` < 0
+// means "add the weights up here" (wave sums in wave order).  Returns the token to every thread.
+template <class W>
+__device__ __forceinline__ int weighted_walk(W weight, int V, float total, float u, char* ws) {
+    float* bins = (float*)ws;              // [16 waves][16]
+    float* tmass = bins + 16 * 16;         // [1024]
+    float* sc = tmass + 1024;              // scalars
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nthr = blockDim.x, nwv = nthr >> 6;
+    __syncthreads();                       // the workspace may still be read by an earlier search or walk
+    // ---- every thread owns a run of consecutive ids ----
     const int chunk = (V + nthr - 1) / nthr;
     const int i0 = min(tid * chunk, V), i1 = min(i0 + chunk, V);
     float mine = 0.f;
-    for (int i = i0; i < i1; ++i) {
-        const float zi = z[i];
-        if (float_key(zi) >= K) mine += expf(zi - m);
-    }
+    for (int i = i0; i < i1; ++i) mine += weight(i);
     tmass[tid] = mine;
     const float wsum = wave_sum(mine);
     if (lane == 0) bins[wave] = wsum;
     __syncthreads();
     if (tid == 0) {
+        float mass = total;
+        if (mass < 0.f) {
+            mass = 0.f;
+            for (int w = 0; w < nwv; ++w) mass += bins[w];
+        }
         const float t = u * mass;
         float run = 0.f;
         int w = 0;
@@ -536,10 +555,10 @@ __device__ __forceinline__ int nucleus_draw(const float* __restrict__ z, int V, 
         const float t = sc[5];
         int tok = -1, last = -1;
         for (int i = i0; i < i1; ++i) {
-            const float zi = z[i];
-            if (float_key(zi) >= K) {
+            const float wi = weight(i);
+            if (wi > 0.f) {
                 last = i;
-                run += expf(zi - m);
+                run += wi;
                 if (run > t) {
                     tok = i;
                     break;
@@ -553,13 +572,20 @@ __device__ __forceinline__ int nucleus_draw(const float* __restrict__ z, int V, 
     if (tok < 0) {  // rounding left the target beyond the last member: take the highest member id
         int best = -1;
         for (int i = tid; i < V; i += nthr)
-            if (float_key(z[i]) >= K) best = max(best, i);
+            if (weight(i) > 0.f) best = max(best, i);
         for (int o = 32; o > 0; o >>= 1) best = max(best, __shfl_xor(best, o, 64));
         if (lane == 0) bins[wave] = __int_as_float(best);
         __syncthreads();
         for (int w = 0; w < nwv; ++w) tok = max(tok, __float_as_int(bins[w]));
     }
     return tok;
+}
+
+__device__ __forceinline__ int nucleus_draw(const float* __restrict__ z, int V, float m, float top_p, float u, char* ws) {
+    uint32_t K;
+    float mass;
+    nucleus_search(z, V, m, top_p, ws, K, mass);
+    return weighted_walk([&](int i) { const float zi = z[i]; return float_key(zi) >= K ? expf(zi - m) : 0.f; }, V, mass, u, ws);
 }
 
 template <bool SAMPLE>
@@ -602,28 +628,89 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
     // Sampling variant: the token that will be committed is drawn by the whole workgroup from the row the
     // policy selects (the last row of a step; row r of a review), at the position it will occupy.
     int drawn = -1;
+    int r_given = -1;  // rejection-sampling acceptance: the index of the first refused draft (n: none), decided here
     if (SAMPLE && a.top_p > 0.f && a.mode <= 2) {
         int* sel = (int*)(lds + kFinishLds);  // [0] row, [1] position
-        if (tid == 0) {
-            int row = a.T - 1, pos = c_ylen;
-            if (a.mode == 1) {
-                const int n = a.T - 1;
-                const float alpha = c_arb;
-                row = n;
-                for (int i = 0; i < n; ++i)
-                    if ((rm[i] + logf(rsum[i])) - a.zt[a.row_off + i] > alpha) {
-                        row = i;
-                        break;
-                    }
-                pos = c_ds + row;
+        char* ws = lds + kFinishLds + 16;
+        if (a.accept_mode == 1 && a.mode == 1) {
+            // Review by the rejection rule (the acceptance of the speculative-decoding methods the paper compares
+            // with, Section 4.2): draft x at position q, drawn from the small model's nucleus distribution p_S, is kept
+            // iff u_acc[q] * p_S(x) < p_L(x); the first refused draft is replaced by a draw from the positive part of
+            // p_L - p_S.  Every thread follows the same scalars; the searches and the walk use the whole workgroup.
+            const int n = a.T - 1, V = a.vocab;
+            int r = n;
+            uint32_t KL = 0;
+            float massL = 1.f;
+            for (int i = 0; i < n; ++i) {
+                const int pos = c_ds + i;
+                const int x = a.y[pos];
+                const float* zl = a.logits + (size_t)(a.row_off + i) * V;
+                if (a.top_p < 1.f) nucleus_search(zl, V, rm[i], a.top_p, ws, KL, massL);
+                else { KL = 0u; massL = rsum[i]; }
+                const float zlx = zl[x];
+                const float pl = float_key(zlx) >= KL ? expf(zlx - rm[i]) / massL : 0.f;
+                const float4 sd = a.s_draw[pos];  // (max logit, threshold key, nucleus mass) of the small model's row
+                const float zsx = a.s_ring[(size_t)i * V + x];
+                const float ps = float_key(zsx) >= __float_as_uint(sd.y) ? expf(zsx - sd.x) / sd.z : 0.f;
+                if (tid == 0) c->res_nll[i] = (rm[i] + logf(rsum[i])) - a.zt[a.row_off + i];
+                if (!(a.u_acc[pos] * ps < pl)) {
+                    r = i;
+                    break;
+                }
             }
-            sel[0] = row;
-            sel[1] = pos;
+            r_given = r;
+            const int pos = c_ds + r;
+            const float* zl = a.logits + (size_t)(a.row_off + r) * V;
+            if (r == n) {
+                drawn = nucleus_draw(zl, V, rm[r], a.top_p, a.u[pos], ws);
+            } else {  // (KL, massL) are those of row r, the last one searched
+                const float4 sd = a.s_draw[pos];
+                const float* zs = a.s_ring + (size_t)r * V;
+                const uint32_t KS = __float_as_uint(sd.y);
+                const float mL = rm[r], iL = 1.f / massL, mS = sd.x, iS = 1.f / sd.z;
+                drawn = weighted_walk([&](int v) {
+                    const float a_ = zl[v], b_ = zs[v];
+                    const float pl = float_key(a_) >= KL ? expf(a_ - mL) * iL : 0.f;
+                    const float ps = float_key(b_) >= KS ? expf(b_ - mS) * iS : 0.f;
+                    return fmaxf(pl - ps, 0.f);
+                }, V, -1.f, a.u[pos], ws);
+            }
+        } else {
+            if (tid == 0) {
+                int row = a.T - 1, pos = c_ylen;
+                if (a.mode == 1) {
+                    const int n = a.T - 1;
+                    const float alpha = c_arb;
+                    row = n;
+                    for (int i = 0; i < n; ++i)
+                        if ((rm[i] + logf(rsum[i])) - a.zt[a.row_off + i] > alpha) {
+                            row = i;
+                            break;
+                        }
+                    pos = c_ds + row;
+                }
+                sel[0] = row;
+                sel[1] = pos;
+            }
+            __syncthreads();
+            const int row = sel[0], pos = sel[1];
+            const float* zr = a.logits + (size_t)(a.row_off + row) * a.vocab;
+            if (a.accept_mode == 1 && a.mode == 0) {
+                // the small model's step under the rejection rule: the review will need the distribution this token was
+                // drawn from - keep the row's logits in the slot of its draft index and its (max, threshold, mass)
+                uint32_t K;
+                float mass;
+                nucleus_search(zr, a.vocab, rm[row], a.top_p, ws, K, mass);
+                drawn = weighted_walk([&](int i) { const float zi = zr[i]; return float_key(zi) >= K ? expf(zi - rm[row]) : 0.f; },
+                                      a.vocab, mass, a.u[pos], ws);
+                const int slot = min(max(c_ylen - c_ds, 0), kMaxRows - 1);
+                float* dst = a.s_ring + (size_t)slot * a.vocab;
+                for (int i = tid; i < a.vocab; i += nthr) dst[i] = zr[i];
+                if (tid == 0) a.s_draw[pos] = make_float4(rm[row], __uint_as_float(K), mass, 0.f);
+            } else {
+                drawn = nucleus_draw(zr, a.vocab, rm[row], a.top_p, a.u[pos], ws);
+            }
         }
-        __syncthreads();
-        const int row = sel[0], pos = sel[1];
-        drawn = nucleus_draw(a.logits + (size_t)(a.row_off + row) * a.vocab, a.vocab, rm[row], a.top_p, a.u[pos],
-                             lds + kFinishLds + 16);
     }
     if (tid == 0) {
         const int w = a.which;
@@ -651,10 +738,14 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
                 const int n = a.T - 1;
                 const float alpha = c_arb;
                 int r = n;
-                for (int i = 0; i < n; ++i) {
-                    const float nll = (rm[i] + logf(rsum[i])) - a.zt[a.row_off + i];
-                    c->res_nll[i] = nll;
-                    if (r == n && nll > alpha) r = i;
+                if (r_given >= 0) {
+                    r = r_given;  // (the rejection rule decided above; it also left res_nll of the rows it judged)
+                } else {
+                    for (int i = 0; i < n; ++i) {
+                        const float nll = (rm[i] + logf(rsum[i])) - a.zt[a.row_off + i];
+                        c->res_nll[i] = nll;
+                        if (r == n && nll > alpha) r = i;
+                    }
                 }
                 const int tok = drawn >= 0 ? drawn : ridx[r];
                 a.y[ds + r] = tok;
@@ -715,6 +806,7 @@ hipError_t launch_row_copy(const RowCopyArgs& a, hipStream_t st) {
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st) {
     if (a.top_p > 0.f && a.mode <= 2) {
         if (!a.logits || !a.u || a.vocab < 1) return hipErrorInvalidValue;
+        if (a.accept_mode == 1 && (!a.u_acc || !a.s_ring || !a.s_draw)) return hipErrorInvalidValue;
         hipLaunchKernelGGL(finish_sample_kernel, dim3(1), dim3(1024), 0, st, a);
         return hipGetLastError();
     }
