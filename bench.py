@@ -411,6 +411,9 @@ def main() -> int:
                                + (f", nucleus sampling top_p={args.top_p}" if args.top_p > 0 else ""),
                    "tokens_per_step": n_tok},
         "roofline": roofline,
+        # matrix-core utilisation of the review GEMMs by row count (config 5: 7B-shaped large model, cache of 4096 rows), read
+        # from the committed rocprofv3 counter summary (profiles/verify_llama_mfma.txt; `--workload verify` times the same passes)
+        "mfma_util_verify_gemm": {f"T{T}": profile_value("verify_llama_mfma.txt", f"mfma_util_T{T}") for T in (1, 4, 8, 16, 32)},
         "stage_latency": stage_latency,
         "cpu_baseline": cpu,
         "bild_stats": stats,

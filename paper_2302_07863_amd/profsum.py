@@ -3,7 +3,10 @@
   python -m paper_2302_07863_amd.profsum stats  <kernel_stats.csv>
   python -m paper_2302_07863_amd.profsum pmc    <fetch counter_collection.csv> <write counter_collection.csv>
   python -m paper_2302_07863_amd.profsum counters <counter_collection.csv>
+  python -m paper_2302_07863_amd.profsum passes <kernel_trace.csv> [passes]
 
+`passes` lists, per kernel instantiation and launch size, the launches of the last `passes` (default 10) decoder passes
+of a `bench.py --profile-run --profile-rows T` run (a pass ends with the policy kernel).
 `stats` groups the template instantiations of one kernel under one name and prints calls,
 total and mean duration.  `pmc` scales FETCH_SIZE / WRITE_SIZE per dispatch by what the same
 counters read for bild::probe_copy_kernel, a plain copy of known size (1 GiB read, 1 GiB written).
@@ -21,7 +24,8 @@ PROBE_BYTES = 1 << 30
 # The decode GEMM is one device function behind four launch wrappers (any row count, exactly one row, two to
 # four rows, input still in key-split attention partials); they are summed under one name.  The encoder / prefill
 # wrapper (row blocks, bild::gemm_rows_kernel) works in another regime and stays separate.
-_DECODE_GEMM = ("bild::gemm_kernel", "bild::gemm_row_kernel", "bild::gemm_few_kernel", "bild::gemm_merge_kernel")
+_DECODE_GEMM = ("bild::gemm_kernel", "bild::gemm_row_kernel", "bild::gemm_few_kernel", "bild::gemm_merge_kernel",
+                "bild::gemm_pre_kernel", "bild::gemm_merge_nx_kernel")
 
 
 def _group(name: str) -> str:
@@ -127,8 +131,31 @@ def verify(path: str) -> str:
     return "\n".join(lines)
 
 
+def passes(path: str, count: int = 10) -> str:
+    rows = sorted(csv.DictReader(open(path)), key=lambda r: int(r["Start_Timestamp"]))
+    fin = [i for i, r in enumerate(rows) if "finish" in r["Kernel_Name"]]
+    if not fin:
+        return "no policy kernel in the trace: not a run of decoder passes"
+    lo = fin[-count - 1] + 1 if len(fin) > count else 0
+    sel = rows[lo:fin[-1] + 1]
+    agg = collections.defaultdict(list)
+    for r in sel:
+        name = re.sub(r"\(.*$", "", r["Kernel_Name"].replace("void ", ""))
+        agg[(name, int(r["Grid_Size_X"]) // max(int(r["Workgroup_Size_X"]), 1) * max(int(r.get("Grid_Size_Y", 1) or 1), 1),
+             r["Workgroup_Size_X"])].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+    n_pass = min(count, len(fin))
+    busy = sum(sum(v) for v in agg.values())
+    lines = [f"passes={n_pass} launches_per_pass={len(sel) / n_pass:.0f} kernel_busy_us_per_pass={busy / n_pass:.1f}",
+             f"{'kernel (template arguments as compiled)':60s} {'workgroups':>10s} {'threads':>7s} {'per_pass':>8s} {'mean_us':>8s} {'us_per_pass':>11s}"]
+    for k, v in sorted(agg.items(), key=lambda kv: -sum(kv[1])):
+        lines.append(f"{k[0][:60]:60s} {k[1]:10d} {k[2]:>7s} {len(v) / n_pass:8.1f} {sum(v) / len(v):8.2f} {sum(v) / n_pass:11.1f}")
+    return "\n".join(lines)
+
+
 if __name__ == "__main__":
-    if len(sys.argv) >= 3 and sys.argv[1] == "verify":
+    if len(sys.argv) >= 3 and sys.argv[1] == "passes":
+        print(passes(sys.argv[2], int(sys.argv[3]) if len(sys.argv) > 3 else 10))
+    elif len(sys.argv) >= 3 and sys.argv[1] == "verify":
         print(verify(sys.argv[2]))
     elif len(sys.argv) >= 3 and sys.argv[1] == "stats":
         print(stats(sys.argv[2]))
