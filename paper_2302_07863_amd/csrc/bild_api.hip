@@ -347,6 +347,13 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         AL(M.q, sizeof(float) * M.rows_cap * I);
         AL(M.a, sizeof(float) * M.rows_cap * I);
         AL(M.h, sizeof(float) * M.rows_cap * F);
+        if (m->cfg.pos == BILD_POS_SINUSOIDAL) {
+            AL(M.pe, sizeof(float) * (size_t)s->cap_len * d);
+            if (launch_pe_table(M.pe, s->cap_len, (int)d, s->stream) != hipSuccess) {
+                bild_state_destroy(s);
+                return BILD_EHIP;
+            }
+        }
         if (m->cfg.dtype == BILD_DT_BF16) {
             AL(M.xb, sizeof(uint16_t) * 2 * kMaxRows * d);
             AL(M.ab, sizeof(uint16_t) * 2 * kMaxRows * I);
@@ -589,6 +596,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
     e.sinusoidal = c.pos == BILD_POS_SINUSOIDAL;
     e.embed_scale = c.embed_scale;
     e.x = M.x;
+    e.pe = M.pe;
     // Early-exit pair: the large model's pass starts from the hidden state the trunk (model 0) left for these
     // rows and runs the layers above the trunk only.
     const int trunk = s->pair->trunk_layers;

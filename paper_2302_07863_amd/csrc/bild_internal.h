@@ -156,6 +156,7 @@ struct EmbedArgs {
     int T, d, vocab, tie_shift, sinusoidal;
     float embed_scale;
     float* x;  // [T][d]
+    const float* pe;  // nullable: sinusoidal position table [positions][d] (launch_pe_table), read instead of evaluating sin / cos
     // non-null (bf16 models): x * nx_gain also as bf16 planes [T][d] for the first projection, and the sum of x^2 of
     // each row in four parts (one per wave), nx_ssq[wave][kMaxRows]
     uint16_t* nx_hi;
@@ -220,6 +221,8 @@ hipError_t launch_gemm_pre(const GemmArgs& a, hipStream_t st);
 hipError_t gemm_pre_init();
 hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st);
 hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st);
+// table[pos][k] = sin / cos of pos * 10000^(-2 floor(k/2) / d) (k even / odd), evaluated in double precision as embed_kernel does
+hipError_t launch_pe_table(float* table, int positions, int d, hipStream_t st);
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st);
 hipError_t launch_row_copy(const RowCopyArgs& a, hipStream_t st);
 hipError_t kernels_init();  // one-time function attributes; call before any stream capture

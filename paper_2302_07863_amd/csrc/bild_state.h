@@ -82,6 +82,7 @@ struct ModelState {
     uint16_t* ab = nullptr;   // [2][32][I]   attention output
     uint16_t* hb = nullptr;   // [2][32][F]   FFN hidden
     float* ssq = nullptr;     // [d / 16 + 8][32] partial sums of squares beside xb
+    float* pe = nullptr;      // sinusoidal models: position table [cap_len][d] for the decoder's embedding
 };
 
 struct bild_state {

@@ -349,8 +349,12 @@ __device__ __forceinline__ void embed_body(const EmbedArgs& a, const int t) {
         float v = DT ? bf2f(((const uint16_t*)p)[j]) : ((const float*)p)[j];
         v *= a.embed_scale;
         if (a.sinusoidal) {
-            const double ang = (double)pos * exp2(-(double)(2 * (k >> 1)) / (double)a.d * lg);
-            v += (float)((k & 1) ? cos(ang) : sin(ang));
+            if (a.pe) {
+                v += a.pe[(size_t)pos * a.d + k];
+            } else {
+                const double ang = (double)pos * exp2(-(double)(2 * (k >> 1)) / (double)a.d * lg);
+                v += (float)((k & 1) ? cos(ang) : sin(ang));
+            }
         }
         st_act(a.x + (size_t)t * a.d + k, v);
         if (a.nx_hi) {
@@ -369,6 +373,21 @@ __device__ __forceinline__ void embed_body(const EmbedArgs& a, const int t) {
 
 template <int DT>
 __global__ __launch_bounds__(256) void embed_kernel(const EmbedArgs a) { embed_body<DT>(a, (int)blockIdx.x); }
+
+__global__ __launch_bounds__(256) void pe_table_kernel(float* table, int d) {
+    const int pos = (int)blockIdx.x;
+    const double lg = log2(10000.0);
+    for (int k = threadIdx.x; k < d; k += blockDim.x) {
+        const double ang = (double)pos * exp2(-(double)(2 * (k >> 1)) / (double)d * lg);
+        table[(size_t)pos * d + k] = (float)((k & 1) ? cos(ang) : sin(ang));
+    }
+}
+
+hipError_t launch_pe_table(float* table, int positions, int d, hipStream_t st) {
+    if (!table || positions < 1 || d < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(pe_table_kernel, dim3(positions), dim3(256), 0, st, table, d);
+    return hipGetLastError();
+}
 
 hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st) {
     if (dtype)
@@ -389,7 +408,7 @@ hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st) {
 //   mode 4  measurement: merge the statistics, commit nothing
 // =====================================================================================
 // LDS use of finish_body (from the start of the workgroup's LDS)
-constexpr int kFinishLds = 3 * kMaxRows * 4;
+constexpr int kFinishLds = 4 * kMaxRows * 4;
 // LDS of the sampling variant behind that: 16 waves x 16 bins, 1024 per-thread masses, a few scalars
 constexpr int kDrawLds = 16 * 16 * 4 + 1024 * 4 + 128;
 
@@ -652,7 +671,6 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
                 const float4 sd = a.s_draw[pos];  // (max logit, threshold key, nucleus mass) of the small model's row
                 const float zsx = a.s_ring[(size_t)i * V + x];
                 const float ps = float_key(zsx) >= __float_as_uint(sd.y) ? expf(zsx - sd.x) / sd.z : 0.f;
-                if (tid == 0) c->res_nll[i] = (rm[i] + logf(rsum[i])) - a.zt[a.row_off + i];
                 if (!(a.u_acc[pos] * ps < pl)) {
                     r = i;
                     break;
@@ -712,70 +730,87 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, char* lds) {
             }
         }
     }
+    // The results go to the control block and, for the caller, to its mirror in pinned host memory: every changed word
+    // is written to both from here (the unchanged words of the mirror are the host's own); the pass counter goes last,
+    // behind a system-wide fence, so that a host that sees the new count also sees every other word.
+    Ctl* hm = a.host_mirror;
+    float* nlls = (float*)(ridx + kMaxRows);  // [kMaxRows] (mode 1)
+    if (a.mode == 1 && tid < a.T - 1) nlls[tid] = (rm[tid] + logf(rsum[tid])) - a.zt[a.row_off + tid];  // -ln p_L(draft)
+    if (a.mode != 3 && tid < a.T) {
+        c->res_rowtok[tid] = ridx[tid];
+        if (hm) ((volatile int*)hm->res_rowtok)[tid] = ridx[tid];
+    }
+    __syncthreads();
+    if (a.mode == 1 && tid < a.T - 1 && (r_given < 0 || tid <= r_given)) {
+        c->res_nll[tid] = nlls[tid];
+        if (hm) ((volatile float*)hm->res_nll)[tid] = nlls[tid];
+    }
     if (tid == 0) {
         const int w = a.which;
         const int y_len = c_ylen, ds = c_ds, n_max = c_nmax;
+        int n_ylen = y_len, n_ds = ds, n_len0 = c_len0, n_lenw = c_lenw;
+        int res_tok = 0, res_flag = 0, res_r = 0, res_n = 0;
+        float res_pmax = 0.f;
         if (a.mode == 3) {
-            c->len[w] = c_lenw + a.rows_consumed;
-        } else {
-            for (int t = 0; t < a.T; ++t) c->res_rowtok[t] = ridx[t];
-            if (a.mode == 0 || a.mode == 2) {
-                const int tok = drawn >= 0 ? drawn : ridx[a.T - 1];
-                const float pmax = 1.f / rsum[a.T - 1];
-                const bool low = (a.mode == 0) && (pmax < c_afb);
-                const bool forced = (a.mode == 0) && n_max > 0 && (y_len - ds) >= n_max;
-                const bool fb = low || forced;
-                c->len[w] = c_lenw + a.rows_consumed;
-                if (!fb && y_len < a.y_cap) {
-                    a.y[y_len] = tok;
-                    c->y_len = y_len + 1;
-                    if (a.mode == 2) c->draft_start = y_len + 1;
-                }
-                c->res_tok = tok;
-                c->res_flag = (fb ? 1 : 0) | ((forced && !low) ? 2 : 0);
-                c->res_pmax = pmax;
-            } else if (a.mode == 1) {  // review of n = T - 1 drafts
-                const int n = a.T - 1;
-                const float alpha = c_arb;
-                int r = n;
-                if (r_given >= 0) {
-                    r = r_given;  // (the rejection rule decided above; it also left res_nll of the rows it judged)
-                } else {
-                    for (int i = 0; i < n; ++i) {
-                        const float nll = (rm[i] + logf(rsum[i])) - a.zt[a.row_off + i];
-                        c->res_nll[i] = nll;
-                        if (r == n && nll > alpha) r = i;
+            n_lenw = c_lenw + a.rows_consumed;
+        } else if (a.mode == 0 || a.mode == 2) {
+            const int tok = drawn >= 0 ? drawn : ridx[a.T - 1];
+            const float pmax = 1.f / rsum[a.T - 1];
+            const bool low = (a.mode == 0) && (pmax < c_afb);
+            const bool forced = (a.mode == 0) && n_max > 0 && (y_len - ds) >= n_max;
+            const bool fb = low || forced;
+            n_lenw = c_lenw + a.rows_consumed;
+            if (!fb && y_len < a.y_cap) {
+                a.y[y_len] = tok;
+                n_ylen = y_len + 1;
+                if (a.mode == 2) n_ds = y_len + 1;
+            }
+            res_tok = tok;
+            res_flag = (fb ? 1 : 0) | ((forced && !low) ? 2 : 0);
+            res_pmax = pmax;
+        } else if (a.mode == 1) {  // review of n = T - 1 drafts
+            const int n = a.T - 1;
+            const float alpha = c_arb;
+            int r = n;
+            if (r_given >= 0) {
+                r = r_given;  // (the rejection rule decided above)
+            } else {
+                for (int i = 0; i < n; ++i)
+                    if (nlls[i] > alpha) {
+                        r = i;
+                        break;
                     }
-                }
-                const int tok = drawn >= 0 ? drawn : ridx[r];
-                a.y[ds + r] = tok;
-                c->y_len = ds + r + 1;
-                c->len[1] = ds + r;
-                c->len[0] = min(c_len0, ds + r);
-                c->draft_start = ds + r + 1;
-                c->res_r = r;
-                c->res_n = n;
-                c->res_tok = tok;
-                c->res_pmax = 1.f / rsum[r];
-                c->res_flag = 0;
+            }
+            const int tok = drawn >= 0 ? drawn : ridx[r];
+            a.y[ds + r] = tok;
+            n_ylen = ds + r + 1;
+            n_lenw = ds + r;            // (w == 1)
+            n_len0 = min(c_len0, ds + r);
+            n_ds = ds + r + 1;
+            res_r = r;
+            res_n = n;
+            res_tok = tok;
+            res_pmax = 1.f / rsum[r];
+        }
+        if (a.mode != 4) {
+            const int l0 = w == 0 ? n_lenw : n_len0, l1 = w == 1 ? n_lenw : c->len[1];
+            c->y_len = n_ylen; c->draft_start = n_ds; c->len[0] = l0; c->len[1] = l1;
+            c->res_tok = res_tok; c->res_flag = res_flag; c->res_r = res_r; c->res_n = res_n; c->res_pmax = res_pmax;
+            if (hm) {
+                volatile Ctl* v = hm;
+                v->y_len = n_ylen; v->draft_start = n_ds; v->len[0] = l0; v->len[1] = l1;
+                v->res_tok = res_tok; v->res_flag = res_flag; v->res_r = res_r; v->res_n = res_n; v->res_pmax = res_pmax;
             }
         }
-        __threadfence();
     }
-    __syncthreads();
-    // mirror the control block into pinned host memory for the caller; the pass counter goes last, behind a
-    // system-wide fence, so that a host that sees the new count also sees every other word
-    if (a.host_mirror) {
+    if (hm) {
         static_assert(offsetof(Ctl, seq) == sizeof(Ctl) - 4, "seq must be the last word of the control block");
-        const int words = sizeof(Ctl) / 4 - 1;
-        for (int i = tid; i < words; i += nthr)
-            ((volatile int*)a.host_mirror)[i] = __hip_atomic_load((int*)c + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __threadfence_system();
         __syncthreads();
         if (tid == 0) {
             const int sq = c_seq + 1;
             c->seq = sq;
-            ((volatile int*)a.host_mirror)[words] = sq;
+            ((volatile Ctl*)hm)->seq = sq;
         }
     }
 }
