@@ -314,6 +314,7 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         const char* ng = std::getenv("BILD_NO_GRAPH");
         s->use_graphs = !(ng && ng[0] == '1');
         if (const char* pm = std::getenv("BILD_PRE_MIN_ROWS")) s->pre_min_rows = std::atoi(pm);  // experiments; > 32 turns the planes off
+        if (const char* km = std::getenv("BILD_KSPLIT_MIN_F")) s->ksplit_min_f = std::atoi(km);  // tests: small widths; 0 turns the split off
     }
     for (int w = 0; w < 2; ++w) {
         ModelState& M = s->ms[w];
@@ -347,6 +348,8 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         AL(M.q, sizeof(float) * M.rows_cap * I);
         AL(M.a, sizeof(float) * M.rows_cap * I);
         AL(M.h, sizeof(float) * M.rows_cap * F);
+        AL(M.x2, sizeof(float) * kMaxRows * d);
+        AL(M.px, sizeof(float) * kPartSlices * kMaxRows * d);
         if (m->cfg.pos == BILD_POS_SINUSOIDAL) {
             AL(M.pe, sizeof(float) * (size_t)s->cap_len * d);
             if (launch_pe_table(M.pe, s->cap_len, (int)d, s->stream) != hipSuccess) {
@@ -577,7 +580,7 @@ int emit_attention(bild_state* s, const ModelState& M, AttnArgs& a, int nkeys, i
 }
 
 // Embedding and all decoder layers of model w over rows y[len .. len+T).
-int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
+int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts, int* xb_parts_out, float** x_out, bool* parts_pending) {
     ModelState& M = s->ms[w];
     const bild_model* m = M.m;
     const bild_model_config& c = m->cfg;
@@ -625,6 +628,24 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
         xb_parts = planes ? (int)gemm_num_blocks(g) * (g.nwv / g.wk) : 0;
         if (xb_parts > kMaxSsqParts) xb_parts = 0;  // more than a consumer adds up: the next projection converts x itself
     };
+    // The FFN output projection of a narrow model at one to four rows (64 feature tiles x thousands of inputs: too few
+    // workgroups with too long a stream each) is cut into kPartSlices slices of its inputs; the next layer's first
+    // projection (or the LM head of a single-row pass) adds the slices to the residual stream while staging and leaves the
+    // sum in the other of two residual buffers.  Measured on the T5-large shape: see the design notes.
+    const int kt = dt == BILD_DT_BF16 ? 32 : 16;
+    const bool split_ffn = !planes && T <= 4 && d <= 1024 && s->ksplit_min_f > 0 && F >= s->ksplit_min_f &&
+                           (F / kt) % kPartSlices == 0 && (T == 1 || ((d / 4) % 64 == 0 && (F / kPartSlices / 4) % 64 == 0)) && M.px != nullptr;
+    float *xcur = M.x, *xoth = M.x2;
+    bool pending = false;  // the residual stream is xcur + the kPartSlices partial results in M.px
+    auto set_parts_in = [&](GemmArgs& g) {
+        if (!pending) return;
+        g.px = M.px; g.px_stride = (int64_t)kMaxRows * d; g.pn = kPartSlices; g.x_out = xoth;
+    };
+    auto after_parts_in = [&]() {
+        if (!pending) return;
+        std::swap(xcur, xoth);
+        pending = false;
+    };
     if (planes && !above_trunk) {
         e.nx_hi = xb_hi; e.nx_lo = xb_lo; e.nx_gain = m->dec[layer0].ln1; e.nx_ssq = M.ssq;
         xb_parts = kEmbedSsqParts;
@@ -650,7 +671,8 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
         char* kc = M.kcache + (size_t)l * s->cap_len * I * esz;
         char* vc = M.vcache + (size_t)l * s->cap_len * I * esz;
         {
-            GemmArgs g = gemm_base(m, L.wqkv, M.x, d, T, L.ln1);
+            GemmArgs g = gemm_base(m, L.wqkv, xcur, d, T, L.ln1);
+            set_parts_in(g);
             g.epi = EPI_QKV;
             g.q_dim = I;
             g.q_out = M.q;
@@ -662,6 +684,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
             set_in(g);
             int rc = emit_gemm(s, m, g);
             if (rc) return rc;
+            after_parts_in();
         }
         {
             AttnArgs a;
@@ -682,7 +705,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
         {
             GemmArgs g = gemm_base(m, L.wo, M.a, I, T, nullptr);
             g.epi = EPI_RESID;
-            g.out = M.x;
+            g.out = xcur;
             g.ldo = d;
             if (merge_splits > 1) { g.mg_splits = merge_splits; g.mg_o = M.att_o; g.mg_ml = M.att_ml; g.mg_heads = c.n_heads; }
             else if (planes) { g.xb_hi = ab_hi; g.xb_lo = ab_lo; }
@@ -693,7 +716,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
         }
         if (c.cross_attn) {
             {
-                GemmArgs g = gemm_base(m, L.cwq, M.x, d, T, L.lnc);
+                GemmArgs g = gemm_base(m, L.cwq, xcur, d, T, L.lnc);
                 g.epi = EPI_STORE;
                 g.out = M.q;
                 g.ldo = I;
@@ -721,7 +744,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
             {
                 GemmArgs g = gemm_base(m, L.cwo, M.a, I, T, nullptr);
                 g.epi = EPI_RESID;
-                g.out = M.x;
+                g.out = xcur;
                 g.ldo = d;
                 if (merge_splits > 1) { g.mg_splits = merge_splits; g.mg_o = M.att_o; g.mg_ml = M.att_ml; g.mg_heads = c.n_heads; }
                 else if (planes) { g.xb_hi = ab_hi; g.xb_lo = ab_lo; }
@@ -732,7 +755,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
             }
         }
         {
-            GemmArgs g = gemm_base(m, L.win, M.x, d, T, L.ln2);
+            GemmArgs g = gemm_base(m, L.win, xcur, d, T, L.ln2);
             g.epi = EPI_ACT;
             g.out = M.h;
             g.ldo = F;
@@ -744,8 +767,15 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
             if (rc) return rc;
             GemmArgs g2 = gemm_base(m, L.wout, M.h, F, T, nullptr);
             g2.epi = EPI_RESID;
-            g2.out = M.x;
+            g2.out = xcur;
             g2.ldo = d;
+            if (split_ffn && (l + 1 < c.n_dec_layers || head_reads_parts)) {
+                g2.epi = EPI_PART;
+                g2.out = M.px;
+                g2.ksplit = kPartSlices;
+                g2.part_stride = (int64_t)kMaxRows * d;
+                pending = true;
+            }
             if (h_planes) { g2.xb_hi = hb_hi; g2.xb_lo = hb_lo; }
             // the next reader of the residual stream: the following layer's first norm, or the final norm (LM head)
             if (h_planes) set_out(g2, l + 1 < c.n_dec_layers ? m->dec[l + 1].ln1 : m->dec_final);
@@ -757,7 +787,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
     if (trunk > 0 && w == 0 && !s->gemm_only) {  // remember what the trunk produced for these positions
         RowCopyArgs rc;
         std::memset((void*)&rc, 0, sizeof(rc));
-        rc.src = M.x;
+        rc.src = xcur;
         rc.dst = s->trunk_x;
         rc.dst_row_ptr = len_ptr;
         rc.d = d;
@@ -765,6 +795,8 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, int* xb_parts_out) {
         HIPC(launch_row_copy(rc, s->stream));
     }
     *xb_parts_out = xb_parts;
+    *x_out = xcur;
+    *parts_pending = pending;
     return BILD_OK;
 }
 
@@ -782,8 +814,12 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
     const int d = c.d_model, dt = c.dtype;
     const int* len_ptr = &s->ctl->len[w];
     int xb_parts = 0;  // > 0: the final hidden state also sits in M.xb as bf16 planes (times the final norm's gain)
+    float* xfin = M.x;  // the residual stream after the last layer ...
+    bool parts = false; // ... to which the partial results in M.px are still to be added (split FFN output projection)
     {
-        int rc = emit_layers(s, w, T, key_hint, &xb_parts);
+        // a single-row pass whose LM head is the one-row kernel with one feature tile per wave can add them itself
+        const bool head_reads_parts = T == 1 && lm_rows == 1 && s->pair->trunk_layers == 0 && m->head.tn < 8192;
+        int rc = emit_layers(s, w, T, key_hint, head_reads_parts, &xb_parts, &xfin, &parts);
         if (rc) return rc;
     }
     FinishArgs f;
@@ -795,7 +831,8 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
     f.y_cap = s->max_len;
     f.host_mirror = s->hctl_dev;
     if (lm_rows > 0) {
-        GemmArgs g = gemm_base(m, m->head, M.x + (size_t)(T - lm_rows) * d, d, lm_rows, m->dec_final);
+        GemmArgs g = gemm_base(m, m->head, xfin + (size_t)(T - lm_rows) * d, d, lm_rows, m->dec_final);
+        if (parts) { g.px = M.px; g.px_stride = (int64_t)kMaxRows * d; g.pn = kPartSlices; g.x_out = xfin == M.x ? M.x2 : M.x; }
         g.epi = EPI_LMHEAD;
         g.scale = c.logit_scale;
         g.pos_ptr = len_ptr;

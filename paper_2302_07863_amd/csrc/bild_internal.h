@@ -61,7 +61,8 @@ enum Epilogue : int {
     EPI_RESID = 1,  // out[t][n] += v
     EPI_QKV = 2,    // n < q_dim -> q_out; then K rows, then V rows of the cache (RoPE on q, k)
     EPI_ACT = 3,    // out[t][n] = act(v) or act(gate) * up for gated FFNs
-    EPI_LMHEAD = 4  // z = scale * v; softmax partials, logit of the target token
+    EPI_LMHEAD = 4, // z = scale * v; softmax partials, logit of the target token
+    EPI_PART = 5    // out[slice][t][n] = v over a slice of the inputs, no norm (see GemmArgs::ksplit)
 };
 
 struct GemmArgs {
@@ -103,6 +104,17 @@ struct GemmArgs {
     const float* mg_o;   // [mg_splits][T][ldx] unnormalised outputs
     const float* mg_ml;  // [mg_splits][T][mg_heads][2]
     int mg_heads;
+    // A projection with few output features and many inputs may be cut into `ksplit` slices of its inputs, each slice a
+    // workgroup row of its own (blockIdx.y) that writes out + slice * part_stride (EPI_PART); its reader then takes
+    // x = base + sum of the slices (px, pn = ksplit) while staging and writes the sum to x_out.
+    int ksplit;             // > 1: EPI_PART launch over blockIdx.y slices; W.tk must be a multiple of it
+    int64_t part_stride;    // floats between the outputs of consecutive slices
+    int k_len;              // (set by the launch wrapper) inputs of this workgroup's slice
+    int k_off_tiles;        // (set by the launch wrapper) first input tile of the slice
+    const float* px;        // reader: pn partial results [pn][px_stride] laid out like x
+    int64_t px_stride;
+    int pn;                 // 0 or kPartSlices
+    float* x_out;           // reader: where workgroup 0 writes base + partial results ([T][ldx], not x itself)
     // bf16 models, passes of a few rows: activations travel between projections as two bf16 planes (high part and
     // low part of each value, [T][ld]) written once by the producer, with the consumer's norm gain already applied
     const uint16_t* xb_hi;  // input planes (non-null: x, gain are not read; ldx is their row stride)
@@ -165,6 +177,7 @@ struct EmbedArgs {
     float* nx_ssq;
 };
 constexpr int kEmbedSsqParts = 4;
+constexpr int kPartSlices = 4;      // input slices of a split projection (EPI_PART) = partial results its reader adds
 constexpr int kMaxSsqParts = 256;  // partial sums of squares a consumer adds per row
 
 // Copies T rows of d floats: dst[dst_row + t] = src[src_row + t], each row index = (*ptr or 0) + add.

@@ -48,18 +48,22 @@ __device__ __forceinline__ void put_planes(const GemmArgs& a, int t, int n0, con
 }
 
 // `vblock` is the index of the feature-tile group this workgroup handles (blockIdx.x); `smem` is its dynamic LDS.
+// KS: this workgroup covers only a slice of the inputs (a.k_len inputs from tile a.k_off_tiles on; a.x points at the
+// slice): the launch wrapper gives every slice its own output (EPI_PART), and the projection that reads the result adds the
+// slices up while staging.  PS > 0: that reader - its input is a.x plus PS partial results a.px[j] (fixed order), and the
+// workgroup with index 0 also writes the sum to a.x_out (another buffer than a.x, which the other workgroups still read).
 // PRE: the input arrives as high / low bf16 planes with the consumer's norm gain already applied, written by the
 // kernel that produced it (a.xb_hi, a.xb_lo; a.ssq_part holds that kernel's per-wave sums of squares): staging is a
 // plain copy into LDS.  NX: this kernel's epilogue hands its own output on in that form (a.nx_*).
 template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, false, NT), int MG = 0,
-          bool ONE = false, bool TWO = true, int TCAP = 0, bool PRE = false, bool NX = false>
+          bool ONE = false, bool TWO = true, int TCAP = 0, bool PRE = false, bool NX = false, int PS = 0, bool KS = false>
 __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, char* smem) {
     constexpr int KT = DT ? 32 : 16;
     // the wave index through readfirstlane: the compiler then knows that it - and every tile index, weight address and
     // range test derived from it - is the same in all lanes, and keeps them in scalar registers
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nthr = blockDim.x, NWV = nthr >> 6;
-    const int T = ONE ? 1 : a.T, K = a.W.k, KC = a.kc;
+    const int T = ONE ? 1 : a.T, K = KS ? a.k_len : a.W.k, KC = a.kc;
     const int WK = a.wk, WR = NWV / WK;
     const int wkid = wave % WK, wrid = wave / WK;
     const int tile0 = (vblock * WR + wrid) * RW;
@@ -79,7 +83,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
     // Every projection that adds to the residual stream reads un-normalised input and every other one reads through an
     // RMSNorm, so the presence of the norm is a compile-time fact (the launcher rejects anything else); a run-time
     // test here would make the gain loads conditional.
-    constexpr bool norm = EPI != EPI_RESID;
+    constexpr bool norm = EPI != EPI_RESID && EPI != EPI_PART;
     const bool few = T < 4;  // few rows: all waves share each row and split it along k
     const bool owner = (wkid == 0);
     bool valid[RW];
@@ -87,7 +91,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
         valid[r] = tile0 + r < a.W.tn;
-        wbase[r] = (const char*)a.W.w + ((size_t)min(tile0 + r, a.W.tn - 1) * a.W.tk) * kTileBytes;  // scalar; the lane part is added per load
+        wbase[r] = (const char*)a.W.w + ((size_t)min(tile0 + r, a.W.tn - 1) * a.W.tk + (KS ? a.k_off_tiles : 0)) * kTileBytes;  // scalar; the lane part is added per load
     }
     const int tok_l = lane & 15, kq = lane >> 4;
 
@@ -236,13 +240,25 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
     auto noop = [](bool) {};
     auto stage = [&](const int k0, const int kc_len, auto&& hook) {
         const int n4 = kc_len >> 2;
-        auto ldx = [&](int t, int k4) -> float4 { return ld_act4(a.x + (size_t)t * a.ldx + k0 + k4 * 4); };
+        struct XV { float4 p[PS + 1]; };  // one piece of x: the base and the PS partial results still to be added
+        auto ldx = [&](int t, int k4) -> XV {
+            XV r;
+            const size_t off = (size_t)t * a.ldx + k0 + k4 * 4;
+            r.p[0] = ld_act4(a.x + off);
+#pragma unroll
+            for (int j = 0; j < PS; ++j) r.p[j + 1] = ld_act4(a.px + (size_t)j * a.px_stride + off);
+            return r;
+        };
         auto ldg = [&](int k4) -> float4 {
             if (!norm) return make_float4(0.f, 0.f, 0.f, 0.f);
             return *(const float4*)(a.gain + k0 + k4 * 4);
         };
         // writes one float4 of row t and returns its sum of squares (for the RMSNorm)
-        auto put = [&](int t, int k4, float4 w, const float4& gg) -> float {
+        auto put = [&](int t, int k4, const XV& wv, const float4& gg) -> float {
+            float4 w = wv.p[0];
+#pragma unroll
+            for (int j = 0; j < PS; ++j) { w.x += wv.p[j + 1].x; w.y += wv.p[j + 1].y; w.z += wv.p[j + 1].z; w.w += wv.p[j + 1].w; }
+            if (PS > 0 && vblock == 0) st_act4(a.x_out + (size_t)t * a.ldx + k0 + k4 * 4, w);  // the residual stream, for later readers
             float ss = 0.f;
             if (norm) {
                 ss = w.x * w.x + w.y * w.y + w.z * w.z + w.w * w.w;
@@ -356,7 +372,9 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
                         const float w = wp[sp];
                         r.x += o[u][sp].x * w; r.y += o[u][sp].y * w; r.z += o[u][sp].z * w; r.w += o[u][sp].w * w;
                     }
-                    put(tt[u], kk[u], r, r);
+                    XV rv;
+                    rv.p[0] = r;
+                    put(tt[u], kk[u], rv, r);
                 }
             };
             // the first round takes as many pieces as the rows need (a padding piece costs SP loads and a conversion)
@@ -383,7 +401,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
             auto pieces = [&](auto np, auto eager, int eb, auto&& hk) {
                 constexpr int P = decltype(np)::value;
                 constexpr bool EAGER = decltype(eager)::value;
-                float4 v[P], g[P];
+                XV v[P];
+                float4 g[P];
                 int tt[P], kk[P];
 #pragma unroll
                 for (int u = 0; u < P; ++u) {
@@ -438,7 +457,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
                 float ssj = 0.f;
                 if (n4 <= step) {  // at most one element per thread (a padding second one would cost a load and a conversion)
                     const int ca = min(start, n4 - 1);
-                    const float4 va = ldx(t, ca), ga = ldg(ca);
+                    const XV va = ldx(t, ca);
+                    const float4 ga = ldg(ca);
                     hk(true);
                     __builtin_amdgcn_sched_barrier(0);  // (as above)
                     const float sa = put(t, ca, va, ga);
@@ -446,15 +466,17 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
                 } else if (n4 <= 2 * step) {  // short rows: at most two elements per thread
                     const int ka = start, kb2 = start + step;
                     const int ca = min(ka, n4 - 1), cb = min(kb2, n4 - 1);
-                    const float4 va = ldx(t, ca), ga = ldg(ca), vb = ldx(t, cb), gb = ldg(cb);
+                    const XV va = ldx(t, ca), vb = ldx(t, cb);
+                    const float4 ga = ldg(ca), gb = ldg(cb);
                     hk(true);
                     __builtin_amdgcn_sched_barrier(0);  // (as above)
                     // unconditional conversions and writes (duplicates carry the same value and count as zero)
                     const float sa = put(t, ca, va, ga), sb = put(t, cb, vb, gb);
                     ssj += (act && ka < n4 ? sa : 0.f) + (act && kb2 < n4 ? sb : 0.f);
-                } else {
+                } else if constexpr (PS == 0) {  // (a reader of partial results is launched with at most two pieces per thread)
                     auto rnd = [&](int kb, auto&& hk2) {
-                        float4 v[8], g[8];
+                        XV v[8];
+                        float4 g[8];
 #pragma unroll
                         for (int u = 0; u < 8; ++u) {  // all loads of the round first
                             const int k4 = min(kb + u * step, n4 - 1);
@@ -618,6 +640,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
             float v4[4] = {acc[rwi][nt][0] * r, acc[rwi][nt][1] * r, acc[rwi][nt][2] * r, acc[rwi][nt][3] * r};
             switch (epi) {
                 case EPI_STORE:
+                case EPI_PART:
                     st_act4(a.out + (size_t)t * a.ldo + n0, make_float4(v4[0], v4[1], v4[2], v4[3]));
                     break;
                 case EPI_RESID: {

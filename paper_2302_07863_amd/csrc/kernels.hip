@@ -48,20 +48,48 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
 //   2: at most 16  - two batches of 8
 //   0: more        - batches of 12 (more bytes in flight for the bandwidth-bound shapes)
 constexpr int kShortBatch = 8;
-template <int DT, int RW, int EPI, int ROPE, int VAR = 0>
+template <int DT, int RW, int EPI, int ROPE, int VAR = 0, int PS = 0>
 __global__ __launch_bounds__(512) void gemm_row_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    gemm_body<DT, RW, EPI, ROPE, 1, VAR ? kShortBatch / RW : gemm_batch(RW, true), 0, true, VAR != 1>(a, (int)blockIdx.x, smem);
+    gemm_body<DT, RW, EPI, ROPE, 1, VAR ? kShortBatch / RW : gemm_batch(RW, true), 0, true, VAR != 1, 0, false, false, PS>(
+        a, (int)blockIdx.x, smem);
 }
 
 // Two to four rows (the bulk of the large model's review passes) on a single-chunk input: the same body without the
 // staging rounds for more rows and without the multi-chunk loop.  Run through the general kernel a pass of these row
 // counts costs about 0.7 us more per projection (measured: one row through gemm_kernel 1018 us per T5-large pass,
 // through gemm_row_kernel 911 us), which is code size and register pressure, not work.
-template <int DT, int RW, int EPI, int ROPE, bool SHORT>
+template <int DT, int RW, int EPI, int ROPE, bool SHORT, int PS = 0>
 __global__ __launch_bounds__(512) void gemm_few_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    gemm_body<DT, RW, EPI, ROPE, 1, gemm_batch(RW, false, 1), 0, false, !SHORT, 4>(a, (int)blockIdx.x, smem);
+    gemm_body<DT, RW, EPI, ROPE, 1, gemm_batch(RW, false, 1), 0, false, !SHORT, 4, false, false, PS>(a, (int)blockIdx.x, smem);
+}
+
+// A projection cut into slices of its inputs (few output features, many inputs: the FFN output projection of the
+// narrow models, 64 feature tiles x 4096 inputs): blockIdx.y picks the slice, every slice writes a partial result of its own
+// and the next projection adds them to the residual stream while staging.  One row (VAR as in gemm_row_kernel) or
+// two to four rows (FEW, SHORT as in gemm_few_kernel).
+__device__ __forceinline__ GemmArgs part_slice(const GemmArgs& a, int kt) {
+    GemmArgs b = a;
+    const int tps = a.W.tk / a.ksplit, ks = (int)blockIdx.y;
+    b.k_off_tiles = ks * tps;
+    b.k_len = tps * kt;
+    b.x = a.x + (size_t)ks * tps * kt;
+    b.out = a.out + (size_t)ks * a.part_stride;
+    return b;
+}
+template <int DT, int VAR>
+__global__ __launch_bounds__(512) void gemm_part_row_kernel(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const GemmArgs b = part_slice(a, DT ? 32 : 16);
+    gemm_body<DT, 1, EPI_PART, 0, 1, VAR ? kShortBatch : gemm_batch(1, true), 0, true, VAR != 1, 0, false, false, 0, true>(
+        b, (int)blockIdx.x, smem);
+}
+template <int DT, bool SHORT>
+__global__ __launch_bounds__(512) void gemm_part_few_kernel(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const GemmArgs b = part_slice(a, DT ? 32 : 16);
+    gemm_body<DT, 1, EPI_PART, 0, 1, gemm_batch(1, false, 1), 0, false, !SHORT, 4, false, false, 0, true>(b, (int)blockIdx.x, smem);
 }
 
 // Output projection whose input is still in key-split attention partials (merged while staging).
@@ -93,6 +121,10 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const GemmArgs a) {
 // a longer chunk means fewer chunk boundaries, at each of which the weight stream of the workgroup pauses for the staging.
 constexpr int kGemmLdsLimit = 160 * 1024;
 constexpr int kGemmStageBudget = 144 * 1024;
+// Inputs (and input tiles) one workgroup covers: all of them, or one slice of a split projection.
+static inline int eff_k(const GemmArgs& a) { return a.ksplit > 1 ? a.W.k / a.ksplit : a.W.k; }
+static inline int eff_tk(const GemmArgs& a) { return a.ksplit > 1 ? a.W.tk / a.ksplit : a.W.tk; }
+
 // Rows-per-wave, chunk length and tiles per chunk of a GEMM: what both launch-shape rules start from.
 static int gemm_pick_chunks(GemmArgs& a, int dtype) {
     const int kt = dtype ? 32 : 16;
@@ -107,10 +139,10 @@ static int gemm_pick_chunks(GemmArgs& a, int dtype) {
     const int budget = std::min(kGemmStageBudget, kGemmLdsLimit - gemm_tail_bytes(8, a.rw * ((Tb + 15) / 16)));
     int kc_max = budget / (4 * Tb) - 8;      // 4 bytes of LDS per staged input for either storage type
     kc_max = std::max(128, (kc_max / 128) * 128);
-    const int nch = (a.W.k + kc_max - 1) / kc_max;
-    const int kc = ((a.W.k + nch - 1) / nch + kt - 1) / kt * kt;
+    const int nch = (eff_k(a) + kc_max - 1) / kc_max;
+    const int kc = ((eff_k(a) + nch - 1) / nch + kt - 1) / kt * kt;
     a.kc = kc;
-    const int tiles_last = (a.W.k - (nch - 1) * kc) / kt;
+    const int tiles_last = (eff_k(a) - (nch - 1) * kc) / kt;
     return std::min(kc / kt, tiles_last);
 }
 
@@ -130,7 +162,7 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     // wave streams a long contiguous run (measured best on 32128x1024, 22016x4096 and 4096x11008).
     const int batch = gemm_batch(a.rw, a.T == 1, (Tb + 15) / 16);
     int wk_lat = 1, wk_par = 1;
-    while (wk_lat < 8 && a.W.tk / wk_lat > batch) wk_lat *= 2;
+    while (wk_lat < 8 && eff_tk(a) / wk_lat > batch) wk_lat *= 2;
     while (wk_par < 8 && (long)a.W.tn * wk_par < 1536) wk_par *= 2;
     int wk = std::min(wk_lat, wk_par);
     while (wk > 1 && (wk * nacc > 32 || wk > tiles_chunk)) wk /= 2;
@@ -149,7 +181,7 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     // workgroup would stage more than eight pieces (staging the activations is then the longer part, and it is shared
     // by all waves; measured on 24 layers of 1024-wide projections: 4 waves win up to 8 rows, 1365 against 1490 us per
     // pass, 8 waves from 9 rows, 1505 against 1578)
-    int wr = std::max(1, ((long)a.T * a.W.k > 8192 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
+    int wr = std::max(1, ((long)a.T * eff_k(a) > 8192 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
     for (int c = wr * 2; c * wk <= 8 && c * wk * nacc <= 32; c *= 2)
         if ((a.W.tn + c * a.rw - 1) / (c * a.rw) >= 512) wr = c;
     // Between one and two workgroups per compute unit the chip ends up half with two and half with one of them:
@@ -235,6 +267,64 @@ hipError_t kernels_init() {
     return attention_init();
 }
 
+// Split projections (EPI_PART) and their readers (pn > 0): one to four rows, one chunk of inputs.
+static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st) {
+    const size_t smem = gemm_lds_bytes(a, dtype);
+    const int kk = eff_k(a), tk = eff_tk(a);
+    const bool one_chunk = kk <= a.kc;
+    const int per_wave = (tk + a.wk - 1) / a.wk;
+    const int n4 = kk / 4, nthr = 64 * a.nwv;
+    if (a.T < 1 || a.T > 4 || !one_chunk || a.rw != 1 || a.mg_splits > 1 || a.xb_hi || a.nx_hi) return hipErrorInvalidValue;
+    // the staging paths these kernels keep: one row with at most two pieces per thread; two to four rows with whole
+    // wavefront-wide rows and at most four pieces per thread
+    if (a.T == 1 ? n4 > 2 * nthr : ((n4 & 63) != 0 || a.T * n4 > 4 * nthr)) return hipErrorInvalidValue;
+    const dim3 block(nthr);
+    if (a.epi == EPI_PART) {
+        if (a.ksplit < 2 || a.W.tk % a.ksplit || a.pn > 0 || !a.out) return hipErrorInvalidValue;
+        const dim3 grid((unsigned)gemm_num_blocks(a), (unsigned)a.ksplit);
+#define BILD_PK(DTV)                                                                                              \
+    do {                                                                                                          \
+        if (a.T == 1 && per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 1>), grid, block, smem, st, a); \
+        else if (a.T == 1 && per_wave <= 2 * kShortBatch) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 2>), grid, block, smem, st, a); \
+        else if (a.T == 1) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 0>), grid, block, smem, st, a);          \
+        else if (per_wave <= gemm_batch(1, false)) hipLaunchKernelGGL((gemm_part_few_kernel<DTV, true>), grid, block, smem, st, a); \
+        else hipLaunchKernelGGL((gemm_part_few_kernel<DTV, false>), grid, block, smem, st, a);                    \
+    } while (0)
+        if (dtype) BILD_PK(1); else BILD_PK(0);
+#undef BILD_PK
+        return hipGetLastError();
+    }
+    if (a.pn != kPartSlices || !a.px || !a.x_out || a.x_out == a.x || a.ksplit > 1) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)gemm_num_blocks(a));
+    constexpr int PSV = kPartSlices;
+#define BILD_RD1(DTV, EPIV, ROPEV) /* one row */                                                                 \
+    do {                                                                                                          \
+        if (per_wave <= kShortBatch)                                                                              \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 1, PSV>), grid, block, smem, st, a);         \
+        else if (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))              \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 2, PSV>), grid, block, smem, st, a);         \
+        else                                                                                                      \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 0, PSV>), grid, block, smem, st, a);         \
+    } while (0)
+#define BILD_RDF(DTV, ROPEV) /* two to four rows: the first projection of a layer only */                         \
+    do {                                                                                                          \
+        if (per_wave <= gemm_batch(1, false))                                                                     \
+            hipLaunchKernelGGL((gemm_few_kernel<DTV, 1, EPI_QKV, ROPEV, true, PSV>), grid, block, smem, st, a);   \
+        else                                                                                                      \
+            hipLaunchKernelGGL((gemm_few_kernel<DTV, 1, EPI_QKV, ROPEV, false, PSV>), grid, block, smem, st, a);  \
+    } while (0)
+#define BILD_RDD(DTV)                                                                                             \
+    if (a.epi == EPI_QKV && a.T == 1) { if (a.rope) BILD_RD1(DTV, EPI_QKV, 1); else BILD_RD1(DTV, EPI_QKV, 0); }  \
+    else if (a.epi == EPI_QKV) { if (a.rope) BILD_RDF(DTV, 1); else BILD_RDF(DTV, 0); }                           \
+    else if (a.epi == EPI_LMHEAD && a.T == 1) BILD_RD1(DTV, EPI_LMHEAD, 0);                                       \
+    else return hipErrorInvalidValue;
+    if (dtype) { BILD_RDD(1) } else { BILD_RDD(0) }
+#undef BILD_RDD
+#undef BILD_RDF
+#undef BILD_RD1
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
     if (a.T >= kDenseMinRows) return launch_gemm_dense(a, dtype, st);
@@ -242,7 +332,8 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     const size_t smem = gemm_lds_bytes(a, dtype);
     const unsigned row_blocks = (unsigned)((a.T + kMaxRows - 1) / kMaxRows);
     if (row_blocks > 1 && a.epi == EPI_LMHEAD) return hipErrorInvalidValue;  // softmax partials are per pass
-    if ((a.gain != nullptr) != (a.epi != EPI_RESID)) return hipErrorInvalidValue;  // the kernels fix the norm by the epilogue
+    if ((a.gain != nullptr) != (a.epi != EPI_RESID && a.epi != EPI_PART)) return hipErrorInvalidValue;  // the kernels fix the norm by the epilogue
+    if (a.epi == EPI_PART || a.pn > 0) return launch_gemm_split(a, dtype, st);
     if (a.mg_splits > 1) {
         // merged staging: 2, 4 or 8 splits, up to 16 rows, one (row, head) pair per thread, weights in the reduction area
         const int sp = a.mg_splits, npairs = a.T * a.mg_heads;

@@ -104,6 +104,32 @@ def test_bf16_plane_handover_at_every_row_count(name, first_rows, monkeypatch):
         assert np.max(np.abs(a - b)) <= parity.logit_tol(R.cfg)
 
 
+@pytest.mark.parametrize("name", ["f32-relu-tied", "bf16-relu-tied", "bf16-trunc-geglu", "f32-rope-swiglu-deconly", "tiny"])
+def test_split_ffn_output_projection_on_small_widths(name, monkeypatch):
+    """Narrow models cut the FFN output projection of passes of one to four rows into slices of its inputs whose partial
+    results the next projection (or the LM head) adds to the residual stream; by default only from an FFN width of 2048
+    (configs 2 and 3 at full size).  Here from a width of 64, so that the toys and config 1 (whose widths also allow the
+    two-to-four-row form) take that route against the oracle, logit by logit."""
+    monkeypatch.setenv("BILD_KSPLIT_MIN_F", "64")
+    if name == "tiny":
+        R = Rig(bi.tiny_pair())
+    else:
+        R = Rig(bi.toy_pair(**dict(TOY_VARIANTS[name], d_ff=128)))
+    for fb, rb, nm in ((R.cfg.alpha_fb, R.cfg.alpha_rb, 10), (0.2, 0.7, 3)):
+        ref = oracle.bild_generate(R.req, fb, rb, nm, R.cfg.max_new, keep_logits=True)
+        st = R.state(R.cfg.max_new, nm)
+        st.encode(R.src)
+        worst = parity.teacher_forced(st, ref, R.n0, fb, rb, R.cfg)
+        print(name, worst)
+        toks, stats = R.state(R.cfg.max_new, nm).generate(R.src, fb, rb, R.cfg.max_new)
+        parity.compare_generation(toks, stats, ref, fb, rb)
+    # the same generation twice is the same bits
+    st = R.state(R.cfg.max_new, 10)
+    a = st.generate(R.src, 0.5, 2.0, R.cfg.max_new)
+    b = st.generate(R.src, 0.5, 2.0, R.cfg.max_new)
+    assert a == b
+
+
 @pytest.mark.parametrize("name", list(TOY_VARIANTS))
 def test_toy_free_running_generate(name):
     R = rig(name)
