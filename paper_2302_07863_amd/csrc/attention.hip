@@ -22,7 +22,9 @@ constexpr int kAttnLdsLimit = 160 * 1024;
 // Cache rows beyond the valid length are finite (zero-filled at allocation, or stale
 // values of discarded tokens), so a probability of exactly 0 removes them.
 // =====================================================================================
-template <int DT, int DH32, bool REL = false>
+// FUSE: the finished output of the head stays in LDS (in q's place, in q's operand layout) for the output projection
+// that the same workgroup runs next (attn_proj_kernel); nothing is written to memory here.
+template <int DT, int DH32, bool REL = false, bool FUSE = false>
 __device__ __forceinline__ void attn_body(const AttnArgs& a, const int vblock, char* smem) {
     constexpr int DHP = DH32 * 32;   // head dim padded to the k-step of the first product
     constexpr int DT16 = DH32 * 2;   // 16-wide output tiles along the head dim
@@ -297,7 +299,20 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int vblock, c
             Lsum += cl[w * 32 + nt * 16 + tok_l] * wgt;
             acc += co[((w * NT + nt) * DT16 + dt) * 64 + lane] * wgt;
         }
-        if (t < T && d0 < dh) {
+        if constexpr (FUSE) {
+            const float inv = t < T ? 1.f / Lsum : 0.f;
+            const float o0 = t < T ? acc[0] * inv : 0.f, o1 = t < T ? acc[1] * inv : 0.f;
+            const float o2 = t < T ? acc[2] * inv : 0.f, o3 = t < T ? acc[3] * inv : 0.f;
+            if (DT) {
+                uint32_t h01, l01, h23, l23;
+                split_bf16x2(o0, o1, h01, l01);
+                split_bf16x2(o2, o3, h23, l23);
+                *(uint2*)(q_hi + t * qstride + d0 * 2) = make_uint2(h01, h23);
+                *(uint2*)(q_lo + t * qstride + d0 * 2) = make_uint2(l01, l23);
+            } else {
+                *(float4*)(q_hi + t * qstride + d0 * 4) = make_float4(o0, o1, o2, o3);
+            }
+        } else if (t < T && d0 < dh) {
             if (a.splits == 1) {
                 const float inv = 1.f / Lsum;
                 if (DT && a.ob_hi) {
@@ -338,6 +353,68 @@ __global__ __launch_bounds__(512) void attn_rows_kernel(const AttnArgs a) {
     b.out = a.out + (size_t)r0 * a.i_dim;
     b.base_add = a.base_add + r0;
     attn_body<DT, DH32, REL>(b, (int)blockIdx.x, smem);
+}
+
+// Attention of one head followed by that head's share of the output projection, for single-row passes of the narrow
+// models: workgroup (head h, column group c) runs the whole attention of head h (every column group repeats it: the
+// cache of a head is a few KiB to 128 KiB) and multiplies the result by the rows h * d_head .. of W_o for its
+// share of the output features.  The product is a partial result of the residual update, one per head
+// (proj_out[h][t][n]); the projection that reads the residual stream next adds them up while staging, so the
+// output projection costs no launch of its own.  The weight tiles are requested at entry and arrive during the attention.
+template <int DT, int DH32, bool REL = false>
+__global__ __launch_bounds__(512) void attn_proj_kernel(const AttnArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int KT = DT ? 32 : 16, DHP = DH32 * 32, KH = DHP / KT, MAXN = DT ? 4 : 2;  // (fp32: four input tiles per head already)
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = (int)blockDim.x >> 6;
+    const int h = (int)blockIdx.x, c = (int)blockIdx.y;
+    const int npc = (a.wo.tn + (int)gridDim.y - 1) / (int)gridDim.y;  // feature tiles per column group
+    const int khr = a.d_head / KT, kt0 = h * khr;                      // this head's input tiles (d_head is a multiple of KT)
+    uint4 Wt[MAXN][KH];
+#pragma unroll
+    for (int i = 0; i < MAXN; ++i) {
+        const int n = min(c * npc + wave + i * nw, a.wo.tn - 1);
+#pragma unroll
+        for (int j = 0; j < KH; ++j)
+            Wt[i][j] = *(const uint4*)((const char*)a.wo.w + ((size_t)n * a.wo.tk + kt0 + min(j, khr - 1)) * kTileBytes + lane * 16);
+    }
+    attn_body<DT, DH32, REL, true>(a, h, smem);
+    __syncthreads();
+    const int tok_l = lane & 15, g = lane >> 4;
+    const int qstride = DT ? (DHP + 8) * 2 : (DHP + 4) * 4;
+    const int NT = (a.T + 15) >> 4;
+    const char* o_hi = smem;
+    const char* o_lo = smem + NT * 16 * qstride;
+#pragma unroll
+    for (int i = 0; i < MAXN; ++i) {
+        const int n = c * npc + wave + i * nw;  // wave-uniform
+        if (n >= (c + 1) * npc || n >= a.wo.tn) continue;
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f}, acc2 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < KH; ++j) {
+            if (j >= khr) continue;
+            if (DT) {
+                const bf16x8 Aw = __builtin_bit_cast(bf16x8, Wt[i][j]);
+                const bf16x8 Bh = __builtin_bit_cast(bf16x8, *(const uint4*)(o_hi + tok_l * qstride + (j * 32 + g * 8) * 2));
+                const bf16x8 Bl = __builtin_bit_cast(bf16x8, *(const uint4*)(o_lo + tok_l * qstride + (j * 32 + g * 8) * 2));
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bh, acc, 0, 0, 0);
+                acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aw, Bl, acc2, 0, 0, 0);
+            } else {
+                const float4 b = *(const float4*)(o_hi + tok_l * qstride + (j * 16 + g * 4) * 4);
+                const float aa[4] = {__uint_as_float(Wt[i][j].x), __uint_as_float(Wt[i][j].y), __uint_as_float(Wt[i][j].z),
+                                     __uint_as_float(Wt[i][j].w)};
+                const float bb[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+                for (int v = 0; v < 4; v += 2) {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[v], bb[v], acc, 0, 0, 0);
+                    acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(aa[v + 1], bb[v + 1], acc2, 0, 0, 0);
+                }
+            }
+        }
+        acc += acc2;
+        if (tok_l < a.T)
+            st_act4(a.proj_out + (size_t)h * a.proj_stride + (size_t)tok_l * a.d_model + n * 16 + g * 4,
+                    make_float4(acc[0], acc[1], acc[2], acc[3]));
+    }
 }
 
 // Joins the key splits of attention: out[t][n] = sum_s w_s O_s[t][n] / sum_s w_s L_s with w_s = exp(m_s - max m) of
@@ -414,7 +491,11 @@ static hipError_t attn_raise_lds_limits() {
                              (const void*)attn_rows_kernel<1, 2, true>, (const void*)attn_rows_kernel<1, 4, true>,
                              (const void*)attn_kernel<0, 1, true>, (const void*)attn_kernel<0, 2, true>,
                              (const void*)attn_kernel<0, 4, true>, (const void*)attn_kernel<1, 1, true>,
-                             (const void*)attn_kernel<1, 2, true>, (const void*)attn_kernel<1, 4, true>};
+                             (const void*)attn_kernel<1, 2, true>, (const void*)attn_kernel<1, 4, true>,
+                             (const void*)attn_proj_kernel<0, 1>, (const void*)attn_proj_kernel<0, 2>,
+                             (const void*)attn_proj_kernel<1, 1>, (const void*)attn_proj_kernel<1, 2>,
+                             (const void*)attn_proj_kernel<0, 1, true>, (const void*)attn_proj_kernel<0, 2, true>,
+                             (const void*)attn_proj_kernel<1, 1, true>, (const void*)attn_proj_kernel<1, 2, true>};
         for (const void* f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsLimit);
             if (e != hipSuccess) return e;
@@ -425,6 +506,32 @@ static hipError_t attn_raise_lds_limits() {
 }
 
 hipError_t attention_init() { return attn_raise_lds_limits(); }
+
+hipError_t launch_attention_proj(const AttnArgs& a, int dtype, hipStream_t st) {
+    if (hipError_t e = attn_raise_lds_limits(); e != hipSuccess) return e;
+    const int kt = dtype ? 32 : 16;
+    const int dh32 = a.d_head <= 32 ? 1 : (a.d_head <= 64 ? 2 : 4);
+    if (a.T < 1 || a.T > 16 || a.splits != 1 || !a.len_ptr || !a.wo.w || !a.proj_out || a.cgroups < 1 || a.d_head % kt || a.d_head > 64 ||
+        a.wo.k != a.heads * a.d_head || a.wo.n != a.d_model || (a.rel_bias && a.rel_d < 1))
+        return hipErrorInvalidValue;
+    const int npc = (a.wo.tn + a.cgroups - 1) / a.cgroups;
+    if ((npc + a.nw - 1) / a.nw > (dtype ? 4 : 2)) return hipErrorInvalidValue;  // feature tiles a wave keeps in registers
+    const size_t smem = attn_lds_bytes(dtype, a.d_head, a.T, a.nw) + (a.rel_bias ? (size_t)(2 * a.rel_d + 1) * 4 : 0);
+    if (smem > (size_t)kAttnLdsLimit) return hipErrorInvalidValue;
+    const dim3 grid(a.heads, a.cgroups), block(64 * a.nw);
+#define BILD_AP(DTV, DHV)                                                                       \
+    do {                                                                                        \
+        if (a.rel_bias) hipLaunchKernelGGL((attn_proj_kernel<DTV, DHV, true>), grid, block, smem, st, a); \
+        else hipLaunchKernelGGL((attn_proj_kernel<DTV, DHV>), grid, block, smem, st, a);        \
+    } while (0)
+    if (dtype) {
+        if (dh32 == 1) BILD_AP(1, 1); else BILD_AP(1, 2);
+    } else {
+        if (dh32 == 1) BILD_AP(0, 1); else BILD_AP(0, 2);
+    }
+#undef BILD_AP
+    return hipGetLastError();
+}
 
 hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
     if (hipError_t e = attn_raise_lds_limits(); e != hipSuccess) return e;

@@ -314,6 +314,8 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         const char* ng = std::getenv("BILD_NO_GRAPH");
         s->use_graphs = !(ng && ng[0] == '1');
         if (const char* pm = std::getenv("BILD_PRE_MIN_ROWS")) s->pre_min_rows = std::atoi(pm);  // experiments; > 32 turns the planes off
+        if (const char* fa = std::getenv("BILD_FUSE_ATTN")) s->fuse_attn = fa[0] != '0';      // experiments / tests
+        if (const char* fk = std::getenv("BILD_FUSE_MAX_KV")) s->fuse_max_kv = std::atoi(fk);
         if (const char* km = std::getenv("BILD_KSPLIT_MIN_F")) s->ksplit_min_f = std::atoi(km);  // tests: small widths; 0 turns the split off
     }
     for (int w = 0; w < 2; ++w) {
@@ -350,6 +352,7 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         AL(M.h, sizeof(float) * M.rows_cap * F);
         AL(M.x2, sizeof(float) * kMaxRows * d);
         AL(M.px, sizeof(float) * kPartSlices * kMaxRows * d);
+        if (d <= 1024) ALZ(M.pxh, sizeof(float) * kMaxHeadParts * kMaxRows * d);  // slots of heads a model does not have stay zero
         if (m->cfg.pos == BILD_POS_SINUSOIDAL) {
             AL(M.pe, sizeof(float) * (size_t)s->cap_len * d);
             if (launch_pe_table(M.pe, s->cap_len, (int)d, s->stream) != hipSuccess) {
@@ -636,15 +639,44 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
     const bool split_ffn = !planes && T <= 4 && d <= 1024 && s->ksplit_min_f > 0 && F >= s->ksplit_min_f &&
                            (F / kt) % kPartSlices == 0 && (T == 1 || ((d / 4) % 64 == 0 && (F / kPartSlices / 4) % 64 == 0)) && M.px != nullptr;
     float *xcur = M.x, *xoth = M.x2;
-    bool pending = false;  // the residual stream is xcur + the kPartSlices partial results in M.px
+    // > 0: the residual stream is xcur + that many partial results in pend_buf (slices of a split FFN output projection,
+    // or one per head of an attention fused with its output projection), to be added by the next reader
+    int pending = 0;
+    const float* pend_buf = nullptr;
     auto set_parts_in = [&](GemmArgs& g) {
         if (!pending) return;
-        g.px = M.px; g.px_stride = (int64_t)kMaxRows * d; g.pn = kPartSlices; g.x_out = xoth;
+        g.px = pend_buf; g.px_stride = (int64_t)kMaxRows * d; g.pn = pending; g.x_out = xoth;
     };
     auto after_parts_in = [&]() {
         if (!pending) return;
         std::swap(xcur, xoth);
-        pending = false;
+        pending = 0;
+    };
+    // Single-row passes of the narrow models: attention and its output projection as one kernel per (head, column
+    // group); the next projection adds one partial result per head.  A head's cache must be small enough for one
+    // workgroup (every column group repeats the head's attention).
+    const bool fuse_shape = s->fuse_attn && T == 1 && !planes && d <= 1024 && c.n_heads <= kMaxHeadParts && c.d_head <= 64 &&
+                            c.d_head % kt == 0 && M.pxh != nullptr;
+    auto fuse_attention = [&](AttnArgs& a, const TMat& wo, int nkeys) -> int {  // 1: launched fused, 0: not applicable, < 0: error
+        // (measured on the T5-large shape: 64 keys 6.1 us against 4.7 + 3.5 for attention and projection apart; 512 keys,
+        // 128 KiB per head, 11.3 us against 5.1 + 4.5)
+        if (!fuse_shape || (size_t)nkeys * c.d_head * 2 * esz > (size_t)s->fuse_max_kv) return 0;
+        a.splits = 1;
+        a.defer_merge = 0;
+        a.nw = pick_attn_waves(dt, a.d_head, T, nkeys, 1);
+        const int maxn = dt == BILD_DT_BF16 ? 4 : 2;
+        int cg = std::max(1, std::min(wo.tn, 64 / c.n_heads));
+        while (cg < wo.tn && ((wo.tn + cg - 1) / cg + a.nw - 1) / a.nw > maxn) cg *= 2;
+        if (((wo.tn + cg - 1) / cg + a.nw - 1) / a.nw > maxn) return 0;
+        a.wo = wo;
+        a.proj_out = M.pxh;
+        a.proj_stride = (int64_t)kMaxRows * d;
+        a.cgroups = cg;
+        a.d_model = d;
+        if (!s->gemm_only && launch_attention_proj(a, dt, s->stream) != hipSuccess) return BILD_EHIP;
+        pending = kMaxHeadParts;
+        pend_buf = M.pxh;
+        return 1;
     };
     if (planes && !above_trunk) {
         e.nx_hi = xb_hi; e.nx_lo = xb_lo; e.nx_gain = m->dec[layer0].ln1; e.nx_ssq = M.ssq;
@@ -670,6 +702,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
         const LayerW& L = m->dec[l];
         char* kc = M.kcache + (size_t)l * s->cap_len * I * esz;
         char* vc = M.vcache + (size_t)l * s->cap_len * I * esz;
+        int fused = 0;  // this attention ran together with its output projection
         {
             GemmArgs g = gemm_base(m, L.wqkv, xcur, d, T, L.ln1);
             set_parts_in(g);
@@ -699,10 +732,14 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
             a.part_o = M.att_o; a.part_ml = M.att_ml;
             a.scale = att_scale;
             if (planes) { a.ob_hi = ab_hi; a.ob_lo = ab_lo; }
-            int rc = emit_attention(s, M, a, key_hint, &merge_splits);
-            if (rc) return rc;
+            fused = fuse_attention(a, L.wo, key_hint);
+            if (fused < 0) return fused;
+            if (!fused) {
+                int rc = emit_attention(s, M, a, key_hint, &merge_splits);
+                if (rc) return rc;
+            }
         }
-        {
+        if (!fused) {
             GemmArgs g = gemm_base(m, L.wo, M.a, I, T, nullptr);
             g.epi = EPI_RESID;
             g.out = xcur;
@@ -721,8 +758,10 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
                 g.out = M.q;
                 g.ldo = I;
                 set_in(g);
+                set_parts_in(g);
                 int rc = emit_gemm(s, m, g);
                 if (rc) return rc;
+                after_parts_in();
             }
             {
                 AttnArgs a;
@@ -738,10 +777,14 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
                 a.part_o = M.att_o; a.part_ml = M.att_ml;
                 a.scale = att_scale;
                 if (planes) { a.ob_hi = ab_hi; a.ob_lo = ab_lo; }
-                int rc = emit_attention(s, M, a, s->n_src, &merge_splits);
-                if (rc) return rc;
+                fused = fuse_attention(a, L.cwo, s->n_src);
+                if (fused < 0) return fused;
+                if (!fused) {
+                    int rc = emit_attention(s, M, a, s->n_src, &merge_splits);
+                    if (rc) return rc;
+                }
             }
-            {
+            if (!fused) {
                 GemmArgs g = gemm_base(m, L.cwo, M.a, I, T, nullptr);
                 g.epi = EPI_RESID;
                 g.out = xcur;
@@ -760,11 +803,13 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
             g.out = M.h;
             g.ldo = F;
             set_in(g);
+            set_parts_in(g);
             // the hidden state goes on as planes only if this projection itself reads planes (one kernel family per pass)
             const bool h_planes = planes && g.xb_hi != nullptr;
             if (h_planes) { g.nx_hi = hb_hi; g.nx_lo = hb_lo; g.nx_ld = F; }
             int rc = emit_gemm(s, m, g);
             if (rc) return rc;
+            after_parts_in();
             GemmArgs g2 = gemm_base(m, L.wout, M.h, F, T, nullptr);
             g2.epi = EPI_RESID;
             g2.out = xcur;
@@ -774,7 +819,8 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
                 g2.out = M.px;
                 g2.ksplit = kPartSlices;
                 g2.part_stride = (int64_t)kMaxRows * d;
-                pending = true;
+                pending = kPartSlices;
+                pend_buf = M.px;
             }
             if (h_planes) { g2.xb_hi = hb_hi; g2.xb_lo = hb_lo; }
             // the next reader of the residual stream: the following layer's first norm, or the final norm (LM head)
@@ -796,7 +842,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
     }
     *xb_parts_out = xb_parts;
     *x_out = xcur;
-    *parts_pending = pending;
+    *parts_pending = pending > 0;
     return BILD_OK;
 }
 

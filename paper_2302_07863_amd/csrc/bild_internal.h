@@ -158,6 +158,13 @@ struct AttnArgs {
     // what the output projection stages) instead of `out`; not used while the partials are left to the consumer
     uint16_t* ob_hi;
     uint16_t* ob_lo;
+    // attention fused with the output projection (launch_attention_proj): W_o, the partial results of the residual
+    // update, one per head ([heads][proj_stride], laid out [T][d_model]), and the number of column groups
+    TMat wo;
+    float* proj_out;
+    int64_t proj_stride;
+    int cgroups;
+    int d_model;
 };
 
 struct EmbedArgs {
@@ -233,6 +240,8 @@ hipError_t launch_gemm_dense(const GemmArgs& a, int dtype, hipStream_t st);
 hipError_t launch_gemm_pre(const GemmArgs& a, hipStream_t st);
 hipError_t gemm_pre_init();
 hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st);
+hipError_t launch_attention_proj(const AttnArgs& a, int dtype, hipStream_t st);
+constexpr int kMaxHeadParts = 16;   // heads whose partial results one reader adds (attention fused with its output projection)
 hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st);
 // table[pos][k] = sin / cos of pos * 10000^(-2 floor(k/2) / d) (k even / odd), evaluated in double precision as embed_kernel does
 hipError_t launch_pe_table(float* table, int positions, int d, hipStream_t st);

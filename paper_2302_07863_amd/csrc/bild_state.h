@@ -84,6 +84,7 @@ struct ModelState {
     float* ssq = nullptr;     // [d / 16 + 8][32] partial sums of squares beside xb
     float* x2 = nullptr;      // [32][d] second residual-stream buffer (see GemmArgs::x_out)
     float* px = nullptr;      // [kPartSlices][32][d] partial results of a split FFN output projection
+    float* pxh = nullptr;     // [kMaxHeadParts][32][d] one partial result per head of attention fused with its output projection
     float* pe = nullptr;      // sinusoidal models: position table [cap_len][d] for the decoder's embedding
 };
 
@@ -98,6 +99,8 @@ struct bild_state {
     float alpha_fb = -1.f, alpha_rb = -1.f;  // thresholds currently in the device control block
     bool use_graphs = true;
     int ksplit_min_f = 2048;      // FFN widths from which the output projection of a narrow model (d <= 1024) is cut into input slices
+    int fuse_max_kv = 32 << 10;   // ... while one head's cached K/V are at most this many bytes
+    bool fuse_attn = true;        // single-row passes of narrow models: attention and its output projection in one kernel
     int pre_min_rows = 0;         // > 0 (experiments): row count from which a bf16 pass hands activations on as bf16 planes
     bool gemm_only = false;       // measurement: a pass launches only its weight-streaming GEMMs
     int64_t gemm_count = 0, gemm_bytes = 0;  // tallied while a pass is being issued

@@ -50,7 +50,8 @@ __device__ __forceinline__ void put_planes(const GemmArgs& a, int t, int n0, con
 // `vblock` is the index of the feature-tile group this workgroup handles (blockIdx.x); `smem` is its dynamic LDS.
 // KS: this workgroup covers only a slice of the inputs (a.k_len inputs from tile a.k_off_tiles on; a.x points at the
 // slice): the launch wrapper gives every slice its own output (EPI_PART), and the projection that reads the result adds the
-// slices up while staging.  PS > 0: that reader - its input is a.x plus PS partial results a.px[j] (fixed order), and the
+// slices up while staging.  PS > 0: that reader - its input is a.x plus PS partial results a.px[j] (fixed order; a producer with fewer leaves the
+// rest of the PS slots zero), and the
 // workgroup with index 0 also writes the sum to a.x_out (another buffer than a.x, which the other workgroups still read).
 // PRE: the input arrives as high / low bf16 planes with the consumer's norm gain already applied, written by the
 // kernel that produced it (a.xb_hi, a.xb_lo; a.ssq_part holds that kernel's per-wave sums of squares): staging is a

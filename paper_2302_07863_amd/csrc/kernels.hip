@@ -274,7 +274,8 @@ static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st
     const bool one_chunk = kk <= a.kc;
     const int per_wave = (tk + a.wk - 1) / a.wk;
     const int n4 = kk / 4, nthr = 64 * a.nwv;
-    if (a.T < 1 || a.T > 4 || !one_chunk || a.rw != 1 || a.mg_splits > 1 || a.xb_hi || a.nx_hi) return hipErrorInvalidValue;
+    if (a.T < 1 || a.T > 4 || !one_chunk || (a.rw != 1 && !(a.rw == 2 && a.epi == EPI_ACT)) || a.mg_splits > 1 || a.xb_hi || a.nx_hi)
+        return hipErrorInvalidValue;
     // the staging paths these kernels keep: one row with at most two pieces per thread; two to four rows with whole
     // wavefront-wide rows and at most four pieces per thread
     if (a.T == 1 ? n4 > 2 * nthr : ((n4 & 63) != 0 || a.T * n4 > 4 * nthr)) return hipErrorInvalidValue;
@@ -294,8 +295,36 @@ static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st
 #undef BILD_PK
         return hipGetLastError();
     }
-    if (a.pn != kPartSlices || !a.px || !a.x_out || a.x_out == a.x || a.ksplit > 1) return hipErrorInvalidValue;
+    if (a.pn < 1 || !a.px || !a.x_out || a.x_out == a.x || a.ksplit > 1) return hipErrorInvalidValue;
     const dim3 grid((unsigned)gemm_num_blocks(a));
+    if (a.epi == EPI_STORE || a.epi == EPI_ACT) {
+        // readers of one partial result per head (attention fused with its output projection): single-row passes
+        if (a.T != 1 || a.pn != kMaxHeadParts) return hipErrorInvalidValue;
+        constexpr int PH = kMaxHeadParts;
+#define BILD_RH(DTV)                                                                                              \
+    do {                                                                                                          \
+        if (a.epi == EPI_ACT && a.rw == 2) {                                                                      \
+            if (per_wave <= kShortBatch / 2) hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 1, PH>), grid, block, smem, st, a); \
+            else if (per_wave <= kShortBatch || (per_wave % 4 == 0 && per_wave % 6 != 0))                         \
+                hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 2, PH>), grid, block, smem, st, a);       \
+            else hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 0, PH>), grid, block, smem, st, a);      \
+        } else if (a.epi == EPI_ACT) {                                                                            \
+            if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 1, PH>), grid, block, smem, st, a); \
+            else if (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))          \
+                hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 2, PH>), grid, block, smem, st, a);       \
+            else hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 0, PH>), grid, block, smem, st, a);      \
+        } else {                                                                                                  \
+            if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 1, PH>), grid, block, smem, st, a); \
+            else if (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))          \
+                hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 2, PH>), grid, block, smem, st, a);     \
+            else hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 0, PH>), grid, block, smem, st, a);    \
+        }                                                                                                         \
+    } while (0)
+        if (dtype) BILD_RH(1); else BILD_RH(0);
+#undef BILD_RH
+        return hipGetLastError();
+    }
+    if (a.pn != kPartSlices) return hipErrorInvalidValue;
     constexpr int PSV = kPartSlices;
 #define BILD_RD1(DTV, EPIV, ROPEV) /* one row */                                                                 \
     do {                                                                                                          \

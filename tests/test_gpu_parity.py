@@ -130,6 +130,43 @@ def test_split_ffn_output_projection_on_small_widths(name, monkeypatch):
     assert a == b
 
 
+FUSED_TOYS = {
+    "f32-dh32": dict(d=128, heads=3, d_head=32, d_ff=128),
+    "bf16-dh32-geglu": dict(d=128, heads=4, d_head=32, d_ff=128, dtype=bi.DT_BF16, act=bi.ACT_GATED_GELU, tied=False),
+    "bf16-dh64-trunc": dict(d=128, heads=2, d_head=64, d_ff=128, dtype=bi.DT_BF16, truncate=True),
+    "bf16-dh64-rope-deconly": dict(d=128, heads=2, d_head=64, d_ff=128, dtype=bi.DT_BF16, act=bi.ACT_SWIGLU, pos=bi.POS_ROPE,
+                                   cross=False, tied=False),
+    "bf16-dh32-relative": dict(d=128, heads=4, d_head=32, d_ff=128, dtype=bi.DT_BF16, pos=bi.POS_RELATIVE),
+}
+
+
+@pytest.mark.parametrize("name", list(FUSED_TOYS))
+def test_single_row_passes_fuse_attention_with_its_output_projection(name, monkeypatch):
+    """Single-row passes of models up to 1024 wide with heads of 32 or 64 dims run attention and its output projection
+    as one kernel per (head, column group) and let the next projection add one partial result per head (configs 1-3
+    take this route at full size).  The same toys with the fusion switched off must give the same distributions up
+    to summation order, and both must meet the oracle."""
+    monkeypatch.setenv("BILD_KSPLIT_MIN_F", "64")
+    R = Rig(bi.toy_pair(**FUSED_TOYS[name]))
+    tol = parity.logit_tol(R.cfg)
+    for fb, rb, nm in ((0.5, 2.0, 10), (0.2, 0.7, 3)):
+        ref = oracle.bild_generate(R.req, fb, rb, nm, R.cfg.max_new, keep_logits=True)
+        st = R.state(R.cfg.max_new, nm)
+        st.encode(R.src)
+        worst = parity.teacher_forced(st, ref, R.n0, fb, rb, R.cfg)
+        print(name, worst)
+    rows = {}
+    for fuse in ("1", "0"):
+        monkeypatch.setenv("BILD_FUSE_ATTN", fuse)
+        st = R.state(R.cfg.max_new, 0)
+        st.debug_enable_logits(True)
+        toks = st.greedy(pkg.LARGE, R.src, 12)
+        rows[fuse] = (toks, st.debug_logits(pkg.LARGE, 0))
+    assert rows["1"][0] == rows["0"][0] and np.max(np.abs(rows["1"][1] - rows["0"][1])) <= tol
+    st = R.state(R.cfg.max_new, 10)
+    assert st.generate(R.src, 0.5, 2.0, R.cfg.max_new) == st.generate(R.src, 0.5, 2.0, R.cfg.max_new)
+
+
 @pytest.mark.parametrize("name", list(TOY_VARIANTS))
 def test_toy_free_running_generate(name):
     R = rig(name)
