@@ -155,6 +155,7 @@ def roofline_leg(c, fb, rb, stats):
 
     uncovered(pkg.SMALL, 1)
     g_s = st.bench_gemm(pkg.SMALL, 1, 50)
+    stages = {"small": st.pass_stages()}
     launches = small_steps * g_s["launches"]
     nbytes = small_steps * g_s["bytes"]
     ms = small_steps * g_s["ms_per_pass"]
@@ -162,6 +163,7 @@ def roofline_leg(c, fb, rb, stats):
     for rows, count in sorted(hist.items()):
         uncovered(pkg.LARGE, rows)
         g = st.bench_gemm(pkg.LARGE, rows, 20)
+        stages[f"large_{rows}"] = st.pass_stages()
         launches += count * g["launches"]
         nbytes += count * g["bytes"]
         ms += count * g["ms_per_pass"]
@@ -177,6 +179,7 @@ def roofline_leg(c, fb, rb, stats):
                 traffic=None if traffic is None else int(traffic),
                 launches_per_step=launches, mean_launch_us=round(ms / launches * 1e3, 3),
                 mean_bytes_per_launch=int(nbytes / launches),
+                stages_per_pass=stages,
                 rocprofv3_mean_us=rocprof_us,
                 frac_at_rocprofv3_mean=None if rocprof_us is None else round(nbytes / launches / rocprof_us / 1e3 / HBM_PEAK_GBS, 4),
                 small_pass=dict(passes=small_steps, launches=g_s["launches"],
@@ -377,13 +380,18 @@ def main() -> int:
     # stage count x the cost of a launch that does nothing.
     launch_us = st.probe_launch(2000)
 
-    def stages(shape):
-        return 1 + shape.n_dec * (8 if shape.cross else 5) + 2     # embed, layer pieces, LM head, policy
-
+    # kernel launches of a single-row pass as the library issues them (embedding, layer pieces, LM head, policy)
+    n_small = roofline["stages_per_pass"]["small"]
+    n_large = roofline["stages_per_pass"].get("large_1")
+    if n_large is None:
+        uncov = st.lengths()
+        st.kv_truncate(pkg.LARGE, min(uncov["len_large"], uncov["y_len"] - 1))
+        st.bench_gemm(pkg.LARGE, 1, 1)
+        n_large = st.pass_stages()
     stage_latency = dict(empty_launch_us=round(launch_us, 3),
-                         small_pass=dict(stages=stages(cfg.small), launch_floor_ms=round(stages(cfg.small) * launch_us * 1e-3, 4),
+                         small_pass=dict(stages=n_small, launch_floor_ms=round(n_small * launch_us * 1e-3, 4),
                                          measured_ms=passes["small_step"]["ms"]),
-                         large_pass=dict(stages=stages(cfg.large), launch_floor_ms=round(stages(cfg.large) * launch_us * 1e-3, 4),
+                         large_pass=dict(stages=n_large, launch_floor_ms=round(n_large * launch_us * 1e-3, 4),
                                          measured_ms=passes["large_step"]["ms"]))
     log(f"[bench] stage latency {stage_latency}")
 

@@ -55,6 +55,9 @@ int bild_probe_stream(bild_state* s, int groups, int kib_per_group, int reps, fl
 /* GEMM launches ISSUED by the host since the last reset and the algorithmic weight bytes they stream
  * (replays of captured graphs are not counted: meaningful when graph replay is disabled). */
 int bild_gemm_tally(bild_state* s, int64_t* launches, int64_t* bytes, int reset);
+/* Kernel launches (dependent stages) of the pass the host issued last - the one bild_bench_gemm issues to count its
+ * GEMM launches counts here too; replays of captured graphs do not change it. */
+int bild_pass_stages(bild_state* s, int32_t* stages);
 int bild_profile_begin(bild_state* s, int max_records);
 int bild_profile_end(bild_state* s, bild_profile* out);
 

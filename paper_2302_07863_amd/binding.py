@@ -82,6 +82,7 @@ _SIGS = {
     "bild_bench_gemm": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int64),
                                   C.POINTER(C.c_int64)]),
     "bild_gemm_tally": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_int]),
+    "bild_pass_stages": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32)]),
     "bild_probe_stream": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float)]),
     "bild_probe_launch": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_float)]),
     "bild_debug_tiled_bytes": (C.c_int64, [C.c_int, C.c_int, C.c_int]),
@@ -310,6 +311,11 @@ class State:
         ms, n, b = C.c_float(), C.c_int64(), C.c_int64()
         _check(lib().bild_bench_gemm(self.h, which, rows, reps, C.byref(ms), C.byref(n), C.byref(b)), "bild_bench_gemm")
         return dict(ms_per_pass=ms.value, launches=n.value, bytes=b.value)
+
+    def pass_stages(self) -> int:
+        n = C.c_int32()
+        _check(lib().bild_pass_stages(self.h, C.byref(n)), "bild_pass_stages")
+        return n.value
 
     def gemm_tally(self, reset: bool = False) -> dict:
         n, b = C.c_int64(), C.c_int64()

@@ -115,6 +115,12 @@ extern "C" int bild_bench_gemm(bild_state* s, int which, int rows, int reps, flo
     return BILD_OK;
 }
 
+extern "C" int bild_pass_stages(bild_state* s, int32_t* stages) {
+    if (!s || !stages) return BILD_EINVAL;
+    *stages = s->stage_count;
+    return BILD_OK;
+}
+
 extern "C" int bild_gemm_tally(bild_state* s, int64_t* launches, int64_t* bytes, int reset) {
     if (!s || !launches || !bytes) return BILD_EINVAL;
     *launches = s->gemm_count;

@@ -536,6 +536,7 @@ GemmArgs gemm_base(const bild_model* m, const TMat& W, const float* x, int ldx, 
 
 int launch_gemm_profiled(bild_state* s, const bild_model* m, const GemmArgs& g) {
     s->gemm_count += 1;
+    s->stage_count += 1;
     s->gemm_bytes += (int64_t)g.W.n * g.W.k * m->esz();
     if (!s->prof_on) {
         HIPC(launch_gemm(g, m->cfg.dtype, s->stream));
@@ -578,6 +579,7 @@ int emit_attention(bild_state* s, const ModelState& M, AttnArgs& a, int nkeys, i
     a.nw = pick_attn_waves(dt, a.d_head, std::min(a.T, kMaxRows), nkeys, a.splits);
     a.defer_merge = a.splits > 1 && defer;
     if (a.defer_merge) *deferred = a.splits;
+    s->stage_count += (a.splits > 1 && !a.defer_merge) ? 2 : 1;  // (the merge kernel is a stage of its own)
     if (!s->gemm_only) HIPC(launch_attention(a, dt, s->stream));
     return BILD_OK;
 }
@@ -673,6 +675,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
         a.proj_stride = (int64_t)kMaxRows * d;
         a.cgroups = cg;
         a.d_model = d;
+        s->stage_count += 1;
         if (!s->gemm_only && launch_attention_proj(a, dt, s->stream) != hipSuccess) return BILD_EHIP;
         pending = kMaxHeadParts;
         pend_buf = M.pxh;
@@ -682,6 +685,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
         e.nx_hi = xb_hi; e.nx_lo = xb_lo; e.nx_gain = m->dec[layer0].ln1; e.nx_ssq = M.ssq;
         xb_parts = kEmbedSsqParts;
     }
+    s->stage_count += 1;  // embedding or the trunk's rows
     if (!s->gemm_only) {
         if (above_trunk) {
             RowCopyArgs rc;
@@ -830,6 +834,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
             if (h_planes) after_out(g2); else xb_parts = 0;
         }
     }
+    if (trunk > 0 && w == 0) s->stage_count += 1;
     if (trunk > 0 && w == 0 && !s->gemm_only) {  // remember what the trunk produced for these positions
         RowCopyArgs rc;
         std::memset((void*)&rc, 0, sizeof(rc));
@@ -859,6 +864,7 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
     const bild_model_config& c = m->cfg;
     const int d = c.d_model, dt = c.dtype;
     const int* len_ptr = &s->ctl->len[w];
+    s->stage_count = 0;
     int xb_parts = 0;  // > 0: the final hidden state also sits in M.xb as bf16 planes (times the final norm's gain)
     float* xfin = M.x;  // the residual stream after the last layer ...
     bool parts = false; // ... to which the partial results in M.px are still to be added (split FFN output projection)
@@ -921,6 +927,7 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
     } else {
         f.mode = 3;
     }
+    s->stage_count += 1;
     if (!s->gemm_only) HIPC(launch_finish(f, s->stream));
     return BILD_OK;
 }

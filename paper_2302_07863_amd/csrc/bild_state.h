@@ -104,6 +104,7 @@ struct bild_state {
     int pre_min_rows = 0;         // > 0 (experiments): row count from which a bf16 pass hands activations on as bf16 planes
     bool gemm_only = false;       // measurement: a pass launches only its weight-streaming GEMMs
     int64_t gemm_count = 0, gemm_bytes = 0;  // tallied while a pass is being issued
+    int stage_count = 0;          // kernel launches of the pass issued last (counted also where a measurement skips the launch)
     std::map<std::array<int, 6>, hipGraphExec_t> graphs;  // captured passes by (model, rows, lm rows, mode, key bucket, debug)
     float top_p = 0.f;         // > 0: sampling variant, tokens are drawn from the nucleus
     float* u_dev[2] = {nullptr, nullptr};  // uniform number per sequence position, per model

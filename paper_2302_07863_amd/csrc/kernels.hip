@@ -940,6 +940,13 @@ __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs a) {
     finish_body<false>(a, lds);
 }
 
+// Reviews of several rows: sixteen waves, so that the rows' partial statistics are merged side by side (a wave takes
+// rows w, w + 16, ...: one trip to memory per row it has).
+__global__ __launch_bounds__(1024) void finish_wide_kernel(const FinishArgs a) {
+    __shared__ __attribute__((aligned(16))) char lds[kFinishLds];
+    finish_body<false>(a, lds);
+}
+
 __global__ __launch_bounds__(1024) void finish_sample_kernel(const FinishArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[kFinishLds + 16 + kDrawLds];
     finish_body<true>(a, lds);
@@ -965,7 +972,8 @@ hipError_t launch_finish(const FinishArgs& a, hipStream_t st) {
         hipLaunchKernelGGL(finish_sample_kernel, dim3(1), dim3(1024), 0, st, a);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(256), 0, st, a);
+    if (a.mode != 3 && a.T > 4) hipLaunchKernelGGL(finish_wide_kernel, dim3(1), dim3(1024), 0, st, a);
+    else hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 

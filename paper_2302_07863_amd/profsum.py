@@ -25,7 +25,7 @@ PROBE_BYTES = 1 << 30
 # four rows, input still in key-split attention partials); they are summed under one name.  The encoder / prefill
 # wrapper (row blocks, bild::gemm_rows_kernel) works in another regime and stays separate.
 _DECODE_GEMM = ("bild::gemm_kernel", "bild::gemm_row_kernel", "bild::gemm_few_kernel", "bild::gemm_merge_kernel",
-                "bild::gemm_pre_kernel", "bild::gemm_merge_nx_kernel")
+                "bild::gemm_pre_kernel", "bild::gemm_merge_nx_kernel", "bild::gemm_part_row_kernel", "bild::gemm_part_few_kernel")
 
 
 def _group(name: str) -> str:
