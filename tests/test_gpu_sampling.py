@@ -152,6 +152,60 @@ def test_sampling_t5_full_size():
     print("t5 sampled free-running", free_running(toks, stats, ref, R.n0, cfg.alpha_fb, cfg.alpha_rb, _margin(cfg)), flush=True)
 
 
+@pytest.mark.timeout(900)
+def test_sampling_mt5_full_size():
+    """Config 3 at full size with nucleus sampling: rows of 250 112 logits, which the drawing workgroup re-reads in
+    every sweep of its threshold search (they no longer fit its registers); 24 new tokens keep the oracle affordable.
+
+    Two checks per step.  (1) The draw itself, free of the models' arithmetic: the token the library commits must be
+    the oracle's draw function applied to the LIBRARY'S OWN logits of that row (read back), with the same uniform
+    number - only float32 against float64 inside the draw separates the two, so the margin is 1e-3.  (2) The
+    trajectory against the oracle's, with the bf16 draw margin (logits of magnitude 20 that differ by up to 1.5e-2
+    move a cumulative mass by up to 4e-2 relative): each excused step is checked to be marginal on the oracle's side."""
+    from dataclasses import replace
+    from oracle import sampling
+    cfg = replace(bi.mt5_pair(), max_new=24)
+    R = Rig(cfg)
+    n = R.n0 + cfg.max_new + 1
+    us, ul = _uniforms(cfg, n)
+    smp = oracle.Sampler(TOP_P, us, ul)
+    fb, rb = cfg.alpha_fb, cfg.alpha_rb
+    ref = oracle.bild_generate(R.req, fb, rb, cfg.n_max, cfg.max_new, sampler=smp)
+    st = R.state(cfg.max_new, cfg.n_max)
+    st.set_sampling(TOP_P, us, ul)
+    st.debug_enable_logits(True)
+    st.encode(R.src)
+    y, ds = list(st.sequence()), R.n0
+    excused = own_marginal = 0
+    for rec in ref.trace:
+        if rec["kind"] == "small":
+            pos = len(y)
+            tok, flag, _ = st.small_step(fb)
+            z = st.debug_logits(pkg.SMALL, 0).astype(np.float64)
+            own, dm = sampling.draw(z, TOP_P, float(us[pos]))
+            assert tok == own or dm < parity.MARGIN, ("small draw", pos, tok, own, dm)
+            own_marginal += int(tok != own)
+            if not rec["fallback"]:
+                y.append(rec["tok"])
+            good = bool(flag) == rec["fallback"] and tok == rec["tok"]
+        else:
+            out, r, _ = st.large_verify(rb)
+            z = st.debug_logits(pkg.LARGE, r).astype(np.float64)
+            own, dm = sampling.draw(z, TOP_P, float(ul[ds + r]))
+            assert out[-1] == own or dm < parity.MARGIN, ("large draw", ds + r, out[-1], own, dm)
+            own_marginal += int(out[-1] != own)
+            y = y[:ds + rec["r"]] + [rec["tok"]]
+            good = r == rec["r"] and out[-1] == rec["tok"]
+            ds = len(y)
+        if not good:
+            assert _marginal(rec, fb, rb, _margin(cfg)), ({k: v for k, v in rec.items() if k != "z"},)
+            excused += 1
+            st.force_tokens(R.n0, y[R.n0:], ds)
+    print("mt5 sampled: steps", len(ref.trace), "excused against the oracle", excused, "own-logit draws off", own_marginal,
+          ref.stats, flush=True)
+    assert st.sequence() == y and own_marginal <= 1 and excused <= len(ref.trace) // 4 and len(set(ref.tokens)) > 4
+
+
 def test_sampling_vocabulary_beyond_the_register_cache():
     """A vocabulary of 40 000 ids (more than 32 768: a row no longer stays in the registers of the 1024 threads
     that draw, so every radix sweep re-reads it) on a narrow model the oracle finishes in seconds; fp32 and bf16."""
