@@ -20,6 +20,7 @@ UNITS = [
     ("gemm_pre.hip", "gemm_pre.o", []),
     ("gemm_dense.hip", "gemm_dense.o", []),
     ("attention.hip", "attention.o", []),
+    ("policy.hip", "policy.o", []),
     ("bild_api.hip", "bild_api.o", []),
     ("head_stats.hip", "head_stats.o", []),
     ("bench_api.hip", "bench_api.o", []),

@@ -316,6 +316,7 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         if (const char* pm = std::getenv("BILD_PRE_MIN_ROWS")) s->pre_min_rows = std::atoi(pm);  // experiments; > 32 turns the planes off
         if (const char* fa = std::getenv("BILD_FUSE_ATTN")) s->fuse_attn = fa[0] != '0';      // experiments / tests
         if (const char* fk = std::getenv("BILD_FUSE_MAX_KV")) s->fuse_max_kv = std::atoi(fk);
+        if (const char* dw = std::getenv("BILD_DRAW_ONE_WG")) s->draw_spread = dw[0] == '0';
         if (const char* km = std::getenv("BILD_KSPLIT_MIN_F")) s->ksplit_min_f = std::atoi(km);  // tests: small widths; 0 turns the split off
     }
     for (int w = 0; w < 2; ++w) {
@@ -927,8 +928,12 @@ int decoder_pass(bild_state* s, int w, int T, int lm_rows, int mode, int key_hin
     } else {
         f.mode = 3;
     }
-    s->stage_count += 1;
-    if (!s->gemm_only) HIPC(launch_finish(f, s->stream));
+    // sampling variant under the threshold rule: the draw runs spread over the chip (seven launches instead of one)
+    const bool spread = f.top_p > 0.f && f.mode <= 2 && f.accept_mode == 0 && s->draw_spread && s->draw_ws &&
+                        c.vocab <= kDrawSliceIds * kDrawMaxSlices;
+    s->stage_count += spread ? kFinishDrawStages : 1;
+    if (spread) f.dws = s->draw_ws;
+    if (!s->gemm_only) HIPC(spread ? launch_finish_draw(f, s->stream) : launch_finish(f, s->stream));
     return BILD_OK;
 }
 
@@ -1392,6 +1397,12 @@ extern "C" int bild_set_sampling(bild_state* s, float top_p, const float* u_smal
             if (rc) return rc;
         }
         HIPC(hipMemcpy(s->u_dev[w], us[w], sizeof(float) * (size_t)s->max_len, hipMemcpyHostToDevice));
+    }
+    if (!s->draw_ws) {
+        rc = dev_alloc(s->allocs, (void**)&s->draw_ws, sizeof(DrawWs));
+        if (rc) return rc;
+        HIPC(hipMemset(s->draw_ws, 0, sizeof(DrawWs)));
+        drop_graphs();  // (none can have been captured with a draw yet; kept for safety)
     }
     if (s->top_p != top_p) drop_graphs();
     s->top_p = top_p;

@@ -222,6 +222,23 @@ struct FinishArgs {
     const float* u_acc;   // uniform number per sequence position for the acceptance test
     float* s_ring;        // [kMaxRows][vocab] the small model's logits of each pending draft, by draft index
     float4* s_draw;       // [sequence capacity] (max logit, nucleus threshold key, nucleus mass, -) of the small model's row
+    // nucleus draw spread over the chip (launch_finish_draw): its workspace
+    struct DrawWs* dws;
+};
+
+// Workspace of the nucleus draw that is spread over many workgroups (policy.hip).  Probability masses are integers
+// there: exp(z - max) in units of 2^-40, so sums do not depend on the order of their terms and atomics stay reproducible.
+constexpr int kDrawSliceIds = 1024;   // ids per workgroup of a sweep
+constexpr int kDrawMaxSlices = 1024;  // vocabularies of up to 1 048 576 ids
+struct DrawWs {
+    int row, pos;                     // row of the pass the token is drawn from, sequence position it will take
+    float m;                          // that row's largest logit
+    uint32_t key;                     // nucleus threshold: members have float_key(z) >= key
+    unsigned long long mass;          // mass of the nucleus
+    unsigned long long pad;
+    StatPart merged[kMaxRows];        // merged LM-head statistics of the pass (one "partial" per row for the commit)
+    unsigned long long hist[4][256];  // mass per value of key byte 3 (most significant) .. 0 among the keys still in play
+    unsigned long long slice[kDrawMaxSlices];  // members' mass per slice of kDrawSliceIds ids
 };
 
 size_t gemm_lds_bytes(const GemmArgs& a, int dtype);
@@ -246,6 +263,9 @@ hipError_t launch_embed(const EmbedArgs& a, int dtype, hipStream_t st);
 // table[pos][k] = sin / cos of pos * 10000^(-2 floor(k/2) / d) (k even / odd), evaluated in double precision as embed_kernel does
 hipError_t launch_pe_table(float* table, int positions, int d, hipStream_t st);
 hipError_t launch_finish(const FinishArgs& a, hipStream_t st);
+// sampling variant with the threshold rule: the same result as launch_finish, the draw spread over the chip (seven launches)
+hipError_t launch_finish_draw(const FinishArgs& a, hipStream_t st);
+constexpr int kFinishDrawStages = 7;
 hipError_t launch_row_copy(const RowCopyArgs& a, hipStream_t st);
 hipError_t kernels_init();  // one-time function attributes; call before any stream capture
 hipError_t attention_init();  // (attention.hip; called by kernels_init)

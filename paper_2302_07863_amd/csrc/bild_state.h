@@ -108,6 +108,8 @@ struct bild_state {
     std::map<std::array<int, 6>, hipGraphExec_t> graphs;  // captured passes by (model, rows, lm rows, mode, key bucket, debug)
     float top_p = 0.f;         // > 0: sampling variant, tokens are drawn from the nucleus
     float* u_dev[2] = {nullptr, nullptr};  // uniform number per sequence position, per model
+    bild::DrawWs* draw_ws = nullptr; // workspace of the draw that is spread over the chip
+    bool draw_spread = true;   // false (BILD_DRAW_ONE_WG=1, tests): every draw by the single workgroup of the policy kernel
     int accept_mode = 0;       // 1: the review uses the rejection-sampling rule (needs top_p > 0)
     float* u_acc = nullptr;    // uniform number per sequence position for that rule
     float* s_ring = nullptr;   // [kMaxRows][vocab] the small model's logits of the pending drafts

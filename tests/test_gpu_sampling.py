@@ -73,9 +73,13 @@ def free_running(tokens, stats, ref, n0, fb, rb, margin):
     return parity.compare_generation(tokens, stats, ref, fb, rb, draw_margin=margin)["exact"]
 
 
+@pytest.mark.parametrize("route", ["spread", "one-workgroup"])
 @pytest.mark.parametrize("name", ["f32-relu-tied", "f32-geglu-untied", "f32-rope-swiglu-deconly", "f32-wide",
                                   "bf16-relu-tied"])
-def test_sampling_toy_parity(name):
+def test_sampling_toy_parity(name, route, monkeypatch):
+    """Both routes of the draw: spread over the chip (integer masses, one workgroup per 1024 ids; the default) and the
+    policy kernel's own single workgroup (BILD_DRAW_ONE_WG=1, read when a state is created)."""
+    monkeypatch.setenv("BILD_DRAW_ONE_WG", "0" if route == "spread" else "1")
     R = Rig(bi.toy_pair(**TOY_VARIANTS[name]))
     cfg = R.cfg
     n = R.n0 + cfg.max_new + 1
@@ -206,9 +210,12 @@ def test_sampling_mt5_full_size():
     assert st.sequence() == y and own_marginal <= 1 and excused <= len(ref.trace) // 4 and len(set(ref.tokens)) > 4
 
 
-def test_sampling_vocabulary_beyond_the_register_cache():
-    """A vocabulary of 40 000 ids (more than 32 768: a row no longer stays in the registers of the 1024 threads
-    that draw, so every radix sweep re-reads it) on a narrow model the oracle finishes in seconds; fp32 and bf16."""
+@pytest.mark.parametrize("route", ["spread", "one-workgroup"])
+def test_sampling_vocabulary_beyond_the_register_cache(route, monkeypatch):
+    """A vocabulary of 40 000 ids on a narrow model the oracle finishes in seconds; fp32 and bf16.  Spread route: 40
+    slices, the last one ragged.  Single workgroup: more than 32 768 ids, so a row no longer stays in the registers of
+    the 1024 threads that draw and every radix sweep re-reads it."""
+    monkeypatch.setenv("BILD_DRAW_ONE_WG", "0" if route == "spread" else "1")
     for dtype in (bi.DT_F32, bi.DT_BF16):
         cfg = bi.toy_pair(dtype=dtype, vocab=40000, d=64, heads=2, d_head=16, d_ff=96, max_new=16, tie_shift=4099,
                           logit_scale=24.0)
