@@ -80,7 +80,7 @@ def setup(workload: str, shared_trunk: bool = False, top_p: float = 0.0):
     st.encode(src)
     encode_ms = (time.perf_counter() - t0) * 1e3
     return SimpleNamespace(cfg=cfg, ws=ws, wl=wl, src=src, pair=pair, st=st, n0=n0, sampler_u=sampler_u,
-                           encode_ms=encode_ms, pkg=pkg, bi=bi)
+                           encode_ms=encode_ms, pkg=pkg, bi=bi, top_p=top_p)
 
 
 def time_generation(c, fb, rb, steps, warmup):
@@ -119,6 +119,46 @@ def time_passes(c, spread: bool, rows_review: int = 11):
                                 single_p90_ms=round(singles[90], 4))
         log(f"[bench] {c.cfg.name} {name}: {passes[name]}")
     return passes
+
+
+def concurrent_leg(c, fb, rb, streams: int, reps: int, want_tokens):
+    """Several independent requests at once, each a state of its own on a stream of its own, driven by one host thread
+    each (the library's calls are blocking per request; ctypes releases the interpreter lock while they run).  Batch 1
+    per request, as in the headline metric: this leg shows how much of the chip one request leaves idle."""
+    import threading
+    pkg, cfg = c.pkg, c.cfg
+    states = [pkg.State(c.pair, len(c.src), c.n0 + cfg.max_new + 2, cfg.n_max) for _ in range(streams)]
+    for st in states:
+        if c.sampler_u:
+            st.set_sampling(c.top_p, *c.sampler_u)
+        st.encode(c.src)
+        st.generate(None, fb, rb, cfg.max_new)  # captures the graphs of this state
+    results = [None] * streams
+    barrier = threading.Barrier(streams + 1)
+
+    def worker(i):
+        st = states[i]
+        barrier.wait()
+        for _ in range(reps):
+            st.seq_truncate(c.n0)
+            results[i] = st.generate(None, fb, rb, cfg.max_new)[0]
+        barrier.wait()
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(streams)]
+    for t in threads:
+        t.start()
+    barrier.wait()
+    t0 = time.perf_counter()
+    barrier.wait()
+    dt = time.perf_counter() - t0
+    for t in threads:
+        t.join()
+    same = all(r == want_tokens for r in results)
+    for st in states:
+        st.close()
+    n_tok = len(want_tokens)
+    return dict(streams=streams, tokens_per_s=round(streams * reps * n_tok / dt, 1),
+                ms_per_generation=round(dt / reps * 1e3, 3), same_tokens_as_single_stream=same)
 
 
 def review_histogram(c, fb, rb):
@@ -303,6 +343,10 @@ def main() -> int:
     ap.add_argument("--probe-stream", action="store_true",
                     help="no benchmark: print how fast 1..256 workgroups stream private regions of 32 KiB..1 MiB "
                          "(the per-compute-unit bandwidth the launch shapes are built around)")
+    ap.add_argument("--concurrent", default="2",
+                    help="comma-separated counts of independent requests run at once, each on a stream of its own (an extra "
+                         "figure beside the batch-1 headline; more than two only scale with GPU_MAX_HW_QUEUES above the "
+                         "box's default of 4)")
     ap.add_argument("--alpha-fb", type=float, default=None)
     ap.add_argument("--alpha-rb", type=float, default=None)
     args = ap.parse_args()
@@ -395,6 +439,13 @@ def main() -> int:
                                          measured_ms=passes["large_step"]["ms"]))
     log(f"[bench] stage latency {stage_latency}")
 
+    # several independent requests at once (one state and one stream each): what the chip delivers when it is not left
+    # waiting for one request's chain of dependent stages
+    concurrent = None
+    if not args.no_extra:
+        concurrent = {f"x{n}": concurrent_leg(c, fb, rb, n, max(2, args.steps // 4), toks) for n in [int(v) for v in args.concurrent.split(",") if v]}
+        log(f"[bench] concurrent requests {concurrent}")
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(c, fb, rb, args.top_p, toks)
@@ -431,6 +482,9 @@ def main() -> int:
         # per request, the paper's "end-to-end latency per example": encode (or prompt prefill) + generation
         "end_to_end_tokens_per_s": round(n_tok / (c.encode_ms * 1e-3 + dt / args.steps), 2),
         "passes": passes,
+        # not the headline metric (that is one request at batch 1): aggregate tokens/s of 2 and 3 independent requests
+        # running at once on streams of their own
+        "concurrent_requests": concurrent,
     }
 
     # The bandwidth target is stated on the T5-large AND the mT5-large shapes: the default run also times the passes

@@ -137,6 +137,10 @@ FUSED_TOYS = {
     "bf16-dh64-rope-deconly": dict(d=128, heads=2, d_head=64, d_ff=128, dtype=bi.DT_BF16, act=bi.ACT_SWIGLU, pos=bi.POS_ROPE,
                                    cross=False, tied=False),
     "bf16-dh32-relative": dict(d=128, heads=4, d_head=32, d_ff=128, dtype=bi.DT_BF16, pos=bi.POS_RELATIVE),
+    # sources long enough that a head's cross-attention K/V exceed what one workgroup takes (key splits, merged by the
+    # output projection) while the self-attention cache stays short (fused with its output projection)
+    "bf16-dh64-long-source": dict(d=128, heads=2, d_head=64, d_ff=128, dtype=bi.DT_BF16, n_src=200),
+    "f32-dh32-long-source": dict(d=128, heads=3, d_head=32, d_ff=128, n_src=200),
 }
 
 
@@ -313,6 +317,33 @@ def test_kv_truncate_recomputes_identically():
     st.large_verify(INF)
     b2 = np.stack([st.debug_logits(pkg.LARGE, i) for i in range(7)])
     assert np.array_equal(a, b2)
+
+
+def test_concurrent_requests_on_streams_of_their_own():
+    """Independent requests may run at once: one state each (a stream of its own), one host thread each, weights shared
+    through the pair.  Every request must produce exactly what it produces alone (config 1 and a bf16 toy)."""
+    import threading
+    for R in (Rig(bi.tiny_pair()), rig("bf16-trunc-geglu")):
+        cfg = R.cfg
+        alone = R.state(cfg.max_new, cfg.n_max).generate(R.src, cfg.alpha_fb, cfg.alpha_rb, cfg.max_new)
+        ref = oracle.bild_generate(R.req, cfg.alpha_fb, cfg.alpha_rb, cfg.n_max, cfg.max_new)
+        parity.compare_generation(alone[0], alone[1], ref, cfg.alpha_fb, cfg.alpha_rb)
+        states = [R.state(cfg.max_new, cfg.n_max) for _ in range(4)]
+        got = [[] for _ in states]
+        start = threading.Barrier(len(states))
+
+        def work(i):
+            start.wait()
+            for _ in range(5):
+                got[i].append(states[i].generate(R.src, cfg.alpha_fb, cfg.alpha_rb, cfg.max_new))
+
+        threads = [threading.Thread(target=work, args=(i,)) for i in range(len(states))]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join(timeout=120)
+        assert all(not t.is_alive() for t in threads)
+        assert all(g == alone for per in got for g in per)
 
 
 def test_tiny_config_full_parity():
