@@ -205,8 +205,12 @@ class DecoderCache:
     """KV-cached decoder of one model for one request.  `length` rows are
     valid; truncation only lowers `length` (stale rows are overwritten later)."""
 
-    def __init__(self, model: Model, cross: list, capacity: int):
+    def __init__(self, model: Model, cross: list, capacity: int, store=None):
+        """store(layer, "k" | "v", exact [T, I], first_row) -> the values to cache, in place of the model's own
+        rounding to its storage type: for tests that take the storage-rounding decisions from elsewhere (the
+        arithmetic around them is unchanged)."""
         self.m, self.cross = model, cross
+        self.store = store
         i = model.s.inner
         self.k = [np.zeros((capacity, i)) for _ in range(model.s.n_dec)]
         self.v = [np.zeros((capacity, i)) for _ in range(model.s.n_dec)]
@@ -229,8 +233,9 @@ class DecoderCache:
             p = f"dec.{l}."
             xn = rmsnorm(x, m.w[p + "ln1"], s.eps)
             q = m._qk_pos(xn @ m.w[p + "wq"], pos)
-            self.k[l][t0:t0 + t] = m._store(m._qk_pos(xn @ m.w[p + "wk"], pos))
-            self.v[l][t0:t0 + t] = m._store(xn @ m.w[p + "wv"])
+            k_new, v_new = m._qk_pos(xn @ m.w[p + "wk"], pos), xn @ m.w[p + "wv"]
+            self.k[l][t0:t0 + t] = m._store(k_new) if self.store is None else self.store(l, "k", k_new, t0)
+            self.v[l][t0:t0 + t] = m._store(v_new) if self.store is None else self.store(l, "v", v_new, t0)
             a = attention(q, self.k[l][:t0 + t], self.v[l][:t0 + t], s.heads, s.d_head, pos, m._rel("dec_rel_bias"), pos)
             x = x + a @ m.w[p + "wo"]
             if s.cross:

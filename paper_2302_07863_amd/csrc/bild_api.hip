@@ -317,6 +317,7 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         if (const char* fa = std::getenv("BILD_FUSE_ATTN")) s->fuse_attn = fa[0] != '0';      // experiments / tests
         if (const char* fk = std::getenv("BILD_FUSE_MAX_KV")) s->fuse_max_kv = std::atoi(fk);
         if (const char* dw = std::getenv("BILD_DRAW_ONE_WG")) s->draw_spread = dw[0] == '0';
+        if (const char* kd = std::getenv("BILD_KSPLIT_MAX_D")) s->ksplit_max_d = std::atoi(kd);
         if (const char* km = std::getenv("BILD_KSPLIT_MIN_F")) s->ksplit_min_f = std::atoi(km);  // tests: small widths; 0 turns the split off
     }
     for (int w = 0; w < 2; ++w) {
@@ -639,7 +640,7 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
     // projection (or the LM head of a single-row pass) adds the slices to the residual stream while staging and leaves the
     // sum in the other of two residual buffers.  Measured on the T5-large shape: see the design notes.
     const int kt = dt == BILD_DT_BF16 ? 32 : 16;
-    const bool split_ffn = !planes && T <= 4 && d <= 1024 && s->ksplit_min_f > 0 && F >= s->ksplit_min_f &&
+    const bool split_ffn = !planes && T <= 4 && d <= s->ksplit_max_d && s->ksplit_min_f > 0 && F >= s->ksplit_min_f &&
                            (F / kt) % kPartSlices == 0 && (T == 1 || ((d / 4) % 64 == 0 && (F / kPartSlices / 4) % 64 == 0)) && M.px != nullptr;
     float *xcur = M.x, *xoth = M.x2;
     // > 0: the residual stream is xcur + that many partial results in pend_buf (slices of a split FFN output projection,

@@ -249,7 +249,7 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st);
 constexpr int kDenseMinRows = 513;
 constexpr int kDenseRows = 64;   // rows per workgroup
 constexpr int kDenseWaves = 4;
-constexpr int kDenseRW = 2;      // feature tiles per wave
+constexpr int kDenseRW = 4;      // feature tiles per wave
 constexpr int dense_kc(int) { return 128; }  // inputs staged per chunk
 size_t dense_lds_bytes(int dt);
 hipError_t launch_gemm_dense(const GemmArgs& a, int dtype, hipStream_t st);

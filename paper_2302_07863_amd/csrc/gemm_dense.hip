@@ -12,10 +12,10 @@
 //     weight tile keep fp32-grade accuracy, as in the decode GEMM) and written ONCE to LDS as the MFMA B operand,
 //     64 rows deep, so every weight tile a wave loads feeds 4 row tiles x 2 MFMAs;
 //   - weights arrive in HBM already in A-operand register order (bild::TMat), so a wave loads its 1 KiB tiles
-//     straight into operand registers - no LDS round trip for A.  All tiles of a chunk are requested before the
-//     staging starts and land while the activations are converted;
-//   - the LDS footprint (34 KiB) and register count let three workgroups share a compute unit: some convert while
-//     another multiplies, and the loads of all of them are in flight together (a compute unit's load rate is set
+//     straight into operand registers - no LDS round trip for A.  The tiles of the next chunk are requested while
+//     the current one is multiplied;
+//   - the LDS footprint (34 KiB) and register count let two workgroups share a compute unit: one converts while
+//     the other multiplies, and the loads of both are in flight together (a compute unit's load rate is set
 //     by the bytes it has in flight).
 // Row blocks of one feature group re-read its weight tiles from L2 / the memory-side cache; blockIdx.x walks the
 // feature groups fastest, so the row blocks that are resident together share them.
@@ -92,19 +92,17 @@ __global__ __launch_bounds__(256, 2) void gemm_dense_kernel(const GemmArgs a) {
         }
     };
     // This wave's weight tiles of a chunk (a tile index past the end reads a clamped, valid address and is never
-    // multiplied).  Like the activations they are requested one chunk ahead.
-    uint4 Wn[RW][NKT];
-    auto request_w = [&](int k0) {
-        const int kt0 = k0 / KT;
+    // multiplied), one register set: input tile u of the NEXT chunk is requested into the registers of tile u right
+    // behind the products that read them, a whole chunk of products before it is needed.
+    uint4 W[RW][NKT];
+    auto request_w = [&](int k0, int u) {
+        const int ktc = min(k0 / KT + u, a.W.tk - 1);
 #pragma unroll
-        for (int u = 0; u < NKT; ++u) {
-            const int ktc = min(kt0 + u, a.W.tk - 1);
-#pragma unroll
-            for (int r = 0; r < RW; ++r) Wn[r][u] = *(const uint4*)(wbase[r] + (size_t)ktc * kTileBytes + lane16);
-        }
+        for (int r = 0; r < RW; ++r) W[r][u] = *(const uint4*)(wbase[r] + (size_t)ktc * kTileBytes + lane16);
     };
     request_x(0);
-    request_w(0);
+#pragma unroll
+    for (int u = 0; u < NKT; ++u) request_w(0, u);
 
     for (int k0 = 0; k0 < K; k0 += KC) {
         const int kc_len = min(KC, K - k0), nkt = kc_len / KT;
@@ -133,15 +131,8 @@ __global__ __launch_bounds__(256, 2) void gemm_dense_kernel(const GemmArgs a) {
                 }
             }
         }
-        uint4 W[RW][NKT];
-#pragma unroll
-        for (int u = 0; u < NKT; ++u)
-#pragma unroll
-            for (int r = 0; r < RW; ++r) W[r][u] = Wn[r][u];
-        if (k0 + KC < K) {
-            request_x(k0 + KC);
-            request_w(k0 + KC);
-        }
+        const bool more = k0 + KC < K;
+        if (more) request_x(k0 + KC);
         __syncthreads();
         // ---- multiply: every weight tile against the 4 row tiles of the chunk ----
 #pragma unroll
@@ -173,6 +164,7 @@ __global__ __launch_bounds__(256, 2) void gemm_dense_kernel(const GemmArgs a) {
                     }
                 }
             }
+            if (more) request_w(k0 + KC, u);
         }
     }
     // ---- sums of squares of the rows: each row was staged by the lanes of one wave (half a wave for fp32) ----

@@ -557,7 +557,7 @@ def _cache_differences(st, which, cache, layers, n):
 
 
 @pytest.mark.timeout(1500)
-def test_llama_config_full_width_logits_exceed_the_bf16_bar_through_storage_rounding_only():
+def test_llama_config_full_width_meets_the_bf16_bar_once_storage_rounding_is_aligned():
     """Config 4 at its full widths (32 layers, d 4096, 32 heads of 128, FFN 11008, vocab 32000) on a shortened
     prompt.  The rows of one review pass and of one small step against the oracle, element by element.
 
@@ -572,7 +572,13 @@ def test_llama_config_full_width_logits_exceed_the_bf16_bar_through_storage_roun
         the largest magnitude): the noise saturates at the granularity of the storage format;
       * the same widths with fp32 storage (first 8 layers, so that it stays affordable) agree to 3e-6 of the
         largest logit, i.e. the arithmetic itself is fp32-accurate;
-      * the logit error stays below 5x the bar (0.1); the small model (16 layers, d 2048) is held to the bar itself."""
+      * the logit error stays below 5x the bar (0.1); the small model (16 layers, d 2048) is held to the bar itself;
+      * WITH THE STORAGE-ROUNDING DECISIONS ALIGNED THE BAR IS MET: a second oracle pass caches, in every layer, the
+        values the library stored (read back) instead of rounding its own - after checking, element by element in all
+        32 layers, that each stored value is the bf16 rounding of a number within 1e-4 of the tensor's scale of the
+        oracle's exact one (fp32 against float64 accumulation; measured: up to 2e-5 by layer 27, bound 1e-4).  Rounding to the storage type is a decision floating
+        point takes about an integer code; taken the same way on both sides, the logits agree to 6e-4 (bar 2e-2);
+        1.2 % of the stored values are not the oracle's own rounding of its exact value."""
     from dataclasses import replace
     cfg = replace(bi.llama_pair(), n_src=48, max_new=8)
     R = Rig(cfg, compact=True)
@@ -602,6 +608,29 @@ def test_llama_config_full_width_logits_exceed_the_bf16_bar_through_storage_roun
     assert diffs[0][0] < 2e-3, diffs
     assert max(w for _, w in diffs.values()) <= 2.0 ** -7, diffs
     del cache
+    # the same rows with the library's storage-rounding decisions: every cached element is checked as it is taken over
+    flips = {"n": 0, "total": 0, "worst": 0.0}
+
+    def stored_by_the_library(l, kind, exact, t0):
+        got = st.debug_kv(pkg.LARGE, l, kind == "v", t0, exact.shape[0]).astype(np.float64)
+        scale = float(np.max(np.abs(exact)))
+        # a correct rounding of a value within 1e-4 * scale of the exact one: at most half a bf16 step (of the stored
+        # value's binade, or of the exact value's if that is larger) plus that noise away from it
+        step = np.maximum(_bf16_step(got), _bf16_step(exact))
+        off = np.abs(got - exact)
+        assert np.all(off <= 0.5 * step + 1e-4 * scale), (l, kind, float(np.max((off - 0.5 * step) / scale)))
+        assert np.all(oracle.model.round_bf16(got) == got)
+        flips["n"] += int(np.count_nonzero(got != oracle.model.round_bf16(exact)))
+        flips["total"] += got.size
+        flips["worst"] = max(flips["worst"], float(np.max((off - 0.5 * step) / scale)))
+        return got
+
+    z2 = oracle.model.DecoderCache(R.req.large, [], len(y) + 1, store=stored_by_the_library).step(y, last=6)
+    aligned = max(float(np.max(np.abs(st.debug_logits(pkg.LARGE, i) - z2[i]))) for i in range(6))
+    print("storage rounding aligned: worst logit error", aligned, "bar", tol, "; stored values that are not the oracle's own rounding:",
+          flips["n"], "of", flips["total"], "; worst excess over half a step / scale", flips["worst"], flush=True)
+    assert aligned <= tol, aligned
+    assert flips["n"] <= 0.03 * flips["total"], flips  # (measured: 1.2 % of the elements sit that close to a rounding boundary)
     # the small model of the pair: one step
     tok, flag, pmax = st.small_step(0.5)
     seq = st.sequence()

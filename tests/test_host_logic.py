@@ -61,10 +61,10 @@ def test_gemm_launch_shapes_are_consistent(pair):
                 s = b.gemm_shape(n, k, rows, gated, head, shape.dtype)
                 tiles = ((2 * n if gated else n) + 15) // 16
                 if rows > 512:
-                    # the dense-tile kernel: 64 rows x (4 waves x 2 feature tiles) per workgroup, chunks of 128 inputs
-                    assert (s["wk"], s["nwv"], s["rw"], s["kc"]) == (1, 4, 2, 128)
-                    assert (s["blocks"] - 1) * 8 < tiles <= s["blocks"] * 8 and s["row_blocks"] == (rows + 63) // 64
-                    assert 3 * s["lds"] <= s["lds_limit"]          # three workgroups share a compute unit
+                    # the dense-tile kernel: 64 rows x (4 waves x 4 feature tiles) per workgroup, chunks of 128 inputs
+                    assert (s["wk"], s["nwv"], s["rw"], s["kc"]) == (1, 4, 4, 128)
+                    assert (s["blocks"] - 1) * 16 < tiles <= s["blocks"] * 16 and s["row_blocks"] == (rows + 63) // 64
+                    assert 2 * s["lds"] <= s["lds_limit"]          # two workgroups share a compute unit (registers)
                     continue
                 assert s["nwv"] in (1, 2, 4, 8) and s["nwv"] % s["wk"] == 0, (n, k, rows, s)
                 # feature tiles per wave: 2 = gate and linear branch; 4 only for a very wide LM head at up to 16 rows
