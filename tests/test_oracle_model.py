@@ -355,6 +355,36 @@ def test_cached_and_block_passes_equal_the_definition(kw):
         assert np.allclose(again, m.logits_full(y2, cross)[4:], rtol=1e-12, atol=1e-12)
 
 
+def test_cache_store_hook_only_replaces_the_storage_rounding():
+    """`DecoderCache(store=...)` hands every new K / V block (exact values, layer, kind, first row) to the caller and
+    caches what comes back.  The model's own rounding supplied through the hook is the plain cache bit for bit; in a
+    bf16 model the identity hook is the fp32-storage forward (no rounding anywhere), which differs from the bf16 one."""
+    cfg = bi.toy_pair(dtype=bi.DT_BF16, pos=bi.POS_ROPE, cross=False, tied=False, act=bi.ACT_SWIGLU)
+    _, wl = bi.make_pair_weights(cfg)
+    m = om.Model(cfg.large, wl)
+    y = [int(t) for t in bi.make_tokens(cfg.large.vocab, 11, seed=3)]
+    c0 = om.DecoderCache(m, [], 16)
+    plain = np.concatenate([c0.step(y[:4]), c0.step(y[4:])])
+    seen = []
+
+    def own(l, kind, exact, t0):
+        seen.append((l, kind, exact.shape, t0))
+        return om.round_bf16(exact)
+
+    c = om.DecoderCache(m, [], 16, store=own)
+    hooked = np.concatenate([c.step(y[:4]), c.step(y[4:])])
+    assert np.array_equal(hooked, plain)
+    inner = cfg.large.inner
+    assert seen[:2] == [(0, "k", (4, inner), 0), (0, "v", (4, inner), 0)] and seen[-1] == (cfg.large.n_dec - 1, "v", (7, inner), 4)
+    assert len(seen) == 2 * 2 * cfg.large.n_dec
+    c1 = om.DecoderCache(m, [], 16, store=lambda l, kind, exact, t0: exact)
+    unrounded = np.concatenate([c1.step(y[:4]), c1.step(y[4:])])
+    from dataclasses import replace
+    c32 = om.DecoderCache(om.Model(replace(cfg.large, dtype=bi.DT_F32), wl), [], 16)
+    assert np.array_equal(unrounded, np.concatenate([c32.step(y[:4]), c32.step(y[4:])]))
+    assert np.max(np.abs(unrounded - plain)) > 1e-6
+
+
 def test_causality_and_encoder_bidirectionality():
     cfg = bi.toy_pair()
     _, wl = bi.make_pair_weights(cfg)
