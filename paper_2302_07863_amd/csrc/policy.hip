@@ -215,28 +215,61 @@ __device__ __forceinline__ int nucleus_draw(const float* __restrict__ z, int V, 
     return weighted_walk([&](int i) { const float zi = z[i]; return float_key(zi) >= K ? expf(zi - m) : 0.f; }, V, mass, u, ws);
 }
 
-// Merge of the LM-head partial statistics of the rows of a pass into (max, sum exp, argmax) per row, in LDS.  Rows are
-// dealt to the waves; a wave's lanes share the partials of its row (eight loads in flight per lane), so the rows of a
-// review merge side by side and a single row costs one round trip.  Ends with a barrier.
+// Merge of the LM-head partial statistics of the rows of a pass into (max, sum exp, argmax) per row, in LDS.  With at
+// least as many waves as rows, every row gets nwv / T waves, each merging a contiguous share of the row's partials
+// (lanes stride through it, eight loads in flight per lane), so that a single row with two thousand partials (250 112
+// ids) costs one trip to memory instead of four; the shares are then joined in a fixed order.  More rows than waves: the
+// rows are dealt to the waves.  Ends with a barrier.
 __device__ __forceinline__ void merge_partials(const FinishArgs& a, float* rm, float* rsum, int* ridx) {
+    __shared__ StatPart share[16];  // [row * wpr + share] (at most 16 waves)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwv = blockDim.x >> 6;
-    for (int t = wave; t < a.T; t += nwv) {
+    auto merge_range = [&](int t, int p_begin, int p_end) {
         Stat r = stat_neutral();
-        for (int p0 = lane; p0 < a.nparts; p0 += 64 * 8) {
+        for (int p0 = p_begin + lane; p0 < p_end; p0 += 64 * 8) {
             StatPart sp[8];
 #pragma unroll
             for (int k = 0; k < 8; ++k)
-                sp[k] = a.part[(size_t)min(p0 + k * 64, a.nparts - 1) * kMaxRows + a.row_off + t];
+                sp[k] = a.part[(size_t)min(p0 + k * 64, p_end - 1) * kMaxRows + a.row_off + t];
 #pragma unroll
             for (int k = 0; k < 8; ++k)
-                if (p0 + k * 64 < a.nparts) r = stat_merge(r, Stat{sp[k].m, sp[k].s, sp[k].idx});
+                if (p0 + k * 64 < p_end) r = stat_merge(r, Stat{sp[k].m, sp[k].s, sp[k].idx});
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) r = stat_merge(r, stat_shfl_xor(r, o));
-        if (lane == 0) {
-            rm[t] = r.m;
-            rsum[t] = r.s;
-            ridx[t] = r.idx;
+        return r;
+    };
+    if (a.T <= nwv) {
+        const int wpr = nwv / a.T;                      // waves per row
+        const int per = (a.nparts + wpr - 1) / wpr;     // partials per share
+        const int t = wave / wpr, c = wave - t * wpr;
+        if (t < a.T) {
+            const int p_begin = min(c * per, a.nparts), p_end = min(p_begin + per, a.nparts);
+            const Stat r = merge_range(t, p_begin, p_end);  // (an empty share stays neutral)
+            if (lane == 0) {
+                StatPart sp;
+                sp.m = r.m; sp.s = r.s; sp.idx = r.idx; sp.pad = 0;
+                share[wave] = sp;
+            }
+        }
+        __syncthreads();
+        if (tid < a.T) {
+            Stat r = stat_neutral();
+            for (int c2 = 0; c2 < wpr; ++c2) {
+                const StatPart sp = share[tid * wpr + c2];
+                r = stat_merge(r, Stat{sp.m, sp.s, sp.idx});
+            }
+            rm[tid] = r.m;
+            rsum[tid] = r.s;
+            ridx[tid] = r.idx;
+        }
+    } else {
+        for (int t = wave; t < a.T; t += nwv) {
+            const Stat r = merge_range(t, 0, a.nparts);
+            if (lane == 0) {
+                rm[t] = r.m;
+                rsum[t] = r.s;
+                ridx[t] = r.idx;
+            }
         }
     }
     __syncthreads();
@@ -717,7 +750,7 @@ hipError_t launch_finish_draw(const FinishArgs& a, hipStream_t st) {
         return hipErrorInvalidValue;
     const int ns = (a.vocab + kDrawSliceIds - 1) / kDrawSliceIds;
     if (ns > kDrawMaxSlices) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(draw_select_kernel, dim3(1), dim3(a.T > 4 ? 1024 : 256), 0, st, a);
+    hipLaunchKernelGGL(draw_select_kernel, dim3(1), dim3(a.T > 4 || a.nparts > 1024 ? 1024 : 256), 0, st, a);
     hipLaunchKernelGGL(draw_sweep_kernel<0>, dim3(ns), dim3(256), 0, st, a);
     hipLaunchKernelGGL(draw_sweep_kernel<1>, dim3(ns), dim3(256), 0, st, a);
     hipLaunchKernelGGL(draw_sweep_kernel<2>, dim3(ns), dim3(256), 0, st, a);
@@ -737,7 +770,7 @@ hipError_t launch_finish(const FinishArgs& a, hipStream_t st) {
         hipLaunchKernelGGL(finish_sample_kernel, dim3(1), dim3(1024), 0, st, a);
         return hipGetLastError();
     }
-    if (a.mode != 3 && a.T > 4) hipLaunchKernelGGL(finish_wide_kernel, dim3(1), dim3(1024), 0, st, a);
+    if (a.mode != 3 && (a.T > 4 || a.nparts > 1024)) hipLaunchKernelGGL(finish_wide_kernel, dim3(1), dim3(1024), 0, st, a);
     else hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(256), 0, st, a);
     return hipGetLastError();
 }
