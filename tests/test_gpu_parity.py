@@ -556,6 +556,18 @@ def _cache_differences(st, which, cache, layers, n):
     return out
 
 
+_llama = {}
+
+
+def llama_rig():
+    """Config 4 at its full widths and depth (weights of both models, the oracle's request on a shortened prompt, the
+    uploaded pair); built once for the two tests that use it and released by the second."""
+    if "rig" not in _llama:
+        from dataclasses import replace
+        _llama["rig"] = Rig(replace(bi.llama_pair(), n_src=48, max_new=8), compact=True)
+    return _llama["rig"]
+
+
 @pytest.mark.timeout(1500)
 def test_llama_config_full_width_meets_the_bf16_bar_once_storage_rounding_is_aligned():
     """Config 4 at its full widths (32 layers, d 4096, 32 heads of 128, FFN 11008, vocab 32000) on a shortened
@@ -580,8 +592,8 @@ def test_llama_config_full_width_meets_the_bf16_bar_once_storage_rounding_is_ali
         point takes about an integer code; taken the same way on both sides, the logits agree to 6e-4 (bar 2e-2);
         1.2 % of the stored values are not the oracle's own rounding of its exact value."""
     from dataclasses import replace
-    cfg = replace(bi.llama_pair(), n_src=48, max_new=8)
-    R = Rig(cfg, compact=True)
+    R = llama_rig()
+    cfg = R.cfg
     tol = parity.logit_tol(cfg)
     st = R.state(cfg.max_new + 8, cfg.n_max)
     st.encode(R.src)
@@ -661,6 +673,79 @@ def test_llama_config_full_width_meets_the_bf16_bar_once_storage_rounding_is_ali
     rel = max(float(np.max(np.abs(st32.debug_logits(pkg.LARGE, i) - z32[i]))) for i in range(6)) / float(np.max(np.abs(z32)))
     print("fp32 storage, 8 layers: logit error relative to the largest logit", rel, flush=True)
     assert rel <= 3e-6, rel
+
+
+@pytest.mark.timeout(900)
+def test_llama_config_full_size_in_the_launch_configuration_of_the_benchmark():
+    """Config 4 exactly as `bench.py --workload llama` runs it: prompt of 1024 Zipf ids (prefilled in one pass by the
+    dense-tile kernel), 256 new tokens, alpha_FB 0.5 / alpha_RB 2, n_max 10, every pass a replayed graph.  The oracle
+    cannot follow at this size (the shortened-prompt test above compares its rows element by element), so this test
+    holds the run to what is true at any size:
+      * the loop is the composition of the calls: the same request driven through bild_small_step / bild_large_verify
+        by Algorithm 1 written out here gives the same tokens and the same counters as bild_generate;
+      * alpha_FB = 0 without a cap is the small model's greedy output and never runs the large model; alpha_FB > 1 is the
+        large model's greedy output for any alpha_RB (the limiting cases of Sections 3.3 / 3.4);
+      * every accepted draft passed both tests: replaying the final sequence, each token produced by a small step has
+        max p_S >= alpha_FB there, and each reviewed draft that was kept has -ln p_L <= alpha_RB (read back from the review);
+      * the prompt's cache does not depend on how it was filled: cutting the large model's cache to 700 rows makes the
+        next pass recompute rows 700..1023 in row-block launches (fewer than 513 rows) instead of the dense-tile kernel, and the next token's
+        distribution stays within the storage-rounding noise measured above (0.1) with the same argmax;
+      * the same request twice gives the same bits."""
+    R = llama_rig()
+    cfg = bi.llama_pair()
+    src = bi.make_source(cfg)
+    n0, n = len(src), cfg.max_new
+    fb, rb = cfg.alpha_fb, cfg.alpha_rb
+    st = pkg.State(R.pair, n0, n0 + n + 2, cfg.n_max)
+    toks, stats = st.generate(src, fb, rb, n)
+    assert len(toks) == n and stats["n_generated"] == n and stats["large_calls"] > 0 and stats["rollbacks"] > 0
+    st.seq_truncate(n0)
+    assert st.generate(None, fb, rb, n) == (toks, stats)
+    # Algorithm 1 through the calls
+    st.seq_truncate(n0)
+    small_steps = large_calls = rollbacks = discarded = rows = 0
+    kept_pmax, kept_nll = [], []
+    while st.lengths()["y_len"] - n0 < n:
+        tok, flag, pmax = st.small_step(fb)
+        small_steps += 1
+        if not flag:
+            kept_pmax.append(pmax)
+            continue
+        before = st.lengths()
+        pending = before["y_len"] - before["draft_start"]
+        out, r, nll = st.large_verify(rb)
+        large_calls += 1
+        rows += pending + 1
+        rollbacks += int(r < pending)
+        discarded += pending - r
+        kept_nll.extend(float(v) for v in nll[:r])
+        assert all(float(v) <= rb for v in nll[:r]) and (r == pending or float(nll[r]) > rb)
+    assert st.sequence()[n0:n0 + n] == toks
+    assert (small_steps, large_calls, rows, rollbacks, discarded) == (
+        stats["small_steps"], stats["large_calls"], stats["rows_verified"], stats["rollbacks"], stats["tokens_discarded"])
+    assert min(kept_pmax) >= fb and len(kept_nll) > 0
+    # limiting cases
+    st0 = pkg.State(R.pair, n0, n0 + n + 2, 0)
+    small_greedy = st0.greedy(pkg.SMALL, src, 64)
+    t0, s0 = st0.generate(src, 0.0, rb, 64)
+    assert t0 == small_greedy and s0["large_calls"] == 0
+    large_greedy = st.greedy(pkg.LARGE, src, 48)
+    for rb_any in (-1.0, INF):
+        t1, s1 = st.generate(src, 2.0, rb_any, 48)
+        assert t1 == large_greedy and s1["rollbacks"] == 0 and s1["large_calls"] == 48
+    # the prompt's cache filled by the dense-tile kernel / recomputed in row blocks
+    st.encode(src)
+    st.debug_enable_logits(True)
+    st.large_verify(INF, draft=[])
+    za = st.debug_logits(pkg.LARGE, 0).copy()
+    st.force_tokens(n0, [], n0)
+    st.kv_truncate(pkg.LARGE, 700)
+    st.large_verify(INF, draft=[])
+    zb = st.debug_logits(pkg.LARGE, 0)
+    print("config 4 full size:", stats, "next-token logits, dense prefill against row-block recompute:",
+          float(np.max(np.abs(za - zb))), "of", float(np.max(np.abs(za))), flush=True)
+    assert int(np.argmax(za)) == int(np.argmax(zb)) and np.max(np.abs(za - zb)) <= 0.1
+    _llama.clear()
 
 
 @pytest.mark.timeout(1500)
