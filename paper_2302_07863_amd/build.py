@@ -28,6 +28,8 @@ UNITS = [
 ]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-pthread",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # leading scalar kernel parameters arrive in scalar registers at wave start (see BILD_GEMM_HOT_PARAMS)
+         "-mllvm", "-amdgpu-kernarg-preload-count=16",
          "-Wno-unused-result", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 

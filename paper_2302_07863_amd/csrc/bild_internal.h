@@ -133,6 +133,12 @@ struct GemmArgs {
     int kc;   // inputs staged in LDS per chunk
 };
 
+// The leading scalar arguments of the GEMM kernels (gemm_body.h, BILD_GEMM_HOT_PARAMS), from a filled GemmArgs.
+#define BILD_GEMM_HOT_TAIL(a) (a).px, (a).W.k, (a).W.tn, (a).W.tk, ((a).wk | ((a).nwv << 4) | ((a).T << 8)), (a).kc, (a).ldx
+#define BILD_GEMM_HOT(a) (a).W.w, (const void*)(a).x, (const void*)(a).gain, BILD_GEMM_HOT_TAIL(a)
+#define BILD_GEMM_HOT_PRE(a) (a).W.w, (const void*)(a).xb_hi, (const void*)(a).xb_lo, BILD_GEMM_HOT_TAIL(a)
+#define BILD_GEMM_HOT_MG(a) (a).W.w, (const void*)(a).mg_o, (const void*)(a).mg_ml, BILD_GEMM_HOT_TAIL(a)
+
 struct AttnArgs {
     const float* q;  // [T][I]
     const void* k;   // [capacity][I]

@@ -37,6 +37,36 @@ __host__ __device__ inline int gemm_tail_bytes(int nwv, int nacc) {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Hot arguments.  The kernels take their arguments as one structure, which the wavefronts fetch from memory when they
+// start: a round trip before the first address can be formed, and a second one where the compiler fetches a field
+// only in front of its first use.  The few values the first requests depend on - where the weights and the activations
+// are, how the workgroup is cut into waves - are therefore passed a second time as leading scalar parameters, which
+// gfx950 delivers in scalar registers at wave start (kernel-argument preload: the library is compiled with it
+// on); the structure behind them is read for everything else while those requests are on their way.
+//   h_w             weight tiles (W.w)
+//   h_x, h_g        activations and norm gain (x, gain) | input planes (xb_hi, xb_lo) | key-split partials (mg_o, mg_ml)
+//   h_px            partial results a reader adds (px; their stride is kMaxRows * ldx)
+//   h_k/h_tn/h_tk   W.k, W.tn, W.tk
+//   h_geom          wk | nwv << 4 | T << 8
+//   h_kc, h_ldx     kc, ldx
+#define BILD_GEMM_HOT_PARAMS                                                                                      \
+    const void* __restrict__ h_w, const void* __restrict__ h_x, const void* __restrict__ h_g,                     \
+        const float* __restrict__ h_px, const int h_k, const int h_tn, const int h_tk, const int h_geom, const int h_kc, \
+        const int h_ldx
+#define BILD_GEMM_HOT_NAMES h_w, h_x, h_g, h_px, h_k, h_tn, h_tk, h_geom, h_kc, h_ldx
+enum HotKind : int { HOT_X = 0, HOT_PRE = 1, HOT_MG = 2 };
+template <int KIND>
+__device__ __forceinline__ GemmArgs gemm_hot(const GemmArgs& a, BILD_GEMM_HOT_PARAMS) {
+    GemmArgs b = a;
+    b.W.w = h_w; b.W.k = h_k; b.W.tn = h_tn; b.W.tk = h_tk;
+    b.wk = h_geom & 15; b.nwv = (h_geom >> 4) & 15; b.T = h_geom >> 8;
+    b.kc = h_kc; b.ldx = h_ldx;
+    if (KIND == HOT_X) { b.x = (const float*)h_x; b.gain = (const float*)h_g; b.px = h_px; b.px_stride = (int64_t)kMaxRows * h_ldx; }
+    if (KIND == HOT_PRE) { b.xb_hi = (const uint16_t*)h_x; b.xb_lo = (const uint16_t*)h_g; }
+    if (KIND == HOT_MG) { b.mg_o = (const float*)h_x; b.mg_ml = (const float*)h_g; }
+    return b;
+}
+
 // Four consecutive features of row t, handed to the next projection as high and low bf16 parts.
 __device__ __forceinline__ void put_planes(const GemmArgs& a, int t, int n0, const float (&w)[4]) {
     uint32_t h01, l01, h23, l23;
@@ -63,7 +93,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
     // the wave index through readfirstlane: the compiler then knows that it - and every tile index, weight address and
     // range test derived from it - is the same in all lanes, and keeps them in scalar registers
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nthr = blockDim.x, NWV = nthr >> 6;
+    const int NWV = a.nwv, nthr = NWV << 6;  // (the launch has 64 * nwv threads; blockDim would be one more fetch)
     const int T = ONE ? 1 : a.T, K = KS ? a.k_len : a.W.k, KC = a.kc;
     const int WK = a.wk, WR = NWV / WK;
     const int wkid = wave % WK, wrid = wave / WK;

@@ -10,16 +10,18 @@ namespace bild {
 
 // Input in planes; residual and activation epilogues hand their output on in planes as well.
 template <int RW, int EPI, int ROPE, int NT, bool SHORT = false>
-__global__ __launch_bounds__(512) void gemm_pre_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(512) void gemm_pre_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    const GemmArgs a = gemm_hot<HOT_PRE>(a0, BILD_GEMM_HOT_NAMES);
     gemm_body<1, RW, EPI, ROPE, NT, gemm_batch(RW, false, NT), 0, false, !SHORT, 0, true,
               EPI == EPI_RESID || EPI == EPI_ACT>(a, (int)blockIdx.x, smem);
 }
 
 // Output projection whose input is still in key-split attention partials (fp32, merged while staging); output in planes.
 template <int SPLITS, bool SHORT = false>
-__global__ __launch_bounds__(512) void gemm_merge_nx_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(512) void gemm_merge_nx_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    const GemmArgs a = gemm_hot<HOT_MG>(a0, BILD_GEMM_HOT_NAMES);
     gemm_body<1, 1, EPI_RESID, 0, 1, gemm_batch(1, false), SPLITS, false, !SHORT, 0, false, true>(a, (int)blockIdx.x, smem);
 }
 
@@ -67,9 +69,9 @@ hipError_t launch_gemm_pre(const GemmArgs& a, hipStream_t st) {
             return hipErrorInvalidValue;
 #define BILD_MG(SH)                                                                              \
     do {                                                                                          \
-        if (sp == 2) hipLaunchKernelGGL((gemm_merge_nx_kernel<2, SH>), grid, block, smem, st, a); \
-        else if (sp == 4) hipLaunchKernelGGL((gemm_merge_nx_kernel<4, SH>), grid, block, smem, st, a); \
-        else hipLaunchKernelGGL((gemm_merge_nx_kernel<8, SH>), grid, block, smem, st, a);         \
+        if (sp == 2) hipLaunchKernelGGL((gemm_merge_nx_kernel<2, SH>), grid, block, smem, st, BILD_GEMM_HOT_MG(a), a); \
+        else if (sp == 4) hipLaunchKernelGGL((gemm_merge_nx_kernel<4, SH>), grid, block, smem, st, BILD_GEMM_HOT_MG(a), a); \
+        else hipLaunchKernelGGL((gemm_merge_nx_kernel<8, SH>), grid, block, smem, st, BILD_GEMM_HOT_MG(a), a);         \
     } while (0)
         if (sh) BILD_MG(true); else BILD_MG(false);
 #undef BILD_MG
@@ -81,9 +83,9 @@ hipError_t launch_gemm_pre(const GemmArgs& a, hipStream_t st) {
         return hipErrorInvalidValue;
 #define BILD_L(RWV, EPIV, ROPEV)                                                                      \
     do {                                                                                               \
-        if (a.T > 16) hipLaunchKernelGGL((gemm_pre_kernel<RWV, EPIV, ROPEV, 2>), grid, block, smem, st, a); \
-        else if (RWV == 1 && sh) hipLaunchKernelGGL((gemm_pre_kernel<1, EPIV, ROPEV, 1, true>), grid, block, smem, st, a); \
-        else hipLaunchKernelGGL((gemm_pre_kernel<RWV, EPIV, ROPEV, 1>), grid, block, smem, st, a);    \
+        if (a.T > 16) hipLaunchKernelGGL((gemm_pre_kernel<RWV, EPIV, ROPEV, 2>), grid, block, smem, st, BILD_GEMM_HOT_PRE(a), a); \
+        else if (RWV == 1 && sh) hipLaunchKernelGGL((gemm_pre_kernel<1, EPIV, ROPEV, 1, true>), grid, block, smem, st, BILD_GEMM_HOT_PRE(a), a); \
+        else hipLaunchKernelGGL((gemm_pre_kernel<RWV, EPIV, ROPEV, 1>), grid, block, smem, st, BILD_GEMM_HOT_PRE(a), a);    \
     } while (0)
     switch (a.epi) {
         case EPI_STORE: BILD_L(1, EPI_STORE, 0); break;
@@ -95,7 +97,7 @@ hipError_t launch_gemm_pre(const GemmArgs& a, hipStream_t st) {
             if (a.rw == 2) BILD_L(2, EPI_ACT, 0); else BILD_L(1, EPI_ACT, 0);
             break;
         case EPI_LMHEAD:
-            if (a.rw == 4 && a.T <= 16) hipLaunchKernelGGL((gemm_pre_kernel<4, EPI_LMHEAD, 0, 1>), grid, block, smem, st, a);
+            if (a.rw == 4 && a.T <= 16) hipLaunchKernelGGL((gemm_pre_kernel<4, EPI_LMHEAD, 0, 1>), grid, block, smem, st, BILD_GEMM_HOT_PRE(a), a);
             else if (a.rw != 1) return hipErrorInvalidValue;
             else BILD_L(1, EPI_LMHEAD, 0);
             break;

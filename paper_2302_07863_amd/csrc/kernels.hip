@@ -31,8 +31,9 @@ namespace bild {
 
 // SHORT: no wave has more than one batch of tiles - the second weight buffer does not exist (see gemm_row_kernel).
 template <int DT, int RW, int EPI, int ROPE, int NT, bool SHORT = false>
-__global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(512) void gemm_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    const GemmArgs a = gemm_hot<HOT_X>(a0, BILD_GEMM_HOT_NAMES);
     gemm_body<DT, RW, EPI, ROPE, NT, gemm_batch(RW, false, NT), 0, false, !SHORT>(a, (int)blockIdx.x, smem);
 }
 
@@ -47,8 +48,9 @@ __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
 //   0: more        - batches of 12 (more bytes in flight for the bandwidth-bound shapes)
 constexpr int kShortBatch = 8;
 template <int DT, int RW, int EPI, int ROPE, int VAR = 0, int PS = 0>
-__global__ __launch_bounds__(512) void gemm_row_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(512) void gemm_row_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    const GemmArgs a = gemm_hot<HOT_X>(a0, BILD_GEMM_HOT_NAMES);
     gemm_body<DT, RW, EPI, ROPE, 1, VAR ? kShortBatch / RW : gemm_batch(RW, true), 0, true, VAR != 1, 0, false, false, PS>(
         a, (int)blockIdx.x, smem);
 }
@@ -58,8 +60,9 @@ __global__ __launch_bounds__(512) void gemm_row_kernel(const GemmArgs a) {
 // counts costs about 0.7 us more per projection (measured: one row through gemm_kernel 1018 us per T5-large pass,
 // through gemm_row_kernel 911 us), which is code size and register pressure, not work.
 template <int DT, int RW, int EPI, int ROPE, bool SHORT, int PS = 0>
-__global__ __launch_bounds__(512) void gemm_few_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(512) void gemm_few_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    const GemmArgs a = gemm_hot<HOT_X>(a0, BILD_GEMM_HOT_NAMES);
     gemm_body<DT, RW, EPI, ROPE, 1, gemm_batch(RW, false, 1), 0, false, !SHORT, 4, false, false, PS>(a, (int)blockIdx.x, smem);
 }
 
@@ -77,23 +80,24 @@ __device__ __forceinline__ GemmArgs part_slice(const GemmArgs& a, int kt) {
     return b;
 }
 template <int DT, int VAR>
-__global__ __launch_bounds__(512) void gemm_part_row_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(512) void gemm_part_row_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const GemmArgs b = part_slice(a, DT ? 32 : 16);
+    const GemmArgs b = part_slice(gemm_hot<HOT_X>(a0, BILD_GEMM_HOT_NAMES), DT ? 32 : 16);
     gemm_body<DT, 1, EPI_PART, 0, 1, VAR ? kShortBatch : gemm_batch(1, true), 0, true, VAR != 1, 0, false, false, 0, true>(
         b, (int)blockIdx.x, smem);
 }
 template <int DT, bool SHORT>
-__global__ __launch_bounds__(512) void gemm_part_few_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(512) void gemm_part_few_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const GemmArgs b = part_slice(a, DT ? 32 : 16);
+    const GemmArgs b = part_slice(gemm_hot<HOT_X>(a0, BILD_GEMM_HOT_NAMES), DT ? 32 : 16);
     gemm_body<DT, 1, EPI_PART, 0, 1, gemm_batch(1, false, 1), 0, false, !SHORT, 4, false, false, 0, true>(b, (int)blockIdx.x, smem);
 }
 
 // Output projection whose input is still in key-split attention partials (merged while staging).
 template <int DT, int SPLITS, bool SHORT = false>
-__global__ __launch_bounds__(512) void gemm_merge_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(512) void gemm_merge_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    const GemmArgs a = gemm_hot<HOT_MG>(a0, BILD_GEMM_HOT_NAMES);
     gemm_body<DT, 1, EPI_RESID, 0, 1, gemm_batch(1, false), SPLITS, false, !SHORT>(a, (int)blockIdx.x, smem);
 }
 
@@ -103,8 +107,9 @@ __global__ __launch_bounds__(512) void gemm_merge_kernel(const GemmArgs a) {
 // is a GFLOP or two: too little to fill the dense-tile kernel's 64-row tiles on 256 compute units (measured on 512 rows
 // of 1024..4096-wide projections: 12..40 us per launch there, 12..25 us here); longer passes go to gemm_dense.hip.
 template <int DT, int RW, int EPI, int ROPE>
-__global__ __launch_bounds__(512) void gemm_rows_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(512) void gemm_rows_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    const GemmArgs a = gemm_hot<HOT_X>(a0, BILD_GEMM_HOT_NAMES);
     GemmArgs b = a;
     const int r0 = (int)blockIdx.y * kMaxRows;
     b.T = min(kMaxRows, a.T - r0);
@@ -283,17 +288,18 @@ static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st
         const dim3 grid((unsigned)gemm_num_blocks(a), (unsigned)a.ksplit);
 #define BILD_PK(DTV)                                                                                              \
     do {                                                                                                          \
-        if (a.T == 1 && per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 1>), grid, block, smem, st, a); \
-        else if (a.T == 1 && per_wave <= 2 * kShortBatch) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 2>), grid, block, smem, st, a); \
-        else if (a.T == 1) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 0>), grid, block, smem, st, a);          \
-        else if (per_wave <= gemm_batch(1, false)) hipLaunchKernelGGL((gemm_part_few_kernel<DTV, true>), grid, block, smem, st, a); \
-        else hipLaunchKernelGGL((gemm_part_few_kernel<DTV, false>), grid, block, smem, st, a);                    \
+        if (a.T == 1 && per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+        else if (a.T == 1 && per_wave <= 2 * kShortBatch) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+        else if (a.T == 1) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 0>), grid, block, smem, st, BILD_GEMM_HOT(a), a);          \
+        else if (per_wave <= gemm_batch(1, false)) hipLaunchKernelGGL((gemm_part_few_kernel<DTV, true>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+        else hipLaunchKernelGGL((gemm_part_few_kernel<DTV, false>), grid, block, smem, st, BILD_GEMM_HOT(a), a);                    \
     } while (0)
         if (dtype) BILD_PK(1); else BILD_PK(0);
 #undef BILD_PK
         return hipGetLastError();
     }
     if (a.pn < 1 || !a.px || !a.x_out || a.x_out == a.x || a.ksplit > 1) return hipErrorInvalidValue;
+    if (a.px_stride != (int64_t)kMaxRows * a.ldx) return hipErrorInvalidValue;  // the kernels derive it from ldx (gemm_hot)
     const dim3 grid((unsigned)gemm_num_blocks(a));
     if (a.epi == EPI_STORE || a.epi == EPI_ACT) {
         // readers of one partial result per head (attention fused with its output projection): single-row passes
@@ -302,20 +308,20 @@ static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st
 #define BILD_RH(DTV)                                                                                              \
     do {                                                                                                          \
         if (a.epi == EPI_ACT && a.rw == 2) {                                                                      \
-            if (per_wave <= kShortBatch / 2) hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 1, PH>), grid, block, smem, st, a); \
+            if (per_wave <= kShortBatch / 2) hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 1, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             else if (per_wave <= kShortBatch || (per_wave % 4 == 0 && per_wave % 6 != 0))                         \
-                hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 2, PH>), grid, block, smem, st, a);       \
-            else hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 0, PH>), grid, block, smem, st, a);      \
+                hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 2, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a);       \
+            else hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 0, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a);      \
         } else if (a.epi == EPI_ACT) {                                                                            \
-            if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 1, PH>), grid, block, smem, st, a); \
+            if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 1, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             else if (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))          \
-                hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 2, PH>), grid, block, smem, st, a);       \
-            else hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 0, PH>), grid, block, smem, st, a);      \
+                hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 2, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a);       \
+            else hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 0, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a);      \
         } else {                                                                                                  \
-            if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 1, PH>), grid, block, smem, st, a); \
+            if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 1, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             else if (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))          \
-                hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 2, PH>), grid, block, smem, st, a);     \
-            else hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 0, PH>), grid, block, smem, st, a);    \
+                hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 2, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a);     \
+            else hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 0, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a);    \
         }                                                                                                         \
     } while (0)
         if (dtype) BILD_RH(1); else BILD_RH(0);
@@ -327,18 +333,18 @@ static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st
 #define BILD_RD1(DTV, EPIV, ROPEV) /* one row */                                                                 \
     do {                                                                                                          \
         if (per_wave <= kShortBatch)                                                                              \
-            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 1, PSV>), grid, block, smem, st, a);         \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 1, PSV>), grid, block, smem, st, BILD_GEMM_HOT(a), a);         \
         else if (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))              \
-            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 2, PSV>), grid, block, smem, st, a);         \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 2, PSV>), grid, block, smem, st, BILD_GEMM_HOT(a), a);         \
         else                                                                                                      \
-            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 0, PSV>), grid, block, smem, st, a);         \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 0, PSV>), grid, block, smem, st, BILD_GEMM_HOT(a), a);         \
     } while (0)
 #define BILD_RDF(DTV, ROPEV) /* two to four rows: the first projection of a layer only */                         \
     do {                                                                                                          \
         if (per_wave <= gemm_batch(1, false))                                                                     \
-            hipLaunchKernelGGL((gemm_few_kernel<DTV, 1, EPI_QKV, ROPEV, true, PSV>), grid, block, smem, st, a);   \
+            hipLaunchKernelGGL((gemm_few_kernel<DTV, 1, EPI_QKV, ROPEV, true, PSV>), grid, block, smem, st, BILD_GEMM_HOT(a), a);   \
         else                                                                                                      \
-            hipLaunchKernelGGL((gemm_few_kernel<DTV, 1, EPI_QKV, ROPEV, false, PSV>), grid, block, smem, st, a);  \
+            hipLaunchKernelGGL((gemm_few_kernel<DTV, 1, EPI_QKV, ROPEV, false, PSV>), grid, block, smem, st, BILD_GEMM_HOT(a), a);  \
     } while (0)
 #define BILD_RDD(DTV)                                                                                             \
     if (a.epi == EPI_QKV && a.T == 1) { if (a.rope) BILD_RD1(DTV, EPI_QKV, 1); else BILD_RD1(DTV, EPI_QKV, 0); }  \
@@ -370,9 +376,9 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
         const dim3 grid1((unsigned)gemm_num_blocks(a)), block1(64 * a.nwv);
 #define BILD_MG(DTV, SH)                                                                       \
     do {                                                                                        \
-        if (sp == 2) hipLaunchKernelGGL((gemm_merge_kernel<DTV, 2, SH>), grid1, block1, smem, st, a); \
-        else if (sp == 4) hipLaunchKernelGGL((gemm_merge_kernel<DTV, 4, SH>), grid1, block1, smem, st, a); \
-        else hipLaunchKernelGGL((gemm_merge_kernel<DTV, 8, SH>), grid1, block1, smem, st, a);   \
+        if (sp == 2) hipLaunchKernelGGL((gemm_merge_kernel<DTV, 2, SH>), grid1, block1, smem, st, BILD_GEMM_HOT_MG(a), a); \
+        else if (sp == 4) hipLaunchKernelGGL((gemm_merge_kernel<DTV, 4, SH>), grid1, block1, smem, st, BILD_GEMM_HOT_MG(a), a); \
+        else hipLaunchKernelGGL((gemm_merge_kernel<DTV, 8, SH>), grid1, block1, smem, st, BILD_GEMM_HOT_MG(a), a);   \
     } while (0)
         // (one batch of tiles per wave at most: no second weight buffer, see gemm_row_kernel)
         const bool sh = a.W.k <= a.kc && (a.W.tk + a.wk - 1) / a.wk <= gemm_batch(1, false);
@@ -391,27 +397,27 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
 #define BILD_L(DTV, RWV, EPIV, ROPEV)                                                              \
     do {                                                                                            \
         if (row_blocks > 1)                                                                         \
-            hipLaunchKernelGGL((gemm_rows_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a); \
+            hipLaunchKernelGGL((gemm_rows_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T == 1 && RWV == 2 && one_chunk && per_wave <= kShortBatch / 2)                  \
-            hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 1>), grid, block, smem, st, a); \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T == 1 && RWV == 2 && one_chunk && (per_wave <= kShortBatch || (per_wave % 4 == 0 && per_wave % 6 != 0))) \
-            hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 2>), grid, block, smem, st, a); \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T == 1 && RWV == 1 && one_chunk && per_wave <= kShortBatch)                      \
-            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 1>), grid, block, smem, st, a); \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T == 1 && RWV == 1 && one_chunk && (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))) \
-            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 2>), grid, block, smem, st, a); \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T == 1)                                                                          \
-            hipLaunchKernelGGL((gemm_row_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, a); \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T > 16)                                                                          \
-            hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 2>), grid, block, smem, st, a);  \
+            hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a);  \
         else if (RWV == 1 && few_ok && per_wave <= gemm_batch(1, false))                            \
-            hipLaunchKernelGGL((gemm_few_kernel<DTV, 1, EPIV, ROPEV, true>), grid, block, smem, st, a); \
+            hipLaunchKernelGGL((gemm_few_kernel<DTV, 1, EPIV, ROPEV, true>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (RWV == 1 && few_ok)                                                                \
-            hipLaunchKernelGGL((gemm_few_kernel<DTV, 1, EPIV, ROPEV, false>), grid, block, smem, st, a); \
+            hipLaunchKernelGGL((gemm_few_kernel<DTV, 1, EPIV, ROPEV, false>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (RWV == 1 && one_chunk && per_wave <= gemm_batch(1, false))                         \
-            hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPIV, ROPEV, 1, true>), grid, block, smem, st, a); \
+            hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPIV, ROPEV, 1, true>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else                                                                                        \
-            hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 1>), grid, block, smem, st, a);  \
+            hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a);  \
     } while (0)
 #define BILD_D(DTV)                                                              \
     switch (a.epi) {                                                             \
@@ -425,19 +431,19 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
             break;                                                               \
         case EPI_LMHEAD:                                                         \
             if (a.rw == 4 && a.T == 1)                                           \
-                hipLaunchKernelGGL((gemm_row_kernel<DTV, 4, EPI_LMHEAD, 0>), grid, block, smem, st, a); \
+                hipLaunchKernelGGL((gemm_row_kernel<DTV, 4, EPI_LMHEAD, 0>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             else if (a.rw == 4 && a.T <= 16)                                     \
-                hipLaunchKernelGGL((gemm_kernel<DTV, 4, EPI_LMHEAD, 0, 1>), grid, block, smem, st, a); \
+                hipLaunchKernelGGL((gemm_kernel<DTV, 4, EPI_LMHEAD, 0, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             else if (a.rw != 1)                                                  \
                 return hipErrorInvalidValue;                                     \
             else if (a.T == 1 && one_chunk && per_wave <= 32 && per_wave % kShortBatch == 0) /* batches of 8 fit exactly */ \
-                hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0, 2>), grid, block, smem, st, a); \
+                hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             else if (a.T == 1)                                                   \
-                hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0>), grid, block, smem, st, a); \
+                hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             else if (a.T > 16)                                                   \
-                hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPI_LMHEAD, 0, 2>), grid, block, smem, st, a); \
+                hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPI_LMHEAD, 0, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             else                                                                 \
-                hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPI_LMHEAD, 0, 1>), grid, block, smem, st, a); \
+                hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPI_LMHEAD, 0, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             break;                                                               \
         default: return hipErrorInvalidValue;                                    \
     }
