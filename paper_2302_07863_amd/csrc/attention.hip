@@ -22,16 +22,40 @@ constexpr int kAttnLdsLimit = 160 * 1024;
 // Cache rows beyond the valid length are finite (zero-filled at allocation, or stale
 // values of discarded tokens), so a probability of exactly 0 removes them.
 // =====================================================================================
+// Hot arguments (see BILD_GEMM_HOT_PARAMS in gemm_body.h): what the first requests of an attention workgroup depend on,
+// passed a second time as leading scalar parameters that arrive in scalar registers at wave start.
+//   h_q, h_k, h_v, h_len   q, k, v, len_ptr
+//   h_T                    T
+//   h_p0                   heads | nw << 8 | causal << 12 | d_head << 13 | splits << 22
+//   h_idim, h_vcap, h_badd, h_nkf   i_dim, vcap, base_add, nkeys_fixed
+#define BILD_ATTN_HOT_PARAMS                                                                                   \
+    const float* __restrict__ h_q, const void* __restrict__ h_k, const void* __restrict__ h_v,                 \
+        const int* __restrict__ h_len, const int h_T, const int h_p0, const int h_idim, const int h_vcap,      \
+        const int h_badd, const int h_nkf
+#define BILD_ATTN_HOT_NAMES h_q, h_k, h_v, h_len, h_T, h_p0, h_idim, h_vcap, h_badd, h_nkf
+__device__ __forceinline__ AttnArgs attn_hot(const AttnArgs& a, BILD_ATTN_HOT_PARAMS) {
+    AttnArgs b = a;
+    b.q = h_q; b.k = h_k; b.v = h_v; b.len_ptr = h_len; b.T = h_T;
+    b.heads = h_p0 & 255; b.nw = (h_p0 >> 8) & 15; b.causal = (h_p0 >> 12) & 1; b.d_head = (h_p0 >> 13) & 511; b.splits = h_p0 >> 22;
+    b.i_dim = h_idim; b.vcap = h_vcap; b.base_add = h_badd; b.nkeys_fixed = h_nkf;
+    return b;
+}
+#define BILD_ATTN_HOT(a)                                                                                             \
+    (a).q, (a).k, (a).v, (a).len_ptr, (a).T,                                                                          \
+        ((a).heads | ((a).nw << 8) | (((a).causal ? 1 : 0) << 12) | ((a).d_head << 13) | ((a).splits << 22)), (a).i_dim, \
+        (a).vcap, (a).base_add, (a).nkeys_fixed
+
 // FUSE: the finished output of the head stays in LDS (in q's place, in q's operand layout) for the output projection
 // that the same workgroup runs next (attn_proj_kernel); nothing is written to memory here.
-template <int DT, int DH32, bool REL = false, bool FUSE = false>
-__device__ __forceinline__ void attn_body(const AttnArgs& a, const int vblock, char* smem) {
+// `h`, `sp`: head and key split of this workgroup; `extra` runs right behind the first K/V request (attn_proj_kernel
+// requests its weight tiles there).
+template <int DT, int DH32, bool REL = false, bool FUSE = false, class Extra>
+__device__ __forceinline__ void attn_body(const AttnArgs& a, const int h, const int sp, char* smem, Extra&& extra) {
     constexpr int DHP = DH32 * 32;   // head dim padded to the k-step of the first product
     constexpr int DT16 = DH32 * 2;   // 16-wide output tiles along the head dim
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
-    const int nthr = blockDim.x, nw = nthr >> 6;
+    const int nw = a.nw, nthr = nw << 6;  // (the launch has 64 * nw threads)
     const int T = a.T, dh = a.d_head, I = a.i_dim;
-    const int h = vblock % a.heads, sp = vblock / a.heads;
     const int NT = (T + 15) >> 4;
     const int tok_l = lane & 15, g = lane >> 4;
     const int qstride = DT ? (DHP + 8) * 2 : (DHP + 4) * 4;
@@ -251,6 +275,7 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int vblock, c
             ranges();
             blk = blk_begin + wave;
             load_kv(K0, V0, blk < blk_end ? blk : 0);
+            extra();
         });
         if constexpr (REL) {
 #pragma unroll
@@ -337,22 +362,24 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int vblock, c
 }
 
 template <int DT, int DH32, bool REL = false>
-__global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(512) void attn_kernel(BILD_ATTN_HOT_PARAMS, const AttnArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    attn_body<DT, DH32, REL>(a, (int)(blockIdx.x + blockIdx.y * gridDim.x), smem);
+    const AttnArgs a = attn_hot(a0, BILD_ATTN_HOT_NAMES);
+    attn_body<DT, DH32, REL>(a, (int)blockIdx.x, (int)blockIdx.y, smem, [] {});  // grid: heads x key splits
 }
 
 // More than kMaxRows query rows: blockIdx.z picks the block of rows (key splits are not combined with it).
 template <int DT, int DH32, bool REL = false>
-__global__ __launch_bounds__(512) void attn_rows_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(512) void attn_rows_kernel(BILD_ATTN_HOT_PARAMS, const AttnArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    const AttnArgs a = attn_hot(a0, BILD_ATTN_HOT_NAMES);
     AttnArgs b = a;
     const int r0 = (int)blockIdx.z * kMaxRows;
     b.T = min(kMaxRows, a.T - r0);
     b.q = a.q + (size_t)r0 * a.i_dim;
     b.out = a.out + (size_t)r0 * a.i_dim;
     b.base_add = a.base_add + r0;
-    attn_body<DT, DH32, REL>(b, (int)blockIdx.x, smem);
+    attn_body<DT, DH32, REL>(b, (int)blockIdx.x, 0, smem, [] {});
 }
 
 // Attention of one head followed by that head's share of the output projection, for single-row passes of the narrow
@@ -362,22 +389,25 @@ __global__ __launch_bounds__(512) void attn_rows_kernel(const AttnArgs a) {
 // (proj_out[h][t][n]); the projection that reads the residual stream next adds them up while staging, so the
 // output projection costs no launch of its own.  The weight tiles are requested at entry and arrive during the attention.
 template <int DT, int DH32, bool REL = false>
-__global__ __launch_bounds__(512) void attn_proj_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(512) void attn_proj_kernel(BILD_ATTN_HOT_PARAMS, const AttnArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    const AttnArgs a = attn_hot(a0, BILD_ATTN_HOT_NAMES);
     constexpr int KT = DT ? 32 : 16, DHP = DH32 * 32, KH = DHP / KT, MAXN = DT ? 4 : 2;  // (fp32: four input tiles per head already)
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = (int)blockDim.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = a.nw;
     const int h = (int)blockIdx.x, c = (int)blockIdx.y;
-    const int npc = (a.wo.tn + (int)gridDim.y - 1) / (int)gridDim.y;  // feature tiles per column group
+    const int npc = (a.wo.tn + a.cgroups - 1) / a.cgroups;            // feature tiles per column group (grid: heads x cgroups)
     const int khr = a.d_head / KT, kt0 = h * khr;                      // this head's input tiles (d_head is a multiple of KT)
     uint4 Wt[MAXN][KH];
+    auto request_w = [&]() {
 #pragma unroll
-    for (int i = 0; i < MAXN; ++i) {
-        const int n = min(c * npc + wave + i * nw, a.wo.tn - 1);
+        for (int i = 0; i < MAXN; ++i) {
+            const int n = min(c * npc + wave + i * nw, a.wo.tn - 1);
 #pragma unroll
-        for (int j = 0; j < KH; ++j)
-            Wt[i][j] = *(const uint4*)((const char*)a.wo.w + ((size_t)n * a.wo.tk + kt0 + min(j, khr - 1)) * kTileBytes + lane * 16);
-    }
-    attn_body<DT, DH32, REL, true>(a, h, smem);
+            for (int j = 0; j < KH; ++j)
+                Wt[i][j] = *(const uint4*)((const char*)a.wo.w + ((size_t)n * a.wo.tk + kt0 + min(j, khr - 1)) * kTileBytes + lane * 16);
+        }
+    };
+    attn_body<DT, DH32, REL, true>(a, h, 0, smem, request_w);
     __syncthreads();
     const int tok_l = lane & 15, g = lane >> 4;
     const int qstride = DT ? (DHP + 8) * 2 : (DHP + 4) * 4;
@@ -514,6 +544,7 @@ hipError_t launch_attention_proj(const AttnArgs& a, int dtype, hipStream_t st) {
     if (a.T < 1 || a.T > 16 || a.splits != 1 || !a.len_ptr || !a.wo.w || !a.proj_out || a.cgroups < 1 || a.d_head % kt || a.d_head > 64 ||
         a.wo.k != a.heads * a.d_head || a.wo.n != a.d_model || (a.rel_bias && a.rel_d < 1))
         return hipErrorInvalidValue;
+    if (a.heads > 255 || a.nw > 15) return hipErrorInvalidValue;  // (BILD_ATTN_HOT packs them)
     const int npc = (a.wo.tn + a.cgroups - 1) / a.cgroups;
     if ((npc + a.nw - 1) / a.nw > (dtype ? 4 : 2)) return hipErrorInvalidValue;  // feature tiles a wave keeps in registers
     const size_t smem = attn_lds_bytes(dtype, a.d_head, a.T, a.nw) + (a.rel_bias ? (size_t)(2 * a.rel_d + 1) * 4 : 0);
@@ -521,8 +552,8 @@ hipError_t launch_attention_proj(const AttnArgs& a, int dtype, hipStream_t st) {
     const dim3 grid(a.heads, a.cgroups), block(64 * a.nw);
 #define BILD_AP(DTV, DHV)                                                                       \
     do {                                                                                        \
-        if (a.rel_bias) hipLaunchKernelGGL((attn_proj_kernel<DTV, DHV, true>), grid, block, smem, st, a); \
-        else hipLaunchKernelGGL((attn_proj_kernel<DTV, DHV>), grid, block, smem, st, a);        \
+        if (a.rel_bias) hipLaunchKernelGGL((attn_proj_kernel<DTV, DHV, true>), grid, block, smem, st, BILD_ATTN_HOT(a), a); \
+        else hipLaunchKernelGGL((attn_proj_kernel<DTV, DHV>), grid, block, smem, st, BILD_ATTN_HOT(a), a);        \
     } while (0)
     if (dtype) {
         if (dh32 == 1) BILD_AP(1, 1); else BILD_AP(1, 2);
@@ -538,6 +569,7 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
     const int dh32 = a.d_head <= 32 ? 1 : (a.d_head <= 64 ? 2 : 4);
     const unsigned row_blocks = (unsigned)((a.T + kMaxRows - 1) / kMaxRows);
     if ((row_blocks > 1 && a.splits != 1) || !a.len_ptr) return hipErrorInvalidValue;
+    if (a.heads > 255 || a.nw > 15 || a.d_head > 511 || a.splits > 1023) return hipErrorInvalidValue;  // (BILD_ATTN_HOT packs them)
     if (a.rel_bias && a.rel_d < 1) return hipErrorInvalidValue;
     const size_t smem = attn_lds_bytes(dtype, a.d_head, std::min(a.T, kMaxRows), a.nw) +
                         (a.rel_bias ? (size_t)(2 * a.rel_d + 1) * 4 : 0);  // + one head's row of the bias table
@@ -546,13 +578,13 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
 #define BILD_ATTN(DTV, DHV)                                                                     \
     do {                                                                                        \
         if (row_blocks > 1 && a.rel_bias)                                                       \
-            hipLaunchKernelGGL((attn_rows_kernel<DTV, DHV, true>), grid, block, smem, st, a);   \
+            hipLaunchKernelGGL((attn_rows_kernel<DTV, DHV, true>), grid, block, smem, st, BILD_ATTN_HOT(a), a);   \
         else if (row_blocks > 1)                                                                \
-            hipLaunchKernelGGL((attn_rows_kernel<DTV, DHV>), grid, block, smem, st, a);         \
+            hipLaunchKernelGGL((attn_rows_kernel<DTV, DHV>), grid, block, smem, st, BILD_ATTN_HOT(a), a);         \
         else if (a.rel_bias)                                                                    \
-            hipLaunchKernelGGL((attn_kernel<DTV, DHV, true>), grid, block, smem, st, a);        \
+            hipLaunchKernelGGL((attn_kernel<DTV, DHV, true>), grid, block, smem, st, BILD_ATTN_HOT(a), a);        \
         else                                                                                    \
-            hipLaunchKernelGGL((attn_kernel<DTV, DHV>), grid, block, smem, st, a);              \
+            hipLaunchKernelGGL((attn_kernel<DTV, DHV>), grid, block, smem, st, BILD_ATTN_HOT(a), a);              \
     } while (0)
     if (dtype) {
         if (dh32 == 1) BILD_ATTN(1, 1); else if (dh32 == 2) BILD_ATTN(1, 2); else BILD_ATTN(1, 4);

@@ -348,11 +348,13 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         }
         // a decoder-only model prefills its whole prompt in one pass of many row blocks
         M.rows_cap = p->decoder_only ? std::max(kMaxRows, max_src) : kMaxRows;
-        AL(M.x, sizeof(float) * M.rows_cap * d);
+        // the two residual-stream buffers in one block: a reader of partial results gets the other buffer as a 32-bit
+        // offset from the one it reads (GemmArgs::x_out)
+        AL(M.x, sizeof(float) * ((size_t)M.rows_cap + kMaxRows) * d);
+        M.x2 = M.x + (size_t)M.rows_cap * d;
         AL(M.q, sizeof(float) * M.rows_cap * I);
         AL(M.a, sizeof(float) * M.rows_cap * I);
         AL(M.h, sizeof(float) * M.rows_cap * F);
-        AL(M.x2, sizeof(float) * kMaxRows * d);
         AL(M.px, sizeof(float) * kPartSlices * kMaxRows * d);
         if (d <= 1024) ALZ(M.pxh, sizeof(float) * kMaxHeadParts * kMaxRows * d);  // slots of heads a model does not have stay zero
         if (m->cfg.pos == BILD_POS_SINUSOIDAL) {

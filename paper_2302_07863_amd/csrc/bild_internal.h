@@ -127,17 +127,23 @@ struct GemmArgs {
     float* nx_ssq;          // EPI_RESID: [feature tiles / rw][kMaxRows] sums of out^2 per owner wave
     int nx_ld;
     // launch shape
-    int wk;   // input slices per workgroup
+    int wk;   // input slices per workgroup (a power of two)
+    int lwk;  // (set by the kernel) log2(wk)
     int nwv;  // waves per workgroup = wk * feature groups (4 or 8)
     int rw;   // feature tiles per wave (1, or 2 for gated FFNs)
     int kc;   // inputs staged in LDS per chunk
 };
 
 // The leading scalar arguments of the GEMM kernels (gemm_body.h, BILD_GEMM_HOT_PARAMS), from a filled GemmArgs.
-#define BILD_GEMM_HOT_TAIL(a) (a).px, (a).W.k, (a).W.tn, (a).W.tk, ((a).wk | ((a).nwv << 4) | ((a).T << 8)), (a).kc, (a).ldx
-#define BILD_GEMM_HOT(a) (a).W.w, (const void*)(a).x, (const void*)(a).gain, BILD_GEMM_HOT_TAIL(a)
-#define BILD_GEMM_HOT_PRE(a) (a).W.w, (const void*)(a).xb_hi, (const void*)(a).xb_lo, BILD_GEMM_HOT_TAIL(a)
-#define BILD_GEMM_HOT_MG(a) (a).W.w, (const void*)(a).mg_o, (const void*)(a).mg_ml, BILD_GEMM_HOT_TAIL(a)
+static inline int gemm_hot_geom(const GemmArgs& a) {
+    int lwk = 0;
+    while ((1 << lwk) < a.wk) ++lwk;
+    return a.wk | (lwk << 4) | (a.nwv << 8) | (a.T << 12);
+}
+#define BILD_GEMM_HOT_MID(a) (a).W.tn, (a).W.tk, gemm_hot_geom(a), (a).kc, (a).ldx
+#define BILD_GEMM_HOT(a) (a).W.w, (const void*)(a).x, (const void*)(a).gain, (a).px, BILD_GEMM_HOT_MID(a), ((a).x_out ? (int)((a).x_out - (a).x) : 0)
+#define BILD_GEMM_HOT_PRE(a) (a).W.w, (const void*)(a).xb_hi, (const void*)(a).xb_lo, (a).px, BILD_GEMM_HOT_MID(a), 0
+#define BILD_GEMM_HOT_MG(a) (a).W.w, (const void*)(a).mg_o, (const void*)(a).mg_ml, (a).px, BILD_GEMM_HOT_MID(a), ((a).mg_heads | ((a).d_head << 16))
 
 struct AttnArgs {
     const float* q;  // [T][I]

@@ -46,24 +46,28 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 //   h_w             weight tiles (W.w)
 //   h_x, h_g        activations and norm gain (x, gain) | input planes (xb_hi, xb_lo) | key-split partials (mg_o, mg_ml)
 //   h_px            partial results a reader adds (px; their stride is kMaxRows * ldx)
-//   h_k/h_tn/h_tk   W.k, W.tn, W.tk
-//   h_geom          wk | nwv << 4 | T << 8
+//   h_tn, h_tk      W.tn, W.tk (W.k is tk whole tiles)
+//   h_geom          wk | log2(wk) << 4 | nwv << 8 | T << 12
 //   h_kc, h_ldx     kc, ldx
+//   h_aux           readers of partial results: x_out - x in floats | key-split partials: mg_heads | d_head << 16
 #define BILD_GEMM_HOT_PARAMS                                                                                      \
     const void* __restrict__ h_w, const void* __restrict__ h_x, const void* __restrict__ h_g,                     \
-        const float* __restrict__ h_px, const int h_k, const int h_tn, const int h_tk, const int h_geom, const int h_kc, \
-        const int h_ldx
-#define BILD_GEMM_HOT_NAMES h_w, h_x, h_g, h_px, h_k, h_tn, h_tk, h_geom, h_kc, h_ldx
+        const float* __restrict__ h_px, const int h_tn, const int h_tk, const int h_geom, const int h_kc,         \
+        const int h_ldx, const int h_aux
+#define BILD_GEMM_HOT_NAMES h_w, h_x, h_g, h_px, h_tn, h_tk, h_geom, h_kc, h_ldx, h_aux
 enum HotKind : int { HOT_X = 0, HOT_PRE = 1, HOT_MG = 2 };
-template <int KIND>
+template <int KIND, int DT>
 __device__ __forceinline__ GemmArgs gemm_hot(const GemmArgs& a, BILD_GEMM_HOT_PARAMS) {
     GemmArgs b = a;
-    b.W.w = h_w; b.W.k = h_k; b.W.tn = h_tn; b.W.tk = h_tk;
-    b.wk = h_geom & 15; b.nwv = (h_geom >> 4) & 15; b.T = h_geom >> 8;
+    b.W.w = h_w; b.W.k = h_tk * (DT ? 32 : 16); b.W.tn = h_tn; b.W.tk = h_tk;
+    b.wk = h_geom & 15; b.lwk = (h_geom >> 4) & 15; b.nwv = (h_geom >> 8) & 15; b.T = h_geom >> 12;
     b.kc = h_kc; b.ldx = h_ldx;
-    if (KIND == HOT_X) { b.x = (const float*)h_x; b.gain = (const float*)h_g; b.px = h_px; b.px_stride = (int64_t)kMaxRows * h_ldx; }
+    if (KIND == HOT_X) {
+        b.x = (const float*)h_x; b.gain = (const float*)h_g; b.px = h_px; b.px_stride = (int64_t)kMaxRows * h_ldx;
+        b.x_out = const_cast<float*>((const float*)h_x) + h_aux;
+    }
     if (KIND == HOT_PRE) { b.xb_hi = (const uint16_t*)h_x; b.xb_lo = (const uint16_t*)h_g; }
-    if (KIND == HOT_MG) { b.mg_o = (const float*)h_x; b.mg_ml = (const float*)h_g; }
+    if (KIND == HOT_MG) { b.mg_o = (const float*)h_x; b.mg_ml = (const float*)h_g; b.mg_heads = h_aux & 0xFFFF; b.d_head = h_aux >> 16; }
     return b;
 }
 
@@ -95,8 +99,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int NWV = a.nwv, nthr = NWV << 6;  // (the launch has 64 * nwv threads; blockDim would be one more fetch)
     const int T = ONE ? 1 : a.T, K = KS ? a.k_len : a.W.k, KC = a.kc;
-    const int WK = a.wk, WR = NWV / WK;
-    const int wkid = wave % WK, wrid = wave / WK;
+    const int WK = a.wk, WR = NWV >> a.lwk;  // wk is a power of two
+    const int wkid = wave & (WK - 1), wrid = wave >> a.lwk;
     const int tile0 = (vblock * WR + wrid) * RW;
     const int nacc = RW * NT;
     const int rstride = xs_row_stride(DT, KC);
@@ -145,31 +149,36 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
         }
     };
 
-    // residual values: unconditional loads from clamped addresses (a conditional load would have to be waited
-    // for where the branches join, that is, here)
+    // What only the epilogue needs - the residual values, the position of row 0, the target ids - is requested by
+    // `late`, which runs right behind the first weight requests: the fields of the argument structure it reads (and the
+    // position behind a pointer in it) are two more trips to memory, and nothing in front of the first requests
+    // may wait for them.  The residual loads are unconditional loads from clamped addresses (a conditional load would
+    // have to be waited for where the branches join).
     float4 old[RW][2];
 #pragma unroll
     for (int r = 0; r < RW; ++r)
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) old[r][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (epi == EPI_RESID) {
-#pragma unroll
-        for (int r = 0; r < RW; ++r)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                old[r][nt] = ld_act4(a.out + (size_t)min(nt * 16 + tok_l, T - 1) * a.ldo + min(tile0 + r, a.W.tn - 1) * 16 + kq * 4);
-    }
-
-    const int pos0 = (a.pos_ptr ? *a.pos_ptr : 0) + a.pos_add;
+    int pos0 = 0;
     int tgt[2] = {-1, -1};
-    if (epi == EPI_LMHEAD) {
-        const int ylen = *a.ylen_ptr;
+    auto late = [&]() {
+        if (epi == EPI_RESID) {
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const int ti = pos0 + nt * 16 + tok_l + 1;
-            if (nt * 16 + tok_l < T && ti < ylen) tgt[nt] = a.y[ti];
+            for (int r = 0; r < RW; ++r)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    old[r][nt] = ld_act4(a.out + (size_t)min(nt * 16 + tok_l, T - 1) * a.ldo + min(tile0 + r, a.W.tn - 1) * 16 + kq * 4);
         }
-    }
+        if (epi == EPI_QKV || epi == EPI_LMHEAD) pos0 = (a.pos_ptr ? *a.pos_ptr : 0) + a.pos_add;
+        if (epi == EPI_LMHEAD) {
+            const int ylen = *a.ylen_ptr;
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const int ti = pos0 + nt * 16 + tok_l + 1;
+                if (nt * 16 + tok_l < T && ti < ylen) tgt[nt] = a.y[ti];
+            }
+        }
+    };
 
     // PRE: the sums of squares of the rows come from the producer, one partial per wave of it that owned output tiles.
     // Wave w adds the partials of rows w, w + NWV, ...: they are requested behind the weights (ssq_request) and added
@@ -554,6 +563,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
             request(B0, wkid, nkt0);
             if (TWO && both) request(B1, wkid + S, nkt0);
             second_out = both;
+            late();
         });
         if (TWO && !second_out) request(B1, wkid + S, nkt0);
         if constexpr (PRE && norm) ssq_request();
@@ -572,6 +582,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
         }
     } else if (TCAP == 0) {  // (the few-rows kernel is launched on single-chunk inputs only)
         request(B0, wkid, nkt0);
+        late();
         if constexpr (PRE && norm) ssq_request();
         for (int k0 = 0; k0 < K; k0 += KC) {
             const int kc_len = min(KC, K - k0);

@@ -12,7 +12,7 @@ namespace bild {
 template <int RW, int EPI, int ROPE, int NT, bool SHORT = false>
 __global__ __launch_bounds__(512) void gemm_pre_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const GemmArgs a = gemm_hot<HOT_PRE>(a0, BILD_GEMM_HOT_NAMES);
+    const GemmArgs a = gemm_hot<HOT_PRE, 1>(a0, BILD_GEMM_HOT_NAMES);
     gemm_body<1, RW, EPI, ROPE, NT, gemm_batch(RW, false, NT), 0, false, !SHORT, 0, true,
               EPI == EPI_RESID || EPI == EPI_ACT>(a, (int)blockIdx.x, smem);
 }
@@ -21,7 +21,7 @@ __global__ __launch_bounds__(512) void gemm_pre_kernel(BILD_GEMM_HOT_PARAMS, con
 template <int SPLITS, bool SHORT = false>
 __global__ __launch_bounds__(512) void gemm_merge_nx_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const GemmArgs a = gemm_hot<HOT_MG>(a0, BILD_GEMM_HOT_NAMES);
+    const GemmArgs a = gemm_hot<HOT_MG, 1>(a0, BILD_GEMM_HOT_NAMES);
     gemm_body<1, 1, EPI_RESID, 0, 1, gemm_batch(1, false), SPLITS, false, !SHORT, 0, false, true>(a, (int)blockIdx.x, smem);
 }
 

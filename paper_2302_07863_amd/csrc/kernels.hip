@@ -33,7 +33,7 @@ namespace bild {
 template <int DT, int RW, int EPI, int ROPE, int NT, bool SHORT = false>
 __global__ __launch_bounds__(512) void gemm_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const GemmArgs a = gemm_hot<HOT_X>(a0, BILD_GEMM_HOT_NAMES);
+    const GemmArgs a = gemm_hot<HOT_X, DT>(a0, BILD_GEMM_HOT_NAMES);
     gemm_body<DT, RW, EPI, ROPE, NT, gemm_batch(RW, false, NT), 0, false, !SHORT>(a, (int)blockIdx.x, smem);
 }
 
@@ -50,7 +50,7 @@ constexpr int kShortBatch = 8;
 template <int DT, int RW, int EPI, int ROPE, int VAR = 0, int PS = 0>
 __global__ __launch_bounds__(512) void gemm_row_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const GemmArgs a = gemm_hot<HOT_X>(a0, BILD_GEMM_HOT_NAMES);
+    const GemmArgs a = gemm_hot<HOT_X, DT>(a0, BILD_GEMM_HOT_NAMES);
     gemm_body<DT, RW, EPI, ROPE, 1, VAR ? kShortBatch / RW : gemm_batch(RW, true), 0, true, VAR != 1, 0, false, false, PS>(
         a, (int)blockIdx.x, smem);
 }
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(512) void gemm_row_kernel(BILD_GEMM_HOT_PARAMS, con
 template <int DT, int RW, int EPI, int ROPE, bool SHORT, int PS = 0>
 __global__ __launch_bounds__(512) void gemm_few_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const GemmArgs a = gemm_hot<HOT_X>(a0, BILD_GEMM_HOT_NAMES);
+    const GemmArgs a = gemm_hot<HOT_X, DT>(a0, BILD_GEMM_HOT_NAMES);
     gemm_body<DT, RW, EPI, ROPE, 1, gemm_batch(RW, false, 1), 0, false, !SHORT, 4, false, false, PS>(a, (int)blockIdx.x, smem);
 }
 
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(512) void gemm_few_kernel(BILD_GEMM_HOT_PARAMS, con
 // two to four rows (FEW, SHORT as in gemm_few_kernel).
 __device__ __forceinline__ GemmArgs part_slice(const GemmArgs& a, int kt) {
     GemmArgs b = a;
-    const int tps = a.W.tk / a.ksplit, ks = (int)blockIdx.y;
+    const int tps = a.W.tk / kPartSlices, ks = (int)blockIdx.y;  // (the launcher insists on ksplit == kPartSlices)
     b.k_off_tiles = ks * tps;
     b.k_len = tps * kt;
     b.x = a.x + (size_t)ks * tps * kt;
@@ -82,14 +82,14 @@ __device__ __forceinline__ GemmArgs part_slice(const GemmArgs& a, int kt) {
 template <int DT, int VAR>
 __global__ __launch_bounds__(512) void gemm_part_row_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const GemmArgs b = part_slice(gemm_hot<HOT_X>(a0, BILD_GEMM_HOT_NAMES), DT ? 32 : 16);
+    const GemmArgs b = part_slice(gemm_hot<HOT_X, DT>(a0, BILD_GEMM_HOT_NAMES), DT ? 32 : 16);
     gemm_body<DT, 1, EPI_PART, 0, 1, VAR ? kShortBatch : gemm_batch(1, true), 0, true, VAR != 1, 0, false, false, 0, true>(
         b, (int)blockIdx.x, smem);
 }
 template <int DT, bool SHORT>
 __global__ __launch_bounds__(512) void gemm_part_few_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const GemmArgs b = part_slice(gemm_hot<HOT_X>(a0, BILD_GEMM_HOT_NAMES), DT ? 32 : 16);
+    const GemmArgs b = part_slice(gemm_hot<HOT_X, DT>(a0, BILD_GEMM_HOT_NAMES), DT ? 32 : 16);
     gemm_body<DT, 1, EPI_PART, 0, 1, gemm_batch(1, false, 1), 0, false, !SHORT, 4, false, false, 0, true>(b, (int)blockIdx.x, smem);
 }
 
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(512) void gemm_part_few_kernel(BILD_GEMM_HOT_PARAMS
 template <int DT, int SPLITS, bool SHORT = false>
 __global__ __launch_bounds__(512) void gemm_merge_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const GemmArgs a = gemm_hot<HOT_MG>(a0, BILD_GEMM_HOT_NAMES);
+    const GemmArgs a = gemm_hot<HOT_MG, DT>(a0, BILD_GEMM_HOT_NAMES);
     gemm_body<DT, 1, EPI_RESID, 0, 1, gemm_batch(1, false), SPLITS, false, !SHORT>(a, (int)blockIdx.x, smem);
 }
 
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(512) void gemm_merge_kernel(BILD_GEMM_HOT_PARAMS, c
 template <int DT, int RW, int EPI, int ROPE>
 __global__ __launch_bounds__(512) void gemm_rows_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const GemmArgs a = gemm_hot<HOT_X>(a0, BILD_GEMM_HOT_NAMES);
+    const GemmArgs a = gemm_hot<HOT_X, DT>(a0, BILD_GEMM_HOT_NAMES);
     GemmArgs b = a;
     const int r0 = (int)blockIdx.y * kMaxRows;
     b.T = min(kMaxRows, a.T - r0);
@@ -176,7 +176,8 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
         // per CU; the remaining waves split the inputs.
         int wr = 8;
         while (wr > 1 && ((a.W.tn + wr * a.rw - 1) / (wr * a.rw)) * row_blocks < 256) wr /= 2;
-        a.wk = std::max(1, std::min(8 / wr, tiles_chunk));
+        a.wk = 8 / wr;
+        while (a.wk > 1 && a.wk > tiles_chunk) a.wk /= 2;  // (a power of two: the kernels cut the wave index by shifts)
         a.nwv = a.wk * wr;
         return;
     }
@@ -284,7 +285,7 @@ static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st
     if (a.T == 1 ? n4 > 2 * nthr : ((n4 & 63) != 0 || a.T * n4 > 4 * nthr)) return hipErrorInvalidValue;
     const dim3 block(nthr);
     if (a.epi == EPI_PART) {
-        if (a.ksplit < 2 || a.W.tk % a.ksplit || a.pn > 0 || !a.out) return hipErrorInvalidValue;
+        if (a.ksplit != kPartSlices || a.W.tk % a.ksplit || a.pn > 0 || !a.out) return hipErrorInvalidValue;
         const dim3 grid((unsigned)gemm_num_blocks(a), (unsigned)a.ksplit);
 #define BILD_PK(DTV)                                                                                              \
     do {                                                                                                          \
@@ -299,7 +300,8 @@ static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st
         return hipGetLastError();
     }
     if (a.pn < 1 || !a.px || !a.x_out || a.x_out == a.x || a.ksplit > 1) return hipErrorInvalidValue;
-    if (a.px_stride != (int64_t)kMaxRows * a.ldx) return hipErrorInvalidValue;  // the kernels derive it from ldx (gemm_hot)
+    // the kernels derive the stride of the partial results from ldx and get x_out as a 32-bit offset from x (gemm_hot)
+    if (a.px_stride != (int64_t)kMaxRows * a.ldx || (int64_t)(a.x_out - a.x) != (int64_t)(int)(a.x_out - a.x)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)gemm_num_blocks(a));
     if (a.epi == EPI_STORE || a.epi == EPI_ACT) {
         // readers of one partial result per head (attention fused with its output projection): single-row passes
@@ -361,6 +363,7 @@ static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st
 hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     if (hipError_t e = raise_lds_limits(); e != hipSuccess) return e;
     if (a.T >= kDenseMinRows) return launch_gemm_dense(a, dtype, st);
+    if (a.wk < 1 || a.wk > 8 || (a.wk & (a.wk - 1)) || a.nwv % a.wk || a.nwv > 8) return hipErrorInvalidValue;  // (gemm_hot_geom)
     if (a.xb_hi || a.nx_hi) return dtype ? launch_gemm_pre(a, st) : hipErrorInvalidValue;
     const size_t smem = gemm_lds_bytes(a, dtype);
     const unsigned row_blocks = (unsigned)((a.T + kMaxRows - 1) / kMaxRows);

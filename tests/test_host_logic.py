@@ -67,6 +67,7 @@ def test_gemm_launch_shapes_are_consistent(pair):
                     assert 2 * s["lds"] <= s["lds_limit"]          # two workgroups share a compute unit (registers)
                     continue
                 assert s["nwv"] in (1, 2, 4, 8) and s["nwv"] % s["wk"] == 0, (n, k, rows, s)
+                assert s["wk"] in (1, 2, 4, 8), (n, k, rows, s)   # the kernels cut the wave index by shifts
                 # feature tiles per wave: 2 = gate and linear branch; 4 only for a very wide LM head at up to 16 rows
                 assert s["rw"] == (2 if gated else (4 if head and rows <= 16 and tiles >= 8192 else 1))
                 per_wg = (s["nwv"] // s["wk"]) * s["rw"]
@@ -127,3 +128,15 @@ def test_debug_calls_reject_bad_arguments():
     assert lib.bild_debug_tiled_bytes(0, 32, 0) == b.EINVAL
     assert lib.bild_debug_tiled_bytes(16, 40, 1) == b.EINVAL
     assert lib.bild_debug_gemm_shape(16, 32, 0, 0, 0, 0, None) == b.EINVAL
+
+
+def test_launch_shapes_of_ragged_widths_keep_a_power_of_two_of_input_slices():
+    """Widths whose tile count is not a power of two (96 inputs = 6 fp32 tiles, 160 = 10) in row-block launches: the
+    kernels split the wave index into (input slice, feature group) by shifts, so the slices must be a power of two."""
+    for dtype, kt in ((bi.DT_F32, 16), (bi.DT_BF16, 32)):
+        for k in (96, 160, 192, 320, 6 * kt, 10 * kt, 12 * kt):
+            for n in (48, 96, 288, 1000, 4096):
+                for rows in (1, 3, 16, 33, 40, 300):
+                    s = b.gemm_shape(n, k, rows, False, False, dtype)
+                    assert s["wk"] in (1, 2, 4, 8) and s["nwv"] in (1, 2, 4, 8) and s["nwv"] % s["wk"] == 0, (n, k, rows, s)
+                    assert s["wk"] <= max(1, min(s["kc"], k) // kt), (n, k, rows, s)
