@@ -162,6 +162,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
     int pos0 = 0;
     int tgt[2] = {-1, -1};
     auto late = [&]() {
+        if (lane < 32) ssq[wave * 32 + lane] = 0.f;  // each wave owns (and later accumulates into) its own row
+        if (tid < 4) ((uint4*)zblk)[tid] = make_uint4(0u, 0u, 0u, 0u);
         if (epi == EPI_RESID) {
 #pragma unroll
             for (int r = 0; r < RW; ++r)
@@ -211,10 +213,6 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
             }
         }
     };
-    if (lane < 32) {
-        ssq[wave * 32 + lane] = 0.f;  // each wave owns (and later accumulates into) its own row
-    }
-    if (tid < 4) ((uint4*)zblk)[tid] = make_uint4(0u, 0u, 0u, 0u);
 
     // up to 16 rows: two accumulators per output tile (bf16: one for the high parts, one for the low parts of the
     // activations), so that consecutive MFMAs do not wait for each other; they are added once at the end.  More rows
