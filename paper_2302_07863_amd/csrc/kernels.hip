@@ -186,6 +186,11 @@ void gemm_pick_shape(GemmArgs& a, int dtype) {
     // by all waves; measured on 24 layers of 1024-wide projections: 4 waves win up to 8 rows, 1365 against 1490 us per
     // pass, 8 waves from 9 rows, 1505 against 1578)
     int wr = std::max(1, ((long)a.T * eff_k(a) > 8192 && a.epi != EPI_LMHEAD ? 8 : 4) / wk);
+    // One row of a small matrix: fewer feature groups per workgroup while that leaves fewer than 256 workgroups - the
+    // stage is bound by latency, and more compute units pulling shorten it (measured on T5-small, 96 feature tiles x 512
+    // inputs: 48 workgroups of 4 waves against 96 of 2, 174.7 -> 168.2 us per step; no change at two to four rows).
+    if (a.T == 1 && a.epi != EPI_LMHEAD)
+        while (wr > 1 && (a.W.tn + wr * a.rw - 1) / (wr * a.rw) < 256) wr /= 2;
     for (int c = wr * 2; c * wk <= 8 && c * wk * nacc <= 32; c *= 2)
         if ((a.W.tn + c * a.rw - 1) / (c * a.rw) >= 512) wr = c;
     // Between one and two workgroups per compute unit the chip ends up half with two and half with one of them:
