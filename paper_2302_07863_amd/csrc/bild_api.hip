@@ -317,6 +317,7 @@ extern "C" int bild_state_create(const bild_pair* p, int max_src, int max_len, i
         if (const char* fa = std::getenv("BILD_FUSE_ATTN")) s->fuse_attn = fa[0] != '0';      // experiments / tests
         if (const char* fk = std::getenv("BILD_FUSE_MAX_KV")) s->fuse_max_kv = std::atoi(fk);
         if (const char* dw = std::getenv("BILD_DRAW_ONE_WG")) s->draw_spread = dw[0] == '0';
+        if (const char* fe = std::getenv("BILD_FUSE_EMBED")) s->fuse_embed = std::atoi(fe) != 0;  // tests and measurements
         if (const char* kd = std::getenv("BILD_KSPLIT_MAX_D")) s->ksplit_max_d = std::atoi(kd);
         if (const char* km = std::getenv("BILD_KSPLIT_MIN_F")) s->ksplit_min_f = std::atoi(km);  // tests: small widths; 0 turns the split off
     }
@@ -689,8 +690,20 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
         e.nx_hi = xb_hi; e.nx_lo = xb_lo; e.nx_gain = m->dec[layer0].ln1; e.nx_ssq = M.ssq;
         xb_parts = kEmbedSsqParts;
     }
-    s->stage_count += 1;  // embedding or the trunk's rows
-    if (!s->gemm_only) {
+    // Single-row passes: the first projection gathers the row from the embedding matrix itself (no embedding kernel).
+    // The table of positions must exist where positions are added (the kernel does not evaluate sines).
+    // Every workgroup of that projection repeats the gather, so it is taken only where one round of two pieces per
+    // thread covers the row (a 4096-wide row in workgroups of two waves would be four dependent rounds: measured slower).
+    bool embed_in_proj = s->fuse_embed && T == 1 && !planes && !above_trunk && (!e.sinusoidal || e.pe != nullptr) &&
+                         c.tie_shift >= 0 && c.tie_shift < c.vocab && layer0 < c.n_dec_layers;
+    if (embed_in_proj) {
+        GemmArgs probe = gemm_base(m, m->dec[layer0].wqkv, M.x, d, T, m->dec[layer0].ln1);
+        probe.epi = EPI_QKV;
+        gemm_pick_shape(probe, dt);
+        embed_in_proj = d / 4 <= 2 * 64 * probe.nwv && probe.W.k <= probe.kc;
+    }
+    if (!embed_in_proj) s->stage_count += 1;  // embedding or the trunk's rows
+    if (!s->gemm_only && !embed_in_proj) {
         if (above_trunk) {
             RowCopyArgs rc;
             std::memset((void*)&rc, 0, sizeof(rc));
@@ -723,6 +736,11 @@ int emit_layers(bild_state* s, int w, int T, int key_hint, bool head_reads_parts
             g.pos_ptr = len_ptr;
             g.rope = c.pos == BILD_POS_ROPE;
             set_in(g);
+            if (embed_in_proj && l == layer0) {
+                g.e_w = e.E.w; g.e_tk = e.E.tk; g.e_tokens = e.tokens; g.e_base_ptr = e.base_ptr; g.e_base_add = e.base_add;
+                g.e_vocab = e.vocab; g.e_shift = e.tie_shift; g.e_scale = e.embed_scale; g.e_pe = e.sinusoidal ? e.pe : nullptr;
+                g.x_out = xcur;  // (= g.x: the row is written where the embedding kernel would have left it)
+            }
             int rc = emit_gemm(s, m, g);
             if (rc) return rc;
             after_parts_in();

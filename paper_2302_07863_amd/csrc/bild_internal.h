@@ -126,6 +126,18 @@ struct GemmArgs {
     const float* nx_gain;   // EPI_RESID: gain of the norm in front of the next projection
     float* nx_ssq;          // EPI_RESID: [feature tiles / rw][kMaxRows] sums of out^2 per owner wave
     int nx_ld;
+    // Single-row passes: the first projection of the pass may gather its input row from the embedding matrix itself
+    // (e_w non-null; x is not read): x = e_scale * E[(tokens[base] + e_shift) mod e_vocab] (+ e_pe[base], the position
+    // table, if non-null) with base = *e_base_ptr + e_base_add; workgroup 0 also writes the row to x_out.
+    const void* e_w;        // tiles of the embedding matrix
+    int e_tk;               // its input tiles per feature block
+    const int* e_tokens;
+    const int* e_base_ptr;
+    int e_base_add;
+    int e_vocab;
+    int e_shift;            // 0 <= e_shift < e_vocab
+    float e_scale;
+    const float* e_pe;      // nullable: [positions][k]
     // launch shape
     int wk;   // input slices per workgroup (a power of two)
     int lwk;  // (set by the kernel) log2(wk)

@@ -102,6 +102,7 @@ struct bild_state {
     int ksplit_min_f = 2048;      // FFN widths from which the output projection of a narrow model (d <= 1024) is cut into input slices
     int fuse_max_kv = 32 << 10;   // ... while one head's cached K/V are at most this many bytes
     bool fuse_attn = true;        // single-row passes of narrow models: attention and its output projection in one kernel
+    bool fuse_embed = true;       // single-row passes: the first projection gathers its input row from the embedding matrix
     int pre_min_rows = 0;         // > 0 (experiments): row count from which a bf16 pass hands activations on as bf16 planes
     bool gemm_only = false;       // measurement: a pass launches only its weight-streaming GEMMs
     int64_t gemm_count = 0, gemm_bytes = 0;  // tallied while a pass is being issued

@@ -87,11 +87,14 @@ __device__ __forceinline__ void put_planes(const GemmArgs& a, int t, int n0, con
 // slices up while staging.  PS > 0: that reader - its input is a.x plus PS partial results a.px[j] (fixed order; a producer with fewer leaves the
 // rest of the PS slots zero), and the
 // workgroup with index 0 also writes the sum to a.x_out (another buffer than a.x, which the other workgroups still read).
+// EMB (single-row launches on one chunk): the input row is gathered from the embedding matrix (GemmArgs::e_w ..), so the
+// pass needs no embedding kernel in front of its first projection; workgroup 0 writes the row to a.x_out for the residual adds.
 // PRE: the input arrives as high / low bf16 planes with the consumer's norm gain already applied, written by the
 // kernel that produced it (a.xb_hi, a.xb_lo; a.ssq_part holds that kernel's per-wave sums of squares): staging is a
 // plain copy into LDS.  NX: this kernel's epilogue hands its own output on in that form (a.nx_*).
 template <int DT, int RW, int EPI, int ROPE, int NT, int U = gemm_batch(RW, false, NT), int MG = 0,
-          bool ONE = false, bool TWO = true, int TCAP = 0, bool PRE = false, bool NX = false, int PS = 0, bool KS = false>
+          bool ONE = false, bool TWO = true, int TCAP = 0, bool PRE = false, bool NX = false, int PS = 0, bool KS = false,
+          bool EMB = false>
 __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, char* smem) {
     constexpr int KT = DT ? 32 : 16;
     // the wave index through readfirstlane: the compiler then knows that it - and every tile index, weight address and
@@ -296,7 +299,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
             float4 w = wv.p[0];
 #pragma unroll
             for (int j = 0; j < PS; ++j) { w.x += wv.p[j + 1].x; w.y += wv.p[j + 1].y; w.z += wv.p[j + 1].z; w.w += wv.p[j + 1].w; }
-            if (PS > 0 && vblock == 0) st_act4(a.x_out + (size_t)t * a.ldx + k0 + k4 * 4, w);  // the residual stream, for later readers
+            if ((PS > 0 || EMB) && vblock == 0) st_act4(a.x_out + (size_t)t * a.ldx + k0 + k4 * 4, w);  // the residual stream, for later readers
             float ss = 0.f;
             if (norm) {
                 ss = w.x * w.x + w.y * w.y + w.z * w.z + w.w * w.w;
@@ -313,7 +316,48 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
             }
             return ss;
         };
-        if constexpr (PRE) {
+        if constexpr (EMB) {
+            // The weights go out first: the row's address is behind two dependent scalar loads (position, token id), so
+            // the gather is a third trip, and the weights' own trip covers most of the chain.  Pieces in pairs (clamped
+            // duplicates carry the same value to the same place and count as zero in the sum of squares).
+            hook(true);
+            const int base = *a.e_base_ptr + a.e_base_add;
+            const int tok = a.e_tokens[base];
+            int erow_i = tok + a.e_shift;
+            erow_i = erow_i >= a.e_vocab ? erow_i - a.e_vocab : erow_i;
+            const char* erow = (const char*)a.e_w + (size_t)(erow_i >> 4) * a.e_tk * kTileBytes + (erow_i & 15) * 16;
+            const float* pe = a.e_pe ? a.e_pe + (size_t)base * K : nullptr;
+            auto gather = [&](int k4) -> float4 {
+                const int k = k4 * 4;
+                float4 v;
+                if (DT) {  // 8 inputs per lane chunk: tile k / 32, chunk (k % 32) / 8, half k % 8
+                    const uint2 raw = *(const uint2*)(erow + (size_t)(k >> 5) * kTileBytes + ((k & 31) >> 3) * 256 + (k & 7) * 2);
+                    v = make_float4(bf2f(raw.x & 0xFFFFu), bf2f(raw.x >> 16), bf2f(raw.y & 0xFFFFu), bf2f(raw.y >> 16));
+                } else {   // 4 inputs per lane chunk: tile k / 16, chunk (k % 16) / 4
+                    v = *(const float4*)(erow + (size_t)(k >> 4) * kTileBytes + ((k & 15) >> 2) * 256);
+                }
+                return v;
+            };
+            float ssj = 0.f;
+            for (int kb = tid; kb < n4; kb += 2 * nthr) {
+                const int ca = min(kb, n4 - 1), cb = min(kb + nthr, n4 - 1);
+                const float4 ea = gather(ca), eb = gather(cb);
+                float4 pa = make_float4(0.f, 0.f, 0.f, 0.f), pb = pa;
+                if (pe) { pa = *(const float4*)(pe + ca * 4); pb = *(const float4*)(pe + cb * 4); }
+                const float4 ga = ldg(ca), gb = ldg(cb);
+                XV va, vb;
+                // (the embedding kernel's arithmetic: one fused multiply-add of value, scale and position term)
+                const float sc = a.e_scale;
+                va.p[0] = make_float4(__builtin_fmaf(ea.x, sc, pa.x), __builtin_fmaf(ea.y, sc, pa.y), __builtin_fmaf(ea.z, sc, pa.z), __builtin_fmaf(ea.w, sc, pa.w));
+                vb.p[0] = make_float4(__builtin_fmaf(eb.x, sc, pb.x), __builtin_fmaf(eb.y, sc, pb.y), __builtin_fmaf(eb.z, sc, pb.z), __builtin_fmaf(eb.w, sc, pb.w));
+                const float sa = put(0, ca, va, ga), sb = put(0, cb, vb, gb);
+                ssj += sa + (kb + nthr < n4 ? sb : 0.f);
+            }
+            if (norm) {
+                const float tot = wave_sum(ssj);
+                if (lane == 0) ssq[wave * 32] += tot;
+            }
+        } else if constexpr (PRE) {
             // both planes are copied as they are: pieces of 16 bytes (8 inputs), rows laid end to end and dealt to all
             // threads; indices past the end are clamped (same value to the same place), so no load is conditional
             const int n8 = kc_len >> 3;

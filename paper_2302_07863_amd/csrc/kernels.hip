@@ -55,6 +55,16 @@ __global__ __launch_bounds__(512) void gemm_row_kernel(BILD_GEMM_HOT_PARAMS, con
         a, (int)blockIdx.x, smem);
 }
 
+// The first projection of a single-row pass, gathering its input row from the embedding matrix (gemm_body, EMB): the
+// pass then has no embedding kernel, one dependent stage fewer.
+template <int DT, int ROPE, int VAR>
+__global__ __launch_bounds__(512) void gemm_row_embed_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const GemmArgs a = gemm_hot<HOT_X, DT>(a0, BILD_GEMM_HOT_NAMES);
+    gemm_body<DT, 1, EPI_QKV, ROPE, 1, VAR ? kShortBatch : gemm_batch(1, true), 0, true, VAR != 1, 0, false, false, 0, false, true>(
+        a, (int)blockIdx.x, smem);
+}
+
 // Two to four rows (the bulk of the large model's review passes) on a single-chunk input: the same body without the
 // staging rounds for more rows and without the multi-chunk loop.  Run through the general kernel a pass of these row
 // counts costs about 0.7 us more per projection (measured: one row through gemm_kernel 1018 us per T5-large pass,
@@ -237,6 +247,8 @@ static hipError_t raise_lds_limits() {
     (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0, 2>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1, 2>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0, 2>, \
     (const void*)gemm_row_kernel<DTV, 2, EPI_ACT, 0, 1>, (const void*)gemm_row_kernel<DTV, 2, EPI_ACT, 0, 2>, \
+    (const void*)gemm_row_embed_kernel<DTV, 0, 0>, (const void*)gemm_row_embed_kernel<DTV, 0, 1>, (const void*)gemm_row_embed_kernel<DTV, 0, 2>, \
+    (const void*)gemm_row_embed_kernel<DTV, 1, 0>, (const void*)gemm_row_embed_kernel<DTV, 1, 1>, (const void*)gemm_row_embed_kernel<DTV, 1, 2>, \
     (const void*)gemm_few_kernel<DTV, 1, EPI_STORE, 0, true>, (const void*)gemm_few_kernel<DTV, 1, EPI_RESID, 0, true>, \
     (const void*)gemm_few_kernel<DTV, 1, EPI_QKV, 0, true>, (const void*)gemm_few_kernel<DTV, 1, EPI_QKV, 1, true>, \
     (const void*)gemm_few_kernel<DTV, 1, EPI_ACT, 0, true>, \
@@ -374,6 +386,25 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
     const unsigned row_blocks = (unsigned)((a.T + kMaxRows - 1) / kMaxRows);
     if (row_blocks > 1 && a.epi == EPI_LMHEAD) return hipErrorInvalidValue;  // softmax partials are per pass
     if ((a.gain != nullptr) != (a.epi != EPI_RESID && a.epi != EPI_PART)) return hipErrorInvalidValue;  // the kernels fix the norm by the epilogue
+    if (a.e_w) {
+        // input row gathered from the embedding matrix: one row, one chunk, the plain first projection of a layer
+        const int per_wave = (a.W.tk + a.wk - 1) / a.wk;
+        if (a.T != 1 || a.epi != EPI_QKV || a.rw != 1 || a.W.k > a.kc || a.pn > 0 || a.mg_splits > 1 || !a.x_out || a.x != a.x_out ||
+            !a.e_tokens || !a.e_base_ptr || a.e_vocab < 1 || a.e_shift < 0 || a.e_shift >= a.e_vocab || a.e_tk * (dtype ? 32 : 16) != a.W.k)
+            return hipErrorInvalidValue;
+        const dim3 grid((unsigned)gemm_num_blocks(a)), block(64 * a.nwv);
+#define BILD_EM(DTV, ROPEV)                                                                                                       \
+    do {                                                                                                                            \
+        if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_embed_kernel<DTV, ROPEV, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+        else if (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))                                \
+            hipLaunchKernelGGL((gemm_row_embed_kernel<DTV, ROPEV, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a);                 \
+        else hipLaunchKernelGGL((gemm_row_embed_kernel<DTV, ROPEV, 0>), grid, block, smem, st, BILD_GEMM_HOT(a), a);                \
+    } while (0)
+        if (dtype) { if (a.rope) BILD_EM(1, 1); else BILD_EM(1, 0); }
+        else { if (a.rope) BILD_EM(0, 1); else BILD_EM(0, 0); }
+#undef BILD_EM
+        return hipGetLastError();
+    }
     if (a.epi == EPI_PART || a.pn > 0) return launch_gemm_split(a, dtype, st);
     if (a.mg_splits > 1) {
         // merged staging: 2, 4 or 8 splits, up to 16 rows, one (row, head) pair per thread, weights in the reduction area
@@ -479,15 +510,18 @@ __device__ __forceinline__ void embed_body(const EmbedArgs& a, const int t) {
         const int ln = (row & 15) + 16 * ((k % KT) / PL), j = k % PL;
         const char* p = (const char*)a.E.w + tile * kTileBytes + ln * 16;
         float v = DT ? bf2f(((const uint16_t*)p)[j]) : ((const float*)p)[j];
-        v *= a.embed_scale;
+        // one fused multiply-add (value times scale plus the position term), spelled out so that the projection that
+        // gathers its own input row (gemm_body, EMB) rounds the same way
+        float pterm = 0.f;
         if (a.sinusoidal) {
             if (a.pe) {
-                v += a.pe[(size_t)pos * a.d + k];
+                pterm = a.pe[(size_t)pos * a.d + k];
             } else {
                 const double ang = (double)pos * exp2(-(double)(2 * (k >> 1)) / (double)a.d * lg);
-                v += (float)((k & 1) ? cos(ang) : sin(ang));
+                pterm = (float)((k & 1) ? cos(ang) : sin(ang));
             }
         }
+        v = __builtin_fmaf(v, a.embed_scale, pterm);
         st_act(a.x + (size_t)t * a.d + k, v);
         if (a.nx_hi) {
             uint32_t hi, lo;

@@ -171,6 +171,36 @@ def test_single_row_passes_fuse_attention_with_its_output_projection(name, monke
     assert st.generate(R.src, 0.5, 2.0, R.cfg.max_new) == st.generate(R.src, 0.5, 2.0, R.cfg.max_new)
 
 
+@pytest.mark.parametrize("name", ["f32-relu-tied", "bf16-relu-tied", "bf16-trunc-geglu", "bf16-rope-swiglu-deconly", "f32-relative", "tiny"])
+def test_single_row_passes_gather_the_embedding_in_their_first_projection(name, monkeypatch):
+    """Single-row passes have no embedding kernel: the first projection gathers its input row from the embedding matrix
+    (scaled, position term added in the same fused multiply-add the embedding kernel uses).  With the route switched off
+    the embedding kernel runs in front as it does for passes of several rows; both must give the same bits - tokens,
+    logits of every step - and the route must meet the oracle (sinusoidal, rotary and relative positions, shifted tied
+    lookup, fp32 and bf16)."""
+    R = Rig(bi.tiny_pair()) if name == "tiny" else rig(name)
+    out = {}
+    for fuse in ("1", "0"):
+        monkeypatch.setenv("BILD_FUSE_EMBED", fuse)
+        st = R.state(R.cfg.max_new, 10)
+        st.debug_enable_logits(True)
+        rows = []
+        for which in (pkg.SMALL, pkg.LARGE):
+            toks = st.greedy(which, R.src, 10)
+            rows.append((toks, st.debug_logits(which, 0).copy()))
+        st.debug_enable_logits(False)
+        rows.append(st.generate(R.src, R.cfg.alpha_fb, R.cfg.alpha_rb, R.cfg.max_new))
+        out[fuse] = rows
+        if fuse == "1":
+            ref = oracle.bild_generate(R.req, R.cfg.alpha_fb, R.cfg.alpha_rb, 10, R.cfg.max_new, keep_logits=True)
+            st2 = R.state(R.cfg.max_new, 10)
+            st2.encode(R.src)
+            print(name, parity.teacher_forced(st2, ref, R.n0, R.cfg.alpha_fb, R.cfg.alpha_rb, R.cfg))
+    for a, b in zip(out["1"][:2], out["0"][:2]):
+        assert a[0] == b[0] and np.array_equal(a[1], b[1])
+    assert out["1"][2] == out["0"][2]
+
+
 @pytest.mark.parametrize("name", list(TOY_VARIANTS))
 def test_toy_free_running_generate(name):
     R = rig(name)
