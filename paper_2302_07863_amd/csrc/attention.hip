@@ -92,6 +92,7 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int h, const 
             const int t = i / (DHP / 4), d4 = (i % (DHP / 4)) * 4;
             const bool real = t < T && d4 < dh;
             float4 v = ld_act4(a.q + (size_t)min(t, T - 1) * I + h * dh + min(d4, dh - 4));
+            __builtin_amdgcn_sched_barrier(0);  // q goes out before anything waits for the length (the hook's first use of it)
             hk();
             __builtin_amdgcn_sched_barrier(0);  // the conversion of q stays behind the K/V requests
             v.x = real ? v.x * a.scale : 0.f; v.y = real ? v.y * a.scale : 0.f;
@@ -395,10 +396,16 @@ __global__ __launch_bounds__(512) void attn_proj_kernel(BILD_ATTN_HOT_PARAMS, co
     constexpr int KT = DT ? 32 : 16, DHP = DH32 * 32, KH = DHP / KT, MAXN = DT ? 4 : 2;  // (fp32: four input tiles per head already)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = a.nw;
     const int h = (int)blockIdx.x, c = (int)blockIdx.y;
-    const int npc = (a.wo.tn + a.cgroups - 1) / a.cgroups;            // feature tiles per column group (grid: heads x cgroups)
-    const int khr = a.d_head / KT, kt0 = h * khr;                      // this head's input tiles (d_head is a multiple of KT)
+    // Everything about W_o is read from the argument structure, which is not among the values that arrive in registers:
+    // it is first touched behind the first K/V request (the barrier keeps the compiler from moving the division up, which
+    // would make the kernel start with a wait for the structure).
+    int npc = 0, khr = 0, kt0 = 0;
     uint4 Wt[MAXN][KH];
     auto request_w = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        npc = (a.wo.tn + a.cgroups - 1) / a.cgroups;  // feature tiles per column group (grid: heads x cgroups)
+        khr = a.d_head / KT;                           // this head's input tiles (d_head is a multiple of KT)
+        kt0 = h * khr;
 #pragma unroll
         for (int i = 0; i < MAXN; ++i) {
             const int n = min(c * npc + wave + i * nw, a.wo.tn - 1);
