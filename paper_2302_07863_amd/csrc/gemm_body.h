@@ -622,7 +622,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
                 if (kt + 3 * S < nkt0) request(B1, kt + 3 * S, nkt0);
             }
         }
-    } else if (TCAP == 0) {  // (the few-rows kernel is launched on single-chunk inputs only)
+    } else if (TCAP == 0 && TWO && !ONE) {  // (the few-rows, single-row and single-buffer kernels are launched on single-chunk inputs only)
         request(B0, wkid, nkt0);
         late();
         if constexpr (PRE && norm) ssq_request();

@@ -445,7 +445,7 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
             hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T == 1 && RWV == 1 && one_chunk && (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))) \
             hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
-        else if (a.T == 1)                                                                          \
+        else if (a.T == 1 && one_chunk)                                                             \
             hipLaunchKernelGGL((gemm_row_kernel<DTV, RWV, EPIV, ROPEV>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T > 16)                                                                          \
             hipLaunchKernelGGL((gemm_kernel<DTV, RWV, EPIV, ROPEV, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a);  \
@@ -469,7 +469,7 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
             if (a.rw == 2) BILD_L(DTV, 2, EPI_ACT, 0); else BILD_L(DTV, 1, EPI_ACT, 0); \
             break;                                                               \
         case EPI_LMHEAD:                                                         \
-            if (a.rw == 4 && a.T == 1)                                           \
+            if (a.rw == 4 && a.T == 1 && one_chunk)                              \
                 hipLaunchKernelGGL((gemm_row_kernel<DTV, 4, EPI_LMHEAD, 0>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             else if (a.rw == 4 && a.T <= 16)                                     \
                 hipLaunchKernelGGL((gemm_kernel<DTV, 4, EPI_LMHEAD, 0, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
@@ -477,7 +477,7 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
                 return hipErrorInvalidValue;                                     \
             else if (a.T == 1 && one_chunk && per_wave <= 32 && per_wave % kShortBatch == 0) /* batches of 8 fit exactly */ \
                 hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
-            else if (a.T == 1)                                                   \
+            else if (a.T == 1 && one_chunk)                                      \
                 hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_LMHEAD, 0>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             else if (a.T > 16)                                                   \
                 hipLaunchKernelGGL((gemm_kernel<DTV, 1, EPI_LMHEAD, 0, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
