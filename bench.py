@@ -334,6 +334,8 @@ def main() -> int:
                          "profiles/ are taken from (with BILD_NO_GRAPH=1)")
     ap.add_argument("--profile-rows", type=int, default=0,
                     help="with --profile-run: instead of generations, --steps large-model passes of this many rows")
+    ap.add_argument("--profile-model", choices=("small", "large"), default="large",
+                    help="with --profile-rows: the model whose passes are run")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="counter-collection run: one 1 GiB device copy of known size, then --steps BiLD steps; "
                          "no timing, no JSON (run under rocprofv3 --pmc with BILD_NO_GRAPH=1)")
@@ -381,8 +383,10 @@ def main() -> int:
         if args.profile_rows > 0:
             toks, _ = st.generate(None, fb, rb, cfg.max_new)
             ln = st.lengths()
-            st.kv_truncate(pkg.LARGE, min(ln["len_large"], ln["y_len"] - args.profile_rows))
-            st.bench_pass(pkg.LARGE, args.profile_rows, args.steps)
+            which = pkg.SMALL if args.profile_model == "small" else pkg.LARGE
+            have = ln["len_small"] if which == pkg.SMALL else ln["len_large"]
+            st.kv_truncate(which, min(have, ln["y_len"] - args.profile_rows))
+            st.bench_pass(which, args.profile_rows, args.steps)
         else:
             for _ in range(args.steps):
                 st.seq_truncate(n0)

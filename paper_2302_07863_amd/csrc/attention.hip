@@ -26,7 +26,7 @@ constexpr int kAttnLdsLimit = 160 * 1024;
 // passed a second time as leading scalar parameters that arrive in scalar registers at wave start.
 //   h_q, h_k, h_v, h_len   q, k, v, len_ptr
 //   h_T                    T
-//   h_p0                   heads | nw << 8 | causal << 12 | d_head << 13 | splits << 22
+//   h_p0                   heads | nw << 8 | causal << 12 | d_head << 13 | splits << 22 | log2(splits) << 29 (a power of two)
 //   h_idim, h_vcap, h_badd, h_nkf   i_dim, vcap, base_add, nkeys_fixed
 #define BILD_ATTN_HOT_PARAMS                                                                                   \
     const float* __restrict__ h_q, const void* __restrict__ h_k, const void* __restrict__ h_v,                 \
@@ -36,13 +36,18 @@ constexpr int kAttnLdsLimit = 160 * 1024;
 __device__ __forceinline__ AttnArgs attn_hot(const AttnArgs& a, BILD_ATTN_HOT_PARAMS) {
     AttnArgs b = a;
     b.q = h_q; b.k = h_k; b.v = h_v; b.len_ptr = h_len; b.T = h_T;
-    b.heads = h_p0 & 255; b.nw = (h_p0 >> 8) & 15; b.causal = (h_p0 >> 12) & 1; b.d_head = (h_p0 >> 13) & 511; b.splits = h_p0 >> 22;
+    b.heads = h_p0 & 255; b.nw = (h_p0 >> 8) & 15; b.causal = (h_p0 >> 12) & 1; b.d_head = (h_p0 >> 13) & 511; b.splits = (h_p0 >> 22) & 127; b.lsplits = (h_p0 >> 29) & 7;
     b.i_dim = h_idim; b.vcap = h_vcap; b.base_add = h_badd; b.nkeys_fixed = h_nkf;
     return b;
 }
+static inline int attn_hot_p0(const AttnArgs& a) {
+    int ls = 0;
+    while ((1 << ls) < a.splits) ++ls;
+    return a.heads | (a.nw << 8) | ((a.causal ? 1 : 0) << 12) | (a.d_head << 13) | (a.splits << 22) | (int)((unsigned)ls << 29);
+}
 #define BILD_ATTN_HOT(a)                                                                                             \
     (a).q, (a).k, (a).v, (a).len_ptr, (a).T,                                                                          \
-        ((a).heads | ((a).nw << 8) | (((a).causal ? 1 : 0) << 12) | ((a).d_head << 13) | ((a).splits << 22)), (a).i_dim, \
+        attn_hot_p0(a), (a).i_dim, \
         (a).vcap, (a).base_add, (a).nkeys_fixed
 
 // FUSE: the finished output of the head stays in LDS (in q's place, in q's operand layout) for the output projection
@@ -77,7 +82,7 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int h, const 
         base = a.causal ? len_v + a.base_add : 0;
         nkeys = a.causal ? base + T : (a.nkeys_fixed > 0 ? a.nkeys_fixed : len_v);
         const int nblk = (nkeys + 31) >> 5;
-        const int bps = (nblk + a.splits - 1) / a.splits;
+        const int bps = (nblk + a.splits - 1) >> a.lsplits;  // (the key splits are a power of two)
         blk_begin = min(nblk, sp * bps);
         blk_end = min(nblk, blk_begin + bps);
     };
@@ -576,7 +581,7 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, hipStream_t st) {
     const int dh32 = a.d_head <= 32 ? 1 : (a.d_head <= 64 ? 2 : 4);
     const unsigned row_blocks = (unsigned)((a.T + kMaxRows - 1) / kMaxRows);
     if ((row_blocks > 1 && a.splits != 1) || !a.len_ptr) return hipErrorInvalidValue;
-    if (a.heads > 255 || a.nw > 15 || a.d_head > 511 || a.splits > 1023) return hipErrorInvalidValue;  // (BILD_ATTN_HOT packs them)
+    if (a.heads > 255 || a.nw > 15 || a.d_head > 511 || a.splits < 1 || a.splits > 64 || (a.splits & (a.splits - 1))) return hipErrorInvalidValue;  // (BILD_ATTN_HOT packs them)
     if (a.rel_bias && a.rel_d < 1) return hipErrorInvalidValue;
     const size_t smem = attn_lds_bytes(dtype, a.d_head, std::min(a.T, kMaxRows), a.nw) +
                         (a.rel_bias ? (size_t)(2 * a.rel_d + 1) * 4 : 0);  // + one head's row of the bias table

@@ -170,6 +170,7 @@ struct AttnArgs {
     int base_add;              // non-causal: number of keys = nkeys_fixed if > 0, else *len_ptr
     int nkeys_fixed;
     int splits;                // key ranges handled by separate workgroups
+    int lsplits;               // (set by the kernel) log2(splits): splits is a power of two
     int defer_merge;           // splits > 1: leave the partials for the consumer GEMM to merge (no merge kernel)
     float* part_o;             // [splits][T][I]   unnormalised partial outputs
     float* part_ml;            // [splits][T][heads][2] (max, sum)
