@@ -7,6 +7,11 @@ namespace bild {
 
 constexpr int kAttnLdsLimit = 160 * 1024;
 
+// exp of a non-positive argument through the hardware's base-2 exponential (one multiply and one transcendental
+// instruction instead of the library routine's range reduction): relative error of a few 1e-7 for the arguments near zero
+// that carry the softmax mass, absolute error below 1e-7 everywhere, exp(-inf) = 0.
+__device__ __forceinline__ float fexp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
+
 // =====================================================================================
 // KV-cache attention on the matrix cores.  K is stored [position][I]; V is stored
 // transposed, [I][capacity], so that both products contract over a contiguous axis:
@@ -217,13 +222,13 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int h, const 
             tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
             const float m_new = fmaxf(m_run[nt], tmax);
-            const float f = (m_run[nt] == -INFINITY) ? 0.f : expf(m_run[nt] - m_new);
+            const float f = (m_run[nt] == -INFINITY) ? 0.f : fexp(m_run[nt] - m_new);
             float p[2][4], psum = 0.f;
 #pragma unroll
             for (int ab = 0; ab < 2; ++ab)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    p[ab][v] = (m_new == -INFINITY) ? 0.f : expf(s[ab][v] - m_new);
+                    p[ab][v] = (m_new == -INFINITY) ? 0.f : fexp(s[ab][v] - m_new);
                     psum += p[ab][v];
                 }
             psum += __shfl_xor(psum, 16, 64);
@@ -326,7 +331,7 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int h, const 
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int w = 0; w < nw; ++w) {
             const float mw = cm[w * 32 + nt * 16 + tok_l];
-            const float wgt = (mw == -INFINITY) ? 0.f : expf(mw - M);
+            const float wgt = (mw == -INFINITY) ? 0.f : fexp(mw - M);
             Lsum += cl[w * 32 + nt * 16 + tok_l] * wgt;
             acc += co[((w * NT + nt) * DT16 + dt) * 64 + lane] * wgt;
         }
