@@ -7,11 +7,6 @@ namespace bild {
 
 constexpr int kAttnLdsLimit = 160 * 1024;
 
-// exp of a non-positive argument through the hardware's base-2 exponential (one multiply and one transcendental
-// instruction instead of the library routine's range reduction): relative error of a few 1e-7 for the arguments near zero
-// that carry the softmax mass, absolute error below 1e-7 everywhere, exp(-inf) = 0.
-__device__ __forceinline__ float fexp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
-
 // =====================================================================================
 // KV-cache attention on the matrix cores.  K is stored [position][I]; V is stored
 // transposed, [I][capacity], so that both products contract over a contiguous axis:

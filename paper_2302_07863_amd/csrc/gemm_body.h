@@ -435,7 +435,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
                     float w[SP], L = 0.f;
 #pragma unroll
                     for (int sp = 0; sp < SP; ++sp) {
-                        w[sp] = (m[sp] == -INFINITY) ? 0.f : expf(m[sp] - M);
+                        w[sp] = (m[sp] == -INFINITY) ? 0.f : fexp(m[sp] - M);
                         L += l[sp] * w[sp];
                     }
                     const float inv = 1.f / L;

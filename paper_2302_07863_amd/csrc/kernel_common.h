@@ -62,6 +62,12 @@ __device__ __forceinline__ float wave_max(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
+// exp through the hardware's base-2 exponential (one multiply and one transcendental instruction instead of the library
+// routine's range reduction).  Used where the argument is a difference of logits or scores, at most zero: relative error of
+// a few 1e-7 for the arguments near zero that carry the softmax mass, below 1e-5 relative where the result is negligible
+// anyway, exp(-inf) = 0.  These exponentials sit on the critical path of every latency-bound stage that has them.
+__device__ __forceinline__ float fexp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
+
 // ---- online softmax statistics ------------------------------------------------------
 struct Stat {
     float m, s;
@@ -70,18 +76,18 @@ struct Stat {
 __device__ __forceinline__ Stat stat_neutral() { return Stat{-INFINITY, 0.f, 0x7FFFFFFF}; }
 __device__ __forceinline__ void stat_push(Stat& a, float z, int n) {
     if (z > a.m) {  // strict: equal maxima keep the lower id (ids arrive in increasing order)
-        a.s = a.s * expf(a.m - z) + 1.f;
+        a.s = a.s * fexp(a.m - z) + 1.f;
         a.m = z;
         a.idx = n;
     } else {
-        a.s += expf(z - a.m);
+        a.s += fexp(z - a.m);
     }
 }
 __device__ __forceinline__ Stat stat_merge(const Stat& a, const Stat& b) {
     Stat r;
     r.m = fmaxf(a.m, b.m);
-    const float sa = (a.m == -INFINITY) ? 0.f : a.s * expf(a.m - r.m);
-    const float sb = (b.m == -INFINITY) ? 0.f : b.s * expf(b.m - r.m);
+    const float sa = (a.m == -INFINITY) ? 0.f : a.s * fexp(a.m - r.m);
+    const float sb = (b.m == -INFINITY) ? 0.f : b.s * fexp(b.m - r.m);
     r.s = sa + sb;
     r.idx = (a.m > b.m || (a.m == b.m && a.idx < b.idx)) ? a.idx : b.idx;
     return r;
@@ -95,9 +101,12 @@ __device__ __forceinline__ Stat stat_shfl_xor(const Stat& a, int o) {
 }
 
 __device__ __forceinline__ float gelu_tanh_f(float u) {
-    return 0.5f * u * (1.f + tanhf(0.7978845608028654f * (u + 0.044715f * u * u * u)));
+    // tanh(y) = 1 - 2 / (1 + e^(2y)) (saturates correctly at both ends; near zero the result is added to 1)
+    const float y = 0.7978845608028654f * (u + 0.044715f * u * u * u);
+    const float th = 1.f - 2.f * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(y * 2.8853900817779268f));
+    return 0.5f * u * (1.f + th);
 }
-__device__ __forceinline__ float silu_f(float u) { return u / (1.f + expf(-u)); }
+__device__ __forceinline__ float silu_f(float u) { return u * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(u * -1.4426950408889634f)); }
 
 
 // ---- activation traffic: plain vector loads and stores (the kernel boundary makes them visible) ----
