@@ -214,8 +214,7 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int h, const 
                     if (key > lim || t >= T) s[ab][v] = -INFINITY;
                     tmax = fmaxf(tmax, s[ab][v]);
                 }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            tmax = quad_rows_max(tmax);
             const float m_new = fmaxf(m_run[nt], tmax);
             const float f = (m_run[nt] == -INFINITY) ? 0.f : fexp(m_run[nt] - m_new);
             float p[2][4], psum = 0.f;
@@ -226,8 +225,7 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int h, const 
                     p[ab][v] = (m_new == -INFINITY) ? 0.f : fexp(s[ab][v] - m_new);
                     psum += p[ab][v];
                 }
-            psum += __shfl_xor(psum, 16, 64);
-            psum += __shfl_xor(psum, 32, 64);
+            psum = quad_rows_sum(psum);
             l_run[nt] = l_run[nt] * f + psum;
             m_run[nt] = m_new;
             // ---- O = O * f + V^T P ----

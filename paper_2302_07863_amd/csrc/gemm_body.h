@@ -801,8 +801,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
             for (int nt = 0; nt < 2; ++nt) {
                 if (nt >= NT) continue;
                 float ss = nx_ss[nt];
-                ss += __shfl_xor(ss, 16, 64);
-                ss += __shfl_xor(ss, 32, 64);
+                ss = quad_rows_sum(ss);
                 const int t = nt * 16 + tok_l;
                 if (kq == 0 && t < T) st_act(a.nx_ssq + (size_t)(vblock * WR + wrid) * kMaxRows + t, ss);
             }
@@ -811,8 +810,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
     if (epi == EPI_LMHEAD) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
-            st[nt] = stat_merge(st[nt], stat_shfl_xor(st[nt], 16));
-            st[nt] = stat_merge(st[nt], stat_shfl_xor(st[nt], 32));
+            st[nt] = stat_quad_rows(st[nt]);
             if (kq == 0) {
                 const int t = nt * 16 + tok_l;
                 StatPart sp;

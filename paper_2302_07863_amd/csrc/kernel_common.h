@@ -62,6 +62,35 @@ __device__ __forceinline__ float wave_max(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
+// The values of the lanes l and l ^ 16 (or l ^ 32) side by side in every lane, through gfx950's lane-swap instructions
+// instead of a trip through the LDS crossbar: swapping a register with a copy of itself leaves the even 16-lane rows'
+// values (the lower half's) in the first result and the odd rows' (the upper half's) in the second, in all lanes.
+__device__ __forceinline__ void pair_xor16(uint32_t x, uint32_t& even, uint32_t& odd) {
+    const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    even = r[0];
+    odd = r[1];
+}
+__device__ __forceinline__ void pair_xor32(uint32_t x, uint32_t& lower, uint32_t& upper) {
+    const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    lower = r[0];
+    upper = r[1];
+}
+// max / sum over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (every lane gets the result; the sums are formed in one fixed order)
+__device__ __forceinline__ float quad_rows_max(float v) {
+    uint32_t a, b;
+    pair_xor16(__float_as_uint(v), a, b);
+    v = fmaxf(__uint_as_float(a), __uint_as_float(b));
+    pair_xor32(__float_as_uint(v), a, b);
+    return fmaxf(__uint_as_float(a), __uint_as_float(b));
+}
+__device__ __forceinline__ float quad_rows_sum(float v) {
+    uint32_t a, b;
+    pair_xor16(__float_as_uint(v), a, b);
+    v = __uint_as_float(a) + __uint_as_float(b);
+    pair_xor32(__float_as_uint(v), a, b);
+    return __uint_as_float(a) + __uint_as_float(b);
+}
+
 // exp through the hardware's base-2 exponential (one multiply and one transcendental instruction instead of the library
 // routine's range reduction).  Used where the argument is a difference of logits or scores, at most zero: relative error of
 // a few 1e-7 for the arguments near zero that carry the softmax mass, below 1e-5 relative where the result is negligible
@@ -91,6 +120,19 @@ __device__ __forceinline__ Stat stat_merge(const Stat& a, const Stat& b) {
     r.s = sa + sb;
     r.idx = (a.m > b.m || (a.m == b.m && a.idx < b.idx)) ? a.idx : b.idx;
     return r;
+}
+// merge of the statistics of the lanes l, l ^ 16, l ^ 32, l ^ 48 (every lane gets the result)
+__device__ __forceinline__ Stat stat_quad_rows(const Stat& v) {
+    Stat x, y;
+    uint32_t a, b;
+    pair_xor16(__float_as_uint(v.m), a, b); x.m = __uint_as_float(a); y.m = __uint_as_float(b);
+    pair_xor16(__float_as_uint(v.s), a, b); x.s = __uint_as_float(a); y.s = __uint_as_float(b);
+    pair_xor16((uint32_t)v.idx, a, b); x.idx = (int)a; y.idx = (int)b;
+    const Stat h = stat_merge(x, y);
+    pair_xor32(__float_as_uint(h.m), a, b); x.m = __uint_as_float(a); y.m = __uint_as_float(b);
+    pair_xor32(__float_as_uint(h.s), a, b); x.s = __uint_as_float(a); y.s = __uint_as_float(b);
+    pair_xor32((uint32_t)h.idx, a, b); x.idx = (int)a; y.idx = (int)b;
+    return stat_merge(x, y);
 }
 __device__ __forceinline__ Stat stat_shfl_xor(const Stat& a, int o) {
     Stat b;
