@@ -675,24 +675,46 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
     __syncthreads();
     float rsc[2] = {1.f, 1.f};  // 1/rms of this lane's rows
     if (owner) {
+        // Both reductions run over a number of waves known only at run time (at most 8).  Written as loops of that length
+        // they become a chain of LDS reads each waited for on its own; unrolled to 8 with a clamped index and the
+        // surplus terms dropped (x + 0 is x: the sums and their order are unchanged) the reads go out together.
         if (norm) {
+            const float inv_k = __builtin_amdgcn_rcpf((float)K);
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) {
                 if (nt < NT) {
                     const int t = min(nt * 16 + tok_l, T - 1);
                     float sum = 0.f;
-                    for (int w = 0; w < NWV; ++w) sum += ssq[w * 32 + t];
-                    rsc[nt] = rsqrtf(sum / (float)K + a.eps);
+#pragma unroll
+                    for (int w = 0; w < 8; ++w) {
+                        const float v = ssq[min(w, NWV - 1) * 32 + t];
+                        sum += (w < NWV) ? v : 0.f;
+                    }
+                    rsc[nt] = __builtin_amdgcn_rsqf(sum * inv_k + a.eps);  // (the argument is at least eps: no denormal handling)
                 }
             }
         }
         if (WK > 1) {
-            for (int w2 = 1; w2 < WK; ++w2)
+            if constexpr (ONE) {
+                // (single-row launches, four or eight input slices as a rule; with several rows there are fewer slices and
+                // more tiles per wave, and the surplus reads cost more than the chain: measured)
 #pragma unroll
-                for (int r = 0; r < RW; ++r)
+                for (int w2 = 1; w2 < 8; ++w2) {
+                    const int wc = wave + min(w2, WK - 1);
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        if (j < NT) acc[r][j] += red[((wave + w2) * nacc + r * NT + j) * 64 + lane];
+                    for (int r = 0; r < RW; ++r) {
+                        const f32x4 v = red[(wc * nacc + r * NT) * 64 + lane];
+                        if (w2 < WK) acc[r][0] += v;
+                    }
+                }
+            } else {
+                for (int w2 = 1; w2 < WK; ++w2)
+#pragma unroll
+                    for (int r = 0; r < RW; ++r)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            if (j < NT) acc[r][j] += red[((wave + w2) * nacc + r * NT + j) * 64 + lane];
+            }
         }
     }
     // ---- epilogue: lane holds features f = tile*16 + kq*4 + v for row t = nt*16 + tok_l ----
