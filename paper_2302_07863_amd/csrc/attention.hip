@@ -318,15 +318,35 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const int h, const 
     for (int qd = wave; qd < NT * DT16; qd += nw) {
         const int nt = qd / DT16, dt = qd % DT16;
         const int t = nt * 16 + tok_l, d0 = dt * 16 + g * 4;
-        float M = -INFINITY;
-        for (int w = 0; w < nw; ++w) M = fmaxf(M, cm[w * 32 + nt * 16 + tok_l]);
-        float Lsum = 0.f;
+        // The waves' results are joined in the order of the waves.  With four waves (the usual workgroup) the reads go out
+        // together; a loop over a run-time count would wait for each wave's values before asking for the next.
+        float M = -INFINITY, Lsum = 0.f;
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int w = 0; w < nw; ++w) {
-            const float mw = cm[w * 32 + nt * 16 + tok_l];
-            const float wgt = (mw == -INFINITY) ? 0.f : fexp(mw - M);
-            Lsum += cl[w * 32 + nt * 16 + tok_l] * wgt;
-            acc += co[((w * NT + nt) * DT16 + dt) * 64 + lane] * wgt;
+        if (nw == 4) {
+            float mw[4], lw[4];
+            f32x4 ow[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                mw[w] = cm[w * 32 + nt * 16 + tok_l];
+                lw[w] = cl[w * 32 + nt * 16 + tok_l];
+                ow[w] = co[((w * NT + nt) * DT16 + dt) * 64 + lane];
+            }
+#pragma unroll
+            for (int w = 0; w < 4; ++w) M = fmaxf(M, mw[w]);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float wgt = (mw[w] == -INFINITY) ? 0.f : fexp(mw[w] - M);
+                Lsum += lw[w] * wgt;
+                acc += ow[w] * wgt;
+            }
+        } else {
+            for (int w = 0; w < nw; ++w) M = fmaxf(M, cm[w * 32 + nt * 16 + tok_l]);
+            for (int w = 0; w < nw; ++w) {
+                const float mw = cm[w * 32 + nt * 16 + tok_l];
+                const float wgt = (mw == -INFINITY) ? 0.f : fexp(mw - M);
+                Lsum += cl[w * 32 + nt * 16 + tok_l] * wgt;
+                acc += co[((w * NT + nt) * DT16 + dt) * 64 + lane] * wgt;
+            }
         }
         if constexpr (FUSE) {
             const float inv = t < T ? 1.f / Lsum : 0.f;
