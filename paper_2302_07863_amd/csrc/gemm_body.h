@@ -695,7 +695,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const int vblock, c
             }
         }
         if (WK > 1) {
-            if constexpr (ONE) {
+            if constexpr (ONE || TCAP > 0) {
                 // (single-row launches, four or eight input slices as a rule; with several rows there are fewer slices and
                 // more tiles per wave, and the surplus reads cost more than the chain: measured)
 #pragma unroll
