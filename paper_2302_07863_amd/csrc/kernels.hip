@@ -44,6 +44,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(BILD_GEMM_HOT_PARAMS, const G
 // pair: 236 -> 206 us per small-model step and 1048 -> 962 us per large-model step once the 512- and 1024-wide inputs
 // stopped padding 8 tiles per wave to 24).  VAR picks the batch geometry by the tiles a wave has:
 //   1: at most 8   - one batch of 8, no second buffer
+//   3: exactly 8 in every wave (RW = 1) - the same without clamped tile indices (gemm_body, EX)
 //   2: at most 16  - two batches of 8
 //   0: more        - batches of 12 (more bytes in flight for the bandwidth-bound shapes)
 constexpr int kShortBatch = 8;
@@ -51,8 +52,8 @@ template <int DT, int RW, int EPI, int ROPE, int VAR = 0, int PS = 0>
 __global__ __launch_bounds__(512) void gemm_row_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const GemmArgs a = gemm_hot<HOT_X, DT>(a0, BILD_GEMM_HOT_NAMES);
-    gemm_body<DT, RW, EPI, ROPE, 1, VAR ? kShortBatch / RW : gemm_batch(RW, true), 0, true, VAR != 1, 0, false, false, PS>(
-        a, (int)blockIdx.x, smem);
+    gemm_body<DT, RW, EPI, ROPE, 1, VAR ? kShortBatch / RW : gemm_batch(RW, true), 0, true, VAR != 1 && VAR != 3, 0, false, false, PS, false,
+              false, VAR == 3>(a, (int)blockIdx.x, smem);
 }
 
 // The first projection of a single-row pass, gathering its input row from the embedding matrix (gemm_body, EMB): the
@@ -61,8 +62,8 @@ template <int DT, int ROPE, int VAR>
 __global__ __launch_bounds__(512) void gemm_row_embed_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const GemmArgs a = gemm_hot<HOT_X, DT>(a0, BILD_GEMM_HOT_NAMES);
-    gemm_body<DT, 1, EPI_QKV, ROPE, 1, VAR ? kShortBatch : gemm_batch(1, true), 0, true, VAR != 1, 0, false, false, 0, false, true>(
-        a, (int)blockIdx.x, smem);
+    gemm_body<DT, 1, EPI_QKV, ROPE, 1, VAR ? kShortBatch : gemm_batch(1, true), 0, true, VAR != 1 && VAR != 3, 0, false, false, 0, false, true,
+              VAR == 3>(a, (int)blockIdx.x, smem);
 }
 
 // Two to four rows (the bulk of the large model's review passes) on a single-chunk input: the same body without the
@@ -93,8 +94,8 @@ template <int DT, int VAR>
 __global__ __launch_bounds__(512) void gemm_part_row_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const GemmArgs b = part_slice(gemm_hot<HOT_X, DT>(a0, BILD_GEMM_HOT_NAMES), DT ? 32 : 16);
-    gemm_body<DT, 1, EPI_PART, 0, 1, VAR ? kShortBatch : gemm_batch(1, true), 0, true, VAR != 1, 0, false, false, 0, true>(
-        b, (int)blockIdx.x, smem);
+    gemm_body<DT, 1, EPI_PART, 0, 1, VAR ? kShortBatch : gemm_batch(1, true), 0, true, VAR != 1 && VAR != 3, 0, false, false, 0, true, false,
+              VAR == 3>(b, (int)blockIdx.x, smem);
 }
 template <int DT, bool SHORT>
 __global__ __launch_bounds__(512) void gemm_part_few_kernel(BILD_GEMM_HOT_PARAMS, const GemmArgs a0) {
@@ -243,6 +244,9 @@ static hipError_t raise_lds_limits() {
     (const void*)gemm_row_kernel<DTV, 1, EPI_STORE, 0, 1>, (const void*)gemm_row_kernel<DTV, 1, EPI_RESID, 0, 1>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0, 1>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1, 1>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0, 1>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_STORE, 0, 3>, (const void*)gemm_row_kernel<DTV, 1, EPI_RESID, 0, 3>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0, 3>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1, 3>, \
+    (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0, 3>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_STORE, 0, 2>, (const void*)gemm_row_kernel<DTV, 1, EPI_RESID, 0, 2>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 0, 2>, (const void*)gemm_row_kernel<DTV, 1, EPI_QKV, 1, 2>, \
     (const void*)gemm_row_kernel<DTV, 1, EPI_ACT, 0, 2>, \
@@ -294,6 +298,7 @@ static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st
     const int kk = eff_k(a), tk = eff_tk(a);
     const bool one_chunk = kk <= a.kc;
     const int per_wave = (tk + a.wk - 1) / a.wk;
+    const bool exact8 = a.rw == 1 && tk == kShortBatch * a.wk;  // every wave has exactly one batch of tiles
     const int n4 = kk / 4, nthr = 64 * a.nwv;
     if (a.T < 1 || a.T > 4 || !one_chunk || (a.rw != 1 && !(a.rw == 2 && a.epi == EPI_ACT)) || a.mg_splits > 1 || a.xb_hi || a.nx_hi)
         return hipErrorInvalidValue;
@@ -306,7 +311,8 @@ static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st
         const dim3 grid((unsigned)gemm_num_blocks(a), (unsigned)a.ksplit);
 #define BILD_PK(DTV)                                                                                              \
     do {                                                                                                          \
-        if (a.T == 1 && per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+        if (a.T == 1 && exact8) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 3>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+        else if (a.T == 1 && per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T == 1 && per_wave <= 2 * kShortBatch) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T == 1) hipLaunchKernelGGL((gemm_part_row_kernel<DTV, 0>), grid, block, smem, st, BILD_GEMM_HOT(a), a);          \
         else if (per_wave <= gemm_batch(1, false)) hipLaunchKernelGGL((gemm_part_few_kernel<DTV, true>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
@@ -332,12 +338,14 @@ static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st
                 hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 2, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a);       \
             else hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 0, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a);      \
         } else if (a.epi == EPI_ACT) {                                                                            \
-            if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 1, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+            if (exact8) hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 3, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+            else if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 1, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             else if (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))          \
                 hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 2, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a);       \
             else hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_ACT, 0, 0, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a);      \
         } else {                                                                                                  \
-            if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 1, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+            if (exact8) hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 3, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+            else if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 1, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
             else if (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))          \
                 hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 2, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a);     \
             else hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPI_STORE, 0, 0, PH>), grid, block, smem, st, BILD_GEMM_HOT(a), a);    \
@@ -351,7 +359,9 @@ static hipError_t launch_gemm_split(const GemmArgs& a, int dtype, hipStream_t st
     constexpr int PSV = kPartSlices;
 #define BILD_RD1(DTV, EPIV, ROPEV) /* one row */                                                                 \
     do {                                                                                                          \
-        if (per_wave <= kShortBatch)                                                                              \
+        if (exact8)                                                                                               \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 3, PSV>), grid, block, smem, st, BILD_GEMM_HOT(a), a);         \
+        else if (per_wave <= kShortBatch)                                                                         \
             hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 1, PSV>), grid, block, smem, st, BILD_GEMM_HOT(a), a);         \
         else if (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))              \
             hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 2, PSV>), grid, block, smem, st, BILD_GEMM_HOT(a), a);         \
@@ -395,7 +405,8 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
         const dim3 grid((unsigned)gemm_num_blocks(a)), block(64 * a.nwv);
 #define BILD_EM(DTV, ROPEV)                                                                                                       \
     do {                                                                                                                            \
-        if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_embed_kernel<DTV, ROPEV, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+        if (a.W.tk == kShortBatch * a.wk) hipLaunchKernelGGL((gemm_row_embed_kernel<DTV, ROPEV, 3>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+        else if (per_wave <= kShortBatch) hipLaunchKernelGGL((gemm_row_embed_kernel<DTV, ROPEV, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))                                \
             hipLaunchKernelGGL((gemm_row_embed_kernel<DTV, ROPEV, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a);                 \
         else hipLaunchKernelGGL((gemm_row_embed_kernel<DTV, ROPEV, 0>), grid, block, smem, st, BILD_GEMM_HOT(a), a);                \
@@ -441,6 +452,8 @@ hipError_t launch_gemm(const GemmArgs& a, int dtype, hipStream_t st) {
             hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T == 1 && RWV == 2 && one_chunk && (per_wave <= kShortBatch || (per_wave % 4 == 0 && per_wave % 6 != 0))) \
             hipLaunchKernelGGL((gemm_row_kernel<DTV, 2, EPI_ACT, 0, 2>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
+        else if (a.T == 1 && RWV == 1 && one_chunk && a.W.tk == kShortBatch * a.wk)                 \
+            hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 3>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T == 1 && RWV == 1 && one_chunk && per_wave <= kShortBatch)                      \
             hipLaunchKernelGGL((gemm_row_kernel<DTV, 1, EPIV, ROPEV, 1>), grid, block, smem, st, BILD_GEMM_HOT(a), a); \
         else if (a.T == 1 && RWV == 1 && one_chunk && (per_wave <= 2 * kShortBatch || (per_wave % kShortBatch == 0 && per_wave % 12 != 0))) \
